@@ -1,0 +1,126 @@
+"""Pins of the oracle's step logic: masked update (Eq. 2-3), single group == full step
+(Eq. 1), hand-computed optimizer updates, delayed learning-rate bookkeeping."""
+import numpy as np
+import pytest
+
+from hift_inputs import WORKLOADS, init_params, make_batch, model_config
+from oracle import hift_oracle as O
+
+WL = WORKLOADS["C1"]
+CFG = model_config(WL)
+SPEC = [(n, s, k) for n, s, k, _u in O.param_tensors(CFG)]
+
+
+def _fresh(opt=None, seed=1):
+    theta = init_params(seed, SPEC, False, jitter=0.05).astype(np.float64)
+    return O.HiftOracle(CFG, opt or WL["opt"], theta), theta
+
+
+@pytest.mark.parametrize("strategy", ["bottom2up", "top2down", "random"])
+def test_frozen_parameters_bit_identical(strategy):
+    o, _ = _fresh()
+    k = o.set_group_schedule(strategy, 1, 99)
+    for t in range(1, 2 * k + 1):
+        gid = o.schedule_group_at(t)
+        before = o.theta.copy()
+        s1, s2 = o.state1.copy(), o.state2.copy()
+        tok, lab = make_batch(WL, 1, t)
+        o.step(tok, lab, gid)
+        lo, hi = o.group_range(gid)
+        keep = np.ones(o.theta.size, bool)
+        keep[lo:hi] = False
+        assert np.array_equal(before[keep], o.theta[keep])
+        assert np.array_equal(s1[keep], o.state1[keep]) and np.array_equal(s2[keep], o.state2[keep])
+        assert not np.array_equal(before[lo:hi], o.theta[lo:hi])
+    assert o.cycles_done == 2
+
+
+def test_single_group_equals_full_finetuning_step():
+    # m = n -> k = 1 -> beta = 1: a plain AdamW step on all parameters, written out here
+    o, theta0 = _fresh()
+    assert o.set_group_schedule("bottom2up", O.n_units(CFG), 0) == 1
+    tok, lab = make_batch(WL, 1, 1)
+    o.step(tok, lab, 0)
+    _loss, g = O.loss_and_grad(CFG, theta0, tok, lab)
+    p = WL["opt"]
+    m = (1 - p["beta1"]) * g
+    v = (1 - p["beta2"]) * g * g
+    th = theta0 * (1 - p["lr"] * p["weight_decay"] * o.decay_mask)
+    th = th - p["lr"] * (m / (1 - p["beta1"])) / (np.sqrt(v / (1 - p["beta2"])) + p["eps"])
+    assert np.array_equal(th, o.theta)
+
+
+def test_union_of_group_gradients_is_the_full_gradient():
+    # SGD, lr 1, no momentum, no decay: theta0 - theta1 = gradient of the active group
+    sgd = dict(kind="sgd", lr=1.0, beta1=0, beta2=0, eps=0, weight_decay=0.0, momentum=0.0)
+    tok, lab = make_batch(WL, 1, 1)
+    _o, theta0 = _fresh(sgd)
+    _loss, g = O.loss_and_grad(CFG, theta0, tok, lab)
+    got = np.zeros_like(g)
+    for gid in range(4):
+        o, _ = _fresh(sgd)
+        o.set_group_schedule("bottom2up", 1, 0)
+        o.step(tok, lab, gid)
+        lo, hi = o.group_range(gid)
+        got[lo:hi] = (theta0 - o.theta)[lo:hi]
+    assert np.allclose(got, g, rtol=0, atol=1e-15)
+
+
+def test_adamw_two_steps_by_hand():
+    th, m, v = np.array([1.0, -2.0]), np.zeros(2), np.zeros(2)
+    dm = np.array([1.0, 0.0])
+    g1, g2 = np.array([0.5, -0.25]), np.array([-1.0, 0.125])
+    lr, b1, b2, eps, wd = 0.1, 0.9, 0.999, 1e-8, 0.01
+    O.adamw_update(th, g1, m, v, 1, lr, b1, b2, eps, wd, dm)
+    # step 1 from zero state: theta(1 - lr wd) - lr g/(|g| + eps)
+    e1 = np.array([1.0 * (1 - 0.001) - 0.1 * 0.5 / (0.5 + 1e-8), -2.0 + 0.1 * 0.25 / (0.25 + 1e-8)])
+    assert np.allclose(th, e1, rtol=1e-14, atol=0)
+    O.adamw_update(th, g2, m, v, 2, lr, b1, b2, eps, wd, dm)
+    m2 = np.array([0.9 * 0.05 + 0.1 * -1.0, 0.9 * -0.025 + 0.1 * 0.125])
+    v2 = np.array([0.999 * 0.00025 + 0.001 * 1.0, 0.999 * 0.0000625 + 0.001 * 0.015625])
+    e2 = e1 * np.array([1 - 0.001, 1.0]) - 0.1 * (m2 / (1 - 0.81)) / (np.sqrt(v2 / (1 - 0.998001)) + 1e-8)
+    assert np.allclose(m, m2, rtol=1e-14) and np.allclose(v, v2, rtol=1e-14)
+    assert np.allclose(th, e2, rtol=1e-13, atol=0)
+
+
+def test_adagrad_and_sgd_momentum_by_hand():
+    th, acc = np.array([1.0]), np.zeros(1)
+    O.adagrad_update(th, np.array([0.5]), acc, 0.1, 1e-10, 0.0, np.ones(1))
+    assert np.allclose(th, 1.0 - 0.1 * 0.5 / (0.5 + 1e-10), rtol=1e-15) and acc[0] == 0.25
+    O.adagrad_update(th, np.array([-1.0]), acc, 0.1, 1e-10, 0.0, np.ones(1))
+    assert np.allclose(acc, 1.25) and np.allclose(th, 0.9 + 0.1 / (np.sqrt(1.25) + 1e-10), rtol=1e-9)
+    th, buf = np.array([1.0]), np.zeros(1)
+    O.sgd_update(th, np.array([0.5]), buf, 1, 0.1, 0.9, 0.0, np.ones(1))
+    assert buf[0] == 0.5 and np.allclose(th, 0.95)
+    O.sgd_update(th, np.array([0.25]), buf, 2, 0.1, 0.9, 0.0, np.ones(1))
+    assert np.allclose(buf, 0.9 * 0.5 + 0.25) and np.allclose(th, 0.95 - 0.07)
+    th = np.array([1.0])
+    O.sgd_update(th, np.array([0.5]), np.zeros(1), 1, 0.1, 0.0, 0.0, np.ones(1))
+    assert np.allclose(th, 0.95)
+
+
+def test_per_group_step_counter_drives_bias_correction():
+    # the second visit of a group is its update number 2, whatever the global step is
+    o, _ = _fresh()
+    k = o.set_group_schedule("bottom2up", 1, 0)
+    for t in range(1, k + 2):
+        tok, lab = make_batch(WL, 1, t)
+        o.step(tok, lab, o.schedule_group_at(t))
+    assert o.group_steps == [2, 1, 1, 1]
+
+
+def test_delayed_learning_rate_changes_only_between_cycles():
+    sgd = dict(kind="sgd", lr=1.0, beta1=0, beta2=0, eps=0, weight_decay=0.0, momentum=0.0)
+    o, _ = _fresh(sgd)
+    k = o.set_group_schedule("top2down", 1, 0)
+    lrs = []
+    for t in range(1, 3 * k + 1):
+        lr = 1.0 / (1 + o.cycles_done)            # schedule indexed by completed cycles
+        o.set_lr(lr)
+        lrs.append(lr)
+        tok, lab = make_batch(WL, 1, t)
+        before = o.theta.copy()
+        o.step(tok, lab, o.schedule_group_at(t))
+        lo, hi = o.group_range(o.schedule_group_at(t))
+        assert np.allclose((before - o.theta)[lo:hi], lr * o.last_grad[lo:hi], rtol=1e-10, atol=1e-15)
+    assert lrs == [1.0] * k + [0.5] * k + [1 / 3] * k
