@@ -1,0 +1,248 @@
+/*
+ * hift.h -- C ABI of the HiFT step library for AMD MI355X (gfx950).
+ *
+ * HiFT (hierarchical fine-tuning, arxiv 2401.15207) updates one group of layers per training
+ * step: forward over the whole model, backward only from the loss down to the lowest unit of
+ * the active group, weight gradients and an optimizer update for that group only, optimizer
+ * state of the other groups parked in host memory (section 3, Algorithm 1).
+ *
+ * Conventions
+ *   - Every call returns a hift_status; nothing throws across this boundary.
+ *   - "device" pointers are HBM addresses of the current HIP device, "host" pointers are CPU
+ *     addresses.  The library never allocates or frees device or pinned memory: the caller
+ *     hands in two arenas (sizes from hift_query_bytes) and keeps them alive until
+ *     hift_model_destroy.  The library owns only small host-side bookkeeping and HIP events.
+ *   - Streams are hipStream_t values passed as void*; all three must have default priority.
+ *   - A model is not thread-safe; calls on one model must not overlap.
+ *
+ * Layer units (appendix "Implementation Details", layering principle): unit 0 holds every
+ * embedding table including the position table (and the embedding LayerNorm of arch 1),
+ * units 1..L are the hidden layers, unit L+1 holds every head parameter including the final
+ * norm.  n = L + 2.
+ *
+ * Canonical parameter order (fp32 values, row-major, matrices stored [out, in]); this is the
+ * order of init_params_host, hift_write_params and hift_read_params:
+ *   arch 0 (pre-LayerNorm decoder, learned positions, GELU, biases, causal LM loss)
+ *     unit 0:   tok_emb[V,d] pos_emb[max_seq,d]
+ *     unit l:   ln1_g[d] ln1_b[d] wqkv[3d,d] bqkv[3d] wo[d,d] bo[d] ln2_g[d] ln2_b[d]
+ *               w1[f,d] b1[f] w2[d,f] b2[d]
+ *     unit L+1: lnf_g[d] lnf_b[d] whead[V,d]
+ *   arch 1 (post-LayerNorm encoder, learned positions, GELU, biases, classifier on token 0)
+ *     unit 0:   tok_emb[V,d] pos_emb[max_seq,d] lne_g[d] lne_b[d]
+ *     unit l:   wqkv[3d,d] bqkv[3d] wo[d,d] bo[d] ln1_g[d] ln1_b[d] w1[f,d] b1[f] w2[d,f] b2[d]
+ *               ln2_g[d] ln2_b[d]
+ *     unit L+1: wc[C,d] bc[C]
+ *   arch 2 (RMSNorm, rotary positions on pairs (i, i+hd/2), SwiGLU, no biases, causal LM loss)
+ *     unit 0:   tok_emb[V,d]
+ *     unit l:   g1[d] wqkv[3d,d] wo[d,d] g2[d] wgu[2f,d] wd[d,f]
+ *     unit L+1: gf[d] whead[V,d]
+ *   wqkv rows are q | k | v; wgu rows are gate | up.  Heads split d into n_heads blocks of hd.
+ */
+#ifndef HIFT_H
+#define HIFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hift_model hift_model; /* opaque, library-owned */
+
+typedef enum {
+  HIFT_OK = 0,
+  HIFT_EINVAL = -1,  /* bad argument; nothing was changed */
+  HIFT_ESTATE = -2,  /* call out of order (e.g. step before a schedule is set) */
+  HIFT_ENOMEM = -3,  /* an arena handed in is too small */
+  HIFT_EDEVICE = -4  /* a HIP call failed; hift_last_error has the HIP message */
+} hift_status;
+
+typedef enum { HIFT_BOTTOM2UP = 0, HIFT_TOP2DOWN = 1, HIFT_RANDOM = 2 } hift_strategy;
+typedef enum { HIFT_ADAMW = 0, HIFT_ADAGRAD = 1, HIFT_SGD = 2 } hift_opt_kind;
+enum { HIFT_ARCH_PRELN_DECODER = 0, HIFT_ARCH_POSTLN_ENCODER = 1, HIFT_ARCH_RMS_ROPE_DECODER = 2 };
+enum { HIFT_F32 = 0, HIFT_BF16 = 1 };
+enum { HIFT_KIND_MATRIX = 0, HIFT_KIND_GAIN = 1, HIFT_KIND_BIAS = 2 };
+
+typedef struct {
+  int32_t arch;          /* HIFT_ARCH_* */
+  int32_t n_layers;      /* L hidden layers */
+  int32_t d_model;       /* d; multiple of n_heads; d / n_heads even */
+  int32_t n_heads;
+  int32_t d_ffn;         /* f */
+  int32_t vocab;         /* V */
+  int32_t max_seq;       /* rows of the position table (arch 0, 1); upper bound of seq for arch 2 */
+  int32_t n_classes;     /* C (arch 1 only) */
+  float norm_eps;
+  float rope_base;       /* arch 2 */
+  int32_t dtype;         /* HIFT_F32: all arithmetic and storage fp32.
+                            HIFT_BF16: bf16 weights/activations with fp32 accumulation and fp32
+                            master weights (appendix "Mixing Precision", adapted mixed precision) */
+  int32_t state_on_host; /* 1: optimizer state of inactive groups lives in the pinned arena and is
+                            moved per step (Algorithm 1 steps i and k); 0: all state stays in HBM */
+} hift_config;
+
+typedef struct {
+  int32_t kind;       /* hift_opt_kind */
+  float lr;
+  float beta1, beta2; /* AdamW */
+  float eps;          /* AdamW (1e-8 usual) and AdaGrad (1e-10 usual) */
+  float weight_decay; /* applied to tensors with two or more dimensions only; AdamW: decoupled,
+                         AdaGrad / SGD: added to the gradient */
+  float momentum;     /* SGD; 0 = plain SGD, which keeps no state and moves no bytes */
+} hift_opt;
+
+typedef struct {
+  const int32_t* tokens; /* device, [batch, seq], each in [0, vocab) */
+  const int32_t* labels; /* device; arch 0/2: [batch, seq], target of each position or -1 for none
+                            (a causal LM batch has labels[b,s] = tokens[b,s+1] and -1 at the end);
+                            arch 1: [batch], class of each sequence */
+  int32_t batch, seq;
+} hift_batch;
+
+typedef struct {
+  char name[32];
+  int32_t unit;    /* layer unit that owns the tensor */
+  int32_t kind;    /* HIFT_KIND_* ; weight decay applies to HIFT_KIND_MATRIX only */
+  int64_t offset;  /* first element in the canonical flat order */
+  int64_t rows, cols; /* cols = 1 for vectors */
+} hift_tensor_info;
+
+/* Section 3 "Notation": k = n/m if m divides n, otherwise floor(n/m)+1.  Pure host integer
+ * helpers, usable without a GPU. */
+hift_status hift_group_count(int32_t n_units, int32_t m, int32_t* k_out);
+/* Visiting order of k groups (section 3.1 and Algorithm 1 initialisation).  Group ids are
+ * positions in model order (group 0 holds the embeddings); the strategy only fixes the order.
+ * random: Fisher-Yates from the top index down with SplitMix64 draws from `seed`, fixed for the
+ * whole run.  order_out: host, k entries. */
+hift_status hift_group_order(int32_t k, hift_strategy s, uint64_t seed, int32_t* order_out);
+
+/* Parameter layout of a configuration.  hift_tensor_count gives the number of tensors and the
+ * total number of parameters; hift_tensor_at fills the description of tensor `index`. */
+hift_status hift_tensor_count(const hift_config* cfg, int32_t* n_tensors, int64_t* n_params);
+hift_status hift_tensor_at(const hift_config* cfg, int32_t index, hift_tensor_info* out);
+
+/* Sizes of the two arenas a model of this shape needs for batches of at most max_batch
+ * sequences of at most max_seq tokens, grouped m units per group (the gradient buffer and the
+ * two state slots are sized for the largest group). */
+hift_status hift_query_bytes(const hift_config* cfg, const hift_opt* opt, int32_t m,
+                             int32_t max_batch, int32_t max_seq,
+                             size_t* device_bytes, size_t* pinned_host_bytes);
+
+/* Build a model inside the caller's arenas (Algorithm 1 "Require": model M, optimizer P).
+ *   init_params_host  host, fp32, canonical order, n_params values; copied.  May be NULL: all
+ *                     parameters start at zero and the caller fills them with hift_write_params.
+ *   device_arena      device, 256-byte aligned, device_bytes long
+ *   pinned_arena      host, page-locked, pinned_bytes long, zero-filled by the library
+ *                     (may be NULL when pinned_host_bytes is 0)
+ *   streams           compute, host-to-device, device-to-host
+ * Optimizer state starts at zero.  Errors: HIFT_EINVAL (bad shape, e.g. tied embeddings are
+ * not expressible), HIFT_ENOMEM, HIFT_EDEVICE. */
+hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32_t m,
+                              int32_t max_batch, int32_t max_seq, const float* init_params_host,
+                              void* device_arena, size_t device_bytes, void* pinned_arena,
+                              size_t pinned_bytes, void* compute_stream, void* h2d_stream,
+                              void* d2h_stream, hift_model** out);
+
+/* Grouping and visiting order (Algorithm 1 initialisation and steps c, d).  m may be any value
+ * whose largest group fits the gradient buffer and state slots sized at creation, else
+ * HIFT_ENOMEM.  Resets the step counter t to 0 and every per-group
+ * update counter; optimizer state is kept.  k_out receives the number of groups. */
+hift_status hift_set_group_schedule(hift_model* mdl, hift_strategy s, int32_t m, uint64_t seed,
+                                    int32_t* k_out);
+/* Group visited at step t (1-based): order[(t-1) mod k]. */
+hift_status hift_schedule_group_at(const hift_model* mdl, int64_t t, int32_t* group_id_out);
+/* Units [unit_lo, unit_hi) of a group. */
+hift_status hift_group_units(const hift_model* mdl, int32_t group_id, int32_t* unit_lo,
+                             int32_t* unit_hi);
+
+/* One HiFT step (Algorithm 1 steps e to k) on one batch: forward over all units; backward from
+ * the loss down to the lowest unit of group `group_id`; weight gradients of that group; its
+ * optimizer state brought to HBM (prefetched during the previous step when group_id is the
+ * scheduled one, fetched synchronously otherwise); optimizer update; state sent back.
+ * Parameters outside the group are not written.  The work is queued on the three streams;
+ * if loss_out (host) is not NULL the call waits for the compute stream and stores the mean
+ * loss, with NULL it returns without waiting.
+ * Errors: HIFT_ESTATE without a schedule; HIFT_EINVAL for group_id outside [0,k), batch or seq
+ * above the maxima, seq above the position table.  Token ids are not range-checked on the
+ * host: an id outside [0, vocab) is clamped by the kernels. */
+hift_status hift_step(hift_model* mdl, const hift_batch* batch, int32_t group_id, float* loss_out);
+
+/* Learning rate used by following steps.  The caller applies its schedule when
+ * hift_cycle_index changes (Algorithm 1: the rate moves only after all layers were updated). */
+hift_status hift_set_lr(hift_model* mdl, float lr);
+/* Steps taken since the schedule was set, and completed sweeps floor(t / k). */
+hift_status hift_cycle_index(const hift_model* mdl, int64_t* steps_done, int64_t* cycles_done);
+
+/* Copy parameters of units [unit_lo, unit_hi) to / from host memory in canonical order.
+ * which = 0: fp32 master values.  which = 1 (read only): the values the forward pass uses
+ * (bf16 widened to fp32 in bf16 mode).  Waits for all three streams first.
+ * dst_count / src_count is the number of floats the buffer holds and must match exactly. */
+hift_status hift_read_params(hift_model* mdl, int32_t unit_lo, int32_t unit_hi, int32_t which,
+                             float* dst_host, size_t dst_count);
+hift_status hift_write_params(hift_model* mdl, int32_t unit_lo, int32_t unit_hi,
+                              const float* src_host, size_t src_count);
+/* Optimizer state of units [unit_lo, unit_hi), slot 0 (AdamW first moment / AdaGrad accumulator /
+ * SGD momentum buffer) or slot 1 (AdamW second moment), wherever it currently lives. */
+hift_status hift_read_state(hift_model* mdl, int32_t unit_lo, int32_t unit_hi, int32_t slot,
+                            float* dst_host, size_t dst_count);
+
+/* Bytes of optimizer state queued host-to-device and device-to-host so far (0 for plain SGD:
+ * section 4.3 "Wallclock Time Efficiency", no state means no traffic). */
+hift_status hift_transfer_stats(hift_model* mdl, uint64_t* h2d_bytes, uint64_t* d2h_bytes);
+
+/* Per-step timing of the most recent hift_step, from HIP events on the compute stream:
+ * whole step, and the time between the point the optimizer was ready to run and the point its
+ * state had arrived (exposed copy time).  Waits for the streams. */
+hift_status hift_last_step_ms(hift_model* mdl, float* step_ms, float* exposed_copy_ms);
+
+/* Kernel-class timing for roofline reports.  While enabled, every kernel launch of hift_step is
+ * bracketed by HIP events on the compute stream.  hift_profile_read sums, for one class
+ * (0 linear-layer contractions, 1 attention contractions, 2 row-wise/elementwise kernels,
+ * 3 optimizer), the launches since hift_profile_enable, their milliseconds, and their
+ * algorithmic work (flops for classes 0 and 1, bytes for class 3, 0 for class 2). */
+hift_status hift_profile_enable(hift_model* mdl, int32_t on);
+hift_status hift_profile_read(hift_model* mdl, int32_t category, int64_t* launches, double* total_ms,
+                              double* work);
+
+const char* hift_last_error(void); /* message of the last failing call on this thread */
+void hift_model_destroy(hift_model* mdl);
+
+/* ---- single kernels, exposed for parity tests and roofline measurement ---------------------
+ * All pointers are device pointers; `stream` is a hipStream_t.  dtype is HIFT_F32 or HIFT_BF16
+ * and names the element type of the activation / weight operands. */
+
+/* C[M,N] = op(A) op(B) (+ bias[n]) (+ R[m,n]);  a_kmajor: A(m,k) at A[m*lda + k], else at
+ * A[k*lda + m]; b_kmajor: B(n,k) at B[n*ldb + k], else at B[k*ldb + n].  out_f32: C is fp32
+ * whatever dtype is.  bias has A's element type, R has C's type and leading dimension.  Batched over `batch` problems with element
+ * strides sa, sb, sc.  This is the one contraction used for every linear layer, its dX and dW
+ * (Algorithm 1 steps h and the backward step). */
+hift_status hift_kernel_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t out_f32,
+                             int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                             const void* B, int64_t ldb, void* C, int64_t ldc, const void* bias,
+                             const void* R, int32_t batch, int64_t sa, int64_t sb, int64_t sc,
+                             void* stream);
+
+/* Group-local optimizer update on `count` contiguous parameters (the update inside Algorithm 1's
+ * backward step): master, grad, state1, state2 fp32; compute_copy (bf16, may be NULL) receives the
+ * rounded new values.  t is the group's update number (1 on its first update). */
+hift_status hift_kernel_optimizer(const hift_opt* opt, int64_t count, int32_t decay, int64_t t,
+                                  float* master, const float* grad, float* state1, float* state2,
+                                  void* compute_copy, void* stream);
+
+/* y = norm(x) * g (+ b) over rows of width d; rms = 1: RMSNorm (b ignored).  stats: fp32 [rows,2]
+ * receives mean (0 for RMSNorm) and reciprocal standard deviation. */
+hift_status hift_kernel_norm_fwd(int32_t dtype, int32_t rms, int64_t rows, int32_t d, float eps,
+                                 const void* x, const void* g, const void* b, void* y,
+                                 float* stats, void* stream);
+
+/* Mean cross-entropy over rows with label >= 0 and its gradient: logits [rows, V] are replaced
+ * by d loss / d logits; loss_out is one device float. */
+hift_status hift_kernel_cross_entropy(int32_t dtype, int64_t rows, int32_t V, void* logits,
+                                      const int32_t* labels, float* row_loss_scratch,
+                                      float* loss_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HIFT_H */

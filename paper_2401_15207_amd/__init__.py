@@ -1,0 +1,10 @@
+"""HiFT step library for AMD MI355X: thin Python binding over the C ABI in include/hift.h.
+
+The shared library libhift.so must have been built (python -m paper_2401_15207_amd.build, or
+__graft_entry__.build()); importing this package fails loudly when it is missing.
+"""
+from .binding import (HiftError, HiftModel, lib, group_count, group_order, tensor_list, query_bytes,
+                      kernel_gemm, kernel_optimizer, kernel_norm_fwd, kernel_cross_entropy, LIB_PATH)
+
+__all__ = ["HiftError", "HiftModel", "lib", "group_count", "group_order", "tensor_list", "query_bytes",
+           "kernel_gemm", "kernel_optimizer", "kernel_norm_fwd", "kernel_cross_entropy", "LIB_PATH"]

@@ -1,0 +1,286 @@
+"""ctypes binding of libhift.so.  Argument marshalling only: every step of the HiFT path runs in
+the library's HIP kernels.  PyTorch is used to allocate device / pinned memory and streams."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+# PyTorch ships its own HIP runtime; it must be loaded first so that libhift.so binds to that
+# same runtime (one runtime per process: streams and pointers are shared with torch).
+import torch  # noqa: F401
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhift.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2401_15207_amd.build); "
+                      "there is no fallback path")
+lib = C.CDLL(LIB_PATH)
+
+STRATEGY = {"bottom2up": 0, "top2down": 1, "random": 2}
+OPT_KIND = {"adamw": 0, "adagrad": 1, "sgd": 2}
+
+
+class HiftError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"hift status {status}: {msg}")
+        self.status = status
+
+
+class Config(C.Structure):
+    _fields_ = [("arch", C.c_int32), ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("max_seq", C.c_int32), ("n_classes", C.c_int32),
+                ("norm_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32),
+                ("state_on_host", C.c_int32)]
+
+
+class Opt(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("weight_decay", C.c_float), ("momentum", C.c_float)]
+
+
+class Batch(C.Structure):
+    _fields_ = [("tokens", C.c_void_p), ("labels", C.c_void_p), ("batch", C.c_int32), ("seq", C.c_int32)]
+
+
+class TensorInfo(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("unit", C.c_int32), ("kind", C.c_int32), ("offset", C.c_int64),
+                ("rows", C.c_int64), ("cols", C.c_int64)]
+
+
+lib.hift_last_error.restype = C.c_char_p
+_vp, _i32, _i64, _u64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_size_t
+_P = C.POINTER
+_SIGS = {
+    "hift_group_count": [_i32, _i32, _P(_i32)],
+    "hift_group_order": [_i32, C.c_int, _u64, _P(_i32)],
+    "hift_tensor_count": [_P(Config), _P(_i32), _P(_i64)],
+    "hift_tensor_at": [_P(Config), _i32, _P(TensorInfo)],
+    "hift_query_bytes": [_P(Config), _P(Opt), _i32, _i32, _i32, _P(_sz), _P(_sz)],
+    "hift_model_create": [_P(Config), _P(Opt), _i32, _i32, _i32, _vp, _vp, _sz, _vp, _sz, _vp, _vp, _vp, _P(_vp)],
+    "hift_set_group_schedule": [_vp, C.c_int, _i32, _u64, _P(_i32)],
+    "hift_schedule_group_at": [_vp, _i64, _P(_i32)],
+    "hift_group_units": [_vp, _i32, _P(_i32), _P(_i32)],
+    "hift_step": [_vp, _P(Batch), _i32, _P(C.c_float)],
+    "hift_set_lr": [_vp, C.c_float],
+    "hift_cycle_index": [_vp, _P(_i64), _P(_i64)],
+    "hift_read_params": [_vp, _i32, _i32, _i32, _vp, _sz],
+    "hift_write_params": [_vp, _i32, _i32, _vp, _sz],
+    "hift_read_state": [_vp, _i32, _i32, _i32, _vp, _sz],
+    "hift_transfer_stats": [_vp, _P(_u64), _P(_u64)],
+    "hift_last_step_ms": [_vp, _P(C.c_float), _P(C.c_float)],
+    "hift_profile_enable": [_vp, _i32],
+    "hift_profile_read": [_vp, _i32, _P(_i64), _P(C.c_double), _P(C.c_double)],
+    "hift_kernel_gemm": [_i32, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp,
+                         _i32, _i64, _i64, _i64, _vp],
+    "hift_kernel_optimizer": [_P(Opt), _i64, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp],
+    "hift_kernel_norm_fwd": [_i32, _i32, _i64, _i32, C.c_float, _vp, _vp, _vp, _vp, _vp, _vp],
+    "hift_kernel_cross_entropy": [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp],
+}
+for _n, _a in _SIGS.items():
+    getattr(lib, _n).argtypes = _a
+    getattr(lib, _n).restype = C.c_int
+lib.hift_model_destroy.argtypes = [_vp]
+lib.hift_model_destroy.restype = None
+
+
+def _check(st):
+    if st != 0:
+        raise HiftError(st, lib.hift_last_error().decode())
+
+
+def make_config(cfg: dict, state_on_host: int = 0) -> Config:
+    return Config(cfg["arch"], cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["d_ffn"], cfg["vocab"],
+                  cfg["max_seq"], cfg.get("n_classes", 0), cfg["norm_eps"], cfg.get("rope_base", 10000.0),
+                  cfg["dtype"], cfg.get("state_on_host", state_on_host))
+
+
+def make_opt(opt: dict) -> Opt:
+    return Opt(OPT_KIND[opt["kind"]], opt["lr"], opt.get("beta1", 0.9), opt.get("beta2", 0.999),
+               opt.get("eps", 1e-8), opt.get("weight_decay", 0.0), opt.get("momentum", 0.0))
+
+
+def group_count(n_units: int, m: int) -> int:
+    k = _i32()
+    _check(lib.hift_group_count(n_units, m, C.byref(k)))
+    return k.value
+
+
+def group_order(k: int, strategy: str, seed: int = 0):
+    out = (_i32 * k)()
+    _check(lib.hift_group_order(k, STRATEGY[strategy], seed & (2 ** 64 - 1), out))
+    return list(out)
+
+
+def tensor_list(cfg: dict):
+    """[(name, shape, kind, unit, offset)] in canonical order, and the parameter count."""
+    c = make_config(cfg)
+    n, total = _i32(), _i64()
+    _check(lib.hift_tensor_count(C.byref(c), C.byref(n), C.byref(total)))
+    out = []
+    for i in range(n.value):
+        t = TensorInfo()
+        _check(lib.hift_tensor_at(C.byref(c), i, C.byref(t)))
+        shape = (t.rows, t.cols) if t.kind == 0 else (t.rows,)
+        out.append((t.name.decode(), shape, t.kind, t.unit, t.offset))
+    return out, total.value
+
+
+def query_bytes(cfg: dict, opt: dict, m: int, max_batch: int, max_seq: int):
+    c, o = make_config(cfg), make_opt(opt)
+    d, p = _sz(), _sz()
+    _check(lib.hift_query_bytes(C.byref(c), C.byref(o), m, max_batch, max_seq, C.byref(d), C.byref(p)))
+    return d.value, p.value
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def kernel_gemm(dtype, a_kmajor, b_kmajor, out_f32, M, N, K, A, lda, B, ldb, Cm, ldc, bias=None, R=None,
+                batch=1, sa=0, sb=0, sc=0, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_gemm(dtype, int(a_kmajor), int(b_kmajor), int(out_f32), M, N, K, _ptr(A), lda, _ptr(B),
+                                ldb, _ptr(Cm), ldc, _ptr(bias), _ptr(R), batch, sa, sb, sc, st))
+
+
+def kernel_optimizer(opt: dict, count, decay, t, master, grad, s1, s2, compute_copy=None, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    o = make_opt(opt)
+    _check(lib.hift_kernel_optimizer(C.byref(o), count, int(decay), t, _ptr(master), _ptr(grad), _ptr(s1), _ptr(s2),
+                                     _ptr(compute_copy), st))
+
+
+def kernel_norm_fwd(dtype, rms, rows, d, eps, x, g, b, y, stats, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_norm_fwd(dtype, int(rms), rows, d, eps, _ptr(x), _ptr(g), _ptr(b), _ptr(y), _ptr(stats), st))
+
+
+def kernel_cross_entropy(dtype, rows, V, logits, labels, row_loss, loss_out, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_cross_entropy(dtype, rows, V, _ptr(logits), _ptr(labels), _ptr(row_loss), _ptr(loss_out), st))
+
+
+class HiftModel:
+    """Owns the arenas (torch tensors) and streams a hift_model lives in."""
+
+    def __init__(self, cfg: dict, opt: dict, m: int, max_batch: int, max_seq: int, init_params=None,
+                 state_on_host: int = 0, device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("HiftModel needs a GPU: there is no CPU path")
+        self.torch = torch
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.cfg = dict(cfg, state_on_host=state_on_host)
+        self.c, self.o = make_config(self.cfg), make_opt(opt)
+        dbytes, pbytes = query_bytes(self.cfg, opt, m, max_batch, max_seq)
+        self.device_arena = torch.empty(dbytes + 256, dtype=torch.uint8, device=self.device)
+        base = self.device_arena.data_ptr()
+        self._dev_ptr = (base + 255) & ~255
+        self.pinned_arena = torch.empty(max(pbytes, 1), dtype=torch.uint8, pin_memory=True) if pbytes else None
+        self.compute_stream = torch.cuda.Stream(self.device)
+        self.h2d_stream = torch.cuda.Stream(self.device)
+        self.d2h_stream = torch.cuda.Stream(self.device)
+        self.device_bytes, self.pinned_bytes = dbytes, pbytes
+        init = None
+        if init_params is not None:
+            init = np.ascontiguousarray(init_params, dtype=np.float32)
+        h = _vp()
+        _check(lib.hift_model_create(C.byref(self.c), C.byref(self.o), m, max_batch, max_seq,
+                                     None if init is None else init.ctypes.data, self._dev_ptr, dbytes,
+                                     None if self.pinned_arena is None else self.pinned_arena.data_ptr(), pbytes,
+                                     self.compute_stream.cuda_stream, self.h2d_stream.cuda_stream,
+                                     self.d2h_stream.cuda_stream, C.byref(h)))
+        self.h = h
+        self.k = None
+        self.tensors, self.n_params = tensor_list(self.cfg)
+        self.n_units = cfg["n_layers"] + 2
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.hift_model_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_group_schedule(self, strategy: str, m: int, seed: int = 0) -> int:
+        k = _i32()
+        _check(lib.hift_set_group_schedule(self.h, STRATEGY[strategy], m, seed & (2 ** 64 - 1), C.byref(k)))
+        self.k = k.value
+        return self.k
+
+    def schedule_group_at(self, t: int) -> int:
+        g = _i32()
+        _check(lib.hift_schedule_group_at(self.h, t, C.byref(g)))
+        return g.value
+
+    def group_units(self, gid: int):
+        lo, hi = _i32(), _i32()
+        _check(lib.hift_group_units(self.h, gid, C.byref(lo), C.byref(hi)))
+        return lo.value, hi.value
+
+    def step(self, tokens, labels, group_id: int, want_loss: bool = True):
+        """tokens / labels: int32 torch tensors on the device ([B,S] and [B,S] or [B])."""
+        assert tokens.dtype == self.torch.int32 and labels.dtype == self.torch.int32
+        assert tokens.is_cuda and labels.is_cuda and tokens.is_contiguous() and labels.is_contiguous()
+        b = Batch(tokens.data_ptr(), labels.data_ptr(), tokens.shape[0], tokens.shape[1])
+        loss = C.c_float()
+        _check(lib.hift_step(self.h, C.byref(b), group_id, C.byref(loss) if want_loss else None))
+        return loss.value if want_loss else None
+
+    def set_lr(self, lr: float):
+        _check(lib.hift_set_lr(self.h, lr))
+
+    def cycle_index(self):
+        s, c = _i64(), _i64()
+        _check(lib.hift_cycle_index(self.h, C.byref(s), C.byref(c)))
+        return s.value, c.value
+
+    def _unit_count(self, lo, hi):
+        return sum(int(np.prod(shape)) for _n, shape, _k, u, _o in self.tensors if lo <= u < hi)
+
+    def read_params(self, unit_lo: int = 0, unit_hi: int | None = None, which: int = 0) -> np.ndarray:
+        unit_hi = self.n_units if unit_hi is None else unit_hi
+        out = np.empty(self._unit_count(unit_lo, unit_hi), dtype=np.float32)
+        _check(lib.hift_read_params(self.h, unit_lo, unit_hi, which, out.ctypes.data, out.size))
+        return out
+
+    def write_params(self, unit_lo: int, unit_hi: int, values: np.ndarray):
+        v = np.ascontiguousarray(values, dtype=np.float32)
+        _check(lib.hift_write_params(self.h, unit_lo, unit_hi, v.ctypes.data, v.size))
+
+    def read_state(self, unit_lo: int, unit_hi: int, slot: int) -> np.ndarray:
+        out = np.empty(self._unit_count(unit_lo, unit_hi), dtype=np.float32)
+        _check(lib.hift_read_state(self.h, unit_lo, unit_hi, slot, out.ctypes.data, out.size))
+        return out
+
+    def transfer_stats(self):
+        a, b = _u64(), _u64()
+        _check(lib.hift_transfer_stats(self.h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def last_step_ms(self):
+        a, b = C.c_float(), C.c_float()
+        _check(lib.hift_last_step_ms(self.h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def profile_enable(self, on: bool):
+        _check(lib.hift_profile_enable(self.h, int(on)))
+
+    def profile_read(self, category: int):
+        n, ms, w = _i64(), C.c_double(), C.c_double()
+        _check(lib.hift_profile_read(self.h, category, C.byref(n), C.byref(ms), C.byref(w)))
+        return n.value, ms.value, w.value
+
+    def synchronize(self):
+        self.compute_stream.synchronize()
+        self.h2d_stream.synchronize()
+        self.d2h_stream.synchronize()

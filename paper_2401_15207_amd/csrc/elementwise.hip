@@ -1,0 +1,722 @@
+// Row-wise and elementwise kernels of the HiFT step for gfx950: embedding lookup and its
+// adjoint, LayerNorm / RMSNorm forward and backward, rotary embedding, GELU / SwiGLU, softmax
+// forward and backward, cross-entropy with its gradient, column sums for bias and gain
+// gradients, type casts and the group-local optimizer update.
+//
+// All of these are bound by HBM traffic.  Rows are walked by one 64-lane wavefront (or one
+// 256-thread block for vocabulary-wide rows) with 16-byte accesses per lane; reductions are
+// wavefront shuffles.  Arithmetic is fp32 whatever the storage type is.
+#include "common.h"
+#include "kernels.h"
+
+namespace hift {
+
+namespace {
+
+constexpr int BLK = 256;
+
+template <typename T>
+constexpr int vecw() { return 16 / sizeof(T); }
+
+template <typename T, int V>
+__device__ __forceinline__ void ldv(const T* p, float (&f)[V]) {
+  Vec<T, V> t = *reinterpret_cast<const Vec<T, V>*>(p);
+#pragma unroll
+  for (int e = 0; e < V; ++e) f[e] = to_f32(t.v[e]);
+}
+template <typename T, int V>
+__device__ __forceinline__ void stv(T* p, const float (&f)[V]) {
+  Vec<T, V> t;
+#pragma unroll
+  for (int e = 0; e < V; ++e) t.v[e] = from_f32<T>(f[e]);
+  *reinterpret_cast<Vec<T, V>*>(p) = t;
+}
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---------------------------------------------------------------------------- embedding
+template <typename T, int V>
+__global__ void __launch_bounds__(BLK) embed_fwd_k(const int32_t* __restrict__ tokens, int64_t T_, int S,
+                                                    int d, int vocab, const T* __restrict__ tok_emb,
+                                                    const T* __restrict__ pos_emb, T* __restrict__ x) {
+  const int64_t t = blockIdx.x;
+  int id = tokens[t];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  const T* er = tok_emb + (int64_t)id * d;
+  const T* pr = pos_emb ? pos_emb + (int64_t)(t % S) * d : nullptr;
+  T* xr = x + t * d;
+  for (int j = threadIdx.x * V; j < d; j += BLK * V) {
+    float a[V];
+    ldv<T, V>(er + j, a);
+    if (pr) {
+      float b[V];
+      ldv<T, V>(pr + j, b);
+#pragma unroll
+      for (int e = 0; e < V; ++e) a[e] += b[e];
+    }
+    stv<T, V>(xr + j, a);
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(BLK) embed_bwd_tok_k(const int32_t* __restrict__ tokens, int d, int vocab,
+                                                        const T* __restrict__ dx, float* __restrict__ g_tok) {
+  const int64_t t = blockIdx.x;
+  int id = tokens[t];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  float* gr = g_tok + (int64_t)id * d;
+  const T* dr = dx + t * d;
+  for (int j = threadIdx.x; j < d; j += BLK) atomicAdd(gr + j, to_f32(dr[j]));
+}
+
+template <typename T>
+__global__ void __launch_bounds__(BLK) embed_bwd_pos_k(int B, int S, int d, const T* __restrict__ dx,
+                                                        float* __restrict__ g_pos) {
+  const int s = blockIdx.x;
+  for (int j = threadIdx.x; j < d; j += BLK) {
+    float a = 0.f;
+    for (int b = 0; b < B; ++b) a += to_f32(dx[((int64_t)b * S + s) * d + j]);
+    g_pos[(int64_t)s * d + j] = a;
+  }
+}
+
+template <typename T, int V>
+__global__ void __launch_bounds__(BLK) first_rows_k(int B, int S, int d, const T* __restrict__ src,
+                                                     T* __restrict__ dst, bool scatter) {
+  // gather: dst[b, :] = src[b*S, :];  scatter: dst[b*S, :] = src[b, :] (dst zero elsewhere)
+  const int b = blockIdx.x;
+  const T* s = scatter ? src + (int64_t)b * d : src + (int64_t)b * S * d;
+  T* o = scatter ? dst + (int64_t)b * S * d : dst + (int64_t)b * d;
+  for (int j = threadIdx.x * V; j < d; j += BLK * V)
+    *reinterpret_cast<Vec<T, V>*>(o + j) = *reinterpret_cast<const Vec<T, V>*>(s + j);
+}
+
+// ---------------------------------------------------------------------------- norms
+// One wavefront per row.  stats[2r] = mean (0 for RMSNorm), stats[2r+1] = 1/sqrt(var + eps).
+template <typename T, int V, bool RMS>
+__global__ void __launch_bounds__(BLK) norm_fwd_k(int64_t rows, int d, float eps, const T* __restrict__ x,
+                                                   const T* __restrict__ g, const T* __restrict__ b,
+                                                   T* __restrict__ y, float* __restrict__ stats) {
+  const int64_t row = (int64_t)blockIdx.x * (BLK / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const T* xr = x + row * d;
+  float s = 0.f;
+  for (int j = lane * V; j < d; j += 64 * V) {
+    float a[V];
+    ldv<T, V>(xr + j, a);
+#pragma unroll
+    for (int e = 0; e < V; ++e) s += RMS ? a[e] * a[e] : a[e];
+  }
+  s = wave_sum(s);
+  float mean = 0.f, var;
+  if (RMS) {
+    var = s / d;
+  } else {
+    mean = s / d;
+    float q = 0.f;
+    for (int j = lane * V; j < d; j += 64 * V) {
+      float a[V];
+      ldv<T, V>(xr + j, a);
+#pragma unroll
+      for (int e = 0; e < V; ++e) q += (a[e] - mean) * (a[e] - mean);
+    }
+    var = wave_sum(q) / d;
+  }
+  const float rstd = 1.0f / sqrtf(var + eps);
+  T* yr = y + row * d;
+  for (int j = lane * V; j < d; j += 64 * V) {
+    float a[V], gg[V];
+    ldv<T, V>(xr + j, a);
+    ldv<T, V>(g + j, gg);
+    if (RMS) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) a[e] = a[e] * rstd * gg[e];
+    } else {
+      float bb[V];
+      ldv<T, V>(b + j, bb);
+#pragma unroll
+      for (int e = 0; e < V; ++e) a[e] = (a[e] - mean) * rstd * gg[e] + bb[e];
+    }
+    stv<T, V>(yr + j, a);
+  }
+  if (lane == 0) {
+    stats[2 * row] = mean;
+    stats[2 * row + 1] = rstd;
+  }
+}
+
+template <typename T, int V, bool RMS>
+__global__ void __launch_bounds__(BLK) norm_bwd_dx_k(int64_t rows, int d, const T* __restrict__ dy,
+                                                      const T* __restrict__ x, const T* __restrict__ g,
+                                                      const float* __restrict__ stats,
+                                                      const T* __restrict__ dres, T* __restrict__ dx) {
+  const int64_t row = (int64_t)blockIdx.x * (BLK / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+  const T* xr = x + row * d;
+  const T* dyr = dy + row * d;
+  float s1 = 0.f, s2 = 0.f;
+  for (int j = lane * V; j < d; j += 64 * V) {
+    float a[V], dd[V], gg[V];
+    ldv<T, V>(xr + j, a);
+    ldv<T, V>(dyr + j, dd);
+    ldv<T, V>(g + j, gg);
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      const float dxh = dd[e] * gg[e];
+      s1 += dxh;
+      s2 += dxh * (a[e] - mean) * rstd;
+    }
+  }
+  s1 = RMS ? 0.f : wave_sum(s1) / d;
+  s2 = wave_sum(s2) / d;
+  T* dxr = dx + row * d;
+  for (int j = lane * V; j < d; j += 64 * V) {
+    float a[V], dd[V], gg[V], o[V];
+    ldv<T, V>(xr + j, a);
+    ldv<T, V>(dyr + j, dd);
+    ldv<T, V>(g + j, gg);
+#pragma unroll
+    for (int e = 0; e < V; ++e) o[e] = rstd * (dd[e] * gg[e] - s1 - (a[e] - mean) * rstd * s2);
+    if (dres) {
+      float r[V];
+      ldv<T, V>(dres + row * d + j, r);
+#pragma unroll
+      for (int e = 0; e < V; ++e) o[e] += r[e];
+    }
+    stv<T, V>(dxr + j, o);
+  }
+}
+
+// Column sums in two deterministic stages.  Stage 1: block (256 columns) x chunk (64 rows).
+// MODE 0: sum y.  MODE 1: sum dy * xhat and sum dy (norm gain / shift gradients).
+template <typename T, int MODE>
+__global__ void __launch_bounds__(BLK) col_part_k(int64_t rows, int64_t n, const T* __restrict__ y, int64_t ld,
+                                                   const T* __restrict__ x, const float* __restrict__ stats,
+                                                   float* __restrict__ part) {
+  const int64_t j = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (j >= n) return;
+  const int64_t r0 = (int64_t)blockIdx.y * 64, r1 = r0 + 64 < rows ? r0 + 64 : rows;
+  float a = 0.f, b = 0.f;
+  for (int64_t r = r0; r < r1; ++r) {
+    const float v = to_f32(y[r * ld + j]);
+    if (MODE == 0) {
+      a += v;
+    } else {
+      a += v * (to_f32(x[r * ld + j]) - stats[2 * r]) * stats[2 * r + 1];
+      b += v;
+    }
+  }
+  part[(int64_t)blockIdx.y * n + j] = a;
+  if (MODE == 1) part[((int64_t)gridDim.y + blockIdx.y) * n + j] = b;
+}
+__global__ void __launch_bounds__(BLK) col_final_k(int64_t nchunk, int64_t n, const float* __restrict__ part,
+                                                    float* __restrict__ out) {
+  const int64_t j = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (j >= n) return;
+  float a = 0.f;
+  for (int64_t c = 0; c < nchunk; ++c) a += part[c * n + j];
+  out[j] = a;
+}
+
+// ---------------------------------------------------------------------------- rotary
+// qkv [T, 3d]; rotates pair (i, i + hd/2) of every head of q (columns 0..d) and k (d..2d).
+// cs: [max_seq, hd/2] pairs (cos, sin) computed in double on the host.
+template <typename T, int V>
+__global__ void __launch_bounds__(BLK) rope_k(T* __restrict__ qkv, int64_t T_, int S, int H, int hd,
+                                               const float2* __restrict__ cs, float sign) {
+  const int h2 = hd / 2, per_row = 2 * H * (h2 / V);
+  const int64_t idx = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (idx >= T_ * per_row) return;
+  const int64_t t = idx / per_row;
+  int r = (int)(idx % per_row);
+  const int which = r / (H * (h2 / V));
+  r %= H * (h2 / V);
+  const int h = r / (h2 / V), i = (r % (h2 / V)) * V;
+  T* p = qkv + t * 3 * H * hd + (int64_t)which * H * hd + h * hd + i;
+  const float2* c = cs + (int64_t)(t % S) * h2 + i;
+  float a[V], b[V], oa[V], ob[V];
+  ldv<T, V>(p, a);
+  ldv<T, V>(p + h2, b);
+#pragma unroll
+  for (int e = 0; e < V; ++e) {
+    const float co = c[e].x, si = sign * c[e].y;
+    oa[e] = a[e] * co - b[e] * si;
+    ob[e] = a[e] * si + b[e] * co;
+  }
+  stv<T, V>(p, oa);
+  stv<T, V>(p + h2, ob);
+}
+
+// ---------------------------------------------------------------------------- activations
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_df(float x) {
+  const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
+  const float pdf = 0.3989422804014327f * expf(-0.5f * x * x);
+  return cdf + x * pdf;
+}
+
+template <typename T, int V, bool BWD>
+__global__ void __launch_bounds__(BLK) gelu_k(int64_t n, const T* __restrict__ dact, const T* __restrict__ pre,
+                                               T* __restrict__ out) {
+  const int64_t i = ((int64_t)blockIdx.x * BLK + threadIdx.x) * V;
+  if (i >= n) return;
+  float a[V], o[V];
+  ldv<T, V>(pre + i, a);
+  if (BWD) {
+    float dd[V];
+    ldv<T, V>(dact + i, dd);
+#pragma unroll
+    for (int e = 0; e < V; ++e) o[e] = dd[e] * gelu_df(a[e]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < V; ++e) o[e] = gelu_f(a[e]);
+  }
+  stv<T, V>(out + i, o);
+}
+
+template <typename T, int V>
+__global__ void __launch_bounds__(BLK) swiglu_fwd_k(int64_t T_, int f, const T* __restrict__ gu, T* __restrict__ act) {
+  const int fv = f / V;
+  const int64_t idx = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (idx >= T_ * fv) return;
+  const int64_t t = idx / fv;
+  const int j = (int)(idx % fv) * V;
+  float g[V], u[V], o[V];
+  ldv<T, V>(gu + t * 2 * f + j, g);
+  ldv<T, V>(gu + t * 2 * f + f + j, u);
+#pragma unroll
+  for (int e = 0; e < V; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+  stv<T, V>(act + t * f + j, o);
+}
+
+template <typename T, int V>
+__global__ void __launch_bounds__(BLK) swiglu_bwd_k(int64_t T_, int f, const T* __restrict__ dact,
+                                                     const T* __restrict__ gu, T* __restrict__ dgu) {
+  const int fv = f / V;
+  const int64_t idx = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (idx >= T_ * fv) return;
+  const int64_t t = idx / fv;
+  const int j = (int)(idx % fv) * V;
+  float g[V], u[V], da[V], dg[V], du[V];
+  ldv<T, V>(gu + t * 2 * f + j, g);
+  ldv<T, V>(gu + t * 2 * f + f + j, u);
+  ldv<T, V>(dact + t * f + j, da);
+#pragma unroll
+  for (int e = 0; e < V; ++e) {
+    const float s = 1.0f / (1.0f + expf(-g[e]));
+    dg[e] = da[e] * u[e] * s * (1.0f + g[e] * (1.0f - s));
+    du[e] = da[e] * g[e] * s;
+  }
+  stv<T, V>(dgu + t * 2 * f + j, dg);
+  stv<T, V>(dgu + t * 2 * f + f + j, du);
+}
+
+// ---------------------------------------------------------------------------- softmax
+// One wavefront per row of S scores.  Row r belongs to query position r % S.
+template <typename T>
+__global__ void __launch_bounds__(BLK) softmax_fwd_k(int64_t rows, int S, float scale, bool causal, T* __restrict__ s) {
+  const int64_t row = (int64_t)blockIdx.x * (BLK / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const int n = causal ? (int)(row % S) + 1 : S;
+  T* sr = s + row * S;
+  float mx = -INFINITY;
+  for (int j = lane; j < n; j += 64) mx = fmaxf(mx, to_f32(sr[j]) * scale);
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int j = lane; j < n; j += 64) sum += expf(to_f32(sr[j]) * scale - mx);
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+  for (int j = lane; j < S; j += 64)
+    sr[j] = from_f32<T>(j < n ? expf(to_f32(sr[j]) * scale - mx) * inv : 0.f);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(BLK) softmax_bwd_k(int64_t rows, int S, float scale, const T* __restrict__ p,
+                                                      T* __restrict__ dp) {
+  const int64_t row = (int64_t)blockIdx.x * (BLK / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const T* pr = p + row * S;
+  T* dr = dp + row * S;
+  float dot = 0.f;
+  for (int j = lane; j < S; j += 64) dot += to_f32(pr[j]) * to_f32(dr[j]);
+  dot = wave_sum(dot);
+  for (int j = lane; j < S; j += 64) dr[j] = from_f32<T>(scale * to_f32(pr[j]) * (to_f32(dr[j]) - dot));
+}
+
+// ---------------------------------------------------------------------------- cross-entropy
+// scratch layout: row_loss[0..rows) per-row losses, row_loss[rows] = number of rows with a target.
+__global__ void __launch_bounds__(BLK) ce_count_k(int64_t rows, const int32_t* __restrict__ labels,
+                                                   float* __restrict__ row_loss) {
+  __shared__ float red[BLK / 64];
+  float c = 0.f;
+  for (int64_t r = threadIdx.x; r < rows; r += BLK) c += labels[r] >= 0 ? 1.f : 0.f;
+  c = block_sum<BLK / 64>(c, red);
+  if (threadIdx.x == 0) row_loss[rows] = c;
+}
+
+template <typename T, int V>
+__global__ void __launch_bounds__(BLK) ce_row_k(int64_t rows, int vocab, T* __restrict__ logits,
+                                                 const int32_t* __restrict__ labels, float* __restrict__ row_loss) {
+  __shared__ float red[BLK / 64];
+  const int64_t row = blockIdx.x;
+  T* lr = logits + row * vocab;
+  int lab = labels[row];
+  const float inv_n = 1.0f / row_loss[rows];
+  if (lab < 0) {  // no target: zero gradient, zero loss
+    float z[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) z[e] = 0.f;
+    for (int j = threadIdx.x * V; j < vocab; j += BLK * V) stv<T, V>(lr + j, z);
+    if (threadIdx.x == 0) row_loss[row] = 0.f;
+    return;
+  }
+  if (lab >= vocab) lab = vocab - 1;
+  float mx = -INFINITY;
+  for (int j = threadIdx.x * V; j < vocab; j += BLK * V) {
+    float a[V];
+    ldv<T, V>(lr + j, a);
+#pragma unroll
+    for (int e = 0; e < V; ++e) mx = fmaxf(mx, a[e]);
+  }
+  mx = block_max<BLK / 64>(mx, red);
+  float sum = 0.f;
+  for (int j = threadIdx.x * V; j < vocab; j += BLK * V) {
+    float a[V];
+    ldv<T, V>(lr + j, a);
+#pragma unroll
+    for (int e = 0; e < V; ++e) sum += expf(a[e] - mx);
+  }
+  sum = block_sum<BLK / 64>(sum, red);
+  const float lse = mx + logf(sum), inv = 1.0f / sum;
+  if (threadIdx.x == 0) row_loss[row] = lse - to_f32(lr[lab]);
+  __syncthreads();  // the target logit is read before any thread overwrites it
+  for (int j = threadIdx.x * V; j < vocab; j += BLK * V) {
+    float a[V];
+    ldv<T, V>(lr + j, a);
+#pragma unroll
+    for (int e = 0; e < V; ++e) a[e] = (expf(a[e] - mx) * inv - (j + e == lab ? 1.f : 0.f)) * inv_n;
+    stv<T, V>(lr + j, a);
+  }
+}
+
+__global__ void __launch_bounds__(BLK) ce_final_k(int64_t rows, const float* __restrict__ row_loss,
+                                                   float* __restrict__ loss_out) {
+  __shared__ float red[BLK / 64];
+  float c = 0.f;
+  for (int64_t r = threadIdx.x; r < rows; r += BLK) c += row_loss[r];
+  c = block_sum<BLK / 64>(c, red);
+  if (threadIdx.x == 0) *loss_out = c / row_loss[rows];
+}
+
+// ---------------------------------------------------------------------------- casts, fill
+template <typename T>
+__global__ void __launch_bounds__(BLK) cast_from_f32_k(int64_t n, const float* __restrict__ s, T* __restrict__ d) {
+  const int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (i < n) d[i] = from_f32<T>(s[i]);
+}
+template <typename T>
+__global__ void __launch_bounds__(BLK) cast_to_f32_k(int64_t n, const T* __restrict__ s, float* __restrict__ d) {
+  const int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (i < n) d[i] = to_f32(s[i]);
+}
+__global__ void __launch_bounds__(BLK) fill_zero_k(uint4* __restrict__ p, int64_t n16, unsigned char* tail_p,
+                                                    int tail) {
+  const int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (i < n16) p[i] = make_uint4(0, 0, 0, 0);
+  if (i < tail) tail_p[i] = 0;
+}
+
+// ---------------------------------------------------------------------------- optimizer
+// Group-local update over contiguous fp32 master weights.  KIND 0 AdamW (decoupled decay),
+// 1 AdaGrad, 2 SGD with momentum, 3 plain SGD.  Four parameters per thread (16-byte accesses).
+template <int KIND, int V>
+__global__ void __launch_bounds__(BLK) opt_k(int64_t n, float lr, float b1, float b2, float eps, float wd,
+                                              float mu, float inv_bc1, float inv_bc2, int first,
+                                              float* __restrict__ master, const float* __restrict__ grad,
+                                              float* __restrict__ s1, float* __restrict__ s2,
+                                              bf16* __restrict__ cc) {
+  const int64_t i = ((int64_t)blockIdx.x * BLK + threadIdx.x) * V;
+  if (i >= n) return;
+  float th[V], g[V], a[V], b[V];
+  ldv<float, V>(master + i, th);
+  ldv<float, V>(grad + i, g);
+  if (KIND != 3) ldv<float, V>(s1 + i, a);
+  if (KIND == 0) ldv<float, V>(s2 + i, b);
+#pragma unroll
+  for (int e = 0; e < V; ++e) {
+    if (KIND == 0) {
+      th[e] -= lr * wd * th[e];
+      a[e] = b1 * a[e] + (1.0f - b1) * g[e];
+      b[e] = b2 * b[e] + (1.0f - b2) * g[e] * g[e];
+      th[e] -= lr * (a[e] * inv_bc1) / (sqrtf(b[e] * inv_bc2) + eps);
+    } else if (KIND == 1) {
+      const float gg = g[e] + wd * th[e];
+      a[e] += gg * gg;
+      th[e] -= lr * gg / (sqrtf(a[e]) + eps);
+    } else {
+      float gg = g[e] + wd * th[e];
+      if (KIND == 2) {
+        a[e] = first ? gg : mu * a[e] + gg;
+        gg = a[e];
+      }
+      th[e] -= lr * gg;
+    }
+  }
+  stv<float, V>(master + i, th);
+  if (KIND != 3) stv<float, V>(s1 + i, a);
+  if (KIND == 0) stv<float, V>(s2 + i, b);
+  if (cc) stv<bf16, V>(cc + i, th);
+}
+
+#define LAUNCH_CHECK() return hipGetLastError()
+
+}  // namespace
+
+// ================================================================================ launchers
+#define DISPATCH_TV(dt, vec_ok, CALL_T_V)                 \
+  do {                                                    \
+    if ((dt) == DT_F32) {                                 \
+      typedef float T;                                    \
+      if (vec_ok(4)) { constexpr int V = 4; CALL_T_V; }   \
+      else { constexpr int V = 1; CALL_T_V; }             \
+    } else {                                              \
+      typedef bf16 T;                                     \
+      if (vec_ok(8)) { constexpr int V = 8; CALL_T_V; }   \
+      else { constexpr int V = 1; CALL_T_V; }             \
+    }                                                     \
+  } while (0)
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+hipError_t embed_fwd(int dt, const int32_t* tokens, int64_t T_, int S, int d, int V_, const void* tok_emb,
+                     const void* pos_emb, void* x, hipStream_t st) {
+  if (T_ == 0) return hipSuccess;
+#define OK(v) (d % (v) == 0 && aligned16(tok_emb) && aligned16(pos_emb) && aligned16(x))
+  DISPATCH_TV(dt, OK, (embed_fwd_k<T, V><<<dim3((unsigned)T_), BLK, 0, st>>>(
+                          tokens, T_, S, d, V_, (const T*)tok_emb, (const T*)pos_emb, (T*)x)));
+#undef OK
+  LAUNCH_CHECK();
+}
+
+hipError_t embed_bwd(int dt, const int32_t* tokens, int64_t T_, int S, int d, int V_, const void* dx,
+                     float* g_tok, float* g_pos, hipStream_t st) {
+  if (T_ == 0) return hipSuccess;
+  if (dt == DT_F32) {
+    embed_bwd_tok_k<float><<<dim3((unsigned)T_), BLK, 0, st>>>(tokens, d, V_, (const float*)dx, g_tok);
+    if (g_pos) embed_bwd_pos_k<float><<<dim3(S), BLK, 0, st>>>((int)(T_ / S), S, d, (const float*)dx, g_pos);
+  } else {
+    embed_bwd_tok_k<bf16><<<dim3((unsigned)T_), BLK, 0, st>>>(tokens, d, V_, (const bf16*)dx, g_tok);
+    if (g_pos) embed_bwd_pos_k<bf16><<<dim3(S), BLK, 0, st>>>((int)(T_ / S), S, d, (const bf16*)dx, g_pos);
+  }
+  LAUNCH_CHECK();
+}
+
+static hipError_t first_rows(int dt, int B, int S, int d, const void* src, void* dst, bool scatter, hipStream_t st) {
+  if (B == 0) return hipSuccess;
+#define OK(v) (d % (v) == 0 && aligned16(src) && aligned16(dst))
+  DISPATCH_TV(dt, OK, (first_rows_k<T, V><<<dim3(B), BLK, 0, st>>>(B, S, d, (const T*)src, (T*)dst, scatter)));
+#undef OK
+  LAUNCH_CHECK();
+}
+hipError_t gather_first(int dt, int B, int S, int d, const void* x, void* y, hipStream_t st) {
+  return first_rows(dt, B, S, d, x, y, false, st);
+}
+hipError_t scatter_first(int dt, int B, int S, int d, const void* dy, void* dx, hipStream_t st) {
+  hipError_t e = fill_zero(dx, (size_t)B * S * d * dt_size(dt), st);
+  if (e != hipSuccess) return e;
+  return first_rows(dt, B, S, d, dy, dx, true, st);
+}
+
+hipError_t norm_fwd(int dt, bool rms, int64_t rows, int d, float eps, const void* x, const void* g, const void* b,
+                    void* y, float* stats, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  const dim3 grid((unsigned)cdiv(rows, BLK / 64));
+#define OK(v) (d % (v) == 0 && aligned16(x) && aligned16(y) && aligned16(g) && aligned16(b))
+  if (rms)
+    DISPATCH_TV(dt, OK, (norm_fwd_k<T, V, true><<<grid, BLK, 0, st>>>(rows, d, eps, (const T*)x, (const T*)g,
+                                                                          (const T*)b, (T*)y, stats)));
+  else
+    DISPATCH_TV(dt, OK, (norm_fwd_k<T, V, false><<<grid, BLK, 0, st>>>(rows, d, eps, (const T*)x, (const T*)g,
+                                                                           (const T*)b, (T*)y, stats)));
+#undef OK
+  LAUNCH_CHECK();
+}
+
+hipError_t norm_bwd_dx(int dt, bool rms, int64_t rows, int d, const void* dy, const void* x, const void* g,
+                       const float* stats, const void* dres, void* dx, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  const dim3 grid((unsigned)cdiv(rows, BLK / 64));
+#define OK(v) (d % (v) == 0 && aligned16(x) && aligned16(dy) && aligned16(g) && aligned16(dres) && aligned16(dx))
+  if (rms)
+    DISPATCH_TV(dt, OK, (norm_bwd_dx_k<T, V, true><<<grid, BLK, 0, st>>>(rows, d, (const T*)dy, (const T*)x,
+                                                                             (const T*)g, stats, (const T*)dres, (T*)dx)));
+  else
+    DISPATCH_TV(dt, OK, (norm_bwd_dx_k<T, V, false><<<grid, BLK, 0, st>>>(rows, d, (const T*)dy, (const T*)x,
+                                                                              (const T*)g, stats, (const T*)dres, (T*)dx)));
+#undef OK
+  LAUNCH_CHECK();
+}
+
+hipError_t norm_bwd_params(int dt, bool rms, int64_t rows, int d, const void* dy, const void* x, const float* stats,
+                           float* part, float* dg, float* db, hipStream_t st) {
+  (void)rms;  // stats[2r] is 0 for RMSNorm, so one formula serves both
+  const int64_t nchunk = cdiv(rows, 64);
+  if (rows == 0) {
+    hipError_t e = fill_zero(dg, (size_t)d * 4, st);
+    if (e == hipSuccess && db) e = fill_zero(db, (size_t)d * 4, st);
+    return e;
+  }
+  const dim3 grid((unsigned)cdiv(d, BLK), (unsigned)nchunk);
+  if (dt == DT_F32)
+    col_part_k<float, 1><<<grid, BLK, 0, st>>>(rows, d, (const float*)dy, d, (const float*)x, stats, part);
+  else
+    col_part_k<bf16, 1><<<grid, BLK, 0, st>>>(rows, d, (const bf16*)dy, d, (const bf16*)x, stats, part);
+  col_final_k<<<dim3((unsigned)cdiv(d, BLK)), BLK, 0, st>>>(nchunk, d, part, dg);
+  if (db) col_final_k<<<dim3((unsigned)cdiv(d, BLK)), BLK, 0, st>>>(nchunk, d, part + nchunk * d, db);
+  LAUNCH_CHECK();
+}
+
+hipError_t col_sum(int dt, int64_t rows, int64_t n, const void* y, int64_t ld, float* part, float* out,
+                   hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  if (rows == 0) return fill_zero(out, (size_t)n * 4, st);
+  const int64_t nchunk = cdiv(rows, 64);
+  const dim3 grid((unsigned)cdiv(n, BLK), (unsigned)nchunk);
+  if (dt == DT_F32)
+    col_part_k<float, 0><<<grid, BLK, 0, st>>>(rows, n, (const float*)y, ld, nullptr, nullptr, part);
+  else
+    col_part_k<bf16, 0><<<grid, BLK, 0, st>>>(rows, n, (const bf16*)y, ld, nullptr, nullptr, part);
+  col_final_k<<<dim3((unsigned)cdiv(n, BLK)), BLK, 0, st>>>(nchunk, n, part, out);
+  LAUNCH_CHECK();
+}
+
+hipError_t rope(int dt, void* qkv, int64_t T_, int S, int H, int hd, const float* cos_sin, int sign, hipStream_t st) {
+  if (T_ == 0) return hipSuccess;
+  const int h2 = hd / 2;
+#define OK(v) (h2 % (v) == 0 && aligned16(qkv))
+#define CALL                                                                                            \
+  {                                                                                                     \
+    const int64_t n = T_ * 2 * H * (h2 / V);                                                            \
+    rope_k<T, V><<<dim3((unsigned)cdiv(n, BLK)), BLK, 0, st>>>((T*)qkv, T_, S, H, hd,                   \
+                                                                (const float2*)cos_sin, (float)sign);   \
+  }
+  DISPATCH_TV(dt, OK, CALL);
+#undef CALL
+#undef OK
+  LAUNCH_CHECK();
+}
+
+hipError_t gelu_fwd(int dt, int64_t n, const void* pre, void* act, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+#define OK(v) (n % (v) == 0 && aligned16(pre) && aligned16(act))
+  DISPATCH_TV(dt, OK, (gelu_k<T, V, false><<<dim3((unsigned)cdiv(n / V, BLK)), BLK, 0, st>>>(n, nullptr, (const T*)pre, (T*)act)));
+#undef OK
+  LAUNCH_CHECK();
+}
+hipError_t gelu_bwd(int dt, int64_t n, const void* dact, const void* pre, void* dpre, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+#define OK(v) (n % (v) == 0 && aligned16(pre) && aligned16(dact) && aligned16(dpre))
+  DISPATCH_TV(dt, OK, (gelu_k<T, V, true><<<dim3((unsigned)cdiv(n / V, BLK)), BLK, 0, st>>>(n, (const T*)dact, (const T*)pre, (T*)dpre)));
+#undef OK
+  LAUNCH_CHECK();
+}
+hipError_t swiglu_fwd(int dt, int64_t T_, int f, const void* gu, void* act, hipStream_t st) {
+  if (T_ == 0) return hipSuccess;
+#define OK(v) (f % (v) == 0 && aligned16(gu) && aligned16(act))
+  DISPATCH_TV(dt, OK, (swiglu_fwd_k<T, V><<<dim3((unsigned)cdiv(T_ * (f / V), BLK)), BLK, 0, st>>>(T_, f, (const T*)gu, (T*)act)));
+#undef OK
+  LAUNCH_CHECK();
+}
+hipError_t swiglu_bwd(int dt, int64_t T_, int f, const void* dact, const void* gu, void* dgu, hipStream_t st) {
+  if (T_ == 0) return hipSuccess;
+#define OK(v) (f % (v) == 0 && aligned16(gu) && aligned16(dact) && aligned16(dgu))
+  DISPATCH_TV(dt, OK, (swiglu_bwd_k<T, V><<<dim3((unsigned)cdiv(T_ * (f / V), BLK)), BLK, 0, st>>>(T_, f, (const T*)dact, (const T*)gu, (T*)dgu)));
+#undef OK
+  LAUNCH_CHECK();
+}
+
+hipError_t softmax_fwd(int dt, int64_t nbh, int S, float scale, bool causal, void* s, hipStream_t st) {
+  const int64_t rows = nbh * S;
+  if (rows == 0) return hipSuccess;
+  const dim3 grid((unsigned)cdiv(rows, BLK / 64));
+  if (dt == DT_F32) softmax_fwd_k<float><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (float*)s);
+  else softmax_fwd_k<bf16><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (bf16*)s);
+  LAUNCH_CHECK();
+}
+hipError_t softmax_bwd(int dt, int64_t nbh, int S, float scale, const void* p, void* dp, hipStream_t st) {
+  const int64_t rows = nbh * S;
+  if (rows == 0) return hipSuccess;
+  const dim3 grid((unsigned)cdiv(rows, BLK / 64));
+  if (dt == DT_F32) softmax_bwd_k<float><<<grid, BLK, 0, st>>>(rows, S, scale, (const float*)p, (float*)dp);
+  else softmax_bwd_k<bf16><<<grid, BLK, 0, st>>>(rows, S, scale, (const bf16*)p, (bf16*)dp);
+  LAUNCH_CHECK();
+}
+
+hipError_t cross_entropy(int dt, int64_t rows, int V_, void* logits, const int32_t* labels, float* row_loss,
+                         float* loss_out, hipStream_t st) {
+  if (rows == 0) return fill_zero(loss_out, 4, st);
+  ce_count_k<<<1, BLK, 0, st>>>(rows, labels, row_loss);
+#define OK(v) (V_ % (v) == 0 && aligned16(logits))
+  DISPATCH_TV(dt, OK, (ce_row_k<T, V><<<dim3((unsigned)rows), BLK, 0, st>>>(rows, V_, (T*)logits, labels, row_loss)));
+#undef OK
+  ce_final_k<<<1, BLK, 0, st>>>(rows, row_loss, loss_out);
+  LAUNCH_CHECK();
+}
+
+hipError_t cast_f32_to(int dt, int64_t n, const float* src, void* dst, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  if (dt == DT_F32) return hipMemcpyAsync(dst, src, (size_t)n * 4, hipMemcpyDeviceToDevice, st);
+  cast_from_f32_k<bf16><<<dim3((unsigned)cdiv(n, BLK)), BLK, 0, st>>>(n, src, (bf16*)dst);
+  LAUNCH_CHECK();
+}
+hipError_t cast_to_f32(int dt, int64_t n, const void* src, float* dst, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  if (dt == DT_F32) return hipMemcpyAsync(dst, src, (size_t)n * 4, hipMemcpyDeviceToDevice, st);
+  cast_to_f32_k<bf16><<<dim3((unsigned)cdiv(n, BLK)), BLK, 0, st>>>(n, (const bf16*)src, dst);
+  LAUNCH_CHECK();
+}
+
+hipError_t fill_zero(void* p, size_t bytes, hipStream_t st) {
+  if (bytes == 0) return hipSuccess;
+  // a fill kernel rather than a memset node, so callers may capture it into a graph
+  const int64_t n16 = aligned16(p) ? (int64_t)(bytes / 16) : 0;
+  const int tail = (int)(bytes - (size_t)n16 * 16);
+  if (tail > BLK && n16 == 0) return hipErrorInvalidValue;  // unaligned large fills are not used
+  fill_zero_k<<<dim3((unsigned)(n16 ? cdiv(n16, BLK) : 1)), BLK, 0, st>>>((uint4*)p, n16,
+                                                                            (unsigned char*)p + n16 * 16, tail);
+  LAUNCH_CHECK();
+}
+
+hipError_t optimizer_update(const OptArgs& o, int64_t n, bool decay, int64_t t, float* master, const float* grad,
+                            float* s1, float* s2, void* cc, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  const float wd = decay ? o.wd : 0.f;
+  const double bc1 = 1.0 - pow((double)o.beta1, (double)t), bc2 = 1.0 - pow((double)o.beta2, (double)t);
+  const float ib1 = (float)(1.0 / bc1), ib2 = (float)(1.0 / bc2);
+  const bool vec = n % 8 == 0 && aligned16(master) && aligned16(grad) && aligned16(s1) && aligned16(s2) && aligned16(cc);
+  int kind = o.kind;
+  if (kind == 2 && o.momentum == 0.f) kind = 3;
+#define OPT_CALL(K, V)                                                                                      \
+  opt_k<K, V><<<dim3((unsigned)cdiv(cdiv(n, V), BLK)), BLK, 0, st>>>(n, o.lr, o.beta1, o.beta2, o.eps, wd, \
+                                                                     o.momentum, ib1, ib2, t == 1 ? 1 : 0, \
+                                                                     master, grad, s1, s2, (bf16*)cc)
+#define OPT_KIND(K) \
+  if (vec) OPT_CALL(K, 4); else OPT_CALL(K, 1)
+  switch (kind) {
+    case 0: OPT_KIND(0); break;
+    case 1: OPT_KIND(1); break;
+    case 2: OPT_KIND(2); break;
+    case 3: OPT_KIND(3); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef OPT_KIND
+#undef OPT_CALL
+  LAUNCH_CHECK();
+}
+
+}  // namespace hift

@@ -1,0 +1,78 @@
+// Host-side launchers of the HIP kernels of the HiFT step (gfx950).  Internal interface
+// between the model code and the kernel sources; the public C ABI is include/hift.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hift {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+inline size_t dt_size(int dt) { return dt == DT_F32 ? 4 : 2; }
+
+// ---- contraction -------------------------------------------------------------------------
+struct Gemm {
+  int dtype = DT_BF16;      // element type of A, B, R and (unless out_f32) C
+  bool a_kmajor = true;     // A(m,k) at A[m*lda + k]; false: at A[k*lda + m]
+  bool b_kmajor = true;     // B(n,k) at B[n*ldb + k]; false: at B[k*ldb + n]
+  bool out_f32 = false;
+  int64_t M = 0, N = 0, K = 0;
+  const void* A = nullptr; int64_t lda = 0;
+  const void* B = nullptr; int64_t ldb = 0;
+  void* C = nullptr; int64_t ldc = 0;
+  const void* bias = nullptr;           // [N], element type of A, or null
+  const void* R = nullptr; int64_t ldr = 0;  // residual added in the epilogue, C's type, or null
+  // two-level batch: problem z = b * nh + h uses offsets b*s?1 + h*s?2 (elements)
+  int nb = 1, nh = 1;
+  int64_t sa1 = 0, sa2 = 0, sb1 = 0, sb2 = 0, sc1 = 0, sc2 = 0;
+};
+hipError_t gemm(const Gemm& g, hipStream_t st);
+
+// ---- row-wise and elementwise kernels ------------------------------------------------------
+hipError_t embed_fwd(int dt, const int32_t* tokens, int64_t T, int S, int d, int V,
+                     const void* tok_emb, const void* pos_emb, void* x, hipStream_t st);
+hipError_t norm_fwd(int dt, bool rms, int64_t rows, int d, float eps, const void* x, const void* g,
+                    const void* b, void* y, float* stats, hipStream_t st);
+// dx = (dres ? dres : 0) + d norm / d x applied to dy
+hipError_t norm_bwd_dx(int dt, bool rms, int64_t rows, int d, const void* dy, const void* x,
+                       const void* g, const float* stats, const void* dres, void* dx, hipStream_t st);
+// dg[j] = sum_r dy[r,j] * xhat[r,j];  db[j] = sum_r dy[r,j]  (db may be null); fp32 outputs.
+// part: fp32 scratch of 2 * ceil(rows/64) * d floats.
+hipError_t norm_bwd_params(int dt, bool rms, int64_t rows, int d, const void* dy, const void* x,
+                           const float* stats, float* part, float* dg, float* db, hipStream_t st);
+// out[j] = sum_r y[r*ld + j], fp32 output; part: scratch of ceil(rows/64) * n floats
+hipError_t col_sum(int dt, int64_t rows, int64_t n, const void* y, int64_t ld, float* part,
+                   float* out, hipStream_t st);
+// rotary embedding in place on the q and k parts of qkv [T, 3d]; sign = +1 forward, -1 adjoint
+hipError_t rope(int dt, void* qkv, int64_t T, int S, int H, int hd, const float* cos_sin, int sign,
+                hipStream_t st);
+hipError_t gelu_fwd(int dt, int64_t n, const void* pre, void* act, hipStream_t st);
+hipError_t gelu_bwd(int dt, int64_t n, const void* dact, const void* pre, void* dpre, hipStream_t st);
+// gu [T, 2f] = gate | up  ->  act [T, f]
+hipError_t swiglu_fwd(int dt, int64_t T, int f, const void* gu, void* act, hipStream_t st);
+hipError_t swiglu_bwd(int dt, int64_t T, int f, const void* dact, const void* gu, void* dgu, hipStream_t st);
+// in place over scores [nbh, S, S]: p = softmax(scale * s + causal mask)
+hipError_t softmax_fwd(int dt, int64_t nbh, int S, float scale, bool causal, void* s, hipStream_t st);
+// in place over dp: ds = scale * p * (dp - sum_j dp p)
+hipError_t softmax_bwd(int dt, int64_t nbh, int S, float scale, const void* p, void* dp, hipStream_t st);
+// logits [rows, V] -> d loss / d logits in place; loss = mean over labels >= 0
+hipError_t cross_entropy(int dt, int64_t rows, int V, void* logits, const int32_t* labels,
+                         float* row_loss, float* loss_out, hipStream_t st);
+// g_tok[tok[t], :] += dx[t, :] (fp32 atomics);  g_pos[s, :] = sum_b dx[b*S+s, :]
+hipError_t embed_bwd(int dt, const int32_t* tokens, int64_t T, int S, int d, int V, const void* dx,
+                     float* g_tok, float* g_pos, hipStream_t st);
+// rows of x at positions b*S (first token of every sequence) -> y [B, d], and the adjoint
+hipError_t gather_first(int dt, int B, int S, int d, const void* x, void* y, hipStream_t st);
+hipError_t scatter_first(int dt, int B, int S, int d, const void* dy, void* dx, hipStream_t st);
+hipError_t cast_f32_to(int dt, int64_t n, const float* src, void* dst, hipStream_t st);
+hipError_t cast_to_f32(int dt, int64_t n, const void* src, float* dst, hipStream_t st);
+hipError_t fill_zero(void* p, size_t bytes, hipStream_t st);
+
+// ---- optimizer ---------------------------------------------------------------------------
+struct OptArgs {
+  int kind; float lr, beta1, beta2, eps, wd, momentum;
+};
+hipError_t optimizer_update(const OptArgs& o, int64_t n, bool decay, int64_t t, float* master,
+                            const float* grad, float* s1, float* s2, void* compute_copy /* bf16 or null */,
+                            hipStream_t st);
+
+}  // namespace hift

@@ -1,0 +1,1265 @@
+// Host side of the HiFT step library: parameter layout, layer units, groups and visiting
+// order, the step itself (forward over all units, backward truncated at the lowest unit of
+// the active group, weight gradients and optimizer update for that group only) and the
+// movement of the group's optimizer state between pinned host memory and HBM on side streams.
+// Implements the C ABI declared in include/hift.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/hift.h"
+#include "kernels.h"
+
+using namespace hift;
+
+namespace {
+
+thread_local std::string g_err;
+
+hift_status fail(hift_status s, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return s;
+}
+
+#define HIP_TRY(expr)                                                                         \
+  do {                                                                                        \
+    hipError_t e_ = (expr);                                                                   \
+    if (e_ != hipSuccess)                                                                     \
+      return fail(HIFT_EDEVICE, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+
+// ------------------------------------------------------------------------------------------
+// layout (appendix "Implementation Details": embeddings = one unit, each hidden layer = one
+// unit, all head parameters = one unit)
+// ------------------------------------------------------------------------------------------
+struct Tensor {
+  std::string name;
+  int unit, kind;
+  int64_t off, rows, cols;
+  int64_t count() const { return rows * cols; }
+};
+
+struct Layout {
+  std::vector<Tensor> t;
+  std::vector<int64_t> unit_off, unit_cnt;
+  std::vector<int> unit_first;  // first tensor index of each unit (+ sentinel)
+  int64_t n_params = 0;
+  int n_units = 0;
+  int find(const std::string& name) const {
+    for (size_t i = 0; i < t.size(); ++i)
+      if (t[i].name == name) return (int)i;
+    return -1;
+  }
+};
+
+hift_status check_config(const hift_config* c) {
+  if (!c) return fail(HIFT_EINVAL, "config is null");
+  if (c->arch < 0 || c->arch > 2) return fail(HIFT_EINVAL, "arch %d unknown", c->arch);
+  if (c->n_layers < 1 || c->d_model < 2 || c->n_heads < 1 || c->d_ffn < 1 || c->vocab < 1 || c->max_seq < 1)
+    return fail(HIFT_EINVAL, "sizes must be positive");
+  if (c->d_model % c->n_heads != 0) return fail(HIFT_EINVAL, "d_model must be a multiple of n_heads");
+  if (c->arch == HIFT_ARCH_RMS_ROPE_DECODER && (c->d_model / c->n_heads) % 2 != 0)
+    return fail(HIFT_EINVAL, "head width must be even for rotary positions");
+  if (c->arch == HIFT_ARCH_POSTLN_ENCODER && c->n_classes < 1) return fail(HIFT_EINVAL, "n_classes must be >= 1");
+  if (c->dtype != HIFT_F32 && c->dtype != HIFT_BF16) return fail(HIFT_EINVAL, "dtype unknown");
+  if (!(c->norm_eps >= 0.f)) return fail(HIFT_EINVAL, "norm_eps must be >= 0");
+  return HIFT_OK;
+}
+
+void build_layout(const hift_config& c, Layout& L) {
+  const int64_t d = c.d_model, f = c.d_ffn, V = c.vocab;
+  const int nl = c.n_layers;
+  int64_t off = 0;
+  auto add = [&](const std::string& n, int unit, int kind, int64_t r, int64_t cl) {
+    L.t.push_back(Tensor{n, unit, kind, off, r, cl});
+    off += r * cl;
+  };
+  const int M = HIFT_KIND_MATRIX, G = HIFT_KIND_GAIN, Bk = HIFT_KIND_BIAS;
+  if (c.arch == HIFT_ARCH_PRELN_DECODER) {
+    add("tok_emb", 0, M, V, d);
+    add("pos_emb", 0, M, c.max_seq, d);
+    for (int l = 0; l < nl; ++l) {
+      const std::string p = "l" + std::to_string(l) + ".";
+      const int u = l + 1;
+      add(p + "ln1_g", u, G, d, 1); add(p + "ln1_b", u, Bk, d, 1);
+      add(p + "wqkv", u, M, 3 * d, d); add(p + "bqkv", u, Bk, 3 * d, 1);
+      add(p + "wo", u, M, d, d); add(p + "bo", u, Bk, d, 1);
+      add(p + "ln2_g", u, G, d, 1); add(p + "ln2_b", u, Bk, d, 1);
+      add(p + "w1", u, M, f, d); add(p + "b1", u, Bk, f, 1);
+      add(p + "w2", u, M, d, f); add(p + "b2", u, Bk, d, 1);
+    }
+    add("lnf_g", nl + 1, G, d, 1); add("lnf_b", nl + 1, Bk, d, 1);
+    add("whead", nl + 1, M, V, d);
+  } else if (c.arch == HIFT_ARCH_POSTLN_ENCODER) {
+    add("tok_emb", 0, M, V, d);
+    add("pos_emb", 0, M, c.max_seq, d);
+    add("lne_g", 0, G, d, 1); add("lne_b", 0, Bk, d, 1);
+    for (int l = 0; l < nl; ++l) {
+      const std::string p = "l" + std::to_string(l) + ".";
+      const int u = l + 1;
+      add(p + "wqkv", u, M, 3 * d, d); add(p + "bqkv", u, Bk, 3 * d, 1);
+      add(p + "wo", u, M, d, d); add(p + "bo", u, Bk, d, 1);
+      add(p + "ln1_g", u, G, d, 1); add(p + "ln1_b", u, Bk, d, 1);
+      add(p + "w1", u, M, f, d); add(p + "b1", u, Bk, f, 1);
+      add(p + "w2", u, M, d, f); add(p + "b2", u, Bk, d, 1);
+      add(p + "ln2_g", u, G, d, 1); add(p + "ln2_b", u, Bk, d, 1);
+    }
+    add("wc", nl + 1, M, c.n_classes, d);
+    add("bc", nl + 1, Bk, c.n_classes, 1);
+  } else {
+    add("tok_emb", 0, M, V, d);
+    for (int l = 0; l < nl; ++l) {
+      const std::string p = "l" + std::to_string(l) + ".";
+      const int u = l + 1;
+      add(p + "g1", u, G, d, 1);
+      add(p + "wqkv", u, M, 3 * d, d);
+      add(p + "wo", u, M, d, d);
+      add(p + "g2", u, G, d, 1);
+      add(p + "wgu", u, M, 2 * f, d);
+      add(p + "wd", u, M, d, f);
+    }
+    add("gf", nl + 1, G, d, 1);
+    add("whead", nl + 1, M, V, d);
+  }
+  L.n_units = nl + 2;
+  L.n_params = off;
+  L.unit_off.assign(L.n_units, 0);
+  L.unit_cnt.assign(L.n_units, 0);
+  L.unit_first.assign(L.n_units + 1, (int)L.t.size());
+  for (int i = (int)L.t.size() - 1; i >= 0; --i) {
+    L.unit_first[L.t[i].unit] = i;
+    L.unit_off[L.t[i].unit] = L.t[i].off;
+    L.unit_cnt[L.t[i].unit] += L.t[i].count();
+  }
+}
+
+int group_count(int n, int m) { return n % m == 0 ? n / m : n / m + 1; }
+
+uint64_t splitmix64(uint64_t& s) {
+  s += 0x9E3779B97F4A7C15ull;
+  uint64_t z = s;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+void make_order(int k, int strategy, uint64_t seed, int32_t* out) {
+  for (int i = 0; i < k; ++i) out[i] = strategy == HIFT_TOP2DOWN ? k - 1 - i : i;
+  if (strategy == HIFT_RANDOM) {
+    uint64_t s = seed;
+    for (int i = k - 1; i > 0; --i) {
+      const int j = (int)(splitmix64(s) % (uint64_t)(i + 1));
+      std::swap(out[i], out[j]);
+    }
+  }
+}
+
+int n_state_of(const hift_opt& o) {
+  if (o.kind == HIFT_ADAMW) return 2;
+  if (o.kind == HIFT_ADAGRAD) return 1;
+  return o.momentum > 0.f ? 1 : 0;
+}
+
+hift_status check_opt(const hift_opt* o) {
+  if (!o) return fail(HIFT_EINVAL, "optimizer is null");
+  if (o->kind < 0 || o->kind > 2) return fail(HIFT_EINVAL, "optimizer kind %d unknown", o->kind);
+  if (o->momentum < 0.f) return fail(HIFT_EINVAL, "momentum must be >= 0");
+  return HIFT_OK;
+}
+
+inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Bump allocator over the caller's arena.  With base == nullptr it only measures.
+struct Bump {
+  unsigned char* base;
+  size_t used = 0;
+  explicit Bump(void* b) : base(reinterpret_cast<unsigned char*>(b)) {}
+  void* take(size_t bytes) {
+    void* p = base ? base + used : nullptr;
+    used += up256(bytes);
+    return p;
+  }
+};
+
+struct LayerAct {
+  void *na, *qkv, *prob, *ctx, *xmid, *nb, *fpre, *act;  // na: h1 | s1, nb: h2 | s2
+  float *st1, *st2;
+};
+
+struct Prof {
+  bool on = false;
+  struct Rec { hipEvent_t a, b; int cat; double work; };
+  std::vector<Rec> pool;
+  size_t used = 0;
+};
+
+}  // namespace
+
+struct hift_model {
+  hift_config cfg;
+  hift_opt opt;
+  Layout lay;
+  int dt, es;  // element type of weights/activations, its size
+  int max_batch, max_seq_len;
+  int64_t maxT;
+  int64_t grad_cap;  // parameters the gradient buffer and one state slot can hold
+  int n_state;
+  bool on_host;
+  // device memory
+  float* master = nullptr;
+  void* wc = nullptr;  // weights the forward uses: bf16 copy, or the master itself in fp32 mode
+  float* grad = nullptr;
+  float* state_full = nullptr;  // [n_state][n_params] when state stays in HBM
+  float* slot[2] = {nullptr, nullptr};  // [n_state][grad_cap] each when state lives on the host
+  float* host_state = nullptr;          // pinned [n_state][n_params]
+  float* cos_sin = nullptr;
+  std::vector<void*> xs;  // residual stream: xs[l] enters layer l, xs[L] enters the head
+  std::vector<LayerAct> la;
+  void *e0 = nullptr, *xf = nullptr, *xcls = nullptr, *logits = nullptr;
+  float *st_e = nullptr, *st_f = nullptr, *row_loss = nullptr, *loss_dev = nullptr, *part = nullptr;
+  void *D[3] = {nullptr, nullptr, nullptr}, *dqkv = nullptr, *dprob = nullptr, *dact = nullptr, *dffn = nullptr,
+       *dcls = nullptr;
+  // streams and events
+  hipStream_t cs, hs, ds;
+  hipEvent_t ev_h2d[2], ev_opt[2], ev_d2h[2], ev_t0, ev_t1, ev_w0, ev_w1;
+  bool d2h_pending[2] = {false, false};
+  int slot_group[2] = {-1, -1};  // group whose state a slot holds (arrived or in flight)
+  int cur_slot = 0;
+  // schedule
+  int m = 0, k = 0;
+  std::vector<int32_t> order;
+  std::vector<int64_t> group_steps;
+  int64_t t = 0;
+  uint64_t h2d_bytes = 0, d2h_bytes = 0;
+  bool timed = false;
+  Prof prof;
+
+  const Tensor& T_(const std::string& n) const { return lay.t[lay.find(n)]; }
+  void* W(const Tensor& t) const { return reinterpret_cast<unsigned char*>(wc) + t.off * es; }
+  void* W(const std::string& n) const { return W(T_(n)); }
+};
+
+namespace {
+
+// Carves every buffer of a model out of the arenas (or only measures them when arena == null).
+void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes) {
+  hift_model& M = *mm;
+  const hift_config& c = M.cfg;
+  const int64_t d = c.d_model, f = c.d_ffn, V = c.vocab, H = c.n_heads;
+  const int64_t T = M.maxT, B = M.max_batch, S = M.max_seq_len;
+  const int64_t np = M.lay.n_params;
+  const size_t es = M.es;
+  const bool enc = c.arch == HIFT_ARCH_POSTLN_ENCODER, rms = c.arch == HIFT_ARCH_RMS_ROPE_DECODER;
+  const int64_t fw = rms ? 2 * f : f;
+  Bump b(dev);
+  M.master = (float*)b.take(np * 4);
+  M.wc = M.dt == DT_BF16 ? b.take(np * 2) : (void*)M.master;
+  M.grad = (float*)b.take(M.grad_cap * 4);
+  if (M.n_state > 0) {
+    if (M.on_host) {
+      M.slot[0] = (float*)b.take((size_t)M.n_state * M.grad_cap * 4);
+      M.slot[1] = (float*)b.take((size_t)M.n_state * M.grad_cap * 4);
+    } else {
+      M.state_full = (float*)b.take((size_t)M.n_state * np * 4);
+    }
+  }
+  if (rms) M.cos_sin = (float*)b.take((size_t)c.max_seq * (d / H / 2) * 2 * 4);
+  M.xs.assign(c.n_layers + 1, nullptr);
+  for (auto& x : M.xs) x = b.take(T * d * es);
+  M.la.assign(c.n_layers, LayerAct{});
+  for (auto& a : M.la) {
+    a.na = b.take(T * d * es);
+    a.qkv = b.take(T * 3 * d * es);
+    a.prob = b.take(B * H * S * S * es);
+    a.ctx = b.take(T * d * es);
+    a.xmid = b.take(T * d * es);
+    a.nb = b.take(T * d * es);
+    a.fpre = b.take(T * fw * es);
+    a.act = b.take(T * f * es);
+    a.st1 = (float*)b.take(T * 2 * 4);
+    a.st2 = (float*)b.take(T * 2 * 4);
+  }
+  if (enc) {
+    M.e0 = b.take(T * d * es);
+    M.st_e = (float*)b.take(T * 2 * 4);
+    M.xcls = b.take(B * d * es);
+    M.dcls = b.take(B * d * es);
+    M.logits = b.take(B * (int64_t)c.n_classes * es);
+  } else {
+    M.xf = b.take(T * d * es);
+    M.st_f = (float*)b.take(T * 2 * 4);
+    M.logits = b.take(T * V * es);
+  }
+  M.row_loss = (float*)b.take((T + 1) * 4);
+  M.loss_dev = (float*)b.take(256);
+  const int64_t wmax = std::max<int64_t>(std::max<int64_t>(3 * d, fw), std::max<int64_t>(d, c.n_classes));
+  M.part = (float*)b.take((size_t)2 * ((T + 63) / 64) * wmax * 4);
+  for (auto& x : M.D) x = b.take(T * d * es);
+  M.dqkv = b.take(T * 3 * d * es);
+  M.dprob = b.take(B * H * S * S * es);
+  M.dact = b.take(T * f * es);
+  M.dffn = b.take(T * fw * es);
+  if (dev_bytes) *dev_bytes = b.used;
+  if (pinned_bytes) *pinned_bytes = (M.on_host && M.n_state > 0) ? (size_t)M.n_state * np * 4 : 0;
+}
+
+int64_t largest_group(const Layout& L, int m) {
+  const int k = group_count(L.n_units, m);
+  int64_t best = 0;
+  for (int j = 0; j < k; ++j) {
+    int64_t c = 0;
+    for (int u = j * m; u < std::min((j + 1) * m, L.n_units); ++u) c += L.unit_cnt[u];
+    best = std::max(best, c);
+  }
+  return best;
+}
+
+hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_opt* opt, int m, int max_batch,
+                             int max_seq) {
+  hift_status s = check_config(cfg);
+  if (s != HIFT_OK) return s;
+  s = check_opt(opt);
+  if (s != HIFT_OK) return s;
+  if (m < 1) return fail(HIFT_EINVAL, "m must be >= 1");
+  if (max_batch < 1 || max_seq < 1) return fail(HIFT_EINVAL, "max_batch and max_seq must be >= 1");
+  if (max_seq > cfg->max_seq) return fail(HIFT_EINVAL, "max_seq %d exceeds the position range %d", max_seq, cfg->max_seq);
+  M->cfg = *cfg;
+  M->opt = *opt;
+  M->dt = cfg->dtype == HIFT_BF16 ? DT_BF16 : DT_F32;
+  M->es = (int)dt_size(M->dt);
+  M->max_batch = max_batch;
+  M->max_seq_len = max_seq;
+  M->maxT = (int64_t)max_batch * max_seq;
+  build_layout(*cfg, M->lay);
+  M->grad_cap = (largest_group(M->lay, m) + 63) & ~(int64_t)63;
+  M->n_state = n_state_of(*opt);
+  M->on_host = cfg->state_on_host != 0;
+  return HIFT_OK;
+}
+
+// ---- profiling of kernel classes (events around launches) ---------------------------------
+enum { CAT_GEMM = 0, CAT_ATTN = 1, CAT_ELEM = 2, CAT_OPT = 3, CAT_N = 4 };
+
+struct Scope {
+  hift_model* M;
+  Prof::Rec* r = nullptr;
+  Scope(hift_model* m, int cat, double work) : M(m) {
+    if (!M->prof.on) return;
+    if (M->prof.used == M->prof.pool.size()) {
+      Prof::Rec n{};
+      if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
+      M->prof.pool.push_back(n);
+    }
+    r = &M->prof.pool[M->prof.used++];
+    r->cat = cat;
+    r->work = work;
+    (void)hipEventRecord(r->a, M->cs);
+  }
+  ~Scope() {
+    if (r) (void)hipEventRecord(r->b, M->cs);
+  }
+};
+
+#define K_TRY(expr) HIP_TRY(expr)
+
+hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, const Tensor* bias, const void* R,
+                   void* y) {
+  // y[rows, out] = x[rows, in] . w[out, in]^T (+ bias) (+ R)
+  Gemm g;
+  g.dtype = M->dt;
+  g.M = rows; g.N = w.rows; g.K = w.cols;
+  g.A = x; g.lda = w.cols;
+  g.B = M->W(w); g.ldb = w.cols;
+  g.C = y; g.ldc = w.rows;
+  g.bias = bias ? M->W(*bias) : nullptr;
+  g.R = R; g.ldr = w.rows;
+  Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
+  K_TRY(gemm(g, M->cs));
+  return HIFT_OK;
+}
+
+hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor& w, const void* R, void* dx) {
+  // dx[rows, in] = dy[rows, out] . w[out, in] (+ R)
+  Gemm g;
+  g.dtype = M->dt;
+  g.M = rows; g.N = w.cols; g.K = w.rows;
+  g.A = dy; g.lda = w.rows;
+  g.B = M->W(w); g.ldb = w.cols; g.b_kmajor = false;
+  g.C = dx; g.ldc = w.cols;
+  g.R = R; g.ldr = w.cols;
+  Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
+  K_TRY(gemm(g, M->cs));
+  return HIFT_OK;
+}
+
+hift_status linear_dw(hift_model* M, const void* dy, const void* x, int64_t rows, const Tensor& w, int64_t glo) {
+  // grad_w[out, in] = dy[rows, out]^T . x[rows, in], fp32, into the group-local gradient buffer
+  Gemm g;
+  g.dtype = M->dt;
+  g.out_f32 = true;
+  g.M = w.rows; g.N = w.cols; g.K = rows;
+  g.A = dy; g.lda = w.rows; g.a_kmajor = false;
+  g.B = x; g.ldb = w.cols; g.b_kmajor = false;
+  g.C = M->grad + (w.off - glo); g.ldc = w.cols;
+  Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
+  K_TRY(gemm(g, M->cs));
+  return HIFT_OK;
+}
+
+hift_status bias_grad(hift_model* M, const void* dy, int64_t rows, const Tensor& b, int64_t glo) {
+  Scope sc(M, CAT_ELEM, 0);
+  K_TRY(col_sum(M->dt, rows, b.rows, dy, b.rows, M->part, M->grad + (b.off - glo), M->cs));
+  return HIFT_OK;
+}
+
+hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S) {
+  const hift_config& c = M->cfg;
+  const int64_t d = c.d_model, H = c.n_heads, hd = d / H;
+  const size_t es = M->es;
+  unsigned char* qkv = (unsigned char*)a.qkv;
+  const bool causal = c.arch != HIFT_ARCH_POSTLN_ENCODER;
+  {
+    Gemm g;  // scores = q . k^T
+    g.dtype = M->dt;
+    g.M = S; g.N = S; g.K = hd;
+    g.A = qkv; g.lda = 3 * d;
+    g.B = qkv + d * es; g.ldb = 3 * d;
+    g.C = a.prob; g.ldc = S;
+    g.nb = B; g.nh = (int)H;
+    g.sa1 = (int64_t)S * 3 * d; g.sa2 = hd; g.sb1 = g.sa1; g.sb2 = hd;
+    g.sc1 = H * (int64_t)S * S; g.sc2 = (int64_t)S * S;
+    Scope sc(M, CAT_ATTN, 2.0 * B * H * S * S * hd);
+    K_TRY(gemm(g, M->cs));
+  }
+  {
+    Scope sc(M, CAT_ELEM, 0);
+    K_TRY(softmax_fwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, a.prob, M->cs));
+  }
+  {
+    Gemm g;  // ctx = p . v
+    g.dtype = M->dt;
+    g.M = S; g.N = hd; g.K = S;
+    g.A = a.prob; g.lda = S;
+    g.B = qkv + 2 * d * es; g.ldb = 3 * d; g.b_kmajor = false;
+    g.C = a.ctx; g.ldc = d;
+    g.nb = B; g.nh = (int)H;
+    g.sa1 = H * (int64_t)S * S; g.sa2 = (int64_t)S * S;
+    g.sb1 = (int64_t)S * 3 * d; g.sb2 = hd;
+    g.sc1 = (int64_t)S * d; g.sc2 = hd;
+    Scope sc(M, CAT_ATTN, 2.0 * B * H * S * S * hd);
+    K_TRY(gemm(g, M->cs));
+  }
+  return HIFT_OK;
+}
+
+hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, int S) {
+  // dctx [T, d] -> M->dqkv [T, 3d] (gradients with respect to the rotated q, k and to v)
+  const hift_config& c = M->cfg;
+  const int64_t d = c.d_model, H = c.n_heads, hd = d / H;
+  const size_t es = M->es;
+  unsigned char* qkv = (unsigned char*)a.qkv;
+  unsigned char* dqkv = (unsigned char*)M->dqkv;
+  const double fl = 2.0 * B * H * S * S * hd;
+  auto batch = [&](Gemm& g) { g.dtype = M->dt; g.nb = B; g.nh = (int)H; };
+  const int64_t sP1 = H * (int64_t)S * S, sP2 = (int64_t)S * S, sQ1 = (int64_t)S * 3 * d, sX1 = (int64_t)S * d;
+  {
+    Gemm g;  // dv[j,e] = sum_i p[i,j] dctx[i,e]
+    batch(g);
+    g.M = S; g.N = hd; g.K = S;
+    g.A = a.prob; g.lda = S; g.a_kmajor = false; g.sa1 = sP1; g.sa2 = sP2;
+    g.B = dctx; g.ldb = d; g.b_kmajor = false; g.sb1 = sX1; g.sb2 = hd;
+    g.C = dqkv + 2 * d * es; g.ldc = 3 * d; g.sc1 = sQ1; g.sc2 = hd;
+    Scope sc(M, CAT_ATTN, fl);
+    K_TRY(gemm(g, M->cs));
+  }
+  {
+    Gemm g;  // dp[i,j] = sum_e dctx[i,e] v[j,e]
+    batch(g);
+    g.M = S; g.N = S; g.K = hd;
+    g.A = dctx; g.lda = d; g.sa1 = sX1; g.sa2 = hd;
+    g.B = qkv + 2 * d * es; g.ldb = 3 * d; g.sb1 = sQ1; g.sb2 = hd;
+    g.C = M->dprob; g.ldc = S; g.sc1 = sP1; g.sc2 = sP2;
+    Scope sc(M, CAT_ATTN, fl);
+    K_TRY(gemm(g, M->cs));
+  }
+  {
+    Scope sc(M, CAT_ELEM, 0);
+    K_TRY(softmax_bwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), a.prob, M->dprob, M->cs));
+  }
+  {
+    Gemm g;  // dq[i,e] = sum_j ds[i,j] k[j,e]
+    batch(g);
+    g.M = S; g.N = hd; g.K = S;
+    g.A = M->dprob; g.lda = S; g.sa1 = sP1; g.sa2 = sP2;
+    g.B = qkv + d * es; g.ldb = 3 * d; g.b_kmajor = false; g.sb1 = sQ1; g.sb2 = hd;
+    g.C = dqkv; g.ldc = 3 * d; g.sc1 = sQ1; g.sc2 = hd;
+    Scope sc(M, CAT_ATTN, fl);
+    K_TRY(gemm(g, M->cs));
+  }
+  {
+    Gemm g;  // dk[j,e] = sum_i ds[i,j] q[i,e]
+    batch(g);
+    g.M = S; g.N = hd; g.K = S;
+    g.A = M->dprob; g.lda = S; g.a_kmajor = false; g.sa1 = sP1; g.sa2 = sP2;
+    g.B = qkv; g.ldb = 3 * d; g.b_kmajor = false; g.sb1 = sQ1; g.sb2 = hd;
+    g.C = dqkv + d * es; g.ldc = 3 * d; g.sc1 = sQ1; g.sc2 = hd;
+    Scope sc(M, CAT_ATTN, fl);
+    K_TRY(gemm(g, M->cs));
+  }
+  return HIFT_OK;
+}
+
+struct Names {
+  const Tensor *n1g, *n1b, *wqkv, *bqkv, *wo, *bo, *n2g, *n2b, *w1, *b1, *w2, *b2;
+};
+
+Names layer_names(const hift_model* M, int l) {
+  const std::string p = "l" + std::to_string(l) + ".";
+  auto get = [&](const char* n) -> const Tensor* {
+    const int i = M->lay.find(p + n);
+    return i < 0 ? nullptr : &M->lay.t[i];
+  };
+  Names n{};
+  if (M->cfg.arch == HIFT_ARCH_RMS_ROPE_DECODER) {
+    n.n1g = get("g1"); n.wqkv = get("wqkv"); n.wo = get("wo"); n.n2g = get("g2"); n.w1 = get("wgu"); n.w2 = get("wd");
+  } else {
+    n.n1g = get("ln1_g"); n.n1b = get("ln1_b"); n.wqkv = get("wqkv"); n.bqkv = get("bqkv"); n.wo = get("wo");
+    n.bo = get("bo"); n.n2g = get("ln2_g"); n.n2b = get("ln2_b"); n.w1 = get("w1"); n.b1 = get("b1");
+    n.w2 = get("w2"); n.b2 = get("b2");
+  }
+  return n;
+}
+
+#define ST_TRY(expr)                 \
+  do {                               \
+    hift_status s_ = (expr);         \
+    if (s_ != HIFT_OK) return s_;    \
+  } while (0)
+
+hift_status ew(hift_model* M, hipError_t e) {
+  if (e != hipSuccess) return fail(HIFT_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
+  (void)M;
+  return HIFT_OK;
+}
+
+hift_status forward(hift_model* M, const hift_batch* bt) {
+  const hift_config& c = M->cfg;
+  const int B = bt->batch, S = bt->seq;
+  const int64_t T = (int64_t)B * S;
+  const int d = c.d_model, f = c.d_ffn, H = c.n_heads, hd = d / H;
+  const int dt = M->dt;
+  const bool enc = c.arch == HIFT_ARCH_POSTLN_ENCODER, rms = c.arch == HIFT_ARCH_RMS_ROPE_DECODER;
+  hipStream_t st = M->cs;
+  {
+    Scope sc(M, CAT_ELEM, 0);
+    const void* pos = rms ? nullptr : M->W("pos_emb");
+    void* dst = enc ? M->e0 : M->xs[0];
+    ST_TRY(ew(M, embed_fwd(dt, bt->tokens, T, S, d, c.vocab, M->W("tok_emb"), pos, dst, st)));
+    if (enc) ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, M->e0, M->W("lne_g"), M->W("lne_b"), M->xs[0], M->st_e, st)));
+  }
+  for (int l = 0; l < c.n_layers; ++l) {
+    LayerAct& a = M->la[l];
+    const Names n = layer_names(M, l);
+    const void* x = M->xs[l];
+    const void* h1 = x;
+    if (!enc) {
+      Scope sc(M, CAT_ELEM, 0);
+      ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, x, M->W(*n.n1g), n.n1b ? M->W(*n.n1b) : nullptr, a.na, a.st1, st)));
+      h1 = a.na;
+    }
+    ST_TRY(linear(M, h1, T, *n.wqkv, n.bqkv, nullptr, a.qkv));
+    if (rms) {
+      Scope sc(M, CAT_ELEM, 0);
+      ST_TRY(ew(M, rope(dt, a.qkv, T, S, H, hd, M->cos_sin, +1, st)));
+    }
+    ST_TRY(attention_fwd(M, a, B, S));
+    if (enc) {
+      ST_TRY(linear(M, a.ctx, T, *n.wo, n.bo, x, a.na));  // s1 = x + attn
+      Scope sc(M, CAT_ELEM, 0);
+      ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, a.na, M->W(*n.n1g), M->W(*n.n1b), a.xmid, a.st1, st)));
+    } else {
+      ST_TRY(linear(M, a.ctx, T, *n.wo, n.bo, x, a.xmid));
+    }
+    const void* h2 = a.xmid;
+    if (!enc) {
+      Scope sc(M, CAT_ELEM, 0);
+      ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, a.xmid, M->W(*n.n2g), n.n2b ? M->W(*n.n2b) : nullptr, a.nb, a.st2, st)));
+      h2 = a.nb;
+    }
+    ST_TRY(linear(M, h2, T, *n.w1, n.b1, nullptr, a.fpre));
+    {
+      Scope sc(M, CAT_ELEM, 0);
+      if (rms) ST_TRY(ew(M, swiglu_fwd(dt, T, f, a.fpre, a.act, st)));
+      else ST_TRY(ew(M, gelu_fwd(dt, T * f, a.fpre, a.act, st)));
+    }
+    if (enc) {
+      ST_TRY(linear(M, a.act, T, *n.w2, n.b2, a.xmid, a.nb));  // s2 = xmid + ffn
+      Scope sc(M, CAT_ELEM, 0);
+      ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, a.nb, M->W(*n.n2g), M->W(*n.n2b), M->xs[l + 1], a.st2, st)));
+    } else {
+      ST_TRY(linear(M, a.act, T, *n.w2, n.b2, a.xmid, M->xs[l + 1]));
+    }
+  }
+  void* xl = M->xs[c.n_layers];
+  if (enc) {
+    {
+      Scope sc(M, CAT_ELEM, 0);
+      ST_TRY(ew(M, gather_first(dt, B, S, d, xl, M->xcls, st)));
+    }
+    ST_TRY(linear(M, M->xcls, B, M->T_("wc"), &M->T_("bc"), nullptr, M->logits));
+    Scope sc(M, CAT_ELEM, 0);
+    ST_TRY(ew(M, cross_entropy(dt, B, c.n_classes, M->logits, bt->labels, M->row_loss, M->loss_dev, st)));
+  } else {
+    {
+      Scope sc(M, CAT_ELEM, 0);
+      if (rms) ST_TRY(ew(M, norm_fwd(dt, true, T, d, c.norm_eps, xl, M->W("gf"), nullptr, M->xf, M->st_f, st)));
+      else ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, xl, M->W("lnf_g"), M->W("lnf_b"), M->xf, M->st_f, st)));
+    }
+    ST_TRY(linear(M, M->xf, T, M->T_("whead"), nullptr, nullptr, M->logits));
+    Scope sc(M, CAT_ELEM, 0);
+    ST_TRY(ew(M, cross_entropy(dt, T, c.vocab, M->logits, bt->labels, M->row_loss, M->loss_dev, st)));
+  }
+  return HIFT_OK;
+}
+
+// Backward from the loss down to unit `lo`; weight gradients for units in [ulo, uhi) only.
+hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int64_t glo) {
+  const hift_config& c = M->cfg;
+  const int B = bt->batch, S = bt->seq;
+  const int64_t T = (int64_t)B * S;
+  const int d = c.d_model, f = c.d_ffn, H = c.n_heads, hd = d / H;
+  const int dt = M->dt, L = c.n_layers;
+  const bool enc = c.arch == HIFT_ARCH_POSTLN_ENCODER, rms = c.arch == HIFT_ARCH_RMS_ROPE_DECODER;
+  hipStream_t st = M->cs;
+  auto active = [&](int u) { return u >= ulo && u < uhi; };
+  auto G = [&](const Tensor& t) { return M->grad + (t.off - glo); };
+  void *Dc = M->D[0], *D1 = M->D[1], *D2 = M->D[2];
+
+  // ---- head unit (L+1) ----
+  const bool head_on = active(L + 1);
+  if (enc) {
+    const Tensor &wc = M->T_("wc"), &bc = M->T_("bc");
+    if (head_on) {
+      ST_TRY(linear_dw(M, M->logits, M->xcls, B, wc, glo));
+      ST_TRY(bias_grad(M, M->logits, B, bc, glo));
+    }
+    if (ulo == L + 1) return HIFT_OK;
+    ST_TRY(linear_dx(M, M->logits, B, wc, nullptr, M->dcls));
+    Scope sc(M, CAT_ELEM, 0);
+    ST_TRY(ew(M, scatter_first(dt, B, S, d, M->dcls, Dc, st)));
+  } else {
+    const Tensor& wh = M->T_("whead");
+    if (head_on) ST_TRY(linear_dw(M, M->logits, M->xf, T, wh, glo));
+    ST_TRY(linear_dx(M, M->logits, T, wh, nullptr, D2));  // d xf
+    const Tensor& g = M->T_(rms ? "gf" : "lnf_g");
+    Scope sc(M, CAT_ELEM, 0);
+    if (head_on)
+      ST_TRY(ew(M, norm_bwd_params(dt, rms, T, d, D2, M->xs[L], M->st_f, M->part, G(g),
+                                   rms ? nullptr : G(M->T_("lnf_b")), st)));
+    if (ulo == L + 1) return HIFT_OK;
+    ST_TRY(ew(M, norm_bwd_dx(dt, rms, T, d, D2, M->xs[L], M->W(g), M->st_f, nullptr, Dc, st)));
+  }
+
+  // ---- hidden layers, top down; Dc holds d loss / d xs[l+1] ----
+  for (int l = L - 1; l >= 0; --l) {
+    const int u = l + 1;
+    if (u < ulo) break;
+    const bool on = active(u), need_dx = u > ulo;
+    LayerAct& a = M->la[l];
+    const Names n = layer_names(M, l);
+    const void* x = M->xs[l];
+    if (!enc) {
+      // x_out = xmid + W2 act(W1 h2),  h2 = norm2(xmid)
+      if (on) {
+        ST_TRY(linear_dw(M, Dc, a.act, T, *n.w2, glo));
+        if (n.b2) ST_TRY(bias_grad(M, Dc, T, *n.b2, glo));
+      }
+      ST_TRY(linear_dx(M, Dc, T, *n.w2, nullptr, M->dact));
+      {
+        Scope sc(M, CAT_ELEM, 0);
+        if (rms) ST_TRY(ew(M, swiglu_bwd(dt, T, f, M->dact, a.fpre, M->dffn, st)));
+        else ST_TRY(ew(M, gelu_bwd(dt, T * f, M->dact, a.fpre, M->dffn, st)));
+      }
+      if (on) {
+        ST_TRY(linear_dw(M, M->dffn, a.nb, T, *n.w1, glo));
+        if (n.b1) ST_TRY(bias_grad(M, M->dffn, T, *n.b1, glo));
+      }
+      ST_TRY(linear_dx(M, M->dffn, T, *n.w1, nullptr, D2));  // d h2
+      {
+        Scope sc(M, CAT_ELEM, 0);
+        if (on)
+          ST_TRY(ew(M, norm_bwd_params(dt, rms, T, d, D2, a.xmid, a.st2, M->part, G(*n.n2g),
+                                       n.n2b ? G(*n.n2b) : nullptr, st)));
+        ST_TRY(ew(M, norm_bwd_dx(dt, rms, T, d, D2, a.xmid, M->W(*n.n2g), a.st2, Dc, D1, st)));  // d xmid
+      }
+      // xmid = x + Wo ctx
+      if (on) {
+        ST_TRY(linear_dw(M, D1, a.ctx, T, *n.wo, glo));
+        if (n.bo) ST_TRY(bias_grad(M, D1, T, *n.bo, glo));
+      }
+      ST_TRY(linear_dx(M, D1, T, *n.wo, nullptr, D2));  // d ctx
+      ST_TRY(attention_bwd(M, a, D2, B, S));
+      if (rms) {
+        Scope sc(M, CAT_ELEM, 0);
+        ST_TRY(ew(M, rope(dt, M->dqkv, T, S, H, hd, M->cos_sin, -1, st)));
+      }
+      if (on) {
+        ST_TRY(linear_dw(M, M->dqkv, a.na, T, *n.wqkv, glo));
+        if (n.bqkv) ST_TRY(bias_grad(M, M->dqkv, T, *n.bqkv, glo));
+      }
+      if (on || need_dx) {
+        ST_TRY(linear_dx(M, M->dqkv, T, *n.wqkv, nullptr, D2));  // d h1
+        Scope sc(M, CAT_ELEM, 0);
+        if (on)
+          ST_TRY(ew(M, norm_bwd_params(dt, rms, T, d, D2, x, a.st1, M->part, G(*n.n1g),
+                                       n.n1b ? G(*n.n1b) : nullptr, st)));
+        if (need_dx) ST_TRY(ew(M, norm_bwd_dx(dt, rms, T, d, D2, x, M->W(*n.n1g), a.st1, D1, Dc, st)));
+      }
+    } else {
+      // x_out = LN2(s2), s2 = xmid + W2 gelu(W1 xmid);  xmid = LN1(s1), s1 = x + Wo ctx
+      {
+        Scope sc(M, CAT_ELEM, 0);
+        if (on) ST_TRY(ew(M, norm_bwd_params(dt, false, T, d, Dc, a.nb, a.st2, M->part, G(*n.n2g), G(*n.n2b), st)));
+        ST_TRY(ew(M, norm_bwd_dx(dt, false, T, d, Dc, a.nb, M->W(*n.n2g), a.st2, nullptr, D1, st)));  // d s2
+      }
+      if (on) {
+        ST_TRY(linear_dw(M, D1, a.act, T, *n.w2, glo));
+        ST_TRY(bias_grad(M, D1, T, *n.b2, glo));
+      }
+      ST_TRY(linear_dx(M, D1, T, *n.w2, nullptr, M->dact));
+      {
+        Scope sc(M, CAT_ELEM, 0);
+        ST_TRY(ew(M, gelu_bwd(dt, T * f, M->dact, a.fpre, M->dffn, st)));
+      }
+      if (on) {
+        ST_TRY(linear_dw(M, M->dffn, a.xmid, T, *n.w1, glo));
+        ST_TRY(bias_grad(M, M->dffn, T, *n.b1, glo));
+      }
+      ST_TRY(linear_dx(M, M->dffn, T, *n.w1, D1, D2));  // d xmid = d s2 + dffn . W1
+      {
+        Scope sc(M, CAT_ELEM, 0);
+        if (on) ST_TRY(ew(M, norm_bwd_params(dt, false, T, d, D2, a.na, a.st1, M->part, G(*n.n1g), G(*n.n1b), st)));
+        ST_TRY(ew(M, norm_bwd_dx(dt, false, T, d, D2, a.na, M->W(*n.n1g), a.st1, nullptr, D1, st)));  // d s1
+      }
+      if (on) {
+        ST_TRY(linear_dw(M, D1, a.ctx, T, *n.wo, glo));
+        ST_TRY(bias_grad(M, D1, T, *n.bo, glo));
+      }
+      ST_TRY(linear_dx(M, D1, T, *n.wo, nullptr, D2));  // d ctx
+      ST_TRY(attention_bwd(M, a, D2, B, S));
+      if (on) {
+        ST_TRY(linear_dw(M, M->dqkv, x, T, *n.wqkv, glo));
+        ST_TRY(bias_grad(M, M->dqkv, T, *n.bqkv, glo));
+      }
+      if (need_dx) ST_TRY(linear_dx(M, M->dqkv, T, *n.wqkv, D1, Dc));  // d x = d s1 + dqkv . Wqkv
+    }
+  }
+
+  // ---- embeddings unit (0) ----
+  if (ulo == 0) {
+    Scope sc(M, CAT_ELEM, 0);
+    const Tensor& te = M->T_("tok_emb");
+    const void* dx = Dc;
+    if (enc) {
+      ST_TRY(ew(M, norm_bwd_params(dt, false, T, d, Dc, M->e0, M->st_e, M->part, G(M->T_("lne_g")), G(M->T_("lne_b")), st)));
+      ST_TRY(ew(M, norm_bwd_dx(dt, false, T, d, Dc, M->e0, M->W("lne_g"), M->st_e, nullptr, D1, st)));
+      dx = D1;
+    }
+    float* gpos = nullptr;
+    int64_t zero_cnt = te.count();
+    if (!rms) {
+      const Tensor& pe = M->T_("pos_emb");
+      gpos = G(pe);
+      zero_cnt += pe.count();  // pos_emb follows tok_emb in the layout
+    }
+    ST_TRY(ew(M, fill_zero(G(te), (size_t)zero_cnt * 4, st)));
+    ST_TRY(ew(M, embed_bwd(dt, bt->tokens, T, S, d, c.vocab, dx, G(te), gpos, st)));
+  }
+  return HIFT_OK;
+}
+
+void group_range(const hift_model* M, int gid, int* ulo, int* uhi, int64_t* plo, int64_t* pcnt) {
+  const int lo = gid * M->m, hi = std::min((gid + 1) * M->m, M->lay.n_units);
+  *ulo = lo;
+  *uhi = hi;
+  *plo = M->lay.unit_off[lo];
+  int64_t c = 0;
+  for (int u = lo; u < hi; ++u) c += M->lay.unit_cnt[u];
+  *pcnt = c;
+}
+
+// Queue the host-to-device copy of a group's state into a slot (Algorithm 1 step i).
+hift_status fetch_state(hift_model* M, int gid, int s) {
+  int ulo, uhi;
+  int64_t plo, cnt;
+  group_range(M, gid, &ulo, &uhi, &plo, &cnt);
+  // the slot may still be draining to the host, and the host copy of this group may still be
+  // in flight from its last visit: both are ordered by the device-to-host events
+  for (int q = 0; q < 2; ++q)
+    if (M->d2h_pending[q]) HIP_TRY(hipStreamWaitEvent(M->hs, M->ev_d2h[q], 0));
+  for (int j = 0; j < M->n_state; ++j) {
+    HIP_TRY(hipMemcpyAsync(M->slot[s] + (size_t)j * M->grad_cap, M->host_state + (size_t)j * M->lay.n_params + plo,
+                           (size_t)cnt * 4, hipMemcpyHostToDevice, M->hs));
+    M->h2d_bytes += (uint64_t)cnt * 4;
+  }
+  HIP_TRY(hipEventRecord(M->ev_h2d[s], M->hs));
+  M->slot_group[s] = gid;
+  return HIFT_OK;
+}
+
+hift_status sync_all(hift_model* M) {
+  HIP_TRY(hipStreamSynchronize(M->cs));
+  HIP_TRY(hipStreamSynchronize(M->hs));
+  HIP_TRY(hipStreamSynchronize(M->ds));
+  M->d2h_pending[0] = M->d2h_pending[1] = false;
+  return HIFT_OK;
+}
+
+hift_status unit_span(const hift_model* M, int ulo, int uhi, int64_t* off, int64_t* cnt) {
+  if (ulo < 0 || uhi > M->lay.n_units || ulo >= uhi) return fail(HIFT_EINVAL, "unit range [%d,%d) invalid", ulo, uhi);
+  *off = M->lay.unit_off[ulo];
+  int64_t c = 0;
+  for (int u = ulo; u < uhi; ++u) c += M->lay.unit_cnt[u];
+  *cnt = c;
+  return HIFT_OK;
+}
+
+}  // namespace
+
+// ==========================================================================================
+// C ABI
+// ==========================================================================================
+extern "C" {
+
+const char* hift_last_error(void) { return g_err.c_str(); }
+
+hift_status hift_group_count(int32_t n_units, int32_t m, int32_t* k_out) {
+  if (n_units < 1 || m < 1 || !k_out) return fail(HIFT_EINVAL, "n_units and m must be >= 1");
+  *k_out = group_count(n_units, m);
+  return HIFT_OK;
+}
+
+hift_status hift_group_order(int32_t k, hift_strategy s, uint64_t seed, int32_t* order_out) {
+  if (k < 1 || !order_out || (int)s < 0 || (int)s > 2) return fail(HIFT_EINVAL, "bad k, strategy or output");
+  make_order(k, (int)s, seed, order_out);
+  return HIFT_OK;
+}
+
+hift_status hift_tensor_count(const hift_config* cfg, int32_t* n_tensors, int64_t* n_params) {
+  hift_status s = check_config(cfg);
+  if (s != HIFT_OK) return s;
+  Layout L;
+  build_layout(*cfg, L);
+  if (n_tensors) *n_tensors = (int32_t)L.t.size();
+  if (n_params) *n_params = L.n_params;
+  return HIFT_OK;
+}
+
+hift_status hift_tensor_at(const hift_config* cfg, int32_t index, hift_tensor_info* out) {
+  hift_status s = check_config(cfg);
+  if (s != HIFT_OK) return s;
+  if (!out) return fail(HIFT_EINVAL, "out is null");
+  Layout L;
+  build_layout(*cfg, L);
+  if (index < 0 || index >= (int)L.t.size()) return fail(HIFT_EINVAL, "tensor index %d out of range", index);
+  const Tensor& t = L.t[index];
+  memset(out, 0, sizeof *out);
+  snprintf(out->name, sizeof out->name, "%s", t.name.c_str());
+  out->unit = t.unit;
+  out->kind = t.kind;
+  out->offset = t.off;
+  out->rows = t.rows;
+  out->cols = t.cols;
+  return HIFT_OK;
+}
+
+hift_status hift_query_bytes(const hift_config* cfg, const hift_opt* opt, int32_t m, int32_t max_batch,
+                             int32_t max_seq, size_t* device_bytes, size_t* pinned_host_bytes) {
+  hift_model M;
+  hift_status s = init_model_shape(&M, cfg, opt, m, max_batch, max_seq);
+  if (s != HIFT_OK) return s;
+  carve(&M, nullptr, device_bytes, pinned_host_bytes);
+  return HIFT_OK;
+}
+
+hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32_t m, int32_t max_batch,
+                              int32_t max_seq, const float* init_params_host, void* device_arena,
+                              size_t device_bytes, void* pinned_arena, size_t pinned_bytes, void* compute_stream,
+                              void* h2d_stream, void* d2h_stream, hift_model** out) {
+  if (!out) return fail(HIFT_EINVAL, "out is null");
+  *out = nullptr;
+  hift_model* M = new hift_model();
+  hift_status s = init_model_shape(M, cfg, opt, m, max_batch, max_seq);
+  if (s != HIFT_OK) { delete M; return s; }
+  size_t need_dev = 0, need_pin = 0;
+  carve(M, nullptr, &need_dev, &need_pin);
+  if (!device_arena || (reinterpret_cast<uintptr_t>(device_arena) & 255)) {
+    delete M;
+    return fail(HIFT_EINVAL, "device arena must be non-null and 256-byte aligned");
+  }
+  if (device_bytes < need_dev || pinned_bytes < need_pin || (need_pin > 0 && !pinned_arena)) {
+    delete M;
+    return fail(HIFT_ENOMEM, "arenas too small: need %zu device and %zu pinned bytes", need_dev, need_pin);
+  }
+  carve(M, device_arena, nullptr, nullptr);
+  M->host_state = need_pin ? reinterpret_cast<float*>(pinned_arena) : nullptr;
+  M->cs = (hipStream_t)compute_stream;
+  M->hs = (hipStream_t)h2d_stream;
+  M->ds = (hipStream_t)d2h_stream;
+  auto bail = [&](hift_status st) { hift_model_destroy(M); return st; };
+#define CR_TRY(expr)                                                                                  \
+  do {                                                                                                \
+    hipError_t e_ = (expr);                                                                           \
+    if (e_ != hipSuccess) {                                                                           \
+      fail(HIFT_EDEVICE, "%s failed: %s", #expr, hipGetErrorString(e_));                              \
+      return bail(HIFT_EDEVICE);                                                                      \
+    }                                                                                                 \
+  } while (0)
+  hipEvent_t* evs[] = {&M->ev_h2d[0], &M->ev_h2d[1], &M->ev_opt[0], &M->ev_opt[1], &M->ev_d2h[0], &M->ev_d2h[1]};
+  for (auto e : evs) *e = nullptr;
+  M->ev_t0 = M->ev_t1 = M->ev_w0 = M->ev_w1 = nullptr;
+  for (auto e : evs) CR_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
+  CR_TRY(hipEventCreate(&M->ev_t0));
+  CR_TRY(hipEventCreate(&M->ev_t1));
+  CR_TRY(hipEventCreate(&M->ev_w0));
+  CR_TRY(hipEventCreate(&M->ev_w1));
+  if (M->host_state) memset(M->host_state, 0, need_pin);
+  // state and gradient buffers start at zero
+  if (M->state_full) CR_TRY(fill_zero(M->state_full, (size_t)M->n_state * M->lay.n_params * 4, M->cs));
+  for (int q = 0; q < 2; ++q)
+    if (M->slot[q]) CR_TRY(fill_zero(M->slot[q], (size_t)M->n_state * M->grad_cap * 4, M->cs));
+  CR_TRY(fill_zero(M->grad, (size_t)M->grad_cap * 4, M->cs));
+  if (M->cos_sin) {
+    const int hd2 = cfg->d_model / cfg->n_heads / 2;
+    std::vector<float> tab((size_t)cfg->max_seq * hd2 * 2);
+    for (int p = 0; p < cfg->max_seq; ++p)
+      for (int i = 0; i < hd2; ++i) {
+        const double ang = (double)p * pow((double)cfg->rope_base, -2.0 * i / (2.0 * hd2));
+        tab[((size_t)p * hd2 + i) * 2] = (float)cos(ang);
+        tab[((size_t)p * hd2 + i) * 2 + 1] = (float)sin(ang);
+      }
+    CR_TRY(hipMemcpyAsync(M->cos_sin, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, M->cs));
+    CR_TRY(hipStreamSynchronize(M->cs));
+  }
+  if (init_params_host) {
+    CR_TRY(hipMemcpyAsync(M->master, init_params_host, (size_t)M->lay.n_params * 4, hipMemcpyHostToDevice, M->cs));
+  } else {
+    CR_TRY(fill_zero(M->master, (size_t)M->lay.n_params * 4, M->cs));
+  }
+  if (M->dt == DT_BF16) CR_TRY(cast_f32_to(DT_BF16, M->lay.n_params, M->master, M->wc, M->cs));
+  CR_TRY(hipStreamSynchronize(M->cs));
+#undef CR_TRY
+  *out = M;
+  return HIFT_OK;
+}
+
+void hift_model_destroy(hift_model* M) {
+  if (!M) return;
+  if (M->cs) (void)hipStreamSynchronize(M->cs);
+  if (M->hs) (void)hipStreamSynchronize(M->hs);
+  if (M->ds) (void)hipStreamSynchronize(M->ds);
+  hipEvent_t evs[] = {M->ev_h2d[0], M->ev_h2d[1], M->ev_opt[0], M->ev_opt[1], M->ev_d2h[0], M->ev_d2h[1],
+                      M->ev_t0, M->ev_t1, M->ev_w0, M->ev_w1};
+  for (auto e : evs)
+    if (e) (void)hipEventDestroy(e);
+  for (auto& r : M->prof.pool) {
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  delete M;
+}
+
+hift_status hift_set_group_schedule(hift_model* M, hift_strategy s, int32_t m, uint64_t seed, int32_t* k_out) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  if (m < 1 || (int)s < 0 || (int)s > 2) return fail(HIFT_EINVAL, "bad m or strategy");
+  const int64_t need = largest_group(M->lay, m);
+  if (need > M->grad_cap) return fail(HIFT_ENOMEM, "largest group (%lld parameters) exceeds the buffers sized at creation (%lld)",
+                                      (long long)need, (long long)M->grad_cap);
+  hift_status st = sync_all(M);
+  if (st != HIFT_OK) return st;
+  // state held in a slot is already mirrored on the host (every step writes it back)
+  M->slot_group[0] = M->slot_group[1] = -1;
+  M->m = m;
+  M->k = group_count(M->lay.n_units, m);
+  M->order.resize(M->k);
+  make_order(M->k, (int)s, seed, M->order.data());
+  M->group_steps.assign(M->k, 0);
+  M->t = 0;
+  if (k_out) *k_out = M->k;
+  return HIFT_OK;
+}
+
+hift_status hift_schedule_group_at(const hift_model* M, int64_t t, int32_t* gid) {
+  if (!M || !gid) return fail(HIFT_EINVAL, "null argument");
+  if (M->k == 0) return fail(HIFT_ESTATE, "no schedule set");
+  if (t < 1) return fail(HIFT_EINVAL, "steps are numbered from 1");
+  *gid = M->order[(t - 1) % M->k];
+  return HIFT_OK;
+}
+
+hift_status hift_group_units(const hift_model* M, int32_t gid, int32_t* unit_lo, int32_t* unit_hi) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  if (M->k == 0) return fail(HIFT_ESTATE, "no schedule set");
+  if (gid < 0 || gid >= M->k) return fail(HIFT_EINVAL, "group %d outside [0,%d)", gid, M->k);
+  if (unit_lo) *unit_lo = gid * M->m;
+  if (unit_hi) *unit_hi = std::min((gid + 1) * M->m, M->lay.n_units);
+  return HIFT_OK;
+}
+
+hift_status hift_set_lr(hift_model* M, float lr) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  M->opt.lr = lr;
+  return HIFT_OK;
+}
+
+hift_status hift_cycle_index(const hift_model* M, int64_t* steps_done, int64_t* cycles_done) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  if (M->k == 0) return fail(HIFT_ESTATE, "no schedule set");
+  if (steps_done) *steps_done = M->t;
+  if (cycles_done) *cycles_done = M->t / M->k;
+  return HIFT_OK;
+}
+
+hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* loss_out) {
+  if (!M || !bt) return fail(HIFT_EINVAL, "null argument");
+  if (M->k == 0) return fail(HIFT_ESTATE, "no schedule set");
+  if (gid < 0 || gid >= M->k) return fail(HIFT_EINVAL, "group %d outside [0,%d)", gid, M->k);
+  if (bt->batch < 1 || bt->seq < 1 || bt->batch > M->max_batch || bt->seq > M->max_seq_len)
+    return fail(HIFT_EINVAL, "batch %d x seq %d outside the maxima %d x %d", bt->batch, bt->seq, M->max_batch,
+                M->max_seq_len);
+  if (!bt->tokens || !bt->labels) return fail(HIFT_EINVAL, "tokens or labels null");
+  int ulo, uhi;
+  int64_t plo, cnt;
+  group_range(M, gid, &ulo, &uhi, &plo, &cnt);
+  const bool moving = M->on_host && M->n_state > 0;
+  HIP_TRY(hipEventRecord(M->ev_t0, M->cs));
+
+  // ---- state movement, queued ahead of the compute (Algorithm 1 step i, issued early) ----
+  int s = 0;
+  if (moving) {
+    if (M->slot_group[M->cur_slot] == gid) s = M->cur_slot;
+    else if (M->slot_group[M->cur_slot ^ 1] == gid) s = M->cur_slot ^ 1;
+    else {
+      s = M->cur_slot;
+      ST_TRY(fetch_state(M, gid, s));
+    }
+    // a slot reused without a new fetch may still be draining to the host from its last update
+    if (M->d2h_pending[s]) HIP_TRY(hipStreamWaitEvent(M->cs, M->ev_d2h[s], 0));
+    M->cur_slot = s;
+    // prefetch the state of the group the schedule visits next into the other slot; the
+    // write-back that last used that slot is ordered before it inside fetch_state
+    const int next = M->order[(M->t + 1) % M->k];
+    const bool on_schedule = M->order[M->t % M->k] == gid;
+    if (on_schedule && next != gid && M->slot_group[s ^ 1] != next) ST_TRY(fetch_state(M, next, s ^ 1));
+  }
+
+  ST_TRY(forward(M, bt));
+  ST_TRY(backward(M, bt, ulo, uhi, plo));
+
+  // ---- optimizer on the group (its update number drives AdamW's bias correction) ----
+  HIP_TRY(hipEventRecord(M->ev_w0, M->cs));
+  if (moving) HIP_TRY(hipStreamWaitEvent(M->cs, M->ev_h2d[s], 0));
+  HIP_TRY(hipEventRecord(M->ev_w1, M->cs));
+  M->group_steps[gid] += 1;
+  const int64_t tg = M->group_steps[gid];
+  OptArgs oa{M->opt.kind, M->opt.lr, M->opt.beta1, M->opt.beta2, M->opt.eps, M->opt.weight_decay, M->opt.momentum};
+  float *s1b = nullptr, *s2b = nullptr;
+  int64_t sbase = plo;  // state index = parameter offset - sbase
+  if (M->n_state > 0) {
+    if (moving) {
+      s1b = M->slot[s];
+      s2b = M->slot[s] + M->grad_cap;
+    } else {
+      s1b = M->state_full;
+      s2b = M->state_full + M->lay.n_params;
+      sbase = 0;
+    }
+  }
+  {
+    double bytes_per = M->n_state == 2 ? 28.0 : (M->n_state == 1 ? 20.0 : 12.0);
+    if (M->dt == DT_BF16) bytes_per += 2.0;
+    Scope sc(M, CAT_OPT, bytes_per * cnt);
+    for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
+      const Tensor& t = M->lay.t[i];
+      void* cc = M->dt == DT_BF16 ? (unsigned char*)M->wc + t.off * 2 : nullptr;
+      K_TRY(optimizer_update(oa, t.count(), t.kind == HIFT_KIND_MATRIX, tg, M->master + t.off,
+                             M->grad + (t.off - plo), s1b ? s1b + (t.off - sbase) : nullptr,
+                             (s2b && M->n_state == 2) ? s2b + (t.off - sbase) : nullptr, cc, M->cs));
+    }
+  }
+  HIP_TRY(hipEventRecord(M->ev_t1, M->cs));
+  M->timed = true;
+
+  // ---- state back to the host (Algorithm 1 step k) ----
+  if (moving) {
+    HIP_TRY(hipEventRecord(M->ev_opt[s], M->cs));
+    HIP_TRY(hipStreamWaitEvent(M->ds, M->ev_opt[s], 0));
+    for (int j = 0; j < M->n_state; ++j) {
+      HIP_TRY(hipMemcpyAsync(M->host_state + (size_t)j * M->lay.n_params + plo, M->slot[s] + (size_t)j * M->grad_cap,
+                             (size_t)cnt * 4, hipMemcpyDeviceToHost, M->ds));
+      M->d2h_bytes += (uint64_t)cnt * 4;
+    }
+    HIP_TRY(hipEventRecord(M->ev_d2h[s], M->ds));
+    M->d2h_pending[s] = true;
+    M->cur_slot = s ^ 1;
+  }
+  M->t += 1;
+  if (loss_out) {
+    HIP_TRY(hipMemcpyAsync(loss_out, M->loss_dev, 4, hipMemcpyDeviceToHost, M->cs));
+    HIP_TRY(hipStreamSynchronize(M->cs));
+  }
+  return HIFT_OK;
+}
+
+hift_status hift_read_params(hift_model* M, int32_t ulo, int32_t uhi, int32_t which, float* dst, size_t dst_count) {
+  if (!M || !dst) return fail(HIFT_EINVAL, "null argument");
+  int64_t off, cnt;
+  ST_TRY(unit_span(M, ulo, uhi, &off, &cnt));
+  if ((int64_t)dst_count != cnt) return fail(HIFT_EINVAL, "buffer holds %zu floats, units hold %lld", dst_count, (long long)cnt);
+  if (which != 0 && which != 1) return fail(HIFT_EINVAL, "which must be 0 or 1");
+  ST_TRY(sync_all(M));
+  if (which == 0 || M->dt == DT_F32) {
+    HIP_TRY(hipMemcpy(dst, M->master + off, (size_t)cnt * 4, hipMemcpyDeviceToHost));
+  } else {
+    std::vector<uint16_t> tmp((size_t)cnt);
+    HIP_TRY(hipMemcpy(tmp.data(), (unsigned char*)M->wc + off * 2, (size_t)cnt * 2, hipMemcpyDeviceToHost));
+    for (int64_t i = 0; i < cnt; ++i) {
+      const uint32_t u = (uint32_t)tmp[i] << 16;
+      memcpy(dst + i, &u, 4);
+    }
+  }
+  return HIFT_OK;
+}
+
+hift_status hift_write_params(hift_model* M, int32_t ulo, int32_t uhi, const float* src, size_t src_count) {
+  if (!M || !src) return fail(HIFT_EINVAL, "null argument");
+  int64_t off, cnt;
+  ST_TRY(unit_span(M, ulo, uhi, &off, &cnt));
+  if ((int64_t)src_count != cnt) return fail(HIFT_EINVAL, "buffer holds %zu floats, units hold %lld", src_count, (long long)cnt);
+  ST_TRY(sync_all(M));
+  HIP_TRY(hipMemcpy(M->master + off, src, (size_t)cnt * 4, hipMemcpyHostToDevice));
+  if (M->dt == DT_BF16) {
+    HIP_TRY(cast_f32_to(DT_BF16, cnt, M->master + off, (unsigned char*)M->wc + off * 2, M->cs));
+    HIP_TRY(hipStreamSynchronize(M->cs));
+  }
+  return HIFT_OK;
+}
+
+hift_status hift_read_state(hift_model* M, int32_t ulo, int32_t uhi, int32_t slot, float* dst, size_t dst_count) {
+  if (!M || !dst) return fail(HIFT_EINVAL, "null argument");
+  int64_t off, cnt;
+  ST_TRY(unit_span(M, ulo, uhi, &off, &cnt));
+  if ((int64_t)dst_count != cnt) return fail(HIFT_EINVAL, "buffer holds %zu floats, units hold %lld", dst_count, (long long)cnt);
+  if (slot < 0 || slot >= M->n_state) return fail(HIFT_EINVAL, "state slot %d outside [0,%d)", slot, M->n_state);
+  ST_TRY(sync_all(M));
+  if (M->on_host) {
+    memcpy(dst, M->host_state + (size_t)slot * M->lay.n_params + off, (size_t)cnt * 4);  // write-back has landed
+  } else {
+    HIP_TRY(hipMemcpy(dst, M->state_full + (size_t)slot * M->lay.n_params + off, (size_t)cnt * 4, hipMemcpyDeviceToHost));
+  }
+  return HIFT_OK;
+}
+
+hift_status hift_transfer_stats(hift_model* M, uint64_t* h2d, uint64_t* d2h) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  if (h2d) *h2d = M->h2d_bytes;
+  if (d2h) *d2h = M->d2h_bytes;
+  return HIFT_OK;
+}
+
+hift_status hift_last_step_ms(hift_model* M, float* step_ms, float* exposed_copy_ms) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  if (!M->timed) return fail(HIFT_ESTATE, "no step taken yet");
+  ST_TRY(sync_all(M));
+  if (step_ms) HIP_TRY(hipEventElapsedTime(step_ms, M->ev_t0, M->ev_t1));
+  if (exposed_copy_ms) HIP_TRY(hipEventElapsedTime(exposed_copy_ms, M->ev_w0, M->ev_w1));
+  return HIFT_OK;
+}
+
+hift_status hift_profile_enable(hift_model* M, int32_t on) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  ST_TRY(sync_all(M));
+  M->prof.on = on != 0;
+  M->prof.used = 0;
+  return HIFT_OK;
+}
+
+hift_status hift_profile_read(hift_model* M, int32_t category, int64_t* launches, double* total_ms, double* work) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  if (category < 0 || category >= CAT_N) return fail(HIFT_EINVAL, "category outside [0,%d)", CAT_N);
+  ST_TRY(sync_all(M));
+  int64_t n = 0;
+  double ms = 0, w = 0;
+  for (size_t i = 0; i < M->prof.used; ++i) {
+    const Prof::Rec& r = M->prof.pool[i];
+    if (r.cat != category) continue;
+    float e = 0.f;
+    HIP_TRY(hipEventElapsedTime(&e, r.a, r.b));
+    ms += e;
+    w += r.work;
+    ++n;
+  }
+  if (launches) *launches = n;
+  if (total_ms) *total_ms = ms;
+  if (work) *work = w;
+  return HIFT_OK;
+}
+
+// ---- single kernels ------------------------------------------------------------------------
+hift_status hift_kernel_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t out_f32, int64_t Mm,
+                             int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
+                             int64_t ldc, const void* bias, const void* R, int32_t batch, int64_t sa, int64_t sb,
+                             int64_t sc, void* stream) {
+  if (dtype != HIFT_F32 && dtype != HIFT_BF16) return fail(HIFT_EINVAL, "dtype unknown");
+  if (Mm < 0 || N < 0 || K < 0 || batch < 0) return fail(HIFT_EINVAL, "negative size");
+  if ((Mm > 0 && N > 0) && (!A || !B || !C) && K > 0) return fail(HIFT_EINVAL, "null operand");
+  Gemm g;
+  g.dtype = dtype == HIFT_BF16 ? DT_BF16 : DT_F32;
+  g.a_kmajor = a_kmajor != 0; g.b_kmajor = b_kmajor != 0; g.out_f32 = out_f32 != 0 || dtype == HIFT_F32;
+  g.M = Mm; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
+  g.bias = bias; g.R = R; g.ldr = ldc;
+  g.nb = batch; g.nh = 1; g.sa1 = sa; g.sb1 = sb; g.sc1 = sc;
+  HIP_TRY(gemm(g, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_optimizer(const hift_opt* opt, int64_t count, int32_t decay, int64_t t, float* master,
+                                  const float* grad, float* state1, float* state2, void* compute_copy, void* stream) {
+  hift_status s = check_opt(opt);
+  if (s != HIFT_OK) return s;
+  if (count < 0 || t < 1) return fail(HIFT_EINVAL, "count must be >= 0 and t >= 1");
+  OptArgs oa{opt->kind, opt->lr, opt->beta1, opt->beta2, opt->eps, opt->weight_decay, opt->momentum};
+  HIP_TRY(optimizer_update(oa, count, decay != 0, t, master, grad, state1, state2, compute_copy, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_norm_fwd(int32_t dtype, int32_t rms, int64_t rows, int32_t d, float eps, const void* x,
+                                 const void* g, const void* b, void* y, float* stats, void* stream) {
+  if (dtype != HIFT_F32 && dtype != HIFT_BF16) return fail(HIFT_EINVAL, "dtype unknown");
+  if (rows < 0 || d < 1) return fail(HIFT_EINVAL, "bad shape");
+  HIP_TRY(norm_fwd(dtype == HIFT_BF16 ? DT_BF16 : DT_F32, rms != 0, rows, d, eps, x, g, b, y, stats, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_cross_entropy(int32_t dtype, int64_t rows, int32_t V, void* logits, const int32_t* labels,
+                                      float* row_loss_scratch, float* loss_out, void* stream) {
+  if (dtype != HIFT_F32 && dtype != HIFT_BF16) return fail(HIFT_EINVAL, "dtype unknown");
+  if (rows < 0 || V < 1) return fail(HIFT_EINVAL, "bad shape");
+  HIP_TRY(cross_entropy(dtype == HIFT_BF16 ? DT_BF16 : DT_F32, rows, V, logits, labels, row_loss_scratch, loss_out,
+                        (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+}  // extern "C"

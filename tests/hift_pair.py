@@ -1,0 +1,102 @@
+"""Helpers of the GPU parity tests: build the oracle and the GPU model from the same seeded
+inputs and run both over the same batches."""
+import numpy as np
+
+from hift_inputs import init_params, make_batch, model_config
+from oracle import hift_oracle as O
+
+
+def spec_of(cfg):
+    return [(n, s, k) for n, s, k, _u in O.param_tensors(cfg)]
+
+
+def make_pair(wl, seed=0, m=None, strategy=None, opt=None, state_on_host=0, batch=None, seq=None,
+              jitter=0.0, sched_seed=17, **cfg_over):
+    """Returns (oracle, gpu_model, theta0).  Weights are bf16-exact when the GPU model is bf16."""
+    import paper_2401_15207_amd as H
+    cfg = model_config(wl, **cfg_over)
+    opt = dict(opt or wl["opt"])
+    m = m or wl["m"]
+    strategy = strategy or wl["strategy"]
+    b, s = batch or wl["batch"], seq or wl["seq"]
+    theta0 = init_params(seed, spec_of(cfg), bf16_exact=(cfg["dtype"] == 1), jitter=jitter)
+    orc = O.HiftOracle(cfg, opt, theta0.astype(np.float64))
+    gpu = H.HiftModel(cfg, opt, m, b, s, init_params=theta0, state_on_host=state_on_host)
+    ko = orc.set_group_schedule(strategy, m, sched_seed)
+    kg = gpu.set_group_schedule(strategy, m, sched_seed)
+    assert ko == kg
+    return orc, gpu, theta0
+
+
+def to_dev(tok, lab):
+    import torch
+    return (torch.from_numpy(np.ascontiguousarray(tok)).cuda(), torch.from_numpy(np.ascontiguousarray(lab)).cuda())
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    den = np.linalg.norm(b)
+    return np.linalg.norm(a - b) / den if den > 0 else np.linalg.norm(a)
+
+
+def run_steps(orc, gpu, wl, seed, steps, batch=None, seq=None):
+    """Runs `steps` scheduled steps on both sides; yields per step
+    (t, gid, loss_oracle, loss_gpu, UpdateCheck, theta_before_gpu)."""
+    for t in range(1, steps + 1):
+        gid = orc.schedule_group_at(t)
+        assert gid == gpu.schedule_group_at(t)
+        tok, lab = make_batch(wl, seed, t, batch, seq)
+        dtok, dlab = to_dev(tok, lab)
+        tb_g = gpu.read_params()
+        chk = UpdateCheck(orc, gid)
+        lo = orc.step(tok, lab, gid)
+        lg = gpu.step(dtok, dlab, gid)
+        yield t, gid, lo, lg, chk, tb_g
+
+
+def oracle_update(opt, theta, g, s1, s2, tg, dm):
+    """New parameters of a slice under the oracle's optimizer formulas; inputs are not modified."""
+    th, a, b = theta.copy(), s1.copy(), s2.copy()
+    if opt["kind"] == "adamw":
+        O.adamw_update(th, g, a, b, tg, opt["lr"], opt["beta1"], opt["beta2"], opt["eps"], opt["weight_decay"], dm)
+    elif opt["kind"] == "adagrad":
+        O.adagrad_update(th, g, a, opt["lr"], opt["eps"], opt["weight_decay"], dm)
+    else:
+        O.sgd_update(th, g, a, tg, opt["lr"], opt["momentum"], opt["weight_decay"], dm)
+    return th
+
+
+class UpdateCheck:
+    """Tolerance of an optimizer update that follows from a tolerance on the gradient.
+
+    The gradient of the GPU path may differ from the oracle's by tol * (|g_i| + rms(g)) per
+    element.  An adaptive optimizer divides by a function of g, so the same relative tolerance
+    does not carry over to the update where |g_i| is tiny (AdamW's first step is
+    lr * g / (|g| + eps)).  The allowed error of element i is therefore the change of the
+    oracle's own update when g_i moves by that amount, plus tol * |update_i|, plus the
+    resolution of fp32 storage of theta."""
+
+    def __init__(self, orc, gid):
+        self.orc, self.gid = orc, gid
+        self.lo, self.hi = orc.group_range(gid)
+        sl = slice(self.lo, self.hi)
+        self.th0 = orc.theta[sl].copy()
+        self.s1, self.s2 = orc.state1[sl].copy(), orc.state2[sl].copy()
+        self.tg = orc.group_steps[gid] + 1
+
+    def check(self, theta_gpu_before, theta_gpu_after, tol, store_eps=1.2e-7):
+        orc = self.orc
+        sl = slice(self.lo, self.hi)
+        g = orc.last_grad[sl]
+        dm = orc.decay_mask[sl]
+        delta = tol * (np.abs(g) + np.sqrt(np.mean(g * g)))
+        up0 = orc.theta[sl] - self.th0
+        upp = oracle_update(orc.opt, self.th0, g + delta, self.s1, self.s2, self.tg, dm) - self.th0
+        upm = oracle_update(orc.opt, self.th0, g - delta, self.s1, self.s2, self.tg, dm) - self.th0
+        slack = 1.5 * np.maximum(np.abs(upp - up0), np.abs(upm - up0))
+        bound = slack + tol * np.abs(up0) + store_eps * np.abs(self.th0)
+        upg = theta_gpu_after[sl].astype(np.float64) - theta_gpu_before[sl].astype(np.float64)
+        err = np.abs(upg - up0)
+        worst = int(np.argmax(err - bound))
+        return bool(np.all(err <= bound)), (worst, float(err[worst]), float(bound[worst]), float(g[worst]))

@@ -1,0 +1,182 @@
+"""GPU parity of single kernels through the C ABI: the contraction in every operand layout
+(bf16 MFMA path and fp32 path), the optimizer update, normalisation and cross-entropy.
+Expected values: the plain definitions in float64 (numpy matmul; the oracle's own functions)."""
+import numpy as np
+import pytest
+
+from oracle import hift_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+F32, BF16 = 0, 1
+
+
+def _bf16_round(x):
+    from hift_inputs import round_to_bf16
+    return round_to_bf16(x.astype(np.float32))
+
+
+def _dev(x, bf16):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if bf16 else t
+
+
+CASES = [  # M, N, K  (several tiles + ragged tails; K not a multiple of 64; tiny)
+    (256, 256, 64), (512, 768, 256), (384, 640, 192), (136, 72, 40), (1000, 264, 520), (8, 3, 64), (64, 64, 8),
+    (2048, 512, 128), (300, 200, 100),
+]
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("ak,bk", [(1, 1), (1, 0), (0, 1), (0, 0)])
+@pytest.mark.parametrize("M,N,K", CASES)
+def test_gemm_layouts(dtype, ak, bk, M, N, K):
+    import torch
+    import paper_2401_15207_amd as H
+    rng = np.random.default_rng(M * 7 + N * 3 + K + ak * 2 + bk)
+    bf = dtype == BF16
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = rng.standard_normal((N, K)).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    R = rng.standard_normal((M, N)).astype(np.float32)
+    if bf:
+        A, B, bias, R = map(_bf16_round, (A, B, bias, R))
+    ref = A.astype(np.float64) @ B.astype(np.float64).T + bias + R
+    dA = _dev(A if ak else A.T, bf)
+    dB = _dev(B if bk else B.T, bf)
+    lda = K if ak else M
+    ldb = K if bk else N
+    for out_f32 in ([1] if not bf else [0, 1]):
+        dC = torch.zeros((M, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device="cuda")
+        dR = _dev(R, bf and not out_f32)
+        H.kernel_gemm(dtype, ak, bk, out_f32, M, N, K, dA, lda, dB, ldb, dC, N, _dev(bias, bf), dR)
+        torch.cuda.synchronize()
+        got = dC.float().cpu().numpy().astype(np.float64)
+        scale = np.sqrt(K) + 1.0
+        if bf and not out_f32:
+            tol = 2 ** -8 * (np.abs(ref) + 0.02 * scale)    # one bf16 rounding of the result
+        elif bf:
+            tol = 1e-5 * (np.abs(ref) + scale)               # exact products, fp32 accumulation
+        else:
+            tol = 2e-6 * (np.abs(ref) + scale)
+        bad = np.abs(got - ref) > tol
+        assert not bad.any(), (out_f32, int(bad.sum()), float(np.max(np.abs(got - ref))))
+
+
+def test_gemm_batched_strided_bf16():
+    import torch
+    import paper_2401_15207_amd as H
+    rng = np.random.default_rng(0)
+    nb, M, N, K = 6, 128, 192, 64
+    A = _bf16_round(rng.standard_normal((nb, M, K)))
+    B = _bf16_round(rng.standard_normal((nb, N, K)))
+    dA, dB = _dev(A, True), _dev(B, True)
+    dC = torch.zeros((nb, M, N), dtype=torch.bfloat16, device="cuda")
+    H.kernel_gemm(BF16, 1, 1, 0, M, N, K, dA, K, dB, K, dC, N, None, None, batch=nb, sa=M * K, sb=N * K, sc=M * N)
+    torch.cuda.synchronize()
+    ref = np.einsum("bmk,bnk->bmn", A.astype(np.float64), B.astype(np.float64))
+    got = dC.float().cpu().numpy()
+    assert np.all(np.abs(got - ref) <= 2 ** -8 * (np.abs(ref) + 0.2))
+
+
+def test_gemm_empty():
+    import torch
+    import paper_2401_15207_amd as H
+    z = torch.zeros(8, device="cuda")
+    H.kernel_gemm(F32, 1, 1, 1, 0, 4, 4, z, 4, z, 4, z, 4)
+    H.kernel_gemm(F32, 1, 1, 1, 2, 2, 0, z, 0, z, 0, z, 2)   # K = 0: result is zero (+0)
+    torch.cuda.synchronize()
+    assert float(z[:4].abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("kind", ["adamw", "adagrad", "sgdm", "sgd"])
+@pytest.mark.parametrize("n", [1, 7, 4096, 100003])
+def test_optimizer_kernel_against_oracle_formulas(kind, n):
+    import torch
+    import paper_2401_15207_amd as H
+    rng = np.random.default_rng(n)
+    opt = {"adamw": dict(kind="adamw", lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, momentum=0.0),
+           "adagrad": dict(kind="adagrad", lr=1e-2, beta1=0, beta2=0, eps=1e-10, weight_decay=0.0, momentum=0.0),
+           "sgdm": dict(kind="sgd", lr=1e-2, beta1=0, beta2=0, eps=0, weight_decay=0.0, momentum=0.9),
+           "sgd": dict(kind="sgd", lr=1e-2, beta1=0, beta2=0, eps=0, weight_decay=0.001, momentum=0.0)}[kind]
+    th = rng.standard_normal(n).astype(np.float32)
+    s1, s2 = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    d_th, d_s1, d_s2 = (torch.from_numpy(x.copy()).cuda() for x in (th, s1, s2))
+    d_cc = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    o_th, o_s1, o_s2 = th.astype(np.float64), s1.astype(np.float64), s2.astype(np.float64)
+    dm = np.ones(n)
+    for t in (1, 2, 3):
+        g = (rng.standard_normal(n) * 0.1).astype(np.float32)
+        H.kernel_optimizer(opt, n, 1, t, d_th, torch.from_numpy(g).cuda(), d_s1, d_s2, d_cc)
+        torch.cuda.synchronize()
+        if opt["kind"] == "adamw":
+            O.adamw_update(o_th, g.astype(np.float64), o_s1, o_s2, t, opt["lr"], opt["beta1"], opt["beta2"], opt["eps"], opt["weight_decay"], dm)
+        elif opt["kind"] == "adagrad":
+            O.adagrad_update(o_th, g.astype(np.float64), o_s1, opt["lr"], opt["eps"], opt["weight_decay"], dm)
+        else:
+            O.sgd_update(o_th, g.astype(np.float64), o_s1, t, opt["lr"], opt["momentum"], opt["weight_decay"], dm)
+        got = d_th.cpu().numpy()
+        assert np.all(np.abs(got - o_th) <= 2e-7 * np.abs(o_th) + 1e-5 * opt["lr"]), t
+        cc = d_cc.float().cpu().numpy()
+        assert np.array_equal(cc, _bf16_round(got))          # bf16 copy = round-to-nearest-even of the master
+    if kind in ("adamw", "adagrad", "sgdm"):
+        assert np.allclose(d_s1.cpu().numpy(), o_s1, rtol=1e-5, atol=1e-9)
+    if kind == "adamw":
+        assert np.allclose(d_s2.cpu().numpy(), o_s2, rtol=1e-5, atol=1e-12)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("rows,d", [(5, 64), (1, 8), (130, 4096), (3, 100), (0, 64)])
+@pytest.mark.parametrize("rms", [0, 1])
+def test_norm_forward(dtype, rows, d, rms):
+    import torch
+    import paper_2401_15207_amd as H
+    rng = np.random.default_rng(rows + d)
+    bf = dtype == BF16
+    x = (rng.standard_normal((rows, d)) * 2 + 0.5).astype(np.float32)
+    g = (1 + 0.1 * rng.standard_normal(d)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(d)).astype(np.float32)
+    if bf:
+        x, g, b = map(_bf16_round, (x, g, b))
+    dy = torch.zeros((rows, d), dtype=torch.bfloat16 if bf else torch.float32, device="cuda")
+    st = torch.zeros((max(rows, 1), 2), device="cuda")
+    H.kernel_norm_fwd(dtype, rms, rows, d, 1e-5, _dev(x, bf), _dev(g, bf), _dev(b, bf), dy, st)
+    torch.cuda.synchronize()
+    if rows == 0:
+        return
+    X = x.astype(np.float64)
+    ref, (_xh, rstd) = (O.rmsnorm_fwd(X, g.astype(np.float64), 1e-5) if rms
+                        else O.layernorm_fwd(X, g.astype(np.float64), b.astype(np.float64), 1e-5))
+    got = dy.float().cpu().numpy()
+    tol = (2 ** -8 if bf else 3e-6) * (np.abs(ref) + 1e-2)
+    assert np.all(np.abs(got - ref) <= tol)
+    assert np.allclose(st[:rows, 1].cpu().numpy(), rstd[:, 0], rtol=2e-6)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("rows,V", [(7, 256), (64, 32000), (5, 3), (1, 2), (0, 16)])
+def test_cross_entropy(dtype, rows, V):
+    import torch
+    import paper_2401_15207_amd as H
+    rng = np.random.default_rng(rows * 31 + V)
+    bf = dtype == BF16
+    z = (rng.standard_normal((rows, V)) * 3).astype(np.float32)
+    if bf:
+        z = _bf16_round(z)
+    lab = rng.integers(0, V, size=rows).astype(np.int32)
+    if rows > 2:
+        lab[1] = -1
+    dz = _dev(z, bf)
+    scratch = torch.zeros(rows + 1, device="cuda")
+    loss = torch.full((1,), -7.0, device="cuda")
+    H.kernel_cross_entropy(dtype, rows, V, dz, torch.from_numpy(lab).cuda(), scratch, loss)
+    torch.cuda.synchronize()
+    if rows == 0:
+        assert float(loss) == 0.0
+        return
+    ref_loss, ref_d = O.cross_entropy_fwd(z.astype(np.float64), lab.astype(np.int64))
+    assert abs(float(loss) - ref_loss) <= 2e-6 * abs(ref_loss) + 1e-6
+    got = dz.float().cpu().numpy()
+    tol = (2 ** -8 if bf else 1e-5) * np.abs(ref_d) + 1e-8
+    assert np.all(np.abs(got - ref_d) <= tol)
