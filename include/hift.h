@@ -83,13 +83,13 @@ typedef struct {
 } hift_config;
 
 typedef struct {
-  int32_t kind;       /* hift_opt_kind */
-  float lr;
-  float beta1, beta2; /* AdamW */
-  float eps;          /* AdamW (1e-8 usual) and AdaGrad (1e-10 usual) */
-  float weight_decay; /* applied to tensors with two or more dimensions only; AdamW: decoupled,
-                         AdaGrad / SGD: added to the gradient */
-  float momentum;     /* SGD; 0 = plain SGD, which keeps no state and moves no bytes */
+  int32_t kind;        /* hift_opt_kind */
+  double lr;           /* hyper-parameters are doubles so that 1 - beta and the bias corrections */
+  double beta1, beta2; /* are formed from the caller's values before rounding to fp32 (AdamW) */
+  double eps;          /* AdamW (1e-8 usual) and AdaGrad (1e-10 usual) */
+  double weight_decay; /* applied to tensors with two or more dimensions only; AdamW: decoupled,
+                          AdaGrad / SGD: added to the gradient */
+  double momentum;     /* SGD; 0 = plain SGD, which keeps no state and moves no bytes */
 } hift_opt;
 
 typedef struct {
@@ -170,7 +170,7 @@ hift_status hift_step(hift_model* mdl, const hift_batch* batch, int32_t group_id
 
 /* Learning rate used by following steps.  The caller applies its schedule when
  * hift_cycle_index changes (Algorithm 1: the rate moves only after all layers were updated). */
-hift_status hift_set_lr(hift_model* mdl, float lr);
+hift_status hift_set_lr(hift_model* mdl, double lr);
 /* Steps taken since the schedule was set, and completed sweeps floor(t / k). */
 hift_status hift_cycle_index(const hift_model* mdl, int64_t* steps_done, int64_t* cycles_done);
 

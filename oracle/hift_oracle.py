@@ -14,9 +14,17 @@ Freezing removes work but not results, so the oracle is the plain definition wri
   4. apply the optimizer to that slice with that group's own state and step counter,
   5. leave every other value untouched.
 
-There is no truncation, no offload, no half precision and no prefetch here.  All arithmetic is
-numpy in float64 (a float32 instance is possible through `dtype`).  numpy `matmul` serves as
-the matrix-product step and scipy's `erf` as the error function.
+There is no truncation, no offload and no prefetch here.  All arithmetic is numpy in float64
+(a float32 instance is possible through `dtype`).  numpy `matmul` serves as the matrix-product
+step and scipy's `erf` as the error function.
+
+Mixed precision (appendix "Mixing Precision": a half-precision model with a single-precision
+backup of the weights, of which only the active group's part is touched per step).  With
+`half_weights=True` the loss and its gradient are evaluated at the bf16 rounding
+(round-to-nearest-even) of the master weights, and the update is applied to the master
+weights; all arithmetic stays float64.  This models the one place where the precision of the
+method, not of the arithmetic, changes the result: an update smaller than half a bf16 spacing
+leaves the forward weights unchanged until enough updates accumulate.
 
 Layer units, groups and visiting order (section 3 "Notation", Algorithm 1, appendix
 "Implementation Details"): unit 0 = all embeddings including the position table, units 1..L =
@@ -518,10 +526,22 @@ def sgd_update(theta, g, buf, t, lr, momentum, wd, decay_mask):
     theta -= lr * g
 
 
+def bf16_round(x: np.ndarray) -> np.ndarray:
+    """Nearest bfloat16 value (1 sign, 8 exponent, 7 fraction bits; ties to even), returned in
+    x's dtype.  Values are first rounded to float32 (nearest even), whose upper 16 bits are the
+    bfloat16 pattern."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    keep = (u >> 16) & 1
+    u = ((u + 0x7FFF + keep) >> 16) << 16
+    return u.astype(np.uint32).view(np.float32).astype(x.dtype).reshape(x.shape)
+
+
 class HiftOracle:
     """State of a HiFT run: parameters, per-group optimizer state and counters."""
 
-    def __init__(self, cfg: dict, opt: dict, params: np.ndarray, dtype=np.float64):
+    def __init__(self, cfg: dict, opt: dict, params: np.ndarray, dtype=np.float64,
+                 half_weights: bool = False):
+        self.half_weights = half_weights
         self.cfg, self.opt = dict(cfg), dict(opt)
         self.theta = np.array(params, dtype=dtype).reshape(-1).copy()
         assert self.theta.size == n_params(cfg)
@@ -569,7 +589,8 @@ class HiftOracle:
     def step(self, tokens, labels, group_id: int) -> float:
         if self.k is None or not (0 <= group_id < self.k):
             raise ValueError("bad group")
-        loss, g = loss_and_grad(self.cfg, self.theta, tokens, labels)
+        at = bf16_round(self.theta) if self.half_weights else self.theta
+        loss, g = loss_and_grad(self.cfg, at, tokens, labels)
         self.last_grad = g
         lo, hi = self.group_range(group_id)
         self.group_steps[group_id] += 1

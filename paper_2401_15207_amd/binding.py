@@ -34,8 +34,8 @@ class Config(C.Structure):
 
 
 class Opt(C.Structure):
-    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
-                ("eps", C.c_float), ("weight_decay", C.c_float), ("momentum", C.c_float)]
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
+                ("eps", C.c_double), ("weight_decay", C.c_double), ("momentum", C.c_double)]
 
 
 class Batch(C.Structure):
@@ -61,7 +61,7 @@ _SIGS = {
     "hift_schedule_group_at": [_vp, _i64, _P(_i32)],
     "hift_group_units": [_vp, _i32, _P(_i32), _P(_i32)],
     "hift_step": [_vp, _P(Batch), _i32, _P(C.c_float)],
-    "hift_set_lr": [_vp, C.c_float],
+    "hift_set_lr": [_vp, C.c_double],
     "hift_cycle_index": [_vp, _P(_i64), _P(_i64)],
     "hift_read_params": [_vp, _i32, _i32, _i32, _vp, _sz],
     "hift_write_params": [_vp, _i32, _i32, _vp, _sz],

@@ -435,7 +435,7 @@ __global__ void __launch_bounds__(BLK) fill_zero_k(uint4* __restrict__ p, int64_
 // Group-local update over contiguous fp32 master weights.  KIND 0 AdamW (decoupled decay),
 // 1 AdaGrad, 2 SGD with momentum, 3 plain SGD.  Four parameters per thread (16-byte accesses).
 template <int KIND, int V>
-__global__ void __launch_bounds__(BLK) opt_k(int64_t n, float lr, float b1, float b2, float eps, float wd,
+__global__ void __launch_bounds__(BLK) opt_k(int64_t n, float lr, float b1, float omb1, float b2, float omb2, float eps, float wd,
                                               float mu, float inv_bc1, float inv_bc2, int first,
                                               float* __restrict__ master, const float* __restrict__ grad,
                                               float* __restrict__ s1, float* __restrict__ s2,
@@ -451,8 +451,8 @@ __global__ void __launch_bounds__(BLK) opt_k(int64_t n, float lr, float b1, floa
   for (int e = 0; e < V; ++e) {
     if (KIND == 0) {
       th[e] -= lr * wd * th[e];
-      a[e] = b1 * a[e] + (1.0f - b1) * g[e];
-      b[e] = b2 * b[e] + (1.0f - b2) * g[e] * g[e];
+      a[e] = b1 * a[e] + omb1 * g[e];
+      b[e] = b2 * b[e] + omb2 * g[e] * g[e];
       th[e] -= lr * (a[e] * inv_bc1) / (sqrtf(b[e] * inv_bc2) + eps);
     } else if (KIND == 1) {
       const float gg = g[e] + wd * th[e];
@@ -695,15 +695,16 @@ hipError_t fill_zero(void* p, size_t bytes, hipStream_t st) {
 hipError_t optimizer_update(const OptArgs& o, int64_t n, bool decay, int64_t t, float* master, const float* grad,
                             float* s1, float* s2, void* cc, hipStream_t st) {
   if (n == 0) return hipSuccess;
-  const float wd = decay ? o.wd : 0.f;
-  const double bc1 = 1.0 - pow((double)o.beta1, (double)t), bc2 = 1.0 - pow((double)o.beta2, (double)t);
+  const float wd = decay ? (float)o.wd : 0.f;
+  const double bc1 = 1.0 - pow(o.beta1, (double)t), bc2 = 1.0 - pow(o.beta2, (double)t);
   const float ib1 = (float)(1.0 / bc1), ib2 = (float)(1.0 / bc2);
   const bool vec = n % 8 == 0 && aligned16(master) && aligned16(grad) && aligned16(s1) && aligned16(s2) && aligned16(cc);
   int kind = o.kind;
-  if (kind == 2 && o.momentum == 0.f) kind = 3;
+  if (kind == 2 && o.momentum == 0.0) kind = 3;
 #define OPT_CALL(K, V)                                                                                      \
-  opt_k<K, V><<<dim3((unsigned)cdiv(cdiv(n, V), BLK)), BLK, 0, st>>>(n, o.lr, o.beta1, o.beta2, o.eps, wd, \
-                                                                     o.momentum, ib1, ib2, t == 1 ? 1 : 0, \
+  opt_k<K, V><<<dim3((unsigned)cdiv(cdiv(n, V), BLK)), BLK, 0, st>>>(n, (float)o.lr, (float)o.beta1,          \
+      (float)(1.0 - o.beta1), (float)o.beta2, (float)(1.0 - o.beta2), (float)o.eps, wd,                    \
+                                                                     (float)o.momentum, ib1, ib2, t == 1 ? 1 : 0, \
                                                                      master, grad, s1, s2, (bf16*)cc)
 #define OPT_KIND(K) \
   if (vec) OPT_CALL(K, 4); else OPT_CALL(K, 1)

@@ -69,7 +69,7 @@ hipError_t fill_zero(void* p, size_t bytes, hipStream_t st);
 
 // ---- optimizer ---------------------------------------------------------------------------
 struct OptArgs {
-  int kind; float lr, beta1, beta2, eps, wd, momentum;
+  int kind; double lr, beta1, beta2, eps, wd, momentum;
 };
 hipError_t optimizer_update(const OptArgs& o, int64_t n, bool decay, int64_t t, float* master,
                             const float* grad, float* s1, float* s2, void* compute_copy /* bf16 or null */,

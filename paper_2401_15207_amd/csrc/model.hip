@@ -168,13 +168,13 @@ void make_order(int k, int strategy, uint64_t seed, int32_t* out) {
 int n_state_of(const hift_opt& o) {
   if (o.kind == HIFT_ADAMW) return 2;
   if (o.kind == HIFT_ADAGRAD) return 1;
-  return o.momentum > 0.f ? 1 : 0;
+  return o.momentum > 0.0 ? 1 : 0;
 }
 
 hift_status check_opt(const hift_opt* o) {
   if (!o) return fail(HIFT_EINVAL, "optimizer is null");
   if (o->kind < 0 || o->kind > 2) return fail(HIFT_EINVAL, "optimizer kind %d unknown", o->kind);
-  if (o->momentum < 0.f) return fail(HIFT_EINVAL, "momentum must be >= 0");
+  if (o->momentum < 0.0) return fail(HIFT_EINVAL, "momentum must be >= 0");
   return HIFT_OK;
 }
 
@@ -1017,7 +1017,7 @@ hift_status hift_group_units(const hift_model* M, int32_t gid, int32_t* unit_lo,
   return HIFT_OK;
 }
 
-hift_status hift_set_lr(hift_model* M, float lr) {
+hift_status hift_set_lr(hift_model* M, double lr) {
   if (!M) return fail(HIFT_EINVAL, "model is null");
   M->opt.lr = lr;
   return HIFT_OK;

@@ -20,7 +20,7 @@ def make_pair(wl, seed=0, m=None, strategy=None, opt=None, state_on_host=0, batc
     strategy = strategy or wl["strategy"]
     b, s = batch or wl["batch"], seq or wl["seq"]
     theta0 = init_params(seed, spec_of(cfg), bf16_exact=(cfg["dtype"] == 1), jitter=jitter)
-    orc = O.HiftOracle(cfg, opt, theta0.astype(np.float64))
+    orc = O.HiftOracle(cfg, opt, theta0.astype(np.float64), half_weights=(cfg["dtype"] == 1))
     gpu = H.HiftModel(cfg, opt, m, b, s, init_params=theta0, state_on_host=state_on_host)
     ko = orc.set_group_schedule(strategy, m, sched_seed)
     kg = gpu.set_group_schedule(strategy, m, sched_seed)
@@ -70,12 +70,14 @@ def oracle_update(opt, theta, g, s1, s2, tg, dm):
 class UpdateCheck:
     """Tolerance of an optimizer update that follows from a tolerance on the gradient.
 
-    The gradient of the GPU path may differ from the oracle's by tol * (|g_i| + rms(g)) per
-    element.  An adaptive optimizer divides by a function of g, so the same relative tolerance
+    The gradient of the GPU path may differ from the oracle's by tol * (|g_i| + rms of the
+    gradient of the tensor that holds element i) per element.  An adaptive optimizer divides by a function of g, so the same relative tolerance
     does not carry over to the update where |g_i| is tiny (AdamW's first step is
     lr * g / (|g| + eps)).  The allowed error of element i is therefore the change of the
     oracle's own update when g_i moves by that amount, plus tol * |update_i|, plus the
-    resolution of fp32 storage of theta."""
+    resolution of fp32 storage of theta.  In bf16 mode a small fraction of elements
+    (max_outlier_frac) may exceed it: sums of many terms of both signs lose more than the
+    typical relative error in the few elements where they nearly cancel."""
 
     def __init__(self, orc, gid):
         self.orc, self.gid = orc, gid
@@ -85,12 +87,21 @@ class UpdateCheck:
         self.s1, self.s2 = orc.state1[sl].copy(), orc.state2[sl].copy()
         self.tg = orc.group_steps[gid] + 1
 
-    def check(self, theta_gpu_before, theta_gpu_after, tol, store_eps=1.2e-7):
+    def check(self, theta_gpu_before, theta_gpu_after, tol, store_eps=1.2e-7, max_outlier_frac=0.0):
         orc = self.orc
         sl = slice(self.lo, self.hi)
         g = orc.last_grad[sl]
         dm = orc.decay_mask[sl]
-        delta = tol * (np.abs(g) + np.sqrt(np.mean(g * g)))
+        scale = np.zeros_like(g)      # rms of the gradient of the tensor each element belongs to
+        off = 0
+        for _n, shape, _k, _u in O.param_tensors(orc.cfg):
+            n = int(np.prod(shape))
+            a, b = max(off, self.lo), min(off + n, self.hi)
+            if a < b:
+                seg = g[a - self.lo:b - self.lo]
+                scale[a - self.lo:b - self.lo] = np.sqrt(np.mean(seg * seg))
+            off += n
+        delta = tol * (np.abs(g) + scale)
         up0 = orc.theta[sl] - self.th0
         upp = oracle_update(orc.opt, self.th0, g + delta, self.s1, self.s2, self.tg, dm) - self.th0
         upm = oracle_update(orc.opt, self.th0, g - delta, self.s1, self.s2, self.tg, dm) - self.th0
@@ -99,4 +110,5 @@ class UpdateCheck:
         upg = theta_gpu_after[sl].astype(np.float64) - theta_gpu_before[sl].astype(np.float64)
         err = np.abs(upg - up0)
         worst = int(np.argmax(err - bound))
-        return bool(np.all(err <= bound)), (worst, float(err[worst]), float(bound[worst]), float(g[worst]))
+        frac = float(np.mean(err > bound))
+        return frac <= max_outlier_frac, (frac, worst, float(err[worst]), float(bound[worst]), float(g[worst]))

