@@ -61,6 +61,7 @@ def oracle_update(opt, theta, g, s1, s2, tg, dm):
     if opt["kind"] == "adamw":
         O.adamw_update(th, g, a, b, tg, opt["lr"], opt["beta1"], opt["beta2"], opt["eps"], opt["weight_decay"], dm)
     elif opt["kind"] == "adagrad":
+        a = np.maximum(a, 0.0)     # a perturbed accumulator stays a sum of squares
         O.adagrad_update(th, g, a, opt["lr"], opt["eps"], opt["weight_decay"], dm)
     else:
         O.sgd_update(th, g, a, tg, opt["lr"], opt["momentum"], opt["weight_decay"], dm)
@@ -92,21 +93,30 @@ class UpdateCheck:
         sl = slice(self.lo, self.hi)
         g = orc.last_grad[sl]
         dm = orc.decay_mask[sl]
-        scale = np.zeros_like(g)      # rms of the gradient of the tensor each element belongs to
-        off = 0
-        for _n, shape, _k, _u in O.param_tensors(orc.cfg):
-            n = int(np.prod(shape))
-            a, b = max(off, self.lo), min(off + n, self.hi)
-            if a < b:
-                seg = g[a - self.lo:b - self.lo]
-                scale[a - self.lo:b - self.lo] = np.sqrt(np.mean(seg * seg))
-            off += n
-        delta = tol * (np.abs(g) + scale)
+        def tensor_rms(v):      # rms of v over the tensor each element belongs to
+            out, off = np.zeros_like(v), 0
+            for _n, shape, _k, _u in O.param_tensors(orc.cfg):
+                n = int(np.prod(shape))
+                a, b = max(off, self.lo), min(off + n, self.hi)
+                if a < b:
+                    seg = v[a - self.lo:b - self.lo]
+                    out[a - self.lo:b - self.lo] = np.sqrt(np.mean(seg * seg))
+                off += n
+            return out
+
+        # the stored first-order state (moment / momentum buffer) carries the same relative
+        # uncertainty as the gradients it was built from
+        delta = tol * (np.abs(g) + tensor_rms(g))
+        delta_s = tol * (np.abs(self.s1) + tensor_rms(self.s1))
         up0 = orc.theta[sl] - self.th0
-        upp = oracle_update(orc.opt, self.th0, g + delta, self.s1, self.s2, self.tg, dm) - self.th0
-        upm = oracle_update(orc.opt, self.th0, g - delta, self.s1, self.s2, self.tg, dm) - self.th0
-        slack = 1.5 * np.maximum(np.abs(upp - up0), np.abs(upm - up0))
-        bound = slack + tol * np.abs(up0) + store_eps * np.abs(self.th0)
+        slack = np.zeros_like(g)
+        for sg in (+1, -1):
+            for ss in ((+1, -1) if self.tg > 1 else (0,)):
+                up = oracle_update(orc.opt, self.th0, g + sg * delta, self.s1 + ss * delta_s, self.s2,
+                                   self.tg, dm) - self.th0
+                slack = np.maximum(slack, np.abs(up - up0))
+        rel = tol if self.tg == 1 else 2 * tol     # later updates also divide by an uncertain second moment
+        bound = 1.5 * slack + rel * np.abs(up0) + store_eps * np.abs(self.th0)
         upg = theta_gpu_after[sl].astype(np.float64) - theta_gpu_before[sl].astype(np.float64)
         err = np.abs(upg - up0)
         worst = int(np.argmax(err - bound))
