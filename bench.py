@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the HiFT step on one MI355X.
+
+A "step" is one pass of the whole hot path (forward over all units, truncated backward, weight
+gradients and optimizer update of the active group, optimizer-state movement) over one batch.
+Workload: the LLaMA-7B-shaped decoder, batch 4 x 512 tokens, m = 1 (34 groups), bottom2up,
+AdamW, optimizer state of inactive groups in pinned host memory.  Tokens are bounded Zipf(1.1),
+weights N(0, 0.02^2): synthetic stand-ins, resident in HBM before the timed region starts.
+
+Prints one JSON line: trained tokens/s over the timed steps, the MFMA roofline figures of the
+linear-layer contraction class measured with HIP events inside the timed region, and the CPU
+oracle timed on this machine's host cores on a bounded sample (the same widths at depth 2).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+
+
+def fill_weights(model, cfg, seed):
+    """N(0, 0.02^2) matrices, unit gains, zero biases, drawn on the device unit by unit."""
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    per_unit = {}
+    for name, shape, kind, unit, off in model.tensors:
+        per_unit.setdefault(unit, []).append((shape, kind))
+    for unit in sorted(per_unit):
+        parts = []
+        for shape, kind in per_unit[unit]:
+            n = int(np.prod(shape))
+            if kind == 0:
+                parts.append(torch.randn(n, generator=g, device="cuda", dtype=torch.float32) * 0.02)
+            else:
+                parts.append(torch.full((n,), 1.0 if kind == 1 else 0.0, device="cuda"))
+        flat = torch.cat(parts).cpu().numpy()
+        model.write_params(unit, unit + 1, flat)
+        del parts, flat
+
+
+def cpu_baseline(wl_name, seed):
+    """Times one oracle step on the depth-2 twin of the workload (same widths, batch, sequence)."""
+    from hift_inputs import WORKLOADS, init_params, make_batch, model_config
+    from oracle import hift_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    full, twin = WORKLOADS[wl_name], WORKLOADS[wl_name + "_L2"]
+    cfg = model_config(twin)
+    spec = [(n, s, k) for n, s, k, _u in O.param_tensors(cfg)]
+    theta = init_params(seed, spec, bf16_exact=True).astype(np.float64)
+    orc = O.HiftOracle(cfg, twin["opt"], theta, half_weights=True)
+    orc.set_group_schedule("bottom2up", 1, 0)
+    tok, lab = make_batch(twin, seed, 1)
+    t0 = time.perf_counter()
+    orc.step(tok, lab, 1)
+    dt = time.perf_counter() - t0
+    T = tok.size
+    # matrix-product flops of a full (untruncated) step: 6 per parameter of the linear layers
+    # per token, plus attention; the oracle always does the full backward
+    def step_flops(L):
+        c = model_config(full, n_layers=L)
+        d, f, V, S = c["d_model"], c["d_ffn"], c["vocab"], twin["seq"]
+        layer = 4 * d * d + 3 * d * f
+        att = 2 * 2 * S * d
+        return 3.0 * T * (2 * L * layer + L * att + 2 * V * d)
+    scale = step_flops(full["n_layers"]) / step_flops(2)
+    return {
+        "value": T / (dt * scale), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"one float64 oracle step (full forward and backward, AdamW on one layer) on the depth-2 twin "
+                   f"of {wl_name} (same widths, batch {twin['batch']} x {twin['seq']}): {dt:.1f} s = {T / dt:.1f} tokens/s; "
+                   f"value is that rate scaled to {full['n_layers']} layers by the matrix-product flop ratio {scale:.2f}"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=34)
+    ap.add_argument("--warmup", type=int, default=34)
+    ap.add_argument("--workload", default="C4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: the HiFT step library is single-GPU in this build "
+              "(--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2401_15207_amd as H
+    from hift_inputs import WORKLOADS, make_batch, model_config
+
+    wl = WORKLOADS[a.workload]
+    cfg = model_config(wl)
+    B, S = wl["batch"], wl["seq"]
+    t_setup = time.perf_counter()
+    model = H.HiftModel(cfg, wl["opt"], wl["m"], B, S, init_params=None, state_on_host=1)
+    fill_weights(model, cfg, a.seed)
+    k = model.set_group_schedule(wl["strategy"], wl["m"], a.seed)
+    n_total = a.steps + a.warmup
+    batches = []
+    for t in range(1, n_total + 1):
+        tok, lab = make_batch(wl, a.seed, t)
+        batches.append((torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda()))
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t_setup
+
+    t = 0
+    loss = None
+    for _ in range(a.warmup):
+        t += 1
+        model.step(*batches[t - 1], model.schedule_group_at(t), want_loss=False)
+    model.synchronize()
+    torch.cuda.synchronize()
+
+    # timed region: K steps, kernel classes bracketed by HIP events on the compute stream
+    model.profile_enable(True)
+    h2d0, d2h0 = model.transfer_stats()
+    exposed = 0.0
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        t += 1
+        model.step(*batches[t - 1], model.schedule_group_at(t), want_loss=False)
+    model.synchronize()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_gemm, ms_gemm, fl_gemm = model.profile_read(0)
+    n_att, ms_att, fl_att = model.profile_read(1)
+    n_el, ms_el, _ = model.profile_read(2)
+    n_opt, ms_opt, by_opt = model.profile_read(3)
+    model.profile_enable(False)
+    h2d1, d2h1 = model.transfer_stats()
+
+    # a second, unprofiled pass over the next K steps tells what the event brackets cost
+    t_plain = None
+    if a.steps > 0:
+        tp0 = time.perf_counter()
+        for _ in range(a.steps):
+            t += 1
+            model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=False)
+        model.synchronize()
+        torch.cuda.synchronize()
+        t_plain = time.perf_counter() - tp0
+    # exposed copy time and loss of one more step
+    t += 1
+    loss = model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=True)
+    _step_ms, exposed = model.last_step_ms()
+
+    tokens = a.steps * B * S
+    gemm_tflops = fl_gemm / (ms_gemm * 1e-3) / 1e12 if ms_gemm > 0 else 0.0
+    out = {
+        "metric": "trained tokens/sec per HiFT step at 7B shape (1 GPU); MFMA util % of bf16 peak",
+        "value": tokens / elapsed if elapsed > 0 else 0.0,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": 1e3 * elapsed / max(a.steps, 1),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{a.workload}: LLaMA-7B-shaped decoder, 32 layers d=4096 h=32 ffn=11008 vocab=32000, "
+                               f"batch {B} x seq {S}, m=1 ({k} groups), bottom2up, AdamW, optimizer state of "
+                               f"inactive groups in pinned host memory" if a.workload == "C4" else a.workload,
+                   "groups": k, "tokens_per_step": B * S},
+        "roofline": {
+            "bound": "mfma", "kernel": "gemm_mfma_k (linear layers: forward, dX, active-group dW)",
+            "achieved": gemm_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": gemm_tflops / BF16_PEAK_TFLOPS, "traffic": None,
+            "launches": n_gemm, "avg_launch_ms": ms_gemm / max(n_gemm, 1),
+            "flops_per_launch": fl_gemm / max(n_gemm, 1),
+        },
+        "kernel_classes_ms_per_step": {
+            "linear_gemm": ms_gemm / max(a.steps, 1), "attention_gemm": ms_att / max(a.steps, 1),
+            "rowwise_elementwise": ms_el / max(a.steps, 1), "optimizer": ms_opt / max(a.steps, 1),
+        },
+        "attention_gemm_tflops": fl_att / (ms_att * 1e-3) / 1e12 if ms_att > 0 else 0.0,
+        "optimizer_gbps": by_opt / (ms_opt * 1e-3) / 1e9 if ms_opt > 0 else 0.0,
+        "state_copy_gb_per_step": {"h2d": (h2d1 - h2d0) / 1e9 / max(a.steps, 1), "d2h": (d2h1 - d2h0) / 1e9 / max(a.steps, 1)},
+        "exposed_state_copy_ms_last_step": exposed,
+        "ms_per_step_without_event_brackets": None if t_plain is None else 1e3 * t_plain / max(a.steps, 1),
+        "last_loss": loss,
+        "setup_s": setup_s,
+    }
+    if not a.no_cpu_baseline and a.workload in ("C4", "C5"):
+        model.close()
+        del model
+        out["cpu_baseline"] = cpu_baseline(a.workload, a.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
