@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--copy-engine", type=int, default=0, help="0 hipMemcpyAsync, 1 small-grid copy kernel")
+    ap.add_argument("--copy-blocks", type=int, default=16)
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: the HiFT step library is single-GPU in this build "
@@ -109,6 +111,7 @@ def main():
     B, S = wl["batch"], wl["seq"]
     t_setup = time.perf_counter()
     model = H.HiftModel(cfg, wl["opt"], wl["m"], B, S, init_params=None, state_on_host=1)
+    model.set_state_copy_engine(a.copy_engine, a.copy_blocks)
     fill_weights(model, cfg, a.seed)
     k = model.set_group_schedule(wl["strategy"], wl["m"], a.seed)
     n_total = a.steps + a.warmup
@@ -123,38 +126,37 @@ def main():
     loss = None
     for _ in range(a.warmup):
         t += 1
-        model.step(*batches[t - 1], model.schedule_group_at(t), want_loss=False)
+        model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=False)
     model.synchronize()
     torch.cuda.synchronize()
 
-    # timed region: K steps, kernel classes bracketed by HIP events on the compute stream
-    model.profile_enable(True)
+    # timed region: K steps.  `value` is taken here, with nothing but the steps on the streams.
     h2d0, d2h0 = model.transfer_stats()
-    exposed = 0.0
     t0 = time.perf_counter()
     for _ in range(a.steps):
         t += 1
-        model.step(*batches[t - 1], model.schedule_group_at(t), want_loss=False)
+        model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=False)
     model.synchronize()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    h2d1, d2h1 = model.transfer_stats()
+
+    # the next K steps repeat the region with every kernel launch bracketed by HIP events on the
+    # compute stream: per-class kernel time for the roofline figures (the brackets keep
+    # consecutive kernels from overlapping, so this pass is a few percent slower)
+    model.profile_enable(True)
+    tp0 = time.perf_counter()
+    for _ in range(a.steps):
+        t += 1
+        model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=False)
+    model.synchronize()
+    torch.cuda.synchronize()
+    t_prof = time.perf_counter() - tp0
     n_gemm, ms_gemm, fl_gemm = model.profile_read(0)
     n_att, ms_att, fl_att = model.profile_read(1)
     n_el, ms_el, _ = model.profile_read(2)
     n_opt, ms_opt, by_opt = model.profile_read(3)
     model.profile_enable(False)
-    h2d1, d2h1 = model.transfer_stats()
-
-    # a second, unprofiled pass over the next K steps tells what the event brackets cost
-    t_plain = None
-    if a.steps > 0:
-        tp0 = time.perf_counter()
-        for _ in range(a.steps):
-            t += 1
-            model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=False)
-        model.synchronize()
-        torch.cuda.synchronize()
-        t_plain = time.perf_counter() - tp0
     # exposed copy time and loss of one more step
     t += 1
     loss = model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=True)
@@ -189,7 +191,8 @@ def main():
         "optimizer_gbps": by_opt / (ms_opt * 1e-3) / 1e9 if ms_opt > 0 else 0.0,
         "state_copy_gb_per_step": {"h2d": (h2d1 - h2d0) / 1e9 / max(a.steps, 1), "d2h": (d2h1 - d2h0) / 1e9 / max(a.steps, 1)},
         "exposed_state_copy_ms_last_step": exposed,
-        "ms_per_step_without_event_brackets": None if t_plain is None else 1e3 * t_plain / max(a.steps, 1),
+        "state_copy_engine": "copy kernel, %d workgroups" % a.copy_blocks if a.copy_engine == 1 else "hipMemcpyAsync",
+        "ms_per_step_with_event_brackets": 1e3 * t_prof / max(a.steps, 1),
         "last_loss": loss,
         "setup_s": setup_s,
     }

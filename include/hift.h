@@ -196,6 +196,14 @@ hift_status hift_transfer_stats(hift_model* mdl, uint64_t* h2d_bytes, uint64_t* 
  * state had arrived (exposed copy time).  Waits for the streams. */
 hift_status hift_last_step_ms(hift_model* mdl, float* step_ms, float* exposed_copy_ms);
 
+/* How optimizer state moves between the pinned arena and HBM (Algorithm 1 steps i and k).
+ * engine 0 (default): hipMemcpyAsync on the two copy streams; the library lets at most one
+ * host-to-device transfer be outstanding when it submits the next, which keeps the runtime on
+ * its DMA engines.  engine 1: a copy kernel with a fixed grid of `blocks` workgroups on the copy
+ * streams (for comparison; kernels that touch host memory slow concurrent kernels).  Results are
+ * identical.  Waits for the streams. */
+hift_status hift_set_state_copy_engine(hift_model* mdl, int32_t engine, int32_t blocks);
+
 /* Kernel-class timing for roofline reports.  While enabled, every kernel launch of hift_step is
  * bracketed by HIP events on the compute stream.  hift_profile_read sums, for one class
  * (0 linear-layer contractions, 1 attention contractions, 2 row-wise/elementwise kernels,

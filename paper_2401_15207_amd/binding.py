@@ -68,6 +68,7 @@ _SIGS = {
     "hift_read_state": [_vp, _i32, _i32, _i32, _vp, _sz],
     "hift_transfer_stats": [_vp, _P(_u64), _P(_u64)],
     "hift_last_step_ms": [_vp, _P(C.c_float), _P(C.c_float)],
+    "hift_set_state_copy_engine": [_vp, _i32, _i32],
     "hift_profile_enable": [_vp, _i32],
     "hift_profile_read": [_vp, _i32, _P(_i64), _P(C.c_double), _P(C.c_double)],
     "hift_kernel_gemm": [_i32, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp,
@@ -271,6 +272,9 @@ class HiftModel:
         a, b = C.c_float(), C.c_float()
         _check(lib.hift_last_step_ms(self.h, C.byref(a), C.byref(b)))
         return a.value, b.value
+
+    def set_state_copy_engine(self, engine: int, blocks: int = 16):
+        _check(lib.hift_set_state_copy_engine(self.h, engine, blocks))
 
     def profile_enable(self, on: bool):
         _check(lib.hift_profile_enable(self.h, int(on)))

@@ -14,6 +14,7 @@ namespace hift {
 namespace {
 
 constexpr int BLK = 256;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 template <typename T>
 constexpr int vecw() { return 16 / sizeof(T); }
@@ -431,6 +432,28 @@ __global__ void __launch_bounds__(BLK) fill_zero_k(uint4* __restrict__ p, int64_
   if (i < tail) tail_p[i] = 0;
 }
 
+// ---------------------------------------------------------------------------- state copy
+// Background copy between pinned host memory and HBM by a deliberately small grid.  The grid
+// bounds how many compute units the copy can occupy, so a copy that runs beside the step's
+// kernels cannot crowd them out; it only has to keep the PCIe link busy, which a few hundred
+// KB of loads in flight already do.  Non-temporal accesses keep the stream out of L2.
+__global__ void __launch_bounds__(BLK) copy_stream_k(u32x4_t* __restrict__ dst, const u32x4_t* __restrict__ src,
+                                                      int64_t n16) {
+  const int64_t stride = (int64_t)gridDim.x * BLK;
+  int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const u32x4_t a = __builtin_nontemporal_load(src + i);
+    const u32x4_t b = __builtin_nontemporal_load(src + i + stride);
+    const u32x4_t c = __builtin_nontemporal_load(src + i + 2 * stride);
+    const u32x4_t d = __builtin_nontemporal_load(src + i + 3 * stride);
+    __builtin_nontemporal_store(a, dst + i);
+    __builtin_nontemporal_store(b, dst + i + stride);
+    __builtin_nontemporal_store(c, dst + i + 2 * stride);
+    __builtin_nontemporal_store(d, dst + i + 3 * stride);
+  }
+  for (; i < n16; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
 // ---------------------------------------------------------------------------- optimizer
 // Group-local update over contiguous fp32 master weights.  KIND 0 AdamW (decoupled decay),
 // 1 AdaGrad, 2 SGD with momentum, 3 plain SGD.  Four parameters per thread (16-byte accesses).
@@ -689,6 +712,13 @@ hipError_t fill_zero(void* p, size_t bytes, hipStream_t st) {
   if (tail > BLK && n16 == 0) return hipErrorInvalidValue;  // unaligned large fills are not used
   fill_zero_k<<<dim3((unsigned)(n16 ? cdiv(n16, BLK) : 1)), BLK, 0, st>>>((uint4*)p, n16,
                                                                             (unsigned char*)p + n16 * 16, tail);
+  LAUNCH_CHECK();
+}
+
+hipError_t copy_stream(void* dst, const void* src, size_t bytes, int blocks, hipStream_t st) {
+  if (bytes == 0) return hipSuccess;
+  if (bytes % 16 != 0 || !aligned16(dst) || !aligned16(src) || blocks < 1) return hipErrorInvalidValue;
+  copy_stream_k<<<dim3((unsigned)blocks), BLK, 0, st>>>((u32x4_t*)dst, (const u32x4_t*)src, (int64_t)(bytes / 16));
   LAUNCH_CHECK();
 }
 

@@ -66,6 +66,8 @@ hipError_t scatter_first(int dt, int B, int S, int d, const void* dy, void* dx, 
 hipError_t cast_f32_to(int dt, int64_t n, const float* src, void* dst, hipStream_t st);
 hipError_t cast_to_f32(int dt, int64_t n, const void* src, float* dst, hipStream_t st);
 hipError_t fill_zero(void* p, size_t bytes, hipStream_t st);
+// copy of a multiple of 16 bytes by a grid of `blocks` workgroups; either side may be pinned host memory
+hipError_t copy_stream(void* dst, const void* src, size_t bytes, int blocks, hipStream_t st);
 
 // ---- optimizer ---------------------------------------------------------------------------
 struct OptArgs {

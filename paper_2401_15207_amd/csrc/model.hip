@@ -234,6 +234,8 @@ struct hift_model {
   hipStream_t cs, hs, ds;
   hipEvent_t ev_h2d[2], ev_opt[2], ev_d2h[2], ev_t0, ev_t1, ev_w0, ev_w1;
   bool d2h_pending[2] = {false, false};
+  int h2d_last = -1;            // slot of the most recent host-to-device transfer
+  int d2h_group[2] = {-1, -1};  // group whose state the pending write-back of a slot carries
   int slot_group[2] = {-1, -1};  // group whose state a slot holds (arrived or in flight)
   int cur_slot = 0;
   // schedule
@@ -243,6 +245,8 @@ struct hift_model {
   int64_t t = 0;
   uint64_t h2d_bytes = 0, d2h_bytes = 0;
   bool timed = false;
+  int copy_engine = 0;   // 0: hipMemcpyAsync, 1: small-grid copy kernel
+  int copy_blocks = 16;
   Prof prof;
 
   const Tensor& T_(const std::string& n) const { return lay.t[lay.find(n)]; }
@@ -372,6 +376,13 @@ struct Scope {
 };
 
 #define K_TRY(expr) HIP_TRY(expr)
+
+#define ST_TRY(expr)                 \
+  do {                               \
+    hift_status s_ = (expr);         \
+    if (s_ != HIFT_OK) return s_;    \
+  } while (0)
+
 
 hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, const Tensor* bias, const void* R,
                    void* y) {
@@ -540,12 +551,6 @@ Names layer_names(const hift_model* M, int l) {
   }
   return n;
 }
-
-#define ST_TRY(expr)                 \
-  do {                               \
-    hift_status s_ = (expr);         \
-    if (s_ != HIFT_OK) return s_;    \
-  } while (0)
 
 hift_status ew(hift_model* M, hipError_t e) {
   if (e != hipSuccess) return fail(HIFT_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
@@ -799,21 +804,42 @@ void group_range(const hift_model* M, int gid, int* ulo, int* uhi, int64_t* plo,
   *pcnt = c;
 }
 
+// One leg of the optimizer-state movement, on the host-to-device or device-to-host stream:
+// hipMemcpyAsync (DMA engines) by default, or a copy kernel with a small fixed grid.  Any
+// kernel that reads or writes host memory while the step runs slows the step's own kernels
+// severely (measured: 4x on the contractions even with 16 workgroups), so the DMA path is the
+// one to use; fetch_state keeps it on the DMA engines.
+hift_status state_copy(hift_model* M, void* dst, const void* src, size_t bytes, bool to_device) {
+  hipStream_t st = to_device ? M->hs : M->ds;
+  if (M->copy_engine == 1 && bytes % 16 == 0 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0 &&
+      (reinterpret_cast<uintptr_t>(src) & 15) == 0) {
+    HIP_TRY(copy_stream(dst, src, bytes, M->copy_blocks, st));
+  } else {
+    HIP_TRY(hipMemcpyAsync(dst, src, bytes, to_device ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost, st));
+  }
+  return HIFT_OK;
+}
+
 // Queue the host-to-device copy of a group's state into a slot (Algorithm 1 step i).
 hift_status fetch_state(hift_model* M, int gid, int s) {
   int ulo, uhi;
   int64_t plo, cnt;
   group_range(M, gid, &ulo, &uhi, &plo, &cnt);
-  // the slot may still be draining to the host, and the host copy of this group may still be
-  // in flight from its last visit: both are ordered by the device-to-host events
+  // order the copy after the write-backs it depends on, and only those: the one that last
+  // drained this slot, and one that carries this group's own state to the host
   for (int q = 0; q < 2; ++q)
-    if (M->d2h_pending[q]) HIP_TRY(hipStreamWaitEvent(M->hs, M->ev_d2h[q], 0));
+    if (M->d2h_pending[q] && (q == s || M->d2h_group[q] == gid)) HIP_TRY(hipStreamWaitEvent(M->hs, M->ev_d2h[q], 0));
+  // keep one host-to-device transfer outstanding at the moment the next is submitted: the host
+  // runs up to a step ahead of the GPU, and a copy submitted while the copy engine still has
+  // a backlog is executed by a full-grid copy kernel instead, which starves the step's kernels
+  if (M->copy_engine == 0 && M->h2d_last >= 0) HIP_TRY(hipEventSynchronize(M->ev_h2d[M->h2d_last]));
   for (int j = 0; j < M->n_state; ++j) {
-    HIP_TRY(hipMemcpyAsync(M->slot[s] + (size_t)j * M->grad_cap, M->host_state + (size_t)j * M->lay.n_params + plo,
-                           (size_t)cnt * 4, hipMemcpyHostToDevice, M->hs));
+    ST_TRY(state_copy(M, M->slot[s] + (size_t)j * M->grad_cap, M->host_state + (size_t)j * M->lay.n_params + plo,
+                      (size_t)cnt * 4, true));
     M->h2d_bytes += (uint64_t)cnt * 4;
   }
   HIP_TRY(hipEventRecord(M->ev_h2d[s], M->hs));
+  M->h2d_last = s;
   M->slot_group[s] = gid;
   return HIFT_OK;
 }
@@ -1106,12 +1132,13 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
     HIP_TRY(hipEventRecord(M->ev_opt[s], M->cs));
     HIP_TRY(hipStreamWaitEvent(M->ds, M->ev_opt[s], 0));
     for (int j = 0; j < M->n_state; ++j) {
-      HIP_TRY(hipMemcpyAsync(M->host_state + (size_t)j * M->lay.n_params + plo, M->slot[s] + (size_t)j * M->grad_cap,
-                             (size_t)cnt * 4, hipMemcpyDeviceToHost, M->ds));
+      ST_TRY(state_copy(M, M->host_state + (size_t)j * M->lay.n_params + plo, M->slot[s] + (size_t)j * M->grad_cap,
+                        (size_t)cnt * 4, false));
       M->d2h_bytes += (uint64_t)cnt * 4;
     }
     HIP_TRY(hipEventRecord(M->ev_d2h[s], M->ds));
     M->d2h_pending[s] = true;
+    M->d2h_group[s] = gid;
     M->cur_slot = s ^ 1;
   }
   M->t += 1;
@@ -1184,6 +1211,15 @@ hift_status hift_last_step_ms(hift_model* M, float* step_ms, float* exposed_copy
   ST_TRY(sync_all(M));
   if (step_ms) HIP_TRY(hipEventElapsedTime(step_ms, M->ev_t0, M->ev_t1));
   if (exposed_copy_ms) HIP_TRY(hipEventElapsedTime(exposed_copy_ms, M->ev_w0, M->ev_w1));
+  return HIFT_OK;
+}
+
+hift_status hift_set_state_copy_engine(hift_model* M, int32_t engine, int32_t blocks) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  if (engine < 0 || engine > 1 || blocks < 1 || blocks > 1024) return fail(HIFT_EINVAL, "engine must be 0 or 1, blocks in [1,1024]");
+  ST_TRY(sync_all(M));
+  M->copy_engine = engine;
+  M->copy_blocks = blocks;
   return HIFT_OK;
 }
 

@@ -78,10 +78,12 @@ def test_single_group_is_full_finetuning_step():
     assert rel_l2(gpu.read_params(), orc.theta) <= TOL
 
 
-def test_state_offload_matches_resident_state_bitwise():
+@pytest.mark.parametrize("engine", [0, 1], ids=["memcpy_async", "copy_kernel"])
+def test_state_offload_matches_resident_state_bitwise(engine):
     wl = WORKLOADS["C1"]
     _o1, g_res, _ = make_pair(wl, seed=4, state_on_host=0, jitter=0.02)
     _o2, g_off, _ = make_pair(wl, seed=4, state_on_host=1, jitter=0.02)
+    g_off.set_state_copy_engine(engine, 4)
     k = g_res.k
     for t in range(1, 3 * k + 1):
         gid = g_res.schedule_group_at(t)
