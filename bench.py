@@ -86,6 +86,65 @@ def cpu_baseline(wl_name, seed):
     }
 
 
+def measured_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed counter runs, or None when
+    the kernel source has changed since they were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "gemm_traffic.json")
+    src = os.path.join(ROOT, "paper_2401_15207_amd", "csrc", "gemm.hip")
+    try:
+        rec = json.load(open(path))
+        if rec.get("gemm_hip_sha256") != hashlib.sha256(open(src, "rb").read()).hexdigest():
+            return None
+        return rec["hbm_bytes_per_launch"]
+    except (OSError, ValueError, KeyError):
+        return None
+
+
+def kernel_bench(reps):
+    """Times the linear-layer contraction at every shape of the 7B workload, stand-alone, with
+    HIP events on the launch stream, then runs one plain 1 GiB device copy (the reference
+    kernel for scaling hardware byte counters).  One JSON line."""
+    import torch
+    import paper_2401_15207_amd as H
+    T, d, f, V = 2048, 4096, 11008, 32000
+    shapes = [  # name, M, N, K, a_kmajor, b_kmajor, out_f32
+        ("fwd_qkv", T, 3 * d, d, 1, 1, 0), ("fwd_o", T, d, d, 1, 1, 0), ("fwd_gate_up", T, 2 * f, d, 1, 1, 0),
+        ("fwd_down", T, d, f, 1, 1, 0), ("fwd_head", T, V, d, 1, 1, 0),
+        ("dx_qkv", T, d, 3 * d, 1, 0, 0), ("dx_o", T, d, d, 1, 0, 0), ("dx_gate_up", T, d, 2 * f, 1, 0, 0),
+        ("dx_down", T, f, d, 1, 0, 0), ("dx_head", T, d, V, 1, 0, 0),
+        ("dw_qkv", 3 * d, d, T, 0, 0, 1), ("dw_o", d, d, T, 0, 0, 1), ("dw_gate_up", 2 * f, d, T, 0, 0, 1),
+        ("dw_down", d, f, T, 0, 0, 1), ("dw_head", V, d, T, 0, 0, 1),
+    ]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0)
+    out = {}
+    st = torch.cuda.current_stream()
+    for name, M, N, K, ak, bk, of in shapes:
+        A = (torch.randn(M * K, generator=g, device="cuda") * 0.5).to(torch.bfloat16)
+        B = (torch.randn(N * K, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+        C = torch.empty(M * N, device="cuda", dtype=torch.float32 if of else torch.bfloat16)
+        lda, ldb = (K if ak else M), (K if bk else N)
+        for _ in range(2):
+            H.kernel_gemm(1, ak, bk, of, M, N, K, A, lda, B, ldb, C, N)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(reps):
+            H.kernel_gemm(1, ak, bk, of, M, N, K, A, lda, B, ldb, C, N)
+        e1.record(st)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        alg_bytes = 2 * (M * K + N * K) + (4 if of else 2) * M * N
+        out[name] = {"M": M, "N": N, "K": K, "us": 1e3 * ms, "tflops": 2.0 * M * N * K / ms / 1e9,
+                     "algorithmic_bytes": alg_bytes}
+        del A, B, C
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)                      # plain copy kernel: reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    print(json.dumps({"kernel_bench": out, "copy_reference_bytes_each_way": 1 << 30}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -96,11 +155,17 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--copy-engine", type=int, default=0, help="0 hipMemcpyAsync, 1 small-grid copy kernel")
     ap.add_argument("--copy-blocks", type=int, default=16)
+    ap.add_argument("--kernel-bench", type=int, default=0, metavar="REPS",
+                    help="time the contraction kernel alone at the 7B shapes, REPS launches each, and exit")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: the HiFT step library is single-GPU in this build "
               "(--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
+
+    if a.kernel_bench > 0:
+        kernel_bench(a.kernel_bench)
+        return
 
     import torch
     import paper_2401_15207_amd as H
@@ -156,6 +221,7 @@ def main():
     n_att, ms_att, fl_att = model.profile_read(1)
     n_el, ms_el, _ = model.profile_read(2)
     n_opt, ms_opt, by_opt = model.profile_read(3)
+    n_rest, ms_rest, fl_rest = model.profile_read(4)
     model.profile_enable(False)
     # exposed copy time and loss of one more step
     t += 1
@@ -177,16 +243,20 @@ def main():
                                f"inactive groups in pinned host memory" if a.workload == "C4" else a.workload,
                    "groups": k, "tokens_per_step": B * S},
         "roofline": {
-            "bound": "mfma", "kernel": "gemm_mfma_k (linear layers: forward, dX, active-group dW)",
+            "bound": "mfma",
+            "kernel": "gemm_mfma_k<256,256,k-major,k-major,bf16 out>: forward linear layers on 256x256 tiles (QKV, gate/up, head)",
             "achieved": gemm_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": gemm_tflops / BF16_PEAK_TFLOPS, "traffic": None,
+            "frac": gemm_tflops / BF16_PEAK_TFLOPS, "traffic": measured_traffic(),
             "launches": n_gemm, "avg_launch_ms": ms_gemm / max(n_gemm, 1),
             "flops_per_launch": fl_gemm / max(n_gemm, 1),
         },
         "kernel_classes_ms_per_step": {
-            "linear_gemm": ms_gemm / max(a.steps, 1), "attention_gemm": ms_att / max(a.steps, 1),
+            "linear_gemm_fwd_256": ms_gemm / max(a.steps, 1), "linear_gemm_other": ms_rest / max(a.steps, 1),
+            "attention_gemm": ms_att / max(a.steps, 1),
             "rowwise_elementwise": ms_el / max(a.steps, 1), "optimizer": ms_opt / max(a.steps, 1),
         },
+        "linear_gemm_all_tflops": (fl_gemm + fl_rest) / ((ms_gemm + ms_rest) * 1e-3) / 1e12 if ms_gemm + ms_rest > 0 else 0.0,
+        "linear_gemm_other_tflops": fl_rest / (ms_rest * 1e-3) / 1e12 if ms_rest > 0 else 0.0,
         "attention_gemm_tflops": fl_att / (ms_att * 1e-3) / 1e12 if ms_att > 0 else 0.0,
         "optimizer_gbps": by_opt / (ms_opt * 1e-3) / 1e9 if ms_opt > 0 else 0.0,
         "state_copy_gb_per_step": {"h2d": (h2d1 - h2d0) / 1e9 / max(a.steps, 1), "d2h": (d2h1 - d2h0) / 1e9 / max(a.steps, 1)},

@@ -472,7 +472,8 @@ inline bool al16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) =
 
 }  // namespace
 
-hipError_t gemm(const Gemm& g, hipStream_t st) {
+hipError_t gemm(const Gemm& g, hipStream_t st, int* variant) {
+  if (variant) *variant = 0;
   if (g.M <= 0 || g.N <= 0 || g.nb <= 0 || g.nh <= 0) return hipSuccess;
   GemmP p;
   p.M = g.M; p.N = g.N; p.K = g.K;
@@ -498,6 +499,7 @@ hipError_t gemm(const Gemm& g, hipStream_t st) {
       const bool big = g.M >= 256 && g.N >= 256 && t256 >= 200;
       const bool vec = g.N % 8 == 0 && g.ldc % 8 == 0 && al16(g.C) && (!g.R || (g.ldr % 8 == 0 && al16(g.R))) &&
                        g.sc1 % 8 == 0 && g.sc2 % 8 == 0 && (!g.bias || al16(g.bias));
+      if (variant) *variant = big ? 2 : 1;
       if (g.out_f32) {
         if (big) return launch_mfma_layout<256, 256, float>(p, g.a_kmajor, g.b_kmajor, ktail, vec, nz, st);
         return launch_mfma_layout<128, 128, float>(p, g.a_kmajor, g.b_kmajor, ktail, vec, nz, st);

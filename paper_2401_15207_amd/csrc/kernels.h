@@ -25,7 +25,8 @@ struct Gemm {
   int nb = 1, nh = 1;
   int64_t sa1 = 0, sa2 = 0, sb1 = 0, sb2 = 0, sc1 = 0, sc2 = 0;
 };
-hipError_t gemm(const Gemm& g, hipStream_t st);
+// variant (optional) receives which kernel ran: 0 plain FMA, 1 MFMA 128x128 tiles, 2 MFMA 256x256 tiles
+hipError_t gemm(const Gemm& g, hipStream_t st, int* variant = nullptr);
 
 // ---- row-wise and elementwise kernels ------------------------------------------------------
 hipError_t embed_fwd(int dt, const int32_t* tokens, int64_t T, int S, int d, int V,

@@ -353,7 +353,9 @@ hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_o
 }
 
 // ---- profiling of kernel classes (events around launches) ---------------------------------
-enum { CAT_GEMM = 0, CAT_ATTN = 1, CAT_ELEM = 2, CAT_OPT = 3, CAT_N = 4 };
+// CAT_GEMM: forward linear layers on 256x256 tiles (the dominant kernel instantiation);
+// CAT_GEMM_REST: every other linear-layer contraction (128x128 tiles, dX, dW)
+enum { CAT_GEMM = 0, CAT_ATTN = 1, CAT_ELEM = 2, CAT_OPT = 3, CAT_GEMM_REST = 4, CAT_N = 5 };
 
 struct Scope {
   hift_model* M;
@@ -396,7 +398,9 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
   g.bias = bias ? M->W(*bias) : nullptr;
   g.R = R; g.ldr = w.rows;
   Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
-  K_TRY(gemm(g, M->cs));
+  int variant = 0;
+  K_TRY(gemm(g, M->cs, &variant));
+  if (sc.r && variant != 2) sc.r->cat = CAT_GEMM_REST;
   return HIFT_OK;
 }
 
@@ -409,7 +413,7 @@ hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor&
   g.B = M->W(w); g.ldb = w.cols; g.b_kmajor = false;
   g.C = dx; g.ldc = w.cols;
   g.R = R; g.ldr = w.cols;
-  Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
+  Scope sc(M, CAT_GEMM_REST, 2.0 * rows * w.rows * w.cols);
   K_TRY(gemm(g, M->cs));
   return HIFT_OK;
 }
@@ -423,7 +427,7 @@ hift_status linear_dw(hift_model* M, const void* dy, const void* x, int64_t rows
   g.A = dy; g.lda = w.rows; g.a_kmajor = false;
   g.B = x; g.ldb = w.cols; g.b_kmajor = false;
   g.C = M->grad + (w.off - glo); g.ldc = w.cols;
-  Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
+  Scope sc(M, CAT_GEMM_REST, 2.0 * rows * w.rows * w.cols);
   K_TRY(gemm(g, M->cs));
   return HIFT_OK;
 }
