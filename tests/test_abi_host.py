@@ -1,0 +1,90 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every function include/hift.h declares,
+and its host-side integer logic (layout, groups, orders, arena sizes, argument errors) agrees with
+the oracle.  No kernel is launched here."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from hift_inputs import WORKLOADS, model_config
+from oracle import hift_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def H():
+    import paper_2401_15207_amd as H
+    return H
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "hift.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hift_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(H):
+    names = declared_functions()
+    assert len(names) >= 25 and "hift_step" in names and "hift_model_create" in names
+    missing = [n for n in names if not hasattr(H.lib, n)]
+    assert not missing, missing
+
+
+def test_layout_matches_oracle_for_all_workloads(H):
+    for name in ("C1", "C2", "C3", "C4", "C5", "C4_L2", "C5_L2"):
+        cfg = model_config(WORKLOADS[name])
+        tl, n = H.tensor_list(cfg)
+        ref = O.param_tensors(cfg)
+        assert n == O.n_params(cfg) and len(tl) == len(ref)
+        off = 0
+        for (gn, gs, gk, gu, go), (rn, rs, rk, ru) in zip(tl, ref):
+            assert (gn, tuple(gs), gk, gu, go) == (rn, tuple(rs), rk, ru, off)
+            off += int(np.prod(rs))
+
+
+def test_groups_and_orders_match_oracle(H):
+    for n in (4, 14, 26, 34, 42):
+        for m in (1, 2, 3, 4, 5, n, n + 3):
+            k = H.group_count(n, m)
+            assert k == O.n_groups(n, m)
+            for s in ("bottom2up", "top2down", "random"):
+                for seed in (0, 1, 2 ** 63 + 5):
+                    assert H.group_order(k, s, seed) == O.group_order(k, s, seed)
+
+
+def test_arena_sizes(H):
+    wl = WORKLOADS["C4"]
+    cfg = model_config(wl)
+    n = O.n_params(cfg)
+    big = max(c for _o, c in O.unit_ranges(cfg))
+    d_host, p_host = H.query_bytes(dict(cfg, state_on_host=1), wl["opt"], 1, 4, 512)
+    d_res, p_res = H.query_bytes(dict(cfg, state_on_host=0), wl["opt"], 1, 4, 512)
+    assert p_res == 0 and p_host == 2 * 4 * n                       # AdamW: m and v of every parameter
+    assert d_res - d_host >= 2 * 4 * (n - 2 * big) - 4096            # two slots instead of all state
+    sgd = dict(kind="sgd", lr=0.1, momentum=0.0, weight_decay=0.0)
+    _d, p = H.query_bytes(dict(cfg, state_on_host=1), sgd, 1, 4, 512)
+    assert p == 0                                                    # plain SGD keeps no state
+    # fp32 AdamW, equal groups: parameters + gradient + state slots per group = (k+3)/k of the parameters
+    # (appendix "Memory Analysis"); here the largest group of the 7B shape is one layer
+    assert 4 * big + 2 * 4 * big == 3 * 4 * big
+
+
+def test_argument_errors_without_a_gpu(H):
+    import ctypes as C
+    from paper_2401_15207_amd import binding as B
+    k = C.c_int32()
+    assert H.lib.hift_group_count(0, 1, C.byref(k)) == -1
+    assert H.lib.hift_group_count(4, 0, C.byref(k)) == -1
+    assert b"must be" in H.lib.hift_last_error()
+    bad = B.make_config(dict(model_config(WORKLOADS["C1"]), n_heads=5))
+    n, t = C.c_int32(), C.c_int64()
+    assert H.lib.hift_tensor_count(C.byref(bad), C.byref(n), C.byref(t)) == -1
+    bad = B.make_config(dict(model_config(WORKLOADS["C1"]), arch=7))
+    assert H.lib.hift_tensor_count(C.byref(bad), C.byref(n), C.byref(t)) == -1
+    with pytest.raises(H.HiftError):
+        H.query_bytes(model_config(WORKLOADS["C1"]), WORKLOADS["C1"]["opt"], 1, 2, 64)   # seq above the position table
+    assert H.lib.hift_step(None, None, 0, None) == -1
+    assert H.lib.hift_read_params(None, 0, 1, 0, None, 0) == -1
+    H.lib.hift_model_destroy(None)
