@@ -206,9 +206,10 @@ hift_status hift_set_state_copy_engine(hift_model* mdl, int32_t engine, int32_t 
 
 /* Kernel-class timing for roofline reports.  While enabled, every kernel launch of hift_step is
  * bracketed by HIP events on the compute stream.  hift_profile_read sums, for one class
- * (0 forward linear-layer contractions that run on 256x256 tiles, 1 attention contractions,
- * 2 row-wise/elementwise kernels, 3 optimizer, 4 all other linear-layer contractions: forward
- * on 128x128 tiles, dX, dW), the launches since hift_profile_enable, their milliseconds, and
+ * (0 linear-layer contractions, forward and dX, that run on the packed-operand kernel,
+ * 1 attention contractions, 2 row-wise/elementwise kernels including the re-packing of updated
+ * weights, 3 optimizer, 4 all other linear-layer contractions: dW, small or unaligned shapes,
+ * fp32), the launches since hift_profile_enable, their milliseconds, and
  * their algorithmic work (flops for classes 0, 1 and 4, bytes for class 3, 0 for class 2). */
 hift_status hift_profile_enable(hift_model* mdl, int32_t on);
 hift_status hift_profile_read(hift_model* mdl, int32_t category, int64_t* launches, double* total_ms,
@@ -231,6 +232,21 @@ hift_status hift_kernel_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, 
                              const void* B, int64_t ldb, void* C, int64_t ldc, const void* bias,
                              const void* R, int32_t batch, int64_t sa, int64_t sb, int64_t sc,
                              void* stream);
+
+/* The forward and dX contractions of large layers read the weight operand from a copy packed in
+ * the register order of the matrix instruction (1 KB blocks: block (nb, kk), lane l holds
+ * B[nb*32 + l%32][kk*16 + (l/32)*8 .. +7]; rows padded to a multiple of 256).
+ * hift_kernel_packed_bytes: size of that copy for a [N, K] operand, 0 if it cannot be packed
+ * (needs N >= 256 and K a multiple of 32).  hift_kernel_pack_b: builds it from bf16 B given
+ * k-major (B(n,k) at B[n*ldb + k]) or transposed (at B[k*ldb + n]).  hift_kernel_gemm_packed:
+ * C[M,N] = A . B^T (+bias)(+R) with bf16 k-major A; HIFT_EINVAL for problems the kernel does
+ * not take (fewer than 200 tiles of 128x256, unaligned operands). */
+hift_status hift_kernel_packed_bytes(int64_t N, int64_t K, size_t* bytes);
+hift_status hift_kernel_pack_b(int32_t b_kmajor, int64_t N, int64_t K, const void* B, int64_t ldb,
+                               void* Bp, void* stream);
+hift_status hift_kernel_gemm_packed(int32_t out_f32, int64_t M, int64_t N, int64_t K, const void* A,
+                                    int64_t lda, const void* Bp, void* C, int64_t ldc,
+                                    const void* bias, const void* R, void* stream);
 
 /* Group-local optimizer update on `count` contiguous parameters (the update inside Algorithm 1's
  * backward step): master, grad, state1, state2 fp32; compute_copy (bf16, may be NULL) receives the

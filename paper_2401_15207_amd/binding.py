@@ -73,6 +73,9 @@ _SIGS = {
     "hift_profile_read": [_vp, _i32, _P(_i64), _P(C.c_double), _P(C.c_double)],
     "hift_kernel_gemm": [_i32, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp,
                          _i32, _i64, _i64, _i64, _vp],
+    "hift_kernel_packed_bytes": [_i64, _i64, _P(_sz)],
+    "hift_kernel_pack_b": [_i32, _i64, _i64, _vp, _i64, _vp, _vp],
+    "hift_kernel_gemm_packed": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp],
     "hift_kernel_optimizer": [_P(Opt), _i64, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_norm_fwd": [_i32, _i32, _i64, _i32, C.c_float, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_cross_entropy": [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp],
@@ -143,6 +146,25 @@ def kernel_gemm(dtype, a_kmajor, b_kmajor, out_f32, M, N, K, A, lda, B, ldb, Cm,
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib.hift_kernel_gemm(dtype, int(a_kmajor), int(b_kmajor), int(out_f32), M, N, K, _ptr(A), lda, _ptr(B),
                                 ldb, _ptr(Cm), ldc, _ptr(bias), _ptr(R), batch, sa, sb, sc, st))
+
+
+def kernel_packed_bytes(N, K) -> int:
+    b = _sz()
+    _check(lib.hift_kernel_packed_bytes(N, K, C.byref(b)))
+    return b.value
+
+
+def kernel_pack_b(b_kmajor, N, K, B, ldb, Bp, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_pack_b(int(b_kmajor), N, K, _ptr(B), ldb, _ptr(Bp), st))
+
+
+def kernel_gemm_packed(out_f32, M, N, K, A, lda, Bp, Cm, ldc, bias=None, R=None, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_gemm_packed(int(out_f32), M, N, K, _ptr(A), lda, _ptr(Bp), _ptr(Cm), ldc, _ptr(bias),
+                                       _ptr(R), st))
 
 
 def kernel_optimizer(opt: dict, count, decay, t, master, grad, s1, s2, compute_copy=None, stream=None):

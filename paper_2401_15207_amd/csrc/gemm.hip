@@ -11,6 +11,9 @@
 //     LDS rows are 128 bytes (64 bf16) with the 16-byte chunk index XOR-swizzled by the row so
 //     that both the 16-byte stores and the MFMA fragment reads spread over all banks.
 //   * fp32 and odd shapes: a plain 64x64x16 LDS-tiled FMA kernel with arbitrary strides.
+#include <cstdlib>
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -39,10 +42,12 @@ struct GemmP {
 // ------------------------------------------------------------------------------------------
 constexpr int KT = 64;  // k extent of a macro-tile
 
-// 16-byte chunk c of LDS row r lives at chunk position c ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 3).
-// f depends on r mod 32 only, so rows 32 apart differ by a constant byte offset and the
-// addresses of all MFMA fragments of a lane are one register plus immediates.
-__device__ __forceinline__ int swz_f(int row) { return (row & 7) ^ ((row >> 3) & 3); }
+// 16-byte chunk c of LDS row r lives at chunk position c ^ f(r), f(r) = (r ^ (r >> 3)) & 7.
+// Both the fragment reads (32 rows, one chunk) and the staging stores (k-major: one row, 8 chunks;
+// transposed: rows 8 apart, one chunk) then spread over all banks.  f(r + 64) = f(r) and
+// f(r + 32) = f(r) ^ 4, so the fragment addresses of a lane are two registers (even and odd
+// 32-row blocks) plus immediates.
+__device__ __forceinline__ int swz_f(int row) { return (row ^ (row >> 3)) & 7; }
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ swz_f(row); }
 
 // Staging of one operand tile (ROWS x 64 bf16) from HBM through registers into LDS, in 16-byte
@@ -113,9 +118,10 @@ struct Stage {
   __device__ __forceinline__ void store(unsigned char* lds, int tid, const u32x4 (&r)[NPIECE]) const {
     if (KMAJOR) {
       const int row = tid >> 3;
-      unsigned char* dst = lds + row * 128 + swz(row, tid & 7) * 16;
+      unsigned char* dst0 = lds + row * 128 + swz(row, tid & 7) * 16;
+      unsigned char* dst1 = lds + row * 128 + swz(row + 32, tid & 7) * 16;
 #pragma unroll
-      for (int i = 0; i < NPIECE; ++i) *reinterpret_cast<u32x4*>(dst + i * 4096) = r[i];
+      for (int i = 0; i < NPIECE; ++i) *reinterpret_cast<u32x4*>(((i & 1) ? dst1 : dst0) + i * 4096) = r[i];
     } else {
       constexpr int RB = ROWS / 8;
 #pragma unroll
@@ -146,143 +152,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return *reinterpret_cast<uint32_t*>(&v);
 }
 
-// Four wavefronts in a 2x2 grid, each (BM/2)x(BN/2).  The accumulators hold the transposed
-// tile (the weight-side operand is fed as MFMA's first operand), so that one lane owns four
-// consecutive output columns of one output row and the epilogue can store vectors.
-// Lane l, accumulator element e of sub-tile (i, j): output row i*32 + l%32,
-// column j*32 + 8*(e/4) + 4*(l/32) + e%4.
-template <int BM, int BN, bool AK, bool BKM, bool KTAIL, bool VEC_EPI, typename OutT>
-__global__ void __launch_bounds__(256) gemm_mfma_k(GemmP p) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, BUF = A_BYTES + B_BYTES;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD a
-  // contiguous run of tiles, ordered so that neighbours share the same B (weight) tile.
-  int tile = blockIdx.x;
-  const int ntile = p.tiles_m * p.tiles_n;
-  if ((ntile & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);
-  const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
-  const int z = blockIdx.y, zb = z / p.nh, zh = z % p.nh;
-  const bf16* A = reinterpret_cast<const bf16*>(p.A) + zb * p.sa1 + zh * p.sa2;
-  const bf16* B = reinterpret_cast<const bf16*>(p.B) + zb * p.sb1 + zh * p.sb2;
-  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-
-  f32x16 acc[MT][NT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int j = 0; j < NT; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  typedef Stage<BM, AK, KTAIL> StA;
-  typedef Stage<BN, BKM, KTAIL> StB;
-  StA sa;
-  StB sb;
-  sa.init(A, p.lda, m0, p.M, p.K, tid);
-  sb.init(B, p.ldb, n0, p.N, p.K, tid);
-  const int64_t nk = (p.K + KT - 1) / KT;
-  u32x4 ra[StA::NPIECE], rb[StB::NPIECE];  // the next tile on its way from HBM to LDS
-
-  sa.load(0, ra);
-  sb.load(0, rb);
-  sa.store(smem, tid, ra);
-  sb.store(smem + A_BYTES, tid, rb);
-  __syncthreads();
-
+// Epilogue shared by the contraction kernels: accumulators (transposed sub-tiles, see above) ->
+// C (+bias)(+residual), through LDS when rows can be moved as 16-byte pieces.
+template <int WM, int WN, bool VEC_EPI, typename OutT>
+__device__ __forceinline__ void store_tile(const GemmP& p, f32x16 (&acc)[WM / 32][WN / 32], unsigned char* smem,
+                                           int64_t m0, int64_t n0, int wm, int wn, int wave, int lane, int zb, int zh) {
+  constexpr int MT = WM / 32, NT = WN / 32;
   const int frow = lane & 31, fhalf = lane >> 5;
-  bf16x8 fa[2][MT], fb[2][NT];
-  // byte offset of this lane's fragment chunk for each k-step; rows 32 apart add 4096 bytes
-  int foff[KT / 16];
-#pragma unroll
-  for (int ks = 0; ks < KT / 16; ++ks) foff[ks] = frow * 128 + swz(frow, ks * 2 + fhalf) * 16;
-  const int a_base = wm * WM * 128, b_base = A_BYTES + wn * WN * 128;
-  auto read_frags = [&](bf16x8(&a)[MT], bf16x8(&b)[NT], const unsigned char* buf, int ks) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < MT; ++i) a[i] = *reinterpret_cast<const bf16x8*>(buf + foff[ks] + (a_base + i * 4096));
-#pragma unroll
-    for (int j = 0; j < NT; ++j) b[j] = *reinterpret_cast<const bf16x8*>(buf + foff[ks] + (b_base + j * 4096));
-  };
-  read_frags(fa[0], fb[0], smem, 0);
-
-  // One pass over a k-tile held in one of the two LDS buffers.  Every k-step is its own scheduling region.
-  // A wavefront cannot issue anything while it waits for the matrix pipe to take its next MFMA,
-  // so the memory instructions of a region are dealt out between its MFMAs:
-  //   step 0     global loads of tile kt+1 into registers, fragment reads of step 1
-  //   steps 1,2  fragment reads of the next step
-  //   step 3a    LDS stores of tile kt+1 into the other buffer, which was last read before the
-  //              previous barrier; first half of the MFMAs
-  //   barrier
-  //   step 3b    fragment reads of step 0 of tile kt+1; second half of the MFMAs
-  // Tiles past the end are the last tile again: loaded, stored, never used.
-  constexpr bool HINT = AK && BKM;  // the counts describe k-major staging; transposed staging schedules freely
-  constexpr int NM = MT * NT, NR = MT + NT, NL = StA::NPIECE + StB::NPIECE;
-  for (int64_t kt = 0; kt < nk; ++kt) {
-    unsigned char* cur = smem + (kt & 1) * BUF;
-    unsigned char* nxt = smem + ((kt + 1) & 1) * BUF;
-    const int64_t kt2 = kt + 1 < nk ? kt + 1 : nk - 1;
-#pragma unroll
-    for (int ks = 0; ks < KT / 16 - 1; ++ks) {
-      if (ks == 0) {
-        sa.load(kt2, ra);
-        sb.load(kt2, rb);
-      }
-      read_frags(fa[(ks + 1) & 1], fb[(ks + 1) & 1], cur, ks + 1);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i], acc[i][j], 0, 0, 0);
-      if (HINT) {
-#pragma unroll
-        for (int q = 0; q < NM; ++q) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          if (ks == 0 && q < NL) __builtin_amdgcn_sched_group_barrier(0x020, (NL + NM - 1) / NM, 0);
-          if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    constexpr int KL = KT / 16 - 1, HM = MT / 2;
-    sa.store(nxt, tid, ra);
-    sb.store(nxt + A_BYTES, tid, rb);
-#pragma unroll
-    for (int i = 0; i < HM; ++i)
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[KL & 1][j], fa[KL & 1][i], acc[i][j], 0, 0, 0);
-    if (HINT) {
-#pragma unroll
-      for (int q = 0; q < HM * NT; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x200, (NL + HM * NT - 1) / (HM * NT), 0);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(fa[0], fb[0], nxt, 0);
-#pragma unroll
-    for (int i = HM; i < MT; ++i)
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[KL & 1][j], fa[KL & 1][i], acc[i][j], 0, 0, 0);
-    if (HINT) {
-#pragma unroll
-      for (int q = 0; q < (MT - HM) * NT; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, (NR + (MT - HM) * NT - 1) / ((MT - HM) * NT), 0);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  }
-
   // ---- epilogue ----
-  const int z_c = zb * 0;  // (batch offsets below)
-  (void)z_c;
   OutT* C = reinterpret_cast<OutT*>(p.C) + zb * p.sc1 + zh * p.sc2;
   const OutT* R = p.R ? reinterpret_cast<const OutT*>(p.R) + zb * p.sc1 + zh * p.sc2 : nullptr;
   const bf16* bias = reinterpret_cast<const bf16*>(p.bias);
@@ -372,6 +249,403 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmP p) {
         }
     }
   }
+}
+
+// Four wavefronts in a 2x2 grid, each (BM/2)x(BN/2).  The accumulators hold the transposed
+// tile (the weight-side operand is fed as MFMA's first operand), so that one lane owns four
+// consecutive output columns of one output row and the epilogue can store vectors.
+// Lane l, accumulator element e of sub-tile (i, j): output row i*32 + l%32,
+// column j*32 + 8*(e/4) + 4*(l/32) + e%4.
+template <int BM, int BN, bool AK, bool BKM, bool KTAIL, bool VEC_EPI, typename OutT>
+__global__ void __launch_bounds__(256) gemm_mfma_k(GemmP p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, BUF = A_BYTES + B_BYTES;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD a
+  // contiguous run of tiles, ordered so that neighbours share the same B (weight) tile.
+  int tile = blockIdx.x;
+  const int ntile = p.tiles_m * p.tiles_n;
+  if ((ntile & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);
+  const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+  const int z = blockIdx.y, zb = z / p.nh, zh = z % p.nh;
+  const bf16* A = reinterpret_cast<const bf16*>(p.A) + zb * p.sa1 + zh * p.sa2;
+  const bf16* B = reinterpret_cast<const bf16*>(p.B) + zb * p.sb1 + zh * p.sb2;
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  typedef Stage<BM, AK, KTAIL> StA;
+  typedef Stage<BN, BKM, KTAIL> StB;
+  StA sa;
+  StB sb;
+  sa.init(A, p.lda, m0, p.M, p.K, tid);
+  sb.init(B, p.ldb, n0, p.N, p.K, tid);
+  const int64_t nk = (p.K + KT - 1) / KT;
+  u32x4 ra[StA::NPIECE], rb[StB::NPIECE];  // the next tile on its way from HBM to LDS
+
+  sa.load(0, ra);
+  sb.load(0, rb);
+  sa.store(smem, tid, ra);
+  sb.store(smem + A_BYTES, tid, rb);
+  __syncthreads();
+
+  const int frow = lane & 31, fhalf = lane >> 5;
+  bf16x8 fa[2][MT], fb[2][NT];
+  // byte offset of this lane's fragment chunk for each k-step; rows 32 apart add 4096 bytes
+  int foff[KT / 16][2];  // [k-step][parity of the 32-row block]
+#pragma unroll
+  for (int ks = 0; ks < KT / 16; ++ks) {
+    foff[ks][0] = frow * 128 + swz(frow, ks * 2 + fhalf) * 16;
+    foff[ks][1] = frow * 128 + swz(frow + 32, ks * 2 + fhalf) * 16;
+  }
+  static_assert(WM % 64 == 0 && WN % 64 == 0, "wave tiles start at multiples of 64 rows");
+  const int a_base = wm * WM * 128, b_base = A_BYTES + wn * WN * 128;
+  auto read_frags = [&](bf16x8(&a)[MT], bf16x8(&b)[NT], const unsigned char* buf, int ks) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) a[i] = *reinterpret_cast<const bf16x8*>(buf + foff[ks][i & 1] + (a_base + i * 4096));
+#pragma unroll
+    for (int j = 0; j < NT; ++j) b[j] = *reinterpret_cast<const bf16x8*>(buf + foff[ks][j & 1] + (b_base + j * 4096));
+  };
+  read_frags(fa[0], fb[0], smem, 0);
+
+  // One pass over a k-tile held in one of the two LDS buffers.  Every k-step is its own scheduling region.
+  // A wavefront cannot issue anything while it waits for the matrix pipe to take its next MFMA,
+  // so the memory instructions of a region are dealt out between its MFMAs:
+  //   step 0     global loads of tile kt+1 into registers, fragment reads of step 1
+  //   steps 1,2  fragment reads of the next step
+  //   step 3a    LDS stores of tile kt+1 into the other buffer, which was last read before the
+  //              previous barrier; first half of the MFMAs
+  //   barrier
+  //   step 3b    fragment reads of step 0 of tile kt+1; second half of the MFMAs
+  // Tiles past the end are the last tile again: loaded, stored, never used.
+  constexpr bool HINT = AK && BKM;  // the counts describe k-major staging; transposed staging schedules freely
+  constexpr int NM = MT * NT, NR = MT + NT, NL = StA::NPIECE + StB::NPIECE;
+  for (int64_t kt = 0; kt < nk; ++kt) {
+    unsigned char* cur = smem + (kt & 1) * BUF;
+    unsigned char* nxt = smem + ((kt + 1) & 1) * BUF;
+    const int64_t kt2 = kt + 1 < nk ? kt + 1 : nk - 1;
+#pragma unroll
+    for (int ks = 0; ks < KT / 16 - 1; ++ks) {
+      if (ks == 0) {
+        sa.load(kt2, ra);
+        sb.load(kt2, rb);
+      }
+      read_frags(fa[(ks + 1) & 1], fb[(ks + 1) & 1], cur, ks + 1);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i], acc[i][j], 0, 0, 0);
+      if (HINT) {
+#pragma unroll
+        for (int q = 0; q < NM; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (ks == 0 && q < NL) __builtin_amdgcn_sched_group_barrier(0x020, (NL + NM - 1) / NM, 0);
+          if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    constexpr int KL = KT / 16 - 1, HM = MT / 2;
+    sa.store(nxt, tid, ra);
+    sb.store(nxt + A_BYTES, tid, rb);
+#pragma unroll
+    for (int i = 0; i < HM; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[KL & 1][j], fa[KL & 1][i], acc[i][j], 0, 0, 0);
+    if (HINT) {
+#pragma unroll
+      for (int q = 0; q < HM * NT; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x200, (NL + HM * NT - 1) / (HM * NT), 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(fa[0], fb[0], nxt, 0);
+#pragma unroll
+    for (int i = HM; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[KL & 1][j], fa[KL & 1][i], acc[i][j], 0, 0, 0);
+    if (HINT) {
+#pragma unroll
+      for (int q = 0; q < (MT - HM) * NT; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, (NR + (MT - HM) * NT - 1) / ((MT - HM) * NT), 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  store_tile<WM, WN, VEC_EPI, OutT>(p, acc, smem, m0, n0, wm, wn, wave, lane, zb, zh);
+}
+
+// Direct-to-LDS load of 16 bytes per lane: M0 carries the LDS address of lane 0's piece and lane l
+// lands 16 l bytes further.  Inline assembly, with hand-placed s_waitcnt where the data is read:
+// the compiler cannot see which LDS reads depend on which load and would otherwise wait for all
+// of them before every read.
+__device__ __forceinline__ void load_to_lds_b128(u32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+               : "memory");
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16 MFMA kernel with the weight operand pre-packed in MFMA fragment order
+// ------------------------------------------------------------------------------------------
+// Weights do not change inside a step, so the library keeps a second copy of every large weight
+// matrix in the order the MFMA wants it: block (nb, kk) of 1 KB holds, for lane l, the 8 values
+// B[nb*32 + l%32][kk*16 + (l/32)*8 ..+7].  A wavefront loads its B fragments straight from
+// HBM/L2 into registers with fully coalesced 1 KB loads, eight k-steps ahead; only the activation
+// operand goes through LDS.  Rows of the packed copy are padded to a multiple of 256, so no load
+// leaves the buffer.
+constexpr int PKF = 8;  // k-steps of B fragments in flight per wavefront
+
+// Generic packer (any alignment): one wavefront per 1 KB block, element-wise reads.
+__global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int64_t ldb, int64_t N, int64_t K,
+                                                 bool b_kmajor, u32x4* __restrict__ Bp, int64_t n_blocks, int64_t k_steps) {
+  const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (w >= n_blocks * k_steps) return;
+  const int lane = threadIdx.x & 63;
+  const int64_t nb = w / k_steps, kk = w % k_steps;
+  const int64_t n = nb * 32 + (lane & 31), k0 = kk * 16 + (lane >> 5) * 8;
+  bf16x8 v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int64_t k = k0 + e;
+    float x = 0.f;
+    if (n < N && k < K) x = static_cast<float>(b_kmajor ? B[n * ldb + k] : B[k * ldb + n]);
+    v[e] = static_cast<__bf16>(x);
+  }
+  Bp[w * 64 + lane] = __builtin_bit_cast(u32x4, v);
+}
+
+// Packer for 16-byte aligned sources: a workgroup moves a 16 KB tile through LDS so that both the
+// reads of the source and the writes of the 1 KB blocks are whole contiguous runs.
+//   KMAJOR: tile = 32 rows (one n-block) x 256 k (16 k-steps); source rows are contiguous in k.
+//   else:   tile = 32 k (two k-steps) x 256 n (eight n-blocks); source rows are contiguous in n.
+template <bool KMAJOR>
+__global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B, int64_t ldb, int64_t N, int64_t K,
+                                                      u32x4* __restrict__ Bp, int64_t k_steps, int tiles_inner) {
+  constexpr int PITCH = 512 + 16;  // bytes per tile row in LDS; the pad spreads 16-byte reads of one column over the banks
+  __shared__ __attribute__((aligned(16))) unsigned char tile[32 * PITCH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t to = blockIdx.x / tiles_inner, ti = blockIdx.x % tiles_inner;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  if (KMAJOR) {
+    const int64_t nb = to, k00 = ti * 256;
+#pragma unroll
+    for (int ps = 0; ps < 4; ++ps) {
+      const int r = ps * 8 + (tid >> 5), c = (tid & 31) * 8;
+      const int64_t n = nb * 32 + r, k = k00 + c;
+      u32x4 v = zero;
+      if (n < N && k < K) v = *reinterpret_cast<const u32x4*>(B + n * ldb + k);
+      *reinterpret_cast<u32x4*>(tile + r * PITCH + c * 2) = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int kkl = wave * 4 + j;
+      const int64_t kk = ti * 16 + kkl;
+      if (kk < k_steps)
+        Bp[(nb * k_steps + kk) * 64 + lane] =
+            *reinterpret_cast<const u32x4*>(tile + (lane & 31) * PITCH + (kkl * 16 + (lane >> 5) * 8) * 2);
+    }
+  } else {
+    const int64_t kk0 = to * 2, n00 = ti * 256;
+#pragma unroll
+    for (int ps = 0; ps < 4; ++ps) {
+      const int r = ps * 8 + (tid >> 5), c = (tid & 31) * 8;
+      const int64_t k = kk0 * 16 + r, n = n00 + c;
+      u32x4 v = zero;
+      if (n + 8 <= N) {
+        v = *reinterpret_cast<const u32x4*>(B + k * ldb + n);
+      } else if (n < N) {
+        bf16x8 t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = n + e < N ? B[k * ldb + n + e] : static_cast<__bf16>(0.f);
+        v = __builtin_bit_cast(u32x4, t);
+      }
+      *reinterpret_cast<u32x4*>(tile + r * PITCH + c * 2) = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int idx = wave * 4 + j, nbl = idx >> 1, kkl = idx & 1;
+      bf16x8 t;
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        t[e] = *reinterpret_cast<const bf16*>(tile + (kkl * 16 + (lane >> 5) * 8 + e) * PITCH + (nbl * 32 + (lane & 31)) * 2);
+      Bp[((ti * 8 + nbl) * k_steps + kk0 + kkl) * 64 + lane] = __builtin_bit_cast(u32x4, t);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// The contraction kernel: a (32 MT) x 256 tile; the four wavefronts sit side by side along N, each
+// (32 MT) x 64, and a stage of A is 64 k wide.  Every 128-byte line of either operand is then
+// requested exactly once per compute unit: no wavefront shares a B fragment with another, and an A
+// row piece is a whole line (half lines and fragments shared by two wavefronts cost a third of the
+// speed in earlier layouts).  All wavefronts read all of A from LDS: MT 1 KB fragment reads per
+// 2 MT MFMAs, a quarter of what LDS delivers (about 240 bytes per clock per compute unit, measured).
+//   A stages arrive by direct-to-LDS loads into a ring of four, requested three stages ahead.
+//   LDS row = 128 bytes = eight 16-byte pieces; piece c of tile row r sits at r*128 + (c ^ ((r>>1)&7))*16,
+//   so that sixteen consecutive rows of one piece fall into sixteen different 16-byte bank groups;
+//   a load instruction fills 8 rows (lane l -> row l/8, position l%8), so the swizzle is applied by
+//   choosing which global piece a lane fetches.
+// MT = 4 (128 x 256 tiles) is the instantiation in use: at M = 2048 it gives the 7B shapes whole
+// numbers of rounds over 256 compute units more often than 256 x 256 does, and ran faster.
+constexpr int PK_DK = 64, PK_STAGES = 4, PK_RD = 3, PK_ROW = 128;
+
+template <int MT, bool VEC_EPI, typename OutT>
+__global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restrict__ Bp, int64_t k_steps) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int BM = 32 * MT, BN = 256, WN = 64, NT = 2;
+  constexpr int STG = BM * PK_ROW;  // one stage of A
+  constexpr int NP = MT;            // 1 KB pieces (8 rows) of a stage each wavefront requests
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int tile = blockIdx.x;
+  const int ntile = p.tiles_m * p.tiles_n;
+  if ((ntile & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);  // contiguous run of tiles per XCD
+  const int band = tile / (8 * p.tiles_n), in_band = tile - band * 8 * p.tiles_n;
+  const int band_rows = min(8, p.tiles_m - band * 8);
+  const int tm = band * 8 + in_band % band_rows, tn = in_band / band_rows;
+  const bf16* A = reinterpret_cast<const bf16*>(p.A);
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // A: direct-to-LDS; lane l of piece gi carries LDS bytes [16 l, 16 l + 16) of rows gi*8 .. gi*8+7
+  const uint64_t aa = reinterpret_cast<uint64_t>(A);
+  const u32x4 rsA = {(uint32_t)aa, (uint32_t)(aa >> 32) & 0xFFFFu, (uint32_t)(((p.M - 1) * p.lda + p.K) * 2), 0x00020000u};
+  uint32_t voA[NP];
+#pragma unroll
+  for (int gi = 0; gi < NP; ++gi) {
+    const int r = wave * (BM / 4) + gi * 8 + (lane >> 3);  // row in the tile
+    const int c = (lane & 7) ^ ((r >> 1) & 7);             // which 16 bytes of the row's 128 this lane fetches
+    const int64_t ra = m0 + r;
+    voA[gi] = (uint32_t)(((ra < p.M ? ra : p.M) * p.lda + c * 8) * 2);  // rows past M start past the buffer: zeros
+  }
+  const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+  auto request_piece = [&](int64_t stage, int gi) __attribute__((always_inline)) {
+    const uint32_t so = (uint32_t)(stage * PK_DK * 2);
+    const uint32_t dst = lds0 + (uint32_t)(stage & (PK_STAGES - 1)) * STG + (uint32_t)wave * (BM / 4 * PK_ROW);
+    load_to_lds_b128(rsA, dst + gi * 1024, voA[gi], so);
+  };
+
+  // B: packed fragments, straight into registers
+  const int64_t pk_bytes = (int64_t)p.tiles_n * 8 * k_steps * 1024;
+  const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4*>(Bp), 0, (int)(uint32_t)pk_bytes, 0x00020000);
+  const uint32_t vb = (uint32_t)lane * 16;
+  const uint32_t nb0 = (uint32_t)((n0 >> 5) + wave * NT);
+  auto load_b1 = [&](u32x4& dst, int64_t kk, int j) __attribute__((always_inline)) {
+    const int64_t kc = kk < k_steps ? kk : k_steps - 1;  // past the end: the last block again
+    dst = __builtin_amdgcn_raw_buffer_load_b128(rsB, (int)vb, (int)(uint32_t)(((nb0 + j) * k_steps + kc) * 1024), 0);
+  };
+
+  const int frow = lane & 31, fhalf = lane >> 5;
+  int foff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) foff[ks] = frow * PK_ROW + (((ks * 2 + fhalf) ^ ((frow >> 1) & 7)) * 16);
+  bf16x8 fa[2][MT];
+  auto read_a1 = [&](bf16x8& a, const unsigned char* buf, int ks, int i) __attribute__((always_inline)) {
+    a = *reinterpret_cast<const bf16x8*>(buf + foff[ks] + i * 32 * PK_ROW);
+  };
+  u32x4 bq[PKF][NT];
+
+#pragma unroll
+  for (int s = 0; s < PK_RD; ++s)
+#pragma unroll
+    for (int gi = 0; gi < NP; ++gi) request_piece(s, gi);
+#pragma unroll
+  for (int s = 0; s < PKF; ++s)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) load_b1(bq[s][j], s, j);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < MT; ++i) read_a1(fa[0][i], smem, 0, i);
+
+  // One k-step: 2 MT MFMAs in the order (j, i); after the q-th one: q < MT: A fragment q of the next
+  // k-step; q == MT: refill of B fragment 0; then (first two k-steps of a stage) NP / 2 pieces of the
+  // request for a later stage; last: refill of B fragment 1.  A wavefront issues in order and an MFMA
+  // holds the matrix pipe for 32 cycles, so every memory instruction sits in the shadow of one.
+  auto kstep = [&](auto KS_, auto SLOT_, auto MAIN_, int64_t kt, const unsigned char* src_next) __attribute__((always_inline)) {
+    constexpr int KS = decltype(KS_)::value, SLOT = decltype(SLOT_)::value;
+    constexpr bool refill = decltype(MAIN_)::value != 0, read_next = decltype(MAIN_)::value != 2;  // 1: in the loop; 0, 2: tail
+    bf16x8 b[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) b[j] = __builtin_bit_cast(bf16x8, bq[SLOT][j]);
+#pragma unroll
+    for (int q = 0; q < NT * MT; ++q) {
+      const int j = q / MT, i = q % MT;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], fa[KS & 1][i], acc[i][j], 0, 0, 0);
+      if (read_next && q < MT) read_a1(fa[(KS + 1) & 1][q], src_next, (KS + 1) & 3, q);
+      if (refill) {
+        if (q == MT) load_b1(bq[SLOT][0], kt * 4 + KS + PKF, 0);
+        if (KS < 2 && q > MT && q <= MT + NP / 2) request_piece(kt + PK_RD, KS * (NP / 2) + q - MT - 1);
+        if (q == NT * MT - 1) load_b1(bq[SLOT][1], kt * 4 + KS + PKF, 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  static_assert(PKF == 8 && NP % 2 == 0 && MT + NP / 2 < NT * MT && 19 + 2 * MT <= 63, "slot rotation and wait count below");
+  auto stage = [&](auto S0_, int64_t kt) __attribute__((always_inline)) {
+    constexpr int S0 = decltype(S0_)::value;
+    const unsigned char* cur = smem + (kt & (PK_STAGES - 1)) * STG;
+    const unsigned char* nxt = smem + ((kt + 1) & (PK_STAGES - 1)) * STG;
+    kstep(std::integral_constant<int, 0>{}, std::integral_constant<int, S0>{}, std::integral_constant<int, 1>{}, kt, cur);
+    kstep(std::integral_constant<int, 1>{}, std::integral_constant<int, S0 + 1>{}, std::integral_constant<int, 1>{}, kt, cur);
+    kstep(std::integral_constant<int, 2>{}, std::integral_constant<int, S0 + 2>{}, std::integral_constant<int, 1>{}, kt, cur);
+    // Stage kt+1 is read from here on: its request (issued two stages ago) must have landed for every
+    // wavefront.  Loads issued after its last piece: 5 of that stage, MT + 8 of the next, 6 + MT of this.
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(19 + 2 * MT) : "memory");
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(std::integral_constant<int, 3>{}, std::integral_constant<int, S0 + 3>{}, std::integral_constant<int, 1>{}, kt, nxt);
+  };
+  const int64_t nk = p.K / PK_DK;
+  int64_t kt = 0;
+  for (; kt + 1 < nk; kt += 2) {
+    stage(std::integral_constant<int, 0>{}, kt);
+    stage(std::integral_constant<int, 4>{}, kt + 1);
+  }
+  if (kt < nk) {
+    stage(std::integral_constant<int, 0>{}, kt++);
+    if (p.K % PK_DK) {  // 32 columns left: two k-steps of the next stage (its A rows are half valid)
+      const unsigned char* cur = smem + (kt & (PK_STAGES - 1)) * STG;
+      kstep(std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{}, std::integral_constant<int, 0>{}, kt, cur);
+      kstep(std::integral_constant<int, 1>{}, std::integral_constant<int, 5>{}, std::integral_constant<int, 2>{}, kt, cur);
+    }
+  } else if (p.K % PK_DK) {
+    const unsigned char* cur = smem + (kt & (PK_STAGES - 1)) * STG;
+    kstep(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, kt, cur);
+    kstep(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{}, kt, cur);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stray requests must land before LDS is reused
+
+  store_tile<BM, WN, VEC_EPI, OutT>(p, acc, smem, m0, n0, 0, wave, wave, lane, 0, 0);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -468,9 +742,92 @@ hipError_t launch_mfma_layout(GemmP& p, bool ak, bool bk, bool ktail, bool vec, 
   return launch_mfma_tail<BM, BN, false, false, OutT>(p, ktail, vec, nz, st);
 }
 
+// HIFT_GEMM_PACKED=0 in the environment keeps every contraction on the register-staged kernels
+inline bool use_packed_kernel() {
+  static const bool on = [] { const char* e = getenv("HIFT_GEMM_PACKED"); return !(e && e[0] == '0'); }();
+  return on;
+}
+
 inline bool al16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; }
 
 }  // namespace
+
+// Size in bytes of the packed copy of a B operand with N rows and K columns (zero if the shape
+// cannot be packed).
+size_t packed_b_bytes(int64_t N, int64_t K) {
+  if (N < 256 || K < 32 || K % 32 != 0) return 0;
+  return (size_t)((N + 255) / 256) * 8 * (size_t)(K / 16) * 1024;
+}
+
+hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st) {
+  if (packed_b_bytes(N, K) == 0) return hipErrorInvalidValue;
+  const int64_t n_blocks = ((N + 255) / 256) * 8, k_steps = K / 16;
+  const bf16* Bs = reinterpret_cast<const bf16*>(B);
+  u32x4* out = reinterpret_cast<u32x4*>(Bp);
+  if (al16(B) && ldb % 8 == 0) {
+    if (b_kmajor) {
+      const int ti = (int)((K + 255) / 256);
+      pack_b_tile_k<true><<<dim3((unsigned)(n_blocks * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti);
+    } else {
+      const int ti = (int)(n_blocks / 8);
+      pack_b_tile_k<false><<<dim3((unsigned)((K / 32) * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti);
+    }
+  } else {
+    const int64_t blocks = n_blocks * k_steps;
+    pack_b_k<<<dim3((unsigned)((blocks + 3) / 4)), 256, 0, st>>>(Bs, ldb, N, K, b_kmajor, out, n_blocks, k_steps);
+  }
+  return hipGetLastError();
+}
+
+constexpr int PK_MT = 4;  // 128 x 256 tiles
+
+bool packed_gemm_applies(const Gemm& g) {
+  if (g.dtype != DT_BF16 || !g.a_kmajor || g.nb * g.nh != 1 || packed_b_bytes(g.N, g.K) == 0) return false;
+  const bool vec = g.N % 8 == 0 && g.ldc % 8 == 0 && al16(g.C) && (!g.R || (g.ldr % 8 == 0 && al16(g.R))) &&
+                   (!g.bias || al16(g.bias));
+  // 32-bit byte offsets, also for the rows past the edge of the last tile and the stages requested past K
+  const bool fits = (g.M + 256) * g.lda * 2 < (int64_t(1) << 32) && al16(g.A) && g.lda % 8 == 0 &&
+                    packed_b_bytes(g.N, g.K) < (size_t(1) << 32);
+  if (!(vec && fits && use_packed_kernel())) return false;
+  return ((g.M + 32 * PK_MT - 1) / (32 * PK_MT)) * ((g.N + 255) / 256) >= 200;  // enough tiles to fill the chip
+}
+
+hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
+  if (!packed_gemm_applies(g)) return hipErrorInvalidValue;
+  GemmP p;
+  p.M = g.M; p.N = g.N; p.K = g.K;
+  p.A = g.A; p.lda = g.lda; p.B = nullptr; p.ldb = 0; p.C = g.C; p.ldc = g.ldc;
+  p.bias = g.bias; p.R = g.R; p.ldr = g.ldr;
+  p.nh = 1; p.sa1 = p.sa2 = p.sb1 = p.sb2 = p.sc1 = p.sc2 = 0;
+  constexpr int OPER = PK_STAGES * 32 * PK_MT * PK_ROW;  // ring of A stages
+  constexpr int STAGE = 4 * 64 * (64 * 4 + 16);          // fp32 epilogue staging, 4 waves
+  constexpr int LDS = STAGE > OPER ? STAGE : OPER;
+  static_assert(LDS <= 160 * 1024, "LDS of a gfx950 compute unit");
+  p.tiles_m = (int)((p.M + 32 * PK_MT - 1) / (32 * PK_MT));
+  p.tiles_n = (int)((p.N + 255) / 256);
+  const dim3 grid((unsigned)(p.tiles_m * p.tiles_n));
+  const u32x4* bp = reinterpret_cast<const u32x4*>(Bp);
+  if (g.out_f32) {
+    static bool attr_done = false;
+    auto kern = gemm_pk_k<PK_MT, true, float>;
+    if (!attr_done) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+      if (e != hipSuccess) return e;
+      attr_done = true;
+    }
+    kern<<<grid, 256, LDS, st>>>(p, bp, p.K / 16);
+  } else {
+    static bool attr_done = false;
+    auto kern = gemm_pk_k<PK_MT, true, bf16>;
+    if (!attr_done) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+      if (e != hipSuccess) return e;
+      attr_done = true;
+    }
+    kern<<<grid, 256, LDS, st>>>(p, bp, p.K / 16);
+  }
+  return hipGetLastError();
+}
 
 hipError_t gemm(const Gemm& g, hipStream_t st, int* variant) {
   if (variant) *variant = 0;

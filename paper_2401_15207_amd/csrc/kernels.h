@@ -28,6 +28,15 @@ struct Gemm {
 // variant (optional) receives which kernel ran: 0 plain FMA, 1 MFMA 128x128 tiles, 2 MFMA 256x256 tiles
 hipError_t gemm(const Gemm& g, hipStream_t st, int* variant = nullptr);
 
+// Weight operand pre-packed in MFMA fragment order (see gemm.hip).  packed_b_bytes: size of the packed
+// copy of a [N, K] operand, 0 if the shape cannot be packed.  pack_b: builds it from B given as in Gemm
+// (b_kmajor or transposed).  gemm_packed: C = A . B^T with A k-major and B packed; only for problems
+// packed_gemm_applies() accepts (g.B / g.ldb are ignored).
+size_t packed_b_bytes(int64_t N, int64_t K);
+hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st);
+bool packed_gemm_applies(const Gemm& g);
+hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st);
+
 // ---- row-wise and elementwise kernels ------------------------------------------------------
 hipError_t embed_fwd(int dt, const int32_t* tokens, int64_t T, int S, int d, int V,
                      const void* tok_emb, const void* pos_emb, void* x, hipStream_t st);

@@ -47,6 +47,9 @@ struct Tensor {
   std::string name;
   int unit, kind;
   int64_t off, rows, cols;
+  // byte offsets of the copies in MFMA fragment order inside the packed-weight arena, or -1:
+  // pk_fwd packs w as [rows, cols] (forward, y = x . w^T), pk_bwd packs w^T (dX = dY . w)
+  int64_t pk_fwd = -1, pk_bwd = -1;
   int64_t count() const { return rows * cols; }
 };
 
@@ -219,6 +222,8 @@ struct hift_model {
   // device memory
   float* master = nullptr;
   void* wc = nullptr;  // weights the forward uses: bf16 copy, or the master itself in fp32 mode
+  unsigned char* wpk = nullptr;  // copies of the large bf16 matrices in MFMA fragment order
+  size_t wpk_bytes = 0;
   float* grad = nullptr;
   float* state_full = nullptr;  // [n_state][n_params] when state stays in HBM
   float* slot[2] = {nullptr, nullptr};  // [n_state][grad_cap] each when state lives on the host
@@ -269,6 +274,7 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes) {
   Bump b(dev);
   M.master = (float*)b.take(np * 4);
   M.wc = M.dt == DT_BF16 ? b.take(np * 2) : (void*)M.master;
+  M.wpk = M.wpk_bytes ? (unsigned char*)b.take(M.wpk_bytes) : nullptr;
   M.grad = (float*)b.take(M.grad_cap * 4);
   if (M.n_state > 0) {
     if (M.on_host) {
@@ -349,12 +355,48 @@ hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_o
   M->grad_cap = (largest_group(M->lay, m) + 63) & ~(int64_t)63;
   M->n_state = n_state_of(*opt);
   M->on_host = cfg->state_on_host != 0;
+  // Which matrices get copies in fragment order: those whose contraction, at the largest batch,
+  // is one the packed-operand kernel takes.
+  M->wpk_bytes = 0;
+  for (Tensor& t : M->lay.t) {
+    if (t.kind != HIFT_KIND_MATRIX || t.unit == 0 || M->dt != DT_BF16) continue;
+    const int64_t rows = (cfg->arch == HIFT_ARCH_POSTLN_ENCODER && t.unit == M->lay.n_units - 1) ? max_batch : M->maxT;
+    Gemm g;
+    g.dtype = DT_BF16;
+    g.M = rows; g.N = t.rows; g.K = t.cols; g.lda = t.cols; g.ldc = t.rows; g.ldr = t.rows;
+    if (packed_gemm_applies(g)) {
+      t.pk_fwd = (int64_t)M->wpk_bytes;
+      M->wpk_bytes += (packed_b_bytes(t.rows, t.cols) + 255) & ~(size_t)255;
+    }
+    g.N = t.cols; g.K = t.rows; g.lda = t.rows; g.ldc = t.cols; g.ldr = t.cols;
+    if (packed_gemm_applies(g)) {
+      t.pk_bwd = (int64_t)M->wpk_bytes;
+      M->wpk_bytes += (packed_b_bytes(t.cols, t.rows) + 255) & ~(size_t)255;
+    }
+  }
   return HIFT_OK;
 }
 
+// Rebuilds the fragment-order copies of the matrices of units [ulo, uhi) from the bf16 weights.
+hipError_t repack_units(hift_model* M, int ulo, int uhi) {
+  if (!M->wpk) return hipSuccess;
+  for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
+    const Tensor& t = M->lay.t[i];
+    if (t.pk_fwd >= 0) {
+      hipError_t e = pack_b(M->W(t), t.cols, t.rows, t.cols, true, M->wpk + t.pk_fwd, M->cs);
+      if (e != hipSuccess) return e;
+    }
+    if (t.pk_bwd >= 0) {
+      hipError_t e = pack_b(M->W(t), t.cols, t.cols, t.rows, false, M->wpk + t.pk_bwd, M->cs);
+      if (e != hipSuccess) return e;
+    }
+  }
+  return hipSuccess;
+}
+
 // ---- profiling of kernel classes (events around launches) ---------------------------------
-// CAT_GEMM: forward linear layers on 256x256 tiles (the dominant kernel instantiation);
-// CAT_GEMM_REST: every other linear-layer contraction (128x128 tiles, dX, dW)
+// CAT_GEMM: linear layers (forward and dX) on the packed-operand kernel (the dominant kernel);
+// CAT_GEMM_REST: every other linear-layer contraction (dW, small shapes, fp32)
 enum { CAT_GEMM = 0, CAT_ATTN = 1, CAT_ELEM = 2, CAT_OPT = 3, CAT_GEMM_REST = 4, CAT_N = 5 };
 
 struct Scope {
@@ -398,9 +440,12 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
   g.bias = bias ? M->W(*bias) : nullptr;
   g.R = R; g.ldr = w.rows;
   Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
-  int variant = 0;
-  K_TRY(gemm(g, M->cs, &variant));
-  if (sc.r && variant != 2) sc.r->cat = CAT_GEMM_REST;
+  if (w.pk_fwd >= 0 && packed_gemm_applies(g)) {
+    K_TRY(gemm_packed(g, M->wpk + w.pk_fwd, M->cs));
+    return HIFT_OK;
+  }
+  if (sc.r) sc.r->cat = CAT_GEMM_REST;
+  K_TRY(gemm(g, M->cs));
   return HIFT_OK;
 }
 
@@ -413,7 +458,12 @@ hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor&
   g.B = M->W(w); g.ldb = w.cols; g.b_kmajor = false;
   g.C = dx; g.ldc = w.cols;
   g.R = R; g.ldr = w.cols;
-  Scope sc(M, CAT_GEMM_REST, 2.0 * rows * w.rows * w.cols);
+  Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
+  if (w.pk_bwd >= 0 && packed_gemm_applies(g)) {
+    K_TRY(gemm_packed(g, M->wpk + w.pk_bwd, M->cs));
+    return HIFT_OK;
+  }
+  if (sc.r) sc.r->cat = CAT_GEMM_REST;
   K_TRY(gemm(g, M->cs));
   return HIFT_OK;
 }
@@ -988,6 +1038,7 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
     CR_TRY(fill_zero(M->master, (size_t)M->lay.n_params * 4, M->cs));
   }
   if (M->dt == DT_BF16) CR_TRY(cast_f32_to(DT_BF16, M->lay.n_params, M->master, M->wc, M->cs));
+  CR_TRY(repack_units(M, 0, M->lay.n_units));
   CR_TRY(hipStreamSynchronize(M->cs));
 #undef CR_TRY
   *out = M;
@@ -1128,12 +1179,19 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
                              (s2b && M->n_state == 2) ? s2b + (t.off - sbase) : nullptr, cc, M->cs));
     }
   }
+  if (moving) HIP_TRY(hipEventRecord(M->ev_opt[s], M->cs));
+  if (M->wpk) {  // the updated matrices in fragment order, for the next forward and dX
+    double bytes = 0;
+    for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i)
+      bytes += 4.0 * M->lay.t[i].count() * ((M->lay.t[i].pk_fwd >= 0) + (M->lay.t[i].pk_bwd >= 0));
+    Scope sc(M, CAT_ELEM, bytes);
+    K_TRY(repack_units(M, ulo, uhi));
+  }
   HIP_TRY(hipEventRecord(M->ev_t1, M->cs));
   M->timed = true;
 
   // ---- state back to the host (Algorithm 1 step k) ----
   if (moving) {
-    HIP_TRY(hipEventRecord(M->ev_opt[s], M->cs));
     HIP_TRY(hipStreamWaitEvent(M->ds, M->ev_opt[s], 0));
     for (int j = 0; j < M->n_state; ++j) {
       ST_TRY(state_copy(M, M->host_state + (size_t)j * M->lay.n_params + plo, M->slot[s] + (size_t)j * M->grad_cap,
@@ -1182,6 +1240,7 @@ hift_status hift_write_params(hift_model* M, int32_t ulo, int32_t uhi, const flo
   HIP_TRY(hipMemcpy(M->master + off, src, (size_t)cnt * 4, hipMemcpyHostToDevice));
   if (M->dt == DT_BF16) {
     HIP_TRY(cast_f32_to(DT_BF16, cnt, M->master + off, (unsigned char*)M->wc + off * 2, M->cs));
+    HIP_TRY(repack_units(M, ulo, uhi));
     HIP_TRY(hipStreamSynchronize(M->cs));
   }
   return HIFT_OK;
@@ -1272,6 +1331,34 @@ hift_status hift_kernel_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, 
   g.bias = bias; g.R = R; g.ldr = ldc;
   g.nb = batch; g.nh = 1; g.sa1 = sa; g.sb1 = sb; g.sc1 = sc;
   HIP_TRY(gemm(g, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_packed_bytes(int64_t N, int64_t K, size_t* bytes) {
+  if (!bytes || N < 0 || K < 0) return fail(HIFT_EINVAL, "bad argument");
+  *bytes = packed_b_bytes(N, K);
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_pack_b(int32_t b_kmajor, int64_t N, int64_t K, const void* B, int64_t ldb, void* Bp,
+                               void* stream) {
+  if (!B || !Bp) return fail(HIFT_EINVAL, "null operand");
+  if (packed_b_bytes(N, K) == 0) return fail(HIFT_EINVAL, "shape cannot be packed (N >= 256, K a multiple of 32)");
+  HIP_TRY(pack_b(B, ldb, N, K, b_kmajor != 0, Bp, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_gemm_packed(int32_t out_f32, int64_t Mm, int64_t N, int64_t K, const void* A, int64_t lda,
+                                    const void* Bp, void* C, int64_t ldc, const void* bias, const void* R,
+                                    void* stream) {
+  if (!A || !Bp || !C) return fail(HIFT_EINVAL, "null operand");
+  Gemm g;
+  g.dtype = DT_BF16;
+  g.out_f32 = out_f32 != 0;
+  g.M = Mm; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.C = C; g.ldc = ldc; g.bias = bias; g.R = R; g.ldr = ldc;
+  if (!packed_gemm_applies(g)) return fail(HIFT_EINVAL, "problem is not one the packed-operand kernel takes");
+  HIP_TRY(gemm_packed(g, Bp, (hipStream_t)stream));
   return HIFT_OK;
 }
 

@@ -25,6 +25,8 @@ def _dev(x, bf16):
 CASES = [  # M, N, K  (several tiles + ragged tails; K not a multiple of 64; tiny)
     (256, 256, 64), (512, 768, 256), (384, 640, 192), (136, 72, 40), (1000, 264, 520), (8, 3, 64), (64, 64, 8),
     (2048, 512, 128), (300, 200, 100),
+    # enough 256x256 tiles to take the large-tile kernels (k-major pair: the direct-to-LDS kernel)
+    (2048, 8192, 96), (2000, 8200, 160), (1800, 7944, 64),
 ]
 
 
@@ -78,6 +80,64 @@ def test_gemm_batched_strided_bf16():
     ref = np.einsum("bmk,bnk->bmn", A.astype(np.float64), B.astype(np.float64))
     got = dC.float().cpu().numpy()
     assert np.all(np.abs(got - ref) <= 2 ** -8 * (np.abs(ref) + 0.2))
+
+
+@pytest.mark.parametrize("bk", [1, 0], ids=["w_kmajor", "w_transposed"])
+@pytest.mark.parametrize("M,N,K", [(2048, 8192, 96), (2000, 8200, 160), (1800, 7944, 64), (2048, 12288, 4096),
+                                   (2048, 4096, 352), (1990, 3592, 96)])
+def test_gemm_with_packed_weight_operand(M, N, K, bk):
+    import torch
+    import paper_2401_15207_amd as H
+    rng = np.random.default_rng(M + N + K + bk)
+    A = _bf16_round(rng.standard_normal((M, K)))
+    B = _bf16_round(rng.standard_normal((N, K)) * 0.5)
+    bias = _bf16_round(rng.standard_normal(N))
+    R = _bf16_round(rng.standard_normal((M, N)))
+    ref = A.astype(np.float64) @ B.astype(np.float64).T + bias + R
+    nbytes = H.kernel_packed_bytes(N, K)
+    assert nbytes == ((N + 255) // 256) * 256 * K * 2
+    dBp = torch.full((nbytes // 2,), float("nan"), dtype=torch.bfloat16, device="cuda")   # every block must be written
+    dB = _dev(B if bk else B.T, True)
+    H.kernel_pack_b(bk, N, K, dB, K if bk else N, dBp)
+    dA = _dev(A, True)
+    for out_f32 in (0, 1):
+        dC = torch.zeros((M, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device="cuda")
+        H.kernel_gemm_packed(out_f32, M, N, K, dA, K, dBp, dC, N, _dev(bias, True), _dev(R, not out_f32))
+        torch.cuda.synchronize()
+        got = dC.float().cpu().numpy().astype(np.float64)
+        scale = np.sqrt(K) + 1.0
+        tol = (1e-5 if out_f32 else 2 ** -8) * (np.abs(ref) + (scale if out_f32 else 0.02 * scale))
+        bad = np.abs(got - ref) > tol
+        assert not bad.any(), (out_f32, int(bad.sum()), float(np.max(np.abs(got - ref))))
+
+
+@pytest.mark.parametrize("bk", [1, 0], ids=["w_kmajor", "w_transposed"])
+def test_pack_of_unaligned_source_matches_aligned(bk):
+    """The fragment-order copy is a pure permutation (plus zero rows up to a multiple of 256): the
+    packer for sources without 16-byte alignment must write the same bytes as the tiled one."""
+    import torch
+    import paper_2401_15207_amd as H
+    N, K = 1000, 96
+    rng = np.random.default_rng(bk)
+    B = _bf16_round(rng.standard_normal((N, K)))
+    src = B if bk else B.T
+    rows, cols = src.shape
+    nbytes = H.kernel_packed_bytes(N, K)
+    p1 = torch.full((nbytes // 2,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    p2 = torch.full((nbytes // 2,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    H.kernel_pack_b(bk, N, K, _dev(src, True), cols, p1)
+    wide = torch.zeros((rows, cols + 3), dtype=torch.bfloat16, device="cuda")   # odd leading dimension
+    wide[:, :cols] = _dev(src, True)
+    H.kernel_pack_b(bk, N, K, wide, cols + 3, p2)
+    torch.cuda.synchronize()
+    a, b = p1.view(torch.int16).cpu().numpy(), p2.view(torch.int16).cpu().numpy()
+    assert np.array_equal(a, b)
+    # block (nb, kk), lane l, element e  <-  B[nb*32 + l%32][kk*16 + (l/32)*8 + e]
+    blk = a.view(np.uint16).reshape(-1, K // 16, 64, 8)
+    want = np.zeros((blk.shape[0] * 32, K), np.float32)
+    want[:N] = B
+    want = want.reshape(-1, 32, K // 16, 2, 8).transpose(0, 2, 3, 1, 4).reshape(blk.shape)
+    assert np.array_equal((blk.astype(np.uint32) << 16).view(np.float32), want)
 
 
 def test_gemm_empty():
