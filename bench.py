@@ -231,6 +231,7 @@ def main():
     n_el, ms_el, _ = model.profile_read(2)
     n_opt, ms_opt, by_opt = model.profile_read(3)
     n_rest, ms_rest, fl_rest = model.profile_read(4)
+    n_pack, ms_pack, by_pack = model.profile_read(5)
     model.profile_enable(False)
     # exposed copy time and loss of one more step
     t += 1
@@ -263,11 +264,13 @@ def main():
             "linear_gemm_packed": ms_gemm / max(a.steps, 1), "linear_gemm_other": ms_rest / max(a.steps, 1),
             "attention_gemm": ms_att / max(a.steps, 1),
             "rowwise_elementwise": ms_el / max(a.steps, 1), "optimizer": ms_opt / max(a.steps, 1),
+            "weight_repack": ms_pack / max(a.steps, 1),
         },
         "linear_gemm_all_tflops": (fl_gemm + fl_rest) / ((ms_gemm + ms_rest) * 1e-3) / 1e12 if ms_gemm + ms_rest > 0 else 0.0,
         "linear_gemm_other_tflops": fl_rest / (ms_rest * 1e-3) / 1e12 if ms_rest > 0 else 0.0,
         "attention_gemm_tflops": fl_att / (ms_att * 1e-3) / 1e12 if ms_att > 0 else 0.0,
         "optimizer_gbps": by_opt / (ms_opt * 1e-3) / 1e9 if ms_opt > 0 else 0.0,
+        "weight_repack_gbps": by_pack / (ms_pack * 1e-3) / 1e9 if ms_pack > 0 else 0.0,
         "state_copy_gb_per_step": {"h2d": (h2d1 - h2d0) / 1e9 / max(a.steps, 1), "d2h": (d2h1 - d2h0) / 1e9 / max(a.steps, 1)},
         "exposed_state_copy_ms_last_step": exposed,
         "state_copy_engine": "copy kernel, %d workgroups" % a.copy_blocks if a.copy_engine == 1 else "hipMemcpyAsync",

@@ -207,10 +207,11 @@ hift_status hift_set_state_copy_engine(hift_model* mdl, int32_t engine, int32_t 
 /* Kernel-class timing for roofline reports.  While enabled, every kernel launch of hift_step is
  * bracketed by HIP events on the compute stream.  hift_profile_read sums, for one class
  * (0 linear-layer contractions, forward and dX, that run on the packed-operand kernel,
- * 1 attention contractions, 2 row-wise/elementwise kernels including the re-packing of updated
- * weights, 3 optimizer, 4 all other linear-layer contractions: dW, small or unaligned shapes,
- * fp32), the launches since hift_profile_enable, their milliseconds, and
- * their algorithmic work (flops for classes 0, 1 and 4, bytes for class 3, 0 for class 2). */
+ * 1 attention contractions, 2 row-wise/elementwise kernels, 3 optimizer, 4 all other
+ * linear-layer contractions: dW, small or unaligned shapes, fp32, 5 the re-packing of the updated
+ * weights; one entry of class 3 or 5 covers all launches of one step), the launches since
+ * hift_profile_enable, their milliseconds, and their algorithmic work (flops for classes 0, 1
+ * and 4, bytes for classes 3 and 5, 0 for class 2). */
 hift_status hift_profile_enable(hift_model* mdl, int32_t on);
 hift_status hift_profile_read(hift_model* mdl, int32_t category, int64_t* launches, double* total_ms,
                               double* work);

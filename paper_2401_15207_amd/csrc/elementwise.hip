@@ -349,6 +349,86 @@ __global__ void __launch_bounds__(BLK) softmax_bwd_k(int64_t rows, int S, float 
   for (int j = lane; j < S; j += 64) dr[j] = from_f32<T>(scale * to_f32(pr[j]) * (to_f32(dr[j]) - dot));
 }
 
+// Row held in registers: lane l owns elements [c*64*V + l*V, +V) of chunk c; one read and one write
+// of the row, one exponential per element.  S must be a multiple of V and at most NCH*64*V.
+template <typename T, int V, int NCH>
+__global__ void __launch_bounds__(BLK) softmax_fwd_reg_k(int64_t rows, int S, float scale, bool causal, T* __restrict__ s) {
+  const int64_t row = (int64_t)blockIdx.x * (BLK / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const int n = causal ? (int)(row % S) + 1 : S;
+  T* sr = s + row * S;
+  float v[NCH][V];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int j0 = (c * 64 + lane) * V;
+    if (j0 < n) {
+      ldv<T, V>(sr + j0, v[c]);
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        v[c][e] = j0 + e < n ? v[c][e] * scale : -INFINITY;
+        mx = fmaxf(mx, v[c][e]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < V; ++e) v[c][e] = -INFINITY;
+    }
+  }
+  mx = wave_max(mx);
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c)
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      v[c][e] = expf(v[c][e] - mx);  // exp(-inf) = 0 for the masked tail
+      sum += v[c][e];
+    }
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int j0 = (c * 64 + lane) * V;
+    if (j0 < S) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) v[c][e] *= inv;
+      stv<T, V>(sr + j0, v[c]);
+    }
+  }
+}
+
+template <typename T, int V, int NCH>
+__global__ void __launch_bounds__(BLK) softmax_bwd_reg_k(int64_t rows, int S, float scale, const T* __restrict__ p,
+                                                          T* __restrict__ dp) {
+  const int64_t row = (int64_t)blockIdx.x * (BLK / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const T* pr = p + row * S;
+  T* dr = dp + row * S;
+  float pv[NCH][V], dv[NCH][V];
+  float dot = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int j0 = (c * 64 + lane) * V;
+    if (j0 < S) {
+      ldv<T, V>(pr + j0, pv[c]);
+      ldv<T, V>(dr + j0, dv[c]);
+#pragma unroll
+      for (int e = 0; e < V; ++e) dot += pv[c][e] * dv[c][e];
+    }
+  }
+  dot = wave_sum(dot);
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int j0 = (c * 64 + lane) * V;
+    if (j0 < S) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) dv[c][e] = scale * pv[c][e] * (dv[c][e] - dot);
+      stv<T, V>(dr + j0, dv[c]);
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------- cross-entropy
 // scratch layout: row_loss[0..rows) per-row losses, row_loss[rows] = number of rows with a target.
 __global__ void __launch_bounds__(BLK) ce_count_k(int64_t rows, const int32_t* __restrict__ labels,
@@ -667,16 +747,40 @@ hipError_t softmax_fwd(int dt, int64_t nbh, int S, float scale, bool causal, voi
   const int64_t rows = nbh * S;
   if (rows == 0) return hipSuccess;
   const dim3 grid((unsigned)cdiv(rows, BLK / 64));
-  if (dt == DT_F32) softmax_fwd_k<float><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (float*)s);
-  else softmax_fwd_k<bf16><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (bf16*)s);
+#define SM_REG(T, V)                                                                                              \
+  if (S % (V) == 0 && aligned16(s)) {                                                                             \
+    if (S <= 64 * (V)) { softmax_fwd_reg_k<T, V, 1><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (T*)s); LAUNCH_CHECK(); }  \
+    if (S <= 128 * (V)) { softmax_fwd_reg_k<T, V, 2><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (T*)s); LAUNCH_CHECK(); } \
+    if (S <= 256 * (V)) { softmax_fwd_reg_k<T, V, 4><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (T*)s); LAUNCH_CHECK(); } \
+  }
+  if (dt == DT_F32) {
+    SM_REG(float, 4)
+    softmax_fwd_k<float><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (float*)s);
+  } else {
+    SM_REG(bf16, 8)
+    softmax_fwd_k<bf16><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (bf16*)s);
+  }
+#undef SM_REG
   LAUNCH_CHECK();
 }
 hipError_t softmax_bwd(int dt, int64_t nbh, int S, float scale, const void* p, void* dp, hipStream_t st) {
   const int64_t rows = nbh * S;
   if (rows == 0) return hipSuccess;
   const dim3 grid((unsigned)cdiv(rows, BLK / 64));
-  if (dt == DT_F32) softmax_bwd_k<float><<<grid, BLK, 0, st>>>(rows, S, scale, (const float*)p, (float*)dp);
-  else softmax_bwd_k<bf16><<<grid, BLK, 0, st>>>(rows, S, scale, (const bf16*)p, (bf16*)dp);
+#define SM_REG(T, V)                                                                                                        \
+  if (S % (V) == 0 && aligned16(p) && aligned16(dp)) {                                                                      \
+    if (S <= 64 * (V)) { softmax_bwd_reg_k<T, V, 1><<<grid, BLK, 0, st>>>(rows, S, scale, (const T*)p, (T*)dp); LAUNCH_CHECK(); }  \
+    if (S <= 128 * (V)) { softmax_bwd_reg_k<T, V, 2><<<grid, BLK, 0, st>>>(rows, S, scale, (const T*)p, (T*)dp); LAUNCH_CHECK(); } \
+    if (S <= 256 * (V)) { softmax_bwd_reg_k<T, V, 4><<<grid, BLK, 0, st>>>(rows, S, scale, (const T*)p, (T*)dp); LAUNCH_CHECK(); } \
+  }
+  if (dt == DT_F32) {
+    SM_REG(float, 4)
+    softmax_bwd_k<float><<<grid, BLK, 0, st>>>(rows, S, scale, (const float*)p, (float*)dp);
+  } else {
+    SM_REG(bf16, 8)
+    softmax_bwd_k<bf16><<<grid, BLK, 0, st>>>(rows, S, scale, (const bf16*)p, (bf16*)dp);
+  }
+#undef SM_REG
   LAUNCH_CHECK();
 }
 

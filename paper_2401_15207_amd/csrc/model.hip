@@ -397,7 +397,7 @@ hipError_t repack_units(hift_model* M, int ulo, int uhi) {
 // ---- profiling of kernel classes (events around launches) ---------------------------------
 // CAT_GEMM: linear layers (forward and dX) on the packed-operand kernel (the dominant kernel);
 // CAT_GEMM_REST: every other linear-layer contraction (dW, small shapes, fp32)
-enum { CAT_GEMM = 0, CAT_ATTN = 1, CAT_ELEM = 2, CAT_OPT = 3, CAT_GEMM_REST = 4, CAT_N = 5 };
+enum { CAT_GEMM = 0, CAT_ATTN = 1, CAT_ELEM = 2, CAT_OPT = 3, CAT_GEMM_REST = 4, CAT_PACK = 5, CAT_N = 6 };
 
 struct Scope {
   hift_model* M;
@@ -1184,7 +1184,7 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
     double bytes = 0;
     for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i)
       bytes += 4.0 * M->lay.t[i].count() * ((M->lay.t[i].pk_fwd >= 0) + (M->lay.t[i].pk_bwd >= 0));
-    Scope sc(M, CAT_ELEM, bytes);
+    Scope sc(M, CAT_PACK, bytes);
     K_TRY(repack_units(M, ulo, uhi));
   }
   HIP_TRY(hipEventRecord(M->ev_t1, M->cs));
