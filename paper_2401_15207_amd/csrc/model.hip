@@ -209,6 +209,8 @@ struct Prof {
 
 }  // namespace
 
+constexpr int NSLOT = 3;
+
 struct hift_model {
   hift_config cfg;
   hift_opt opt;
@@ -226,7 +228,10 @@ struct hift_model {
   size_t wpk_bytes = 0;
   float* grad = nullptr;
   float* state_full = nullptr;  // [n_state][n_params] when state stays in HBM
-  float* slot[2] = {nullptr, nullptr};  // [n_state][grad_cap] each when state lives on the host
+  // State of the active group when the rest lives on the host: [n_state][grad_cap] each.  Three slots:
+  // while one is updated, the next group's state arrives in the second and the previous group's
+  // drains from the third, so the two directions of the host link run at the same time.
+  float* slot[NSLOT] = {nullptr, nullptr, nullptr};
   float* host_state = nullptr;          // pinned [n_state][n_params]
   float* cos_sin = nullptr;
   std::vector<void*> xs;  // residual stream: xs[l] enters layer l, xs[L] enters the head
@@ -237,11 +242,11 @@ struct hift_model {
        *dcls = nullptr;
   // streams and events
   hipStream_t cs, hs, ds;
-  hipEvent_t ev_h2d[2], ev_opt[2], ev_d2h[2], ev_t0, ev_t1, ev_w0, ev_w1;
-  bool d2h_pending[2] = {false, false};
+  hipEvent_t ev_h2d[NSLOT], ev_opt[NSLOT], ev_d2h[NSLOT], ev_t0, ev_t1, ev_w0, ev_w1;
+  bool d2h_pending[NSLOT] = {false, false, false};
   int h2d_last = -1;            // slot of the most recent host-to-device transfer
-  int d2h_group[2] = {-1, -1};  // group whose state the pending write-back of a slot carries
-  int slot_group[2] = {-1, -1};  // group whose state a slot holds (arrived or in flight)
+  int d2h_group[NSLOT] = {-1, -1, -1};  // group whose state the pending write-back of a slot carries
+  int slot_group[NSLOT] = {-1, -1, -1};  // group whose state a slot holds (arrived or in flight)
   int cur_slot = 0;
   // schedule
   int m = 0, k = 0;
@@ -278,8 +283,7 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes) {
   M.grad = (float*)b.take(M.grad_cap * 4);
   if (M.n_state > 0) {
     if (M.on_host) {
-      M.slot[0] = (float*)b.take((size_t)M.n_state * M.grad_cap * 4);
-      M.slot[1] = (float*)b.take((size_t)M.n_state * M.grad_cap * 4);
+      for (auto& sl : M.slot) sl = (float*)b.take((size_t)M.n_state * M.grad_cap * 4);
     } else {
       M.state_full = (float*)b.take((size_t)M.n_state * np * 4);
     }
@@ -881,7 +885,7 @@ hift_status fetch_state(hift_model* M, int gid, int s) {
   group_range(M, gid, &ulo, &uhi, &plo, &cnt);
   // order the copy after the write-backs it depends on, and only those: the one that last
   // drained this slot, and one that carries this group's own state to the host
-  for (int q = 0; q < 2; ++q)
+  for (int q = 0; q < NSLOT; ++q)
     if (M->d2h_pending[q] && (q == s || M->d2h_group[q] == gid)) HIP_TRY(hipStreamWaitEvent(M->hs, M->ev_d2h[q], 0));
   // keep one host-to-device transfer outstanding at the moment the next is submitted: the host
   // runs up to a step ahead of the GPU, and a copy submitted while the copy engine still has
@@ -902,7 +906,7 @@ hift_status sync_all(hift_model* M) {
   HIP_TRY(hipStreamSynchronize(M->cs));
   HIP_TRY(hipStreamSynchronize(M->hs));
   HIP_TRY(hipStreamSynchronize(M->ds));
-  M->d2h_pending[0] = M->d2h_pending[1] = false;
+  for (bool& b : M->d2h_pending) b = false;
   return HIFT_OK;
 }
 
@@ -1006,7 +1010,8 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
       return bail(HIFT_EDEVICE);                                                                      \
     }                                                                                                 \
   } while (0)
-  hipEvent_t* evs[] = {&M->ev_h2d[0], &M->ev_h2d[1], &M->ev_opt[0], &M->ev_opt[1], &M->ev_d2h[0], &M->ev_d2h[1]};
+  std::vector<hipEvent_t*> evs;
+  for (int q = 0; q < NSLOT; ++q) { evs.push_back(&M->ev_h2d[q]); evs.push_back(&M->ev_opt[q]); evs.push_back(&M->ev_d2h[q]); }
   for (auto e : evs) *e = nullptr;
   M->ev_t0 = M->ev_t1 = M->ev_w0 = M->ev_w1 = nullptr;
   for (auto e : evs) CR_TRY(hipEventCreateWithFlags(e, hipEventDisableTiming));
@@ -1017,7 +1022,7 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
   if (M->host_state) memset(M->host_state, 0, need_pin);
   // state and gradient buffers start at zero
   if (M->state_full) CR_TRY(fill_zero(M->state_full, (size_t)M->n_state * M->lay.n_params * 4, M->cs));
-  for (int q = 0; q < 2; ++q)
+  for (int q = 0; q < NSLOT; ++q)
     if (M->slot[q]) CR_TRY(fill_zero(M->slot[q], (size_t)M->n_state * M->grad_cap * 4, M->cs));
   CR_TRY(fill_zero(M->grad, (size_t)M->grad_cap * 4, M->cs));
   if (M->cos_sin) {
@@ -1050,7 +1055,7 @@ void hift_model_destroy(hift_model* M) {
   if (M->cs) (void)hipStreamSynchronize(M->cs);
   if (M->hs) (void)hipStreamSynchronize(M->hs);
   if (M->ds) (void)hipStreamSynchronize(M->ds);
-  hipEvent_t evs[] = {M->ev_h2d[0], M->ev_h2d[1], M->ev_opt[0], M->ev_opt[1], M->ev_d2h[0], M->ev_d2h[1],
+  hipEvent_t evs[] = {M->ev_h2d[0], M->ev_h2d[1], M->ev_h2d[2], M->ev_opt[0], M->ev_opt[1], M->ev_opt[2], M->ev_d2h[0], M->ev_d2h[1], M->ev_d2h[2],
                       M->ev_t0, M->ev_t1, M->ev_w0, M->ev_w1};
   for (auto e : evs)
     if (e) (void)hipEventDestroy(e);
@@ -1070,7 +1075,7 @@ hift_status hift_set_group_schedule(hift_model* M, hift_strategy s, int32_t m, u
   hift_status st = sync_all(M);
   if (st != HIFT_OK) return st;
   // state held in a slot is already mirrored on the host (every step writes it back)
-  M->slot_group[0] = M->slot_group[1] = -1;
+  for (int& g : M->slot_group) g = -1;
   M->m = m;
   M->k = group_count(M->lay.n_units, m);
   M->order.resize(M->k);
@@ -1129,20 +1134,24 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
   // ---- state movement, queued ahead of the compute (Algorithm 1 step i, issued early) ----
   int s = 0;
   if (moving) {
-    if (M->slot_group[M->cur_slot] == gid) s = M->cur_slot;
-    else if (M->slot_group[M->cur_slot ^ 1] == gid) s = M->cur_slot ^ 1;
-    else {
+    s = -1;
+    for (int q = 0; q < NSLOT; ++q)
+      if (M->slot_group[q] == gid) s = q;
+    if (s < 0) {
       s = M->cur_slot;
       ST_TRY(fetch_state(M, gid, s));
     }
     // a slot reused without a new fetch may still be draining to the host from its last update
     if (M->d2h_pending[s]) HIP_TRY(hipStreamWaitEvent(M->cs, M->ev_d2h[s], 0));
     M->cur_slot = s;
-    // prefetch the state of the group the schedule visits next into the other slot; the
-    // write-back that last used that slot is ordered before it inside fetch_state
+    // prefetch the state of the group the schedule visits next into the slot after this one (the
+    // one after that is still draining the previous group's state); the write-back that last used
+    // the slot is ordered before the copy inside fetch_state
     const int next = M->order[(M->t + 1) % M->k];
     const bool on_schedule = M->order[M->t % M->k] == gid;
-    if (on_schedule && next != gid && M->slot_group[s ^ 1] != next) ST_TRY(fetch_state(M, next, s ^ 1));
+    bool resident = false;
+    for (int q = 0; q < NSLOT; ++q) resident = resident || M->slot_group[q] == next;
+    if (on_schedule && !resident) ST_TRY(fetch_state(M, next, (s + 1) % NSLOT));
   }
 
   ST_TRY(forward(M, bt));
@@ -1201,7 +1210,7 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
     HIP_TRY(hipEventRecord(M->ev_d2h[s], M->ds));
     M->d2h_pending[s] = true;
     M->d2h_group[s] = gid;
-    M->cur_slot = s ^ 1;
+    M->cur_slot = (s + 1) % NSLOT;
   }
   M->t += 1;
   if (loss_out) {

@@ -62,7 +62,7 @@ def test_arena_sizes(H):
     d_host, p_host = H.query_bytes(dict(cfg, state_on_host=1), wl["opt"], 1, 4, 512)
     d_res, p_res = H.query_bytes(dict(cfg, state_on_host=0), wl["opt"], 1, 4, 512)
     assert p_res == 0 and p_host == 2 * 4 * n                       # AdamW: m and v of every parameter
-    assert d_res - d_host >= 2 * 4 * (n - 2 * big) - 4096            # two slots instead of all state
+    assert d_res - d_host >= 2 * 4 * (n - 3 * big) - 4096            # three slots (in use, arriving, draining) instead of all state
     sgd = dict(kind="sgd", lr=0.1, momentum=0.0, weight_decay=0.0)
     _d, p = H.query_bytes(dict(cfg, state_on_host=1), sgd, 1, 4, 512)
     assert p == 0                                                    # plain SGD keeps no state
