@@ -164,6 +164,10 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--copy-engine", type=int, default=0, help="0 hipMemcpyAsync, 1 small-grid copy kernel")
     ap.add_argument("--copy-blocks", type=int, default=16)
+    ap.add_argument("--master-on-host", action="store_true",
+                    help="park the fp32 master of inactive groups in pinned memory too (small-memory mode)")
+    ap.add_argument("--no-packed-copies", action="store_true",
+                    help="do not keep the fragment-order weight copies (small-memory mode; slower contractions)")
     ap.add_argument("--kernel-bench", type=int, default=0, metavar="REPS",
                     help="time the contraction kernel alone at the 7B shapes, REPS launches each, and exit")
     a = ap.parse_args()
@@ -184,7 +188,9 @@ def main():
     cfg = model_config(wl)
     B, S = wl["batch"], wl["seq"]
     t_setup = time.perf_counter()
-    model = H.HiftModel(cfg, wl["opt"], wl["m"], B, S, init_params=None, state_on_host=1)
+    model = H.HiftModel(cfg, wl["opt"], wl["m"], B, S, init_params=None, state_on_host=1,
+                        master_on_host=int(a.master_on_host), no_packed_copies=int(a.no_packed_copies))
+    mem = model.memory()
     model.set_state_copy_engine(a.copy_engine, a.copy_blocks)
     fill_weights(model, cfg, a.seed)
     k = model.set_group_schedule(wl["strategy"], wl["m"], a.seed)
@@ -277,6 +283,8 @@ def main():
         "ms_per_step_with_event_brackets": 1e3 * t_prof / max(a.steps, 1),
         "last_loss": loss,
         "setup_s": setup_s,
+        "memory_gb": {kk: round(mem[kk] / 1e9, 2) for kk in ("para", "gra", "sta", "pgs", "residual", "total", "pinned_total")},
+        "memory_mode": {"master_on_host": bool(a.master_on_host), "packed_copies": not a.no_packed_copies},
     }
     if not a.no_cpu_baseline and a.workload in ("C4", "C5"):
         model.close()

@@ -80,6 +80,14 @@ typedef struct {
                             master weights (appendix "Mixing Precision", adapted mixed precision) */
   int32_t state_on_host; /* 1: optimizer state of inactive groups lives in the pinned arena and is
                             moved per step (Algorithm 1 steps i and k); 0: all state stays in HBM */
+  int32_t master_on_host; /* 1 (bf16 mode with state_on_host only): the fp32 master weights of inactive
+                            groups live in the pinned arena too and travel with the state, so that HBM
+                            holds the bf16 model plus one group's fp32 master (appendix "Mixing
+                            Precision", the adapted mixed precision); results are identical.  0: the
+                            master stays in HBM */
+  int32_t no_packed_copies; /* 1: do not keep the second and third bf16 copy of the large matrices (in
+                            MFMA fragment order, for the fast contraction kernel); the contractions
+                            then read the row-major copy.  Saves 4 bytes per parameter, costs speed */
 } hift_config;
 
 typedef struct {
@@ -124,10 +132,34 @@ hift_status hift_tensor_at(const hift_config* cfg, int32_t index, hift_tensor_in
 
 /* Sizes of the two arenas a model of this shape needs for batches of at most max_batch
  * sequences of at most max_seq tokens, grouped m units per group (the gradient buffer and the
- * two state slots are sized for the largest group). */
+ * three state slots are sized for the largest group). */
 hift_status hift_query_bytes(const hift_config* cfg, const hift_opt* opt, int32_t m,
                              int32_t max_batch, int32_t max_seq,
                              size_t* device_bytes, size_t* pinned_host_bytes);
+
+/* Where the memory goes (appendix "Memory Analysis" and the tables of appendix "Mixing Precision":
+ * #Para, #Gra, #Sta, #PGS, residual states, total).  All figures in bytes.  Host-only arithmetic,
+ * usable without a GPU.
+ *   device_*: this library's device arena by purpose.  master = fp32 weights resident in HBM (all of
+ *   them, or three group-sized slots when master_on_host); forward = the bf16 model; packed = the
+ *   fragment-order copies; grad = one fp32 buffer for the largest group; state = optimizer state in HBM
+ *   (three group-sized slots, or all of it); activations = everything the forward keeps for the
+ *   backward; workspace = backward temporaries, tables, reduction scratch.
+ *   para/gra/sta/pgs/residual/total: the same bytes in the paper's columns (para = master + forward +
+ *   packed, residual = activations + workspace).
+ *   zeta_*: the closed forms for fp32 AdamW: zeta1 = 4 bytes x parameters, zeta_fpft = 4 zeta1,
+ *   zeta_hift = (k+3)/k zeta1 (average over equal groups), zeta_hift_peak = zeta1 + 12 bytes x
+ *   parameters of the largest group; peak_trainable = parameters of the largest group. */
+typedef struct {
+  uint64_t device_master, device_forward, device_packed, device_grad, device_state, device_activations,
+      device_workspace, device_total, pinned_total;
+  uint64_t para, gra, sta, pgs, residual, total;
+  uint64_t n_params, peak_trainable;
+  int32_t k, reserved;
+  double zeta1, zeta_fpft, zeta_hift, zeta_hift_peak;
+} hift_memory;
+hift_status hift_memory_report(const hift_config* cfg, const hift_opt* opt, int32_t m, int32_t max_batch,
+                               int32_t max_seq, hift_memory* out);
 
 /* Build a model inside the caller's arenas (Algorithm 1 "Require": model M, optimizer P).
  *   init_params_host  host, fp32, canonical order, n_params values; copied.  May be NULL: all

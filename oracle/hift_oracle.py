@@ -129,6 +129,34 @@ def n_params(cfg: dict) -> int:
 
 
 # ----------------------------------------------------------------------------------------
+# memory accounting (appendix "Memory Analysis")
+# ----------------------------------------------------------------------------------------
+STATE_ARRAYS = {"adamw": 2, "adagrad": 1, "sgd": 0, "sgdm": 1}
+
+
+def memory_model(cfg: dict, m: int, state_arrays: int = 2, bytes_per: int = 4) -> dict:
+    """Bytes held by weights, gradients and optimizer state (the three terms of the appendix).
+    zeta1 = weights, zeta2 = state_arrays * zeta1, zeta3 = zeta1 (gradients of what is updated).
+    Full fine-tuning keeps all three whole; HiFT keeps the weights whole and, of the other two, only
+    the active group's share: averaged over k equal groups that is zeta1 + (zeta2 + zeta3) / k, which
+    for AdamW is (k + 3) / k * zeta1; the peak over the cycle uses the largest group instead."""
+    ur = unit_ranges(cfg)
+    n = len(ur)
+    k = n_groups(n, m)
+    P = sum(c for _o, c in ur)
+    peak = max(sum(ur[u][1] for u in group_units(n, m, j)) for j in range(k))
+    z1 = bytes_per * P
+    z2, z3 = state_arrays * z1, z1
+    return {
+        "k": k, "n_params": P, "peak_trainable": peak,
+        "zeta1": z1, "zeta_fpft": z1 + z2 + z3,
+        "zeta_hift": z1 + (z2 + z3) / k,
+        "zeta_hift_peak": z1 + (state_arrays + 1) * bytes_per * peak,
+        "delta": (z1 + z2 + z3) - (z1 + (z2 + z3) / k),
+    }
+
+
+# ----------------------------------------------------------------------------------------
 # grouping and visiting order (section 3 "Notation"; Algorithm 1 initialisation, steps c-d)
 # ----------------------------------------------------------------------------------------
 def n_groups(n: int, m: int) -> int:

@@ -30,7 +30,16 @@ class Config(C.Structure):
     _fields_ = [("arch", C.c_int32), ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("max_seq", C.c_int32), ("n_classes", C.c_int32),
                 ("norm_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32),
-                ("state_on_host", C.c_int32)]
+                ("state_on_host", C.c_int32), ("master_on_host", C.c_int32), ("no_packed_copies", C.c_int32)]
+
+
+class Memory(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in
+                ("device_master", "device_forward", "device_packed", "device_grad", "device_state",
+                 "device_activations", "device_workspace", "device_total", "pinned_total",
+                 "para", "gra", "sta", "pgs", "residual", "total", "n_params", "peak_trainable")] + \
+               [("k", C.c_int32), ("reserved", C.c_int32), ("zeta1", C.c_double), ("zeta_fpft", C.c_double),
+                ("zeta_hift", C.c_double), ("zeta_hift_peak", C.c_double)]
 
 
 class Opt(C.Structure):
@@ -56,6 +65,7 @@ _SIGS = {
     "hift_tensor_count": [_P(Config), _P(_i32), _P(_i64)],
     "hift_tensor_at": [_P(Config), _i32, _P(TensorInfo)],
     "hift_query_bytes": [_P(Config), _P(Opt), _i32, _i32, _i32, _P(_sz), _P(_sz)],
+    "hift_memory_report": [_P(Config), _P(Opt), _i32, _i32, _i32, _P(Memory)],
     "hift_model_create": [_P(Config), _P(Opt), _i32, _i32, _i32, _vp, _vp, _sz, _vp, _sz, _vp, _vp, _vp, _P(_vp)],
     "hift_set_group_schedule": [_vp, C.c_int, _i32, _u64, _P(_i32)],
     "hift_schedule_group_at": [_vp, _i64, _P(_i32)],
@@ -95,7 +105,8 @@ def _check(st):
 def make_config(cfg: dict, state_on_host: int = 0) -> Config:
     return Config(cfg["arch"], cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["d_ffn"], cfg["vocab"],
                   cfg["max_seq"], cfg.get("n_classes", 0), cfg["norm_eps"], cfg.get("rope_base", 10000.0),
-                  cfg["dtype"], cfg.get("state_on_host", state_on_host))
+                  cfg["dtype"], cfg.get("state_on_host", state_on_host), cfg.get("master_on_host", 0),
+                  cfg.get("no_packed_copies", 0))
 
 
 def make_opt(opt: dict) -> Opt:
@@ -127,6 +138,12 @@ def tensor_list(cfg: dict):
         shape = (t.rows, t.cols) if t.kind == 0 else (t.rows,)
         out.append((t.name.decode(), shape, t.kind, t.unit, t.offset))
     return out, total.value
+
+
+def memory_report(cfg: dict, opt: dict, m: int, max_batch: int, max_seq: int) -> dict:
+    c, o, out = make_config(cfg), make_opt(opt), Memory()
+    _check(lib.hift_memory_report(C.byref(c), C.byref(o), m, max_batch, max_seq, C.byref(out)))
+    return {n: getattr(out, n) for n, _t in Memory._fields_ if n != "reserved"}
 
 
 def query_bytes(cfg: dict, opt: dict, m: int, max_batch: int, max_seq: int):
@@ -187,24 +204,64 @@ def kernel_cross_entropy(dtype, rows, V, logits, labels, row_loss, loss_out, str
     _check(lib.hift_kernel_cross_entropy(dtype, rows, V, _ptr(logits), _ptr(labels), _ptr(row_loss), _ptr(loss_out), st))
 
 
+def _hip_runtime():
+    """The HIP runtime this process already uses (the one torch loaded)."""
+    with open("/proc/self/maps") as f:
+        for line in f:
+            if "libamdhip64" in line:
+                return C.CDLL(line.split()[-1])
+    raise RuntimeError("no HIP runtime is loaded")
+
+
+class _PinnedArena:
+    """Page-locked host memory of exactly the size asked for.  torch's pinned allocator rounds a
+    request up to a power of two, which for arenas of tens of GB can double the host memory used."""
+
+    def __init__(self, nbytes: int):
+        self.hip = _hip_runtime()
+        self.hip.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), C.c_size_t, C.c_uint]
+        self.hip.hipHostFree.argtypes = [C.c_void_p]
+        p = C.c_void_p()
+        err = self.hip.hipHostMalloc(C.byref(p), nbytes, 0)
+        if err != 0 or not p.value:
+            raise MemoryError(f"hipHostMalloc of {nbytes} bytes failed (error {err})")
+        self.ptr, self.nbytes = p.value, nbytes
+
+    def data_ptr(self) -> int:
+        return self.ptr
+
+    def free(self):
+        if getattr(self, "ptr", None):
+            self.hip.hipHostFree(self.ptr)
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
 class HiftModel:
     """Owns the arenas (torch tensors) and streams a hift_model lives in."""
 
     def __init__(self, cfg: dict, opt: dict, m: int, max_batch: int, max_seq: int, init_params=None,
-                 state_on_host: int = 0, device: str = "cuda:0"):
+                 state_on_host: int = 0, device: str = "cuda:0", master_on_host: int = 0, no_packed_copies: int = 0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("HiftModel needs a GPU: there is no CPU path")
         self.torch = torch
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
-        self.cfg = dict(cfg, state_on_host=state_on_host)
+        self.cfg = dict(cfg, state_on_host=state_on_host, master_on_host=master_on_host,
+                        no_packed_copies=no_packed_copies)
         self.c, self.o = make_config(self.cfg), make_opt(opt)
+        self.opt_dict, self.m0, self.max_batch, self.max_seq = dict(opt), m, max_batch, max_seq
         dbytes, pbytes = query_bytes(self.cfg, opt, m, max_batch, max_seq)
         self.device_arena = torch.empty(dbytes + 256, dtype=torch.uint8, device=self.device)
         base = self.device_arena.data_ptr()
         self._dev_ptr = (base + 255) & ~255
-        self.pinned_arena = torch.empty(max(pbytes, 1), dtype=torch.uint8, pin_memory=True) if pbytes else None
+        self.pinned_arena = _PinnedArena(pbytes) if pbytes else None
         self.compute_stream = torch.cuda.Stream(self.device)
         self.h2d_stream = torch.cuda.Stream(self.device)
         self.d2h_stream = torch.cuda.Stream(self.device)
@@ -225,8 +282,11 @@ class HiftModel:
 
     def close(self):
         if getattr(self, "h", None):
-            lib.hift_model_destroy(self.h)
+            lib.hift_model_destroy(self.h)      # waits for the streams
             self.h = None
+        if getattr(self, "pinned_arena", None) is not None:
+            self.pinned_arena.free()
+            self.pinned_arena = None
 
     def __del__(self):
         try:
@@ -300,6 +360,10 @@ class HiftModel:
 
     def profile_enable(self, on: bool):
         _check(lib.hift_profile_enable(self.h, int(on)))
+
+    def memory(self) -> dict:
+        """hift_memory_report of this model's configuration."""
+        return memory_report(self.cfg, self.opt_dict, self.m0, self.max_batch, self.max_seq)
 
     def profile_read(self, category: int):
         n, ms, w = _i64(), C.c_double(), C.c_double()

@@ -77,6 +77,8 @@ hift_status check_config(const hift_config* c) {
   if (c->arch == HIFT_ARCH_POSTLN_ENCODER && c->n_classes < 1) return fail(HIFT_EINVAL, "n_classes must be >= 1");
   if (c->dtype != HIFT_F32 && c->dtype != HIFT_BF16) return fail(HIFT_EINVAL, "dtype unknown");
   if (!(c->norm_eps >= 0.f)) return fail(HIFT_EINVAL, "norm_eps must be >= 0");
+  if (c->master_on_host && (c->dtype != HIFT_BF16 || !c->state_on_host))
+    return fail(HIFT_EINVAL, "master_on_host needs dtype bf16 (the forward copy stays in HBM) and state_on_host");
   return HIFT_OK;
 }
 
@@ -184,13 +186,19 @@ hift_status check_opt(const hift_opt* o) {
 inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Bump allocator over the caller's arena.  With base == nullptr it only measures.
+// categories of device memory, for the memory report
+enum { MEM_MASTER = 0, MEM_FORWARD = 1, MEM_PACKED = 2, MEM_GRAD = 3, MEM_STATE = 4, MEM_ACT = 5, MEM_WORK = 6, MEM_N = 7 };
+
 struct Bump {
   unsigned char* base;
   size_t used = 0;
+  size_t by_cat[MEM_N] = {0, 0, 0, 0, 0, 0, 0};
+  int cat = MEM_WORK;
   explicit Bump(void* b) : base(reinterpret_cast<unsigned char*>(b)) {}
   void* take(size_t bytes) {
     void* p = base ? base + used : nullptr;
     used += up256(bytes);
+    by_cat[cat] += up256(bytes);
     return p;
   }
 };
@@ -221,6 +229,8 @@ struct hift_model {
   int64_t grad_cap;  // parameters the gradient buffer and one state slot can hold
   int n_state;
   bool on_host;
+  bool master_host;  // fp32 master of inactive groups in pinned memory, travelling with the state
+  int n_move;        // arrays per parameter that a slot holds: optimizer state (+ master)
   // device memory
   float* master = nullptr;
   void* wc = nullptr;  // weights the forward uses: bf16 copy, or the master itself in fp32 mode
@@ -233,6 +243,7 @@ struct hift_model {
   // drains from the third, so the two directions of the host link run at the same time.
   float* slot[NSLOT] = {nullptr, nullptr, nullptr};
   float* host_state = nullptr;          // pinned [n_state][n_params]
+  float* host_master = nullptr;         // pinned [n_params] when the master lives on the host (before host_state)
   float* cos_sin = nullptr;
   std::vector<void*> xs;  // residual stream: xs[l] enters layer l, xs[L] enters the head
   std::vector<LayerAct> la;
@@ -267,7 +278,7 @@ struct hift_model {
 namespace {
 
 // Carves every buffer of a model out of the arenas (or only measures them when arena == null).
-void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes) {
+void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes, size_t* by_cat = nullptr) {
   hift_model& M = *mm;
   const hift_config& c = M.cfg;
   const int64_t d = c.d_model, f = c.d_ffn, V = c.vocab, H = c.n_heads;
@@ -277,18 +288,30 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes) {
   const bool enc = c.arch == HIFT_ARCH_POSTLN_ENCODER, rms = c.arch == HIFT_ARCH_RMS_ROPE_DECODER;
   const int64_t fw = rms ? 2 * f : f;
   Bump b(dev);
-  M.master = (float*)b.take(np * 4);
+  b.cat = MEM_MASTER;
+  M.master = M.master_host ? nullptr : (float*)b.take(np * 4);
+  b.cat = MEM_FORWARD;
   M.wc = M.dt == DT_BF16 ? b.take(np * 2) : (void*)M.master;
+  b.cat = MEM_PACKED;
   M.wpk = M.wpk_bytes ? (unsigned char*)b.take(M.wpk_bytes) : nullptr;
+  b.cat = MEM_GRAD;
   M.grad = (float*)b.take(M.grad_cap * 4);
-  if (M.n_state > 0) {
-    if (M.on_host) {
-      for (auto& sl : M.slot) sl = (float*)b.take((size_t)M.n_state * M.grad_cap * 4);
-    } else {
-      M.state_full = (float*)b.take((size_t)M.n_state * np * 4);
+  if (M.n_move > 0 && M.on_host) {
+    // a slot holds [master (if it travels)][state 0][state 1] of one group
+    for (auto& sl : M.slot) {
+      b.cat = MEM_MASTER;
+      sl = M.master_host ? (float*)b.take((size_t)M.grad_cap * 4) : nullptr;
+      b.cat = MEM_STATE;
+      float* st = M.n_state > 0 ? (float*)b.take((size_t)M.n_state * M.grad_cap * 4) : nullptr;
+      if (!sl) sl = st;
     }
+  } else if (M.n_state > 0) {
+    b.cat = MEM_STATE;
+    M.state_full = (float*)b.take((size_t)M.n_state * np * 4);
   }
+  b.cat = MEM_WORK;
   if (rms) M.cos_sin = (float*)b.take((size_t)c.max_seq * (d / H / 2) * 2 * 4);
+  b.cat = MEM_ACT;
   M.xs.assign(c.n_layers + 1, nullptr);
   for (auto& x : M.xs) x = b.take(T * d * es);
   M.la.assign(c.n_layers, LayerAct{});
@@ -315,6 +338,7 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes) {
     M.st_f = (float*)b.take(T * 2 * 4);
     M.logits = b.take(T * V * es);
   }
+  b.cat = MEM_WORK;
   M.row_loss = (float*)b.take((T + 1) * 4);
   M.loss_dev = (float*)b.take(256);
   const int64_t wmax = std::max<int64_t>(std::max<int64_t>(3 * d, fw), std::max<int64_t>(d, c.n_classes));
@@ -325,7 +349,9 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes) {
   M.dact = b.take(T * f * es);
   M.dffn = b.take(T * fw * es);
   if (dev_bytes) *dev_bytes = b.used;
-  if (pinned_bytes) *pinned_bytes = (M.on_host && M.n_state > 0) ? (size_t)M.n_state * np * 4 : 0;
+  if (pinned_bytes) *pinned_bytes = M.on_host ? (size_t)M.n_move * np * 4 : 0;
+  if (by_cat)
+    for (int i = 0; i < MEM_N; ++i) by_cat[i] = b.by_cat[i];
 }
 
 int64_t largest_group(const Layout& L, int m) {
@@ -359,11 +385,13 @@ hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_o
   M->grad_cap = (largest_group(M->lay, m) + 63) & ~(int64_t)63;
   M->n_state = n_state_of(*opt);
   M->on_host = cfg->state_on_host != 0;
+  M->master_host = cfg->master_on_host != 0;
+  M->n_move = M->n_state + (M->master_host ? 1 : 0);
   // Which matrices get copies in fragment order: those whose contraction, at the largest batch,
   // is one the packed-operand kernel takes.
   M->wpk_bytes = 0;
   for (Tensor& t : M->lay.t) {
-    if (t.kind != HIFT_KIND_MATRIX || t.unit == 0 || M->dt != DT_BF16) continue;
+    if (t.kind != HIFT_KIND_MATRIX || t.unit == 0 || M->dt != DT_BF16 || cfg->no_packed_copies) continue;
     const int64_t rows = (cfg->arch == HIFT_ARCH_POSTLN_ENCODER && t.unit == M->lay.n_units - 1) ? max_batch : M->maxT;
     Gemm g;
     g.dtype = DT_BF16;
@@ -891,14 +919,30 @@ hift_status fetch_state(hift_model* M, int gid, int s) {
   // runs up to a step ahead of the GPU, and a copy submitted while the copy engine still has
   // a backlog is executed by a full-grid copy kernel instead, which starves the step's kernels
   if (M->copy_engine == 0 && M->h2d_last >= 0) HIP_TRY(hipEventSynchronize(M->ev_h2d[M->h2d_last]));
-  for (int j = 0; j < M->n_state; ++j) {
-    ST_TRY(state_copy(M, M->slot[s] + (size_t)j * M->grad_cap, M->host_state + (size_t)j * M->lay.n_params + plo,
+  float* host0 = M->master_host ? M->host_master : M->host_state;  // the pinned arrays are one block
+  for (int j = 0; j < M->n_move; ++j) {
+    ST_TRY(state_copy(M, M->slot[s] + (size_t)j * M->grad_cap, host0 + (size_t)j * M->lay.n_params + plo,
                       (size_t)cnt * 4, true));
     M->h2d_bytes += (uint64_t)cnt * 4;
   }
   HIP_TRY(hipEventRecord(M->ev_h2d[s], M->hs));
   M->h2d_last = s;
   M->slot_group[s] = gid;
+  return HIFT_OK;
+}
+
+hift_status sync_all(hift_model* M);
+
+// Master on the host: rebuilds the bf16 forward copy of parameters [off, off+cnt) from the pinned
+// master, one slot-sized piece at a time through the first slot (the streams must be idle).
+hift_status load_forward_copy(hift_model* M, int64_t off, int64_t cnt) {
+  for (int64_t done = 0; done < cnt; done += M->grad_cap) {
+    const int64_t n = std::min<int64_t>(M->grad_cap, cnt - done);
+    HIP_TRY(hipMemcpyAsync(M->slot[0], M->host_master + off + done, (size_t)n * 4, hipMemcpyHostToDevice, M->cs));
+    HIP_TRY(cast_f32_to(DT_BF16, n, M->slot[0], (unsigned char*)M->wc + (off + done) * 2, M->cs));
+    HIP_TRY(hipStreamSynchronize(M->cs));
+  }
+  for (int& g : M->slot_group) g = -1;  // slot 0 no longer holds a group's state
   return HIFT_OK;
 }
 
@@ -977,6 +1021,40 @@ hift_status hift_query_bytes(const hift_config* cfg, const hift_opt* opt, int32_
   return HIFT_OK;
 }
 
+hift_status hift_memory_report(const hift_config* cfg, const hift_opt* opt, int32_t m, int32_t max_batch,
+                               int32_t max_seq, hift_memory* out) {
+  if (!out) return fail(HIFT_EINVAL, "out is null");
+  hift_model M;
+  hift_status s = init_model_shape(&M, cfg, opt, m, max_batch, max_seq);
+  if (s != HIFT_OK) return s;
+  size_t dev = 0, pin = 0, cat[MEM_N];
+  carve(&M, nullptr, &dev, &pin, cat);
+  memset(out, 0, sizeof(*out));
+  out->device_master = cat[MEM_MASTER];
+  out->device_forward = cat[MEM_FORWARD];
+  out->device_packed = cat[MEM_PACKED];
+  out->device_grad = cat[MEM_GRAD];
+  out->device_state = cat[MEM_STATE];
+  out->device_activations = cat[MEM_ACT];
+  out->device_workspace = cat[MEM_WORK];
+  out->device_total = dev;
+  out->pinned_total = pin;
+  out->para = out->device_master + out->device_forward + out->device_packed;
+  out->gra = out->device_grad;
+  out->sta = out->device_state;
+  out->pgs = out->para + out->gra + out->sta;
+  out->residual = out->device_activations + out->device_workspace;
+  out->total = out->pgs + out->residual;
+  out->n_params = (uint64_t)M.lay.n_params;
+  out->peak_trainable = (uint64_t)largest_group(M.lay, m);
+  out->k = group_count(M.lay.n_units, m);
+  out->zeta1 = 4.0 * (double)M.lay.n_params;
+  out->zeta_fpft = 4.0 * out->zeta1;
+  out->zeta_hift = (out->k + 3.0) / out->k * out->zeta1;
+  out->zeta_hift_peak = out->zeta1 + 12.0 * (double)out->peak_trainable;
+  return HIFT_OK;
+}
+
 hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32_t m, int32_t max_batch,
                               int32_t max_seq, const float* init_params_host, void* device_arena,
                               size_t device_bytes, void* pinned_arena, size_t pinned_bytes, void* compute_stream,
@@ -997,7 +1075,8 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
     return fail(HIFT_ENOMEM, "arenas too small: need %zu device and %zu pinned bytes", need_dev, need_pin);
   }
   carve(M, device_arena, nullptr, nullptr);
-  M->host_state = need_pin ? reinterpret_cast<float*>(pinned_arena) : nullptr;
+  M->host_master = (need_pin && M->master_host) ? reinterpret_cast<float*>(pinned_arena) : nullptr;
+  M->host_state = (need_pin && M->n_state > 0) ? reinterpret_cast<float*>(pinned_arena) + (M->master_host ? M->lay.n_params : 0) : nullptr;
   M->cs = (hipStream_t)compute_stream;
   M->hs = (hipStream_t)h2d_stream;
   M->ds = (hipStream_t)d2h_stream;
@@ -1019,11 +1098,11 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
   CR_TRY(hipEventCreate(&M->ev_t1));
   CR_TRY(hipEventCreate(&M->ev_w0));
   CR_TRY(hipEventCreate(&M->ev_w1));
-  if (M->host_state) memset(M->host_state, 0, need_pin);
+  if (need_pin) memset(pinned_arena, 0, need_pin);
   // state and gradient buffers start at zero
   if (M->state_full) CR_TRY(fill_zero(M->state_full, (size_t)M->n_state * M->lay.n_params * 4, M->cs));
   for (int q = 0; q < NSLOT; ++q)
-    if (M->slot[q]) CR_TRY(fill_zero(M->slot[q], (size_t)M->n_state * M->grad_cap * 4, M->cs));
+    if (M->slot[q]) CR_TRY(fill_zero(M->slot[q], (size_t)M->n_move * M->grad_cap * 4, M->cs));
   CR_TRY(fill_zero(M->grad, (size_t)M->grad_cap * 4, M->cs));
   if (M->cos_sin) {
     const int hd2 = cfg->d_model / cfg->n_heads / 2;
@@ -1037,12 +1116,17 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
     CR_TRY(hipMemcpyAsync(M->cos_sin, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, M->cs));
     CR_TRY(hipStreamSynchronize(M->cs));
   }
-  if (init_params_host) {
-    CR_TRY(hipMemcpyAsync(M->master, init_params_host, (size_t)M->lay.n_params * 4, hipMemcpyHostToDevice, M->cs));
+  if (M->master_host) {
+    if (init_params_host) memcpy(M->host_master, init_params_host, (size_t)M->lay.n_params * 4);
+    if (load_forward_copy(M, 0, M->lay.n_params) != HIFT_OK) return bail(HIFT_EDEVICE);
   } else {
-    CR_TRY(fill_zero(M->master, (size_t)M->lay.n_params * 4, M->cs));
+    if (init_params_host) {
+      CR_TRY(hipMemcpyAsync(M->master, init_params_host, (size_t)M->lay.n_params * 4, hipMemcpyHostToDevice, M->cs));
+    } else {
+      CR_TRY(fill_zero(M->master, (size_t)M->lay.n_params * 4, M->cs));
+    }
+    if (M->dt == DT_BF16) CR_TRY(cast_f32_to(DT_BF16, M->lay.n_params, M->master, M->wc, M->cs));
   }
-  if (M->dt == DT_BF16) CR_TRY(cast_f32_to(DT_BF16, M->lay.n_params, M->master, M->wc, M->cs));
   CR_TRY(repack_units(M, 0, M->lay.n_units));
   CR_TRY(hipStreamSynchronize(M->cs));
 #undef CR_TRY
@@ -1128,7 +1212,7 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
   int ulo, uhi;
   int64_t plo, cnt;
   group_range(M, gid, &ulo, &uhi, &plo, &cnt);
-  const bool moving = M->on_host && M->n_state > 0;
+  const bool moving = M->on_host && M->n_move > 0;
   HIP_TRY(hipEventRecord(M->ev_t0, M->cs));
 
   // ---- state movement, queued ahead of the compute (Algorithm 1 step i, issued early) ----
@@ -1166,10 +1250,11 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
   OptArgs oa{M->opt.kind, M->opt.lr, M->opt.beta1, M->opt.beta2, M->opt.eps, M->opt.weight_decay, M->opt.momentum};
   float *s1b = nullptr, *s2b = nullptr;
   int64_t sbase = plo;  // state index = parameter offset - sbase
+  float* mbase = M->master_host ? M->slot[s] - plo : M->master;  // master of parameter i at mbase[i]
   if (M->n_state > 0) {
     if (moving) {
-      s1b = M->slot[s];
-      s2b = M->slot[s] + M->grad_cap;
+      s1b = M->slot[s] + (size_t)(M->master_host ? 1 : 0) * M->grad_cap;
+      s2b = s1b + M->grad_cap;
     } else {
       s1b = M->state_full;
       s2b = M->state_full + M->lay.n_params;
@@ -1183,7 +1268,7 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
     for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
       const Tensor& t = M->lay.t[i];
       void* cc = M->dt == DT_BF16 ? (unsigned char*)M->wc + t.off * 2 : nullptr;
-      K_TRY(optimizer_update(oa, t.count(), t.kind == HIFT_KIND_MATRIX, tg, M->master + t.off,
+      K_TRY(optimizer_update(oa, t.count(), t.kind == HIFT_KIND_MATRIX, tg, mbase + t.off,
                              M->grad + (t.off - plo), s1b ? s1b + (t.off - sbase) : nullptr,
                              (s2b && M->n_state == 2) ? s2b + (t.off - sbase) : nullptr, cc, M->cs));
     }
@@ -1202,8 +1287,9 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
   // ---- state back to the host (Algorithm 1 step k) ----
   if (moving) {
     HIP_TRY(hipStreamWaitEvent(M->ds, M->ev_opt[s], 0));
-    for (int j = 0; j < M->n_state; ++j) {
-      ST_TRY(state_copy(M, M->host_state + (size_t)j * M->lay.n_params + plo, M->slot[s] + (size_t)j * M->grad_cap,
+    float* host0 = M->master_host ? M->host_master : M->host_state;
+    for (int j = 0; j < M->n_move; ++j) {
+      ST_TRY(state_copy(M, host0 + (size_t)j * M->lay.n_params + plo, M->slot[s] + (size_t)j * M->grad_cap,
                         (size_t)cnt * 4, false));
       M->d2h_bytes += (uint64_t)cnt * 4;
     }
@@ -1227,7 +1313,9 @@ hift_status hift_read_params(hift_model* M, int32_t ulo, int32_t uhi, int32_t wh
   if ((int64_t)dst_count != cnt) return fail(HIFT_EINVAL, "buffer holds %zu floats, units hold %lld", dst_count, (long long)cnt);
   if (which != 0 && which != 1) return fail(HIFT_EINVAL, "which must be 0 or 1");
   ST_TRY(sync_all(M));
-  if (which == 0 || M->dt == DT_F32) {
+  if (which == 0 && M->master_host) {
+    memcpy(dst, M->host_master + off, (size_t)cnt * 4);  // every write-back has landed
+  } else if (which == 0 || M->dt == DT_F32) {
     HIP_TRY(hipMemcpy(dst, M->master + off, (size_t)cnt * 4, hipMemcpyDeviceToHost));
   } else {
     std::vector<uint16_t> tmp((size_t)cnt);
@@ -1246,6 +1334,13 @@ hift_status hift_write_params(hift_model* M, int32_t ulo, int32_t uhi, const flo
   ST_TRY(unit_span(M, ulo, uhi, &off, &cnt));
   if ((int64_t)src_count != cnt) return fail(HIFT_EINVAL, "buffer holds %zu floats, units hold %lld", src_count, (long long)cnt);
   ST_TRY(sync_all(M));
+  if (M->master_host) {
+    memcpy(M->host_master + off, src, (size_t)cnt * 4);
+    ST_TRY(load_forward_copy(M, off, cnt));
+    HIP_TRY(repack_units(M, ulo, uhi));
+    HIP_TRY(hipStreamSynchronize(M->cs));
+    return HIFT_OK;
+  }
   HIP_TRY(hipMemcpy(M->master + off, src, (size_t)cnt * 4, hipMemcpyHostToDevice));
   if (M->dt == DT_BF16) {
     HIP_TRY(cast_f32_to(DT_BF16, cnt, M->master + off, (unsigned char*)M->wc + off * 2, M->cs));

@@ -11,7 +11,7 @@ def spec_of(cfg):
 
 
 def make_pair(wl, seed=0, m=None, strategy=None, opt=None, state_on_host=0, batch=None, seq=None,
-              jitter=0.0, sched_seed=17, **cfg_over):
+              jitter=0.0, sched_seed=17, master_on_host=0, no_packed_copies=0, **cfg_over):
     """Returns (oracle, gpu_model, theta0).  Weights are bf16-exact when the GPU model is bf16."""
     import paper_2401_15207_amd as H
     cfg = model_config(wl, **cfg_over)
@@ -21,7 +21,8 @@ def make_pair(wl, seed=0, m=None, strategy=None, opt=None, state_on_host=0, batc
     b, s = batch or wl["batch"], seq or wl["seq"]
     theta0 = init_params(seed, spec_of(cfg), bf16_exact=(cfg["dtype"] == 1), jitter=jitter)
     orc = O.HiftOracle(cfg, opt, theta0.astype(np.float64), half_weights=(cfg["dtype"] == 1))
-    gpu = H.HiftModel(cfg, opt, m, b, s, init_params=theta0, state_on_host=state_on_host)
+    gpu = H.HiftModel(cfg, opt, m, b, s, init_params=theta0, state_on_host=state_on_host,
+                      master_on_host=master_on_host, no_packed_copies=no_packed_copies)
     ko = orc.set_group_schedule(strategy, m, sched_seed)
     kg = gpu.set_group_schedule(strategy, m, sched_seed)
     assert ko == kg

@@ -71,6 +71,45 @@ def test_arena_sizes(H):
     assert 4 * big + 2 * 4 * big == 3 * 4 * big
 
 
+def test_memory_report(H):
+    wl = WORKLOADS["C4"]
+    cfg = model_config(wl)
+    ref = O.memory_model(cfg, 1)
+    base = H.memory_report(dict(cfg, state_on_host=1), wl["opt"], 1, 4, 512)
+    d, p = H.query_bytes(dict(cfg, state_on_host=1), wl["opt"], 1, 4, 512)
+    assert base["device_total"] == d and base["pinned_total"] == p
+    parts = ["device_master", "device_forward", "device_packed", "device_grad", "device_state", "device_activations",
+             "device_workspace"]
+    assert sum(base[q] for q in parts) == base["device_total"] == base["total"]
+    assert base["pgs"] == base["para"] + base["gra"] + base["sta"] and base["total"] == base["pgs"] + base["residual"]
+    # closed forms (appendix "Memory Analysis") against the oracle's
+    for key in ("k", "n_params", "peak_trainable"):
+        assert base[key] == ref[key]
+    for key in ("zeta1", "zeta_fpft", "zeta_hift", "zeta_hift_peak"):
+        assert abs(base[key] - ref[key]) <= 1e-9 * ref[key]
+    # what the arena holds: fp32 master and bf16 copy of every parameter, one gradient buffer and three
+    # state slots for the largest group (rounded up to 64 parameters, 256-byte pieces)
+    n, big = ref["n_params"], ref["peak_trainable"]
+    assert 4 * n <= base["device_master"] < 4 * n + 4096 and 2 * n <= base["device_forward"] < 2 * n + 4096
+    assert 4 * big <= base["device_grad"] < 4 * big + 4096
+    assert 3 * 8 * big <= base["device_state"] < 3 * 8 * big + 4096
+    assert base["device_packed"] >= 2 * 2 * (n - 2 * 32000 * 4096 - 300000)   # two copies of every layer matrix and the head
+    # the small-memory mode: master of inactive groups on the host, no fragment-order copies
+    lean = H.memory_report(dict(cfg, state_on_host=1, master_on_host=1, no_packed_copies=1), wl["opt"], 1, 4, 512)
+    assert lean["device_packed"] == 0 and 3 * 4 * big <= lean["device_master"] < 3 * 4 * big + 4096
+    assert lean["pinned_total"] == 12 * n                       # master, m and v of every parameter
+    assert lean["device_activations"] == base["device_activations"]
+    one = H.memory_report(dict(cfg, state_on_host=1, master_on_host=1, no_packed_copies=1), wl["opt"], 1, 1, 512)
+    assert one["device_total"] < 24 * 2 ** 30                   # a 7B model in a 24 GiB budget at batch 1 (appendix "Mixing Precision")
+    # all state resident: the state term is the whole of zeta2
+    res = H.memory_report(dict(cfg, state_on_host=0), wl["opt"], 1, 4, 512)
+    assert 8 * n <= res["device_state"] < 8 * n + 4096 and res["pinned_total"] == 0
+    with pytest.raises(H.HiftError):
+        H.memory_report(dict(cfg, state_on_host=0, master_on_host=1), wl["opt"], 1, 4, 512)
+    with pytest.raises(H.HiftError):
+        H.memory_report(dict(cfg, dtype=0, state_on_host=1, master_on_host=1), wl["opt"], 1, 4, 512)
+
+
 def test_argument_errors_without_a_gpu(H):
     import ctypes as C
     from paper_2401_15207_amd import binding as B

@@ -124,3 +124,48 @@ def test_small_rope_decoder_other_optimizers_bf16(optk):
         assert abs(lg - lo_) <= TOL * abs(lo_)
         ok, info = chk.check(tb_g, gpu.read_params(), TOL, max_outlier_frac=1e-3)
         assert ok, (t, gid, info)
+
+
+SMALL_ROPE = dict(arch=2, n_layers=3, d_model=256, n_heads=4, d_ffn=512, vocab=1000, max_seq=128, n_classes=0,
+                  norm_eps=1e-5, rope_base=10000.0, dtype=1, batch=2, seq=128, m=1, strategy="random", opt=None)
+
+
+@pytest.mark.parametrize("optk", ["adamw", "sgd"])
+def test_master_on_host_gives_the_same_trajectory(optk):
+    """Adapted mixed precision (appendix "Mixing Precision"): with the fp32 master of the inactive groups
+    parked on the host, every step must produce bit-identical weights, state and loss to the run that
+    keeps the master in HBM, and stay within tolerance of the oracle."""
+    opt = (dict(kind="adamw", lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01) if optk == "adamw"
+           else dict(kind="sgd", lr=1e-2, momentum=0.0, weight_decay=0.0))
+    orc, hbm, theta0 = make_pair(SMALL_ROPE, seed=21, opt=opt, state_on_host=1)
+    _o, host, _t = make_pair(SMALL_ROPE, seed=21, opt=opt, state_on_host=1, master_on_host=1)
+    assert np.array_equal(host.read_params(), theta0) and np.array_equal(host.read_params(which=1), hbm.read_params(which=1))
+    for t, gid, lo_, lg, chk, tb_g in run_steps(orc, hbm, SMALL_ROPE, 21, 2 * orc.k):
+        tok, lab = make_batch(SMALL_ROPE, 21, t)
+        lh = host.step(*to_dev(tok, lab), gid)
+        assert lh == lg, (t, lh, lg)
+        after = hbm.read_params()
+        assert np.array_equal(host.read_params(), after), t
+        assert np.array_equal(host.read_params(which=1), hbm.read_params(which=1)), t
+        assert abs(lg - lo_) <= TOL * abs(lo_)
+        ok, info = chk.check(tb_g, after, TOL, max_outlier_frac=1e-3)
+        assert ok, (t, gid, info)
+    if optk == "adamw":
+        for j in (0, 1):
+            assert np.array_equal(host.read_state(0, host.n_units, j), hbm.read_state(0, hbm.n_units, j))
+    # writing parameters goes to the host master and refreshes the forward copy
+    ulo, uhi = host.group_units(1)
+    lo, hi = orc.group_range(1)
+    host.write_params(ulo, uhi, theta0[lo:hi])
+    hbm.write_params(ulo, uhi, theta0[lo:hi])
+    assert np.array_equal(host.read_params(), hbm.read_params())
+    tok, lab = make_batch(SMALL_ROPE, 21, 99)
+    assert host.step(*to_dev(tok, lab), 1) == hbm.step(*to_dev(tok, lab), 1)
+    assert np.array_equal(host.read_params(), hbm.read_params())
+    m = host.memory()
+    assert m["device_master"] < hbm.memory()["device_master"]
+
+
+def test_c4_width_without_packed_copies():
+    # the contractions read the row-major bf16 copy when the fragment-order copies are switched off
+    _gradient_check(WORKLOADS["C4_L2"], lambda k: [1, k - 1], no_packed_copies=1)

@@ -91,3 +91,28 @@ def test_memory_closed_forms_equal_groups():
     grp = P // k
     assert P + 2 * P + P == GOLD["memory_fpft_over_zeta1"]["value"] * P
     assert P + 2 * grp + grp == (k + 3) * P // k
+
+
+def test_memory_model_against_the_printed_forms():
+    """The oracle's accounting reduces to the appendix's three equations for fp32 AdamW and to the
+    worked FPFT figure; for other optimizers only the state multiplicity changes."""
+    from fractions import Fraction
+    cfg = model_config(WORKLOADS["C4"])
+    mm = O.memory_model(cfg, 1)
+    k = GOLD["llama7b_groups_m1"]["value"]
+    assert mm["k"] == k
+    assert mm["zeta_fpft"] == GOLD["memory_fpft_over_zeta1"]["value"] * mm["zeta1"]
+    assert abs(mm["zeta_hift"] - float(Fraction(k + 3, k)) * mm["zeta1"]) <= 1e-6 * mm["zeta1"]
+    assert abs(mm["delta"] - float(Fraction(3 * k - 3, k)) * mm["zeta1"]) <= 1e-6 * mm["zeta1"]
+    w = GOLD["memory_fpft_7b_worked"]
+    assert abs(w["fpft_G"] - 4 * w["zeta1_G"]) < 1e-9          # the printed pair obeys the first equation
+    # the peak uses the largest group (a hidden layer at 7B), the average an equal share
+    layer = max(c for _o, c in O.unit_ranges(cfg))
+    assert mm["peak_trainable"] == layer and mm["zeta_hift_peak"] == mm["zeta1"] + 12 * layer
+    assert mm["zeta_hift_peak"] >= mm["zeta_hift"]
+    # plain SGD keeps no state: gradients are the only extra term
+    sgd = O.memory_model(cfg, 1, state_arrays=0)
+    assert sgd["zeta_fpft"] == 2 * sgd["zeta1"] and sgd["zeta_hift_peak"] == sgd["zeta1"] + 4 * layer
+    # grouping m units: k shrinks, the peak group grows
+    m4 = O.memory_model(cfg, 4)
+    assert m4["k"] == 9 and m4["peak_trainable"] == 4 * layer
