@@ -554,6 +554,37 @@ def sgd_update(theta, g, buf, t, lr, momentum, wd, decay_mask):
     theta -= lr * g
 
 
+def adafactor_update(theta, g, state, shape, t, lr, wd, decay, eps1=1e-30, clip=1.0, decay_rate=0.8):
+    """Adafactor (Shazeer and Stern 2018, Algorithm 4 without momentum, with an external step
+    size: no relative step, no parameter scaling).  One tensor per call; theta, g flat views.
+      beta2_t = 1 - t^(-decay_rate)
+      matrices [n, m]:  R <- beta2_t R + (1 - beta2_t) mean_j (G^2 + eps1)      (n values)
+                        C <- beta2_t C + (1 - beta2_t) mean_i (G^2 + eps1)      (m values)
+                        V_ij = R_i C_j / mean(R);   U = G / sqrt(V)
+      vectors:          V <- beta2_t V + (1 - beta2_t) (G^2 + eps1);  U = G / sqrt(V)
+      U <- U / max(1, rms(U) / clip);  theta <- theta - lr wd theta (decayed tensors) - lr U
+    state: dict, created empty; holds "r", "c" (matrices) or "v" (vectors)."""
+    b2 = 1.0 - float(t) ** (-decay_rate)
+    if len(shape) >= 2:
+        G = g.reshape(shape)
+        sq = G * G + eps1
+        if "r" not in state:
+            state["r"], state["c"] = np.zeros(shape[0], theta.dtype), np.zeros(shape[1], theta.dtype)
+        state["r"][...] = b2 * state["r"] + (1.0 - b2) * sq.mean(axis=1)
+        state["c"][...] = b2 * state["c"] + (1.0 - b2) * sq.mean(axis=0)
+        V = np.outer(state["r"], state["c"]) / state["r"].mean()
+        U = (G / np.sqrt(V)).reshape(-1)
+    else:
+        if "v" not in state:
+            state["v"] = np.zeros(g.shape, theta.dtype)
+        state["v"][...] = b2 * state["v"] + (1.0 - b2) * (g * g + eps1)
+        U = g / np.sqrt(state["v"])
+    U = U / max(1.0, float(np.sqrt(np.mean(U * U))) / clip)
+    if decay:
+        theta -= lr * wd * theta
+    theta -= lr * U
+
+
 def bf16_round(x: np.ndarray) -> np.ndarray:
     """Nearest bfloat16 value (1 sign, 8 exponent, 7 fraction bits; ties to even), returned in
     x's dtype.  Values are first rounded to float32 (nearest even), whose upper 16 bits are the
@@ -584,6 +615,7 @@ class HiftOracle:
             off += c
         self.state1 = np.zeros_like(self.theta)   # AdamW m / AdaGrad accumulator / SGD buffer
         self.state2 = np.zeros_like(self.theta)   # AdamW v
+        self.factored = {}                        # Adafactor: tensor name -> {"r","c"} or {"v"}
         self.k = None
         self.t = 0
         self.last_grad = None
@@ -632,6 +664,14 @@ class HiftOracle:
             adagrad_update(th, gs, self.state1[lo:hi], o["lr"], o["eps"], o["weight_decay"], dm)
         elif o["kind"] == "sgd":
             sgd_update(th, gs, self.state1[lo:hi], tg, o["lr"], o["momentum"], o["weight_decay"], dm)
+        elif o["kind"] == "adafactor":
+            off = 0
+            for name, shape, _kind, _u in param_tensors(self.cfg):
+                c = int(np.prod(shape))
+                if lo <= off and off + c <= hi:
+                    adafactor_update(self.theta[off:off + c], g[off:off + c], self.factored.setdefault(name, {}),
+                                     shape, tg, o["lr"], o["weight_decay"], len(shape) >= 2)
+                off += c
         else:
             raise ValueError("unknown optimizer")
         self.t += 1

@@ -152,3 +152,70 @@ def test_half_weights_step_evaluates_at_rounded_master_and_updates_master():
     exp = theta0[lo:hi] * (1 - p["lr"] * p["weight_decay"] * oh.decay_mask[lo:hi]) - p["lr"] * g / (np.abs(g) + p["eps"])
     assert np.allclose(oh.theta[lo:hi], exp, rtol=1e-12, atol=0)
     assert not np.array_equal(oh.theta[lo:hi], O.bf16_round(oh.theta[lo:hi]))   # master keeps full precision
+
+
+ADAFACTOR = dict(kind="adafactor", lr=1e-3, weight_decay=0.0)
+
+
+def test_adafactor_first_step_by_hand():
+    # one 1 x 2 matrix, G = [3, 4], first update (beta2_1 = 0): R = mean(9, 16) = 12.5, C = [9, 16],
+    # V = R C / mean(R) = C, U = G / sqrt(C) = [1, 1], rms(U) = 1: not clipped
+    th = np.array([0.5, -0.5])
+    st = {}
+    O.adafactor_update(th, np.array([3.0, 4.0]), st, (1, 2), 1, 0.1, 0.0, True)
+    assert np.allclose(th, [0.4, -0.6], atol=1e-12)
+    assert np.allclose(st["r"], [12.5]) and np.allclose(st["c"], [9.0, 16.0])
+    # a vector with one large entry: U = sign(G) on the first step, so rms(U) = 1 again; with decay
+    th = np.array([1.0, 1.0, 1.0])
+    O.adafactor_update(th, np.array([2.0, -4.0, 8.0]), {}, (3,), 1, 0.1, 0.5, True)
+    assert np.allclose(th, 1.0 - 0.1 * 0.5 - 0.1 * np.array([1.0, -1.0, 1.0]), atol=1e-12)
+    # second step of a vector: beta2_2 = 1 - 2^-0.8; V = b V + (1 - b) G^2; |U| > 1 possible -> clipped to rms 1
+    th, st = np.zeros(2), {}
+    O.adafactor_update(th, np.array([1.0, 1.0]), st, (2,), 1, 1.0, 0.0, False)
+    b = 1.0 - 2.0 ** -0.8
+    g2 = np.array([3.0, 0.0])
+    v = b * 1.0 + (1 - b) * (g2 * g2 + 1e-30)
+    u = g2 / np.sqrt(v)
+    u = u / max(1.0, np.sqrt(np.mean(u * u)))
+    O.adafactor_update(th, g2, st, (2,), 2, 1.0, 0.0, False)
+    assert np.allclose(th, -1.0 - u, atol=1e-12) and np.sqrt(np.mean(u * u)) <= 1.0 + 1e-12
+
+
+def test_adafactor_against_the_transformers_implementation():
+    """Same hyper-parameters (external step size, no parameter scaling, no momentum, clip 1.0,
+    decay exponent 0.8, eps 1e-30): an independent implementation of the published algorithm."""
+    import torch
+    from transformers.optimization import Adafactor
+    rng = np.random.default_rng(5)
+    W0, b0 = rng.standard_normal((5, 7)), rng.standard_normal(6)
+    W = torch.tensor(W0, dtype=torch.float64, requires_grad=True)
+    b = torch.tensor(b0, dtype=torch.float64, requires_grad=True)
+    opt = Adafactor([W, b], lr=0.01, relative_step=False, scale_parameter=False, warmup_init=False,
+                    clip_threshold=1.0, decay_rate=-0.8, beta1=None, weight_decay=0.0, eps=(1e-30, 1e-3))
+    thW, thb, sW, sb = W0.reshape(-1).copy(), b0.copy(), {}, {}
+    for t in range(1, 5):
+        gW, gb = rng.standard_normal((5, 7)) * (10.0 if t == 3 else 1.0), rng.standard_normal(6) * 0.01
+        W.grad, b.grad = torch.tensor(gW), torch.tensor(gb)
+        opt.step()
+        O.adafactor_update(thW, gW.reshape(-1), sW, (5, 7), t, 0.01, 0.0, True)
+        O.adafactor_update(thb, gb, sb, (6,), t, 0.01, 0.0, False)
+        assert np.allclose(thW, W.detach().numpy().reshape(-1), rtol=1e-12, atol=1e-14)
+        assert np.allclose(thb, b.detach().numpy(), rtol=1e-12, atol=1e-14)
+
+
+def test_adafactor_in_the_hift_loop_keeps_other_groups_frozen():
+    o, _ = _fresh(ADAFACTOR)
+    k = o.set_group_schedule("top2down", 1, 0)
+    for t in range(1, 2 * k + 1):
+        gid = o.schedule_group_at(t)
+        before = o.theta.copy()
+        tok, lab = make_batch(WL, 1, t)
+        o.step(tok, lab, gid)
+        lo, hi = o.group_range(gid)
+        keep = np.ones(o.theta.size, bool)
+        keep[lo:hi] = False
+        assert np.array_equal(before[keep], o.theta[keep]) and not np.array_equal(before[lo:hi], o.theta[lo:hi])
+    # factored state: n + m numbers for an n x m matrix, one per element for a vector
+    total = sum(sum(v.size for v in st.values()) for st in o.factored.values())
+    want = sum((s[0] + s[1]) if len(s) >= 2 else s[0] for _n, s, _k in SPEC)
+    assert total == want
