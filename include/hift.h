@@ -59,7 +59,7 @@ typedef enum {
 } hift_status;
 
 typedef enum { HIFT_BOTTOM2UP = 0, HIFT_TOP2DOWN = 1, HIFT_RANDOM = 2 } hift_strategy;
-typedef enum { HIFT_ADAMW = 0, HIFT_ADAGRAD = 1, HIFT_SGD = 2 } hift_opt_kind;
+typedef enum { HIFT_ADAMW = 0, HIFT_ADAGRAD = 1, HIFT_SGD = 2, HIFT_ADAFACTOR = 3 } hift_opt_kind;
 enum { HIFT_ARCH_PRELN_DECODER = 0, HIFT_ARCH_POSTLN_ENCODER = 1, HIFT_ARCH_RMS_ROPE_DECODER = 2 };
 enum { HIFT_F32 = 0, HIFT_BF16 = 1 };
 enum { HIFT_KIND_MATRIX = 0, HIFT_KIND_GAIN = 1, HIFT_KIND_BIAS = 2 };
@@ -99,6 +99,12 @@ typedef struct {
                           AdaGrad / SGD: added to the gradient */
   double momentum;     /* SGD; 0 = plain SGD, which keeps no state and moves no bytes */
 } hift_opt;
+/* HIFT_ADAFACTOR (section "Memory Efficiency Analysis" lists it among the optimizers): Shazeer and Stern
+ * 2018, Algorithm 4 without momentum, with the caller's lr as the step size (no relative step, no
+ * parameter scaling); epsilon_1 = 1e-30, clipping threshold 1, beta2_t = 1 - t^-0.8 with t the group's own
+ * update count; matrices keep one statistic per row and per column, vectors one per element; uses lr and
+ * weight_decay only.  The statistics of all groups stay in HBM (rows + cols floats per matrix), so nothing
+ * moves between host and device. */
 
 typedef struct {
   const int32_t* tokens; /* device, [batch, seq], each in [0, vocab) */
@@ -214,6 +220,10 @@ hift_status hift_read_params(hift_model* mdl, int32_t unit_lo, int32_t unit_hi, 
                              float* dst_host, size_t dst_count);
 hift_status hift_write_params(hift_model* mdl, int32_t unit_lo, int32_t unit_hi,
                               const float* src_host, size_t src_count);
+/* Adafactor only: the statistics of tensor `tensor_index` (hift_tensor_at order): rows then cols floats
+ * for a matrix, rows floats for a vector.  dst: host.  Waits for the streams. */
+hift_status hift_read_factored_state(hift_model* mdl, int32_t tensor_index, float* dst, size_t dst_count);
+
 /* Optimizer state of units [unit_lo, unit_hi), slot 0 (AdamW first moment / AdaGrad accumulator /
  * SGD momentum buffer) or slot 1 (AdamW second moment), wherever it currently lives. */
 hift_status hift_read_state(hift_model* mdl, int32_t unit_lo, int32_t unit_hi, int32_t slot,

@@ -17,7 +17,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 STRATEGY = {"bottom2up": 0, "top2down": 1, "random": 2}
-OPT_KIND = {"adamw": 0, "adagrad": 1, "sgd": 2}
+OPT_KIND = {"adamw": 0, "adagrad": 1, "sgd": 2, "adafactor": 3}
 
 
 class HiftError(RuntimeError):
@@ -66,6 +66,7 @@ _SIGS = {
     "hift_tensor_at": [_P(Config), _i32, _P(TensorInfo)],
     "hift_query_bytes": [_P(Config), _P(Opt), _i32, _i32, _i32, _P(_sz), _P(_sz)],
     "hift_memory_report": [_P(Config), _P(Opt), _i32, _i32, _i32, _P(Memory)],
+    "hift_read_factored_state": [_vp, _i32, _vp, _sz],
     "hift_model_create": [_P(Config), _P(Opt), _i32, _i32, _i32, _vp, _vp, _sz, _vp, _sz, _vp, _vp, _vp, _P(_vp)],
     "hift_set_group_schedule": [_vp, C.c_int, _i32, _u64, _P(_i32)],
     "hift_schedule_group_at": [_vp, _i64, _P(_i32)],
@@ -360,6 +361,13 @@ class HiftModel:
 
     def profile_enable(self, on: bool):
         _check(lib.hift_profile_enable(self.h, int(on)))
+
+    def read_factored_state(self, tensor_index: int) -> np.ndarray:
+        _name, shape, _kind, _unit, _off = self.tensors[tensor_index]
+        n = int(shape[0] + shape[1]) if len(shape) >= 2 else int(shape[0])
+        out = np.empty(n, dtype=np.float32)
+        _check(lib.hift_read_factored_state(self.h, tensor_index, out.ctypes.data, out.size))
+        return out
 
     def memory(self) -> dict:
         """hift_memory_report of this model's configuration."""

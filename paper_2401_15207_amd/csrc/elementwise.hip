@@ -576,6 +576,111 @@ __global__ void __launch_bounds__(BLK) opt_k(int64_t n, float lr, float b1, floa
   if (cc) stv<bf16, V>(cc + i, th);
 }
 
+// ---------------------------------------------------------------------------- Adafactor
+constexpr float AF_EPS1 = 1e-30f;
+constexpr int AF_CHUNK = 256;  // rows per partial column sum
+
+// R_i <- b2 R_i + (1 - b2) (mean_j G_ij^2 + eps1); one wavefront per row
+__global__ void __launch_bounds__(BLK) af_row_stats_k(int64_t rows, int64_t cols, float b2, const float* __restrict__ g,
+                                                       float* __restrict__ R) {
+  const int64_t row = (int64_t)blockIdx.x * (BLK / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const float* gr = g + row * cols;
+  float s = 0.f;
+  for (int64_t j = lane; j < cols; j += 64) s += gr[j] * gr[j];
+  s = wave_sum(s);
+  if (lane == 0) R[row] = b2 * R[row] + (1.f - b2) * (s / (float)cols + AF_EPS1);
+}
+
+// partial[chunk][j] = sum over the chunk's rows of G_ij^2; one thread per column
+__global__ void __launch_bounds__(BLK) af_col_part_k(int64_t rows, int64_t cols, const float* __restrict__ g,
+                                                      float* __restrict__ partial) {
+  const int64_t j = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (j >= cols) return;
+  const int64_t r0 = (int64_t)blockIdx.y * AF_CHUNK, r1 = r0 + AF_CHUNK < rows ? r0 + AF_CHUNK : rows;
+  float s = 0.f;
+  for (int64_t i = r0; i < r1; ++i) {
+    const float v = g[i * cols + j];
+    s += v * v;
+  }
+  partial[(int64_t)blockIdx.y * cols + j] = s;
+}
+
+__global__ void __launch_bounds__(BLK) af_col_final_k(int64_t rows, int64_t cols, int chunks, float b2,
+                                                       const float* __restrict__ partial, float* __restrict__ Cst) {
+  const int64_t j = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (j >= cols) return;
+  float s = 0.f;
+  for (int c = 0; c < chunks; ++c) s += partial[(int64_t)c * cols + j];
+  Cst[j] = b2 * Cst[j] + (1.f - b2) * (s / (float)rows + AF_EPS1);
+}
+
+// out[0] = (sum of v[0..n)) * scale; one workgroup
+__global__ void __launch_bounds__(BLK) af_sum_k(int64_t n, const float* __restrict__ v, float scale, float* __restrict__ out) {
+  __shared__ float red[BLK / 64];
+  float s = 0.f;
+  for (int64_t i = threadIdx.x; i < n; i += BLK) s += v[i];
+  s = block_sum<BLK / 64>(s, red);
+  if (threadIdx.x == 0) out[0] = s * scale;
+}
+
+// rowu2[i] = (meanR / R_i) * sum_j G_ij^2 / C_j  (the row's share of sum U^2); one wavefront per row
+__global__ void __launch_bounds__(BLK) af_row_u2_k(int64_t rows, int64_t cols, const float* __restrict__ g,
+                                                    const float* __restrict__ R, const float* __restrict__ Cst,
+                                                    const float* __restrict__ meanR, float* __restrict__ rowu2) {
+  const int64_t row = (int64_t)blockIdx.x * (BLK / 64) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const float* gr = g + row * cols;
+  float s = 0.f;
+  for (int64_t j = lane; j < cols; j += 64) s += gr[j] * gr[j] / Cst[j];
+  s = wave_sum(s);
+  if (lane == 0) rowu2[row] = s * (meanR[0] / R[row]);
+}
+
+// theta <- theta - lr wd theta - lr U / max(1, rms(U)), U_ij = G_ij sqrt(meanR / R_i) / sqrt(C_j); meanU2 = mean of U^2
+__global__ void __launch_bounds__(BLK) af_apply_k(int64_t rows, int64_t cols, float lr, float wd, const float* __restrict__ g,
+                                                   const float* __restrict__ R, const float* __restrict__ Cst,
+                                                   const float* __restrict__ meanR, const float* __restrict__ meanU2,
+                                                   float* __restrict__ master, bf16* __restrict__ cc) {
+  const int64_t idx = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (idx >= rows * cols) return;
+  const int64_t i = idx / cols, j = idx - i * cols;
+  const float rms = sqrtf(meanU2[0]);
+  const float step = lr / fmaxf(1.f, rms);
+  const float u = g[idx] * sqrtf(meanR[0] / R[i]) / sqrtf(Cst[j]);
+  float th = master[idx];
+  th -= lr * wd * th;
+  th -= step * u;
+  master[idx] = th;
+  if (cc) cc[idx] = from_f32<bf16>(th);
+}
+
+// vectors: V <- b2 V + (1 - b2)(G^2 + eps1); U = G / sqrt(V); one workgroup does the whole vector
+__global__ void __launch_bounds__(BLK) af_vec_k(int64_t n, float b2, float lr, float wd, const float* __restrict__ g,
+                                                 float* __restrict__ V, float* __restrict__ master, bf16* __restrict__ cc) {
+  __shared__ float red[BLK / 64];
+  __shared__ float bcast;
+  float s = 0.f;
+  for (int64_t i = threadIdx.x; i < n; i += BLK) {
+    const float v = b2 * V[i] + (1.f - b2) * (g[i] * g[i] + AF_EPS1);
+    V[i] = v;
+    s += g[i] * g[i] / v;
+  }
+  s = block_sum<BLK / 64>(s, red);
+  if (threadIdx.x == 0) bcast = s;
+  __syncthreads();
+  const float step = lr / fmaxf(1.f, sqrtf(bcast / (float)n));
+  for (int64_t i = threadIdx.x; i < n; i += BLK) {
+    float th = master[i];
+    th -= lr * wd * th;
+    th -= step * g[i] / sqrtf(V[i]);
+    master[i] = th;
+    if (cc) cc[i] = from_f32<bf16>(th);
+  }
+}
+
 #define LAUNCH_CHECK() return hipGetLastError()
 
 }  // namespace
@@ -851,6 +956,36 @@ hipError_t optimizer_update(const OptArgs& o, int64_t n, bool decay, int64_t t, 
   }
 #undef OPT_KIND
 #undef OPT_CALL
+  LAUNCH_CHECK();
+}
+
+size_t adafactor_work_floats(int64_t rows, int64_t cols) {
+  if (cols <= 1) return 0;
+  return (size_t)(cdiv(rows, AF_CHUNK) * cols + rows + 2);
+}
+
+hipError_t adafactor_update(double lr, double wd, bool decay, int64_t t, int64_t rows, int64_t cols, float* master,
+                            const float* grad, float* fac, float* work, void* cc, hipStream_t st) {
+  if (rows * cols == 0) return hipSuccess;
+  const float b2 = (float)(1.0 - pow((double)t, -0.8));
+  const float wdf = decay ? (float)wd : 0.f;
+  if (cols <= 1) {
+    af_vec_k<<<1, BLK, 0, st>>>(rows, b2, (float)lr, wdf, grad, fac, master, (bf16*)cc);
+    LAUNCH_CHECK();
+  }
+  float *R = fac, *Cst = fac + rows;
+  const int chunks = (int)cdiv(rows, AF_CHUNK);
+  float* partial = work;
+  float* rowu2 = work + (size_t)chunks * cols;
+  float* scal = rowu2 + rows;  // [0] mean of R, [1] mean of U^2
+  af_row_stats_k<<<dim3((unsigned)cdiv(rows, BLK / 64)), BLK, 0, st>>>(rows, cols, b2, grad, R);
+  af_col_part_k<<<dim3((unsigned)cdiv(cols, BLK), (unsigned)chunks), BLK, 0, st>>>(rows, cols, grad, partial);
+  af_col_final_k<<<dim3((unsigned)cdiv(cols, BLK)), BLK, 0, st>>>(rows, cols, chunks, b2, partial, Cst);
+  af_sum_k<<<1, BLK, 0, st>>>(rows, R, 1.0f / (float)rows, scal);
+  af_row_u2_k<<<dim3((unsigned)cdiv(rows, BLK / 64)), BLK, 0, st>>>(rows, cols, grad, R, Cst, scal, rowu2);
+  af_sum_k<<<1, BLK, 0, st>>>(rows, rowu2, (float)(1.0 / ((double)rows * (double)cols)), scal + 1);
+  af_apply_k<<<dim3((unsigned)cdiv(rows * cols, BLK)), BLK, 0, st>>>(rows, cols, (float)lr, wdf, grad, R, Cst, scal, scal + 1,
+                                                                      master, (bf16*)cc);
   LAUNCH_CHECK();
 }
 

@@ -87,4 +87,13 @@ hipError_t optimizer_update(const OptArgs& o, int64_t n, bool decay, int64_t t, 
                             const float* grad, float* s1, float* s2, void* compute_copy /* bf16 or null */,
                             hipStream_t st);
 
+// Adafactor on one tensor (Shazeer and Stern 2018, Algorithm 4 without momentum, external step
+// size; constants: epsilon_1 1e-30, clipping threshold 1, decay exponent 0.8).
+//   rows x cols matrix: fac = [R (rows) | C (cols)];  vector (cols == 1): fac = V (rows).
+//   work: floats, at least adafactor_work_floats(rows, cols).
+size_t adafactor_work_floats(int64_t rows, int64_t cols);
+hipError_t adafactor_update(double lr, double wd, bool decay, int64_t t, int64_t rows, int64_t cols, float* master,
+                            const float* grad, float* fac, float* work, void* compute_copy /* bf16 or null */,
+                            hipStream_t st);
+
 }  // namespace hift

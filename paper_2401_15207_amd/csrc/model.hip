@@ -50,6 +50,8 @@ struct Tensor {
   // byte offsets of the copies in MFMA fragment order inside the packed-weight arena, or -1:
   // pk_fwd packs w as [rows, cols] (forward, y = x . w^T), pk_bwd packs w^T (dX = dY . w)
   int64_t pk_fwd = -1, pk_bwd = -1;
+  int64_t fac_off = 0;  // Adafactor: first float of this tensor's statistics ([rows | cols], or [rows] for vectors)
+  int64_t fac_count() const { return cols > 1 ? rows + cols : rows; }
   int64_t count() const { return rows * cols; }
 };
 
@@ -173,12 +175,13 @@ void make_order(int k, int strategy, uint64_t seed, int32_t* out) {
 int n_state_of(const hift_opt& o) {
   if (o.kind == HIFT_ADAMW) return 2;
   if (o.kind == HIFT_ADAGRAD) return 1;
+  if (o.kind == HIFT_ADAFACTOR) return 0;  // factored statistics: a few numbers per row and column, kept in HBM
   return o.momentum > 0.0 ? 1 : 0;
 }
 
 hift_status check_opt(const hift_opt* o) {
   if (!o) return fail(HIFT_EINVAL, "optimizer is null");
-  if (o->kind < 0 || o->kind > 2) return fail(HIFT_EINVAL, "optimizer kind %d unknown", o->kind);
+  if (o->kind < 0 || o->kind > 3) return fail(HIFT_EINVAL, "optimizer kind %d unknown", o->kind);
   if (o->momentum < 0.0) return fail(HIFT_EINVAL, "momentum must be >= 0");
   return HIFT_OK;
 }
@@ -236,6 +239,10 @@ struct hift_model {
   void* wc = nullptr;  // weights the forward uses: bf16 copy, or the master itself in fp32 mode
   unsigned char* wpk = nullptr;  // copies of the large bf16 matrices in MFMA fragment order
   size_t wpk_bytes = 0;
+  float* fac = nullptr;      // Adafactor statistics of every tensor (resident: they are tiny)
+  float* af_work = nullptr;  // Adafactor reduction scratch
+  int64_t n_fac = 0;
+  size_t af_work_floats = 0;
   float* grad = nullptr;
   float* state_full = nullptr;  // [n_state][n_params] when state stays in HBM
   // State of the active group when the rest lives on the host: [n_state][grad_cap] each.  Three slots:
@@ -308,6 +315,12 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes, s
   } else if (M.n_state > 0) {
     b.cat = MEM_STATE;
     M.state_full = (float*)b.take((size_t)M.n_state * np * 4);
+  }
+  if (M.n_fac > 0) {
+    b.cat = MEM_STATE;
+    M.fac = (float*)b.take((size_t)M.n_fac * 4);
+    b.cat = MEM_WORK;
+    M.af_work = (float*)b.take(M.af_work_floats * 4);
   }
   b.cat = MEM_WORK;
   if (rms) M.cos_sin = (float*)b.take((size_t)c.max_seq * (d / H / 2) * 2 * 4);
@@ -387,6 +400,14 @@ hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_o
   M->on_host = cfg->state_on_host != 0;
   M->master_host = cfg->master_on_host != 0;
   M->n_move = M->n_state + (M->master_host ? 1 : 0);
+  M->n_fac = 0;
+  M->af_work_floats = 0;
+  if (opt->kind == HIFT_ADAFACTOR)
+    for (Tensor& t : M->lay.t) {
+      t.fac_off = M->n_fac;
+      M->n_fac += t.fac_count();
+      M->af_work_floats = std::max(M->af_work_floats, adafactor_work_floats(t.rows, t.cols));
+    }
   // Which matrices get copies in fragment order: those whose contraction, at the largest batch,
   // is one the packed-operand kernel takes.
   M->wpk_bytes = 0;
@@ -1104,6 +1125,7 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
   for (int q = 0; q < NSLOT; ++q)
     if (M->slot[q]) CR_TRY(fill_zero(M->slot[q], (size_t)M->n_move * M->grad_cap * 4, M->cs));
   CR_TRY(fill_zero(M->grad, (size_t)M->grad_cap * 4, M->cs));
+  if (M->fac) CR_TRY(fill_zero(M->fac, (size_t)M->n_fac * 4, M->cs));
   if (M->cos_sin) {
     const int hd2 = cfg->d_model / cfg->n_heads / 2;
     std::vector<float> tab((size_t)cfg->max_seq * hd2 * 2);
@@ -1263,11 +1285,17 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
   }
   {
     double bytes_per = M->n_state == 2 ? 28.0 : (M->n_state == 1 ? 20.0 : 12.0);
+    if (M->opt.kind == HIFT_ADAFACTOR) bytes_per = 24.0;  // the gradient is read four times (row, column, clipping, update)
     if (M->dt == DT_BF16) bytes_per += 2.0;
     Scope sc(M, CAT_OPT, bytes_per * cnt);
     for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
       const Tensor& t = M->lay.t[i];
       void* cc = M->dt == DT_BF16 ? (unsigned char*)M->wc + t.off * 2 : nullptr;
+      if (M->opt.kind == HIFT_ADAFACTOR) {
+        K_TRY(adafactor_update(M->opt.lr, M->opt.weight_decay, t.kind == HIFT_KIND_MATRIX, tg, t.rows, t.cols,
+                               mbase + t.off, M->grad + (t.off - plo), M->fac + t.fac_off, M->af_work, cc, M->cs));
+        continue;
+      }
       K_TRY(optimizer_update(oa, t.count(), t.kind == HIFT_KIND_MATRIX, tg, mbase + t.off,
                              M->grad + (t.off - plo), s1b ? s1b + (t.off - sbase) : nullptr,
                              (s2b && M->n_state == 2) ? s2b + (t.off - sbase) : nullptr, cc, M->cs));
@@ -1362,6 +1390,17 @@ hift_status hift_read_state(hift_model* M, int32_t ulo, int32_t uhi, int32_t slo
   } else {
     HIP_TRY(hipMemcpy(dst, M->state_full + (size_t)slot * M->lay.n_params + off, (size_t)cnt * 4, hipMemcpyDeviceToHost));
   }
+  return HIFT_OK;
+}
+
+hift_status hift_read_factored_state(hift_model* M, int32_t tensor_index, float* dst, size_t dst_count) {
+  if (!M || !dst) return fail(HIFT_EINVAL, "null argument");
+  if (!M->fac) return fail(HIFT_ESTATE, "the optimizer keeps no factored statistics");
+  if (tensor_index < 0 || tensor_index >= (int)M->lay.t.size()) return fail(HIFT_EINVAL, "tensor %d outside [0,%zu)", tensor_index, M->lay.t.size());
+  const Tensor& t = M->lay.t[tensor_index];
+  if ((int64_t)dst_count != t.fac_count()) return fail(HIFT_EINVAL, "buffer holds %zu floats, the tensor has %lld statistics", dst_count, (long long)t.fac_count());
+  ST_TRY(sync_all(M));
+  HIP_TRY(hipMemcpy(dst, M->fac + t.fac_off, (size_t)t.fac_count() * 4, hipMemcpyDeviceToHost));
   return HIFT_OK;
 }
 
@@ -1471,6 +1510,7 @@ hift_status hift_kernel_optimizer(const hift_opt* opt, int64_t count, int32_t de
   hift_status s = check_opt(opt);
   if (s != HIFT_OK) return s;
   if (count < 0 || t < 1) return fail(HIFT_EINVAL, "count must be >= 0 and t >= 1");
+  if (opt->kind == HIFT_ADAFACTOR) return fail(HIFT_EINVAL, "Adafactor works on whole tensors; it has no element-wise kernel entry");
   OptArgs oa{opt->kind, opt->lr, opt->beta1, opt->beta2, opt->eps, opt->weight_decay, opt->momentum};
   HIP_TRY(optimizer_update(oa, count, decay != 0, t, master, grad, state1, state2, compute_copy, (hipStream_t)stream));
   return HIFT_OK;

@@ -110,6 +110,16 @@ def test_memory_report(H):
         H.memory_report(dict(cfg, dtype=0, state_on_host=1, master_on_host=1), wl["opt"], 1, 4, 512)
 
 
+def test_adafactor_keeps_a_few_numbers_per_row_and_column(H):
+    wl = WORKLOADS["C4"]
+    cfg = model_config(wl)
+    af = dict(kind="adafactor", lr=1e-3, weight_decay=0.0)
+    r = H.memory_report(dict(cfg, state_on_host=1), af, 1, 4, 512)
+    want = sum((s[0] + s[1]) if len(s) >= 2 else s[0] for _n, s, _k, _u in O.param_tensors(cfg))
+    assert 4 * want <= r["sta"] < 4 * want + 4096 and r["pinned_total"] == 0
+    assert r["sta"] < 1e-3 * r["device_master"]          # against 2 x the weights for AdamW
+
+
 def test_argument_errors_without_a_gpu(H):
     import ctypes as C
     from paper_2401_15207_amd import binding as B
