@@ -164,6 +164,10 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--copy-engine", type=int, default=0, help="0 hipMemcpyAsync, 1 small-grid copy kernel")
     ap.add_argument("--copy-blocks", type=int, default=16)
+    ap.add_argument("--m", type=int, default=0,
+                    help="units per group (default: the workload's); the number of units gives one group, "
+                         "i.e. a full fine-tuning step on the same kernels")
+    ap.add_argument("--state-resident", action="store_true", help="keep all optimizer state in HBM")
     ap.add_argument("--master-on-host", action="store_true",
                     help="park the fp32 master of inactive groups in pinned memory too (small-memory mode)")
     ap.add_argument("--no-packed-copies", action="store_true",
@@ -188,7 +192,9 @@ def main():
     cfg = model_config(wl)
     B, S = wl["batch"], wl["seq"]
     t_setup = time.perf_counter()
-    model = H.HiftModel(cfg, wl["opt"], wl["m"], B, S, init_params=None, state_on_host=1,
+    if a.m > 0:
+        wl = dict(wl, m=a.m)
+    model = H.HiftModel(cfg, wl["opt"], wl["m"], B, S, init_params=None, state_on_host=0 if a.state_resident else 1,
                         master_on_host=int(a.master_on_host), no_packed_copies=int(a.no_packed_copies))
     mem = model.memory()
     model.set_state_copy_engine(a.copy_engine, a.copy_blocks)
@@ -255,8 +261,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload}: LLaMA-7B-shaped decoder, 32 layers d=4096 h=32 ffn=11008 vocab=32000, "
-                               f"batch {B} x seq {S}, m=1 ({k} groups), bottom2up, AdamW, optimizer state of "
-                               f"inactive groups in pinned host memory" if a.workload == "C4" else a.workload,
+                               f"batch {B} x seq {S}, m={wl['m']} ({k} groups), bottom2up, AdamW, optimizer state "
+                               + ("resident in HBM" if a.state_resident else "of inactive groups in pinned host memory")
+                               if a.workload == "C4" else a.workload,
                    "groups": k, "tokens_per_step": B * S},
         "roofline": {
             "bound": "mfma",

@@ -170,6 +170,23 @@ def group_units(n: int, m: int, j: int):
     return list(range(j * m, min((j + 1) * m, n)))
 
 
+def lr_at_cycle(kind: str, base_lr: float, warmup_cycles: int, total_cycles: int, cycle: int) -> float:
+    """Learning rate in force during cycle `cycle` (0-based count of completed sweeps over all groups).
+    The delayed update strategy (section 3, "delayed learning rate update") advances the scheduler once per
+    sweep instead of once per step, so the usual schedules are evaluated at the cycle index:
+      constant: base_lr
+      linear:   base_lr * cycle / warmup_cycles                       while cycle < warmup_cycles
+                base_lr * max(0, (total - cycle) / (total - warmup))  afterwards (the warm-up/linear-decay
+                schedule of the paper's hyper-parameter tables)."""
+    if kind == "constant":
+        return base_lr
+    if kind != "linear":
+        raise ValueError("unknown schedule")
+    if cycle < warmup_cycles:
+        return base_lr * cycle / max(1, warmup_cycles)
+    return base_lr * max(0.0, (total_cycles - cycle) / max(1, total_cycles - warmup_cycles))
+
+
 def splitmix64(state: int):
     """One draw of the SplitMix64 generator (Steele, Lea, Flood 2014): returns (value, new state)."""
     mask = (1 << 64) - 1

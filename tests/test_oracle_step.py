@@ -219,3 +219,32 @@ def test_adafactor_in_the_hift_loop_keeps_other_groups_frozen():
     total = sum(sum(v.size for v in st.values()) for st in o.factored.values())
     want = sum((s[0] + s[1]) if len(s) >= 2 else s[0] for _n, s, _k in SPEC)
     assert total == want
+
+
+def test_cycle_indexed_linear_schedule_against_the_transformers_scheduler():
+    """One scheduler step per sweep: the rate of cycle c is what the standard warm-up / linear-decay
+    scheduler gives after c steps."""
+    import torch
+    from transformers import get_linear_schedule_with_warmup
+    p = torch.nn.Parameter(torch.zeros(1))
+    opt = torch.optim.SGD([p], lr=3e-5)
+    sch = get_linear_schedule_with_warmup(opt, num_warmup_steps=3, num_training_steps=11)
+    for c in range(13):
+        assert abs(O.lr_at_cycle("linear", 3e-5, 3, 11, c) - sch.get_last_lr()[0]) <= 1e-18, c
+        opt.step()
+        sch.step()
+    assert O.lr_at_cycle("constant", 0.1, 3, 11, 7) == 0.1
+    assert O.lr_at_cycle("linear", 1.0, 0, 4, 0) == 1.0 and O.lr_at_cycle("linear", 1.0, 0, 4, 4) == 0.0
+
+
+def test_rate_is_constant_inside_a_cycle_under_the_schedule():
+    o, _ = _fresh(dict(kind="sgd", lr=0.0, momentum=0.0, weight_decay=0.0))
+    k = o.set_group_schedule("bottom2up", 1, 0)
+    seen = []
+    for t in range(1, 3 * k + 1):
+        o.set_lr(O.lr_at_cycle("linear", 1e-2, 1, 3, o.cycles_done))
+        seen.append(o.opt["lr"])
+        tok, lab = make_batch(WL, 1, t)
+        o.step(tok, lab, o.schedule_group_at(t))
+    assert all(len(set(seen[c * k:(c + 1) * k])) == 1 for c in range(3))
+    assert seen[0] == 0.0 and seen[k] == 1e-2 and abs(seen[2 * k] - 0.5e-2) < 1e-18
