@@ -209,6 +209,32 @@ hift_status hift_step(hift_model* mdl, const hift_batch* batch, int32_t group_id
 /* Learning rate used by following steps.  The caller applies its schedule when
  * hift_cycle_index changes (Algorithm 1: the rate moves only after all layers were updated). */
 hift_status hift_set_lr(hift_model* mdl, double lr);
+/* Delayed learning-rate update (section 3): the rate changes only after every group has been updated
+ * once, i.e. the scheduler advances once per sweep.  Rate in force during cycle c (c = completed sweeps):
+ * HIFT_LR_CONSTANT: base_lr.  HIFT_LR_LINEAR (warm-up then linear decay, the schedule of the paper's
+ * hyper-parameter tables): base_lr c / warmup while c < warmup, afterwards
+ * base_lr max(0, (total - c) / (total - warmup)).  hift_lr_at_cycle is a pure host helper. */
+enum { HIFT_LR_CONSTANT = 0, HIFT_LR_LINEAR = 1 };
+hift_status hift_lr_at_cycle(int32_t kind, double base_lr, int64_t warmup_cycles, int64_t total_cycles,
+                             int64_t cycle, double* lr_out);
+hift_status hift_set_lr_schedule(hift_model* mdl, int32_t kind, double base_lr, int64_t warmup_cycles,
+                                 int64_t total_cycles);
+/* n_steps steps of Algorithm 1, continuing from the model's step count: the i-th step of this call
+ * takes batches[i mod n_batches], the group the schedule visits next, and, if a schedule was set with
+ * hift_set_lr_schedule, the rate of its cycle.  batches: host array of descriptors of device buffers.
+ * losses_out: host, n_steps floats, or null (then no step waits for the GPU). */
+hift_status hift_train(hift_model* mdl, const hift_batch* batches, int32_t n_batches, int64_t n_steps,
+                       float* losses_out);
+/* Checkpoint: step count, visiting order, per-group update counts, learning-rate schedule, fp32 master
+ * weights, optimizer state of every group (wherever it lives) and Adafactor statistics, into / out of a
+ * host buffer of hift_checkpoint_bytes bytes.  A run that loads a checkpoint into a model created with
+ * the same configuration, optimizer kind and buffer sizes continues exactly as the saved one would have
+ * (bit-identical as long as the embeddings unit is not updated: its gradient is summed with atomics).
+ * Both calls wait for the streams.  Errors: HIFT_EINVAL for a foreign or mismatching checkpoint,
+ * HIFT_ENOMEM for a short buffer. */
+hift_status hift_checkpoint_bytes(const hift_model* mdl, size_t* bytes);
+hift_status hift_checkpoint_save(hift_model* mdl, void* host_buffer, size_t bytes);
+hift_status hift_checkpoint_load(hift_model* mdl, const void* host_buffer, size_t bytes);
 /* Steps taken since the schedule was set, and completed sweeps floor(t / k). */
 hift_status hift_cycle_index(const hift_model* mdl, int64_t* steps_done, int64_t* cycles_done);
 

@@ -67,6 +67,12 @@ _SIGS = {
     "hift_query_bytes": [_P(Config), _P(Opt), _i32, _i32, _i32, _P(_sz), _P(_sz)],
     "hift_memory_report": [_P(Config), _P(Opt), _i32, _i32, _i32, _P(Memory)],
     "hift_read_factored_state": [_vp, _i32, _vp, _sz],
+    "hift_lr_at_cycle": [_i32, C.c_double, _i64, _i64, _i64, _P(C.c_double)],
+    "hift_set_lr_schedule": [_vp, _i32, C.c_double, _i64, _i64],
+    "hift_train": [_vp, _P(Batch), _i32, _i64, _vp],
+    "hift_checkpoint_bytes": [_vp, _P(_sz)],
+    "hift_checkpoint_save": [_vp, _vp, _sz],
+    "hift_checkpoint_load": [_vp, _vp, _sz],
     "hift_model_create": [_P(Config), _P(Opt), _i32, _i32, _i32, _vp, _vp, _sz, _vp, _sz, _vp, _vp, _vp, _P(_vp)],
     "hift_set_group_schedule": [_vp, C.c_int, _i32, _u64, _P(_i32)],
     "hift_schedule_group_at": [_vp, _i64, _P(_i32)],
@@ -139,6 +145,15 @@ def tensor_list(cfg: dict):
         shape = (t.rows, t.cols) if t.kind == 0 else (t.rows,)
         out.append((t.name.decode(), shape, t.kind, t.unit, t.offset))
     return out, total.value
+
+
+LR_KIND = {"constant": 0, "linear": 1}
+
+
+def lr_at_cycle(kind: str, base_lr: float, warmup_cycles: int, total_cycles: int, cycle: int) -> float:
+    out = C.c_double()
+    _check(lib.hift_lr_at_cycle(LR_KIND[kind], base_lr, warmup_cycles, total_cycles, cycle, C.byref(out)))
+    return out.value
 
 
 def memory_report(cfg: dict, opt: dict, m: int, max_batch: int, max_seq: int) -> dict:
@@ -361,6 +376,29 @@ class HiftModel:
 
     def profile_enable(self, on: bool):
         _check(lib.hift_profile_enable(self.h, int(on)))
+
+    def set_lr_schedule(self, kind: str, base_lr: float, warmup_cycles: int, total_cycles: int):
+        _check(lib.hift_set_lr_schedule(self.h, LR_KIND[kind], base_lr, warmup_cycles, total_cycles))
+
+    def train(self, batches, n_steps: int, want_losses: bool = True):
+        """batches: list of (tokens, labels) device tensors; returns the losses (or None)."""
+        arr = (Batch * len(batches))()
+        for i, (tok, lab) in enumerate(batches):
+            arr[i] = Batch(tok.data_ptr(), lab.data_ptr(), tok.shape[0], tok.shape[1])
+        losses = np.empty(n_steps, dtype=np.float32) if want_losses else None
+        _check(lib.hift_train(self.h, arr, len(batches), n_steps, None if losses is None else losses.ctypes.data))
+        return losses
+
+    def checkpoint_save(self) -> np.ndarray:
+        n = _sz()
+        _check(lib.hift_checkpoint_bytes(self.h, C.byref(n)))
+        buf = np.empty(n.value, dtype=np.uint8)
+        _check(lib.hift_checkpoint_save(self.h, buf.ctypes.data, buf.size))
+        return buf
+
+    def checkpoint_load(self, buf: np.ndarray):
+        buf = np.ascontiguousarray(buf, dtype=np.uint8)
+        _check(lib.hift_checkpoint_load(self.h, buf.ctypes.data, buf.size))
 
     def read_factored_state(self, tensor_index: int) -> np.ndarray:
         _name, shape, _kind, _unit, _off = self.tensors[tensor_index]

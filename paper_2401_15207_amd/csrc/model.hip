@@ -271,6 +271,10 @@ struct hift_model {
   std::vector<int32_t> order;
   std::vector<int64_t> group_steps;
   int64_t t = 0;
+  // learning-rate schedule evaluated at the cycle index (used by hift_train)
+  int lr_kind = -1;  // -1: none set, the rate is whatever hift_set_lr left
+  double lr_base = 0.0;
+  int64_t lr_warmup = 0, lr_total = 0;
   uint64_t h2d_bytes = 0, d2h_bytes = 0;
   bool timed = false;
   int copy_engine = 0;   // 0: hipMemcpyAsync, 1: small-grid copy kernel
@@ -1212,6 +1216,132 @@ hift_status hift_group_units(const hift_model* M, int32_t gid, int32_t* unit_lo,
 hift_status hift_set_lr(hift_model* M, double lr) {
   if (!M) return fail(HIFT_EINVAL, "model is null");
   M->opt.lr = lr;
+  return HIFT_OK;
+}
+
+hift_status hift_lr_at_cycle(int32_t kind, double base_lr, int64_t warmup, int64_t total, int64_t cycle, double* lr_out) {
+  if (!lr_out) return fail(HIFT_EINVAL, "lr_out is null");
+  if (kind != HIFT_LR_CONSTANT && kind != HIFT_LR_LINEAR) return fail(HIFT_EINVAL, "schedule kind %d unknown", kind);
+  if (warmup < 0 || total < 0 || cycle < 0) return fail(HIFT_EINVAL, "warm-up, total and cycle must be >= 0");
+  if (kind == HIFT_LR_CONSTANT) {
+    *lr_out = base_lr;
+  } else if (cycle < warmup) {
+    *lr_out = base_lr * (double)cycle / (double)std::max<int64_t>(1, warmup);
+  } else {
+    *lr_out = base_lr * std::max(0.0, (double)(total - cycle) / (double)std::max<int64_t>(1, total - warmup));
+  }
+  return HIFT_OK;
+}
+
+hift_status hift_set_lr_schedule(hift_model* M, int32_t kind, double base_lr, int64_t warmup_cycles, int64_t total_cycles) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  double probe;
+  ST_TRY(hift_lr_at_cycle(kind, base_lr, warmup_cycles, total_cycles, 0, &probe));
+  M->lr_kind = kind;
+  M->lr_base = base_lr;
+  M->lr_warmup = warmup_cycles;
+  M->lr_total = total_cycles;
+  return HIFT_OK;
+}
+
+hift_status hift_train(hift_model* M, const hift_batch* batches, int32_t n_batches, int64_t n_steps, float* losses_out) {
+  if (!M || !batches) return fail(HIFT_EINVAL, "null argument");
+  if (M->k == 0) return fail(HIFT_ESTATE, "no schedule set");
+  if (n_batches < 1 || n_steps < 0) return fail(HIFT_EINVAL, "n_batches must be >= 1 and n_steps >= 0");
+  for (int64_t i = 0; i < n_steps; ++i) {
+    if (M->lr_kind >= 0) {  // the rate moves only when a sweep over all groups is complete
+      double lr;
+      ST_TRY(hift_lr_at_cycle(M->lr_kind, M->lr_base, M->lr_warmup, M->lr_total, M->t / M->k, &lr));
+      M->opt.lr = lr;
+    }
+    const int32_t gid = M->order[M->t % M->k];
+    ST_TRY(hift_step(M, &batches[i % n_batches], gid, losses_out ? losses_out + i : nullptr));
+  }
+  return HIFT_OK;
+}
+
+// ---- checkpoint: everything a run needs to continue as if it had not stopped ----
+namespace {
+struct CkptHeader {
+  char magic[8];
+  int64_t n_params, n_fac, t;
+  int32_t version, n_state, k, m, lr_kind, opt_kind;
+  double lr, lr_base;
+  int64_t lr_warmup, lr_total;
+};
+constexpr char CKPT_MAGIC[8] = {'H', 'I', 'F', 'T', 'C', 'K', 'P', '1'};
+
+size_t ckpt_bytes(const hift_model* M) {
+  return sizeof(CkptHeader) + (size_t)M->k * (4 + 8) +
+         ((size_t)M->lay.n_params * (1 + M->n_state) + (size_t)M->n_fac) * 4;
+}
+}  // namespace
+
+hift_status hift_checkpoint_bytes(const hift_model* M, size_t* bytes) {
+  if (!M || !bytes) return fail(HIFT_EINVAL, "null argument");
+  if (M->k == 0) return fail(HIFT_ESTATE, "no schedule set");
+  *bytes = ckpt_bytes(M);
+  return HIFT_OK;
+}
+
+hift_status hift_checkpoint_save(hift_model* M, void* host_buffer, size_t bytes) {
+  if (!M || !host_buffer) return fail(HIFT_EINVAL, "null argument");
+  if (M->k == 0) return fail(HIFT_ESTATE, "no schedule set");
+  if (bytes < ckpt_bytes(M)) return fail(HIFT_ENOMEM, "buffer holds %zu bytes, the checkpoint needs %zu", bytes, ckpt_bytes(M));
+  ST_TRY(sync_all(M));  // every write-back has landed: the host copies of state (and master) are current
+  unsigned char* p = reinterpret_cast<unsigned char*>(host_buffer);
+  CkptHeader h{};
+  memcpy(h.magic, CKPT_MAGIC, 8);
+  h.n_params = M->lay.n_params; h.n_fac = M->n_fac; h.t = M->t;
+  h.version = 1; h.n_state = M->n_state; h.k = M->k; h.m = M->m; h.lr_kind = M->lr_kind; h.opt_kind = M->opt.kind;
+  h.lr = M->opt.lr; h.lr_base = M->lr_base; h.lr_warmup = M->lr_warmup; h.lr_total = M->lr_total;
+  memcpy(p, &h, sizeof(h)); p += sizeof(h);
+  memcpy(p, M->order.data(), (size_t)M->k * 4); p += (size_t)M->k * 4;
+  memcpy(p, M->group_steps.data(), (size_t)M->k * 8); p += (size_t)M->k * 8;
+  const size_t np4 = (size_t)M->lay.n_params * 4;
+  if (M->master_host) memcpy(p, M->host_master, np4);
+  else HIP_TRY(hipMemcpy(p, M->master, np4, hipMemcpyDeviceToHost));
+  p += np4;
+  for (int j = 0; j < M->n_state; ++j, p += np4) {
+    if (M->on_host) memcpy(p, M->host_state + (size_t)j * M->lay.n_params, np4);
+    else HIP_TRY(hipMemcpy(p, M->state_full + (size_t)j * M->lay.n_params, np4, hipMemcpyDeviceToHost));
+  }
+  if (M->n_fac) HIP_TRY(hipMemcpy(p, M->fac, (size_t)M->n_fac * 4, hipMemcpyDeviceToHost));
+  return HIFT_OK;
+}
+
+hift_status hift_checkpoint_load(hift_model* M, const void* host_buffer, size_t bytes) {
+  if (!M || !host_buffer) return fail(HIFT_EINVAL, "null argument");
+  if (bytes < sizeof(CkptHeader)) return fail(HIFT_EINVAL, "buffer too small for a checkpoint header");
+  const unsigned char* p = reinterpret_cast<const unsigned char*>(host_buffer);
+  CkptHeader h;
+  memcpy(&h, p, sizeof(h)); p += sizeof(h);
+  if (memcmp(h.magic, CKPT_MAGIC, 8) != 0 || h.version != 1) return fail(HIFT_EINVAL, "not a checkpoint of this library");
+  if (h.n_params != M->lay.n_params || h.n_state != M->n_state || h.n_fac != M->n_fac || h.opt_kind != M->opt.kind)
+    return fail(HIFT_EINVAL, "checkpoint is of another model or optimizer (%lld parameters, %d state arrays)",
+                (long long)h.n_params, h.n_state);
+  if (h.k < 1 || h.m < 1 || h.k != group_count(M->lay.n_units, h.m) || largest_group(M->lay, h.m) > M->grad_cap)
+    return fail(HIFT_EINVAL, "checkpoint grouping (m = %d, k = %d) does not fit this model's buffers", h.m, h.k);
+  const size_t np4 = (size_t)M->lay.n_params * 4;
+  const size_t need = sizeof(CkptHeader) + (size_t)h.k * 12 + np4 * (1 + (size_t)M->n_state) + (size_t)M->n_fac * 4;
+  if (bytes < need) return fail(HIFT_EINVAL, "buffer holds %zu bytes, the checkpoint has %zu", bytes, need);
+  ST_TRY(sync_all(M));
+  M->m = h.m; M->k = h.k; M->t = h.t;
+  M->order.resize(h.k);
+  memcpy(M->order.data(), p, (size_t)h.k * 4); p += (size_t)h.k * 4;
+  M->group_steps.resize(h.k);
+  memcpy(M->group_steps.data(), p, (size_t)h.k * 8); p += (size_t)h.k * 8;
+  for (int i = 0; i < h.k; ++i)
+    if (M->order[i] < 0 || M->order[i] >= h.k) return fail(HIFT_EINVAL, "checkpoint order is damaged");
+  M->opt.lr = h.lr; M->lr_kind = h.lr_kind; M->lr_base = h.lr_base; M->lr_warmup = h.lr_warmup; M->lr_total = h.lr_total;
+  ST_TRY(hift_write_params(M, 0, M->lay.n_units, reinterpret_cast<const float*>(p), (size_t)M->lay.n_params));
+  p += np4;
+  for (int j = 0; j < M->n_state; ++j, p += np4) {
+    if (M->on_host) memcpy(M->host_state + (size_t)j * M->lay.n_params, p, np4);
+    else HIP_TRY(hipMemcpy(M->state_full + (size_t)j * M->lay.n_params, p, np4, hipMemcpyHostToDevice));
+  }
+  if (M->n_fac) HIP_TRY(hipMemcpy(M->fac, p, (size_t)M->n_fac * 4, hipMemcpyHostToDevice));
+  for (int& g : M->slot_group) g = -1;  // whatever the slots hold is stale
   return HIFT_OK;
 }
 
