@@ -229,7 +229,7 @@ hift_status hift_train(hift_model* mdl, const hift_batch* batches, int32_t n_bat
  * weights, optimizer state of every group (wherever it lives) and Adafactor statistics, into / out of a
  * host buffer of hift_checkpoint_bytes bytes.  A run that loads a checkpoint into a model created with
  * the same configuration, optimizer kind and buffer sizes continues exactly as the saved one would have
- * (bit-identical as long as the embeddings unit is not updated: its gradient is summed with atomics).
+ * (bit-identical: no kernel of the step sums in an order that depends on timing).
  * Both calls wait for the streams.  Errors: HIFT_EINVAL for a foreign or mismatching checkpoint,
  * HIFT_ENOMEM for a short buffer. */
 hift_status hift_checkpoint_bytes(const hift_model* mdl, size_t* bytes);

@@ -45,8 +45,7 @@ def test_train_loop_with_linear_schedule_follows_the_oracle(optk):
     orc2, gpu2, _ = make_pair(SMALL2, seed=31, opt=opt, strategy="bottom2up", jitter=0.02, state_on_host=1)
     gpu2.set_lr_schedule("linear", base, warm, total)
     assert gpu2.train(dev, n, want_losses=False) is None
-    assert np.array_equal(gpu2.read_params()[orc.units[1][0]:], gpu.read_params()[orc.units[1][0]:]) or \
-        rel_l2(gpu2.read_params(), gpu.read_params()) <= 1e-6       # embeddings: atomically summed gradient
+    assert np.array_equal(gpu2.read_params(), gpu.read_params())   # no kernel sums in a timing-dependent order
 
 
 def test_rate_zero_sweep_changes_nothing():
@@ -68,11 +67,11 @@ def test_checkpoint_resume_continues_bit_identically(optk, on_host):
     a.set_lr_schedule("linear", 1e-3, 1, 6)
     a.train(dev, k + 1, want_losses=False)              # one sweep and the head again
     ckpt = a.checkpoint_save()
-    la = a.train(dev, k - 2)                            # layer 1, layer 0: the embeddings stay untouched
+    la = a.train(dev, k + 1)                            # through the embeddings and round again
     _o, b, _t = make_pair(SMALL2, seed=34, opt=opt, strategy="bottom2up", state_on_host=on_host)   # other weights, other order
     b.checkpoint_load(ckpt)
     assert b.cycle_index() == (k + 1, 1) and [b.schedule_group_at(t) for t in range(1, k + 1)] == list(range(k - 1, -1, -1))
-    lb = b.train(dev, k - 2)
+    lb = b.train(dev, k + 1)
     assert np.array_equal(la, lb)
     assert np.array_equal(a.read_params(), b.read_params())
     if optk == "adamw":
