@@ -324,6 +324,13 @@ hift_status hift_kernel_optimizer(const hift_opt* opt, int64_t count, int32_t de
                                   float* master, const float* grad, float* state1, float* state2,
                                   void* compute_copy, void* stream);
 
+/* Attention forward, fused (section 3 forward, step h of Algorithm 1, for one layer): bf16 only.
+ * qkv: device [batch*seq, 3*heads*head_dim], row = q | k | v of all heads side by side (already rotated
+ * where the architecture rotates).  prob: device [batch, heads, seq, seq] bf16, written completely
+ * (zeros where masked).  ctx: device [batch*seq, heads*head_dim].  head_dim 64 or 128.  scale is
+ * 1/sqrt(head_dim); causal != 0 masks keys after the query. */
+hift_status hift_kernel_attention_fwd(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
+                                      const void* qkv, void* prob, void* ctx, void* stream);
 /* y = norm(x) * g (+ b) over rows of width d; rms = 1: RMSNorm (b ignored).  stats: fp32 [rows,2]
  * receives mean (0 for RMSNorm) and reciprocal standard deviation. */
 hift_status hift_kernel_norm_fwd(int32_t dtype, int32_t rms, int64_t rows, int32_t d, float eps,

@@ -95,6 +95,7 @@ _SIGS = {
     "hift_kernel_gemm_packed": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp],
     "hift_kernel_optimizer": [_P(Opt), _i64, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_norm_fwd": [_i32, _i32, _i64, _i32, C.c_float, _vp, _vp, _vp, _vp, _vp, _vp],
+    "hift_kernel_attention_fwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
     "hift_kernel_cross_entropy": [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp],
 }
 for _n, _a in _SIGS.items():
@@ -212,6 +213,12 @@ def kernel_norm_fwd(dtype, rms, rows, d, eps, x, g, b, y, stats, stream=None):
     import torch
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib.hift_kernel_norm_fwd(dtype, int(rms), rows, d, eps, _ptr(x), _ptr(g), _ptr(b), _ptr(y), _ptr(stats), st))
+
+
+def kernel_attention_fwd(batch, heads, seq, head_dim, causal, qkv, prob, ctx, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_attention_fwd(batch, heads, seq, head_dim, int(causal), _ptr(qkv), _ptr(prob), _ptr(ctx), st))
 
 
 def kernel_cross_entropy(dtype, rows, V, logits, labels, row_loss, loss_out, stream=None):

@@ -1,0 +1,364 @@
+// Fused attention forward for gfx950: scores, softmax and the product with V in one kernel; the
+// scores never reach HBM.  The probabilities do (bf16, [B, H, S, S]): the backward pass reads them.
+//
+// One workgroup = 32 NW query rows of one (batch, head), NW = 2 or 4 wavefronts; each wavefront owns
+// 32 rows from start to end, so the softmax of a row never leaves its wavefront.  Keys and values pass
+// through LDS in tiles of 64 keys; the next tile is on its way from HBM (in registers) while the
+// current one is used.  Two passes over the keys: the first finds each row's maximum and
+// normaliser (online), the second recomputes the scores, writes the normalised probabilities and
+// accumulates P.V from the bf16-rounded probabilities, which is exactly what separate softmax and
+// contraction kernels compute.
+//
+// MFMA (v_mfma_f32_32x32x16_bf16) conventions, as in gemm.hip: an operand fragment gives lane l row
+// l%32 and the eight k-values 8*(l/32)..+7; acc = mfma(X, Y, acc) leaves in lane l, element e the
+// entry (Y row l%32, X row 8*(e/4) + 4*(l/32) + e%4).
+//   scores: Y = Q rows, X = K rows.  The K rows of a 32-key block are fed in the order
+//   pi(r) = r with bits 2 and 3 swapped; then element e of lane l is key 16*(e/8) + 8*(l/32) + e%8 of
+//   the block: elements 0..7 and 8..15 are, as they lie in registers, the two operand fragments of
+//   P for the next product, and 16 contiguous bytes of a probability row each.
+//   P.V: Y = P (rows = queries, k = keys), X = V^T (rows = head columns, k = keys), read from the
+//   row-major V tile with transposing LDS reads (ds_read_b64_tr_b16: lane i of a group of 16 gets,
+//   as element e, what lane i/4 + 4e of the group addressed as its element i%4).
+#include <type_traits>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace hift {
+namespace {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+
+constexpr int KTILE = 64;  // keys per LDS tile
+
+__device__ __forceinline__ int pi_row(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+// 16 bytes per lane straight from memory into LDS: M0 carries the LDS address of lane 0's piece, lane l
+// lands 16 l bytes further; reads past the buffer's end deliver zeros.
+__device__ __forceinline__ void dma_b128(u32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+               : "memory");
+}
+
+// LDS tiles are [64 keys][HD] bf16 without padding; the 16-byte piece c of row r sits at piece position
+// c ^ swz(r), which spreads both the fragment reads (sixteen rows, one piece) and the transposing
+// reads over the banks.  A tile is filled by loads that write 1 KB of consecutive LDS bytes each, so
+// the swizzle is applied by choosing which piece of its row a lane fetches.
+template <int HD, bool CAUSAL, int NW>
+__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_fwd_k(const bf16* __restrict__ qkv, int64_t ld, int S, int H, int BH, float scale_log2e,
+                                                       bf16* __restrict__ prob, bf16* __restrict__ ctx, int64_t ldc) {
+  constexpr int QB = 32 * NW;       // query rows per workgroup
+  constexpr int ROWB = HD * 2;      // bytes per LDS row
+  constexpr int PPR = HD / 8;       // 16-byte pieces per row: 16 or 8
+  constexpr int TILEB = KTILE * ROWB;
+  constexpr int KS = HD / 16;       // k-steps of a score block
+  constexpr int NB = HD / 32;       // 32-column blocks of the output
+  constexpr int IPW = KTILE * PPR / 64 / NW;  // load instructions per wavefront and tile
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * TILEB];  // [buffer][K | V]
+  auto swz = [](int r) { return PPR == 16 ? (r & 15) : ((r >> 1) & 7); };
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int fr = lane & 31, fh = lane >> 5;
+  // Causal rows get longer towards the end of the sequence.  Workgroups are handed out in the order of
+  // their index, two fit a compute unit: the first half of the grid takes the long row blocks, the second
+  // half their short counterparts, so that the two that share a compute unit add up to the same work.
+  const int nqb = (S + QB - 1) / QB;
+  int bh, qb;
+  if (CAUSAL) {
+    const int n_long = (nqb + 1) / 2, n_short = nqb - n_long;
+    const int L = (int)blockIdx.x, first = n_long * BH;
+    if (L < first) {
+      bh = L / n_long;
+      qb = nqb - 1 - L % n_long;
+    } else {
+      bh = (L - first) / n_short;
+      qb = (L - first) % n_short;
+    }
+  } else {
+    bh = (int)blockIdx.x / nqb;
+    qb = (int)blockIdx.x % nqb;
+  }
+  const int b = bh / H, h = bh % H;
+  const int64_t d = (int64_t)H * HD;
+  const bf16* q = qkv + (int64_t)b * S * ld + (int64_t)h * HD;
+  const bf16* k = q + d;
+  const bf16* v = q + 2 * d;
+  bf16* P = prob + (int64_t)bh * S * S;
+  bf16* O = ctx + (int64_t)b * S * ldc + (int64_t)h * HD;
+
+  const int q0 = qb * QB + wave * 32;  // this wavefront's first row
+  const int row = q0 + fr;
+  const bool row_ok = row < S;
+
+  bf16x8 qf[KS];  // Q fragments of the wavefront's 32 rows
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    u32x4 t = {0u, 0u, 0u, 0u};
+    if (row_ok) t = *reinterpret_cast<const u32x4*>(q + (int64_t)row * ld + ks * 16 + fh * 8);
+    qf[ks] = __builtin_bit_cast(bf16x8, t);
+  }
+
+  const int last_row = min(S, qb * QB + QB) - 1;
+  const int n_tiles = CAUSAL ? last_row / KTILE + 1 : (S + KTILE - 1) / KTILE;  // key tiles with unmasked keys
+  const int all_tiles = (S + KTILE - 1) / KTILE;
+
+  // tile loads
+  const uint32_t rec = (uint32_t)((((int64_t)S - 1) * ld + HD) * 2);  // bytes of K (or V) of this head from its first row
+  const uint64_t ka = reinterpret_cast<uint64_t>(k), va = reinterpret_cast<uint64_t>(v);
+  const u32x4 rsK = {(uint32_t)ka, (uint32_t)(ka >> 32) & 0xFFFFu, rec, 0x00020000u};
+  const u32x4 rsV = {(uint32_t)va, (uint32_t)(va >> 32) & 0xFFFFu, rec, 0x00020000u};
+  uint32_t vo[IPW];
+#pragma unroll
+  for (int jj = 0; jj < IPW; ++jj) {
+    const int pc = (wave * IPW + jj) * 64 + lane, r = pc / PPR, c = (pc % PPR) ^ swz(r);
+    vo[jj] = (uint32_t)((r * ld + c * 8) * 2);
+  }
+  const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(lds);
+  auto request = [&](int kt, bool with_v) __attribute__((always_inline)) {
+    const uint32_t so = (uint32_t)((int64_t)kt * KTILE * ld * 2);
+    const uint32_t dst = lds0 + (uint32_t)(kt & 1) * (2 * TILEB) + (uint32_t)wave * (IPW * 1024);
+#pragma unroll
+    for (int jj = 0; jj < IPW; ++jj) dma_b128(rsK, dst + jj * 1024, vo[jj], so);
+    if (with_v) {
+#pragma unroll
+      for (int jj = 0; jj < IPW; ++jj) dma_b128(rsV, dst + TILEB + jj * 1024, vo[jj], so);
+    }
+  };
+
+  // Addresses inside a tile, computed once (the swizzle makes them irregular; recomputing them per tile
+  // would cost more instructions than the arithmetic of the softmax).
+  int kaddr[2][KS];  // K fragment of block blk, k-step ks
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk) {
+    const int r = blk * 32 + pi_row(fr);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kaddr[blk][ks] = r * ROWB + (((2 * ks + fh) ^ swz(r)) * 16);
+  }
+  // transposing reads of V for k-step t (16 keys): lane -> key row 16 t + 8 fh + sl/4 (+4 for the second
+  // half) and columns nb*32 + 16*((lane/16)%2) + 4*(sl%4) ..+3; swz(row) does not depend on t
+  const int sl = lane & 15;
+  int vaddr[NB][2];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int krow = 8 * fh + (sl >> 2) + 4 * hh;
+      const int col = nb * 32 + 16 * ((lane >> 4) & 1) + 4 * (sl & 3);
+      vaddr[nb][hh] = krow * ROWB + (((col >> 3) ^ swz(krow)) * 16) + (col & 7) * 2;
+    }
+  static_assert(KTILE == 64 && (16 * ROWB) % (PPR == 16 ? 16 * ROWB : 2 * ROWB) == 0, "swz(row + 16 t) = swz(row)");
+
+  // raw scores (unscaled) of the tile's two 32-key blocks; MASKED: masked positions become -inf
+  auto scores = [&](auto MASKED_, const unsigned char* Kb, int kt, float (&s)[32]) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(MASKED_)::value;
+    f32x16 a0, a1;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) a0[e] = a1[e] = 0.f;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      bf16x8 f0[KS / 2], f1[KS / 2];
+#pragma unroll
+      for (int i = 0; i < KS / 2; ++i) {
+        f0[i] = *reinterpret_cast<const bf16x8*>(Kb + kaddr[0][hf * (KS / 2) + i]);
+        f1[i] = *reinterpret_cast<const bf16x8*>(Kb + kaddr[1][hf * (KS / 2) + i]);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // all fragment reads of this half before its MFMAs
+#pragma unroll
+      for (int i = 0; i < KS / 2; ++i) {
+        const int ks = hf * (KS / 2) + i;
+        a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0[i], qf[ks], a0, 0, 0, 0);
+        a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[i], qf[ks], a1, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      s[e] = a0[e];
+      s[16 + e] = a1[e];
+    }
+    if (MASKED) {
+      const int key0 = kt * KTILE + 8 * fh;
+#pragma unroll
+      for (int e = 0; e < 32; ++e) {
+        const int key = key0 + 32 * (e / 16) + 16 * ((e % 16) / 8) + (e % 8);
+        const bool ok = key < S && (!CAUSAL || key <= row);
+        s[e] = ok ? s[e] : -INFINITY;
+      }
+    }
+  };
+  // true when no key of tile kt is masked for any row of this wavefront
+  auto tile_plain = [&](int kt) { return kt * KTILE + KTILE <= S && (!CAUSAL || kt * KTILE + KTILE - 1 <= q0); };
+  using std::false_type;
+  using std::true_type;
+
+  // ---- pass 1: row maximum and normaliser (m in the log2 domain: raw score * scale_log2e) ----
+  float m = -INFINITY, l = 0.f;
+  request(0, false);
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();  // tile kt is complete; nobody reads the other buffer any more
+    if (kt + 1 < n_tiles) request(kt + 1, false);
+    if (CAUSAL && kt * KTILE > q0 + 31) continue;  // wholly above the diagonal for this wavefront
+    const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
+    float s[32];
+    if (tile_plain(kt)) scores(false_type{}, Kb, kt, s);
+    else scores(true_type{}, Kb, kt, s);
+    float mr = s[0];
+#pragma unroll
+    for (int e = 1; e < 32; ++e) mr = fmaxf(mr, s[e]);
+    const float mx = fmaxf(m, mr * scale_log2e);  // scale > 0
+    if (mx > -INFINITY) {
+      float add = 0.f;
+#pragma unroll
+      for (int e = 0; e < 32; ++e) add += __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], scale_log2e, -mx));
+      l = l * __builtin_amdgcn_exp2f(m - mx) + add;
+      m = mx;
+    }
+  }
+  {  // the two lanes that share a row
+    const float m2 = __shfl_xor(m, 32, 64), l2 = __shfl_xor(l, 32, 64);
+    const float mm = fmaxf(m, m2);  // finite for every row < S: key 0 is never masked
+    l = (m > -INFINITY ? l * __builtin_amdgcn_exp2f(m - mm) : 0.f) + (m2 > -INFINITY ? l2 * __builtin_amdgcn_exp2f(m2 - mm) : 0.f);
+    m = mm;
+  }
+  const float inv = l > 0.f ? 1.0f / l : 0.f;
+  __syncthreads();  // pass 1 has left the buffers
+
+  // ---- pass 2: probabilities and P.V ----
+  f32x16 oacc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[nb][e] = 0.f;
+  // probabilities leave as 16-byte pieces (S is a multiple of 8); pieces of rows or keys past S get the
+  // offset 2^31, which is beyond the buffer (at most 2^31 bytes) with or without the small scalar
+  // offset added, and are dropped by the store
+  const __amdgpu_buffer_rsrc_t rsP = __builtin_amdgcn_make_buffer_rsrc(P, 0, (int)(uint32_t)((int64_t)S * S * 2), 0x00020000);
+  const uint32_t prow = row_ok ? (uint32_t)((int64_t)row * S * 2) + 16u * fh : 0x80000000u;
+  auto store_p = [&](int kt, const u32x4(&pk)[4]) __attribute__((always_inline)) {
+    // whole tiles inside S (the usual case): the row offset plus a scalar; else per piece
+    if (kt * KTILE + KTILE <= S) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) __builtin_amdgcn_raw_buffer_store_b128(pk[i], rsP, (int)prow, (kt * KTILE + 16 * i) * 2, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = kt * KTILE + 16 * i + 8 * fh;
+        const uint32_t off = (row_ok && key < S) ? prow + (uint32_t)(kt * KTILE + 16 * i) * 2 : 0x80000000u;
+        __builtin_amdgcn_raw_buffer_store_b128(pk[i], rsP, (int)off, 0, 0);
+      }
+    }
+  };
+  request(0, true);
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (kt + 1 < n_tiles) request(kt + 1, true);
+    u32x4 pk[4];  // the wavefront's probabilities of this tile: four 16-byte pieces per row
+    if (CAUSAL && kt * KTILE > q0 + 31) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pk[i] = u32x4{0u, 0u, 0u, 0u};
+      store_p(kt, pk);
+      continue;
+    }
+    const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
+    const unsigned char* Vb = Kb + TILEB;
+    float s[32];
+    if (tile_plain(kt)) scores(false_type{}, Kb, kt, s);
+    else scores(true_type{}, Kb, kt, s);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      bf16x8 t;
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        t[e] = static_cast<__bf16>(__builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * i + e], scale_log2e, -m)) * inv);  // exp2(-inf) = 0
+      pk[i] = __builtin_bit_cast(u32x4, t);
+    }
+    store_p(kt, pk);
+    // P.V over the tile's 64 keys: four k-steps of 16
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      bf16x8 vt[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const unsigned char* a0 = Vb + t * 16 * ROWB + vaddr[nb][0];
+        const unsigned char* a1 = Vb + t * 16 * ROWB + vaddr[nb][1];
+        const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(a0));
+        const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(a1));
+        typedef short v8i16 __attribute__((ext_vector_type(8)));
+        const v8i16 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        vt[nb] = __builtin_bit_cast(bf16x8, both);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      const bf16x8 pf = __builtin_bit_cast(bf16x8, pk[t]);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[nb], pf, oacc[nb], 0, 0, 0);
+    }
+  }
+  // keys past the last unmasked tile: zeros, so that every entry of the probability matrix is defined
+  {
+    u32x4 z[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) z[i] = u32x4{0u, 0u, 0u, 0u};
+    for (int kt = n_tiles; kt < all_tiles; ++kt) store_p(kt, z);
+  }
+  // ---- output rows ----
+  if (row_ok) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 o4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(oacc[nb][4 * g + e]);
+        *reinterpret_cast<bf16x4*>(O + (int64_t)row * ldc + nb * 32 + 8 * g + 4 * fh) = o4;
+      }
+  }
+}
+
+inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+bool attention_fwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* prob, const void* ctx) {
+  return dt == DT_BF16 && (hd == 64 || hd == 128) && S >= 8 && S % 8 == 0 && ld % 8 == 0 && ldc % 4 == 0 && al16(qkv) && al16(prob) &&
+         (int64_t)S * ld * 2 < (int64_t(1) << 32) && (int64_t)S * S * 2 <= (int64_t(1) << 31) &&
+         (reinterpret_cast<uintptr_t>(ctx) & 7) == 0;
+}
+
+hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, void* prob, void* ctx,
+                               int64_t ldc, hipStream_t st) {
+  if (B == 0 || H == 0 || S == 0) return hipSuccess;
+  const float sl2 = (1.0f / sqrtf((float)hd)) * 1.4426950408889634f;
+  // 128-row workgroups when there are enough of them to give every compute unit two; else 64-row ones
+  const bool big = (int64_t)B * H * ((S + 127) / 128) >= 512;
+  const int qb = big ? 128 : 64;
+  const int64_t nblk = (int64_t)((S + qb - 1) / qb) * B * H;
+  if (nblk > 0x7FFFFFFF) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)nblk);
+  const bf16* x = reinterpret_cast<const bf16*>(qkv);
+  bf16* p = reinterpret_cast<bf16*>(prob);
+  bf16* o = reinterpret_cast<bf16*>(ctx);
+#define ATTN_LAUNCH(HD_, C_)                                                                      \
+  do {                                                                                            \
+    if (big) attn_fwd_k<HD_, C_, 4><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sl2, p, o, ldc);    \
+    else attn_fwd_k<HD_, C_, 2><<<grid, 128, 0, st>>>(x, ld, S, H, B * H, sl2, p, o, ldc);        \
+  } while (0)
+  if (hd == 128) {
+    if (causal) ATTN_LAUNCH(128, true); else ATTN_LAUNCH(128, false);
+  } else if (hd == 64) {
+    if (causal) ATTN_LAUNCH(64, true); else ATTN_LAUNCH(64, false);
+  } else {
+    return hipErrorInvalidValue;
+  }
+#undef ATTN_LAUNCH
+  return hipGetLastError();
+}
+
+}  // namespace hift

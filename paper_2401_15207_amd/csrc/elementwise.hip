@@ -358,17 +358,18 @@ __global__ void __launch_bounds__(BLK) softmax_fwd_k(int64_t rows, int S, float 
 }
 
 template <typename T>
-__global__ void __launch_bounds__(BLK) softmax_bwd_k(int64_t rows, int S, float scale, const T* __restrict__ p,
+__global__ void __launch_bounds__(BLK) softmax_bwd_k(int64_t rows, int S, float scale, bool causal, const T* __restrict__ p,
                                                       T* __restrict__ dp) {
   const int64_t row = (int64_t)blockIdx.x * (BLK / 64) + (threadIdx.x >> 6);
   if (row >= rows) return;
   const int lane = threadIdx.x & 63;
+  const int n = causal ? (int)(row % S) + 1 : S;  // dp beyond the diagonal is not read: it may never have been written
   const T* pr = p + row * S;
   T* dr = dp + row * S;
   float dot = 0.f;
-  for (int j = lane; j < S; j += 64) dot += to_f32(pr[j]) * to_f32(dr[j]);
+  for (int j = lane; j < n; j += 64) dot += to_f32(pr[j]) * to_f32(dr[j]);
   dot = wave_sum(dot);
-  for (int j = lane; j < S; j += 64) dr[j] = from_f32<T>(scale * to_f32(pr[j]) * (to_f32(dr[j]) - dot));
+  for (int j = lane; j < S; j += 64) dr[j] = from_f32<T>(j < n ? scale * to_f32(pr[j]) * (to_f32(dr[j]) - dot) : 0.f);
 }
 
 // Row held in registers: lane l owns elements [c*64*V + l*V, +V) of chunk c; one read and one write
@@ -420,11 +421,12 @@ __global__ void __launch_bounds__(BLK) softmax_fwd_reg_k(int64_t rows, int S, fl
 }
 
 template <typename T, int V, int NCH>
-__global__ void __launch_bounds__(BLK) softmax_bwd_reg_k(int64_t rows, int S, float scale, const T* __restrict__ p,
+__global__ void __launch_bounds__(BLK) softmax_bwd_reg_k(int64_t rows, int S, float scale, bool causal, const T* __restrict__ p,
                                                           T* __restrict__ dp) {
   const int64_t row = (int64_t)blockIdx.x * (BLK / 64) + (threadIdx.x >> 6);
   if (row >= rows) return;
   const int lane = threadIdx.x & 63;
+  const int n = causal ? (int)(row % S) + 1 : S;  // dp beyond the diagonal may never have been written
   const T* pr = p + row * S;
   T* dr = dp + row * S;
   float pv[NCH][V], dv[NCH][V];
@@ -432,11 +434,16 @@ __global__ void __launch_bounds__(BLK) softmax_bwd_reg_k(int64_t rows, int S, fl
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const int j0 = (c * 64 + lane) * V;
-    if (j0 < S) {
+#pragma unroll
+    for (int e = 0; e < V; ++e) pv[c][e] = dv[c][e] = 0.f;
+    if (j0 < n) {
       ldv<T, V>(pr + j0, pv[c]);
       ldv<T, V>(dr + j0, dv[c]);
 #pragma unroll
-      for (int e = 0; e < V; ++e) dot += pv[c][e] * dv[c][e];
+      for (int e = 0; e < V; ++e) {
+        if (j0 + e >= n) pv[c][e] = dv[c][e] = 0.f;
+        dot += pv[c][e] * dv[c][e];
+      }
     }
   }
   dot = wave_sum(dot);
@@ -890,22 +897,22 @@ hipError_t softmax_fwd(int dt, int64_t nbh, int S, float scale, bool causal, voi
 #undef SM_REG
   LAUNCH_CHECK();
 }
-hipError_t softmax_bwd(int dt, int64_t nbh, int S, float scale, const void* p, void* dp, hipStream_t st) {
+hipError_t softmax_bwd(int dt, int64_t nbh, int S, float scale, bool causal, const void* p, void* dp, hipStream_t st) {
   const int64_t rows = nbh * S;
   if (rows == 0) return hipSuccess;
   const dim3 grid((unsigned)cdiv(rows, BLK / 64));
 #define SM_REG(T, V)                                                                                                        \
   if (S % (V) == 0 && aligned16(p) && aligned16(dp)) {                                                                      \
-    if (S <= 64 * (V)) { softmax_bwd_reg_k<T, V, 1><<<grid, BLK, 0, st>>>(rows, S, scale, (const T*)p, (T*)dp); LAUNCH_CHECK(); }  \
-    if (S <= 128 * (V)) { softmax_bwd_reg_k<T, V, 2><<<grid, BLK, 0, st>>>(rows, S, scale, (const T*)p, (T*)dp); LAUNCH_CHECK(); } \
-    if (S <= 256 * (V)) { softmax_bwd_reg_k<T, V, 4><<<grid, BLK, 0, st>>>(rows, S, scale, (const T*)p, (T*)dp); LAUNCH_CHECK(); } \
+    if (S <= 64 * (V)) { softmax_bwd_reg_k<T, V, 1><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (const T*)p, (T*)dp); LAUNCH_CHECK(); }  \
+    if (S <= 128 * (V)) { softmax_bwd_reg_k<T, V, 2><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (const T*)p, (T*)dp); LAUNCH_CHECK(); } \
+    if (S <= 256 * (V)) { softmax_bwd_reg_k<T, V, 4><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (const T*)p, (T*)dp); LAUNCH_CHECK(); } \
   }
   if (dt == DT_F32) {
     SM_REG(float, 4)
-    softmax_bwd_k<float><<<grid, BLK, 0, st>>>(rows, S, scale, (const float*)p, (float*)dp);
+    softmax_bwd_k<float><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (const float*)p, (float*)dp);
   } else {
     SM_REG(bf16, 8)
-    softmax_bwd_k<bf16><<<grid, BLK, 0, st>>>(rows, S, scale, (const bf16*)p, (bf16*)dp);
+    softmax_bwd_k<bf16><<<grid, BLK, 0, st>>>(rows, S, scale, causal, (const bf16*)p, (bf16*)dp);
   }
 #undef SM_REG
   LAUNCH_CHECK();

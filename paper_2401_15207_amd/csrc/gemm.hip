@@ -35,6 +35,7 @@ struct GemmP {
   int nh;
   int64_t sa1, sa2, sb1, sb2, sc1, sc2;
   int tiles_m, tiles_n;
+  int band = 0;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -290,12 +291,17 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmP p) {
   sa.init(A, p.lda, m0, p.M, p.K, tid);
   sb.init(B, p.ldb, n0, p.N, p.K, tid);
   const int64_t nk = (p.K + KT - 1) / KT;
+  // k-tiles [kb, ke) of this output tile; a band hint (causal attention) shortens the range
+  int64_t kb = 0, ke = nk;
+  if (p.band == BAND_SKIP_UPPER && n0 >= m0 + BM) return;  // uniform over the workgroup
+  if (p.band == BAND_K_UPTO_ROW) ke = (m0 + BM + KT - 1) / KT < nk ? (m0 + BM + KT - 1) / KT : nk;
+  if (p.band == BAND_K_FROM_ROW) kb = m0 / KT < nk - 1 ? m0 / KT : nk - 1;
   u32x4 ra[StA::NPIECE], rb[StB::NPIECE];  // the next tile on its way from HBM to LDS
 
-  sa.load(0, ra);
-  sb.load(0, rb);
-  sa.store(smem, tid, ra);
-  sb.store(smem + A_BYTES, tid, rb);
+  sa.load(kb, ra);
+  sb.load(kb, rb);
+  sa.store(smem + (kb & 1) * BUF, tid, ra);
+  sb.store(smem + (kb & 1) * BUF + A_BYTES, tid, rb);
   __syncthreads();
 
   const int frow = lane & 31, fhalf = lane >> 5;
@@ -315,7 +321,7 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmP p) {
 #pragma unroll
     for (int j = 0; j < NT; ++j) b[j] = *reinterpret_cast<const bf16x8*>(buf + foff[ks][j & 1] + (b_base + j * 4096));
   };
-  read_frags(fa[0], fb[0], smem, 0);
+  read_frags(fa[0], fb[0], smem + (kb & 1) * BUF, 0);
 
   // One pass over a k-tile held in one of the two LDS buffers.  Every k-step is its own scheduling region.
   // A wavefront cannot issue anything while it waits for the matrix pipe to take its next MFMA,
@@ -329,10 +335,10 @@ __global__ void __launch_bounds__(256) gemm_mfma_k(GemmP p) {
   // Tiles past the end are the last tile again: loaded, stored, never used.
   constexpr bool HINT = AK && BKM;  // the counts describe k-major staging; transposed staging schedules freely
   constexpr int NM = MT * NT, NR = MT + NT, NL = StA::NPIECE + StB::NPIECE;
-  for (int64_t kt = 0; kt < nk; ++kt) {
+  for (int64_t kt = kb; kt < ke; ++kt) {
     unsigned char* cur = smem + (kt & 1) * BUF;
     unsigned char* nxt = smem + ((kt + 1) & 1) * BUF;
-    const int64_t kt2 = kt + 1 < nk ? kt + 1 : nk - 1;
+    const int64_t kt2 = kt + 1 < ke ? kt + 1 : ke - 1;
 #pragma unroll
     for (int ks = 0; ks < KT / 16 - 1; ++ks) {
       if (ks == 0) {
@@ -837,6 +843,7 @@ hipError_t gemm(const Gemm& g, hipStream_t st, int* variant) {
   p.A = g.A; p.lda = g.lda; p.B = g.B; p.ldb = g.ldb; p.C = g.C; p.ldc = g.ldc;
   p.bias = g.bias; p.R = g.R; p.ldr = g.ldr;
   p.nh = g.nh; p.sa1 = g.sa1; p.sa2 = g.sa2; p.sb1 = g.sb1; p.sb2 = g.sb2; p.sc1 = g.sc1; p.sc2 = g.sc2;
+  p.band = g.band;  // only the MFMA kernel uses it; the FMA kernel computes everything, which is also correct
   const int nz = g.nb * g.nh;
   if (nz > 65535) return hipErrorInvalidValue;
 

@@ -24,7 +24,14 @@ struct Gemm {
   // two-level batch: problem z = b * nh + h uses offsets b*s?1 + h*s?2 (elements)
   int nb = 1, nh = 1;
   int64_t sa1 = 0, sa2 = 0, sb1 = 0, sb2 = 0, sc1 = 0, sc2 = 0;
+  // Structure the caller vouches for (causal attention), used only to skip work that cannot matter:
+  //   BAND_SKIP_UPPER   C(m,n) with n > m is never read: tiles wholly above the diagonal are not computed
+  //                     (their part of C keeps whatever it held)
+  //   BAND_K_UPTO_ROW   A(m,k) = 0 for k > m: the contraction of a tile stops at its last row
+  //   BAND_K_FROM_ROW   A(m,k) = 0 for k < m: the contraction of a tile starts at its first row
+  int band = 0;
 };
+enum { BAND_NONE = 0, BAND_SKIP_UPPER = 1, BAND_K_UPTO_ROW = 2, BAND_K_FROM_ROW = 3 };
 // variant (optional) receives which kernel ran: 0 plain FMA, 1 MFMA 128x128 tiles, 2 MFMA 256x256 tiles
 hipError_t gemm(const Gemm& g, hipStream_t st, int* variant = nullptr);
 
@@ -61,9 +68,15 @@ hipError_t gelu_bwd(int dt, int64_t n, const void* dact, const void* pre, void* 
 hipError_t swiglu_fwd(int dt, int64_t T, int f, const void* gu, void* act, hipStream_t st);
 hipError_t swiglu_bwd(int dt, int64_t T, int f, const void* dact, const void* gu, void* dgu, hipStream_t st);
 // in place over scores [nbh, S, S]: p = softmax(scale * s + causal mask)
+// Fused attention forward (attention.hip): qkv [B*S, ld] holds q | k | v of every head side by side
+// (head h at columns h*hd, d + h*hd, 2d + h*hd, d = H*hd); writes the probabilities [B, H, S, S] and the
+// context [B*S, ldc] (head h at columns h*hd).  bf16 only, hd 64 or 128.
+bool attention_fwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* prob, const void* ctx);
+hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, void* prob, void* ctx,
+                               int64_t ldc, hipStream_t st);
 hipError_t softmax_fwd(int dt, int64_t nbh, int S, float scale, bool causal, void* s, hipStream_t st);
 // in place over dp: ds = scale * p * (dp - sum_j dp p)
-hipError_t softmax_bwd(int dt, int64_t nbh, int S, float scale, const void* p, void* dp, hipStream_t st);
+hipError_t softmax_bwd(int dt, int64_t nbh, int S, float scale, bool causal, const void* p, void* dp, hipStream_t st);
 // logits [rows, V] -> d loss / d logits in place; loss = mean over labels >= 0
 hipError_t cross_entropy(int dt, int64_t rows, int V, void* logits, const int32_t* labels,
                          float* row_loss, float* loss_out, hipStream_t st);

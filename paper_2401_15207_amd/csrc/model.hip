@@ -551,6 +551,13 @@ hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S) {
   const size_t es = M->es;
   unsigned char* qkv = (unsigned char*)a.qkv;
   const bool causal = c.arch != HIFT_ARCH_POSTLN_ENCODER;
+  static const bool fused_on = [] { const char* e = getenv("HIFT_ATTN_FUSED"); return !(e && e[0] == '0'); }();
+  if (fused_on && attention_fwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, a.prob, a.ctx)) {
+    // scores, softmax and P.V in one kernel; the probabilities are kept for the backward pass
+    Scope sc(M, CAT_ATTN, 4.0 * B * H * S * S * hd);
+    K_TRY(attention_fwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, a.prob, a.ctx, d, M->cs));
+    return HIFT_OK;
+  }
   {
     Gemm g;  // scores = q . k^T
     g.dtype = M->dt;
@@ -561,6 +568,7 @@ hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S) {
     g.nb = B; g.nh = (int)H;
     g.sa1 = (int64_t)S * 3 * d; g.sa2 = hd; g.sb1 = g.sa1; g.sb2 = hd;
     g.sc1 = H * (int64_t)S * S; g.sc2 = (int64_t)S * S;
+    if (causal) g.band = BAND_SKIP_UPPER;  // the softmax never reads scores above the diagonal
     Scope sc(M, CAT_ATTN, 2.0 * B * H * S * S * hd);
     K_TRY(gemm(g, M->cs));
   }
@@ -579,6 +587,7 @@ hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S) {
     g.sa1 = H * (int64_t)S * S; g.sa2 = (int64_t)S * S;
     g.sb1 = (int64_t)S * 3 * d; g.sb2 = hd;
     g.sc1 = (int64_t)S * d; g.sc2 = hd;
+    if (causal) g.band = BAND_K_UPTO_ROW;  // probabilities above the diagonal are exact zeros
     Scope sc(M, CAT_ATTN, 2.0 * B * H * S * S * hd);
     K_TRY(gemm(g, M->cs));
   }
@@ -593,6 +602,7 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
   unsigned char* qkv = (unsigned char*)a.qkv;
   unsigned char* dqkv = (unsigned char*)M->dqkv;
   const double fl = 2.0 * B * H * S * S * hd;
+  const bool causal = c.arch != HIFT_ARCH_POSTLN_ENCODER;
   auto batch = [&](Gemm& g) { g.dtype = M->dt; g.nb = B; g.nh = (int)H; };
   const int64_t sP1 = H * (int64_t)S * S, sP2 = (int64_t)S * S, sQ1 = (int64_t)S * 3 * d, sX1 = (int64_t)S * d;
   {
@@ -602,6 +612,7 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
     g.A = a.prob; g.lda = S; g.a_kmajor = false; g.sa1 = sP1; g.sa2 = sP2;
     g.B = dctx; g.ldb = d; g.b_kmajor = false; g.sb1 = sX1; g.sb2 = hd;
     g.C = dqkv + 2 * d * es; g.ldc = 3 * d; g.sc1 = sQ1; g.sc2 = hd;
+    if (causal) g.band = BAND_K_FROM_ROW;  // p[i,j] = 0 for i < j
     Scope sc(M, CAT_ATTN, fl);
     K_TRY(gemm(g, M->cs));
   }
@@ -612,12 +623,13 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
     g.A = dctx; g.lda = d; g.sa1 = sX1; g.sa2 = hd;
     g.B = qkv + 2 * d * es; g.ldb = 3 * d; g.sb1 = sQ1; g.sb2 = hd;
     g.C = M->dprob; g.ldc = S; g.sc1 = sP1; g.sc2 = sP2;
+    if (causal) g.band = BAND_SKIP_UPPER;  // the softmax backward never reads dp above the diagonal
     Scope sc(M, CAT_ATTN, fl);
     K_TRY(gemm(g, M->cs));
   }
   {
     Scope sc(M, CAT_ELEM, 0);
-    K_TRY(softmax_bwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), a.prob, M->dprob, M->cs));
+    K_TRY(softmax_bwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, a.prob, M->dprob, M->cs));
   }
   {
     Gemm g;  // dq[i,e] = sum_j ds[i,j] k[j,e]
@@ -626,6 +638,7 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
     g.A = M->dprob; g.lda = S; g.sa1 = sP1; g.sa2 = sP2;
     g.B = qkv + d * es; g.ldb = 3 * d; g.b_kmajor = false; g.sb1 = sQ1; g.sb2 = hd;
     g.C = dqkv; g.ldc = 3 * d; g.sc1 = sQ1; g.sc2 = hd;
+    if (causal) g.band = BAND_K_UPTO_ROW;  // ds[i,j] = 0 for j > i
     Scope sc(M, CAT_ATTN, fl);
     K_TRY(gemm(g, M->cs));
   }
@@ -636,6 +649,7 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
     g.A = M->dprob; g.lda = S; g.a_kmajor = false; g.sa1 = sP1; g.sa2 = sP2;
     g.B = qkv; g.ldb = 3 * d; g.b_kmajor = false; g.sb1 = sQ1; g.sb2 = hd;
     g.C = dqkv + d * es; g.ldc = 3 * d; g.sc1 = sQ1; g.sc2 = hd;
+    if (causal) g.band = BAND_K_FROM_ROW;  // ds[i,j] = 0 for i < j
     Scope sc(M, CAT_ATTN, fl);
     K_TRY(gemm(g, M->cs));
   }
@@ -1643,6 +1657,16 @@ hift_status hift_kernel_optimizer(const hift_opt* opt, int64_t count, int32_t de
   if (opt->kind == HIFT_ADAFACTOR) return fail(HIFT_EINVAL, "Adafactor works on whole tensors; it has no element-wise kernel entry");
   OptArgs oa{opt->kind, opt->lr, opt->beta1, opt->beta2, opt->eps, opt->weight_decay, opt->momentum};
   HIP_TRY(optimizer_update(oa, count, decay != 0, t, master, grad, state1, state2, compute_copy, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_attention_fwd(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
+                                      const void* qkv, void* prob, void* ctx, void* stream) {
+  const int64_t d = (int64_t)heads * head_dim;
+  if (batch < 0 || heads < 1 || seq < 0 || !qkv || !prob || !ctx) return fail(HIFT_EINVAL, "bad argument");
+  if (!attention_fwd_fused_applies(DT_BF16, seq, head_dim, 3 * d, d, qkv, prob, ctx))
+    return fail(HIFT_EINVAL, "the fused kernel takes bf16, head widths 64 and 128 and 16-byte aligned buffers");
+  HIP_TRY(attention_fwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, ctx, d, (hipStream_t)stream));
   return HIFT_OK;
 }
 

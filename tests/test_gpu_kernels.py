@@ -240,3 +240,44 @@ def test_cross_entropy(dtype, rows, V):
     got = dz.float().cpu().numpy()
     tol = (2 ** -8 if bf else 1e-5) * np.abs(ref_d) + 1e-8
     assert np.all(np.abs(got - ref_d) <= tol)
+
+
+def test_fused_attention_refuses_what_it_cannot_take():
+    import torch
+    import paper_2401_15207_amd as H_
+    z = torch.zeros(77 * 3 * 64 * 2, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(H_.HiftError):            # rows of the probability matrix must be multiples of 16 bytes
+        H_.kernel_attention_fwd(1, 2, 77, 64, 1, z, z, z)
+    with pytest.raises(H_.HiftError):            # head widths 64 and 128 only
+        H_.kernel_attention_fwd(1, 2, 64, 32, 1, z, z, z)
+
+
+@pytest.mark.parametrize("B,H,S,hd,causal", [(2, 3, 200, 64, 1), (1, 2, 512, 128, 1), (2, 2, 136, 128, 0), (1, 2, 72, 64, 1),
+                                              (1, 1, 8, 128, 1), (2, 4, 384, 64, 0)])
+def test_fused_attention_forward(B, H, S, hd, causal):
+    """Scores, softmax and P.V in one kernel against the oracle's attention (float64).  Probabilities
+    and context are bf16: 2^-8 relative plus the rounding of inputs that are sums of S terms."""
+    import torch
+    import paper_2401_15207_amd as H_
+    from oracle import hift_oracle as O
+    rng = np.random.default_rng(B * 1000 + S + hd + causal)
+    d = H * hd
+    qkv = _bf16_round(rng.standard_normal((B * S, 3 * d)) * 1.5)
+    q = qkv[:, :d].reshape(B, S, H, hd).transpose(0, 2, 1, 3).astype(np.float64)
+    k = qkv[:, d:2 * d].reshape(B, S, H, hd).transpose(0, 2, 1, 3).astype(np.float64)
+    v = qkv[:, 2 * d:].reshape(B, S, H, hd).transpose(0, 2, 1, 3).astype(np.float64)
+    ctx_ref, p_ref = O.attention_fwd(q, k, v, bool(causal))
+    dq = _dev(qkv, True)
+    dp = torch.full((B, H, S, S), float("nan"), dtype=torch.bfloat16, device="cuda")   # every entry must be written
+    dc = torch.full((B * S, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    H_.kernel_attention_fwd(B, H, S, hd, causal, dq, dp, dc)
+    torch.cuda.synchronize()
+    p = dp.float().cpu().numpy().astype(np.float64)
+    c = dc.float().cpu().numpy().astype(np.float64).reshape(B, S, H, hd).transpose(0, 2, 1, 3)
+    assert np.isfinite(p).all() and np.isfinite(c).all()
+    if causal:
+        assert np.all(p[:, :, np.triu_indices(S, 1)[0], np.triu_indices(S, 1)[1]] == 0.0)
+    assert np.all(np.abs(p - p_ref) <= 2 ** -8 * p_ref + 1e-6)
+    assert np.all(np.abs(p.sum(-1) - 1.0) <= 2e-2)
+    assert np.all(np.abs(c - ctx_ref) <= 2 ** -7 * np.abs(ctx_ref) + 2e-2)
+    assert np.sqrt(np.mean((c - ctx_ref) ** 2)) <= 4e-3 * np.sqrt(np.mean(ctx_ref ** 2)) + 1e-4
