@@ -169,6 +169,75 @@ __global__ void __launch_bounds__(BLK) norm_fwd_k(int64_t rows, int d, float eps
   }
 }
 
+// Same, with the row held in registers (d <= 64 * V * NCH): every load of the row is in flight at once
+// and x is read from memory a single time.  One wavefront per row, one row per 64-thread workgroup so
+// that short batches still spread over the whole chip.
+template <typename T, int V, int NCH, bool RMS>
+__global__ void __launch_bounds__(64) norm_fwd_reg_k(int64_t rows, int d, float eps, const T* __restrict__ x,
+                                                      const T* __restrict__ g, const T* __restrict__ b,
+                                                      T* __restrict__ y, float* __restrict__ stats) {
+  const int64_t row = blockIdx.x;
+  const int lane = threadIdx.x;
+  const T* xr = x + row * d;
+  float a[NCH][V];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int j = (c * 64 + lane) * V;
+    if (j < d) {
+      ldv<T, V>(xr + j, a[c]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < V; ++e) a[c][e] = 0.f;
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c)
+#pragma unroll
+    for (int e = 0; e < V; ++e) s += RMS ? a[c][e] * a[c][e] : a[c][e];
+  s = wave_sum(s);
+  float mean = 0.f, var;
+  if (RMS) {
+    var = s / d;
+  } else {
+    mean = s / d;
+    float q = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int j = (c * 64 + lane) * V;
+      if (j < d) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) q += (a[c][e] - mean) * (a[c][e] - mean);
+      }
+    }
+    var = wave_sum(q) / d;
+  }
+  const float rstd = 1.0f / sqrtf(var + eps);
+  T* yr = y + row * d;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int j = (c * 64 + lane) * V;
+    if (j < d) {
+      float gg[V];
+      ldv<T, V>(g + j, gg);
+      if (RMS) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) a[c][e] = a[c][e] * rstd * gg[e];
+      } else {
+        float bb[V];
+        ldv<T, V>(b + j, bb);
+#pragma unroll
+        for (int e = 0; e < V; ++e) a[c][e] = (a[c][e] - mean) * rstd * gg[e] + bb[e];
+      }
+      stv<T, V>(yr + j, a[c]);
+    }
+  }
+  if (lane == 0) {
+    stats[2 * row] = mean;
+    stats[2 * row + 1] = rstd;
+  }
+}
+
 template <typename T, int V, bool RMS>
 __global__ void __launch_bounds__(BLK) norm_bwd_dx_k(int64_t rows, int d, const T* __restrict__ dy,
                                                       const T* __restrict__ x, const T* __restrict__ g,
@@ -774,6 +843,17 @@ hipError_t norm_fwd(int dt, bool rms, int64_t rows, int d, float eps, const void
   if (rows == 0) return hipSuccess;
   const dim3 grid((unsigned)cdiv(rows, BLK / 64));
 #define OK(v) (d % (v) == 0 && aligned16(x) && aligned16(y) && aligned16(g) && aligned16(b))
+  // rows of up to 4096 bf16 (2048 fp32) values: the row stays in registers
+  if (dt == DT_BF16 && OK(8) && d <= 64 * 8 * 8 && rows <= 0x7FFFFFFF) {
+    if (rms) norm_fwd_reg_k<bf16, 8, 8, true><<<dim3((unsigned)rows), 64, 0, st>>>(rows, d, eps, (const bf16*)x, (const bf16*)g, (const bf16*)b, (bf16*)y, stats);
+    else norm_fwd_reg_k<bf16, 8, 8, false><<<dim3((unsigned)rows), 64, 0, st>>>(rows, d, eps, (const bf16*)x, (const bf16*)g, (const bf16*)b, (bf16*)y, stats);
+    LAUNCH_CHECK();
+  }
+  if (dt == DT_F32 && OK(4) && d <= 64 * 4 * 8 && rows <= 0x7FFFFFFF) {
+    if (rms) norm_fwd_reg_k<float, 4, 8, true><<<dim3((unsigned)rows), 64, 0, st>>>(rows, d, eps, (const float*)x, (const float*)g, (const float*)b, (float*)y, stats);
+    else norm_fwd_reg_k<float, 4, 8, false><<<dim3((unsigned)rows), 64, 0, st>>>(rows, d, eps, (const float*)x, (const float*)g, (const float*)b, (float*)y, stats);
+    LAUNCH_CHECK();
+  }
   if (rms)
     DISPATCH_TV(dt, OK, (norm_fwd_k<T, V, true><<<grid, BLK, 0, st>>>(rows, d, eps, (const T*)x, (const T*)g,
                                                                           (const T*)b, (T*)y, stats)));
