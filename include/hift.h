@@ -331,6 +331,17 @@ hift_status hift_kernel_optimizer(const hift_opt* opt, int64_t count, int32_t de
  * 1/sqrt(head_dim); causal != 0 masks keys after the query. */
 hift_status hift_kernel_attention_fwd(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
                                       const void* qkv, void* prob, void* ctx, void* stream);
+/* Query-major half of the attention backward, fused (Algorithm 1's backward through one layer's
+ * attention; the softmax and product derivatives of the section 3 forward): bf16 only.
+ * qkv, prob, ctx: as written by hift_kernel_attention_fwd (ctx = prob . v).  dctx: device
+ * [batch*seq, heads*head_dim], gradient of ctx.  Writes dprob: device [batch, heads, seq, seq] bf16,
+ * ds = p * (dp - sum_j dp p) / sqrt(head_dim) with dp = dctx . v^T, completely (zeros where masked), and
+ * the q columns of dqkv: device [batch*seq, 3*heads*head_dim], dq = ds . k; the k and v columns of dqkv
+ * are not touched (dk = ds^T . q and dv = prob^T . dctx are the caller's).  Buffers stay the
+ * caller's; none may overlap another.  HIFT_EINVAL for shapes or alignments the kernel does not take. */
+hift_status hift_kernel_attention_bwd_query(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
+                                            const void* qkv, const void* prob, const void* ctx, const void* dctx,
+                                            void* dprob, void* dqkv, void* stream);
 /* y = norm(x) * g (+ b) over rows of width d; rms = 1: RMSNorm (b ignored).  stats: fp32 [rows,2]
  * receives mean (0 for RMSNorm) and reciprocal standard deviation. */
 hift_status hift_kernel_norm_fwd(int32_t dtype, int32_t rms, int64_t rows, int32_t d, float eps,

@@ -96,6 +96,7 @@ _SIGS = {
     "hift_kernel_optimizer": [_P(Opt), _i64, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_norm_fwd": [_i32, _i32, _i64, _i32, C.c_float, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_attention_fwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
+    "hift_kernel_attention_bwd_query": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_cross_entropy": [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp],
 }
 for _n, _a in _SIGS.items():
@@ -219,6 +220,13 @@ def kernel_attention_fwd(batch, heads, seq, head_dim, causal, qkv, prob, ctx, st
     import torch
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib.hift_kernel_attention_fwd(batch, heads, seq, head_dim, int(causal), _ptr(qkv), _ptr(prob), _ptr(ctx), st))
+
+
+def kernel_attention_bwd_query(batch, heads, seq, head_dim, causal, qkv, prob, ctx, dctx, dprob, dqkv, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_attention_bwd_query(batch, heads, seq, head_dim, int(causal), _ptr(qkv), _ptr(prob), _ptr(ctx),
+                                               _ptr(dctx), _ptr(dprob), _ptr(dqkv), st))
 
 
 def kernel_cross_entropy(dtype, rows, V, logits, labels, row_loss, loss_out, stream=None):

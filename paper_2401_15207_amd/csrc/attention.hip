@@ -50,9 +50,20 @@ __device__ __forceinline__ void dma_b128(u32x4 rsrc, uint32_t lds_addr, uint32_t
 // c ^ swz(r), which spreads both the fragment reads (sixteen rows, one piece) and the transposing
 // reads over the banks.  A tile is filled by loads that write 1 KB of consecutive LDS bytes each, so
 // the swizzle is applied by choosing which piece of its row a lane fetches.
-template <int HD, bool CAUSAL, int NW>
-__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_fwd_k(const bf16* __restrict__ qkv, int64_t ld, int S, int H, int BH, float scale_log2e,
-                                                       bf16* __restrict__ prob, bf16* __restrict__ ctx, int64_t ldc) {
+//
+// BWD = false: the forward kernel.  `scale` is log2(e) / sqrt(HD); writes prob and ctx.
+// BWD = true: the query-major half of the backward pass, on the same tiling with the roles of K and V
+// exchanged.  Reads prob (P), ctx (O) and dctx (dO); `scale` is 1 / sqrt(HD).  Per row i:
+//   D_i = sum_e dO[i,e] O[i,e]   (= sum_j P[i,j] dP[i,j], since O = P V)
+//   dP[i,j] = dO[i,:] . V[j,:],  dS[i,j] = scale * P[i,j] * (dP[i,j] - D_i),  dQ[i,:] = sum_j dS[i,j] K[j,:]
+// dS goes to dprob in the layout of prob (bf16; exact zeros wherever P is zero), dQ to the q columns
+// of dqkv (row stride ld, like qkv).  dV = P^T dO and dK = dS^T Q are key-major sums and stay with
+// the caller.
+template <int HD, bool CAUSAL, int NW, bool BWD>
+__global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* __restrict__ qkv, int64_t ld, int S, int H, int BH, float scale,
+                                                   bf16* __restrict__ prob, bf16* __restrict__ ctx, int64_t ldc,
+                                                   const bf16* __restrict__ dctx, bf16* __restrict__ dprob, bf16* __restrict__ dqkv) {
+  const float scale_log2e = scale;
   constexpr int QB = 32 * NW;       // query rows per workgroup
   constexpr int ROWB = HD * 2;      // bytes per LDS row
   constexpr int PPR = HD / 8;       // 16-byte pieces per row: 16 or 8
@@ -97,12 +108,27 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_fwd_k(const bf1
   const int row = q0 + fr;
   const bool row_ok = row < S;
 
-  bf16x8 qf[KS];  // Q fragments of the wavefront's 32 rows
+  bf16x8 qf[KS];  // fragments of the wavefront's 32 rows: Q (forward) or dO (backward)
+  float Drow = 0.f;  // backward: D of this lane's row
+  {
+    const bf16* src = BWD ? dctx + (int64_t)b * S * ldc + (int64_t)h * HD + (int64_t)row * ldc : q + (int64_t)row * ld;
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    u32x4 t = {0u, 0u, 0u, 0u};
-    if (row_ok) t = *reinterpret_cast<const u32x4*>(q + (int64_t)row * ld + ks * 16 + fh * 8);
-    qf[ks] = __builtin_bit_cast(bf16x8, t);
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 t = {0u, 0u, 0u, 0u};
+      if (row_ok) t = *reinterpret_cast<const u32x4*>(src + ks * 16 + fh * 8);
+      qf[ks] = __builtin_bit_cast(bf16x8, t);
+    }
+    if (BWD) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        u32x4 t = {0u, 0u, 0u, 0u};
+        if (row_ok) t = *reinterpret_cast<const u32x4*>(O + (int64_t)row * ldc + ks * 16 + fh * 8);
+        const bf16x8 of = __builtin_bit_cast(bf16x8, t);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) Drow = __builtin_fmaf((float)qf[ks][e], (float)of[e], Drow);
+      }
+      Drow += __shfl_xor(Drow, 32, 64);  // the two lanes of a row hold the two halves of every 16 columns
+    }
   }
 
   const int last_row = min(S, qb * QB + QB) - 1;
@@ -197,128 +223,236 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_fwd_k(const bf1
   using std::false_type;
   using std::true_type;
 
-  // ---- pass 1: row maximum and normaliser (m in the log2 domain: raw score * scale_log2e) ----
-  float m = -INFINITY, l = 0.f;
-  request(0, false);
-  for (int kt = 0; kt < n_tiles; ++kt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();  // tile kt is complete; nobody reads the other buffer any more
-    if (kt + 1 < n_tiles) request(kt + 1, false);
-    if (CAUSAL && kt * KTILE > q0 + 31) continue;  // wholly above the diagonal for this wavefront
-    const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
-    float s[32];
-    if (tile_plain(kt)) scores(false_type{}, Kb, kt, s);
-    else scores(true_type{}, Kb, kt, s);
-    float mr = s[0];
-#pragma unroll
-    for (int e = 1; e < 32; ++e) mr = fmaxf(mr, s[e]);
-    const float mx = fmaxf(m, mr * scale_log2e);  // scale > 0
-    if (mx > -INFINITY) {
-      float add = 0.f;
-#pragma unroll
-      for (int e = 0; e < 32; ++e) add += __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], scale_log2e, -mx));
-      l = l * __builtin_amdgcn_exp2f(m - mx) + add;
-      m = mx;
+  if constexpr (!BWD) {
+    // ---- pass 1: row maximum and normaliser (m in the log2 domain: raw score * scale_log2e) ----
+    float m = -INFINITY, l = 0.f;
+    request(0, false);
+    for (int kt = 0; kt < n_tiles; ++kt) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();  // tile kt is complete; nobody reads the other buffer any more
+      if (kt + 1 < n_tiles) request(kt + 1, false);
+      if (CAUSAL && kt * KTILE > q0 + 31) continue;  // wholly above the diagonal for this wavefront
+      const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
+      float s[32];
+      if (tile_plain(kt)) scores(false_type{}, Kb, kt, s);
+      else scores(true_type{}, Kb, kt, s);
+      float mr = s[0];
+  #pragma unroll
+      for (int e = 1; e < 32; ++e) mr = fmaxf(mr, s[e]);
+      const float mx = fmaxf(m, mr * scale_log2e);  // scale > 0
+      if (mx > -INFINITY) {
+        float add = 0.f;
+  #pragma unroll
+        for (int e = 0; e < 32; ++e) add += __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], scale_log2e, -mx));
+        l = l * __builtin_amdgcn_exp2f(m - mx) + add;
+        m = mx;
+      }
     }
-  }
-  {  // the two lanes that share a row
-    const float m2 = __shfl_xor(m, 32, 64), l2 = __shfl_xor(l, 32, 64);
-    const float mm = fmaxf(m, m2);  // finite for every row < S: key 0 is never masked
-    l = (m > -INFINITY ? l * __builtin_amdgcn_exp2f(m - mm) : 0.f) + (m2 > -INFINITY ? l2 * __builtin_amdgcn_exp2f(m2 - mm) : 0.f);
-    m = mm;
-  }
-  const float inv = l > 0.f ? 1.0f / l : 0.f;
-  __syncthreads();  // pass 1 has left the buffers
+    {  // the two lanes that share a row
+      const float m2 = __shfl_xor(m, 32, 64), l2 = __shfl_xor(l, 32, 64);
+      const float mm = fmaxf(m, m2);  // finite for every row < S: key 0 is never masked
+      l = (m > -INFINITY ? l * __builtin_amdgcn_exp2f(m - mm) : 0.f) + (m2 > -INFINITY ? l2 * __builtin_amdgcn_exp2f(m2 - mm) : 0.f);
+      m = mm;
+    }
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    __syncthreads();  // pass 1 has left the buffers
 
-  // ---- pass 2: probabilities and P.V ----
-  f32x16 oacc[NB];
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[nb][e] = 0.f;
-  // probabilities leave as 16-byte pieces (S is a multiple of 8); pieces of rows or keys past S get the
-  // offset 2^31, which is beyond the buffer (at most 2^31 bytes) with or without the small scalar
-  // offset added, and are dropped by the store
-  const __amdgpu_buffer_rsrc_t rsP = __builtin_amdgcn_make_buffer_rsrc(P, 0, (int)(uint32_t)((int64_t)S * S * 2), 0x00020000);
-  const uint32_t prow = row_ok ? (uint32_t)((int64_t)row * S * 2) + 16u * fh : 0x80000000u;
-  auto store_p = [&](int kt, const u32x4(&pk)[4]) __attribute__((always_inline)) {
-    // whole tiles inside S (the usual case): the row offset plus a scalar; else per piece
-    if (kt * KTILE + KTILE <= S) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) __builtin_amdgcn_raw_buffer_store_b128(pk[i], rsP, (int)prow, (kt * KTILE + 16 * i) * 2, 0);
-    } else {
-#pragma unroll
+    // ---- pass 2: probabilities and P.V ----
+    f32x16 oacc[NB];
+  #pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+  #pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[nb][e] = 0.f;
+    // probabilities leave as 16-byte pieces (S is a multiple of 8); pieces of rows or keys past S get the
+    // offset 2^31, which is beyond the buffer (at most 2^31 bytes) with or without the small scalar
+    // offset added, and are dropped by the store
+    const __amdgpu_buffer_rsrc_t rsP = __builtin_amdgcn_make_buffer_rsrc(P, 0, (int)(uint32_t)((int64_t)S * S * 2), 0x00020000);
+    const uint32_t prow = row_ok ? (uint32_t)((int64_t)row * S * 2) + 16u * fh : 0x80000000u;
+    auto store_p = [&](int kt, const u32x4(&pk)[4]) __attribute__((always_inline)) {
+      // whole tiles inside S (the usual case): the row offset plus a scalar; else per piece
+      if (kt * KTILE + KTILE <= S) {
+  #pragma unroll
+        for (int i = 0; i < 4; ++i) __builtin_amdgcn_raw_buffer_store_b128(pk[i], rsP, (int)prow, (kt * KTILE + 16 * i) * 2, 0);
+      } else {
+  #pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int key = kt * KTILE + 16 * i + 8 * fh;
+          const uint32_t off = (row_ok && key < S) ? prow + (uint32_t)(kt * KTILE + 16 * i) * 2 : 0x80000000u;
+          __builtin_amdgcn_raw_buffer_store_b128(pk[i], rsP, (int)off, 0, 0);
+        }
+      }
+    };
+    request(0, true);
+    for (int kt = 0; kt < n_tiles; ++kt) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (kt + 1 < n_tiles) request(kt + 1, true);
+      u32x4 pk[4];  // the wavefront's probabilities of this tile: four 16-byte pieces per row
+      if (CAUSAL && kt * KTILE > q0 + 31) {
+  #pragma unroll
+        for (int i = 0; i < 4; ++i) pk[i] = u32x4{0u, 0u, 0u, 0u};
+        store_p(kt, pk);
+        continue;
+      }
+      const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
+      const unsigned char* Vb = Kb + TILEB;
+      float s[32];
+      if (tile_plain(kt)) scores(false_type{}, Kb, kt, s);
+      else scores(true_type{}, Kb, kt, s);
+  #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int key = kt * KTILE + 16 * i + 8 * fh;
-        const uint32_t off = (row_ok && key < S) ? prow + (uint32_t)(kt * KTILE + 16 * i) * 2 : 0x80000000u;
-        __builtin_amdgcn_raw_buffer_store_b128(pk[i], rsP, (int)off, 0, 0);
+        bf16x8 t;
+  #pragma unroll
+        for (int e = 0; e < 8; ++e)
+          t[e] = static_cast<__bf16>(__builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * i + e], scale_log2e, -m)) * inv);  // exp2(-inf) = 0
+        pk[i] = __builtin_bit_cast(u32x4, t);
       }
-    }
-  };
-  request(0, true);
-  for (int kt = 0; kt < n_tiles; ++kt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < n_tiles) request(kt + 1, true);
-    u32x4 pk[4];  // the wavefront's probabilities of this tile: four 16-byte pieces per row
-    if (CAUSAL && kt * KTILE > q0 + 31) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) pk[i] = u32x4{0u, 0u, 0u, 0u};
       store_p(kt, pk);
-      continue;
-    }
-    const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
-    const unsigned char* Vb = Kb + TILEB;
-    float s[32];
-    if (tile_plain(kt)) scores(false_type{}, Kb, kt, s);
-    else scores(true_type{}, Kb, kt, s);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      bf16x8 t;
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-        t[e] = static_cast<__bf16>(__builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * i + e], scale_log2e, -m)) * inv);  // exp2(-inf) = 0
-      pk[i] = __builtin_bit_cast(u32x4, t);
-    }
-    store_p(kt, pk);
-    // P.V over the tile's 64 keys: four k-steps of 16
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      bf16x8 vt[NB];
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        const unsigned char* a0 = Vb + t * 16 * ROWB + vaddr[nb][0];
-        const unsigned char* a1 = Vb + t * 16 * ROWB + vaddr[nb][1];
-        const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(a0));
-        const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(a1));
-        typedef short v8i16 __attribute__((ext_vector_type(8)));
-        const v8i16 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        vt[nb] = __builtin_bit_cast(bf16x8, both);
+      // P.V over the tile's 64 keys: four k-steps of 16
+  #pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        bf16x8 vt[NB];
+  #pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const unsigned char* a0 = Vb + t * 16 * ROWB + vaddr[nb][0];
+          const unsigned char* a1 = Vb + t * 16 * ROWB + vaddr[nb][1];
+          const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(a0));
+          const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(a1));
+          typedef short v8i16 __attribute__((ext_vector_type(8)));
+          const v8i16 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          vt[nb] = __builtin_bit_cast(bf16x8, both);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pk[t]);
+  #pragma unroll
+        for (int nb = 0; nb < NB; ++nb) oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[nb], pf, oacc[nb], 0, 0, 0);
       }
-      __builtin_amdgcn_sched_barrier(0);
-      const bf16x8 pf = __builtin_bit_cast(bf16x8, pk[t]);
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[nb], pf, oacc[nb], 0, 0, 0);
     }
-  }
-  // keys past the last unmasked tile: zeros, so that every entry of the probability matrix is defined
-  {
-    u32x4 z[4];
+    // keys past the last unmasked tile: zeros, so that every entry of the probability matrix is defined
+    {
+      u32x4 z[4];
+  #pragma unroll
+      for (int i = 0; i < 4; ++i) z[i] = u32x4{0u, 0u, 0u, 0u};
+      for (int kt = n_tiles; kt < all_tiles; ++kt) store_p(kt, z);
+    }
+    // ---- output rows ----
+    if (row_ok) {
+  #pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+  #pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 o4;
+  #pragma unroll
+          for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(oacc[nb][4 * g + e]);
+          *reinterpret_cast<bf16x4*>(O + (int64_t)row * ldc + nb * 32 + 8 * g + 4 * fh) = o4;
+        }
+    }
+  } else {
+    // dS leaves (and P arrives) as 16-byte pieces, addressed like the forward kernel's stores
+    const __amdgpu_buffer_rsrc_t rsP = __builtin_amdgcn_make_buffer_rsrc(P, 0, (int)(uint32_t)((int64_t)S * S * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsD =
+        __builtin_amdgcn_make_buffer_rsrc(dprob + (int64_t)bh * S * S, 0, (int)(uint32_t)((int64_t)S * S * 2), 0x00020000);
+    const uint32_t prow = row_ok ? (uint32_t)((int64_t)row * S * 2) + 16u * fh : 0x80000000u;
+    auto piece_off = [&](int kt, int i) {
+      const int key = kt * KTILE + 16 * i + 8 * fh;
+      return (row_ok && key < S) ? prow + (uint32_t)(kt * KTILE + 16 * i) * 2 : 0x80000000u;
+    };
+    auto load_p = [&](int kt, u32x4(&pk)[4]) __attribute__((always_inline)) {
+      if (kt * KTILE + KTILE <= S) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) z[i] = u32x4{0u, 0u, 0u, 0u};
-    for (int kt = n_tiles; kt < all_tiles; ++kt) store_p(kt, z);
-  }
-  // ---- output rows ----
-  if (row_ok) {
+        for (int i = 0; i < 4; ++i) pk[i] = __builtin_amdgcn_raw_buffer_load_b128(rsP, (int)prow, (kt * KTILE + 16 * i) * 2, 0);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pk[i] = __builtin_amdgcn_raw_buffer_load_b128(rsP, (int)piece_off(kt, i), 0, 0);
+      }
+    };
+    auto store_ds = [&](int kt, const u32x4(&pk)[4]) __attribute__((always_inline)) {
+      if (kt * KTILE + KTILE <= S) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) __builtin_amdgcn_raw_buffer_store_b128(pk[i], rsD, (int)prow, (kt * KTILE + 16 * i) * 2, 0);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) __builtin_amdgcn_raw_buffer_store_b128(pk[i], rsD, (int)piece_off(kt, i), 0, 0);
+      }
+    };
+    auto above = [&](int kt) { return CAUSAL && kt * KTILE > q0 + 31; };  // wholly above the diagonal for this wavefront
+    f32x16 qacc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 o4;
+      for (int e = 0; e < 16; ++e) qacc[nb][e] = 0.f;
+    u32x4 pn[4];  // probabilities of the next tile, requested one tile ahead
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(oacc[nb][4 * g + e]);
-        *reinterpret_cast<bf16x4*>(O + (int64_t)row * ldc + nb * 32 + 8 * g + 4 * fh) = o4;
+    for (int i = 0; i < 4; ++i) pn[i] = u32x4{0u, 0u, 0u, 0u};
+    if (!above(0)) load_p(0, pn);
+    request(0, true);
+    for (int kt = 0; kt < n_tiles; ++kt) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      u32x4 pk[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pk[i] = pn[i];
+      if (kt + 1 < n_tiles) {
+        if (!above(kt + 1)) load_p(kt + 1, pn);
+        request(kt + 1, true);
       }
+      if (above(kt)) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pk[i] = u32x4{0u, 0u, 0u, 0u};
+        store_ds(kt, pk);
+        continue;
+      }
+      const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
+      const unsigned char* Vb = Kb + TILEB;
+      float s[32];  // dP of the tile; P is zero at every masked position, so no mask is needed
+      scores(false_type{}, Vb, kt, s);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pk[i]);
+        bf16x8 t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = static_cast<__bf16>(scale * (float)pf[e] * (s[8 * i + e] - Drow));
+        pk[i] = __builtin_bit_cast(u32x4, t);
+      }
+      store_ds(kt, pk);
+      // dQ += dS . K over the tile's 64 keys: four k-steps of 16, K^T by transposing reads
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        bf16x8 kt_[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const unsigned char* a0 = Kb + t * 16 * ROWB + vaddr[nb][0];
+          const unsigned char* a1 = Kb + t * 16 * ROWB + vaddr[nb][1];
+          const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(a0));
+          const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(a1));
+          typedef short v8i16 __attribute__((ext_vector_type(8)));
+          const v8i16 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          kt_[nb] = __builtin_bit_cast(bf16x8, both);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const bf16x8 df = __builtin_bit_cast(bf16x8, pk[t]);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) qacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_[nb], df, qacc[nb], 0, 0, 0);
+      }
+    }
+    {
+      u32x4 z[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) z[i] = u32x4{0u, 0u, 0u, 0u};
+      for (int kt = n_tiles; kt < all_tiles; ++kt) store_ds(kt, z);
+    }
+    if (row_ok) {
+      bf16* dq = dqkv + (int64_t)b * S * ld + (int64_t)h * HD + (int64_t)row * ld;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 o4;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(qacc[nb][4 * g + e]);
+          *reinterpret_cast<bf16x4*>(dq + nb * 32 + 8 * g + 4 * fh) = o4;
+        }
+    }
   }
 }
 
@@ -332,10 +466,12 @@ bool attention_fwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc,
          (reinterpret_cast<uintptr_t>(ctx) & 7) == 0;
 }
 
-hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, void* prob, void* ctx,
-                               int64_t ldc, hipStream_t st) {
+namespace {
+template <bool BWD_>
+hipError_t attn_launch(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, void* prob, void* ctx, int64_t ldc,
+                       const void* dctx, void* dprob, void* dqkv, hipStream_t st) {
   if (B == 0 || H == 0 || S == 0) return hipSuccess;
-  const float sl2 = (1.0f / sqrtf((float)hd)) * 1.4426950408889634f;
+  const float sc = (1.0f / sqrtf((float)hd)) * (BWD_ ? 1.0f : 1.4426950408889634f);
   // 128-row workgroups when there are enough of them to give every compute unit two; else 64-row ones
   const bool big = (int64_t)B * H * ((S + 127) / 128) >= 512;
   const int qb = big ? 128 : 64;
@@ -345,10 +481,13 @@ hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const v
   const bf16* x = reinterpret_cast<const bf16*>(qkv);
   bf16* p = reinterpret_cast<bf16*>(prob);
   bf16* o = reinterpret_cast<bf16*>(ctx);
-#define ATTN_LAUNCH(HD_, C_)                                                                      \
-  do {                                                                                            \
-    if (big) attn_fwd_k<HD_, C_, 4><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sl2, p, o, ldc);    \
-    else attn_fwd_k<HD_, C_, 2><<<grid, 128, 0, st>>>(x, ld, S, H, B * H, sl2, p, o, ldc);        \
+  const bf16* dO = reinterpret_cast<const bf16*>(dctx);
+  bf16* dS = reinterpret_cast<bf16*>(dprob);
+  bf16* dq = reinterpret_cast<bf16*>(dqkv);
+#define ATTN_LAUNCH(HD_, C_)                                                                                 \
+  do {                                                                                                       \
+    if (big) attn_k<HD_, C_, 4, BWD_><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sc, p, o, ldc, dO, dS, dq);  \
+    else attn_k<HD_, C_, 2, BWD_><<<grid, 128, 0, st>>>(x, ld, S, H, B * H, sc, p, o, ldc, dO, dS, dq);      \
   } while (0)
   if (hd == 128) {
     if (causal) ATTN_LAUNCH(128, true); else ATTN_LAUNCH(128, false);
@@ -359,6 +498,23 @@ hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const v
   }
 #undef ATTN_LAUNCH
   return hipGetLastError();
+}
+}  // namespace
+
+hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, void* prob, void* ctx,
+                               int64_t ldc, hipStream_t st) {
+  return attn_launch<false>(B, H, S, hd, causal, qkv, ld, prob, ctx, ldc, nullptr, nullptr, nullptr, st);
+}
+
+bool attention_bwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* prob, const void* ctx,
+                                 const void* dctx, const void* dprob, const void* dqkv) {
+  return attention_fwd_fused_applies(dt, S, hd, ld, ldc, qkv, prob, ctx) && ldc % 8 == 0 && al16(ctx) && al16(dctx) && al16(dprob) &&
+         (reinterpret_cast<uintptr_t>(dqkv) & 7) == 0;
+}
+
+hipError_t attention_bwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* prob,
+                               const void* ctx, const void* dctx, int64_t ldc, void* dprob, void* dqkv, hipStream_t st) {
+  return attn_launch<true>(B, H, S, hd, causal, qkv, ld, const_cast<void*>(prob), const_cast<void*>(ctx), ldc, dctx, dprob, dqkv, st);
 }
 
 }  // namespace hift

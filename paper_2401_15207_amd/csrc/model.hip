@@ -616,7 +616,14 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
     Scope sc(M, CAT_ATTN, fl);
     K_TRY(gemm(g, M->cs));
   }
-  {
+  static const bool fused_on = [] { const char* e = getenv("HIFT_ATTN_FUSED"); return !(e && e[0] == '0'); }();
+  const bool fused = fused_on && attention_bwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, a.prob, a.ctx, dctx, M->dprob, M->dqkv);
+  if (fused) {
+    // dp, the softmax backward and dq in one kernel; dp never reaches memory
+    Scope sc(M, CAT_ATTN, 2 * fl);
+    K_TRY(attention_bwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, a.prob, a.ctx, dctx, d, M->dprob, M->dqkv, M->cs));
+  }
+  if (!fused) {
     Gemm g;  // dp[i,j] = sum_e dctx[i,e] v[j,e]
     batch(g);
     g.M = S; g.N = S; g.K = hd;
@@ -627,11 +634,11 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
     Scope sc(M, CAT_ATTN, fl);
     K_TRY(gemm(g, M->cs));
   }
-  {
+  if (!fused) {
     Scope sc(M, CAT_ELEM, 0);
     K_TRY(softmax_bwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, a.prob, M->dprob, M->cs));
   }
-  {
+  if (!fused) {
     Gemm g;  // dq[i,e] = sum_j ds[i,j] k[j,e]
     batch(g);
     g.M = S; g.N = hd; g.K = S;
@@ -1667,6 +1674,18 @@ hift_status hift_kernel_attention_fwd(int32_t batch, int32_t heads, int32_t seq,
   if (!attention_fwd_fused_applies(DT_BF16, seq, head_dim, 3 * d, d, qkv, prob, ctx))
     return fail(HIFT_EINVAL, "the fused kernel takes bf16, head widths 64 and 128 and 16-byte aligned buffers");
   HIP_TRY(attention_fwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, ctx, d, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_attention_bwd_query(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
+                                            const void* qkv, const void* prob, const void* ctx, const void* dctx, void* dprob,
+                                            void* dqkv, void* stream) {
+  const int64_t d = (int64_t)heads * head_dim;
+  if (batch < 0 || heads < 1 || seq < 0 || !qkv || !prob || !ctx || !dctx || !dprob || !dqkv) return fail(HIFT_EINVAL, "bad argument");
+  if (!attention_bwd_fused_applies(DT_BF16, seq, head_dim, 3 * d, d, qkv, prob, ctx, dctx, dprob, dqkv))
+    return fail(HIFT_EINVAL, "the fused kernel takes bf16, head widths 64 and 128 and 16-byte aligned buffers");
+  HIP_TRY(attention_bwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, ctx, dctx, d, dprob, dqkv,
+                              (hipStream_t)stream));
   return HIFT_OK;
 }
 
