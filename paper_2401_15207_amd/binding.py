@@ -95,6 +95,7 @@ _SIGS = {
     "hift_kernel_gemm_packed": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp],
     "hift_kernel_optimizer": [_P(Opt), _i64, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_norm_fwd": [_i32, _i32, _i64, _i32, C.c_float, _vp, _vp, _vp, _vp, _vp, _vp],
+    "hift_kernel_linear_fused": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _vp],
     "hift_kernel_attention_fwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
     "hift_kernel_attention_bwd_query": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_cross_entropy": [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp],
@@ -214,6 +215,16 @@ def kernel_norm_fwd(dtype, rms, rows, d, eps, x, g, b, y, stats, stream=None):
     import torch
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib.hift_kernel_norm_fwd(dtype, int(rms), rows, d, eps, _ptr(x), _ptr(g), _ptr(b), _ptr(y), _ptr(stats), st))
+
+
+EPILOGUE_SWIGLU, EPILOGUE_ROPE = 1, 2
+
+
+def kernel_linear_fused(epilogue, M, N, K, A, lda, W, packed_scratch, C, act, cos_sin, seq, rot_cols, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_linear_fused(epilogue, M, N, K, _ptr(A), lda, _ptr(W), _ptr(packed_scratch), _ptr(C), _ptr(act),
+                                        _ptr(cos_sin), seq, rot_cols, st))
 
 
 def kernel_attention_fwd(batch, heads, seq, head_dim, causal, qkv, prob, ctx, stream=None):

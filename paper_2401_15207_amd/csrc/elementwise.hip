@@ -369,6 +369,13 @@ __global__ void __launch_bounds__(BLK) gelu_k(int64_t n, const T* __restrict__ d
   stv<T, V>(out + i, o);
 }
 
+// 1 / (1 + e^-x) with the hardware's base-2 exponential and reciprocal (about 1e-7 relative each): with
+// the library's expf and an IEEE division these kernels are bound by instruction issue, not by memory.
+// e^-x = inf for x < -88 and 1 / inf = 0.
+__device__ __forceinline__ float sigmoid_fast(float x) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
+
 template <typename T, int V>
 __global__ void __launch_bounds__(BLK) swiglu_fwd_k(int64_t T_, int f, const T* __restrict__ gu, T* __restrict__ act) {
   const int fv = f / V;
@@ -380,7 +387,7 @@ __global__ void __launch_bounds__(BLK) swiglu_fwd_k(int64_t T_, int f, const T* 
   ldv<T, V>(gu + t * 2 * f + j, g);
   ldv<T, V>(gu + t * 2 * f + f + j, u);
 #pragma unroll
-  for (int e = 0; e < V; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+  for (int e = 0; e < V; ++e) o[e] = g[e] * sigmoid_fast(g[e]) * u[e];
   stv<T, V>(act + t * f + j, o);
 }
 
@@ -398,7 +405,7 @@ __global__ void __launch_bounds__(BLK) swiglu_bwd_k(int64_t T_, int f, const T* 
   ldv<T, V>(dact + t * f + j, da);
 #pragma unroll
   for (int e = 0; e < V; ++e) {
-    const float s = 1.0f / (1.0f + expf(-g[e]));
+    const float s = sigmoid_fast(g[e]);
     dg[e] = da[e] * u[e] * s * (1.0f + g[e] * (1.0f - s));
     du[e] = da[e] * g[e] * s;
   }
@@ -568,7 +575,7 @@ __global__ void __launch_bounds__(BLK) ce_row_k(int64_t rows, int vocab, T* __re
     float a[V];
     ldv<T, V>(lr + j, a);
 #pragma unroll
-    for (int e = 0; e < V; ++e) sum += expf(a[e] - mx);
+    for (int e = 0; e < V; ++e) sum += __builtin_amdgcn_exp2f((a[e] - mx) * 1.4426950408889634f);  // hardware exponential: 1e-7 relative
   }
   sum = block_sum<BLK / 64>(sum, red);
   const float lse = mx + logf(sum), inv = 1.0f / sum;
@@ -578,7 +585,7 @@ __global__ void __launch_bounds__(BLK) ce_row_k(int64_t rows, int vocab, T* __re
     float a[V];
     ldv<T, V>(lr + j, a);
 #pragma unroll
-    for (int e = 0; e < V; ++e) a[e] = (expf(a[e] - mx) * inv - (j + e == lab ? 1.f : 0.f)) * inv_n;
+    for (int e = 0; e < V; ++e) a[e] = (__builtin_amdgcn_exp2f((a[e] - mx) * 1.4426950408889634f) * inv - (j + e == lab ? 1.f : 0.f)) * inv_n;
     stv<T, V>(lr + j, a);
   }
 }

@@ -36,6 +36,9 @@ struct GemmP {
   int64_t sa1, sa2, sb1, sb2, sc1, sc2;
   int tiles_m, tiles_n;
   int band = 0;
+  // fused epilogues of the packed-operand kernel
+  void* C2 = nullptr; int64_t ldc2 = 0;
+  const float2* cos_sin = nullptr; int S = 1; int64_t rot_cols = 0;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -420,9 +423,24 @@ __device__ __forceinline__ void load_to_lds_b128(u32x4 rsrc, uint32_t lds_addr, 
 // leaves the buffer.
 constexpr int PKF = 8;  // k-steps of B fragments in flight per wavefront
 
+// Position in the packed copy of the 32-row block s of B (half = blocks in half of B).
+__device__ __forceinline__ int64_t pk_block_pos(int64_t s, int order, int64_t half) {
+  if (order == PK_ORDER_HALVES) {
+    if (s >= 2 * half) return s;  // no such block: N is a multiple of 256 in this order
+    const int64_t h = s >= half ? 1 : 0, i = s - h * half;
+    return (i >> 2) * 8 + (i & 3) * 2 + h;
+  }
+  if (order == PK_ORDER_PAIR64) {
+    const int64_t q = s & 3;
+    return (s & ~int64_t(3)) | (q == 1 ? 2 : q == 2 ? 1 : q);
+  }
+  return s;
+}
+
 // Generic packer (any alignment): one wavefront per 1 KB block, element-wise reads.
 __global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int64_t ldb, int64_t N, int64_t K,
-                                                 bool b_kmajor, u32x4* __restrict__ Bp, int64_t n_blocks, int64_t k_steps) {
+                                                 bool b_kmajor, u32x4* __restrict__ Bp, int64_t n_blocks, int64_t k_steps,
+                                                 int order, int64_t half) {
   const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (w >= n_blocks * k_steps) return;
   const int lane = threadIdx.x & 63;
@@ -436,7 +454,7 @@ __global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int6
     if (n < N && k < K) x = static_cast<float>(b_kmajor ? B[n * ldb + k] : B[k * ldb + n]);
     v[e] = static_cast<__bf16>(x);
   }
-  Bp[w * 64 + lane] = __builtin_bit_cast(u32x4, v);
+  Bp[(pk_block_pos(nb, order, half) * k_steps + kk) * 64 + lane] = __builtin_bit_cast(u32x4, v);
 }
 
 // Packer for 16-byte aligned sources: a workgroup moves a 16 KB tile through LDS so that both the
@@ -445,7 +463,8 @@ __global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int6
 //   else:   tile = 32 k (two k-steps) x 256 n (eight n-blocks); source rows are contiguous in n.
 template <bool KMAJOR>
 __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B, int64_t ldb, int64_t N, int64_t K,
-                                                      u32x4* __restrict__ Bp, int64_t k_steps, int tiles_inner) {
+                                                      u32x4* __restrict__ Bp, int64_t k_steps, int tiles_inner, int order,
+                                                      int64_t half) {
   constexpr int PITCH = 512 + 16;  // bytes per tile row in LDS; the pad spreads 16-byte reads of one column over the banks
   __shared__ __attribute__((aligned(16))) unsigned char tile[32 * PITCH];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -467,7 +486,7 @@ __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B,
       const int kkl = wave * 4 + j;
       const int64_t kk = ti * 16 + kkl;
       if (kk < k_steps)
-        Bp[(nb * k_steps + kk) * 64 + lane] =
+        Bp[(pk_block_pos(nb, order, half) * k_steps + kk) * 64 + lane] =
             *reinterpret_cast<const u32x4*>(tile + (lane & 31) * PITCH + (kkl * 16 + (lane >> 5) * 8) * 2);
     }
   } else {
@@ -495,7 +514,7 @@ __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B,
 #pragma unroll
       for (int e = 0; e < 8; ++e)
         t[e] = *reinterpret_cast<const bf16*>(tile + (kkl * 16 + (lane >> 5) * 8 + e) * PITCH + (nbl * 32 + (lane & 31)) * 2);
-      Bp[((ti * 8 + nbl) * k_steps + kk0 + kkl) * 64 + lane] = __builtin_bit_cast(u32x4, t);
+      Bp[(pk_block_pos(ti * 8 + nbl, order, half) * k_steps + kk0 + kkl) * 64 + lane] = __builtin_bit_cast(u32x4, t);
     }
   }
 }
@@ -516,7 +535,103 @@ __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B,
 // numbers of rounds over 256 compute units more often than 256 x 256 does, and ran faster.
 constexpr int PK_DK = 64, PK_STAGES = 4, PK_RD = 3, PK_ROW = 128;
 
-template <int MT, bool VEC_EPI, typename OutT>
+// Fused epilogues of the packed-operand kernel (bf16 output).  The packed copy holds B's 32-row blocks in
+// an order (PK_ORDER_*) that puts, side by side in a wavefront's two accumulator columns, the blocks
+// that are combined element by element: gate and up block of the same features (EPI_SWIGLU), or a
+// block and the one 64 columns further in the same head (EPI_ROPE).  A wavefront stages 64 rows of its
+// 64 accumulator columns in LDS as fp32 and walks whole rows: lane -> (row, one of eight 8-column
+// chunks); chunks 0..3 are of the first block, 4..7 the same columns of the second.
+// x / (1 + e^-x) with the hardware's base-2 exponential and reciprocal (about 1e-7 relative each; the
+// library's expf and the IEEE division cost more than the memory traffic of the elementwise kernels).
+// e^-x = inf for x < -88: 1 / inf = 0 and the result is -0.
+__device__ __forceinline__ float silu_fast(float x) {
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
+
+template <int MT, int EPI>
+__device__ __forceinline__ void store_tile_fused(const GemmP& p, f32x16 (&acc)[MT][2], unsigned char* smem, int64_t m0, int tn,
+                                                 int wave, int lane) {
+  constexpr int RP = 64, PITCH = 64 * 4 + 16;
+  static_assert((32 * MT) % RP == 0, "whole passes");
+  const int frow = lane & 31, fhalf = lane >> 5;
+  unsigned char* reg = smem + wave * (RP * PITCH);
+  const int cc = lane & 7, rr = lane >> 3, half = cc >> 2, c4 = cc & 3;
+  // column of this lane's own chunk in C
+  const int64_t col = EPI == EPI_SWIGLU ? (int64_t)half * (p.N / 2) + 128 * (int64_t)tn + 32 * wave + 8 * c4
+                                        : 256 * (int64_t)tn + 128 * (wave >> 1) + 32 * (wave & 1) + 64 * half + 8 * c4;
+  bf16* C = reinterpret_cast<bf16*>(p.C);
+#pragma unroll
+  for (int pass = 0; pass < 32 * MT / RP; ++pass) {
+    __syncthreads();  // operand tiles (first pass) or the previous pass are no longer read
+#pragma unroll
+    for (int ii = 0; ii < RP / 32; ++ii)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int i = pass * (RP / 32) + ii;
+          const f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          *reinterpret_cast<f32x4*>(reg + (ii * 32 + frow) * PITCH + (j * 32 + 8 * g + 4 * fhalf) * 4) = v;
+        }
+    __syncthreads();
+    if (EPI == EPI_SWIGLU && C) {  // the pre-activations: each lane its own chunk, 8 rows per sweep
+#pragma unroll 2
+      for (int it = 0; it < RP / 8; ++it) {
+        const int lr = it * 8 + rr;
+        const int64_t row = m0 + pass * RP + lr;
+        if (row >= p.M) continue;
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + cc * 32);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + cc * 32 + 16);
+        bf16x8 t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { t[e] = static_cast<__bf16>(lo[e]); t[4 + e] = static_cast<__bf16>(hi[e]); }
+        *reinterpret_cast<bf16x8*>(C + row * p.ldc + col) = t;
+      }
+    }
+    // the combining step: lane -> (row, 8 columns of the first block and the same of the second), 16 rows per sweep
+    const int q4 = lane & 3, r16 = lane >> 2;
+#pragma unroll 2
+    for (int it = 0; it < RP / 16; ++it) {
+      const int lr = it * 16 + r16;
+      const int64_t row = m0 + pass * RP + lr;
+      if (row >= p.M) continue;
+      float x1[8], x2[8];
+      *reinterpret_cast<f32x4*>(x1) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + q4 * 32);
+      *reinterpret_cast<f32x4*>(x1 + 4) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + q4 * 32 + 16);
+      *reinterpret_cast<f32x4*>(x2) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + (q4 + 4) * 32);
+      *reinterpret_cast<f32x4*>(x2 + 4) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + (q4 + 4) * 32 + 16);
+      if (EPI == EPI_SWIGLU) {  // x1 = gate, x2 = up: the activation from the values as they are stored
+        bf16x8 a;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float g = static_cast<float>(static_cast<__bf16>(x1[e])), u = static_cast<float>(static_cast<__bf16>(x2[e]));
+          a[e] = static_cast<__bf16>(silu_fast(g) * u);
+        }
+        *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(p.C2) + row * p.ldc2 + 128 * (int64_t)tn + 32 * wave + 8 * q4) = a;
+      } else {
+        const int64_t c1 = 256 * (int64_t)tn + 128 * (wave >> 1) + 32 * (wave & 1) + 8 * q4;  // x1's column; x2's is 64 further
+        bf16x8 t1, t2;
+        if (c1 < p.rot_cols) {
+          // pairs (x1, x2) at frequencies 32 (wave & 1) + 8 q4 ..+7:  x1' = x1 cos - x2 sin,  x2' = x2 cos + x1 sin
+          const float2* cs = p.cos_sin + (int64_t)((uint32_t)row % (uint32_t)p.S) * 64 + 32 * (wave & 1) + 8 * q4;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float2 c = cs[e];
+            t1[e] = static_cast<__bf16>(x1[e] * c.x - x2[e] * c.y);
+            t2[e] = static_cast<__bf16>(x2[e] * c.x + x1[e] * c.y);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { t1[e] = static_cast<__bf16>(x1[e]); t2[e] = static_cast<__bf16>(x2[e]); }
+        }
+        *reinterpret_cast<bf16x8*>(C + row * p.ldc + c1) = t1;
+        *reinterpret_cast<bf16x8*>(C + row * p.ldc + c1 + 64) = t2;
+      }
+    }
+  }
+}
+
+template <int MT, bool VEC_EPI, typename OutT, int EPI = EPI_NONE>
 __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restrict__ Bp, int64_t k_steps) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BM = 32 * MT, BN = 256, WN = 64, NT = 2;
@@ -651,7 +766,8 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stray requests must land before LDS is reused
 
-  store_tile<BM, WN, VEC_EPI, OutT>(p, acc, smem, m0, n0, 0, wave, wave, lane, 0, 0);
+  if constexpr (EPI == EPI_NONE) store_tile<BM, WN, VEC_EPI, OutT>(p, acc, smem, m0, n0, 0, wave, wave, lane, 0, 0);
+  else store_tile_fused<MT, EPI>(p, acc, smem, m0, tn, wave, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -765,22 +881,25 @@ size_t packed_b_bytes(int64_t N, int64_t K) {
   return (size_t)((N + 255) / 256) * 8 * (size_t)(K / 16) * 1024;
 }
 
-hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st) {
+hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st, int order) {
   if (packed_b_bytes(N, K) == 0) return hipErrorInvalidValue;
+  if (order == PK_ORDER_HALVES ? N % 256 != 0 : order == PK_ORDER_PAIR64 ? N % 128 != 0 : order != PK_ORDER_PLAIN)
+    return hipErrorInvalidValue;
+  const int64_t half = N / 64;  // 32-row blocks in half of B
   const int64_t n_blocks = ((N + 255) / 256) * 8, k_steps = K / 16;
   const bf16* Bs = reinterpret_cast<const bf16*>(B);
   u32x4* out = reinterpret_cast<u32x4*>(Bp);
   if (al16(B) && ldb % 8 == 0) {
     if (b_kmajor) {
       const int ti = (int)((K + 255) / 256);
-      pack_b_tile_k<true><<<dim3((unsigned)(n_blocks * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti);
+      pack_b_tile_k<true><<<dim3((unsigned)(n_blocks * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti, order, half);
     } else {
       const int ti = (int)(n_blocks / 8);
-      pack_b_tile_k<false><<<dim3((unsigned)((K / 32) * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti);
+      pack_b_tile_k<false><<<dim3((unsigned)((K / 32) * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti, order, half);
     }
   } else {
     const int64_t blocks = n_blocks * k_steps;
-    pack_b_k<<<dim3((unsigned)((blocks + 3) / 4)), 256, 0, st>>>(Bs, ldb, N, K, b_kmajor, out, n_blocks, k_steps);
+    pack_b_k<<<dim3((unsigned)((blocks + 3) / 4)), 256, 0, st>>>(Bs, ldb, N, K, b_kmajor, out, n_blocks, k_steps, order, half);
   }
   return hipGetLastError();
 }
@@ -805,6 +924,21 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   p.A = g.A; p.lda = g.lda; p.B = nullptr; p.ldb = 0; p.C = g.C; p.ldc = g.ldc;
   p.bias = g.bias; p.R = g.R; p.ldr = g.ldr;
   p.nh = 1; p.sa1 = p.sa2 = p.sb1 = p.sb2 = p.sc1 = p.sc2 = 0;
+  if (g.epi != EPI_NONE) {
+    // the fused epilogues write bf16 rows in 16-byte pieces and take neither bias nor residual
+    if (g.out_f32 || g.bias || g.R) return hipErrorInvalidValue;
+    if (g.epi == EPI_SWIGLU) {
+      if (g.N % 256 != 0 || !g.C2 || !al16(g.C2) || g.ldc2 % 8 != 0 || g.ldc2 < g.N / 2) return hipErrorInvalidValue;
+    } else if (g.epi == EPI_ROPE) {
+      if (g.N % 256 != 0 || !g.C || !g.cos_sin || g.S < 1 || g.rot_cols % 128 != 0 || g.rot_cols > g.N ||
+          (reinterpret_cast<uintptr_t>(g.cos_sin) & 7) != 0)
+        return hipErrorInvalidValue;
+    } else {
+      return hipErrorInvalidValue;
+    }
+    p.C2 = g.C2; p.ldc2 = g.ldc2;
+    p.cos_sin = reinterpret_cast<const float2*>(g.cos_sin); p.S = g.S > 0 ? g.S : 1; p.rot_cols = g.rot_cols;
+  }
   constexpr int OPER = PK_STAGES * 32 * PK_MT * PK_ROW;  // ring of A stages
   constexpr int STAGE = 4 * 64 * (64 * 4 + 16);          // fp32 epilogue staging, 4 waves
   constexpr int LDS = STAGE > OPER ? STAGE : OPER;
@@ -816,6 +950,24 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   if (g.out_f32) {
     static bool attr_done = false;
     auto kern = gemm_pk_k<PK_MT, true, float>;
+    if (!attr_done) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+      if (e != hipSuccess) return e;
+      attr_done = true;
+    }
+    kern<<<grid, 256, LDS, st>>>(p, bp, p.K / 16);
+  } else if (g.epi == EPI_SWIGLU) {
+    static bool attr_done = false;
+    auto kern = gemm_pk_k<PK_MT, true, bf16, EPI_SWIGLU>;
+    if (!attr_done) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+      if (e != hipSuccess) return e;
+      attr_done = true;
+    }
+    kern<<<grid, 256, LDS, st>>>(p, bp, p.K / 16);
+  } else if (g.epi == EPI_ROPE) {
+    static bool attr_done = false;
+    auto kern = gemm_pk_k<PK_MT, true, bf16, EPI_ROPE>;
     if (!attr_done) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
       if (e != hipSuccess) return e;

@@ -30,7 +30,18 @@ struct Gemm {
   //   BAND_K_UPTO_ROW   A(m,k) = 0 for k > m: the contraction of a tile stops at its last row
   //   BAND_K_FROM_ROW   A(m,k) = 0 for k < m: the contraction of a tile starts at its first row
   int band = 0;
+  // Fused epilogue of the packed-operand kernel (gemm_packed only; the packed copy must have been built
+  // with the matching column order, see pack_b):
+  //   EPI_SWIGLU  B = gate | up, N = 2 f.  C [M, N] (may be null: not kept) receives the pre-activations as
+  //               usual; C2 [M, f] (ldc2) receives silu(gate) * up computed from the rounded pre-activations.
+  //   EPI_ROPE    B = q | k | v of heads of width 128.  Columns below rot_cols are rotated pairwise
+  //               (i, i + 64 within a head) by the angle of position (row % S) before the one rounding;
+  //               cos_sin: [>= S, 64] pairs (cos, sin), fp32.
+  int epi = 0;
+  void* C2 = nullptr; int64_t ldc2 = 0;
+  const void* cos_sin = nullptr; int S = 0; int64_t rot_cols = 0;
 };
+enum { EPI_NONE = 0, EPI_SWIGLU = 1, EPI_ROPE = 2 };
 enum { BAND_NONE = 0, BAND_SKIP_UPPER = 1, BAND_K_UPTO_ROW = 2, BAND_K_FROM_ROW = 3 };
 // variant (optional) receives which kernel ran: 0 plain FMA, 1 MFMA 128x128 tiles, 2 MFMA 256x256 tiles
 hipError_t gemm(const Gemm& g, hipStream_t st, int* variant = nullptr);
@@ -39,8 +50,16 @@ hipError_t gemm(const Gemm& g, hipStream_t st, int* variant = nullptr);
 // copy of a [N, K] operand, 0 if the shape cannot be packed.  pack_b: builds it from B given as in Gemm
 // (b_kmajor or transposed).  gemm_packed: C = A . B^T with A k-major and B packed; only for problems
 // packed_gemm_applies() accepts (g.B / g.ldb are ignored).
+// The packed copy may hold the 32-row blocks of B in another order, so that the two blocks a wavefront
+// multiplies side by side are the ones a fused epilogue combines element by element:
+//   PK_ORDER_HALVES  block i of the first half of B next to block i of the second half (EPI_SWIGLU;
+//                    N / 2 must be a multiple of 128)
+//   PK_ORDER_PAIR64  within every four blocks the middle two exchanged: a block next to the one 64
+//                    rows further (EPI_ROPE; N must be a multiple of 128)
+enum { PK_ORDER_PLAIN = 0, PK_ORDER_HALVES = 1, PK_ORDER_PAIR64 = 2 };
 size_t packed_b_bytes(int64_t N, int64_t K);
-hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st);
+hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st,
+                  int order = PK_ORDER_PLAIN);
 bool packed_gemm_applies(const Gemm& g);
 hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st);
 

@@ -50,6 +50,7 @@ struct Tensor {
   // byte offsets of the copies in MFMA fragment order inside the packed-weight arena, or -1:
   // pk_fwd packs w as [rows, cols] (forward, y = x . w^T), pk_bwd packs w^T (dX = dY . w)
   int64_t pk_fwd = -1, pk_bwd = -1;
+  int pk_order = PK_ORDER_PLAIN;  // block order of the forward copy (which fused epilogue it is made for)
   int64_t fac_off = 0;  // Adafactor: first float of this tensor's statistics ([rows | cols], or [rows] for vectors)
   int64_t fac_count() const { return cols > 1 ? rows + cols : rows; }
   int64_t count() const { return rows * cols; }
@@ -424,6 +425,15 @@ hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_o
     if (packed_gemm_applies(g)) {
       t.pk_fwd = (int64_t)M->wpk_bytes;
       M->wpk_bytes += (packed_b_bytes(t.rows, t.cols) + 255) & ~(size_t)255;
+      // forward copies of the RMSNorm/RoPE/SwiGLU decoder whose epilogue applies the rotation or the gated
+      // activation; HIFT_EPI_FUSED=0 in the environment keeps the separate kernels
+      static const bool epi_on = [] { const char* e = getenv("HIFT_EPI_FUSED"); return !(e && e[0] == '0'); }();
+      const bool layer_t = t.unit >= 1 && t.unit <= cfg->n_layers;
+      const std::string leaf = t.name.substr(t.name.find('.') + 1);
+      if (epi_on && layer_t && cfg->arch == HIFT_ARCH_RMS_ROPE_DECODER && t.rows % 256 == 0) {
+        if (leaf == "wqkv" && cfg->d_model / cfg->n_heads == 128) t.pk_order = PK_ORDER_PAIR64;
+        if (leaf == "wgu") t.pk_order = PK_ORDER_HALVES;
+      }
     }
     g.N = t.cols; g.K = t.rows; g.lda = t.rows; g.ldc = t.cols; g.ldr = t.cols;
     if (packed_gemm_applies(g)) {
@@ -440,7 +450,7 @@ hipError_t repack_units(hift_model* M, int ulo, int uhi) {
   for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
     const Tensor& t = M->lay.t[i];
     if (t.pk_fwd >= 0) {
-      hipError_t e = pack_b(M->W(t), t.cols, t.rows, t.cols, true, M->wpk + t.pk_fwd, M->cs);
+      hipError_t e = pack_b(M->W(t), t.cols, t.rows, t.cols, true, M->wpk + t.pk_fwd, M->cs, t.pk_order);
       if (e != hipSuccess) return e;
     }
     if (t.pk_bwd >= 0) {
@@ -485,8 +495,19 @@ struct Scope {
   } while (0)
 
 
+// What a linear layer's epilogue may take over when the weight's packed copy is ordered for it:
+// the rotary embedding of q and k (S = sequence length), or the gated activation (act [rows, out/2];
+// keep_pre = false: the pre-activations are not needed later and y is not written).  fused reports
+// whether it did; if not, y holds the plain product and the caller runs the separate kernel.
+struct LinEpi {
+  int S = 0;
+  void* act = nullptr;
+  bool keep_pre = true;
+  bool fused = false;
+};
+
 hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, const Tensor* bias, const void* R,
-                   void* y) {
+                   void* y, LinEpi* epi = nullptr) {
   // y[rows, out] = x[rows, in] . w[out, in]^T (+ bias) (+ R)
   Gemm g;
   g.dtype = M->dt;
@@ -498,6 +519,19 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
   g.R = R; g.ldr = w.rows;
   Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
   if (w.pk_fwd >= 0 && packed_gemm_applies(g)) {
+    if (w.pk_order != PK_ORDER_PLAIN) {
+      // the copy's block order is undone only by the epilogue it was made for
+      if (!epi || bias || R) return fail(HIFT_ESTATE, "packed copy ordered for a fused epilogue used without one");
+      if (w.pk_order == PK_ORDER_HALVES) {
+        g.epi = EPI_SWIGLU;
+        g.C2 = epi->act; g.ldc2 = w.rows / 2;
+        if (!epi->keep_pre) g.C = nullptr;
+      } else {
+        g.epi = EPI_ROPE;
+        g.cos_sin = M->cos_sin; g.S = epi->S; g.rot_cols = 2 * (int64_t)M->cfg.d_model;
+      }
+      epi->fused = true;
+    }
     K_TRY(gemm_packed(g, M->wpk + w.pk_fwd, M->cs));
     return HIFT_OK;
   }
@@ -690,7 +724,8 @@ hift_status ew(hift_model* M, hipError_t e) {
   return HIFT_OK;
 }
 
-hift_status forward(hift_model* M, const hift_batch* bt) {
+// keep_from: lowest unit the backward pass will reach; layers below it keep no pre-activations
+hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
   const hift_config& c = M->cfg;
   const int B = bt->batch, S = bt->seq;
   const int64_t T = (int64_t)B * S;
@@ -715,8 +750,10 @@ hift_status forward(hift_model* M, const hift_batch* bt) {
       ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, x, M->W(*n.n1g), n.n1b ? M->W(*n.n1b) : nullptr, a.na, a.st1, st)));
       h1 = a.na;
     }
-    ST_TRY(linear(M, h1, T, *n.wqkv, n.bqkv, nullptr, a.qkv));
-    if (rms) {
+    LinEpi rot;
+    rot.S = S;
+    ST_TRY(linear(M, h1, T, *n.wqkv, n.bqkv, nullptr, a.qkv, &rot));
+    if (rms && !rot.fused) {
       Scope sc(M, CAT_ELEM, 0);
       ST_TRY(ew(M, rope(dt, a.qkv, T, S, H, hd, M->cos_sin, +1, st)));
     }
@@ -734,8 +771,11 @@ hift_status forward(hift_model* M, const hift_batch* bt) {
       ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, a.xmid, M->W(*n.n2g), n.n2b ? M->W(*n.n2b) : nullptr, a.nb, a.st2, st)));
       h2 = a.nb;
     }
-    ST_TRY(linear(M, h2, T, *n.w1, n.b1, nullptr, a.fpre));
-    {
+    LinEpi gate;
+    gate.act = a.act;
+    gate.keep_pre = l + 1 >= keep_from;
+    ST_TRY(linear(M, h2, T, *n.w1, n.b1, nullptr, a.fpre, &gate));
+    if (!gate.fused) {
       Scope sc(M, CAT_ELEM, 0);
       if (rms) ST_TRY(ew(M, swiglu_fwd(dt, T, f, a.fpre, a.act, st)));
       else ST_TRY(ew(M, gelu_fwd(dt, T * f, a.fpre, a.act, st)));
@@ -1411,7 +1451,7 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
     if (on_schedule && !resident) ST_TRY(fetch_state(M, next, (s + 1) % NSLOT));
   }
 
-  ST_TRY(forward(M, bt));
+  ST_TRY(forward(M, bt, ulo));
   ST_TRY(backward(M, bt, ulo, uhi, plo));
 
   // ---- optimizer on the group (its update number drives AdamW's bias correction) ----
@@ -1653,6 +1693,31 @@ hift_status hift_kernel_gemm_packed(int32_t out_f32, int64_t Mm, int64_t N, int6
   g.A = A; g.lda = lda; g.C = C; g.ldc = ldc; g.bias = bias; g.R = R; g.ldr = ldc;
   if (!packed_gemm_applies(g)) return fail(HIFT_EINVAL, "problem is not one the packed-operand kernel takes");
   HIP_TRY(gemm_packed(g, Bp, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_linear_fused(int32_t epilogue, int64_t Mm, int64_t N, int64_t K, const void* A, int64_t lda,
+                                     const void* W, void* packed_scratch, void* C, void* act, const float* cos_sin,
+                                     int32_t seq, int64_t rot_cols, void* stream) {
+  if (!A || !W || !packed_scratch) return fail(HIFT_EINVAL, "null operand");
+  if (epilogue != HIFT_EPILOGUE_SWIGLU && epilogue != HIFT_EPILOGUE_ROPE) return fail(HIFT_EINVAL, "epilogue unknown");
+  if (packed_b_bytes(N, K) == 0 || N % 256 != 0) return fail(HIFT_EINVAL, "shape cannot be packed (N a multiple of 256, K of 32)");
+  Gemm g;
+  g.dtype = DT_BF16;
+  g.M = Mm; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.C = C; g.ldc = N;
+  if (epilogue == HIFT_EPILOGUE_SWIGLU) {
+    if (!act) return fail(HIFT_EINVAL, "act is null");
+    g.epi = EPI_SWIGLU; g.C2 = act; g.ldc2 = N / 2;
+  } else {
+    if (!C || !cos_sin || seq < 1 || rot_cols < 0 || rot_cols > N || rot_cols % 128 != 0)
+      return fail(HIFT_EINVAL, "rotation needs C, the table, seq >= 1 and rot_cols a multiple of 128 within N");
+    g.epi = EPI_ROPE; g.cos_sin = cos_sin; g.S = seq; g.rot_cols = rot_cols;
+  }
+  if (!packed_gemm_applies(g)) return fail(HIFT_EINVAL, "problem is not one the packed-operand kernel takes");
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(pack_b(W, K, N, K, true, packed_scratch, st, epilogue == HIFT_EPILOGUE_SWIGLU ? PK_ORDER_HALVES : PK_ORDER_PAIR64));
+  HIP_TRY(gemm_packed(g, packed_scratch, st));
   return HIFT_OK;
 }
 

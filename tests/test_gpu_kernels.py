@@ -334,3 +334,70 @@ def test_fused_attention_backward_query_half(B, H, S, hd, causal):
             bad = err > 2 ** -7 * np.abs(ref) + 2e-2 * rms + slack + 1e-6
             assert not bad.any(), (name, b, h, int(bad.sum()), float(err.max()), float(rms))
             assert np.sqrt(np.mean(err ** 2)) <= 5e-3 * rms + np.sqrt(np.mean(slack ** 2)) + 1e-6, (name, b, h)
+
+
+@pytest.mark.parametrize("M,f,K,keep", [(2048, 1664, 256, 1), (1992, 1792, 96, 1), (2048, 11008, 128, 0)])
+def test_linear_with_gated_activation_in_the_epilogue(M, f, K, keep):
+    """x . [Wg | Wu]^T with silu(gate) * up formed in the contraction's epilogue, against the oracle's
+    swiglu on the float64 product.  The activation is computed from the bf16-rounded pre-activations
+    (what the backward pass reads), so it is compared with the oracle's function of those."""
+    import torch
+    import paper_2401_15207_amd as H_
+    from oracle import hift_oracle as O
+    rng = np.random.default_rng(M + f + K)
+    x = _bf16_round(rng.standard_normal((M, K)))
+    w = _bf16_round(rng.standard_normal((2 * f, K)) * (1.5 / np.sqrt(K)))
+    pre_ref = x.astype(np.float64) @ w.astype(np.float64).T
+    dx, dw = _dev(x, True), _dev(w, True)
+    scratch = torch.empty(H_.kernel_packed_bytes(2 * f, K) // 2, dtype=torch.bfloat16, device="cuda")
+    pre = torch.full((M, 2 * f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    act = torch.full((M, f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    H_.kernel_linear_fused(H_.EPILOGUE_SWIGLU, M, 2 * f, K, dx, K, dw, scratch, pre if keep else None, act, None, 0, 0)
+    torch.cuda.synchronize()
+    a = act.float().cpu().numpy().astype(np.float64)
+    if keep:
+        p = pre.float().cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(p - pre_ref) <= 2 ** -8 * np.abs(pre_ref) + 1e-5)
+    else:
+        assert torch.isnan(pre.float()).all()
+        p = _bf16_round(pre_ref).astype(np.float64)      # within one rounding of what the kernel held
+    a_ref = O.swiglu_fwd(p[:, :f], p[:, f:])
+    if keep:
+        assert np.all(np.abs(a - a_ref) <= 2 ** -8 * np.abs(a_ref) + 1e-6)
+    else:
+        # the kernel's pre-activations may sit one bf16 step from the rounded float64 product
+        g, u = p[:, :f], p[:, f:]
+        slack = 2 ** -7 * (np.abs(a_ref) + np.abs(u) * (np.abs(g) + 1.0))
+        assert np.all(np.abs(a - a_ref) <= slack + 1e-6)
+
+
+@pytest.mark.parametrize("M,S,heads,K,rot_heads", [(2048, 512, 10, 256, 20), (1000, 200, 18, 96, 24), (2048, 128, 10, 64, 0)])
+def test_linear_with_rotary_embedding_in_the_epilogue(M, S, heads, K, rot_heads):
+    """x . Wqkv^T with the rotation of the q and k heads applied to the fp32 accumulators, against the
+    oracle's rope on the float64 product (one rounding: 2^-8 relative on the pair's magnitude)."""
+    import torch
+    import paper_2401_15207_amd as H_
+    from oracle import hift_oracle as O
+    hd, d = 128, heads * 128
+    N = 3 * d
+    rng = np.random.default_rng(M + S + heads + K)
+    x = _bf16_round(rng.standard_normal((M, K)))
+    w = _bf16_round(rng.standard_normal((N, K)) / np.sqrt(K))
+    y_ref = x.astype(np.float64) @ w.astype(np.float64).T
+    cos, sin = O.rope_angles(S, hd, 10000.0, np.float64)
+    pos = np.arange(M) % S
+    rot_cols = rot_heads * hd
+    blk = y_ref[:, :rot_cols].reshape(M, rot_heads, hd).transpose(1, 0, 2)           # [heads, M, hd]
+    if rot_heads:
+        y_ref[:, :rot_cols] = O.rope_fwd(blk, cos[pos], sin[pos]).transpose(1, 0, 2).reshape(M, rot_cols)
+    mag = np.abs(y_ref).copy()
+    if rot_heads:
+        pair = np.abs(blk) + np.abs(np.roll(blk, hd // 2, axis=-1))
+        mag[:, :rot_cols] = pair.transpose(1, 0, 2).reshape(M, rot_cols)
+    tab = torch.from_numpy(np.stack([cos, sin], -1).astype(np.float32)).cuda().contiguous()
+    scratch = torch.empty(H_.kernel_packed_bytes(N, K) // 2, dtype=torch.bfloat16, device="cuda")
+    y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    H_.kernel_linear_fused(H_.EPILOGUE_ROPE, M, N, K, _dev(x, True), K, _dev(w, True), scratch, y, None, tab, S, rot_cols)
+    torch.cuda.synchronize()
+    got = y.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - y_ref) <= 2 ** -8 * np.abs(y_ref) + 1e-5 * mag + 1e-6)
