@@ -550,11 +550,13 @@ __device__ __forceinline__ float silu_fast(float x) {
 
 template <int MT, int EPI>
 __device__ __forceinline__ void store_tile_fused(const GemmP& p, f32x16 (&acc)[MT][2], unsigned char* smem, int64_t m0, int tn,
-                                                 int wave, int lane) {
+                                                 int wave, int lane, int slot) {
+  // m0: first row of this wavefront's sub-tile; wave: its 64-column strip (0..3) of the 256-column tile;
+  // slot: which staging region of LDS it uses
   constexpr int RP = 64, PITCH = 64 * 4 + 16;
   static_assert((32 * MT) % RP == 0, "whole passes");
   const int frow = lane & 31, fhalf = lane >> 5;
-  unsigned char* reg = smem + wave * (RP * PITCH);
+  unsigned char* reg = smem + slot * (RP * PITCH);
   const int cc = lane & 7, rr = lane >> 3, half = cc >> 2, c4 = cc & 3;
   // column of this lane's own chunk in C
   const int64_t col = EPI == EPI_SWIGLU ? (int64_t)half * (p.N / 2) + 128 * (int64_t)tn + 32 * wave + 8 * c4
@@ -767,7 +769,7 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stray requests must land before LDS is reused
 
   if constexpr (EPI == EPI_NONE) store_tile<BM, WN, VEC_EPI, OutT>(p, acc, smem, m0, n0, 0, wave, wave, lane, 0, 0);
-  else store_tile_fused<MT, EPI>(p, acc, smem, m0, tn, wave, lane);
+  else store_tile_fused<MT, EPI>(p, acc, smem, m0, tn, wave, lane, wave);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -917,6 +919,22 @@ bool packed_gemm_applies(const Gemm& g) {
   return ((g.M + 32 * PK_MT - 1) / (32 * PK_MT)) * ((g.N + 255) / 256) >= 200;  // enough tiles to fill the chip
 }
 
+namespace {
+// Launch of a packed-operand kernel with its dynamic LDS size enabled once per kernel.
+template <auto Kern>
+hipError_t launch_pk(dim3 grid, int threads, int lds, hipStream_t st, const GemmP& p, const u32x4* bp) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  Kern<<<grid, threads, lds, st>>>(p, bp, p.K / 16);
+  return hipGetLastError();
+}
+
+}  // namespace
+
 hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   if (!packed_gemm_applies(g)) return hipErrorInvalidValue;
   GemmP p;
@@ -939,52 +957,18 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
     p.C2 = g.C2; p.ldc2 = g.ldc2;
     p.cos_sin = reinterpret_cast<const float2*>(g.cos_sin); p.S = g.S > 0 ? g.S : 1; p.rot_cols = g.rot_cols;
   }
+  const u32x4* bp = reinterpret_cast<const u32x4*>(Bp);
+  p.tiles_n = (int)((p.N + 255) / 256);
   constexpr int OPER = PK_STAGES * 32 * PK_MT * PK_ROW;  // ring of A stages
   constexpr int STAGE = 4 * 64 * (64 * 4 + 16);          // fp32 epilogue staging, 4 waves
   constexpr int LDS = STAGE > OPER ? STAGE : OPER;
   static_assert(LDS <= 160 * 1024, "LDS of a gfx950 compute unit");
   p.tiles_m = (int)((p.M + 32 * PK_MT - 1) / (32 * PK_MT));
-  p.tiles_n = (int)((p.N + 255) / 256);
   const dim3 grid((unsigned)(p.tiles_m * p.tiles_n));
-  const u32x4* bp = reinterpret_cast<const u32x4*>(Bp);
-  if (g.out_f32) {
-    static bool attr_done = false;
-    auto kern = gemm_pk_k<PK_MT, true, float>;
-    if (!attr_done) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-      if (e != hipSuccess) return e;
-      attr_done = true;
-    }
-    kern<<<grid, 256, LDS, st>>>(p, bp, p.K / 16);
-  } else if (g.epi == EPI_SWIGLU) {
-    static bool attr_done = false;
-    auto kern = gemm_pk_k<PK_MT, true, bf16, EPI_SWIGLU>;
-    if (!attr_done) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-      if (e != hipSuccess) return e;
-      attr_done = true;
-    }
-    kern<<<grid, 256, LDS, st>>>(p, bp, p.K / 16);
-  } else if (g.epi == EPI_ROPE) {
-    static bool attr_done = false;
-    auto kern = gemm_pk_k<PK_MT, true, bf16, EPI_ROPE>;
-    if (!attr_done) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-      if (e != hipSuccess) return e;
-      attr_done = true;
-    }
-    kern<<<grid, 256, LDS, st>>>(p, bp, p.K / 16);
-  } else {
-    static bool attr_done = false;
-    auto kern = gemm_pk_k<PK_MT, true, bf16>;
-    if (!attr_done) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-      if (e != hipSuccess) return e;
-      attr_done = true;
-    }
-    kern<<<grid, 256, LDS, st>>>(p, bp, p.K / 16);
-  }
-  return hipGetLastError();
+  if (g.out_f32) return launch_pk<gemm_pk_k<PK_MT, true, float>>(grid, 256, LDS, st, p, bp);
+  if (g.epi == EPI_SWIGLU) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_SWIGLU>>(grid, 256, LDS, st, p, bp);
+  if (g.epi == EPI_ROPE) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_ROPE>>(grid, 256, LDS, st, p, bp);
+  return launch_pk<gemm_pk_k<PK_MT, true, bf16>>(grid, 256, LDS, st, p, bp);
 }
 
 hipError_t gemm(const Gemm& g, hipStream_t st, int* variant) {

@@ -84,7 +84,9 @@ def test_gemm_batched_strided_bf16():
 
 @pytest.mark.parametrize("bk", [1, 0], ids=["w_kmajor", "w_transposed"])
 @pytest.mark.parametrize("M,N,K", [(2048, 8192, 96), (2000, 8200, 160), (1800, 7944, 64), (2048, 12288, 4096),
-                                   (2048, 4096, 352), (1990, 3592, 96)])
+                                   (2048, 4096, 352), (1990, 3592, 96),
+                                   # more column tiles than compute units twice over; a short and ragged M with many columns
+                                   (2048, 8192, 192), (1000, 16128, 128), (2048, 22016, 256)])
 def test_gemm_with_packed_weight_operand(M, N, K, bk):
     import torch
     import paper_2401_15207_amd as H
@@ -371,7 +373,7 @@ def test_linear_with_gated_activation_in_the_epilogue(M, f, K, keep):
         assert np.all(np.abs(a - a_ref) <= slack + 1e-6)
 
 
-@pytest.mark.parametrize("M,S,heads,K,rot_heads", [(2048, 512, 10, 256, 20), (1000, 200, 18, 96, 24), (2048, 128, 10, 64, 0)])
+@pytest.mark.parametrize("M,S,heads,K,rot_heads", [(2048, 512, 10, 256, 20), (1000, 200, 18, 96, 24), (2048, 128, 10, 64, 0), (1024, 256, 42, 64, 84)])
 def test_linear_with_rotary_embedding_in_the_epilogue(M, S, heads, K, rot_heads):
     """x . Wqkv^T with the rotation of the q and k heads applied to the fp32 accumulators, against the
     oracle's rope on the float64 product (one rounding: 2^-8 relative on the pair's magnitude)."""
