@@ -318,18 +318,23 @@ hift_status hift_kernel_gemm_packed(int32_t out_f32, int64_t M, int64_t N, int64
                                     const void* bias, const void* R, void* stream);
 
 /* A linear layer of the RMSNorm / rotary / gated-FFN decoder with the elementwise step that follows it
- * done in the contraction's epilogue (forward of Algorithm 1 step h; bf16).  A: device [M, K] (row
- * stride lda); W: device [N, K] bf16, contiguous; packed_scratch: device, hift_kernel_packed_bytes(N, K)
- * bytes, receives W in fragment order with its 32-row blocks arranged for the epilogue.
+ * done in the contraction's epilogue (forward and backward of Algorithm 1 step h; bf16).  A: device
+ * [M, K] (row stride lda); W: device [N, K] bf16, contiguous; packed_scratch: device,
+ * hift_kernel_packed_bytes(N, K) bytes, receives W in fragment order with its 32-row blocks arranged
+ * for the epilogue.
  *   HIFT_EPILOGUE_SWIGLU: W = gate | up (N = 2 f).  C: device [M, N] or NULL, the rounded
- *     pre-activations; act: device [M, f] = silu(gate) * up from the rounded pre-activations.
+ *     pre-activations; aux: device [M, f], receives silu(gate) * up from the rounded pre-activations.
  *   HIFT_EPILOGUE_ROPE: W = q | k | v with heads of width 128.  C: device [M, N]; columns below
  *     rot_cols are rotated pairwise (i, i + 64 inside a head) by the angle of position row % seq;
- *     cos_sin: device fp32 [>= seq, 64, 2] (cos, sin).  act is ignored.
- * N a multiple of 256; HIFT_EINVAL for problems the packed-operand kernel does not take. */
-enum { HIFT_EPILOGUE_SWIGLU = 1, HIFT_EPILOGUE_ROPE = 2 };
+ *     cos_sin: device fp32 [>= seq, 64, 2] (cos, sin).  aux is ignored.
+ *   HIFT_EPILOGUE_SWIGLU_BWD: A . W^T is the gradient of the gated activation, [M, N], and is not
+ *     stored; aux: device [M, 2 N], the forward's pre-activations gate | up (read only); C: device
+ *     [M, 2 N], receives d gate | d up.
+ * N a multiple of 256 (of 8 for the backward epilogue); HIFT_EINVAL for problems the packed-operand
+ * kernel does not take. */
+enum { HIFT_EPILOGUE_SWIGLU = 1, HIFT_EPILOGUE_ROPE = 2, HIFT_EPILOGUE_SWIGLU_BWD = 3 };
 hift_status hift_kernel_linear_fused(int32_t epilogue, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
-                                     const void* W, void* packed_scratch, void* C, void* act,
+                                     const void* W, void* packed_scratch, void* C, void* aux,
                                      const float* cos_sin, int32_t seq, int64_t rot_cols, void* stream);
 
 /* Group-local optimizer update on `count` contiguous parameters (the update inside Algorithm 1's

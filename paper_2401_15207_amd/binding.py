@@ -217,13 +217,13 @@ def kernel_norm_fwd(dtype, rms, rows, d, eps, x, g, b, y, stats, stream=None):
     _check(lib.hift_kernel_norm_fwd(dtype, int(rms), rows, d, eps, _ptr(x), _ptr(g), _ptr(b), _ptr(y), _ptr(stats), st))
 
 
-EPILOGUE_SWIGLU, EPILOGUE_ROPE = 1, 2
+EPILOGUE_SWIGLU, EPILOGUE_ROPE, EPILOGUE_SWIGLU_BWD = 1, 2, 3
 
 
-def kernel_linear_fused(epilogue, M, N, K, A, lda, W, packed_scratch, C, act, cos_sin, seq, rot_cols, stream=None):
+def kernel_linear_fused(epilogue, M, N, K, A, lda, W, packed_scratch, C, aux, cos_sin, seq, rot_cols, stream=None):
     import torch
     st = (stream or torch.cuda.current_stream()).cuda_stream
-    _check(lib.hift_kernel_linear_fused(epilogue, M, N, K, _ptr(A), lda, _ptr(W), _ptr(packed_scratch), _ptr(C), _ptr(act),
+    _check(lib.hift_kernel_linear_fused(epilogue, M, N, K, _ptr(A), lda, _ptr(W), _ptr(packed_scratch), _ptr(C), _ptr(aux),
                                         _ptr(cos_sin), seq, rot_cols, st))
 
 

@@ -282,6 +282,62 @@ __global__ void __launch_bounds__(BLK) norm_bwd_dx_k(int64_t rows, int d, const 
   }
 }
 
+// Same, with the row held in registers (d <= 64 * V * NCH): x, dy and the gain are read once, and every
+// load of the row is in flight at once.  One row per 64-thread workgroup.
+template <typename T, int V, int NCH, bool RMS>
+__global__ void __launch_bounds__(64) norm_bwd_dx_reg_k(int64_t rows, int d, const T* __restrict__ dy, const T* __restrict__ x,
+                                                         const T* __restrict__ g, const float* __restrict__ stats,
+                                                         const T* __restrict__ dres, T* __restrict__ dx) {
+  const int64_t row = blockIdx.x;
+  const int lane = threadIdx.x;
+  const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+  float xh[NCH][V], dh[NCH][V];  // normalised input; dy * gain
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int j = (c * 64 + lane) * V;
+    if (j < d) {
+      float gg[V];
+      ldv<T, V>(x + row * d + j, xh[c]);
+      ldv<T, V>(dy + row * d + j, dh[c]);
+      ldv<T, V>(g + j, gg);
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        xh[c][e] = (xh[c][e] - mean) * rstd;
+        dh[c][e] *= gg[e];
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < V; ++e) xh[c][e] = dh[c][e] = 0.f;
+    }
+  }
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c)
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      s1 += dh[c][e];
+      s2 += dh[c][e] * xh[c][e];
+    }
+  s1 = RMS ? 0.f : wave_sum(s1) / d;
+  s2 = wave_sum(s2) / d;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int j = (c * 64 + lane) * V;
+    if (j < d) {
+      float o[V];
+#pragma unroll
+      for (int e = 0; e < V; ++e) o[e] = rstd * (dh[c][e] - s1 - xh[c][e] * s2);
+      if (dres) {
+        float r[V];
+        ldv<T, V>(dres + row * d + j, r);
+#pragma unroll
+        for (int e = 0; e < V; ++e) o[e] += r[e];
+      }
+      stv<T, V>(dx + row * d + j, o);
+    }
+  }
+}
+
 // Column sums in two deterministic stages.  Stage 1: block (256 columns) x chunk (64 rows).
 // MODE 0: sum y.  MODE 1: sum dy * xhat and sum dy (norm gain / shift gradients).
 template <typename T, int MODE>
@@ -876,6 +932,11 @@ hipError_t norm_bwd_dx(int dt, bool rms, int64_t rows, int d, const void* dy, co
   if (rows == 0) return hipSuccess;
   const dim3 grid((unsigned)cdiv(rows, BLK / 64));
 #define OK(v) (d % (v) == 0 && aligned16(x) && aligned16(dy) && aligned16(g) && aligned16(dres) && aligned16(dx))
+  if (dt == DT_BF16 && OK(8) && d <= 64 * 8 * 8 && rows <= 0x7FFFFFFF) {
+    if (rms) norm_bwd_dx_reg_k<bf16, 8, 8, true><<<dim3((unsigned)rows), 64, 0, st>>>(rows, d, (const bf16*)dy, (const bf16*)x, (const bf16*)g, stats, (const bf16*)dres, (bf16*)dx);
+    else norm_bwd_dx_reg_k<bf16, 8, 8, false><<<dim3((unsigned)rows), 64, 0, st>>>(rows, d, (const bf16*)dy, (const bf16*)x, (const bf16*)g, stats, (const bf16*)dres, (bf16*)dx);
+    LAUNCH_CHECK();
+  }
   if (rms)
     DISPATCH_TV(dt, OK, (norm_bwd_dx_k<T, V, true><<<grid, BLK, 0, st>>>(rows, d, (const T*)dy, (const T*)x,
                                                                              (const T*)g, stats, (const T*)dres, (T*)dx)));

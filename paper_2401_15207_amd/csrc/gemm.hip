@@ -633,6 +633,57 @@ __device__ __forceinline__ void store_tile_fused(const GemmP& p, f32x16 (&acc)[M
   }
 }
 
+// Epilogue of dX through the down projection of the gated feed-forward block: the accumulators are d act;
+// with the forward's pre-activations g | u (C2, [M, 2 N]) it writes d g = d act u s (1 + g (1 - s)) and
+// d u = d act g s, s = 1 / (1 + e^-g), to C [M, 2 N].  Plain block order; staging and row walk as in store_tile.
+template <int MT>
+__device__ __forceinline__ void store_tile_gate_bwd(const GemmP& p, f32x16 (&acc)[MT][2], unsigned char* smem, int64_t m0, int64_t n0,
+                                                    int wave, int lane) {
+  constexpr int RP = 64, PITCH = 64 * 4 + 16;
+  const int frow = lane & 31, fhalf = lane >> 5;
+  unsigned char* reg = smem + wave * (RP * PITCH);
+  const int cc = lane & 7, rr = lane >> 3;
+  const int64_t col = n0 + wave * 64 + cc * 8;
+  bf16* C = reinterpret_cast<bf16*>(p.C);
+  const bf16* GU = reinterpret_cast<const bf16*>(p.C2);
+#pragma unroll
+  for (int pass = 0; pass < 32 * MT / RP; ++pass) {
+    __syncthreads();
+#pragma unroll
+    for (int ii = 0; ii < RP / 32; ++ii)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int i = pass * (RP / 32) + ii;
+          const f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          *reinterpret_cast<f32x4*>(reg + (ii * 32 + frow) * PITCH + (j * 32 + 8 * g + 4 * fhalf) * 4) = v;
+        }
+    __syncthreads();
+#pragma unroll 2
+    for (int it = 0; it < RP / 8; ++it) {
+      const int lr = it * 8 + rr;
+      const int64_t row = m0 + pass * RP + lr;
+      if (row >= p.M || col >= p.N) continue;
+      float da[8];
+      *reinterpret_cast<f32x4*>(da) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + cc * 32);
+      *reinterpret_cast<f32x4*>(da + 4) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + cc * 32 + 16);
+      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(GU + row * p.ldc2 + col);
+      const bf16x8 uv = *reinterpret_cast<const bf16x8*>(GU + row * p.ldc2 + p.N + col);
+      bf16x8 dg, du;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float g = static_cast<float>(gv[e]), u = static_cast<float>(uv[e]);
+        const float s = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+        dg[e] = static_cast<__bf16>(da[e] * u * s * (1.0f + g * (1.0f - s)));
+        du[e] = static_cast<__bf16>(da[e] * g * s);
+      }
+      *reinterpret_cast<bf16x8*>(C + row * p.ldc + col) = dg;
+      *reinterpret_cast<bf16x8*>(C + row * p.ldc + p.N + col) = du;
+    }
+  }
+}
+
 template <int MT, bool VEC_EPI, typename OutT, int EPI = EPI_NONE>
 __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restrict__ Bp, int64_t k_steps) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -769,6 +820,7 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stray requests must land before LDS is reused
 
   if constexpr (EPI == EPI_NONE) store_tile<BM, WN, VEC_EPI, OutT>(p, acc, smem, m0, n0, 0, wave, wave, lane, 0, 0);
+  else if constexpr (EPI == EPI_SWIGLU_BWD) store_tile_gate_bwd<MT>(p, acc, smem, m0, n0, wave, lane);
   else store_tile_fused<MT, EPI>(p, acc, smem, m0, tn, wave, lane, wave);
 }
 
@@ -951,6 +1003,9 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
       if (g.N % 256 != 0 || !g.C || !g.cos_sin || g.S < 1 || g.rot_cols % 128 != 0 || g.rot_cols > g.N ||
           (reinterpret_cast<uintptr_t>(g.cos_sin) & 7) != 0)
         return hipErrorInvalidValue;
+    } else if (g.epi == EPI_SWIGLU_BWD) {
+      if (g.N % 8 != 0 || !g.C || !g.C2 || !al16(g.C2) || g.ldc2 % 8 != 0 || g.ldc2 < 2 * g.N || g.ldc < 2 * g.N)
+        return hipErrorInvalidValue;
     } else {
       return hipErrorInvalidValue;
     }
@@ -968,6 +1023,7 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   if (g.out_f32) return launch_pk<gemm_pk_k<PK_MT, true, float>>(grid, 256, LDS, st, p, bp);
   if (g.epi == EPI_SWIGLU) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_SWIGLU>>(grid, 256, LDS, st, p, bp);
   if (g.epi == EPI_ROPE) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_ROPE>>(grid, 256, LDS, st, p, bp);
+  if (g.epi == EPI_SWIGLU_BWD) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_SWIGLU_BWD>>(grid, 256, LDS, st, p, bp);
   return launch_pk<gemm_pk_k<PK_MT, true, bf16>>(grid, 256, LDS, st, p, bp);
 }
 

@@ -37,11 +37,13 @@ struct Gemm {
   //   EPI_ROPE    B = q | k | v of heads of width 128.  Columns below rot_cols are rotated pairwise
   //               (i, i + 64 within a head) by the angle of position (row % S) before the one rounding;
   //               cos_sin: [>= S, 64] pairs (cos, sin), fp32.
+  //   EPI_SWIGLU_BWD  (plain block order) the product is d act [M, N]; C2 holds the forward's pre-activations
+  //               gate | up [M, 2 N] (ldc2, read only); C [M, 2 N] (ldc) receives d gate | d up.  d act is not stored.
   int epi = 0;
   void* C2 = nullptr; int64_t ldc2 = 0;
   const void* cos_sin = nullptr; int S = 0; int64_t rot_cols = 0;
 };
-enum { EPI_NONE = 0, EPI_SWIGLU = 1, EPI_ROPE = 2 };
+enum { EPI_NONE = 0, EPI_SWIGLU = 1, EPI_ROPE = 2, EPI_SWIGLU_BWD = 3 };
 enum { BAND_NONE = 0, BAND_SKIP_UPPER = 1, BAND_K_UPTO_ROW = 2, BAND_K_FROM_ROW = 3 };
 // variant (optional) receives which kernel ran: 0 plain FMA, 1 MFMA 128x128 tiles, 2 MFMA 256x256 tiles
 hipError_t gemm(const Gemm& g, hipStream_t st, int* variant = nullptr);

@@ -540,7 +540,11 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
   return HIFT_OK;
 }
 
-hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor& w, const void* R, void* dx) {
+// gate_pre / dgu: if given and the packed kernel takes the problem, dx (the gradient of the gated activation,
+// [rows, in]) is not stored; the epilogue turns it into the gradient of gate | up ([rows, 2 in]) with the forward's
+// pre-activations and *fused is set.  Otherwise dx is written and the caller runs the separate kernel.
+hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor& w, const void* R, void* dx,
+                      const void* gate_pre = nullptr, void* dgu = nullptr, bool* fused = nullptr) {
   // dx[rows, in] = dy[rows, out] . w[out, in] (+ R)
   Gemm g;
   g.dtype = M->dt;
@@ -551,6 +555,14 @@ hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor&
   g.R = R; g.ldr = w.cols;
   Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
   if (w.pk_bwd >= 0 && packed_gemm_applies(g)) {
+    static const bool epi_on = [] { const char* e = getenv("HIFT_EPI_FUSED"); return !(e && e[0] == '0'); }();
+    if (epi_on && gate_pre && dgu && fused && !R && w.cols % 8 == 0 && (reinterpret_cast<uintptr_t>(dgu) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(gate_pre) & 15) == 0) {
+      g.epi = EPI_SWIGLU_BWD;
+      g.C2 = const_cast<void*>(gate_pre); g.ldc2 = 2 * w.cols;
+      g.C = dgu; g.ldc = 2 * w.cols;
+      *fused = true;
+    }
     K_TRY(gemm_packed(g, M->wpk + w.pk_bwd, M->cs));
     return HIFT_OK;
   }
@@ -862,8 +874,10 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
         ST_TRY(linear_dw(M, Dc, a.act, T, *n.w2, glo));
         if (n.b2) ST_TRY(bias_grad(M, Dc, T, *n.b2, glo));
       }
-      ST_TRY(linear_dx(M, Dc, T, *n.w2, nullptr, M->dact));
-      {
+      bool gate_done = false;
+      if (rms) ST_TRY(linear_dx(M, Dc, T, *n.w2, nullptr, M->dact, a.fpre, M->dffn, &gate_done));
+      else ST_TRY(linear_dx(M, Dc, T, *n.w2, nullptr, M->dact));
+      if (!gate_done) {
         Scope sc(M, CAT_ELEM, 0);
         if (rms) ST_TRY(ew(M, swiglu_bwd(dt, T, f, M->dact, a.fpre, M->dffn, st)));
         else ST_TRY(ew(M, gelu_bwd(dt, T * f, M->dact, a.fpre, M->dffn, st)));
@@ -1697,26 +1711,35 @@ hift_status hift_kernel_gemm_packed(int32_t out_f32, int64_t Mm, int64_t N, int6
 }
 
 hift_status hift_kernel_linear_fused(int32_t epilogue, int64_t Mm, int64_t N, int64_t K, const void* A, int64_t lda,
-                                     const void* W, void* packed_scratch, void* C, void* act, const float* cos_sin,
+                                     const void* W, void* packed_scratch, void* C, void* aux, const float* cos_sin,
                                      int32_t seq, int64_t rot_cols, void* stream) {
   if (!A || !W || !packed_scratch) return fail(HIFT_EINVAL, "null operand");
-  if (epilogue != HIFT_EPILOGUE_SWIGLU && epilogue != HIFT_EPILOGUE_ROPE) return fail(HIFT_EINVAL, "epilogue unknown");
-  if (packed_b_bytes(N, K) == 0 || N % 256 != 0) return fail(HIFT_EINVAL, "shape cannot be packed (N a multiple of 256, K of 32)");
+  if (epilogue != HIFT_EPILOGUE_SWIGLU && epilogue != HIFT_EPILOGUE_ROPE && epilogue != HIFT_EPILOGUE_SWIGLU_BWD)
+    return fail(HIFT_EINVAL, "epilogue unknown");
+  const bool bwd = epilogue == HIFT_EPILOGUE_SWIGLU_BWD;
+  if (packed_b_bytes(N, K) == 0 || (!bwd && N % 256 != 0) || (bwd && N % 8 != 0))
+    return fail(HIFT_EINVAL, "shape cannot be packed (N a multiple of 256, or of 8 for the backward epilogue; K of 32)");
   Gemm g;
   g.dtype = DT_BF16;
   g.M = Mm; g.N = N; g.K = K;
-  g.A = A; g.lda = lda; g.C = C; g.ldc = N;
+  g.A = A; g.lda = lda; g.C = C; g.ldc = bwd ? 2 * N : N;
+  int order = PK_ORDER_PLAIN;
   if (epilogue == HIFT_EPILOGUE_SWIGLU) {
-    if (!act) return fail(HIFT_EINVAL, "act is null");
-    g.epi = EPI_SWIGLU; g.C2 = act; g.ldc2 = N / 2;
+    if (!aux) return fail(HIFT_EINVAL, "act is null");
+    g.epi = EPI_SWIGLU; g.C2 = aux; g.ldc2 = N / 2;
+    order = PK_ORDER_HALVES;
+  } else if (bwd) {
+    if (!aux || !C) return fail(HIFT_EINVAL, "the backward epilogue needs the pre-activations and C");
+    g.epi = EPI_SWIGLU_BWD; g.C2 = aux; g.ldc2 = 2 * N;
   } else {
     if (!C || !cos_sin || seq < 1 || rot_cols < 0 || rot_cols > N || rot_cols % 128 != 0)
       return fail(HIFT_EINVAL, "rotation needs C, the table, seq >= 1 and rot_cols a multiple of 128 within N");
     g.epi = EPI_ROPE; g.cos_sin = cos_sin; g.S = seq; g.rot_cols = rot_cols;
+    order = PK_ORDER_PAIR64;
   }
   if (!packed_gemm_applies(g)) return fail(HIFT_EINVAL, "problem is not one the packed-operand kernel takes");
   hipStream_t st = (hipStream_t)stream;
-  HIP_TRY(pack_b(W, K, N, K, true, packed_scratch, st, epilogue == HIFT_EPILOGUE_SWIGLU ? PK_ORDER_HALVES : PK_ORDER_PAIR64));
+  HIP_TRY(pack_b(W, K, N, K, true, packed_scratch, st, order));
   HIP_TRY(gemm_packed(g, packed_scratch, st));
   return HIFT_OK;
 }

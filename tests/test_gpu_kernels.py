@@ -403,3 +403,27 @@ def test_linear_with_rotary_embedding_in_the_epilogue(M, S, heads, K, rot_heads)
     torch.cuda.synchronize()
     got = y.float().cpu().numpy().astype(np.float64)
     assert np.all(np.abs(got - y_ref) <= 2 ** -8 * np.abs(y_ref) + 1e-5 * mag + 1e-6)
+
+
+@pytest.mark.parametrize("M,f,K", [(2048, 3328, 64), (1992, 3592, 96)])
+def test_linear_dx_with_gated_activation_backward_in_the_epilogue(M, f, K):
+    """dY . Wd (the gradient of the gated activation, never stored) turned into d gate | d up in the
+    contraction's epilogue, against the oracle's swiglu_bwd on the float64 product."""
+    import torch
+    import paper_2401_15207_amd as H_
+    from oracle import hift_oracle as O
+    rng = np.random.default_rng(M + f + K + 1)
+    dy = _bf16_round(rng.standard_normal((M, K)))
+    wt = _bf16_round(rng.standard_normal((f, K)) / np.sqrt(K))           # rows = columns of the down projection
+    pre = _bf16_round(rng.standard_normal((M, 2 * f)) * 1.5)
+    dact = dy.astype(np.float64) @ wt.astype(np.float64).T
+    dg_ref, du_ref = O.swiglu_bwd(dact, pre[:, :f].astype(np.float64), pre[:, f:].astype(np.float64))
+    scratch = torch.empty(H_.kernel_packed_bytes(f, K) // 2, dtype=torch.bfloat16, device="cuda")
+    out = torch.full((M, 2 * f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    H_.kernel_linear_fused(H_.EPILOGUE_SWIGLU_BWD, M, f, K, _dev(dy, True), K, _dev(wt, True), scratch, out, _dev(pre, True), None, 0, 0)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    ref = np.concatenate([dg_ref, du_ref], 1)
+    # one bf16 rounding of the result; the fp32 accumulation of d act enters through its factor
+    fac = np.abs(ref) / np.maximum(np.abs(np.concatenate([dact, dact], 1)), 1e-30)
+    assert np.all(np.abs(got - ref) <= 2 ** -8 * np.abs(ref) + 1e-5 * fac * np.sqrt(K) + 1e-7)
