@@ -1,0 +1,89 @@
+"""The 7B-shaped workload at its full depth, in the configuration the benchmark times (32 layers,
+batch 4 x 512, one unit per group, AdamW state of inactive groups in pinned host memory).  The float64
+oracle cannot run this size, so the checks are properties that hold at any size, a closed form for the
+first loss, and sampled elements of the update that the oracle's optimizer formula reproduces one by one
+from the state the library stores."""
+import math
+
+import numpy as np
+import pytest
+
+from hift_inputs import WORKLOADS, make_batch, model_config
+from oracle import hift_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.timeout(600)
+def test_c4_full_depth_step_properties():
+    import torch
+    import paper_2401_15207_amd as H
+    from bench import fill_weights
+    wl = WORKLOADS["C4"]
+    cfg = model_config(wl)
+    opt = wl["opt"]
+    B, S, L = wl["batch"], wl["seq"], cfg["n_layers"]
+    model = H.HiftModel(cfg, opt, wl["m"], B, S, init_params=None, state_on_host=1)
+    try:
+        fill_weights(model, cfg, 0)
+        k = model.set_group_schedule(wl["strategy"], wl["m"], 0)
+        assert k == L + 2
+        dev = lambda t: [torch.from_numpy(x).cuda() for x in make_batch(wl, 0, t)]
+
+        # --- step on a middle layer: unit 17 ---
+        u = 17
+        watch = [0, u - 1, u + 1, L + 1]                       # embeddings, both neighbours, head
+        before = {w: (model.read_params(w, w + 1, 0), model.read_params(w, w + 1, 1)) for w in watch}
+        state_before = model.read_state(u + 1, u + 2, 0)
+        th0 = model.read_params(u, u + 1, 0)
+        loss = model.step(*dev(1), u, want_loss=True)
+
+        # First loss, closed form: the final RMSNorm (gain 1) gives rows of squared length d, the head rows are
+        # N(0, 0.02^2), so the logits of a position are V independent N(0, s2 = 0.02^2 d) values:
+        # E[log sum exp] = ln V + s2 / 2 up to O(e^{s2} / V), and the label's logit has mean 0.
+        s2 = 0.02 ** 2 * cfg["d_model"]
+        # the mean over 2044 positions of the label logit has standard deviation sqrt(s2 / 2044) = 0.028
+        assert abs(loss - (math.log(cfg["vocab"]) + s2 / 2)) < 0.12, loss
+
+        # Frozen units: master, forward copy and host-resident state are bit-identical (equations 2-3).
+        for w in watch:
+            assert np.array_equal(model.read_params(w, w + 1, 0), before[w][0]), w
+            assert np.array_equal(model.read_params(w, w + 1, 1), before[w][1]), w
+        assert np.array_equal(model.read_state(u + 1, u + 2, 0), state_before)
+
+        # The active unit: AdamW's first update from zero state moves every parameter by
+        # lr |g| / (|g| + eps) <= lr, and the stored moments are (1 - b1) g and (1 - b2) g^2.
+        th1 = model.read_params(u, u + 1, 0)
+        m1 = model.read_state(u, u + 1, 0).astype(np.float64)
+        v1 = model.read_state(u, u + 1, 1).astype(np.float64)
+        lr, b1, b2, eps = opt["lr"], opt["beta1"], opt["beta2"], opt["eps"]
+        step = np.abs(th1.astype(np.float64) - th0.astype(np.float64))
+        ulp = np.spacing(np.abs(th0).astype(np.float32)).astype(np.float64)
+        assert np.all(step <= lr * (1 + 1e-5) + ulp)
+        g = m1 / (1 - b1)
+        assert np.median(np.abs(g)) > 100 * eps                 # gradients reached this layer
+        big = np.abs(g) > 1e-5
+        assert big.mean() > 0.01 and np.all(step[big] >= lr * (1 - 2e-3) - ulp[big])
+        assert np.all(np.abs(v1 - (1 - b2) * g * g) <= 1e-5 * (1 - b2) * g * g + 1e-30)
+        # sampled elements through the oracle's optimizer formula
+        rng = np.random.default_rng(0)
+        idx = rng.choice(th0.size, 20000, replace=False)
+        th = th0[idx].astype(np.float64)
+        s1, s2_ = np.zeros(idx.size), np.zeros(idx.size)
+        O.adamw_update(th, g[idx], s1, s2_, 1, lr, b1, b2, eps, opt["weight_decay"], np.ones(idx.size, bool))
+        assert np.all(np.abs(th1[idx] - th) <= 1e-5 * lr + ulp[idx])
+        # the forward copy of the active unit is the rounded master
+        from hift_inputs import round_to_bf16
+        assert np.array_equal(model.read_params(u, u + 1, 1), round_to_bf16(th1))
+
+        # --- step on the head: nothing below it changes; on the embeddings: everything above is frozen ---
+        for unit, frozen in ((L + 1, [0, 1, L]), (0, [1, L, L + 1])):
+            keep = {w: model.read_params(w, w + 1, 0) for w in frozen}
+            t0 = model.read_params(unit, unit + 1, 0)
+            lo = model.step(*dev(2), unit, want_loss=True)
+            assert math.isfinite(lo)
+            for w in frozen:
+                assert np.array_equal(model.read_params(w, w + 1, 0), keep[w]), (unit, w)
+            assert not np.array_equal(model.read_params(unit, unit + 1, 0), t0)
+    finally:
+        model.close()
