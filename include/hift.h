@@ -317,6 +317,18 @@ hift_status hift_kernel_gemm_packed(int32_t out_f32, int64_t M, int64_t N, int64
                                     int64_t lda, const void* Bp, void* C, int64_t ldc,
                                     const void* bias, const void* R, void* stream);
 
+/* hift_kernel_gemm_packed with a work space: when the tiles of the problem leave a last round over the
+ * 256 compute units in which at most half of them would have a tile, each of those tiles is shared by 2
+ * to 4 workgroups that take consecutive shares of K and are summed, in a fixed order, by whichever of
+ * them finishes last.  workspace: device, hift_kernel_packed_workspace_bytes() bytes, 16-byte aligned;
+ * its first 1 KB must be zero before the first call and every call leaves it zero; calls that share a
+ * work space must not overlap.  Same result as without it up to the order of the fp32 sums. */
+hift_status hift_kernel_packed_workspace_bytes(size_t* bytes);
+hift_status hift_kernel_gemm_packed_ws(int32_t out_f32, int64_t M, int64_t N, int64_t K, const void* A,
+                                       int64_t lda, const void* Bp, void* C, int64_t ldc,
+                                       const void* bias, const void* R, void* workspace,
+                                       size_t workspace_bytes, void* stream);
+
 /* A linear layer of the RMSNorm / rotary / gated-FFN decoder with the elementwise step that follows it
  * done in the contraction's epilogue (forward and backward of Algorithm 1 step h; bf16).  A: device
  * [M, K] (row stride lda); W: device [N, K] bf16, contiguous; packed_scratch: device,

@@ -95,6 +95,8 @@ _SIGS = {
     "hift_kernel_gemm_packed": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp],
     "hift_kernel_optimizer": [_P(Opt), _i64, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_norm_fwd": [_i32, _i32, _i64, _i32, C.c_float, _vp, _vp, _vp, _vp, _vp, _vp],
+    "hift_kernel_packed_workspace_bytes": [_P(_sz)],
+    "hift_kernel_gemm_packed_ws": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _sz, _vp],
     "hift_kernel_linear_fused": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _vp],
     "hift_kernel_attention_fwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
     "hift_kernel_attention_bwd_query": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
@@ -215,6 +217,19 @@ def kernel_norm_fwd(dtype, rms, rows, d, eps, x, g, b, y, stats, stream=None):
     import torch
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib.hift_kernel_norm_fwd(dtype, int(rms), rows, d, eps, _ptr(x), _ptr(g), _ptr(b), _ptr(y), _ptr(stats), st))
+
+
+def kernel_packed_workspace_bytes():
+    n = _sz()
+    _check(lib.hift_kernel_packed_workspace_bytes(C.byref(n)))
+    return n.value
+
+
+def kernel_gemm_packed_ws(out_f32, M, N, K, A, lda, Bp, Cm, ldc, bias, R, workspace, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_gemm_packed_ws(out_f32, M, N, K, _ptr(A), lda, _ptr(Bp), _ptr(Cm), ldc, _ptr(bias), _ptr(R),
+                                          _ptr(workspace), workspace.numel() * workspace.element_size(), st))
 
 
 EPILOGUE_SWIGLU, EPILOGUE_ROPE, EPILOGUE_SWIGLU_BWD = 1, 2, 3

@@ -39,6 +39,10 @@ struct GemmP {
   // fused epilogues of the packed-operand kernel
   void* C2 = nullptr; int64_t ldc2 = 0;
   const float2* cos_sin = nullptr; int S = 1; int64_t rot_cols = 0;
+  // split tail of the packed-operand kernel: workgroups from split_from on work in groups of `split` on one
+  // tile each, every member a share of the k range; ws: counters (first 1 KB) and partial tiles
+  int split_from = 0x7FFFFFFF, split = 1;
+  unsigned char* ws = nullptr;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -693,14 +697,25 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  int tile = blockIdx.x;
-  const int ntile = p.tiles_m * p.tiles_n;
-  if ((ntile & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);  // contiguous run of tiles per XCD
+  // Whole tiles first (a multiple of 256 of them when the tail is split, else all), then the tiles of the
+  // last, partial round, each shared by `split` workgroups that take consecutive shares of the k range.
+  int tile = blockIdx.x, part = 0, unit = -1;
+  const bool shared_tile = tile >= p.split_from;
+  if (shared_tile) {
+    unit = tile - p.split_from;
+    part = unit % p.split;
+    tile = p.split_from + unit / p.split;
+  } else {
+    const int ntile = p.split > 1 ? p.split_from : p.tiles_m * p.tiles_n;
+    if ((ntile & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);  // contiguous run of tiles per XCD
+  }
   const int band = tile / (8 * p.tiles_n), in_band = tile - band * 8 * p.tiles_n;
   const int band_rows = min(8, p.tiles_m - band * 8);
   const int tm = band * 8 + in_band % band_rows, tn = in_band / band_rows;
   const bf16* A = reinterpret_cast<const bf16*>(p.A);
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+  const int64_t nk = p.K / PK_DK;
+  const int64_t kt0 = shared_tile ? nk * part / p.split : 0, kt1 = shared_tile ? nk * (part + 1) / p.split : nk;
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -751,15 +766,15 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
 #pragma unroll
   for (int s = 0; s < PK_RD; ++s)
 #pragma unroll
-    for (int gi = 0; gi < NP; ++gi) request_piece(s, gi);
+    for (int gi = 0; gi < NP; ++gi) request_piece(kt0 + s, gi);
 #pragma unroll
   for (int s = 0; s < PKF; ++s)
 #pragma unroll
-    for (int j = 0; j < NT; ++j) load_b1(bq[s][j], s, j);
+    for (int j = 0; j < NT; ++j) load_b1(bq[s][j], kt0 * 4 + s, j);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < MT; ++i) read_a1(fa[0][i], smem, 0, i);
+  for (int i = 0; i < MT; ++i) read_a1(fa[0][i], smem + (kt0 & (PK_STAGES - 1)) * STG, 0, i);
 
   // One k-step: 2 MT MFMAs in the order (j, i); after the q-th one: q < MT: A fragment q of the next
   // k-step; q == MT: refill of B fragment 0; then (first two k-steps of a stage) NP / 2 pieces of the
@@ -799,13 +814,12 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
     __builtin_amdgcn_sched_barrier(0);
     kstep(std::integral_constant<int, 3>{}, std::integral_constant<int, S0 + 3>{}, std::integral_constant<int, 1>{}, kt, nxt);
   };
-  const int64_t nk = p.K / PK_DK;
-  int64_t kt = 0;
-  for (; kt + 1 < nk; kt += 2) {
+  int64_t kt = kt0;
+  for (; kt + 1 < kt1; kt += 2) {
     stage(std::integral_constant<int, 0>{}, kt);
     stage(std::integral_constant<int, 4>{}, kt + 1);
   }
-  if (kt < nk) {
+  if (kt < kt1) {
     stage(std::integral_constant<int, 0>{}, kt++);
     if (p.K % PK_DK) {  // 32 columns left: two k-steps of the next stage (its A rows are half valid)
       const unsigned char* cur = smem + (kt & (PK_STAGES - 1)) * STG;
@@ -818,6 +832,54 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
     kstep(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{}, kt, cur);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stray requests must land before LDS is reused
+
+  if (shared_tile) {
+    // Every member leaves its partial tile in its own slot (register order: 4 KB per wavefront and store)
+    // and counts itself in; the member that finds all the others counted adds the slots up in their fixed
+    // order (its own included: the sum must not depend on who came last) and goes on to the epilogue.
+    // Nobody waits for anybody.  The members of a tile run on different XCDs, whose L2s do not see each
+    // other's lines: slots are written and read with device-scope accesses (sc1: written through to memory,
+    // read past the L2), which costs nothing but these accesses -- a device-scope fence instead writes back
+    // and invalidates the whole L2 under the workgroups still computing and made the shared round slower
+    // than a whole one.
+    __shared__ int is_last;
+    unsigned* count = reinterpret_cast<unsigned*>(p.ws) + (tile - p.split_from);
+    constexpr int SLOTB = BM * BN * 4;  // bytes of a partial tile
+    constexpr int SC1 = 16;             // cache-policy bit of the buffer instructions: device scope
+    const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc(p.ws + 1024, 0, (int)(p.split * (p.tiles_m * p.tiles_n - p.split_from) * SLOTB), 0x00020000);
+    const int mine = unit * SLOTB + tid * 16;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rsW, mine, ((i * NT + j) * 4 + g) * 4096, SC1);
+        }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this lane's part of the slot has reached memory
+    __syncthreads();
+    if (tid == 0) {
+      const unsigned before = __hip_atomic_fetch_add(count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      is_last = before == (unsigned)p.split - 1;
+      if (is_last) __hip_atomic_store(count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // every member has counted
+    }
+    __syncthreads();
+    if (!is_last) return;
+    const int first = (unit - part) * SLOTB + tid * 16;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4 sum = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsW, first, ((i * NT + j) * 4 + g) * 4096, SC1));
+          for (int q = 1; q < p.split; ++q)
+            sum += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsW, first + q * SLOTB, ((i * NT + j) * 4 + g) * 4096, SC1));
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] = sum[e];
+        }
+  }
 
   if constexpr (EPI == EPI_NONE) store_tile<BM, WN, VEC_EPI, OutT>(p, acc, smem, m0, n0, 0, wave, wave, lane, 0, 0);
   else if constexpr (EPI == EPI_SWIGLU_BWD) store_tile_gate_bwd<MT>(p, acc, smem, m0, n0, wave, lane);
@@ -1019,7 +1081,23 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   constexpr int LDS = STAGE > OPER ? STAGE : OPER;
   static_assert(LDS <= 160 * 1024, "LDS of a gfx950 compute unit");
   p.tiles_m = (int)((p.M + 32 * PK_MT - 1) / (32 * PK_MT));
-  const dim3 grid((unsigned)(p.tiles_m * p.tiles_n));
+  // The last round: if at most half the compute units would have a tile, 2 to 4 workgroups share each
+  // (HIFT_GEMM_SPLIT=0 in the environment: never).
+  int blocks = p.tiles_m * p.tiles_n;
+  static const bool split_on = [] { const char* e = getenv("HIFT_GEMM_SPLIT"); return !(e && e[0] == '0'); }();
+  const int rem = blocks % 256;
+  if (split_on && g.ws && (reinterpret_cast<uintptr_t>(g.ws) & 15) == 0 && rem > 0 && rem <= 128 && g.K % PK_DK == 0) {
+    int split = 256 / rem;
+    if (split > 4) split = 4;
+    while (split > 1 && g.K / PK_DK < 8 * split) --split;  // at least 8 stages per share
+    if (split > 1) {
+      p.split = split;
+      p.split_from = blocks - rem;
+      p.ws = reinterpret_cast<unsigned char*>(g.ws);
+      blocks = p.split_from + rem * split;
+    }
+  }
+  const dim3 grid((unsigned)blocks);
   if (g.out_f32) return launch_pk<gemm_pk_k<PK_MT, true, float>>(grid, 256, LDS, st, p, bp);
   if (g.epi == EPI_SWIGLU) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_SWIGLU>>(grid, 256, LDS, st, p, bp);
   if (g.epi == EPI_ROPE) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_ROPE>>(grid, 256, LDS, st, p, bp);

@@ -42,7 +42,13 @@ struct Gemm {
   int epi = 0;
   void* C2 = nullptr; int64_t ldc2 = 0;
   const void* cos_sin = nullptr; int S = 0; int64_t rot_cols = 0;
+  // Work space of the packed-operand kernel (gemm_packed only; optional): PACKED_WS_BYTES of device memory,
+  // zero before its first use and left zero-counted by every launch.  With it, the tiles of a last, partial
+  // round over the 256 compute units are shared by 2 to 4 workgroups each, every one taking a share of the
+  // k range; launches that use the same work space must not overlap.
+  void* ws = nullptr;
 };
+constexpr size_t PACKED_WS_BYTES = 1024 + size_t(256) * 128 * 256 * 4;
 enum { EPI_NONE = 0, EPI_SWIGLU = 1, EPI_ROPE = 2, EPI_SWIGLU_BWD = 3 };
 enum { BAND_NONE = 0, BAND_SKIP_UPPER = 1, BAND_K_UPTO_ROW = 2, BAND_K_FROM_ROW = 3 };
 // variant (optional) receives which kernel ran: 0 plain FMA, 1 MFMA 128x128 tiles, 2 MFMA 256x256 tiles

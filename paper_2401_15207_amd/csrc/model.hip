@@ -240,6 +240,7 @@ struct hift_model {
   void* wc = nullptr;  // weights the forward uses: bf16 copy, or the master itself in fp32 mode
   unsigned char* wpk = nullptr;  // copies of the large bf16 matrices in MFMA fragment order
   size_t wpk_bytes = 0;
+  void* gemm_ws = nullptr;
   float* fac = nullptr;      // Adafactor statistics of every tensor (resident: they are tiny)
   float* af_work = nullptr;  // Adafactor reduction scratch
   int64_t n_fac = 0;
@@ -366,6 +367,7 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes, s
   M.dprob = b.take(B * H * S * S * es);
   M.dact = b.take(T * f * es);
   M.dffn = b.take(T * fw * es);
+  M.gemm_ws = M.wpk_bytes ? b.take(PACKED_WS_BYTES) : nullptr;  // shared tiles of the packed-operand contraction
   if (dev_bytes) *dev_bytes = b.used;
   if (pinned_bytes) *pinned_bytes = M.on_host ? (size_t)M.n_move * np * 4 : 0;
   if (by_cat)
@@ -532,6 +534,7 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
       }
       epi->fused = true;
     }
+    g.ws = M->gemm_ws;
     K_TRY(gemm_packed(g, M->wpk + w.pk_fwd, M->cs));
     return HIFT_OK;
   }
@@ -563,6 +566,7 @@ hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor&
       g.C = dgu; g.ldc = 2 * w.cols;
       *fused = true;
     }
+    g.ws = M->gemm_ws;
     K_TRY(gemm_packed(g, M->wpk + w.pk_bwd, M->cs));
     return HIFT_OK;
   }
@@ -1204,6 +1208,7 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
   for (int q = 0; q < NSLOT; ++q)
     if (M->slot[q]) CR_TRY(fill_zero(M->slot[q], (size_t)M->n_move * M->grad_cap * 4, M->cs));
   CR_TRY(fill_zero(M->grad, (size_t)M->grad_cap * 4, M->cs));
+  if (M->gemm_ws) CR_TRY(fill_zero(M->gemm_ws, 1024, M->cs));  // the counters; every launch leaves them at zero
   if (M->fac) CR_TRY(fill_zero(M->fac, (size_t)M->n_fac * 4, M->cs));
   if (M->cos_sin) {
     const int hd2 = cfg->d_model / cfg->n_heads / 2;
@@ -1705,6 +1710,29 @@ hift_status hift_kernel_gemm_packed(int32_t out_f32, int64_t Mm, int64_t N, int6
   g.out_f32 = out_f32 != 0;
   g.M = Mm; g.N = N; g.K = K;
   g.A = A; g.lda = lda; g.C = C; g.ldc = ldc; g.bias = bias; g.R = R; g.ldr = ldc;
+  if (!packed_gemm_applies(g)) return fail(HIFT_EINVAL, "problem is not one the packed-operand kernel takes");
+  HIP_TRY(gemm_packed(g, Bp, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_packed_workspace_bytes(size_t* bytes) {
+  if (!bytes) return fail(HIFT_EINVAL, "bytes is null");
+  *bytes = PACKED_WS_BYTES;
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_gemm_packed_ws(int32_t out_f32, int64_t Mm, int64_t N, int64_t K, const void* A, int64_t lda,
+                                       const void* Bp, void* C, int64_t ldc, const void* bias, const void* R,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!A || !Bp || !C || !workspace) return fail(HIFT_EINVAL, "null operand");
+  if (workspace_bytes < PACKED_WS_BYTES || (reinterpret_cast<uintptr_t>(workspace) & 15) != 0)
+    return fail(HIFT_EINVAL, "work space too small or not 16-byte aligned");
+  Gemm g;
+  g.dtype = DT_BF16;
+  g.out_f32 = out_f32 != 0;
+  g.M = Mm; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.C = C; g.ldc = ldc; g.bias = bias; g.R = R; g.ldr = ldc;
+  g.ws = workspace;
   if (!packed_gemm_applies(g)) return fail(HIFT_EINVAL, "problem is not one the packed-operand kernel takes");
   HIP_TRY(gemm_packed(g, Bp, (hipStream_t)stream));
   return HIFT_OK;

@@ -427,3 +427,37 @@ def test_linear_dx_with_gated_activation_backward_in_the_epilogue(M, f, K):
     # one bf16 rounding of the result; the fp32 accumulation of d act enters through its factor
     fac = np.abs(ref) / np.maximum(np.abs(np.concatenate([dact, dact], 1)), 1e-30)
     assert np.all(np.abs(got - ref) <= 2 ** -8 * np.abs(ref) + 1e-5 * fac * np.sqrt(K) + 1e-7)
+
+
+@pytest.mark.parametrize("M,N,K", [(2048, 5120, 2048), (2048, 5632, 1024), (1990, 4392, 1024)])
+def test_gemm_with_packed_weight_operand_and_shared_last_round(M, N, K):
+    """Tiles of the last, partial round shared by 2 to 4 workgroups along K and summed by the last one to
+    finish: against the float64 product, twice in a row on the same work space (the counters must come
+    back to zero), and bit-identical between the two calls (the sum is taken in a fixed order)."""
+    import torch
+    import paper_2401_15207_amd as H
+    rng = np.random.default_rng(M + N + K)
+    A = _bf16_round(rng.standard_normal((M, K)))
+    B = _bf16_round(rng.standard_normal((N, K)) * 0.5)
+    bias = _bf16_round(rng.standard_normal(N))
+    R = _bf16_round(rng.standard_normal((M, N)))
+    ref = A.astype(np.float64) @ B.astype(np.float64).T + bias + R
+    dBp = torch.empty(H.kernel_packed_bytes(N, K) // 2, dtype=torch.bfloat16, device="cuda")
+    H.kernel_pack_b(1, N, K, _dev(B, True), K, dBp)
+    ws = torch.zeros(H.kernel_packed_workspace_bytes() // 4, dtype=torch.float32, device="cuda")
+    ws[256:] = float("nan")                     # only the counters need to start at zero
+    dA = _dev(A, True)
+    for out_f32 in (0, 1):
+        outs = []
+        for _rep in range(2):
+            dC = torch.zeros((M, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device="cuda")
+            H.kernel_gemm_packed_ws(out_f32, M, N, K, dA, K, dBp, dC, N, _dev(bias, True), _dev(R, not out_f32), ws)
+            torch.cuda.synchronize()
+            assert int(ws[:256].view(torch.int32).abs().sum()) == 0
+            outs.append(dC.float().cpu().numpy())
+        assert np.array_equal(outs[0], outs[1])
+        got = outs[0].astype(np.float64)
+        scale = np.sqrt(K) + 1.0
+        tol = (1e-5 if out_f32 else 2 ** -8) * (np.abs(ref) + (scale if out_f32 else 0.02 * scale))
+        bad = np.abs(got - ref) > tol
+        assert not bad.any(), (out_f32, int(bad.sum()), float(np.max(np.abs(got - ref))))
