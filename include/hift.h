@@ -374,6 +374,14 @@ hift_status hift_kernel_attention_fwd(int32_t batch, int32_t heads, int32_t seq,
 hift_status hift_kernel_attention_bwd_query(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
                                             const void* qkv, const void* prob, const void* ctx, const void* dctx,
                                             void* dprob, void* dqkv, void* stream);
+/* The whole attention backward in two fused kernels: the query-major half above, then the key-major half,
+ * dv = prob^T . dctx and dk = ds^T . q, into the v and k columns of dqkv (all of dqkv is written; dprob
+ * receives ds).  cos_sin: device fp32 [>= seq, head_dim/2, 2] (cos, sin) or NULL; if given, q and k are taken
+ * to have been rotated by the rotary embedding after their projection (pairs (i, i + head_dim/2), position =
+ * row within the sequence) and dq, dk are un-rotated on the way out. */
+hift_status hift_kernel_attention_bwd(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
+                                      const void* qkv, const void* prob, const void* ctx, const void* dctx,
+                                      void* dprob, void* dqkv, const float* cos_sin, void* stream);
 /* y = norm(x) * g (+ b) over rows of width d; rms = 1: RMSNorm (b ignored).  stats: fp32 [rows,2]
  * receives mean (0 for RMSNorm) and reciprocal standard deviation. */
 hift_status hift_kernel_norm_fwd(int32_t dtype, int32_t rms, int64_t rows, int32_t d, float eps,

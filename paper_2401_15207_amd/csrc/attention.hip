@@ -46,6 +46,24 @@ __device__ __forceinline__ void dma_b128(u32x4 rsrc, uint32_t lds_addr, uint32_t
                : "memory");
 }
 
+// Adjoint of the rotary embedding on a row held as NB accumulator blocks of 32 columns (lane: columns
+// 8 g + 4 fh + e of each block): the pair (c, c + HD/2) is (block nb, block nb + NB/2), same lane and element;
+// cs: the row's position in the table, [HD/2] pairs (cos, sin).  d x1 = d y1 cos + d y2 sin, d x2 = d y2 cos - d y1 sin.
+template <int NB>
+__device__ __forceinline__ void unrotate(f32x16 (&acc)[NB], const float2* __restrict__ cs, int fh) {
+#pragma unroll
+  for (int nb = 0; nb < NB / 2; ++nb)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float2 c = cs[nb * 32 + 8 * g + 4 * fh + e];
+        const float y1 = acc[nb][4 * g + e], y2 = acc[nb + NB / 2][4 * g + e];
+        acc[nb][4 * g + e] = y1 * c.x + y2 * c.y;
+        acc[nb + NB / 2][4 * g + e] = y2 * c.x - y1 * c.y;
+      }
+}
+
 // LDS tiles are [64 keys][HD] bf16 without padding; the 16-byte piece c of row r sits at piece position
 // c ^ swz(r), which spreads both the fragment reads (sixteen rows, one piece) and the transposing
 // reads over the banks.  A tile is filled by loads that write 1 KB of consecutive LDS bytes each, so
@@ -62,7 +80,8 @@ __device__ __forceinline__ void dma_b128(u32x4 rsrc, uint32_t lds_addr, uint32_t
 template <int HD, bool CAUSAL, int NW, bool BWD>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* __restrict__ qkv, int64_t ld, int S, int H, int BH, float scale,
                                                    bf16* __restrict__ prob, bf16* __restrict__ ctx, int64_t ldc,
-                                                   const bf16* __restrict__ dctx, bf16* __restrict__ dprob, bf16* __restrict__ dqkv) {
+                                                   const bf16* __restrict__ dctx, bf16* __restrict__ dprob, bf16* __restrict__ dqkv,
+                                                   const float2* __restrict__ cos_sin) {
   const float scale_log2e = scale;
   constexpr int QB = 32 * NW;       // query rows per workgroup
   constexpr int ROWB = HD * 2;      // bytes per LDS row
@@ -443,6 +462,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
     }
     if (row_ok) {
       bf16* dq = dqkv + (int64_t)b * S * ld + (int64_t)h * HD + (int64_t)row * ld;
+      if (cos_sin) unrotate<NB>(qacc, cos_sin + (int64_t)row * (HD / 2), fh);  // q was rotated after its projection
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -453,6 +473,172 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
           *reinterpret_cast<bf16x4*>(dq + nb * 32 + 8 * g + 4 * fh) = o4;
         }
     }
+  }
+}
+
+// Key-major half of the attention backward: dV = P^T dO and dK = dS^T Q, both sums over the queries.  A workgroup
+// owns 128 keys of one (batch, head), a wavefront 32 of them from start to end; queries pass through LDS in tiles
+// of 64: Q and dO rows (HD wide) and the matching 64 x 128 pieces of P and dS, all by direct-to-LDS loads into
+// swizzled rows.  Every MFMA operand is a transpose of what lies in LDS (the contraction index is the row index of
+// all four tiles), read with ds_read_b64_tr_b16 exactly as V is in the forward kernel.  Single-buffered; two
+// workgroups share a compute unit and cover each other's loads, a long and a short one under the causal mask.
+// cos_sin, if given, un-rotates dK (k was rotated after its projection).
+template <int HD, bool CAUSAL>
+__global__ void __launch_bounds__(256, 2) attn_bwd_kv_k(const bf16* __restrict__ qkv, int64_t ld, int S, int H, int BH,
+                                                         const bf16* __restrict__ prob, const bf16* __restrict__ dprob,
+                                                         const bf16* __restrict__ dctx, int64_t ldc, bf16* __restrict__ dqkv,
+                                                         const float2* __restrict__ cos_sin) {
+  constexpr int KB = 128;           // keys per workgroup
+  constexpr int QT = 64;            // queries per tile
+  constexpr int ROWB = HD * 2, PPR = HD / 8, NB = HD / 32;
+  constexpr int TQ = QT * ROWB;     // bytes of the Q (or dO) tile
+  constexpr int TP = QT * KB * 2;   // bytes of the P (or dS) tile: rows of 256 bytes = 16 pieces
+  constexpr int IQ = QT * PPR / 64 / 4, IP = QT * 16 / 64 / 4;  // load instructions per wavefront and tile
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * TQ + 2 * TP];  // Q | dO | P | dS
+  auto swq = [](int r) { return PPR == 16 ? (r & 15) : ((r >> 1) & 7); };
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int fr = lane & 31, fh = lane >> 5;
+  // key blocks late in the sequence see few queries under the causal mask: the first half of the grid takes the
+  // early (long) blocks, the second half their late counterparts
+  const int nkb = (S + KB - 1) / KB;
+  int bh, kb;
+  if (CAUSAL) {
+    const int n_long = (nkb + 1) / 2, n_short = nkb - n_long;
+    const int L = (int)blockIdx.x, first = n_long * BH;
+    if (L < first) {
+      bh = L / n_long;
+      kb = L % n_long;
+    } else {
+      bh = (L - first) / n_short;
+      kb = nkb - 1 - (L - first) % n_short;
+    }
+  } else {
+    bh = (int)blockIdx.x / nkb;
+    kb = (int)blockIdx.x % nkb;
+  }
+  const int b = bh / H, h = bh % H;
+  const int64_t d = (int64_t)H * HD;
+  const bf16* q = qkv + (int64_t)b * S * ld + (int64_t)h * HD;
+  const bf16* dO = dctx + (int64_t)b * S * ldc + (int64_t)h * HD;
+  const bf16* P = prob + (int64_t)bh * S * S;
+  const bf16* dS = dprob + (int64_t)bh * S * S;
+  const int j0 = kb * KB + wave * 32;  // this wavefront's first key
+  const int row = j0 + fr;
+  const bool row_ok = row < S;
+
+  const uint64_t qa = reinterpret_cast<uint64_t>(q), oa = reinterpret_cast<uint64_t>(dO), pa = reinterpret_cast<uint64_t>(P),
+                 sa = reinterpret_cast<uint64_t>(dS);
+  const uint32_t recq = (uint32_t)((((int64_t)S - 1) * ld + HD) * 2), reco = (uint32_t)((((int64_t)S - 1) * ldc + HD) * 2),
+                 recp = (uint32_t)((int64_t)S * S * 2);
+  const u32x4 rsQ = {(uint32_t)qa, (uint32_t)(qa >> 32) & 0xFFFFu, recq, 0x00020000u};
+  const u32x4 rsO = {(uint32_t)oa, (uint32_t)(oa >> 32) & 0xFFFFu, reco, 0x00020000u};
+  const u32x4 rsP = {(uint32_t)pa, (uint32_t)(pa >> 32) & 0xFFFFu, recp, 0x00020000u};
+  const u32x4 rsS = {(uint32_t)sa, (uint32_t)(sa >> 32) & 0xFFFFu, recp, 0x00020000u};
+  uint32_t voq[IQ], voo[IQ], vop[IP];
+#pragma unroll
+  for (int jj = 0; jj < IQ; ++jj) {
+    const int pc = (wave * IQ + jj) * 64 + lane, r = pc / PPR, c = (pc % PPR) ^ swq(r);
+    voq[jj] = (uint32_t)((r * ld + c * 8) * 2);
+    voo[jj] = (uint32_t)((r * ldc + c * 8) * 2);
+  }
+#pragma unroll
+  for (int jj = 0; jj < IP; ++jj) {
+    const int pc = (wave * IP + jj) * 64 + lane, r = pc / 16, c = (pc % 16) ^ (r & 15);
+    // pieces that start past the end of a probability row are not fetched (offset past the buffer: zeros);
+    // a piece never straddles the end, S being a multiple of 8
+    vop[jj] = kb * KB + c * 8 < S ? (uint32_t)(((int64_t)r * S + kb * KB + c * 8) * 2) : 0x80000000u;
+  }
+  const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(lds);
+  auto request = [&](int it) __attribute__((always_inline)) {
+    const uint32_t sq = (uint32_t)((int64_t)it * QT * ld * 2), so = (uint32_t)((int64_t)it * QT * ldc * 2),
+                   sp = (uint32_t)((int64_t)it * QT * S * 2);
+#pragma unroll
+    for (int jj = 0; jj < IQ; ++jj) dma_b128(rsQ, lds0 + (wave * IQ + jj) * 1024, voq[jj], sq);
+#pragma unroll
+    for (int jj = 0; jj < IQ; ++jj) dma_b128(rsO, lds0 + TQ + (wave * IQ + jj) * 1024, voo[jj], so);
+#pragma unroll
+    for (int jj = 0; jj < IP; ++jj) dma_b128(rsP, lds0 + 2 * TQ + (wave * IP + jj) * 1024, vop[jj], sp);
+#pragma unroll
+    for (int jj = 0; jj < IP; ++jj) dma_b128(rsS, lds0 + 2 * TQ + TP + (wave * IP + jj) * 1024, vop[jj], sp);
+  };
+
+  // transposing reads (k-step t = 16 queries, rows 16 t + 8 fh + sl/4 (+4)): from the Q / dO tile the fragment of
+  // column block nb; from the P / dS tile the fragment of this wavefront's 32 keys
+  const int sl = lane & 15;
+  int xaddr[NB][2], yaddr[2];
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh) {
+    const int krow = 8 * fh + (sl >> 2) + 4 * hh;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int col = nb * 32 + 16 * ((lane >> 4) & 1) + 4 * (sl & 3);
+      xaddr[nb][hh] = krow * ROWB + (((col >> 3) ^ swq(krow)) * 16) + (col & 7) * 2;
+    }
+    const int colp = wave * 32 + 16 * ((lane >> 4) & 1) + 4 * (sl & 3);
+    yaddr[hh] = krow * (KB * 2) + (((colp >> 3) ^ (krow & 15)) * 16) + (colp & 7) * 2;
+  }
+  auto tr_frag = [&](const unsigned char* base, int a0, int a1) __attribute__((always_inline)) {
+    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(base + a0));
+    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(base + a1));
+    typedef short v8i16 __attribute__((ext_vector_type(8)));
+    const v8i16 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, both);
+  };
+
+  f32x16 vacc[NB], kacc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) vacc[nb][e] = kacc[nb][e] = 0.f;
+
+  const int all_tiles = (S + QT - 1) / QT;
+  const int it0 = CAUSAL ? kb * KB / QT : 0;  // earlier tiles hold no query at or after this block's first key
+  for (int it = it0; it < all_tiles; ++it) {
+    __syncthreads();  // the previous tile has been read by everyone
+    request(it);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (CAUSAL && it * QT + QT - 1 < j0) continue;  // every query of the tile precedes this wavefront's keys: P = dS = 0
+    const unsigned char* Qb = lds;
+    const unsigned char* Ob = lds + TQ;
+    const unsigned char* Pb = lds + 2 * TQ;
+    const unsigned char* Sb = lds + 2 * TQ + TP;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const bf16x8 yp = tr_frag(Pb + t * 16 * (KB * 2), yaddr[0], yaddr[1]);
+      const bf16x8 ys = tr_frag(Sb + t * 16 * (KB * 2), yaddr[0], yaddr[1]);
+      bf16x8 xo[NB], xq[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        xo[nb] = tr_frag(Ob + t * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
+        xq[nb] = tr_frag(Qb + t * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
+      }
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        vacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo[nb], yp, vacc[nb], 0, 0, 0);
+        kacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xq[nb], ys, kacc[nb], 0, 0, 0);
+      }
+    }
+  }
+  if (row_ok) {
+    if (cos_sin) unrotate<NB>(kacc, cos_sin + (int64_t)row * (HD / 2), fh);
+    bf16* dk = dqkv + (int64_t)b * S * ld + d + (int64_t)h * HD + (int64_t)row * ld;
+    bf16* dv = dk + d;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 k4, v4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          k4[e] = static_cast<__bf16>(kacc[nb][4 * g + e]);
+          v4[e] = static_cast<__bf16>(vacc[nb][4 * g + e]);
+        }
+        *reinterpret_cast<bf16x4*>(dk + nb * 32 + 8 * g + 4 * fh) = k4;
+        *reinterpret_cast<bf16x4*>(dv + nb * 32 + 8 * g + 4 * fh) = v4;
+      }
   }
 }
 
@@ -469,8 +655,9 @@ bool attention_fwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc,
 namespace {
 template <bool BWD_>
 hipError_t attn_launch(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, void* prob, void* ctx, int64_t ldc,
-                       const void* dctx, void* dprob, void* dqkv, hipStream_t st) {
+                       const void* dctx, void* dprob, void* dqkv, const float* cos_sin, hipStream_t st) {
   if (B == 0 || H == 0 || S == 0) return hipSuccess;
+  const float2* cs = reinterpret_cast<const float2*>(cos_sin);
   const float sc = (1.0f / sqrtf((float)hd)) * (BWD_ ? 1.0f : 1.4426950408889634f);
   // 128-row workgroups when there are enough of them to give every compute unit two; else 64-row ones
   const bool big = (int64_t)B * H * ((S + 127) / 128) >= 512;
@@ -486,8 +673,8 @@ hipError_t attn_launch(int B, int H, int S, int hd, bool causal, const void* qkv
   bf16* dq = reinterpret_cast<bf16*>(dqkv);
 #define ATTN_LAUNCH(HD_, C_)                                                                                 \
   do {                                                                                                       \
-    if (big) attn_k<HD_, C_, 4, BWD_><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sc, p, o, ldc, dO, dS, dq);  \
-    else attn_k<HD_, C_, 2, BWD_><<<grid, 128, 0, st>>>(x, ld, S, H, B * H, sc, p, o, ldc, dO, dS, dq);      \
+    if (big) attn_k<HD_, C_, 4, BWD_><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sc, p, o, ldc, dO, dS, dq, cs);  \
+    else attn_k<HD_, C_, 2, BWD_><<<grid, 128, 0, st>>>(x, ld, S, H, B * H, sc, p, o, ldc, dO, dS, dq, cs);      \
   } while (0)
   if (hd == 128) {
     if (causal) ATTN_LAUNCH(128, true); else ATTN_LAUNCH(128, false);
@@ -503,7 +690,7 @@ hipError_t attn_launch(int B, int H, int S, int hd, bool causal, const void* qkv
 
 hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, void* prob, void* ctx,
                                int64_t ldc, hipStream_t st) {
-  return attn_launch<false>(B, H, S, hd, causal, qkv, ld, prob, ctx, ldc, nullptr, nullptr, nullptr, st);
+  return attn_launch<false>(B, H, S, hd, causal, qkv, ld, prob, ctx, ldc, nullptr, nullptr, nullptr, nullptr, st);
 }
 
 bool attention_bwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* prob, const void* ctx,
@@ -513,8 +700,35 @@ bool attention_bwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc,
 }
 
 hipError_t attention_bwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* prob,
-                               const void* ctx, const void* dctx, int64_t ldc, void* dprob, void* dqkv, hipStream_t st) {
-  return attn_launch<true>(B, H, S, hd, causal, qkv, ld, const_cast<void*>(prob), const_cast<void*>(ctx), ldc, dctx, dprob, dqkv, st);
+                               const void* ctx, const void* dctx, int64_t ldc, void* dprob, void* dqkv, const float* cos_sin,
+                               hipStream_t st) {
+  return attn_launch<true>(B, H, S, hd, causal, qkv, ld, const_cast<void*>(prob), const_cast<void*>(ctx), ldc, dctx, dprob, dqkv,
+                           cos_sin, st);
+}
+
+hipError_t attention_bwd_kv_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* prob,
+                                  const void* dprob, const void* dctx, int64_t ldc, void* dqkv, const float* cos_sin,
+                                  hipStream_t st) {
+  if (B == 0 || H == 0 || S == 0) return hipSuccess;
+  const int64_t nblk = (int64_t)((S + 127) / 128) * B * H;
+  if (nblk > 0x7FFFFFFF) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)nblk);
+  const bf16* x = reinterpret_cast<const bf16*>(qkv);
+  const bf16* p = reinterpret_cast<const bf16*>(prob);
+  const bf16* ds = reinterpret_cast<const bf16*>(dprob);
+  const bf16* dO = reinterpret_cast<const bf16*>(dctx);
+  bf16* dq = reinterpret_cast<bf16*>(dqkv);
+  const float2* cs = reinterpret_cast<const float2*>(cos_sin);
+  if (hd == 128) {
+    if (causal) attn_bwd_kv_k<128, true><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, p, ds, dO, ldc, dq, cs);
+    else attn_bwd_kv_k<128, false><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, p, ds, dO, ldc, dq, cs);
+  } else if (hd == 64) {
+    if (causal) attn_bwd_kv_k<64, true><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, p, ds, dO, ldc, dq, cs);
+    else attn_bwd_kv_k<64, false><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, p, ds, dO, ldc, dq, cs);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 }  // namespace hift

@@ -106,7 +106,15 @@ hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const v
 bool attention_bwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* prob, const void* ctx,
                                  const void* dctx, const void* dprob, const void* dqkv);
 hipError_t attention_bwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* prob,
-                               const void* ctx, const void* dctx, int64_t ldc, void* dprob, void* dqkv, hipStream_t st);
+                               const void* ctx, const void* dctx, int64_t ldc, void* dprob, void* dqkv, const float* cos_sin,
+                               hipStream_t st);
+// Fused key-major half (same conditions as attention_bwd_fused_applies): dv = prob^T . dctx into the v columns of
+// dqkv and dk = dprob^T . q into its k columns (dprob = ds as written by attention_bwd_fused).
+// cos_sin (both halves): fp32 [>= S, hd/2] pairs (cos, sin) or null; if given, dq and dk are un-rotated on the
+// way out (the adjoint of the rotary embedding applied to q and k after their projection).
+hipError_t attention_bwd_kv_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* prob,
+                                  const void* dprob, const void* dctx, int64_t ldc, void* dqkv, const float* cos_sin,
+                                  hipStream_t st);
 // in place over scores [nbh, S, S]: p = softmax(scale * s + causal mask)
 hipError_t softmax_fwd(int dt, int64_t nbh, int S, float scale, bool causal, void* s, hipStream_t st);
 // in place over dp: ds = scale * p * (dp - sum_j dp p)

@@ -644,8 +644,9 @@ hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S) {
   return HIFT_OK;
 }
 
-hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, int S) {
-  // dctx [T, d] -> M->dqkv [T, 3d] (gradients with respect to the rotated q, k and to v)
+hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, int S, bool* unrotated) {
+  // dctx [T, d] -> M->dqkv [T, 3d]: gradients with respect to v and to the rotated q, k -- or, with *unrotated set
+  // (fused kernels on a rotary architecture), to q and k as projected
   const hift_config& c = M->cfg;
   const int64_t d = c.d_model, H = c.n_heads, hd = d / H;
   const size_t es = M->es;
@@ -655,6 +656,22 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
   const bool causal = c.arch != HIFT_ARCH_POSTLN_ENCODER;
   auto batch = [&](Gemm& g) { g.dtype = M->dt; g.nb = B; g.nh = (int)H; };
   const int64_t sP1 = H * (int64_t)S * S, sP2 = (int64_t)S * S, sQ1 = (int64_t)S * 3 * d, sX1 = (int64_t)S * d;
+  static const bool fused_on = [] { const char* e = getenv("HIFT_ATTN_FUSED"); return !(e && e[0] == '0'); }();
+  const bool fused = fused_on && attention_bwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, a.prob, a.ctx, dctx, M->dprob, M->dqkv);
+  *unrotated = false;
+  if (fused) {
+    // dp, the softmax backward and dq in one kernel (dp never reaches memory), then dv and dk in another; both undo
+    // the rotary embedding on the way out
+    const float* cs = c.arch == HIFT_ARCH_RMS_ROPE_DECODER ? M->cos_sin : nullptr;
+    *unrotated = cs != nullptr;
+    {
+      Scope sc(M, CAT_ATTN, 2 * fl);
+      K_TRY(attention_bwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, a.prob, a.ctx, dctx, d, M->dprob, M->dqkv, cs, M->cs));
+    }
+    Scope sc(M, CAT_ATTN, 2 * fl);
+    K_TRY(attention_bwd_kv_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, a.prob, M->dprob, dctx, d, M->dqkv, cs, M->cs));
+    return HIFT_OK;
+  }
   {
     Gemm g;  // dv[j,e] = sum_i p[i,j] dctx[i,e]
     batch(g);
@@ -666,14 +683,7 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
     Scope sc(M, CAT_ATTN, fl);
     K_TRY(gemm(g, M->cs));
   }
-  static const bool fused_on = [] { const char* e = getenv("HIFT_ATTN_FUSED"); return !(e && e[0] == '0'); }();
-  const bool fused = fused_on && attention_bwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, a.prob, a.ctx, dctx, M->dprob, M->dqkv);
-  if (fused) {
-    // dp, the softmax backward and dq in one kernel; dp never reaches memory
-    Scope sc(M, CAT_ATTN, 2 * fl);
-    K_TRY(attention_bwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, a.prob, a.ctx, dctx, d, M->dprob, M->dqkv, M->cs));
-  }
-  if (!fused) {
+  {
     Gemm g;  // dp[i,j] = sum_e dctx[i,e] v[j,e]
     batch(g);
     g.M = S; g.N = S; g.K = hd;
@@ -684,11 +694,11 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
     Scope sc(M, CAT_ATTN, fl);
     K_TRY(gemm(g, M->cs));
   }
-  if (!fused) {
+  {
     Scope sc(M, CAT_ELEM, 0);
     K_TRY(softmax_bwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, a.prob, M->dprob, M->cs));
   }
-  if (!fused) {
+  {
     Gemm g;  // dq[i,e] = sum_j ds[i,j] k[j,e]
     batch(g);
     g.M = S; g.N = hd; g.K = S;
@@ -904,8 +914,9 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
         if (n.bo) ST_TRY(bias_grad(M, D1, T, *n.bo, glo));
       }
       ST_TRY(linear_dx(M, D1, T, *n.wo, nullptr, D2));  // d ctx
-      ST_TRY(attention_bwd(M, a, D2, B, S));
-      if (rms) {
+      bool unrotated = false;
+      ST_TRY(attention_bwd(M, a, D2, B, S, &unrotated));
+      if (rms && !unrotated) {
         Scope sc(M, CAT_ELEM, 0);
         ST_TRY(ew(M, rope(dt, M->dqkv, T, S, H, hd, M->cos_sin, -1, st)));
       }
@@ -952,7 +963,8 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
         ST_TRY(bias_grad(M, D1, T, *n.bo, glo));
       }
       ST_TRY(linear_dx(M, D1, T, *n.wo, nullptr, D2));  // d ctx
-      ST_TRY(attention_bwd(M, a, D2, B, S));
+      bool unrotated = false;  // no rotary embedding in this architecture
+      ST_TRY(attention_bwd(M, a, D2, B, S, &unrotated));
       if (on) {
         ST_TRY(linear_dw(M, M->dqkv, x, T, *n.wqkv, glo));
         ST_TRY(bias_grad(M, M->dqkv, T, *n.bqkv, glo));
@@ -1800,8 +1812,22 @@ hift_status hift_kernel_attention_bwd_query(int32_t batch, int32_t heads, int32_
   if (batch < 0 || heads < 1 || seq < 0 || !qkv || !prob || !ctx || !dctx || !dprob || !dqkv) return fail(HIFT_EINVAL, "bad argument");
   if (!attention_bwd_fused_applies(DT_BF16, seq, head_dim, 3 * d, d, qkv, prob, ctx, dctx, dprob, dqkv))
     return fail(HIFT_EINVAL, "the fused kernel takes bf16, head widths 64 and 128 and 16-byte aligned buffers");
-  HIP_TRY(attention_bwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, ctx, dctx, d, dprob, dqkv,
+  HIP_TRY(attention_bwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, ctx, dctx, d, dprob, dqkv, nullptr,
                               (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_attention_bwd(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
+                                      const void* qkv, const void* prob, const void* ctx, const void* dctx, void* dprob,
+                                      void* dqkv, const float* cos_sin, void* stream) {
+  const int64_t d = (int64_t)heads * head_dim;
+  if (batch < 0 || heads < 1 || seq < 0 || !qkv || !prob || !ctx || !dctx || !dprob || !dqkv) return fail(HIFT_EINVAL, "bad argument");
+  if (!attention_bwd_fused_applies(DT_BF16, seq, head_dim, 3 * d, d, qkv, prob, ctx, dctx, dprob, dqkv) ||
+      (reinterpret_cast<uintptr_t>(cos_sin) & 7) != 0)
+    return fail(HIFT_EINVAL, "the fused kernels take bf16, head widths 64 and 128 and 16-byte aligned buffers");
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(attention_bwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, ctx, dctx, d, dprob, dqkv, cos_sin, st));
+  HIP_TRY(attention_bwd_kv_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, dprob, dctx, d, dqkv, cos_sin, st));
   return HIFT_OK;
 }
 

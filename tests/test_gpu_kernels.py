@@ -461,3 +461,53 @@ def test_gemm_with_packed_weight_operand_and_shared_last_round(M, N, K):
         tol = (1e-5 if out_f32 else 2 ** -8) * (np.abs(ref) + (scale if out_f32 else 0.02 * scale))
         bad = np.abs(got - ref) > tol
         assert not bad.any(), (out_f32, int(bad.sum()), float(np.max(np.abs(got - ref))))
+
+
+@pytest.mark.parametrize("B,H,S,hd,causal,rope", [(2, 3, 200, 64, 1, 1), (1, 2, 512, 128, 1, 1), (2, 2, 136, 128, 0, 0),
+                                                   (1, 2, 72, 64, 1, 0), (1, 1, 8, 128, 1, 1), (2, 4, 384, 64, 0, 1),
+                                                   (4, 32, 512, 128, 1, 1)])
+def test_fused_attention_backward_both_halves(B, H, S, hd, causal, rope):
+    """Query-major and key-major kernels together against the oracle's attention backward, followed (rope) by
+    the oracle's adjoint of the rotary embedding on dq and dk.  Inputs as in the query-half test; dv and dk
+    are sums over queries of bf16 P / dS times bf16 dO / Q in fp32, rounded once."""
+    import torch
+    import paper_2401_15207_amd as H_
+    from oracle import hift_oracle as O
+    rng = np.random.default_rng(11 + B * 1000 + S + hd + causal)
+    d = H * hd
+    full = B * H * S * S <= 2 ** 22
+    qkv = _bf16_round(rng.standard_normal((B * S, 3 * d)) * (1.5 if full else 1.0))
+    dctx = _bf16_round(rng.standard_normal((B * S, d)))
+    heads = lambda a: a.reshape(B, S, H, hd).transpose(0, 2, 1, 3).astype(np.float64)
+    q, k, v, do = heads(qkv[:, :d]), heads(qkv[:, d:2 * d]), heads(qkv[:, 2 * d:]), heads(dctx)
+    _c, p = O.attention_fwd(q, k, v, bool(causal))
+    p = _bf16_round(p).astype(np.float64)
+    ctx = _bf16_round(np.matmul(p, v))
+    ctx_rows = np.ascontiguousarray(ctx.transpose(0, 2, 1, 3).reshape(B * S, d))
+    cos, sin = O.rope_angles(S, hd, 10000.0, np.float64)
+    tab = torch.from_numpy(np.stack([cos, sin], -1).astype(np.float32)).cuda().contiguous() if rope else None
+    d_ds = torch.full((B, H, S, S), float("nan"), dtype=torch.bfloat16, device="cuda")
+    d_dqkv = torch.full((B * S, 3 * d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    H_.kernel_attention_bwd(B, H, S, hd, causal, _dev(qkv, True), _dev(p, True), _dev(ctx_rows, True), _dev(dctx, True), d_ds,
+                            d_dqkv, tab)
+    torch.cuda.synchronize()
+    out = d_dqkv.float().cpu().numpy()
+    assert np.isfinite(out).all()
+    dq, dk, dv = heads(out[:, :d]), heads(out[:, d:2 * d]), heads(out[:, 2 * d:])
+    pairs = [(b, h) for b in range(B) for h in range(H)] if full else [(0, 0), (B - 1, H - 1)]
+    for b, h in pairs:
+        dq_ref, dk_ref, dv_ref = O.attention_bwd(do[b, h], q[b, h], k[b, h], v[b, h], p[b, h])
+        delta = 2.0 ** -8 * np.abs(do[b, h] * ctx[b, h]).sum(-1, keepdims=True) / np.sqrt(hd)
+        slack_q = delta * np.abs(p[b, h] @ k[b, h])
+        slack_k = (p[b, h] * delta).T @ np.abs(q[b, h])
+        if rope:
+            dq_ref, dk_ref = O.rope_bwd(dq_ref, cos, sin), O.rope_bwd(dk_ref, cos, sin)
+            mix = lambda s: s + np.roll(s, hd // 2, axis=-1)       # a rotated entry mixes the two of its pair
+            slack_q, slack_k = mix(slack_q), mix(slack_k)
+        for name, got, ref, slack in (("dq", dq[b, h], dq_ref, slack_q), ("dk", dk[b, h], dk_ref, slack_k),
+                                      ("dv", dv[b, h], dv_ref, 0.0)):
+            rms = np.sqrt(np.mean(ref ** 2))
+            err = np.abs(got - ref)
+            bad = err > 2 ** -7 * np.abs(ref) + 2e-2 * rms + slack + 1e-6
+            assert not bad.any(), (name, b, h, int(bad.sum()), float(err.max()), float(rms))
+            assert np.sqrt(np.mean(err ** 2)) <= 5e-3 * rms + np.sqrt(np.mean(np.square(slack))) + 1e-6, (name, b, h)
