@@ -39,7 +39,10 @@ that matter here: final norm belongs to the head unit, embedding LayerNorm to th
 unit; AdamW bias correction uses a per-group update counter; weight decay applies to tensors
 with two or more dimensions; eps 1e-8 (AdamW), 1e-10 (AdaGrad, zero initial accumulator);
 SGD momentum without dampening or Nesterov, first buffer = first gradient; erf-GELU; RoPE pairs
-(i, i + hd/2) with base 10000; no dropout, clipping or accumulation; untied embeddings.
+(i, i + hd/2) with base 10000; no dropout, clipping or accumulation; embeddings untied unless
+the configuration sets `tie_embeddings` (GPT-2 / OPT of section 4.1 share the token table with the
+output matrix): the shared matrix then belongs to the embeddings unit, the head unit keeps the
+final norm alone, and the table's gradient is the sum over its two uses.
 
 Pins (tests/test_oracle_*.py): central finite differences of every tensor in float64,
 PyTorch-autograd gradients of an independently written forward, frozen-parameter bit
@@ -68,6 +71,9 @@ STRATEGIES = ("bottom2up", "top2down", "random")
 def param_tensors(cfg: dict):
     """Canonical tensor list [(name, shape, kind, unit)], in storage order."""
     a, L, d, f, V = cfg["arch"], cfg["n_layers"], cfg["d_model"], cfg["d_ffn"], cfg["vocab"]
+    tied = bool(cfg.get("tie_embeddings", 0))   # decoders only: the output matrix is the token table (unit 0)
+    if tied and a == ARCH_POSTLN_ENCODER:
+        raise ValueError("tie_embeddings applies to the decoders")
     out = []
     if a == ARCH_PRELN_DECODER:
         out += [("tok_emb", (V, d), KIND_MATRIX, 0), ("pos_emb", (cfg["max_seq"], d), KIND_MATRIX, 0)]
@@ -79,8 +85,9 @@ def param_tensors(cfg: dict):
                     (p + "ln2_g", (d,), KIND_GAIN, u), (p + "ln2_b", (d,), KIND_BIAS, u),
                     (p + "w1", (f, d), KIND_MATRIX, u), (p + "b1", (f,), KIND_BIAS, u),
                     (p + "w2", (d, f), KIND_MATRIX, u), (p + "b2", (d,), KIND_BIAS, u)]
-        out += [("lnf_g", (d,), KIND_GAIN, L + 1), ("lnf_b", (d,), KIND_BIAS, L + 1),
-                ("whead", (V, d), KIND_MATRIX, L + 1)]
+        out += [("lnf_g", (d,), KIND_GAIN, L + 1), ("lnf_b", (d,), KIND_BIAS, L + 1)]
+        if not tied:
+            out += [("whead", (V, d), KIND_MATRIX, L + 1)]
     elif a == ARCH_POSTLN_ENCODER:
         out += [("tok_emb", (V, d), KIND_MATRIX, 0), ("pos_emb", (cfg["max_seq"], d), KIND_MATRIX, 0),
                 ("lne_g", (d,), KIND_GAIN, 0), ("lne_b", (d,), KIND_BIAS, 0)]
@@ -101,7 +108,9 @@ def param_tensors(cfg: dict):
             out += [(p + "g1", (d,), KIND_GAIN, u), (p + "wqkv", (3 * d, d), KIND_MATRIX, u),
                     (p + "wo", (d, d), KIND_MATRIX, u), (p + "g2", (d,), KIND_GAIN, u),
                     (p + "wgu", (2 * f, d), KIND_MATRIX, u), (p + "wd", (d, f), KIND_MATRIX, u)]
-        out += [("gf", (d,), KIND_GAIN, L + 1), ("whead", (V, d), KIND_MATRIX, L + 1)]
+        out += [("gf", (d,), KIND_GAIN, L + 1)]
+        if not tied:
+            out += [("whead", (V, d), KIND_MATRIX, L + 1)]
     else:
         raise ValueError("unknown arch")
     return out
@@ -452,7 +461,8 @@ def loss_and_grad(cfg: dict, flat: np.ndarray, tokens: np.ndarray, labels: np.nd
         loss, dlogits = cross_entropy_fwd(logits, labels.reshape(-1).astype(np.int64))
     else:
         xf, nf = norm_fwd(x, "gf" if rms else "lnf_g", "lnf_b")
-        logits = xf @ P["whead"].T
+        head = "tok_emb" if cfg.get("tie_embeddings", 0) else "whead"
+        logits = xf @ P[head].T
         loss, dlogits = cross_entropy_fwd(logits, labels.reshape(-1).astype(np.int64))
     if not need_grad:
         return float(loss), None
@@ -468,8 +478,8 @@ def loss_and_grad(cfg: dict, flat: np.ndarray, tokens: np.ndarray, labels: np.nd
         dx[:, 0, :] = dxc
         dx = dx.reshape(T, d)
     else:
-        G["whead"][...] = dlogits.T @ xf
-        dxf = dlogits @ P["whead"]
+        G[head][...] = dlogits.T @ xf      # tied: the token table's gradient starts with its use as output matrix
+        dxf = dlogits @ P[head]
         if rms:
             dx, G["gf"][...] = rmsnorm_bwd(dxf, nf, P["gf"])
         else:

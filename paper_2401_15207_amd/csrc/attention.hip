@@ -1,9 +1,13 @@
-// Fused attention forward for gfx950: scores, softmax and the product with V in one kernel; the
-// scores never reach HBM.  The probabilities do (bf16, [B, H, S, S]): the backward pass reads them.
+// Fused attention for gfx950, three kernels:
+//   attn_k<.., BWD = false>  forward: scores, softmax and the product with V; the scores never reach HBM.  The
+//                            probabilities do (bf16, [B, H, S, S]): the backward pass reads them.
+//   attn_k<.., BWD = true>   query-major half of the backward: dP, the softmax derivative and dQ (same body, K and V
+//                            exchanged); writes dS for the other half.
+//   attn_bwd_kv_k            key-major half of the backward: dV and dK, sums over the queries.
 //
-// One workgroup = 32 NW query rows of one (batch, head), NW = 2 or 4 wavefronts; each wavefront owns
+// Forward: one workgroup = 32 NW query rows of one (batch, head), NW = 2 or 4 wavefronts; each wavefront owns
 // 32 rows from start to end, so the softmax of a row never leaves its wavefront.  Keys and values pass
-// through LDS in tiles of 64 keys; the next tile is on its way from HBM (in registers) while the
+// through LDS in tiles of 64 keys; the next tile is on its way from HBM (direct-to-LDS loads) while the
 // current one is used.  Two passes over the keys: the first finds each row's maximum and
 // normaliser (online), the second recomputes the scores, writes the normalised probabilities and
 // accumulates P.V from the bf16-rounded probabilities, which is exactly what separate softmax and

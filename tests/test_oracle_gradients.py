@@ -20,8 +20,8 @@ SMALL = {
 }
 
 
-def _setup(arch, seed=3, B=2, S=6, std=0.3):
-    cfg = SMALL[arch]
+def _setup(arch, seed=3, B=2, S=6, std=0.3, tied=0):
+    cfg = dict(SMALL[arch], tie_embeddings=tied)
     spec = [(n, s, k) for n, s, k, _u in O.param_tensors(cfg)]
     theta = init_params(seed, spec, bf16_exact=False, std=std, jitter=0.2).astype(np.float64)
     wl = dict(cfg, batch=B, seq=S)
@@ -29,9 +29,9 @@ def _setup(arch, seed=3, B=2, S=6, std=0.3):
     return cfg, theta, tok, lab
 
 
-@pytest.mark.parametrize("arch", [0, 1, 2])
-def test_finite_differences_every_tensor(arch):
-    cfg, theta, tok, lab = _setup(arch)
+@pytest.mark.parametrize("arch,tied", [(0, 0), (1, 0), (2, 0), (0, 1), (2, 1)])
+def test_finite_differences_every_tensor(arch, tied):
+    cfg, theta, tok, lab = _setup(arch, tied=tied)
     loss, g = O.loss_and_grad(cfg, theta, tok, lab)
     rng = np.random.default_rng(0)
     off, h = 0, 1e-5
@@ -101,13 +101,13 @@ def _torch_forward(cfg, P, tok, lab):
         logits = F.linear(x[:, 0, :], P["wc"], P["bc"])
         return F.cross_entropy(logits, lab_t)
     xf = rms(x, P["gf"]) if a == 2 else F.layer_norm(x, (d,), P["lnf_g"], P["lnf_b"], eps)
-    logits = F.linear(xf, P["whead"])
+    logits = F.linear(xf, P["tok_emb"] if cfg.get("tie_embeddings", 0) else P["whead"])
     return F.cross_entropy(logits.reshape(B * S, -1), lab_t.reshape(-1), ignore_index=-1)
 
 
-@pytest.mark.parametrize("arch", [0, 1, 2])
-def test_against_torch_autograd(arch):
-    cfg, theta, tok, lab = _setup(arch, seed=11, B=3, S=7)
+@pytest.mark.parametrize("arch,tied", [(0, 0), (1, 0), (2, 0), (0, 1), (2, 1)])
+def test_against_torch_autograd(arch, tied):
+    cfg, theta, tok, lab = _setup(arch, seed=11, B=3, S=7, tied=tied)
     loss, g = O.loss_and_grad(cfg, theta, tok, lab)
     P, off = {}, 0
     for name, shape, _k, _u in O.param_tensors(cfg):
@@ -138,3 +138,22 @@ def test_tiny_config_c1_against_torch_autograd():
     lt.backward()
     gt = np.concatenate([P[n].grad.numpy().reshape(-1) for n, _s, _k, _u in O.param_tensors(cfg)])
     assert np.max(np.abs(gt - g)) <= 1e-12
+
+
+@pytest.mark.parametrize("arch", [0, 2])
+def test_tied_gradient_is_the_sum_over_both_uses(arch):
+    """Chain rule: with the output matrix set equal to the token table, the tied model computes the same
+    loss as the untied one, every other gradient is the same, and the table's gradient is the untied
+    table's plus the untied output matrix's."""
+    cfg_t, theta_t, tok, lab = _setup(arch, seed=7, tied=1)
+    cfg_u = dict(cfg_t, tie_embeddings=0)
+    V, d = cfg_t["vocab"], cfg_t["d_model"]
+    theta_u = np.concatenate([theta_t, theta_t[:V * d]])          # whead is the last tensor of the untied layout
+    assert O.param_tensors(cfg_u)[-1][0] == "whead" and O.param_tensors(cfg_u)[0][0] == "tok_emb"
+    loss_t, g_t = O.loss_and_grad(cfg_t, theta_t, tok, lab)
+    loss_u, g_u = O.loss_and_grad(cfg_u, theta_u, tok, lab)
+    assert loss_t == loss_u
+    n = theta_t.size
+    assert np.array_equal(g_t[V * d:], g_u[V * d:n])
+    assert np.max(np.abs(g_t[:V * d] - (g_u[:V * d] + g_u[n:]))) <= 1e-15
+    assert O.n_units(cfg_t) == O.n_units(cfg_u) and O.unit_ranges(cfg_t)[-1][1] == O.unit_ranges(cfg_u)[-1][1] - V * d
