@@ -263,7 +263,11 @@ def main():
         "config": {"workload": f"{a.workload}: LLaMA-7B-shaped decoder, 32 layers d=4096 h=32 ffn=11008 vocab=32000, "
                                f"batch {B} x seq {S}, m={wl['m']} ({k} groups), bottom2up, AdamW, optimizer state "
                                + ("resident in HBM" if a.state_resident else "of inactive groups in pinned host memory")
-                               if a.workload == "C4" else a.workload,
+                               if a.workload == "C4" else
+                               f"{a.workload}: arch {cfg['arch']}, {cfg['n_layers']} layers d={cfg['d_model']} h={cfg['n_heads']} "
+                               f"ffn={cfg['d_ffn']} vocab={cfg['vocab']}" + (", tied embeddings" if cfg.get("tie_embeddings") else "")
+                               + f", batch {B} x seq {S}, m={wl['m']} ({k} groups), {wl['strategy']}, {wl['opt']['kind']}, state "
+                               + ("resident in HBM" if a.state_resident else "of inactive groups in pinned host memory"),
                    "groups": k, "tokens_per_step": B * S},
         "roofline": {
             "bound": "mfma",

@@ -48,6 +48,13 @@ WORKLOADS = {
                opt=dict(kind="adamw", lr=1e-5, beta1=0.9, beta2=0.999, eps=1e-8,
                         weight_decay=0.0, momentum=0.0)),
 }
+# The second decoder family of the paper's model list (GPT-2 / OPT: learned positions, LayerNorm, GELU,
+# biases, output matrix tied to the token table) at the OPT-13B shape, batch and grouping as C5.
+WORKLOADS["OPT13B"] = dict(arch=0, n_layers=40, d_model=5120, n_heads=40, d_ffn=20480, vocab=50272,
+                           max_seq=2048, n_classes=0, norm_eps=1e-5, rope_base=10000.0, dtype=1,
+                           batch=2, seq=1024, m=4, strategy="bottom2up", tie_embeddings=1,
+                           opt=dict(kind="adamw", lr=1e-5, beta1=0.9, beta2=0.999, eps=1e-8,
+                                    weight_decay=0.0, momentum=0.0))
 WORKLOADS["C4_L2"] = dict(WORKLOADS["C4"], n_layers=2)
 WORKLOADS["C5_L2"] = dict(WORKLOADS["C5"], n_layers=2, m=2)
 
@@ -58,6 +65,8 @@ MODEL_KEYS = ("arch", "n_layers", "d_model", "n_heads", "d_ffn", "vocab", "max_s
 def model_config(workload: dict, **overrides) -> dict:
     """The model-shape part of a workload, optionally with fields replaced."""
     cfg = {k: workload[k] for k in MODEL_KEYS}
+    if workload.get("tie_embeddings"):
+        cfg["tie_embeddings"] = 1
     cfg.update(overrides)
     return cfg
 

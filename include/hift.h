@@ -88,6 +88,10 @@ typedef struct {
   int32_t no_packed_copies; /* 1: do not keep the second and third bf16 copy of the large matrices (in
                             MFMA fragment order, for the fast contraction kernel); the contractions
                             then read the row-major copy.  Saves 4 bytes per parameter, costs speed */
+  int32_t tie_embeddings; /* 1 (arch 0 and 2): the output matrix is the token table (GPT-2, OPT of section
+                            "Experiments"): there is no whead tensor, the shared matrix belongs to unit 0,
+                            unit L+1 keeps the final norm alone, and the table's gradient is the sum over
+                            its two uses */
 } hift_config;
 
 typedef struct {
@@ -174,8 +178,7 @@ hift_status hift_memory_report(const hift_config* cfg, const hift_opt* opt, int3
  *   pinned_arena      host, page-locked, pinned_bytes long, zero-filled by the library
  *                     (may be NULL when pinned_host_bytes is 0)
  *   streams           compute, host-to-device, device-to-host
- * Optimizer state starts at zero.  Errors: HIFT_EINVAL (bad shape, e.g. tied embeddings are
- * not expressible), HIFT_ENOMEM, HIFT_EDEVICE. */
+ * Optimizer state starts at zero.  Errors: HIFT_EINVAL (bad shape), HIFT_ENOMEM, HIFT_EDEVICE. */
 hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32_t m,
                               int32_t max_batch, int32_t max_seq, const float* init_params_host,
                               void* device_arena, size_t device_bytes, void* pinned_arena,

@@ -30,7 +30,8 @@ class Config(C.Structure):
     _fields_ = [("arch", C.c_int32), ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("max_seq", C.c_int32), ("n_classes", C.c_int32),
                 ("norm_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32),
-                ("state_on_host", C.c_int32), ("master_on_host", C.c_int32), ("no_packed_copies", C.c_int32)]
+                ("state_on_host", C.c_int32), ("master_on_host", C.c_int32), ("no_packed_copies", C.c_int32),
+                ("tie_embeddings", C.c_int32)]
 
 
 class Memory(C.Structure):
@@ -119,7 +120,7 @@ def make_config(cfg: dict, state_on_host: int = 0) -> Config:
     return Config(cfg["arch"], cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["d_ffn"], cfg["vocab"],
                   cfg["max_seq"], cfg.get("n_classes", 0), cfg["norm_eps"], cfg.get("rope_base", 10000.0),
                   cfg["dtype"], cfg.get("state_on_host", state_on_host), cfg.get("master_on_host", 0),
-                  cfg.get("no_packed_copies", 0))
+                  cfg.get("no_packed_copies", 0), cfg.get("tie_embeddings", 0))
 
 
 def make_opt(opt: dict) -> Opt:

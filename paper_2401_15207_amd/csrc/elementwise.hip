@@ -62,10 +62,10 @@ __global__ void __launch_bounds__(BLK) embed_fwd_k(const int32_t* __restrict__ t
 // Gradient of the token table, deterministic: the workgroup of the first position that holds a token
 // sums the rows of all positions holding it, in position order, and writes the table row once; the
 // workgroups of later occurrences have nothing to do.  (Rows of tokens that do not occur are zeroed
-// by the caller.)  T_ is a few thousand: the scan over the token list costs nothing against the rows.
+// by the caller; with `add` the row's previous content is kept and added to.)  T_ is a few thousand: the scan over the token list costs nothing against the rows.
 template <typename T>
 __global__ void __launch_bounds__(BLK) embed_bwd_tok_k(const int32_t* __restrict__ tokens, int64_t T_, int d, int vocab,
-                                                        const T* __restrict__ dx, float* __restrict__ g_tok) {
+                                                        const T* __restrict__ dx, float* __restrict__ g_tok, bool add) {
   const int64_t p = blockIdx.x;
   auto clamp = [vocab](int id) { return id < 0 ? 0 : (id >= vocab ? vocab - 1 : id); };
   const int id = clamp(tokens[p]);
@@ -87,7 +87,7 @@ __global__ void __launch_bounds__(BLK) embed_bwd_tok_k(const int32_t* __restrict
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int j = j0 + e * BLK + threadIdx.x;
-      if (j < d) gr[j] = acc[e];
+      if (j < d) gr[j] = add ? gr[j] + acc[e] : acc[e];
     }
   }
 }
@@ -873,13 +873,13 @@ hipError_t embed_fwd(int dt, const int32_t* tokens, int64_t T_, int S, int d, in
 }
 
 hipError_t embed_bwd(int dt, const int32_t* tokens, int64_t T_, int S, int d, int V_, const void* dx,
-                     float* g_tok, float* g_pos, hipStream_t st) {
+                     float* g_tok, float* g_pos, bool add, hipStream_t st) {
   if (T_ == 0) return hipSuccess;
   if (dt == DT_F32) {
-    embed_bwd_tok_k<float><<<dim3((unsigned)T_), BLK, 0, st>>>(tokens, T_, d, V_, (const float*)dx, g_tok);
+    embed_bwd_tok_k<float><<<dim3((unsigned)T_), BLK, 0, st>>>(tokens, T_, d, V_, (const float*)dx, g_tok, add);
     if (g_pos) embed_bwd_pos_k<float><<<dim3(S), BLK, 0, st>>>((int)(T_ / S), S, d, (const float*)dx, g_pos);
   } else {
-    embed_bwd_tok_k<bf16><<<dim3((unsigned)T_), BLK, 0, st>>>(tokens, T_, d, V_, (const bf16*)dx, g_tok);
+    embed_bwd_tok_k<bf16><<<dim3((unsigned)T_), BLK, 0, st>>>(tokens, T_, d, V_, (const bf16*)dx, g_tok, add);
     if (g_pos) embed_bwd_pos_k<bf16><<<dim3(S), BLK, 0, st>>>((int)(T_ / S), S, d, (const bf16*)dx, g_pos);
   }
   LAUNCH_CHECK();

@@ -122,9 +122,10 @@ hipError_t softmax_bwd(int dt, int64_t nbh, int S, float scale, bool causal, con
 // logits [rows, V] -> d loss / d logits in place; loss = mean over labels >= 0
 hipError_t cross_entropy(int dt, int64_t rows, int V, void* logits, const int32_t* labels,
                          float* row_loss, float* loss_out, hipStream_t st);
-// g_tok[tok[t], :] += dx[t, :] (fp32 atomics);  g_pos[s, :] = sum_b dx[b*S+s, :]
+// g_tok[v, :] = (add ? g_tok[v, :] : as zeroed by the caller) + sum over positions t holding token v of dx[t, :],
+// in position order (no atomics: the first position holding a token does its row);  g_pos[s, :] = sum_b dx[b*S+s, :]
 hipError_t embed_bwd(int dt, const int32_t* tokens, int64_t T, int S, int d, int V, const void* dx,
-                     float* g_tok, float* g_pos, hipStream_t st);
+                     float* g_tok, float* g_pos, bool add, hipStream_t st);
 // rows of x at positions b*S (first token of every sequence) -> y [B, d], and the adjoint
 hipError_t gather_first(int dt, int B, int S, int d, const void* x, void* y, hipStream_t st);
 hipError_t scatter_first(int dt, int B, int S, int d, const void* dy, void* dx, hipStream_t st);

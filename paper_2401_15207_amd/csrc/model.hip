@@ -79,6 +79,8 @@ hift_status check_config(const hift_config* c) {
     return fail(HIFT_EINVAL, "head width must be even for rotary positions");
   if (c->arch == HIFT_ARCH_POSTLN_ENCODER && c->n_classes < 1) return fail(HIFT_EINVAL, "n_classes must be >= 1");
   if (c->dtype != HIFT_F32 && c->dtype != HIFT_BF16) return fail(HIFT_EINVAL, "dtype unknown");
+  if (c->tie_embeddings && c->arch == HIFT_ARCH_POSTLN_ENCODER)
+    return fail(HIFT_EINVAL, "tie_embeddings applies to the decoders (the encoder's head is a classifier)");
   if (!(c->norm_eps >= 0.f)) return fail(HIFT_EINVAL, "norm_eps must be >= 0");
   if (c->master_on_host && (c->dtype != HIFT_BF16 || !c->state_on_host))
     return fail(HIFT_EINVAL, "master_on_host needs dtype bf16 (the forward copy stays in HBM) and state_on_host");
@@ -108,7 +110,7 @@ void build_layout(const hift_config& c, Layout& L) {
       add(p + "w2", u, M, d, f); add(p + "b2", u, Bk, d, 1);
     }
     add("lnf_g", nl + 1, G, d, 1); add("lnf_b", nl + 1, Bk, d, 1);
-    add("whead", nl + 1, M, V, d);
+    if (!c.tie_embeddings) add("whead", nl + 1, M, V, d);
   } else if (c.arch == HIFT_ARCH_POSTLN_ENCODER) {
     add("tok_emb", 0, M, V, d);
     add("pos_emb", 0, M, c.max_seq, d);
@@ -138,7 +140,7 @@ void build_layout(const hift_config& c, Layout& L) {
       add(p + "wd", u, M, d, f);
     }
     add("gf", nl + 1, G, d, 1);
-    add("whead", nl + 1, M, V, d);
+    if (!c.tie_embeddings) add("whead", nl + 1, M, V, d);
   }
   L.n_units = nl + 2;
   L.n_params = off;
@@ -419,7 +421,9 @@ hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_o
   // is one the packed-operand kernel takes.
   M->wpk_bytes = 0;
   for (Tensor& t : M->lay.t) {
-    if (t.kind != HIFT_KIND_MATRIX || t.unit == 0 || M->dt != DT_BF16 || cfg->no_packed_copies) continue;
+    // of the embeddings unit only a token table that doubles as output matrix multiplies anything
+    const bool contracts = t.unit != 0 || (cfg->tie_embeddings && t.name == "tok_emb");
+    if (t.kind != HIFT_KIND_MATRIX || !contracts || M->dt != DT_BF16 || cfg->no_packed_copies) continue;
     const int64_t rows = (cfg->arch == HIFT_ARCH_POSTLN_ENCODER && t.unit == M->lay.n_units - 1) ? max_batch : M->maxT;
     Gemm g;
     g.dtype = DT_BF16;
@@ -829,7 +833,7 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
       if (rms) ST_TRY(ew(M, norm_fwd(dt, true, T, d, c.norm_eps, xl, M->W("gf"), nullptr, M->xf, M->st_f, st)));
       else ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, xl, M->W("lnf_g"), M->W("lnf_b"), M->xf, M->st_f, st)));
     }
-    ST_TRY(linear(M, M->xf, T, M->T_("whead"), nullptr, nullptr, M->logits));
+    ST_TRY(linear(M, M->xf, T, M->T_(c.tie_embeddings ? "tok_emb" : "whead"), nullptr, nullptr, M->logits));
     Scope sc(M, CAT_ELEM, 0);
     ST_TRY(ew(M, cross_entropy(dt, T, c.vocab, M->logits, bt->labels, M->row_loss, M->loss_dev, st)));
   }
@@ -862,8 +866,10 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
     Scope sc(M, CAT_ELEM, 0);
     ST_TRY(ew(M, scatter_first(dt, B, S, d, M->dcls, Dc, st)));
   } else {
-    const Tensor& wh = M->T_("whead");
-    if (head_on) ST_TRY(linear_dw(M, M->logits, M->xf, T, wh, glo));
+    // tied embeddings: the output matrix is the token table of unit 0; its gradient starts here and the
+    // embedding part is added at the bottom of the backward pass
+    const Tensor& wh = M->T_(c.tie_embeddings ? "tok_emb" : "whead");
+    if (c.tie_embeddings ? active(0) : head_on) ST_TRY(linear_dw(M, M->logits, M->xf, T, wh, glo));
     ST_TRY(linear_dx(M, M->logits, T, wh, nullptr, D2));  // d xf
     const Tensor& g = M->T_(rms ? "gf" : "lnf_g");
     Scope sc(M, CAT_ELEM, 0);
@@ -984,14 +990,15 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
       dx = D1;
     }
     float* gpos = nullptr;
-    int64_t zero_cnt = te.count();
+    const bool tied = c.tie_embeddings != 0;  // the table's gradient already holds its part as output matrix
+    int64_t zero_cnt = tied ? 0 : te.count();
     if (!rms) {
       const Tensor& pe = M->T_("pos_emb");
       gpos = G(pe);
       zero_cnt += pe.count();  // pos_emb follows tok_emb in the layout
     }
-    ST_TRY(ew(M, fill_zero(G(te), (size_t)zero_cnt * 4, st)));
-    ST_TRY(ew(M, embed_bwd(dt, bt->tokens, T, S, d, c.vocab, dx, G(te), gpos, st)));
+    if (zero_cnt) ST_TRY(ew(M, fill_zero(tied ? gpos : G(te), (size_t)zero_cnt * 4, st)));
+    ST_TRY(ew(M, embed_bwd(dt, bt->tokens, T, S, d, c.vocab, dx, G(te), gpos, tied, st)));
   }
   return HIFT_OK;
 }

@@ -33,8 +33,12 @@ def test_every_declared_symbol_is_exported(H):
 
 
 def test_layout_matches_oracle_for_all_workloads(H):
-    for name in ("C1", "C2", "C3", "C4", "C5", "C4_L2", "C5_L2"):
-        cfg = model_config(WORKLOADS[name])
+    cfgs = [model_config(WORKLOADS[name]) for name in ("C1", "C2", "C3", "C4", "C5", "C4_L2", "C5_L2")]
+    cfgs += [model_config(WORKLOADS[name], tie_embeddings=1) for name in ("C1", "C4")]     # no whead tensor
+    assert O.n_params(cfgs[-1]) == O.n_params(cfgs[3]) - 32000 * 4096
+    with pytest.raises(H.HiftError):
+        H.tensor_list(model_config(WORKLOADS["C2"], tie_embeddings=1))                        # the encoder has no output matrix to tie
+    for cfg in cfgs:
         tl, n = H.tensor_list(cfg)
         ref = O.param_tensors(cfg)
         assert n == O.n_params(cfg) and len(tl) == len(ref)

@@ -108,6 +108,16 @@ def test_c4_width_two_layers_gradients_all_groups():
     _gradient_check(WORKLOADS["C4_L2"], lambda k: range(k))
 
 
+def test_tied_embeddings_on_the_packed_kernels():
+    # The token table doubles as output matrix (GPT-2 / OPT style) and is wide enough to get fragment-order
+    # copies: forward head, head dX and the two-part gradient of the table all run on the fast kernels.
+    wl = dict(arch=2, n_layers=2, d_model=1024, n_heads=8, d_ffn=2816, vocab=8192, max_seq=512, n_classes=0,
+              norm_eps=1e-5, rope_base=10000.0, dtype=1, batch=4, seq=512, m=1, strategy="bottom2up",
+              opt=WORKLOADS["C4"]["opt"], tie_embeddings=1)
+    orc, gpu = _gradient_check(wl, lambda k: range(k))
+    assert gpu.n_units == 4 and [n for n, *_ in gpu.tensors][-1] == "gf"      # no separate output matrix
+
+
 def test_c5_width_two_layers_group_of_two_units():
     wl = dict(WORKLOADS["C5_L2"], batch=1)
     _gradient_check(wl, lambda k: [1], m=2)

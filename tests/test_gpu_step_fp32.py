@@ -18,10 +18,13 @@ SMALL1 = dict(arch=1, n_layers=2, d_model=64, n_heads=4, d_ffn=128, vocab=300, m
 SMALL2 = dict(arch=2, n_layers=2, d_model=64, n_heads=4, d_ffn=96, vocab=320, max_seq=48, n_classes=0,
               norm_eps=1e-5, rope_base=10000.0, dtype=0, batch=2, seq=40, m=1, strategy="random",
               opt=WORKLOADS["C1"]["opt"])
+# GPT-2 / OPT style: the output matrix is the token table (section 4.1 lists both families)
+TIED0 = dict(WORKLOADS["C1"], tie_embeddings=1)
+TIED2 = dict(SMALL2, tie_embeddings=1)
 SGD1 = dict(kind="sgd", lr=1.0, beta1=0, beta2=0, eps=0, weight_decay=0.0, momentum=0.0)
 
 
-@pytest.mark.parametrize("wl", [WORKLOADS["C1"], SMALL1, SMALL2], ids=["C1", "enc", "rope"])
+@pytest.mark.parametrize("wl", [WORKLOADS["C1"], SMALL1, SMALL2, TIED0, TIED2], ids=["C1", "enc", "rope", "C1_tied", "rope_tied"])
 def test_two_cycles_adamw(wl):
     orc, gpu, _ = make_pair(wl, seed=3, jitter=0.02)
     k = orc.k
@@ -40,7 +43,7 @@ def test_two_cycles_adamw(wl):
     assert gpu.cycle_index() == (2 * k, 2)
 
 
-@pytest.mark.parametrize("wl", [WORKLOADS["C1"], SMALL1, SMALL2], ids=["C1", "enc", "rope"])
+@pytest.mark.parametrize("wl", [WORKLOADS["C1"], SMALL1, SMALL2, TIED0, TIED2], ids=["C1", "enc", "rope", "C1_tied", "rope_tied"])
 def test_gradient_of_every_group_via_sgd(wl):
     # SGD, lr 1, no momentum/decay: theta0 - theta1 is the gradient of the active group
     tok, lab = make_batch(wl, 5, 1)
