@@ -245,6 +245,16 @@ def main():
     n_rest, ms_rest, fl_rest = model.profile_read(4)
     n_pack, ms_pack, by_pack = model.profile_read(5)
     model.profile_enable(False)
+    # one more cycle read step by step from the library's own events on the compute stream: what a step costs
+    # as a function of the group's depth (group 0 = the whole dX chain and almost no dW: the cost shape of an
+    # adapter method; the top group = forward and the head only).  Reading the events waits for the streams,
+    # so the state copies of consecutive steps do not overlap here as they do in the timed region.
+    by_group = {}
+    for _ in range(k):
+        t += 1
+        gid = model.schedule_group_at(t)
+        model.step(*batches[(t - 1) % n_total], gid, want_loss=False)
+        by_group[gid] = round(model.last_step_ms()[0], 3)
     # exposed copy time and loss of one more step
     t += 1
     loss = model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=True)
@@ -292,6 +302,7 @@ def main():
         "exposed_state_copy_ms_last_step": exposed,
         "state_copy_engine": "copy kernel, %d workgroups" % a.copy_blocks if a.copy_engine == 1 else "hipMemcpyAsync",
         "ms_per_step_with_event_brackets": 1e3 * t_prof / max(a.steps, 1),
+        "compute_stream_ms_by_group": [by_group[g] for g in sorted(by_group)],
         "last_loss": loss,
         "setup_s": setup_s,
         "memory_gb": {kk: round(mem[kk] / 1e9, 2) for kk in ("para", "gra", "sta", "pgs", "residual", "total", "pinned_total")},
