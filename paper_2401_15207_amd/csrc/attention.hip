@@ -124,7 +124,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
   const bf16* q = qkv + (int64_t)b * S * ld + (int64_t)h * HD;
   const bf16* k = q + d;
   const bf16* v = q + 2 * d;
-  bf16* P = prob + (int64_t)bh * S * S;
+  bf16* P = prob ? prob + (int64_t)bh * S * S : nullptr;
   bf16* O = ctx + (int64_t)b * S * ldc + (int64_t)h * HD;
 
   const int q0 = qb * QB + wave * 32;  // this wavefront's first row
@@ -291,7 +291,9 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
     // offset added, and are dropped by the store
     const __amdgpu_buffer_rsrc_t rsP = __builtin_amdgcn_make_buffer_rsrc(P, 0, (int)(uint32_t)((int64_t)S * S * 2), 0x00020000);
     const uint32_t prow = row_ok ? (uint32_t)((int64_t)row * S * 2) + 16u * fh : 0x80000000u;
+    const bool keep_p = prob != nullptr;  // null: nobody will read the probabilities (no backward through this layer)
     auto store_p = [&](int kt, const u32x4(&pk)[4]) __attribute__((always_inline)) {
+      if (!keep_p) return;
       // whole tiles inside S (the usual case): the row offset plus a scalar; else per piece
       if (kt * KTILE + KTILE <= S) {
   #pragma unroll
@@ -650,6 +652,7 @@ inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) =
 
 }  // namespace
 
+// prob may be null for the forward (the probabilities are then not stored)
 bool attention_fwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* prob, const void* ctx) {
   return dt == DT_BF16 && (hd == 64 || hd == 128) && S >= 8 && S % 8 == 0 && ld % 8 == 0 && ldc % 4 == 0 && al16(qkv) && al16(prob) &&
          (int64_t)S * ld * 2 < (int64_t(1) << 32) && (int64_t)S * S * 2 <= (int64_t(1) << 31) &&

@@ -599,7 +599,9 @@ hift_status bias_grad(hift_model* M, const void* dy, int64_t rows, const Tensor&
   return HIFT_OK;
 }
 
-hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S) {
+// keep_prob = false: no backward pass will come through this layer; the fused kernel then does not store the
+// probabilities (the unfused path needs the buffer as its work space either way)
+hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S, bool keep_prob) {
   const hift_config& c = M->cfg;
   const int64_t d = c.d_model, H = c.n_heads, hd = d / H;
   const size_t es = M->es;
@@ -609,7 +611,7 @@ hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S) {
   if (fused_on && attention_fwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, a.prob, a.ctx)) {
     // scores, softmax and P.V in one kernel; the probabilities are kept for the backward pass
     Scope sc(M, CAT_ATTN, 4.0 * B * H * S * S * hd);
-    K_TRY(attention_fwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, a.prob, a.ctx, d, M->cs));
+    K_TRY(attention_fwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, keep_prob ? a.prob : nullptr, a.ctx, d, M->cs));
     return HIFT_OK;
   }
   {
@@ -787,7 +789,7 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
       Scope sc(M, CAT_ELEM, 0);
       ST_TRY(ew(M, rope(dt, a.qkv, T, S, H, hd, M->cos_sin, +1, st)));
     }
-    ST_TRY(attention_fwd(M, a, B, S));
+    ST_TRY(attention_fwd(M, a, B, S, l + 1 >= keep_from));
     if (enc) {
       ST_TRY(linear(M, a.ctx, T, *n.wo, n.bo, x, a.na));  // s1 = x + attn
       Scope sc(M, CAT_ELEM, 0);
