@@ -359,32 +359,26 @@ hift_status hift_kernel_optimizer(const hift_opt* opt, int64_t count, int32_t de
                                   float* master, const float* grad, float* state1, float* state2,
                                   void* compute_copy, void* stream);
 
-/* Attention forward, fused (section 3 forward, step h of Algorithm 1, for one layer): bf16 only.
+/* Attention, fused (forward and backward of Algorithm 1 step h for one layer's attention): bf16 only,
+ * head_dim 64 or 128, seq a multiple of 8, buffers 16-byte aligned, else HIFT_EINVAL.
  * qkv: device [batch*seq, 3*heads*head_dim], row = q | k | v of all heads side by side (already rotated
- * where the architecture rotates).  prob: device [batch, heads, seq, seq] bf16, written completely
- * (zeros where masked).  ctx: device [batch*seq, heads*head_dim].  head_dim 64 or 128.  scale is
- * 1/sqrt(head_dim); causal != 0 masks keys after the query. */
+ * where the architecture rotates).  The scale is 1/sqrt(head_dim); causal != 0 masks keys after the query.
+ * Forward: ctx: device [batch*seq, heads*head_dim].  prob: device [batch, heads, seq, seq] bf16 or NULL;
+ * if given it receives the probabilities, completely (zeros where masked).  lse: device fp32
+ * [batch*heads*seq] or NULL; if given it receives log2 of each row's sum of exponentials of the scaled
+ * scores, which is all the backward needs of the softmax.
+ * Backward: ctx and lse as the forward left them; dctx: device [batch*seq, heads*head_dim], gradient of
+ * ctx.  Writes all of dqkv: device [batch*seq, 3*heads*head_dim] (dq, dk, dv); the probabilities and their
+ * gradient are formed again tile by tile and never stored.  dsum: device fp32 [batch*heads*seq], work space
+ * (receives sum_e dctx * ctx per row).  cos_sin: device fp32 [>= seq, head_dim/2, 2] (cos, sin) or NULL;
+ * if given, q and k are taken to have been rotated by the rotary embedding after their projection (pairs
+ * (i, i + head_dim/2), position = row within the sequence) and dq, dk are un-rotated on the way out.
+ * Buffers stay the caller's; none may overlap another. */
 hift_status hift_kernel_attention_fwd(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
-                                      const void* qkv, void* prob, void* ctx, void* stream);
-/* Query-major half of the attention backward, fused (Algorithm 1's backward through one layer's
- * attention; the softmax and product derivatives of the section 3 forward): bf16 only.
- * qkv, prob, ctx: as written by hift_kernel_attention_fwd (ctx = prob . v).  dctx: device
- * [batch*seq, heads*head_dim], gradient of ctx.  Writes dprob: device [batch, heads, seq, seq] bf16,
- * ds = p * (dp - sum_j dp p) / sqrt(head_dim) with dp = dctx . v^T, completely (zeros where masked), and
- * the q columns of dqkv: device [batch*seq, 3*heads*head_dim], dq = ds . k; the k and v columns of dqkv
- * are not touched (dk = ds^T . q and dv = prob^T . dctx are the caller's).  Buffers stay the
- * caller's; none may overlap another.  HIFT_EINVAL for shapes or alignments the kernel does not take. */
-hift_status hift_kernel_attention_bwd_query(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
-                                            const void* qkv, const void* prob, const void* ctx, const void* dctx,
-                                            void* dprob, void* dqkv, void* stream);
-/* The whole attention backward in two fused kernels: the query-major half above, then the key-major half,
- * dv = prob^T . dctx and dk = ds^T . q, into the v and k columns of dqkv (all of dqkv is written; dprob
- * receives ds).  cos_sin: device fp32 [>= seq, head_dim/2, 2] (cos, sin) or NULL; if given, q and k are taken
- * to have been rotated by the rotary embedding after their projection (pairs (i, i + head_dim/2), position =
- * row within the sequence) and dq, dk are un-rotated on the way out. */
+                                      const void* qkv, void* prob, void* ctx, float* lse, void* stream);
 hift_status hift_kernel_attention_bwd(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
-                                      const void* qkv, const void* prob, const void* ctx, const void* dctx,
-                                      void* dprob, void* dqkv, const float* cos_sin, void* stream);
+                                      const void* qkv, const void* ctx, const float* lse, const void* dctx,
+                                      float* dsum, void* dqkv, const float* cos_sin, void* stream);
 /* y = norm(x) * g (+ b) over rows of width d; rms = 1: RMSNorm (b ignored).  stats: fp32 [rows,2]
  * receives mean (0 for RMSNorm) and reciprocal standard deviation. */
 hift_status hift_kernel_norm_fwd(int32_t dtype, int32_t rms, int64_t rows, int32_t d, float eps,

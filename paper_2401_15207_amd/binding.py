@@ -99,8 +99,7 @@ _SIGS = {
     "hift_kernel_packed_workspace_bytes": [_P(_sz)],
     "hift_kernel_gemm_packed_ws": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _sz, _vp],
     "hift_kernel_linear_fused": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _vp],
-    "hift_kernel_attention_fwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
-    "hift_kernel_attention_bwd_query": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
+    "hift_kernel_attention_fwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_attention_bwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_cross_entropy": [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp],
 }
@@ -244,24 +243,17 @@ def kernel_linear_fused(epilogue, M, N, K, A, lda, W, packed_scratch, C, aux, co
                                         _ptr(cos_sin), seq, rot_cols, st))
 
 
-def kernel_attention_fwd(batch, heads, seq, head_dim, causal, qkv, prob, ctx, stream=None):
+def kernel_attention_fwd(batch, heads, seq, head_dim, causal, qkv, prob, ctx, lse=None, stream=None):
     import torch
     st = (stream or torch.cuda.current_stream()).cuda_stream
-    _check(lib.hift_kernel_attention_fwd(batch, heads, seq, head_dim, int(causal), _ptr(qkv), _ptr(prob), _ptr(ctx), st))
+    _check(lib.hift_kernel_attention_fwd(batch, heads, seq, head_dim, int(causal), _ptr(qkv), _ptr(prob), _ptr(ctx), _ptr(lse), st))
 
 
-def kernel_attention_bwd_query(batch, heads, seq, head_dim, causal, qkv, prob, ctx, dctx, dprob, dqkv, stream=None):
+def kernel_attention_bwd(batch, heads, seq, head_dim, causal, qkv, ctx, lse, dctx, dsum, dqkv, cos_sin=None, stream=None):
     import torch
     st = (stream or torch.cuda.current_stream()).cuda_stream
-    _check(lib.hift_kernel_attention_bwd_query(batch, heads, seq, head_dim, int(causal), _ptr(qkv), _ptr(prob), _ptr(ctx),
-                                               _ptr(dctx), _ptr(dprob), _ptr(dqkv), st))
-
-
-def kernel_attention_bwd(batch, heads, seq, head_dim, causal, qkv, prob, ctx, dctx, dprob, dqkv, cos_sin=None, stream=None):
-    import torch
-    st = (stream or torch.cuda.current_stream()).cuda_stream
-    _check(lib.hift_kernel_attention_bwd(batch, heads, seq, head_dim, int(causal), _ptr(qkv), _ptr(prob), _ptr(ctx),
-                                         _ptr(dctx), _ptr(dprob), _ptr(dqkv), _ptr(cos_sin), st))
+    _check(lib.hift_kernel_attention_bwd(batch, heads, seq, head_dim, int(causal), _ptr(qkv), _ptr(ctx), _ptr(lse),
+                                         _ptr(dctx), _ptr(dsum), _ptr(dqkv), _ptr(cos_sin), st))
 
 
 def kernel_cross_entropy(dtype, rows, V, logits, labels, row_loss, loss_out, stream=None):

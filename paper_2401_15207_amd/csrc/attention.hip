@@ -35,6 +35,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 
 constexpr int KTILE = 64;  // keys per LDS tile
@@ -73,20 +74,21 @@ __device__ __forceinline__ void unrotate(f32x16 (&acc)[NB], const float2* __rest
 // reads over the banks.  A tile is filled by loads that write 1 KB of consecutive LDS bytes each, so
 // the swizzle is applied by choosing which piece of its row a lane fetches.
 //
-// BWD = false: the forward kernel.  `scale` is log2(e) / sqrt(HD); writes prob and ctx.
-// BWD = true: the query-major half of the backward pass, on the same tiling with the roles of K and V
-// exchanged.  Reads prob (P), ctx (O) and dctx (dO); `scale` is 1 / sqrt(HD).  Per row i:
-//   D_i = sum_e dO[i,e] O[i,e]   (= sum_j P[i,j] dP[i,j], since O = P V)
+// BWD = false: the forward kernel.  `scale` is log2(e) / sqrt(HD); writes ctx, the probabilities if prob is
+// given, and lse (if given): log2 of each row's sum of exponentials, m + log2(l) in the notation below.
+// BWD = true: the query-major half of the backward pass, on the same tiling.  Reads ctx (O), dctx (dO) and lse;
+// `scale` is 1 / sqrt(HD).  Per row i:
+//   D_i = sum_e dO[i,e] O[i,e]   (= sum_j P[i,j] dP[i,j], since O = P V); written to dsum for the other half
+//   P[i,j] = exp2(S[i,j] scale log2(e) - lse_i) with S = Q K^T formed again tile by tile,
 //   dP[i,j] = dO[i,:] . V[j,:],  dS[i,j] = scale * P[i,j] * (dP[i,j] - D_i),  dQ[i,:] = sum_j dS[i,j] K[j,:]
-// dS goes to dprob in the layout of prob (bf16; exact zeros wherever P is zero), dQ to the q columns
-// of dqkv (row stride ld, like qkv).  dV = P^T dO and dK = dS^T Q are key-major sums and stay with
-// the caller.
+// dQ goes to the q columns of dqkv (row stride ld, like qkv), un-rotated if cos_sin is given.  Neither P nor dS
+// is stored: the key-major kernel below forms its own.
 template <int HD, bool CAUSAL, int NW, bool BWD>
 __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* __restrict__ qkv, int64_t ld, int S, int H, int BH, float scale,
                                                    bf16* __restrict__ prob, bf16* __restrict__ ctx, int64_t ldc,
-                                                   const bf16* __restrict__ dctx, bf16* __restrict__ dprob, bf16* __restrict__ dqkv,
-                                                   const float2* __restrict__ cos_sin) {
-  const float scale_log2e = scale;
+                                                   const bf16* __restrict__ dctx, float* __restrict__ lse, float* __restrict__ dsum,
+                                                   bf16* __restrict__ dqkv, const float2* __restrict__ cos_sin) {
+  const float scale_log2e = BWD ? scale * 1.4426950408889634f : scale;
   constexpr int QB = 32 * NW;       // query rows per workgroup
   constexpr int ROWB = HD * 2;      // bytes per LDS row
   constexpr int PPR = HD / 8;       // 16-byte pieces per row: 16 or 8
@@ -132,7 +134,16 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
   const bool row_ok = row < S;
 
   bf16x8 qf[KS];  // fragments of the wavefront's 32 rows: Q (forward) or dO (backward)
+  bf16x8 qq[BWD ? KS : 1];  // backward: the Q rows as well
   float Drow = 0.f;  // backward: D of this lane's row
+  if (BWD) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 t = {0u, 0u, 0u, 0u};
+      if (row_ok) t = *reinterpret_cast<const u32x4*>(q + (int64_t)row * ld + ks * 16 + fh * 8);
+      qq[ks] = __builtin_bit_cast(bf16x8, t);
+    }
+  }
   {
     const bf16* src = BWD ? dctx + (int64_t)b * S * ldc + (int64_t)h * HD + (int64_t)row * ldc : q + (int64_t)row * ld;
 #pragma unroll
@@ -205,7 +216,7 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
   static_assert(KTILE == 64 && (16 * ROWB) % (PPR == 16 ? 16 * ROWB : 2 * ROWB) == 0, "swz(row + 16 t) = swz(row)");
 
   // raw scores (unscaled) of the tile's two 32-key blocks; MASKED: masked positions become -inf
-  auto scores = [&](auto MASKED_, const unsigned char* Kb, int kt, float (&s)[32]) __attribute__((always_inline)) {
+  auto scores = [&](auto MASKED_, const unsigned char* Kb, int kt, float (&s)[32], const bf16x8* yf) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(MASKED_)::value;
     f32x16 a0, a1;
 #pragma unroll
@@ -222,8 +233,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
 #pragma unroll
       for (int i = 0; i < KS / 2; ++i) {
         const int ks = hf * (KS / 2) + i;
-        a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0[i], qf[ks], a0, 0, 0, 0);
-        a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[i], qf[ks], a1, 0, 0, 0);
+        a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0[i], yf[ks], a0, 0, 0, 0);
+        a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[i], yf[ks], a1, 0, 0, 0);
       }
     }
 #pragma unroll
@@ -257,8 +268,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
       if (CAUSAL && kt * KTILE > q0 + 31) continue;  // wholly above the diagonal for this wavefront
       const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
       float s[32];
-      if (tile_plain(kt)) scores(false_type{}, Kb, kt, s);
-      else scores(true_type{}, Kb, kt, s);
+      if (tile_plain(kt)) scores(false_type{}, Kb, kt, s, qf);
+      else scores(true_type{}, Kb, kt, s, qf);
       float mr = s[0];
   #pragma unroll
       for (int e = 1; e < 32; ++e) mr = fmaxf(mr, s[e]);
@@ -278,6 +289,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
       m = mm;
     }
     const float inv = l > 0.f ? 1.0f / l : 0.f;
+    // log2 of the row's sum of exponentials: what the backward kernels need to form a probability again
+    if (lse && row_ok && fh == 0) lse[(int64_t)bh * S + row] = m + __builtin_amdgcn_logf(l);
     __syncthreads();  // pass 1 has left the buffers
 
     // ---- pass 2: probabilities and P.V ----
@@ -322,8 +335,8 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
       const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
       const unsigned char* Vb = Kb + TILEB;
       float s[32];
-      if (tile_plain(kt)) scores(false_type{}, Kb, kt, s);
-      else scores(true_type{}, Kb, kt, s);
+      if (tile_plain(kt)) scores(false_type{}, Kb, kt, s, qf);
+      else scores(true_type{}, Kb, kt, s, qf);
   #pragma unroll
       for (int i = 0; i < 4; ++i) {
         bf16x8 t;
@@ -373,73 +386,38 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
         }
     }
   } else {
-    // dS leaves (and P arrives) as 16-byte pieces, addressed like the forward kernel's stores
-    const __amdgpu_buffer_rsrc_t rsP = __builtin_amdgcn_make_buffer_rsrc(P, 0, (int)(uint32_t)((int64_t)S * S * 2), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsD =
-        __builtin_amdgcn_make_buffer_rsrc(dprob + (int64_t)bh * S * S, 0, (int)(uint32_t)((int64_t)S * S * 2), 0x00020000);
-    const uint32_t prow = row_ok ? (uint32_t)((int64_t)row * S * 2) + 16u * fh : 0x80000000u;
-    auto piece_off = [&](int kt, int i) {
-      const int key = kt * KTILE + 16 * i + 8 * fh;
-      return (row_ok && key < S) ? prow + (uint32_t)(kt * KTILE + 16 * i) * 2 : 0x80000000u;
-    };
-    auto load_p = [&](int kt, u32x4(&pk)[4]) __attribute__((always_inline)) {
-      if (kt * KTILE + KTILE <= S) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pk[i] = __builtin_amdgcn_raw_buffer_load_b128(rsP, (int)prow, (kt * KTILE + 16 * i) * 2, 0);
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pk[i] = __builtin_amdgcn_raw_buffer_load_b128(rsP, (int)piece_off(kt, i), 0, 0);
-      }
-    };
-    auto store_ds = [&](int kt, const u32x4(&pk)[4]) __attribute__((always_inline)) {
-      if (kt * KTILE + KTILE <= S) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) __builtin_amdgcn_raw_buffer_store_b128(pk[i], rsD, (int)prow, (kt * KTILE + 16 * i) * 2, 0);
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) __builtin_amdgcn_raw_buffer_store_b128(pk[i], rsD, (int)piece_off(kt, i), 0, 0);
-      }
-    };
+    // P is formed again from the scores and the row's stored log-sum; neither P nor dS touches memory
+    const float lrow = row_ok ? lse[(int64_t)bh * S + row] : 0.f;
+    if (row_ok && fh == 0) dsum[(int64_t)bh * S + row] = Drow;  // the key-major kernel needs it per query
     auto above = [&](int kt) { return CAUSAL && kt * KTILE > q0 + 31; };  // wholly above the diagonal for this wavefront
     f32x16 qacc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) qacc[nb][e] = 0.f;
-    u32x4 pn[4];  // probabilities of the next tile, requested one tile ahead
-#pragma unroll
-    for (int i = 0; i < 4; ++i) pn[i] = u32x4{0u, 0u, 0u, 0u};
-    if (!above(0)) load_p(0, pn);
     request(0, true);
     for (int kt = 0; kt < n_tiles; ++kt) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
-      u32x4 pk[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) pk[i] = pn[i];
-      if (kt + 1 < n_tiles) {
-        if (!above(kt + 1)) load_p(kt + 1, pn);
-        request(kt + 1, true);
-      }
-      if (above(kt)) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pk[i] = u32x4{0u, 0u, 0u, 0u};
-        store_ds(kt, pk);
-        continue;
-      }
+      if (kt + 1 < n_tiles) request(kt + 1, true);
+      if (above(kt)) continue;
       const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
       const unsigned char* Vb = Kb + TILEB;
-      float s[32];  // dP of the tile; P is zero at every masked position, so no mask is needed
-      scores(false_type{}, Vb, kt, s);
+      float s[32], dp[32];
+      if (tile_plain(kt)) scores(false_type{}, Kb, kt, s, qq);
+      else scores(true_type{}, Kb, kt, s, qq);
+      scores(false_type{}, Vb, kt, dp, qf);  // dO . V^T; masked positions get P = 0 below
+      u32x4 pk[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const bf16x8 pf = __builtin_bit_cast(bf16x8, pk[i]);
         bf16x8 t;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = static_cast<__bf16>(scale * (float)pf[e] * (s[8 * i + e] - Drow));
+        for (int e = 0; e < 8; ++e) {
+          const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * i + e], scale_log2e, -lrow));  // exp2(-inf) = 0
+          t[e] = static_cast<__bf16>(scale * pr * (dp[8 * i + e] - Drow));
+        }
         pk[i] = __builtin_bit_cast(u32x4, t);
       }
-      store_ds(kt, pk);
       // dQ += dS . K over the tile's 64 keys: four k-steps of 16, K^T by transposing reads
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -460,12 +438,6 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
         for (int nb = 0; nb < NB; ++nb) qacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_[nb], df, qacc[nb], 0, 0, 0);
       }
     }
-    {
-      u32x4 z[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) z[i] = u32x4{0u, 0u, 0u, 0u};
-      for (int kt = n_tiles; kt < all_tiles; ++kt) store_ds(kt, z);
-    }
     if (row_ok) {
       bf16* dq = dqkv + (int64_t)b * S * ld + (int64_t)h * HD + (int64_t)row * ld;
       if (cos_sin) unrotate<NB>(qacc, cos_sin + (int64_t)row * (HD / 2), fh);  // q was rotated after its projection
@@ -483,97 +455,92 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
 }
 
 // Key-major half of the attention backward: dV = P^T dO and dK = dS^T Q, both sums over the queries.  A workgroup
-// owns 128 keys of one (batch, head), a wavefront 32 of them from start to end; queries pass through LDS in tiles
-// of 64: Q and dO rows (HD wide) and the matching 64 x 128 pieces of P and dS, all by direct-to-LDS loads into
-// swizzled rows.  Every MFMA operand is a transpose of what lies in LDS (the contraction index is the row index of
-// all four tiles), read with ds_read_b64_tr_b16 exactly as V is in the forward kernel.  Single-buffered; two
-// workgroups share a compute unit and cover each other's loads, a long and a short one under the causal mask.
+// owns 128 keys of one (batch, head), a wavefront 32 of them from start to end with their K and V rows in
+// registers; queries pass through LDS in tiles of 64 (Q and dO rows, double-buffered direct-to-LDS loads).  Per
+// tile a wavefront forms S^T = K Q^T and dP^T = V dO^T (Y = its key rows, X = the tile's rows in the pi order of
+// the forward kernel), from them P^T = exp2(S^T c - lse[query]) and dS^T = scale P^T (dP^T - D[query]); in
+// that order of rows the 16 values a lane holds per 32 queries are, as they lie in registers, the operand
+// fragments of the two sums, whose other operands (dO^T, Q^T) come from the same tiles by transposing LDS
+// reads.  Nothing of size S x S is read or written.  One workgroup per compute unit (the accumulators of four
+// products and 64 K / V registers); workgroups are issued longest first under the causal mask.
+// lse: log2 of each query's sum of exponentials (forward kernel); dsum: D = dO . O per query (query-major kernel).
 // cos_sin, if given, un-rotates dK (k was rotated after its projection).
 template <int HD, bool CAUSAL>
-__global__ void __launch_bounds__(256, 2) attn_bwd_kv_k(const bf16* __restrict__ qkv, int64_t ld, int S, int H, int BH,
-                                                         const bf16* __restrict__ prob, const bf16* __restrict__ dprob,
+__global__ void __launch_bounds__(256, 1) attn_bwd_kv_k(const bf16* __restrict__ qkv, int64_t ld, int S, int H, int BH, float scale,
+                                                         const float* __restrict__ lse, const float* __restrict__ dsum,
                                                          const bf16* __restrict__ dctx, int64_t ldc, bf16* __restrict__ dqkv,
                                                          const float2* __restrict__ cos_sin) {
   constexpr int KB = 128;           // keys per workgroup
   constexpr int QT = 64;            // queries per tile
-  constexpr int ROWB = HD * 2, PPR = HD / 8, NB = HD / 32;
+  constexpr int ROWB = HD * 2, PPR = HD / 8, NB = HD / 32, KS = HD / 16;
   constexpr int TQ = QT * ROWB;     // bytes of the Q (or dO) tile
-  constexpr int TP = QT * KB * 2;   // bytes of the P (or dS) tile: rows of 256 bytes = 16 pieces
-  constexpr int IQ = QT * PPR / 64 / 4, IP = QT * 16 / 64 / 4;  // load instructions per wavefront and tile
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * TQ + 2 * TP];  // Q | dO | P | dS
+  constexpr int IQ = QT * PPR / 64 / 4;  // load instructions per wavefront, tile and operand
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * TQ];  // [buffer][Q | dO]
   auto swq = [](int r) { return PPR == 16 ? (r & 15) : ((r >> 1) & 7); };
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
-  // key blocks late in the sequence see few queries under the causal mask: the first half of the grid takes the
-  // early (long) blocks, the second half their late counterparts
+  // key blocks early in the sequence see the most queries under the causal mask and go first
   const int nkb = (S + KB - 1) / KB;
-  int bh, kb;
-  if (CAUSAL) {
-    const int n_long = (nkb + 1) / 2, n_short = nkb - n_long;
-    const int L = (int)blockIdx.x, first = n_long * BH;
-    if (L < first) {
-      bh = L / n_long;
-      kb = L % n_long;
-    } else {
-      bh = (L - first) / n_short;
-      kb = nkb - 1 - (L - first) % n_short;
-    }
-  } else {
-    bh = (int)blockIdx.x / nkb;
-    kb = (int)blockIdx.x % nkb;
-  }
+  const int kb = (int)blockIdx.x / BH, bh = (int)blockIdx.x % BH;
   const int b = bh / H, h = bh % H;
   const int64_t d = (int64_t)H * HD;
   const bf16* q = qkv + (int64_t)b * S * ld + (int64_t)h * HD;
   const bf16* dO = dctx + (int64_t)b * S * ldc + (int64_t)h * HD;
-  const bf16* P = prob + (int64_t)bh * S * S;
-  const bf16* dS = dprob + (int64_t)bh * S * S;
   const int j0 = kb * KB + wave * 32;  // this wavefront's first key
   const int row = j0 + fr;
   const bool row_ok = row < S;
+  const float scale_log2e = scale * 1.4426950408889634f;
+  (void)nkb;
 
-  const uint64_t qa = reinterpret_cast<uint64_t>(q), oa = reinterpret_cast<uint64_t>(dO), pa = reinterpret_cast<uint64_t>(P),
-                 sa = reinterpret_cast<uint64_t>(dS);
-  const uint32_t recq = (uint32_t)((((int64_t)S - 1) * ld + HD) * 2), reco = (uint32_t)((((int64_t)S - 1) * ldc + HD) * 2),
-                 recp = (uint32_t)((int64_t)S * S * 2);
+  bf16x8 kf[KS], vf[KS];  // this lane's key row: fragments of K and V
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    u32x4 tk = {0u, 0u, 0u, 0u}, tv = tk;
+    if (row_ok) {
+      tk = *reinterpret_cast<const u32x4*>(q + d + (int64_t)row * ld + ks * 16 + fh * 8);
+      tv = *reinterpret_cast<const u32x4*>(q + 2 * d + (int64_t)row * ld + ks * 16 + fh * 8);
+    }
+    kf[ks] = __builtin_bit_cast(bf16x8, tk);
+    vf[ks] = __builtin_bit_cast(bf16x8, tv);
+  }
+
+  const uint64_t qa = reinterpret_cast<uint64_t>(q), oa = reinterpret_cast<uint64_t>(dO);
+  const uint32_t recq = (uint32_t)((((int64_t)S - 1) * ld + HD) * 2), reco = (uint32_t)((((int64_t)S - 1) * ldc + HD) * 2);
   const u32x4 rsQ = {(uint32_t)qa, (uint32_t)(qa >> 32) & 0xFFFFu, recq, 0x00020000u};
   const u32x4 rsO = {(uint32_t)oa, (uint32_t)(oa >> 32) & 0xFFFFu, reco, 0x00020000u};
-  const u32x4 rsP = {(uint32_t)pa, (uint32_t)(pa >> 32) & 0xFFFFu, recp, 0x00020000u};
-  const u32x4 rsS = {(uint32_t)sa, (uint32_t)(sa >> 32) & 0xFFFFu, recp, 0x00020000u};
-  uint32_t voq[IQ], voo[IQ], vop[IP];
+  // per-query scalars of the tile, read straight from memory: reads past the sequence end return zeros
+  const __amdgpu_buffer_rsrc_t rsL = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lse + (int64_t)bh * S), 0, S * 4, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsD = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(dsum + (int64_t)bh * S), 0, S * 4, 0x00020000);
+  uint32_t voq[IQ], voo[IQ];
 #pragma unroll
   for (int jj = 0; jj < IQ; ++jj) {
     const int pc = (wave * IQ + jj) * 64 + lane, r = pc / PPR, c = (pc % PPR) ^ swq(r);
     voq[jj] = (uint32_t)((r * ld + c * 8) * 2);
     voo[jj] = (uint32_t)((r * ldc + c * 8) * 2);
   }
-#pragma unroll
-  for (int jj = 0; jj < IP; ++jj) {
-    const int pc = (wave * IP + jj) * 64 + lane, r = pc / 16, c = (pc % 16) ^ (r & 15);
-    // pieces that start past the end of a probability row are not fetched (offset past the buffer: zeros);
-    // a piece never straddles the end, S being a multiple of 8
-    vop[jj] = kb * KB + c * 8 < S ? (uint32_t)(((int64_t)r * S + kb * KB + c * 8) * 2) : 0x80000000u;
-  }
   const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(lds);
   auto request = [&](int it) __attribute__((always_inline)) {
-    const uint32_t sq = (uint32_t)((int64_t)it * QT * ld * 2), so = (uint32_t)((int64_t)it * QT * ldc * 2),
-                   sp = (uint32_t)((int64_t)it * QT * S * 2);
+    const uint32_t sq = (uint32_t)((int64_t)it * QT * ld * 2), so = (uint32_t)((int64_t)it * QT * ldc * 2);
+    const uint32_t dst = lds0 + (uint32_t)(it & 1) * (2 * TQ) + (uint32_t)wave * (IQ * 1024);
 #pragma unroll
-    for (int jj = 0; jj < IQ; ++jj) dma_b128(rsQ, lds0 + (wave * IQ + jj) * 1024, voq[jj], sq);
+    for (int jj = 0; jj < IQ; ++jj) dma_b128(rsQ, dst + jj * 1024, voq[jj], sq);
 #pragma unroll
-    for (int jj = 0; jj < IQ; ++jj) dma_b128(rsO, lds0 + TQ + (wave * IQ + jj) * 1024, voo[jj], so);
-#pragma unroll
-    for (int jj = 0; jj < IP; ++jj) dma_b128(rsP, lds0 + 2 * TQ + (wave * IP + jj) * 1024, vop[jj], sp);
-#pragma unroll
-    for (int jj = 0; jj < IP; ++jj) dma_b128(rsS, lds0 + 2 * TQ + TP + (wave * IP + jj) * 1024, vop[jj], sp);
+    for (int jj = 0; jj < IQ; ++jj) dma_b128(rsO, dst + TQ + jj * 1024, voo[jj], so);
   };
 
-  // transposing reads (k-step t = 16 queries, rows 16 t + 8 fh + sl/4 (+4)): from the Q / dO tile the fragment of
-  // column block nb; from the P / dS tile the fragment of this wavefront's 32 keys
+  // fragment of tile rows in pi order (block blk of 32 queries, k-step ks) and transposing reads (k-step t = 16
+  // queries, rows 16 t + 8 fh + sl/4 (+4), column block nb), as in the forward kernel
+  int faddr[2][KS];
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk) {
+    const int r = blk * 32 + pi_row(fr);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) faddr[blk][ks] = r * ROWB + (((2 * ks + fh) ^ swq(r)) * 16);
+  }
   const int sl = lane & 15;
-  int xaddr[NB][2], yaddr[2];
+  int xaddr[NB][2];
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh) {
     const int krow = 8 * fh + (sl >> 2) + 4 * hh;
@@ -582,8 +549,6 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_kv_k(const bf16* __restrict__
       const int col = nb * 32 + 16 * ((lane >> 4) & 1) + 4 * (sl & 3);
       xaddr[nb][hh] = krow * ROWB + (((col >> 3) ^ swq(krow)) * 16) + (col & 7) * 2;
     }
-    const int colp = wave * 32 + 16 * ((lane >> 4) & 1) + 4 * (sl & 3);
-    yaddr[hh] = krow * (KB * 2) + (((colp >> 3) ^ (krow & 15)) * 16) + (colp & 7) * 2;
   }
   auto tr_frag = [&](const unsigned char* base, int a0, int a1) __attribute__((always_inline)) {
     const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(base + a0));
@@ -601,30 +566,58 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_kv_k(const bf16* __restrict__
 
   const int all_tiles = (S + QT - 1) / QT;
   const int it0 = CAUSAL ? kb * KB / QT : 0;  // earlier tiles hold no query at or after this block's first key
+  request(it0);
   for (int it = it0; it < all_tiles; ++it) {
-    __syncthreads();  // the previous tile has been read by everyone
-    request(it);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (CAUSAL && it * QT + QT - 1 < j0) continue;  // every query of the tile precedes this wavefront's keys: P = dS = 0
-    const unsigned char* Qb = lds;
-    const unsigned char* Ob = lds + TQ;
-    const unsigned char* Pb = lds + 2 * TQ;
-    const unsigned char* Sb = lds + 2 * TQ + TP;
+    __syncthreads();  // tile `it` has landed for everyone; nobody reads the other buffer any more
+    if (it + 1 < all_tiles) request(it + 1);
+    if (CAUSAL && it * QT + QT - 1 < j0) continue;  // every query of the tile precedes this wavefront's keys
+    const unsigned char* Qb = lds + (it & 1) * (2 * TQ);
+    const unsigned char* Ob = Qb + TQ;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const bf16x8 yp = tr_frag(Pb + t * 16 * (KB * 2), yaddr[0], yaddr[1]);
-      const bf16x8 ys = tr_frag(Sb + t * 16 * (KB * 2), yaddr[0], yaddr[1]);
-      bf16x8 xo[NB], xq[NB];
+    for (int blk = 0; blk < 2; ++blk) {
+      const int qb0 = it * QT + blk * 32;  // first query of the block
+      // element e of a lane: query qb0 + 16 (e / 8) + 8 fh + e % 8
+      f32x4 lq[4], dq4[4];
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        xo[nb] = tr_frag(Ob + t * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
-        xq[nb] = tr_frag(Qb + t * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
+      for (int c = 0; c < 4; ++c) {
+        const int off = (qb0 + 16 * (c >> 1) + 8 * fh + 4 * (c & 1)) * 4;
+        lq[c] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsL, off, 0, 0));
+        dq4[c] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsD, off, 0, 0));
+      }
+      f32x16 st, dpt;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) st[e] = dpt[e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 xq = *reinterpret_cast<const bf16x8*>(Qb + faddr[blk][ks]);
+        const bf16x8 xo = *reinterpret_cast<const bf16x8*>(Ob + faddr[blk][ks]);
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xq, kf[ks], st, 0, 0, 0);
+        dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo, vf[ks], dpt, 0, 0, 0);
+      }
+      bf16x8 pf[2], sf[2];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int qi = qb0 + 16 * (e / 8) + 8 * fh + e % 8;
+        const bool ok = qi < S && (!CAUSAL || qi >= row);
+        const float pr = ok ? __builtin_amdgcn_exp2f(__builtin_fmaf(st[e], scale_log2e, -lq[e / 4][e % 4])) : 0.f;
+        pf[e / 8][e % 8] = static_cast<__bf16>(pr);
+        sf[e / 8][e % 8] = static_cast<__bf16>(scale * pr * (dpt[e] - dq4[e / 4][e % 4]));
       }
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        vacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo[nb], yp, vacc[nb], 0, 0, 0);
-        kacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xq[nb], ys, kacc[nb], 0, 0, 0);
+      for (int t2 = 0; t2 < 2; ++t2) {
+        const int t = 2 * blk + t2;
+        bf16x8 xo[NB], xq[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          xo[nb] = tr_frag(Ob + t * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
+          xq[nb] = tr_frag(Qb + t * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          vacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo[nb], pf[t2], vacc[nb], 0, 0, 0);
+          kacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xq[nb], sf[t2], kacc[nb], 0, 0, 0);
+        }
       }
     }
   }
@@ -662,7 +655,7 @@ bool attention_fwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc,
 namespace {
 template <bool BWD_>
 hipError_t attn_launch(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, void* prob, void* ctx, int64_t ldc,
-                       const void* dctx, void* dprob, void* dqkv, const float* cos_sin, hipStream_t st) {
+                       const void* dctx, float* lse, float* dsum, void* dqkv, const float* cos_sin, hipStream_t st) {
   if (B == 0 || H == 0 || S == 0) return hipSuccess;
   const float2* cs = reinterpret_cast<const float2*>(cos_sin);
   const float sc = (1.0f / sqrtf((float)hd)) * (BWD_ ? 1.0f : 1.4426950408889634f);
@@ -676,12 +669,11 @@ hipError_t attn_launch(int B, int H, int S, int hd, bool causal, const void* qkv
   bf16* p = reinterpret_cast<bf16*>(prob);
   bf16* o = reinterpret_cast<bf16*>(ctx);
   const bf16* dO = reinterpret_cast<const bf16*>(dctx);
-  bf16* dS = reinterpret_cast<bf16*>(dprob);
   bf16* dq = reinterpret_cast<bf16*>(dqkv);
-#define ATTN_LAUNCH(HD_, C_)                                                                                 \
-  do {                                                                                                       \
-    if (big) attn_k<HD_, C_, 4, BWD_><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sc, p, o, ldc, dO, dS, dq, cs);  \
-    else attn_k<HD_, C_, 2, BWD_><<<grid, 128, 0, st>>>(x, ld, S, H, B * H, sc, p, o, ldc, dO, dS, dq, cs);      \
+#define ATTN_LAUNCH(HD_, C_)                                                                                       \
+  do {                                                                                                             \
+    if (big) attn_k<HD_, C_, 4, BWD_><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sc, p, o, ldc, dO, lse, dsum, dq, cs); \
+    else attn_k<HD_, C_, 2, BWD_><<<grid, 128, 0, st>>>(x, ld, S, H, B * H, sc, p, o, ldc, dO, lse, dsum, dq, cs);     \
   } while (0)
   if (hd == 128) {
     if (causal) ATTN_LAUNCH(128, true); else ATTN_LAUNCH(128, false);
@@ -696,42 +688,37 @@ hipError_t attn_launch(int B, int H, int S, int hd, bool causal, const void* qkv
 }  // namespace
 
 hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, void* prob, void* ctx,
-                               int64_t ldc, hipStream_t st) {
-  return attn_launch<false>(B, H, S, hd, causal, qkv, ld, prob, ctx, ldc, nullptr, nullptr, nullptr, nullptr, st);
+                               int64_t ldc, float* lse, hipStream_t st) {
+  return attn_launch<false>(B, H, S, hd, causal, qkv, ld, prob, ctx, ldc, nullptr, lse, nullptr, nullptr, nullptr, st);
 }
 
-bool attention_bwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* prob, const void* ctx,
-                                 const void* dctx, const void* dprob, const void* dqkv) {
-  return attention_fwd_fused_applies(dt, S, hd, ld, ldc, qkv, prob, ctx) && ldc % 8 == 0 && al16(ctx) && al16(dctx) && al16(dprob) &&
+bool attention_bwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* ctx, const void* dctx,
+                                 const void* dqkv) {
+  return attention_fwd_fused_applies(dt, S, hd, ld, ldc, qkv, nullptr, ctx) && ldc % 8 == 0 && al16(ctx) && al16(dctx) &&
          (reinterpret_cast<uintptr_t>(dqkv) & 7) == 0;
 }
 
-hipError_t attention_bwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* prob,
-                               const void* ctx, const void* dctx, int64_t ldc, void* dprob, void* dqkv, const float* cos_sin,
+hipError_t attention_bwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* ctx,
+                               const float* lse, const void* dctx, int64_t ldc, float* dsum, void* dqkv, const float* cos_sin,
                                hipStream_t st) {
-  return attn_launch<true>(B, H, S, hd, causal, qkv, ld, const_cast<void*>(prob), const_cast<void*>(ctx), ldc, dctx, dprob, dqkv,
-                           cos_sin, st);
-}
-
-hipError_t attention_bwd_kv_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* prob,
-                                  const void* dprob, const void* dctx, int64_t ldc, void* dqkv, const float* cos_sin,
-                                  hipStream_t st) {
-  if (B == 0 || H == 0 || S == 0) return hipSuccess;
+  if (!lse || !dsum) return hipErrorInvalidValue;
+  hipError_t e = attn_launch<true>(B, H, S, hd, causal, qkv, ld, nullptr, const_cast<void*>(ctx), ldc, dctx, const_cast<float*>(lse),
+                                   dsum, dqkv, cos_sin, st);
+  if (e != hipSuccess || B == 0 || H == 0 || S == 0) return e;
   const int64_t nblk = (int64_t)((S + 127) / 128) * B * H;
   if (nblk > 0x7FFFFFFF) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nblk);
   const bf16* x = reinterpret_cast<const bf16*>(qkv);
-  const bf16* p = reinterpret_cast<const bf16*>(prob);
-  const bf16* ds = reinterpret_cast<const bf16*>(dprob);
   const bf16* dO = reinterpret_cast<const bf16*>(dctx);
   bf16* dq = reinterpret_cast<bf16*>(dqkv);
   const float2* cs = reinterpret_cast<const float2*>(cos_sin);
+  const float sc = 1.0f / sqrtf((float)hd);
   if (hd == 128) {
-    if (causal) attn_bwd_kv_k<128, true><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, p, ds, dO, ldc, dq, cs);
-    else attn_bwd_kv_k<128, false><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, p, ds, dO, ldc, dq, cs);
+    if (causal) attn_bwd_kv_k<128, true><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sc, lse, dsum, dO, ldc, dq, cs);
+    else attn_bwd_kv_k<128, false><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sc, lse, dsum, dO, ldc, dq, cs);
   } else if (hd == 64) {
-    if (causal) attn_bwd_kv_k<64, true><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, p, ds, dO, ldc, dq, cs);
-    else attn_bwd_kv_k<64, false><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, p, ds, dO, ldc, dq, cs);
+    if (causal) attn_bwd_kv_k<64, true><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sc, lse, dsum, dO, ldc, dq, cs);
+    else attn_bwd_kv_k<64, false><<<grid, 256, 0, st>>>(x, ld, S, H, B * H, sc, lse, dsum, dO, ldc, dq, cs);
   } else {
     return hipErrorInvalidValue;
   }

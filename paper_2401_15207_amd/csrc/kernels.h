@@ -94,27 +94,22 @@ hipError_t gelu_bwd(int dt, int64_t n, const void* dact, const void* pre, void* 
 // gu [T, 2f] = gate | up  ->  act [T, f]
 hipError_t swiglu_fwd(int dt, int64_t T, int f, const void* gu, void* act, hipStream_t st);
 hipError_t swiglu_bwd(int dt, int64_t T, int f, const void* dact, const void* gu, void* dgu, hipStream_t st);
-// Fused attention forward (attention.hip): qkv [B*S, ld] holds q | k | v of every head side by side
-// (head h at columns h*hd, d + h*hd, 2d + h*hd, d = H*hd); writes the probabilities [B, H, S, S] and the
-// context [B*S, ldc] (head h at columns h*hd).  bf16 only, hd 64 or 128.
+// Fused attention (attention.hip): qkv [B*S, ld] holds q | k | v of every head side by side (head h at columns
+// h*hd, d + h*hd, 2d + h*hd, d = H*hd).  bf16 only, hd 64 or 128.
+// Forward: writes the context [B*S, ldc] (head h at columns h*hd); the probabilities [B, H, S, S] if prob is
+// given; lse [B*H*S] fp32 if given: log2 of each row's sum of exponentials, what the backward needs.
 bool attention_fwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* prob, const void* ctx);
 hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, void* prob, void* ctx,
-                               int64_t ldc, hipStream_t st);
-// Fused query-major half of the attention backward (attention.hip): from the probabilities, the context
-// and dctx [B*S, ldc] writes ds = scale * p * (dp - sum_j dp p) into dprob (layout of prob) and
-// dq = ds . k into the q columns of dqkv [B*S, ld].  dv and dk are left to the caller.
-bool attention_bwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* prob, const void* ctx,
-                                 const void* dctx, const void* dprob, const void* dqkv);
-hipError_t attention_bwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* prob,
-                               const void* ctx, const void* dctx, int64_t ldc, void* dprob, void* dqkv, const float* cos_sin,
+                               int64_t ldc, float* lse, hipStream_t st);
+// Backward in two kernels, query-major (dq; leaves D = dO . O per query in dsum [B*H*S] fp32) and key-major
+// (dk, dv); both form the probabilities again from q, k and lse, so nothing of size S x S is read or written.
+// All of dqkv [B*S, ld] is written.  cos_sin: fp32 [>= S, hd/2] pairs (cos, sin) or null; if given, dq and dk
+// are un-rotated on the way out (the adjoint of the rotary embedding applied to q and k after their projection).
+bool attention_bwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* ctx, const void* dctx,
+                                 const void* dqkv);
+hipError_t attention_bwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* ctx,
+                               const float* lse, const void* dctx, int64_t ldc, float* dsum, void* dqkv, const float* cos_sin,
                                hipStream_t st);
-// Fused key-major half (same conditions as attention_bwd_fused_applies): dv = prob^T . dctx into the v columns of
-// dqkv and dk = dprob^T . q into its k columns (dprob = ds as written by attention_bwd_fused).
-// cos_sin (both halves): fp32 [>= S, hd/2] pairs (cos, sin) or null; if given, dq and dk are un-rotated on the
-// way out (the adjoint of the rotary embedding applied to q and k after their projection).
-hipError_t attention_bwd_kv_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* prob,
-                                  const void* dprob, const void* dctx, int64_t ldc, void* dqkv, const float* cos_sin,
-                                  hipStream_t st);
 // in place over scores [nbh, S, S]: p = softmax(scale * s + causal mask)
 hipError_t softmax_fwd(int dt, int64_t nbh, int S, float scale, bool causal, void* s, hipStream_t st);
 // in place over dp: ds = scale * p * (dp - sum_j dp p)

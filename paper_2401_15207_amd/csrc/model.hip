@@ -212,6 +212,7 @@ struct Bump {
 struct LayerAct {
   void *na, *qkv, *prob, *ctx, *xmid, *nb, *fpre, *act;  // na: h1 | s1, nb: h2 | s2
   float *st1, *st2;
+  float* lse;  // fused attention: log2 of each row's sum of exponentials, [B, H, S]
 };
 
 struct Prof {
@@ -260,7 +261,7 @@ struct hift_model {
   std::vector<LayerAct> la;
   void *e0 = nullptr, *xf = nullptr, *xcls = nullptr, *logits = nullptr;
   float *st_e = nullptr, *st_f = nullptr, *row_loss = nullptr, *loss_dev = nullptr, *part = nullptr;
-  void *D[3] = {nullptr, nullptr, nullptr}, *dqkv = nullptr, *dprob = nullptr, *dact = nullptr, *dffn = nullptr,
+  void *D[3] = {nullptr, nullptr, nullptr}, *dqkv = nullptr, *dprob = nullptr, *attn_dsum = nullptr, *dact = nullptr, *dffn = nullptr,
        *dcls = nullptr;
   // streams and events
   hipStream_t cs, hs, ds;
@@ -347,6 +348,7 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes, s
     a.act = b.take(T * f * es);
     a.st1 = (float*)b.take(T * 2 * 4);
     a.st2 = (float*)b.take(T * 2 * 4);
+    a.lse = (float*)b.take(B * H * S * 4);
   }
   if (enc) {
     M.e0 = b.take(T * d * es);
@@ -367,6 +369,7 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes, s
   for (auto& x : M.D) x = b.take(T * d * es);
   M.dqkv = b.take(T * 3 * d * es);
   M.dprob = b.take(B * H * S * S * es);
+  M.attn_dsum = b.take(B * H * S * 4);
   M.dact = b.take(T * f * es);
   M.dffn = b.take(T * fw * es);
   M.gemm_ws = M.wpk_bytes ? b.take(PACKED_WS_BYTES) : nullptr;  // shared tiles of the packed-operand contraction
@@ -599,19 +602,26 @@ hift_status bias_grad(hift_model* M, const void* dy, int64_t rows, const Tensor&
   return HIFT_OK;
 }
 
-// keep_prob = false: no backward pass will come through this layer; the fused kernel then does not store the
-// probabilities (the unfused path needs the buffer as its work space either way)
-hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S, bool keep_prob) {
+// Whether a layer's attention runs on the fused kernels, forward and backward alike (the backward needs what
+// only the fused forward leaves, and the other way round).  HIFT_ATTN_FUSED=0 in the environment: never.
+bool attention_is_fused(const hift_model* M, const LayerAct& a, int S) {
+  static const bool fused_on = [] { const char* e = getenv("HIFT_ATTN_FUSED"); return !(e && e[0] == '0'); }();
+  const int64_t d = M->cfg.d_model, hd = d / M->cfg.n_heads;
+  return fused_on && attention_fwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, nullptr, a.ctx) &&
+         attention_bwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, a.ctx, M->D[2], M->dqkv);
+}
+
+// keep = false: no backward pass will come through this layer; the fused kernel then stores nothing but the context
+hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S, bool keep) {
   const hift_config& c = M->cfg;
   const int64_t d = c.d_model, H = c.n_heads, hd = d / H;
   const size_t es = M->es;
   unsigned char* qkv = (unsigned char*)a.qkv;
   const bool causal = c.arch != HIFT_ARCH_POSTLN_ENCODER;
-  static const bool fused_on = [] { const char* e = getenv("HIFT_ATTN_FUSED"); return !(e && e[0] == '0'); }();
-  if (fused_on && attention_fwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, a.prob, a.ctx)) {
-    // scores, softmax and P.V in one kernel; the probabilities are kept for the backward pass
+  if (attention_is_fused(M, a, S)) {
+    // scores, softmax and P.V in one kernel; of the softmax only each row's log-sum is kept for the backward pass
     Scope sc(M, CAT_ATTN, 4.0 * B * H * S * S * hd);
-    K_TRY(attention_fwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, keep_prob ? a.prob : nullptr, a.ctx, d, M->cs));
+    K_TRY(attention_fwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, nullptr, a.ctx, d, keep ? a.lse : nullptr, M->cs));
     return HIFT_OK;
   }
   {
@@ -662,20 +672,16 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
   const bool causal = c.arch != HIFT_ARCH_POSTLN_ENCODER;
   auto batch = [&](Gemm& g) { g.dtype = M->dt; g.nb = B; g.nh = (int)H; };
   const int64_t sP1 = H * (int64_t)S * S, sP2 = (int64_t)S * S, sQ1 = (int64_t)S * 3 * d, sX1 = (int64_t)S * d;
-  static const bool fused_on = [] { const char* e = getenv("HIFT_ATTN_FUSED"); return !(e && e[0] == '0'); }();
-  const bool fused = fused_on && attention_bwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, a.prob, a.ctx, dctx, M->dprob, M->dqkv);
   *unrotated = false;
-  if (fused) {
-    // dp, the softmax backward and dq in one kernel (dp never reaches memory), then dv and dk in another; both undo
-    // the rotary embedding on the way out
+  if (attention_is_fused(M, a, S)) {
+    // two kernels, query-major (dq) and key-major (dk, dv); both form the probabilities again from q, k and the
+    // stored log-sums and undo the rotary embedding on the way out
+    if (dctx != M->D[2]) return fail(HIFT_ESTATE, "attention backward expects its input in the third gradient buffer");
     const float* cs = c.arch == HIFT_ARCH_RMS_ROPE_DECODER ? M->cos_sin : nullptr;
     *unrotated = cs != nullptr;
-    {
-      Scope sc(M, CAT_ATTN, 2 * fl);
-      K_TRY(attention_bwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, a.prob, a.ctx, dctx, d, M->dprob, M->dqkv, cs, M->cs));
-    }
-    Scope sc(M, CAT_ATTN, 2 * fl);
-    K_TRY(attention_bwd_kv_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, a.prob, M->dprob, dctx, d, M->dqkv, cs, M->cs));
+    Scope sc(M, CAT_ATTN, 7 * fl);  // S and dP twice, dQ, dV, dK
+    K_TRY(attention_bwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, a.ctx, a.lse, dctx, d, (float*)M->attn_dsum, M->dqkv, cs,
+                              M->cs));
     return HIFT_OK;
   }
   {
@@ -1805,38 +1811,25 @@ hift_status hift_kernel_optimizer(const hift_opt* opt, int64_t count, int32_t de
 }
 
 hift_status hift_kernel_attention_fwd(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
-                                      const void* qkv, void* prob, void* ctx, void* stream) {
+                                      const void* qkv, void* prob, void* ctx, float* lse, void* stream) {
   const int64_t d = (int64_t)heads * head_dim;
-  if (batch < 0 || heads < 1 || seq < 0 || !qkv || !prob || !ctx) return fail(HIFT_EINVAL, "bad argument");
+  if (batch < 0 || heads < 1 || seq < 0 || !qkv || !ctx) return fail(HIFT_EINVAL, "bad argument");
   if (!attention_fwd_fused_applies(DT_BF16, seq, head_dim, 3 * d, d, qkv, prob, ctx))
     return fail(HIFT_EINVAL, "the fused kernel takes bf16, head widths 64 and 128 and 16-byte aligned buffers");
-  HIP_TRY(attention_fwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, ctx, d, (hipStream_t)stream));
-  return HIFT_OK;
-}
-
-hift_status hift_kernel_attention_bwd_query(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
-                                            const void* qkv, const void* prob, const void* ctx, const void* dctx, void* dprob,
-                                            void* dqkv, void* stream) {
-  const int64_t d = (int64_t)heads * head_dim;
-  if (batch < 0 || heads < 1 || seq < 0 || !qkv || !prob || !ctx || !dctx || !dprob || !dqkv) return fail(HIFT_EINVAL, "bad argument");
-  if (!attention_bwd_fused_applies(DT_BF16, seq, head_dim, 3 * d, d, qkv, prob, ctx, dctx, dprob, dqkv))
-    return fail(HIFT_EINVAL, "the fused kernel takes bf16, head widths 64 and 128 and 16-byte aligned buffers");
-  HIP_TRY(attention_bwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, ctx, dctx, d, dprob, dqkv, nullptr,
-                              (hipStream_t)stream));
+  HIP_TRY(attention_fwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, ctx, d, lse, (hipStream_t)stream));
   return HIFT_OK;
 }
 
 hift_status hift_kernel_attention_bwd(int32_t batch, int32_t heads, int32_t seq, int32_t head_dim, int32_t causal,
-                                      const void* qkv, const void* prob, const void* ctx, const void* dctx, void* dprob,
+                                      const void* qkv, const void* ctx, const float* lse, const void* dctx, float* dsum,
                                       void* dqkv, const float* cos_sin, void* stream) {
   const int64_t d = (int64_t)heads * head_dim;
-  if (batch < 0 || heads < 1 || seq < 0 || !qkv || !prob || !ctx || !dctx || !dprob || !dqkv) return fail(HIFT_EINVAL, "bad argument");
-  if (!attention_bwd_fused_applies(DT_BF16, seq, head_dim, 3 * d, d, qkv, prob, ctx, dctx, dprob, dqkv) ||
+  if (batch < 0 || heads < 1 || seq < 0 || !qkv || !ctx || !lse || !dctx || !dsum || !dqkv) return fail(HIFT_EINVAL, "bad argument");
+  if (!attention_bwd_fused_applies(DT_BF16, seq, head_dim, 3 * d, d, qkv, ctx, dctx, dqkv) ||
       (reinterpret_cast<uintptr_t>(cos_sin) & 7) != 0)
     return fail(HIFT_EINVAL, "the fused kernels take bf16, head widths 64 and 128 and 16-byte aligned buffers");
-  hipStream_t st = (hipStream_t)stream;
-  HIP_TRY(attention_bwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, ctx, dctx, d, dprob, dqkv, cos_sin, st));
-  HIP_TRY(attention_bwd_kv_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, prob, dprob, dctx, d, dqkv, cos_sin, st));
+  HIP_TRY(attention_bwd_fused(batch, heads, seq, head_dim, causal != 0, qkv, 3 * d, ctx, lse, dctx, d, dsum, dqkv, cos_sin,
+                              (hipStream_t)stream));
   return HIFT_OK;
 }
 
