@@ -475,7 +475,8 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_kv_k(const bf16* __restrict__
   constexpr int ROWB = HD * 2, PPR = HD / 8, NB = HD / 32, KS = HD / 16;
   constexpr int TQ = QT * ROWB;     // bytes of the Q (or dO) tile
   constexpr int IQ = QT * PPR / 64 / 4;  // load instructions per wavefront, tile and operand
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * TQ];  // [buffer][Q | dO]
+  constexpr int BUF = 2 * TQ + 2048;  // Q | dO | lse (1 KB, 256 bytes used) | D (same)
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * BUF];
   auto swq = [](int r) { return PPR == 16 ? (r & 15) : ((r >> 1) & 7); };
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -510,9 +511,12 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_kv_k(const bf16* __restrict__
   const uint32_t recq = (uint32_t)((((int64_t)S - 1) * ld + HD) * 2), reco = (uint32_t)((((int64_t)S - 1) * ldc + HD) * 2);
   const u32x4 rsQ = {(uint32_t)qa, (uint32_t)(qa >> 32) & 0xFFFFu, recq, 0x00020000u};
   const u32x4 rsO = {(uint32_t)oa, (uint32_t)(oa >> 32) & 0xFFFFu, reco, 0x00020000u};
-  // per-query scalars of the tile, read straight from memory: reads past the sequence end return zeros
-  const __amdgpu_buffer_rsrc_t rsL = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lse + (int64_t)bh * S), 0, S * 4, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsD = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(dsum + (int64_t)bh * S), 0, S * 4, 0x00020000);
+  // per-query scalars travel with the tile (64 floats each; the lanes past them, and queries past the sequence
+  // end, fetch zeros)
+  const uint64_t la = reinterpret_cast<uint64_t>(lse + (int64_t)bh * S), da = reinterpret_cast<uint64_t>(dsum + (int64_t)bh * S);
+  const u32x4 rsL = {(uint32_t)la, (uint32_t)(la >> 32) & 0xFFFFu, (uint32_t)S * 4u, 0x00020000u};
+  const u32x4 rsD = {(uint32_t)da, (uint32_t)(da >> 32) & 0xFFFFu, (uint32_t)S * 4u, 0x00020000u};
+  const uint32_t vos = lane < 16 ? (uint32_t)lane * 16u : 0x80000000u;
   uint32_t voq[IQ], voo[IQ];
 #pragma unroll
   for (int jj = 0; jj < IQ; ++jj) {
@@ -523,11 +527,13 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_kv_k(const bf16* __restrict__
   const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(lds);
   auto request = [&](int it) __attribute__((always_inline)) {
     const uint32_t sq = (uint32_t)((int64_t)it * QT * ld * 2), so = (uint32_t)((int64_t)it * QT * ldc * 2);
-    const uint32_t dst = lds0 + (uint32_t)(it & 1) * (2 * TQ) + (uint32_t)wave * (IQ * 1024);
+    const uint32_t buf = lds0 + (uint32_t)(it & 1) * BUF, dst = buf + (uint32_t)wave * (IQ * 1024);
 #pragma unroll
     for (int jj = 0; jj < IQ; ++jj) dma_b128(rsQ, dst + jj * 1024, voq[jj], sq);
 #pragma unroll
     for (int jj = 0; jj < IQ; ++jj) dma_b128(rsO, dst + TQ + jj * 1024, voo[jj], so);
+    if (wave == 0) dma_b128(rsL, buf + 2 * TQ, vos, (uint32_t)(it * QT * 4));
+    if (wave == 1) dma_b128(rsD, buf + 2 * TQ + 1024, vos, (uint32_t)(it * QT * 4));
   };
 
   // fragment of tile rows in pi order (block blk of 32 queries, k-step ks) and transposing reads (k-step t = 16
@@ -572,7 +578,7 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_kv_k(const bf16* __restrict__
     __syncthreads();  // tile `it` has landed for everyone; nobody reads the other buffer any more
     if (it + 1 < all_tiles) request(it + 1);
     if (CAUSAL && it * QT + QT - 1 < j0) continue;  // every query of the tile precedes this wavefront's keys
-    const unsigned char* Qb = lds + (it & 1) * (2 * TQ);
+    const unsigned char* Qb = lds + (it & 1) * BUF;
     const unsigned char* Ob = Qb + TQ;
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
@@ -581,9 +587,9 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_kv_k(const bf16* __restrict__
       f32x4 lq[4], dq4[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const int off = (qb0 + 16 * (c >> 1) + 8 * fh + 4 * (c & 1)) * 4;
-        lq[c] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsL, off, 0, 0));
-        dq4[c] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsD, off, 0, 0));
+        const int off = (blk * 32 + 16 * (c >> 1) + 8 * fh + 4 * (c & 1)) * 4;
+        lq[c] = *reinterpret_cast<const f32x4*>(Qb + 2 * TQ + off);
+        dq4[c] = *reinterpret_cast<const f32x4*>(Qb + 2 * TQ + 1024 + off);
       }
       f32x16 st, dpt;
 #pragma unroll
