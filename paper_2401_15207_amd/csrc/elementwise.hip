@@ -59,36 +59,63 @@ __global__ void __launch_bounds__(BLK) embed_fwd_k(const int32_t* __restrict__ t
   }
 }
 
-// Gradient of the token table, deterministic: the workgroup of the first position that holds a token
-// sums the rows of all positions holding it, in position order, and writes the table row once; the
-// workgroups of later occurrences have nothing to do.  (Rows of tokens that do not occur are zeroed
-// by the caller; with `add` the row's previous content is kept and added to.)  T_ is a few thousand: the scan over the token list costs nothing against the rows.
+// Gradient of the token table, deterministic: the workgroups of the first position that holds a token
+// (one per chunk of 4 BLK columns) sum the rows of all positions holding it, in position order, and write
+// their part of the table row once; the workgroups of later occurrences have nothing to do.  (Rows of tokens
+// that do not occur are zeroed by the caller; with `add` the row's previous content is kept and added to.)
+// The positions holding the token are first collected, in order, into a list in LDS (a frequent token of a
+// Zipf-distributed batch occurs hundreds of times: walking the whole token list once per row read made this
+// kernel take milliseconds), then only those rows are read, several loads in flight.
 template <typename T>
 __global__ void __launch_bounds__(BLK) embed_bwd_tok_k(const int32_t* __restrict__ tokens, int64_t T_, int d, int vocab,
                                                         const T* __restrict__ dx, float* __restrict__ g_tok, bool add) {
+  constexpr int LCAP = 2048;  // positions per batch of the list
+  __shared__ int list[LCAP];
+  __shared__ int wcount[BLK / 64];
   const int64_t p = blockIdx.x;
+  const int j0 = (int)blockIdx.y * (BLK * 4);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   auto clamp = [vocab](int id) { return id < 0 ? 0 : (id >= vocab ? vocab - 1 : id); };
   const int id = clamp(tokens[p]);
   int seen = 0;
   for (int64_t q = threadIdx.x; q < p; q += BLK) seen |= clamp(tokens[q]) == id;
   if (__syncthreads_or(seen)) return;
-  float* gr = g_tok + (int64_t)id * d;
-  for (int j0 = 0; j0 < d; j0 += BLK * 4) {
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t q = p; q < T_; ++q) {
-      if (clamp(tokens[q]) != id) continue;  // uniform over the workgroup
-      const T* dr = dx + q * d;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  int64_t c0 = p;
+  while (c0 < T_) {
+    // one batch of the list: positions c0 .. of this token, in order, at most LCAP of them
+    int n = 0;
+    for (; c0 < T_ && n + BLK <= LCAP; c0 += BLK) {
+      const int64_t q = c0 + threadIdx.x;
+      const bool hit = q < T_ && clamp(tokens[q]) == id;
+      const unsigned long long m = __ballot(hit);
+      if (lane == 0) wcount[wave] = __popcll(m);
+      __syncthreads();
+      int before = 0, total = 0;
+#pragma unroll
+      for (int w = 0; w < BLK / 64; ++w) {
+        before += w < wave ? wcount[w] : 0;
+        total += wcount[w];
+      }
+      if (hit) list[n + before + __popcll(m & ((1ull << lane) - 1ull))] = (int)q;
+      n += total;
+      __syncthreads();  // wcount is rewritten in the next round; the list is read below
+    }
+    for (int i = 0; i < n; ++i) {
+      const T* dr = dx + (int64_t)list[i] * d;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int j = j0 + e * BLK + threadIdx.x;
         if (j < d) acc[e] += to_f32(dr[j]);
       }
     }
+    __syncthreads();  // the list is rebuilt in the next batch
+  }
+  float* gr = g_tok + (int64_t)id * d;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int j = j0 + e * BLK + threadIdx.x;
-      if (j < d) gr[j] = add ? gr[j] + acc[e] : acc[e];
-    }
+  for (int e = 0; e < 4; ++e) {
+    const int j = j0 + e * BLK + threadIdx.x;
+    if (j < d) gr[j] = add ? gr[j] + acc[e] : acc[e];
   }
 }
 
@@ -876,10 +903,10 @@ hipError_t embed_bwd(int dt, const int32_t* tokens, int64_t T_, int S, int d, in
                      float* g_tok, float* g_pos, bool add, hipStream_t st) {
   if (T_ == 0) return hipSuccess;
   if (dt == DT_F32) {
-    embed_bwd_tok_k<float><<<dim3((unsigned)T_), BLK, 0, st>>>(tokens, T_, d, V_, (const float*)dx, g_tok, add);
+    embed_bwd_tok_k<float><<<dim3((unsigned)T_, (unsigned)cdiv(d, BLK * 4)), BLK, 0, st>>>(tokens, T_, d, V_, (const float*)dx, g_tok, add);
     if (g_pos) embed_bwd_pos_k<float><<<dim3(S), BLK, 0, st>>>((int)(T_ / S), S, d, (const float*)dx, g_pos);
   } else {
-    embed_bwd_tok_k<bf16><<<dim3((unsigned)T_), BLK, 0, st>>>(tokens, T_, d, V_, (const bf16*)dx, g_tok, add);
+    embed_bwd_tok_k<bf16><<<dim3((unsigned)T_, (unsigned)cdiv(d, BLK * 4)), BLK, 0, st>>>(tokens, T_, d, V_, (const bf16*)dx, g_tok, add);
     if (g_pos) embed_bwd_pos_k<bf16><<<dim3(S), BLK, 0, st>>>((int)(T_ / S), S, d, (const bf16*)dx, g_pos);
   }
   LAUNCH_CHECK();
