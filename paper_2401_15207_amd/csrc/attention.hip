@@ -602,13 +602,25 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_kv_k(const bf16* __restrict__
         dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo, vf[ks], dpt, 0, 0, 0);
       }
       bf16x8 pf[2], sf[2];
+      // no query of the block is masked for any key of this wavefront: all inside the sequence and, under the
+      // causal mask, at or after its last key
+      const bool plain = qb0 + 32 <= S && (!CAUSAL || qb0 >= j0 + 31);
+      if (plain) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int qi = qb0 + 16 * (e / 8) + 8 * fh + e % 8;
-        const bool ok = qi < S && (!CAUSAL || qi >= row);
-        const float pr = ok ? __builtin_amdgcn_exp2f(__builtin_fmaf(st[e], scale_log2e, -lq[e / 4][e % 4])) : 0.f;
-        pf[e / 8][e % 8] = static_cast<__bf16>(pr);
-        sf[e / 8][e % 8] = static_cast<__bf16>(scale * pr * (dpt[e] - dq4[e / 4][e % 4]));
+        for (int e = 0; e < 16; ++e) {
+          const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(st[e], scale_log2e, -lq[e / 4][e % 4]));
+          pf[e / 8][e % 8] = static_cast<__bf16>(pr);
+          sf[e / 8][e % 8] = static_cast<__bf16>(scale * pr * (dpt[e] - dq4[e / 4][e % 4]));
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int qi = qb0 + 16 * (e / 8) + 8 * fh + e % 8;
+          const bool ok = qi < S && (!CAUSAL || qi >= row);
+          const float pr = ok ? __builtin_amdgcn_exp2f(__builtin_fmaf(st[e], scale_log2e, -lq[e / 4][e % 4])) : 0.f;
+          pf[e / 8][e % 8] = static_cast<__bf16>(pr);
+          sf[e / 8][e % 8] = static_cast<__bf16>(scale * pr * (dpt[e] - dq4[e / 4][e % 4]));
+        }
       }
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2) {
