@@ -87,3 +87,41 @@ def test_c4_full_depth_step_properties():
             assert not np.array_equal(model.read_params(unit, unit + 1, 0), t0)
     finally:
         model.close()
+
+
+@pytest.mark.timeout(900)
+def test_c4_full_depth_state_in_host_memory_changes_nothing():
+    """The same five scheduled steps with the optimizer state of inactive groups in pinned host memory (copies
+    on two side streams, prefetch of the next group) and with all state resident in HBM: losses and the
+    updated units are bit-identical (where the state lives must be invisible in the result)."""
+    import torch
+    import paper_2401_15207_amd as H
+    from bench import fill_weights
+    wl = WORKLOADS["C4"]
+    cfg = model_config(wl)
+    B, S = wl["batch"], wl["seq"]
+    steps = 5
+    batches = [[torch.from_numpy(x).cuda() for x in make_batch(wl, 0, t)] for t in range(1, steps + 1)]
+    out = []
+    for on_host in (1, 0):
+        model = H.HiftModel(cfg, wl["opt"], wl["m"], B, S, init_params=None, state_on_host=on_host)
+        try:
+            fill_weights(model, cfg, 0)
+            model.set_group_schedule(wl["strategy"], wl["m"], 0)
+            losses, units = [], []
+            for t in range(1, steps + 1):
+                gid = model.schedule_group_at(t)
+                losses.append(model.step(*batches[t - 1], gid, want_loss=True))
+                units.append(gid)
+            params = [model.read_params(u, u + 1, 0) for u in units]
+            moments = [model.read_state(u, u + 1, 1) for u in units]
+            out.append((losses, units, params, moments))
+        finally:
+            model.close()
+        del model
+        torch.cuda.empty_cache()
+    (la, ua, pa, ma), (lb, ub, pb, mb) = out
+    assert ua == ub == [0, 1, 2, 3, 4]
+    assert la == lb
+    for x, y in zip(pa + ma, pb + mb):
+        assert np.array_equal(x, y)
