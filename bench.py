@@ -281,7 +281,8 @@ def main():
                    "groups": k, "tokens_per_step": B * S},
         "roofline": {
             "bound": "mfma",
-            "kernel": "gemm_pk_k<128x256 tiles, bf16 out>: linear layers, forward and dX, weight operand in MFMA fragment order",
+            "kernel": "gemm_pk_k<128x256 tiles, bf16 out>, its fused-epilogue instantiations included: linear layers, forward and dX, "
+                      "weight operand in MFMA fragment order",
             "achieved": gemm_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": gemm_tflops / BF16_PEAK_TFLOPS, "traffic": measured_traffic(),
             "launches": n_gemm, "avg_launch_ms": ms_gemm / max(n_gemm, 1),
