@@ -352,6 +352,33 @@ hift_status hift_kernel_linear_fused(int32_t epilogue, int64_t M, int64_t N, int
                                      const void* W, void* packed_scratch, void* C, void* aux,
                                      const float* cos_sin, int32_t seq, int64_t rot_cols, void* stream);
 
+/* The RMS normalisation in front of such a layer done by the layer itself (forward of Algorithm 1
+ * step h; bf16): y = (x / rms(x) * gain) . W^T is computed as (1 / rms(x)) (x . (W gain)^T).
+ *   hift_kernel_gemm_packed_rowsq: hift_kernel_gemm_packed with bf16 C (N a multiple of 256, R optional)
+ *     that also leaves the sums of squares of the values it stored: rowsq, device fp32 [M, N / 64], one
+ *     partial per row and 64-column strip.
+ *   hift_kernel_row_sumsq: the same quantity for rows written by something else: x device bf16
+ *     [rows, d] contiguous, d a multiple of 8; out device fp32 [rows, n]: out[r][0] = sum of squares,
+ *     the other n - 1 entries of the row zero.
+ *   hift_kernel_linear_norm_fused: hift_kernel_linear_fused (SWIGLU or ROPE) on rows A that are not
+ *     normalised yet.  gain: device bf16 [K], multiplied into the packed copy of W (each product rounded
+ *     once); rowsq: device fp32 [M, K / 64], 16-byte aligned, a row's entries add up to its sum of
+ *     squares; every accumulator of row r is multiplied by 1 / sqrt(sum_r / K + norm_eps) before the
+ *     epilogue proper; stats: device fp32 [M, 2] or NULL, receives (0, that factor) per row, what
+ *     hift_kernel_norm_fwd leaves for the backward pass.  K a multiple of 512, at most 6144.  gain and rowsq both
+ *     NULL: exactly hift_kernel_linear_fused.
+ * workspace (the first and the last of the three): NULL, or a work space as hift_kernel_gemm_packed_ws
+ * takes it (hift_kernel_packed_workspace_bytes() bytes, same rules), with the same effect. */
+hift_status hift_kernel_gemm_packed_rowsq(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                                          const void* Bp, void* C, int64_t ldc, const void* R,
+                                          float* rowsq, void* workspace, void* stream);
+hift_status hift_kernel_row_sumsq(int64_t rows, int32_t d, const void* x, int32_t n, float* out, void* stream);
+hift_status hift_kernel_linear_norm_fused(int32_t epilogue, int64_t M, int64_t N, int64_t K, const void* A,
+                                          int64_t lda, const void* W, const void* gain, void* packed_scratch,
+                                          void* C, void* aux, const float* cos_sin, int32_t seq,
+                                          int64_t rot_cols, const float* rowsq, float norm_eps,
+                                          float* stats, void* workspace, void* stream);
+
 /* Group-local optimizer update on `count` contiguous parameters (the update inside Algorithm 1's
  * backward step): master, grad, state1, state2 fp32; compute_copy (bf16, may be NULL) receives the
  * rounded new values.  t is the group's update number (1 on its first update). */

@@ -99,6 +99,10 @@ _SIGS = {
     "hift_kernel_packed_workspace_bytes": [_P(_sz)],
     "hift_kernel_gemm_packed_ws": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _sz, _vp],
     "hift_kernel_linear_fused": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _vp],
+    "hift_kernel_gemm_packed_rowsq": [_i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp],
+    "hift_kernel_row_sumsq": [_i64, _i32, _vp, _i32, _vp, _vp],
+    "hift_kernel_linear_norm_fused": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _vp,
+                                      C.c_float, _vp, _vp, _vp],
     "hift_kernel_attention_fwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_attention_bwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_cross_entropy": [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp],
@@ -241,6 +245,28 @@ def kernel_linear_fused(epilogue, M, N, K, A, lda, W, packed_scratch, C, aux, co
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib.hift_kernel_linear_fused(epilogue, M, N, K, _ptr(A), lda, _ptr(W), _ptr(packed_scratch), _ptr(C), _ptr(aux),
                                         _ptr(cos_sin), seq, rot_cols, st))
+
+
+def kernel_gemm_packed_rowsq(M, N, K, A, lda, Bp, Cm, ldc, R, rowsq, workspace=None, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_gemm_packed_rowsq(M, N, K, _ptr(A), lda, _ptr(Bp), _ptr(Cm), ldc, _ptr(R), _ptr(rowsq),
+                                             _ptr(workspace), st))
+
+
+def kernel_row_sumsq(rows, d, x, n, out, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_row_sumsq(rows, d, _ptr(x), n, _ptr(out), st))
+
+
+def kernel_linear_norm_fused(epilogue, M, N, K, A, lda, W, gain, packed_scratch, Cm, aux, cos_sin, seq, rot_cols, rowsq,
+                             norm_eps, stats, workspace=None, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_linear_norm_fused(epilogue, M, N, K, _ptr(A), lda, _ptr(W), _ptr(gain), _ptr(packed_scratch),
+                                             _ptr(Cm), _ptr(aux), _ptr(cos_sin), seq, rot_cols, _ptr(rowsq), norm_eps,
+                                             _ptr(stats), _ptr(workspace), st))
 
 
 def kernel_attention_fwd(batch, heads, seq, head_dim, causal, qkv, prob, ctx, lse=None, stream=None):

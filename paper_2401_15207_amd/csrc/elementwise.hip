@@ -196,6 +196,22 @@ __global__ void __launch_bounds__(BLK) norm_fwd_k(int64_t rows, int d, float eps
   }
 }
 
+// Sums of squares of bf16 rows for a contraction that applies the RMS normalisation itself (Gemm::rowsq):
+// out[row][0] = sum of x^2, out[row][1 .. n) = 0.  One wavefront per row.
+__global__ void __launch_bounds__(64) row_sumsq_k(int d, const bf16* __restrict__ x, int n, float* __restrict__ out) {
+  const int64_t row = blockIdx.x;
+  const int lane = threadIdx.x;
+  float q = 0.f;
+  for (int j = lane * 8; j < d; j += 512) {
+    float a[8];
+    ldv<bf16, 8>(x + row * d + j, a);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q += a[e] * a[e];
+  }
+  q = wave_sum(q);
+  for (int c = lane; c < n; c += 64) out[row * n + c] = c == 0 ? q : 0.f;
+}
+
 // Same, with the row held in registers (d <= 64 * V * NCH): every load of the row is in flight at once
 // and x is read from memory a single time.  One wavefront per row, one row per 64-thread workgroup so
 // that short batches still spread over the whole chip.
@@ -951,6 +967,13 @@ hipError_t norm_fwd(int dt, bool rms, int64_t rows, int d, float eps, const void
     DISPATCH_TV(dt, OK, (norm_fwd_k<T, V, false><<<grid, BLK, 0, st>>>(rows, d, eps, (const T*)x, (const T*)g,
                                                                            (const T*)b, (T*)y, stats)));
 #undef OK
+  LAUNCH_CHECK();
+}
+
+hipError_t row_sumsq(int64_t rows, int d, const void* x, int n, float* out, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  if (d % 8 != 0 || !aligned16(x) || n < 1 || rows > 0x7FFFFFFF) return hipErrorInvalidValue;
+  row_sumsq_k<<<dim3((unsigned)rows), 64, 0, st>>>(d, (const bf16*)x, n, out);
   LAUNCH_CHECK();
 }
 

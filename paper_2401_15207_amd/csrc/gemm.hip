@@ -43,6 +43,9 @@ struct GemmP {
   // tile each, every member a share of the k range; ws: counters (first 1 KB) and partial tiles
   int split_from = 0x7FFFFFFF, split = 1;
   unsigned char* ws = nullptr;
+  // row normalisation folded into the packed-operand kernel (see Gemm in kernels.h)
+  float* rowsq_out = nullptr;
+  const float* rowsq = nullptr; int rowsq_n = 0; float norm_eps = 0.f; float* norm_stats = nullptr;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -223,6 +226,19 @@ __device__ __forceinline__ void store_tile(const GemmP& p, f32x16 (&acc)[WM / 32
 #pragma unroll
           for (int e = 0; e < 4; ++e) { t[e] = static_cast<__bf16>(lo[e]); t[4 + e] = static_cast<__bf16>(hi[e]); }
           *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(C) + row * p.ldc + col) = t;
+          if constexpr (WN == 64) {
+            if (p.rowsq_out) {
+              // sum of squares of this row's 64 stored values of the strip (the eight lanes of a row are
+              // all here: N is a whole number of strips), one partial per row and strip
+              float q = 0.f;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) { const float f = static_cast<float>(t[e]); q += f * f; }
+              q += __shfl_xor(q, 1);
+              q += __shfl_xor(q, 2);
+              q += __shfl_xor(q, 4);
+              if (cc == 0) p.rowsq_out[row * (p.N / 64) + (n0 + wn * WN) / 64] = q;
+            }
+          }
         } else {
           float* cp = reinterpret_cast<float*>(C) + row * p.ldc + col;
           if (R) {
@@ -441,10 +457,21 @@ __device__ __forceinline__ int64_t pk_block_pos(int64_t s, int order, int64_t ha
   return s;
 }
 
+// Product of eight bf16 pairs, each rounded once.
+__device__ __forceinline__ u32x4 scale8(u32x4 a, u32x4 b) {
+  bf16x8 x = __builtin_bit_cast(bf16x8, a);
+  const bf16x8 y = __builtin_bit_cast(bf16x8, b);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = static_cast<__bf16>(static_cast<float>(x[e]) * static_cast<float>(y[e]));
+  return __builtin_bit_cast(u32x4, x);
+}
+
+// The packers take an optional gain [K]: the copy then holds B[n][k] gain[k] (a row normalisation's gain folded
+// into the weight that consumes the normalised rows).
 // Generic packer (any alignment): one wavefront per 1 KB block, element-wise reads.
 __global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int64_t ldb, int64_t N, int64_t K,
                                                  bool b_kmajor, u32x4* __restrict__ Bp, int64_t n_blocks, int64_t k_steps,
-                                                 int order, int64_t half) {
+                                                 int order, int64_t half, const bf16* __restrict__ gain) {
   const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (w >= n_blocks * k_steps) return;
   const int lane = threadIdx.x & 63;
@@ -456,6 +483,7 @@ __global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int6
     const int64_t k = k0 + e;
     float x = 0.f;
     if (n < N && k < K) x = static_cast<float>(b_kmajor ? B[n * ldb + k] : B[k * ldb + n]);
+    if (gain && k < K) x *= static_cast<float>(gain[k]);
     v[e] = static_cast<__bf16>(x);
   }
   Bp[(pk_block_pos(nb, order, half) * k_steps + kk) * 64 + lane] = __builtin_bit_cast(u32x4, v);
@@ -468,7 +496,7 @@ __global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int6
 template <bool KMAJOR>
 __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B, int64_t ldb, int64_t N, int64_t K,
                                                       u32x4* __restrict__ Bp, int64_t k_steps, int tiles_inner, int order,
-                                                      int64_t half) {
+                                                      int64_t half, const bf16* __restrict__ gain) {
   constexpr int PITCH = 512 + 16;  // bytes per tile row in LDS; the pad spreads 16-byte reads of one column over the banks
   __shared__ __attribute__((aligned(16))) unsigned char tile[32 * PITCH];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -482,6 +510,7 @@ __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B,
       const int64_t n = nb * 32 + r, k = k00 + c;
       u32x4 v = zero;
       if (n < N && k < K) v = *reinterpret_cast<const u32x4*>(B + n * ldb + k);
+      if (gain && n < N && k < K) v = scale8(v, *reinterpret_cast<const u32x4*>(gain + k));  // K % 8 == 0 here
       *reinterpret_cast<u32x4*>(tile + r * PITCH + c * 2) = v;
     }
     __syncthreads();
@@ -506,6 +535,13 @@ __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B,
         bf16x8 t;
 #pragma unroll
         for (int e = 0; e < 8; ++e) t[e] = n + e < N ? B[k * ldb + n + e] : static_cast<__bf16>(0.f);
+        v = __builtin_bit_cast(u32x4, t);
+      }
+      if (gain && k < K) {
+        const float gk = static_cast<float>(gain[k]);
+        bf16x8 t = __builtin_bit_cast(bf16x8, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = static_cast<__bf16>(static_cast<float>(t[e]) * gk);
         v = __builtin_bit_cast(u32x4, t);
       }
       *reinterpret_cast<u32x4*>(tile + r * PITCH + c * 2) = v;
@@ -538,6 +574,7 @@ __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B,
 // MT = 4 (128 x 256 tiles) is the instantiation in use: at M = 2048 it gives the 7B shapes whole
 // numbers of rounds over 256 compute units more often than 256 x 256 does, and ran faster.
 constexpr int PK_DK = 64, PK_STAGES = 4, PK_RD = 3, PK_ROW = 128;
+constexpr int PK_SQ_MAX = 12;  // folded normalisation: 16-byte pieces of row partials a thread holds (K <= 6144)
 
 // Fused epilogues of the packed-operand kernel (bf16 output).  The packed copy holds B's 32-row blocks in
 // an order (PK_ORDER_*) that puts, side by side in a wavefront's two accumulator columns, the blocks
@@ -554,7 +591,7 @@ __device__ __forceinline__ float silu_fast(float x) {
 
 template <int MT, int EPI>
 __device__ __forceinline__ void store_tile_fused(const GemmP& p, f32x16 (&acc)[MT][2], unsigned char* smem, int64_t m0, int tn,
-                                                 int wave, int lane, int slot) {
+                                                 int wave, int lane, int slot, const float* row_rstd) {
   // m0: first row of this wavefront's sub-tile; wave: its 64-column strip (0..3) of the 256-column tile;
   // slot: which staging region of LDS it uses
   constexpr int RP = 64, PITCH = 64 * 4 + 16;
@@ -570,15 +607,19 @@ __device__ __forceinline__ void store_tile_fused(const GemmP& p, f32x16 (&acc)[M
   for (int pass = 0; pass < 32 * MT / RP; ++pass) {
     __syncthreads();  // operand tiles (first pass) or the previous pass are no longer read
 #pragma unroll
-    for (int ii = 0; ii < RP / 32; ++ii)
+    for (int ii = 0; ii < RP / 32; ++ii) {
+      const int i = pass * (RP / 32) + ii;
+      // folded row normalisation: every accumulator of a lane belongs to tile row 32 i + frow
+      const float r = row_rstd ? row_rstd[32 * i + frow] : 1.0f;
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int i = pass * (RP / 32) + ii;
-          const f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          if (row_rstd) v *= r;
           *reinterpret_cast<f32x4*>(reg + (ii * 32 + frow) * PITCH + (j * 32 + 8 * g + 4 * fhalf) * 4) = v;
         }
+    }
     __syncthreads();
     if (EPI == EPI_SWIGLU && C) {  // the pre-activations: each lane its own chunk, 8 rows per sweep
 #pragma unroll 2
@@ -776,6 +817,24 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
 #pragma unroll
   for (int i = 0; i < MT; ++i) read_a1(fa[0][i], smem + (kt0 & (PK_STAGES - 1)) * STG, 0, i);
 
+  // Folded row normalisation: A holds the rows before normalisation and B the weight times the gain, so the
+  // product only lacks each row's 1 / sqrt(mean of squares + eps).  The producer of A left the sums of squares
+  // as K / 64 partials per row; two threads fetch a row's partials here (they arrive under the main loop; older
+  // than every load of the loop, they are covered by its first wait) and add them up after it.
+  __shared__ float row_rstd[BM];
+  constexpr bool NORM_EPI = EPI == EPI_SWIGLU || EPI == EPI_ROPE;
+  f32x4 sqv[NORM_EPI ? PK_SQ_MAX : 1];
+  if constexpr (NORM_EPI) {
+    static_assert(BM == 128, "two threads per row");
+    if (p.rowsq) {
+      const int hn4 = p.rowsq_n >> 3;  // 16-byte pieces per thread
+      const int64_t row = m0 + (tid >> 1);
+      const f32x4* src = reinterpret_cast<const f32x4*>(p.rowsq + (row < p.M ? row : 0) * p.rowsq_n) + (tid & 1) * hn4;
+#pragma unroll
+      for (int c = 0; c < PK_SQ_MAX; ++c) sqv[c] = c < hn4 ? src[c] : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  }
+
   // One k-step: 2 MT MFMAs in the order (j, i); after the q-th one: q < MT: A fragment q of the next
   // k-step; q == MT: refill of B fragment 0; then (first two k-steps of a stage) NP / 2 pieces of the
   // request for a later stage; last: refill of B fragment 1.  A wavefront issues in order and an MFMA
@@ -832,6 +891,24 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
     kstep(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{}, kt, cur);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stray requests must land before LDS is reused
+  if constexpr (NORM_EPI) {
+    if (p.rowsq) {
+      const int r = tid >> 1;
+      const int64_t row = m0 + r;
+      float q = 0.f;
+#pragma unroll
+      for (int c = 0; c < PK_SQ_MAX; ++c) q += (sqv[c][0] + sqv[c][1]) + (sqv[c][2] + sqv[c][3]);
+      q += __shfl_xor(q, 1);
+      const float rstd = 1.0f / sqrtf(q / (float)p.K + p.norm_eps);
+      if ((tid & 1) == 0) {
+        row_rstd[r] = rstd;  // read after the epilogue's first barrier
+        if (p.norm_stats && tn == 0 && part == 0 && row < p.M) {  // what the normalisation's backward reads
+          p.norm_stats[2 * row] = 0.f;
+          p.norm_stats[2 * row + 1] = rstd;
+        }
+      }
+    }
+  }
 
   if (shared_tile) {
     // Every member leaves its partial tile in its own slot (register order: 4 KB per wavefront and store)
@@ -883,7 +960,7 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
 
   if constexpr (EPI == EPI_NONE) store_tile<BM, WN, VEC_EPI, OutT>(p, acc, smem, m0, n0, 0, wave, wave, lane, 0, 0);
   else if constexpr (EPI == EPI_SWIGLU_BWD) store_tile_gate_bwd<MT>(p, acc, smem, m0, n0, wave, lane);
-  else store_tile_fused<MT, EPI>(p, acc, smem, m0, tn, wave, lane, wave);
+  else store_tile_fused<MT, EPI>(p, acc, smem, m0, tn, wave, lane, wave, p.rowsq ? row_rstd : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -997,25 +1074,27 @@ size_t packed_b_bytes(int64_t N, int64_t K) {
   return (size_t)((N + 255) / 256) * 8 * (size_t)(K / 16) * 1024;
 }
 
-hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st, int order) {
+hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st, int order,
+                  const void* gain) {
   if (packed_b_bytes(N, K) == 0) return hipErrorInvalidValue;
   if (order == PK_ORDER_HALVES ? N % 256 != 0 : order == PK_ORDER_PAIR64 ? N % 128 != 0 : order != PK_ORDER_PLAIN)
     return hipErrorInvalidValue;
   const int64_t half = N / 64;  // 32-row blocks in half of B
   const int64_t n_blocks = ((N + 255) / 256) * 8, k_steps = K / 16;
   const bf16* Bs = reinterpret_cast<const bf16*>(B);
+  const bf16* gn = reinterpret_cast<const bf16*>(gain);
   u32x4* out = reinterpret_cast<u32x4*>(Bp);
-  if (al16(B) && ldb % 8 == 0) {
+  if (al16(B) && ldb % 8 == 0 && (!gain || (al16(gain) && K % 8 == 0))) {
     if (b_kmajor) {
       const int ti = (int)((K + 255) / 256);
-      pack_b_tile_k<true><<<dim3((unsigned)(n_blocks * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti, order, half);
+      pack_b_tile_k<true><<<dim3((unsigned)(n_blocks * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti, order, half, gn);
     } else {
       const int ti = (int)(n_blocks / 8);
-      pack_b_tile_k<false><<<dim3((unsigned)((K / 32) * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti, order, half);
+      pack_b_tile_k<false><<<dim3((unsigned)((K / 32) * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti, order, half, gn);
     }
   } else {
     const int64_t blocks = n_blocks * k_steps;
-    pack_b_k<<<dim3((unsigned)((blocks + 3) / 4)), 256, 0, st>>>(Bs, ldb, N, K, b_kmajor, out, n_blocks, k_steps, order, half);
+    pack_b_k<<<dim3((unsigned)((blocks + 3) / 4)), 256, 0, st>>>(Bs, ldb, N, K, b_kmajor, out, n_blocks, k_steps, order, half, gn);
   }
   return hipGetLastError();
 }
@@ -1073,6 +1152,15 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
     }
     p.C2 = g.C2; p.ldc2 = g.ldc2;
     p.cos_sin = reinterpret_cast<const float2*>(g.cos_sin); p.S = g.S > 0 ? g.S : 1; p.rot_cols = g.rot_cols;
+  }
+  if (g.rowsq_out) {  // one partial per row and 64-column strip: bf16 rows, plain epilogue, whole strips
+    if (g.out_f32 || g.epi != EPI_NONE || g.N % 256 != 0) return hipErrorInvalidValue;
+    p.rowsq_out = g.rowsq_out;
+  }
+  if (g.rowsq) {  // K / 64 partials per row, read in 16-byte pieces by two threads per row
+    if ((g.epi != EPI_SWIGLU && g.epi != EPI_ROPE) || g.K % 512 != 0 || g.K > 512 * PK_SQ_MAX || !al16(g.rowsq))
+      return hipErrorInvalidValue;
+    p.rowsq = g.rowsq; p.rowsq_n = (int)(g.K / 64); p.norm_eps = g.norm_eps; p.norm_stats = g.norm_stats;
   }
   const u32x4* bp = reinterpret_cast<const u32x4*>(Bp);
   p.tiles_n = (int)((p.N + 255) / 256);

@@ -47,6 +47,15 @@ struct Gemm {
   // round over the 256 compute units are shared by 2 to 4 workgroups each, every one taking a share of the
   // k range; launches that use the same work space must not overlap.
   void* ws = nullptr;
+  // Row normalisation without a kernel of its own (gemm_packed only).  y = (x / rms(x)) gain . W^T is computed
+  // as rstd(x) (x . (W gain)^T): the packed copy is built with the gain (pack_b), and
+  //   rowsq_out  (plain epilogue, bf16 C, N a multiple of 256) the kernel that writes the rows x also leaves
+  //              the sums of squares of the values it stored, [M, N / 64]: one partial per row and 64-column strip;
+  //   rowsq      (EPI_ROPE and EPI_SWIGLU, K a multiple of 512 up to 6144) the consumer adds a row's K / 64 partials up,
+  //              multiplies its accumulators by rstd = 1 / sqrt(sum / K + norm_eps) before anything else, and, if
+  //              norm_stats is given, leaves (0, rstd) per row there, as the RMS normalisation kernel does.
+  float* rowsq_out = nullptr;
+  const float* rowsq = nullptr; float norm_eps = 0.f; float* norm_stats = nullptr;
 };
 constexpr size_t PACKED_WS_BYTES = 1024 + size_t(256) * 128 * 256 * 4;
 enum { EPI_NONE = 0, EPI_SWIGLU = 1, EPI_ROPE = 2, EPI_SWIGLU_BWD = 3 };
@@ -66,14 +75,17 @@ hipError_t gemm(const Gemm& g, hipStream_t st, int* variant = nullptr);
 //                    rows further (EPI_ROPE; N must be a multiple of 128)
 enum { PK_ORDER_PLAIN = 0, PK_ORDER_HALVES = 1, PK_ORDER_PAIR64 = 2 };
 size_t packed_b_bytes(int64_t N, int64_t K);
+// gain (optional, bf16 [K]): the copy holds B[n][k] gain[k], each product rounded once.
 hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st,
-                  int order = PK_ORDER_PLAIN);
+                  int order = PK_ORDER_PLAIN, const void* gain = nullptr);
 bool packed_gemm_applies(const Gemm& g);
 hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st);
 
 // ---- row-wise and elementwise kernels ------------------------------------------------------
 hipError_t embed_fwd(int dt, const int32_t* tokens, int64_t T, int S, int d, int V,
                      const void* tok_emb, const void* pos_emb, void* x, hipStream_t st);
+// bf16 rows [rows, d] (d a multiple of 8): out[row][0] = sum of squares, out[row][1 .. n) = 0 (see Gemm::rowsq)
+hipError_t row_sumsq(int64_t rows, int d, const void* x, int n, float* out, hipStream_t st);
 hipError_t norm_fwd(int dt, bool rms, int64_t rows, int d, float eps, const void* x, const void* g,
                     const void* b, void* y, float* stats, hipStream_t st);
 // dx = (dres ? dres : 0) + d norm / d x applied to dy

@@ -51,6 +51,9 @@ struct Tensor {
   // pk_fwd packs w as [rows, cols] (forward, y = x . w^T), pk_bwd packs w^T (dX = dY . w)
   int64_t pk_fwd = -1, pk_bwd = -1;
   int pk_order = PK_ORDER_PLAIN;  // block order of the forward copy (which fused epilogue it is made for)
+  // index of the normalisation gain folded into the forward copy, or -1: the layer then multiplies the rows
+  // as they are before the normalisation, and the kernel scales by their 1 / rms (see Gemm::rowsq)
+  int pk_gain = -1;
   int64_t fac_off = 0;  // Adafactor: first float of this tensor's statistics ([rows | cols], or [rows] for vectors)
   int64_t fac_count() const { return cols > 1 ? rows + cols : rows; }
   int64_t count() const { return rows * cols; }
@@ -244,6 +247,7 @@ struct hift_model {
   unsigned char* wpk = nullptr;  // copies of the large bf16 matrices in MFMA fragment order
   size_t wpk_bytes = 0;
   void* gemm_ws = nullptr;
+  float* rowsq = nullptr;  // [maxT, d / 64] partial sums of squares of the rows a folded normalisation takes
   float* fac = nullptr;      // Adafactor statistics of every tensor (resident: they are tiny)
   float* af_work = nullptr;  // Adafactor reduction scratch
   int64_t n_fac = 0;
@@ -373,6 +377,7 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes, s
   M.dact = b.take(T * f * es);
   M.dffn = b.take(T * fw * es);
   M.gemm_ws = M.wpk_bytes ? b.take(PACKED_WS_BYTES) : nullptr;  // shared tiles of the packed-operand contraction
+  M.rowsq = M.wpk_bytes ? (float*)b.take((size_t)M.maxT * ((M.cfg.d_model + 63) / 64) * 4) : nullptr;
   if (dev_bytes) *dev_bytes = b.used;
   if (pinned_bytes) *pinned_bytes = M.on_host ? (size_t)M.n_move * np * 4 : 0;
   if (by_cat)
@@ -442,6 +447,11 @@ hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_o
       if (epi_on && layer_t && cfg->arch == HIFT_ARCH_RMS_ROPE_DECODER && t.rows % 256 == 0) {
         if (leaf == "wqkv" && cfg->d_model / cfg->n_heads == 128) t.pk_order = PK_ORDER_PAIR64;
         if (leaf == "wgu") t.pk_order = PK_ORDER_HALVES;
+        // The normalisation in front of either goes into the contraction (Gemm::rowsq);
+        // HIFT_NORM_FOLDED=0 in the environment keeps the normalisation kernels
+        static const bool fold_on = [] { const char* e = getenv("HIFT_NORM_FOLDED"); return !(e && e[0] == '0'); }();
+        if (fold_on && t.cols % 512 == 0 && t.cols <= 6144 && t.pk_order != PK_ORDER_PLAIN)
+          t.pk_gain = M->lay.find(t.name.substr(0, t.name.find('.') + 1) + (leaf == "wqkv" ? "g1" : "g2"));
       }
     }
     g.N = t.cols; g.K = t.rows; g.lda = t.rows; g.ldc = t.cols; g.ldr = t.cols;
@@ -459,7 +469,8 @@ hipError_t repack_units(hift_model* M, int ulo, int uhi) {
   for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
     const Tensor& t = M->lay.t[i];
     if (t.pk_fwd >= 0) {
-      hipError_t e = pack_b(M->W(t), t.cols, t.rows, t.cols, true, M->wpk + t.pk_fwd, M->cs, t.pk_order);
+      hipError_t e = pack_b(M->W(t), t.cols, t.rows, t.cols, true, M->wpk + t.pk_fwd, M->cs, t.pk_order,
+                            t.pk_gain >= 0 ? M->W(M->lay.t[t.pk_gain]) : nullptr);
       if (e != hipSuccess) return e;
     }
     if (t.pk_bwd >= 0) {
@@ -513,10 +524,23 @@ struct LinEpi {
   void* act = nullptr;
   bool keep_pre = true;
   bool fused = false;
+  float* norm_stats = nullptr;  // weights with a folded normalisation: where (0, 1 / rms) per row goes, or null
 };
 
+// Whether a linear layer with this weight applies the normalisation in front of it itself: x is then the rows
+// before the normalisation, and M->rowsq must hold their sums of squares.
+bool folds_norm(const hift_model* M, const Tensor& w, int64_t rows) {
+  if (w.pk_gain < 0 || w.pk_fwd < 0) return false;
+  Gemm g;
+  g.dtype = M->dt;
+  g.M = rows; g.N = w.rows; g.K = w.cols; g.lda = w.cols; g.ldc = g.ldr = w.rows;
+  return packed_gemm_applies(g);  // alignment aside, which the arenas guarantee
+}
+
+// rowsq (optional): in, whether the sums of squares of y's rows are wanted in M->rowsq (y feeds a weight that
+// folds its normalisation); out, whether the kernel that ran left them there.
 hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, const Tensor* bias, const void* R,
-                   void* y, LinEpi* epi = nullptr) {
+                   void* y, LinEpi* epi = nullptr, bool* rowsq = nullptr) {
   // y[rows, out] = x[rows, in] . w[out, in]^T (+ bias) (+ R)
   Gemm g;
   g.dtype = M->dt;
@@ -540,11 +564,19 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
         g.cos_sin = M->cos_sin; g.S = epi->S; g.rot_cols = 2 * (int64_t)M->cfg.d_model;
       }
       epi->fused = true;
+      if (w.pk_gain >= 0) {
+        g.rowsq = M->rowsq; g.norm_eps = M->cfg.norm_eps; g.norm_stats = epi->norm_stats;
+      }
+    }
+    if (rowsq) {
+      *rowsq = *rowsq && g.epi == EPI_NONE && w.rows % 256 == 0;
+      if (*rowsq) g.rowsq_out = M->rowsq;
     }
     g.ws = M->gemm_ws;
     K_TRY(gemm_packed(g, M->wpk + w.pk_fwd, M->cs));
     return HIFT_OK;
   }
+  if (rowsq) *rowsq = false;
   if (sc.r) sc.r->cat = CAT_GEMM_REST;
   K_TRY(gemm(g, M->cs));
   return HIFT_OK;
@@ -778,18 +810,25 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
     ST_TRY(ew(M, embed_fwd(dt, bt->tokens, T, S, d, c.vocab, M->W("tok_emb"), pos, dst, st)));
     if (enc) ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, M->e0, M->W("lne_g"), M->W("lne_b"), M->xs[0], M->st_e, st)));
   }
+  bool have_sq = false;  // M->rowsq holds the sums of squares of the rows the next normalisation takes
   for (int l = 0; l < c.n_layers; ++l) {
     LayerAct& a = M->la[l];
     const Names n = layer_names(M, l);
     const void* x = M->xs[l];
     const void* h1 = x;
-    if (!enc) {
+    if (folds_norm(M, *n.wqkv, T)) {
+      if (!have_sq) {
+        Scope sc(M, CAT_ELEM, 0);
+        ST_TRY(ew(M, row_sumsq(T, d, x, d / 64, M->rowsq, st)));
+      }
+    } else if (!enc) {
       Scope sc(M, CAT_ELEM, 0);
       ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, x, M->W(*n.n1g), n.n1b ? M->W(*n.n1b) : nullptr, a.na, a.st1, st)));
       h1 = a.na;
     }
     LinEpi rot;
     rot.S = S;
+    rot.norm_stats = a.st1;
     ST_TRY(linear(M, h1, T, *n.wqkv, n.bqkv, nullptr, a.qkv, &rot));
     if (rms && !rot.fused) {
       Scope sc(M, CAT_ELEM, 0);
@@ -801,10 +840,16 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
       Scope sc(M, CAT_ELEM, 0);
       ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, a.na, M->W(*n.n1g), M->W(*n.n1b), a.xmid, a.st1, st)));
     } else {
-      ST_TRY(linear(M, a.ctx, T, *n.wo, n.bo, x, a.xmid));
+      have_sq = folds_norm(M, *n.w1, T);
+      ST_TRY(linear(M, a.ctx, T, *n.wo, n.bo, x, a.xmid, nullptr, &have_sq));
     }
     const void* h2 = a.xmid;
-    if (!enc) {
+    if (folds_norm(M, *n.w1, T)) {
+      if (!have_sq) {
+        Scope sc(M, CAT_ELEM, 0);
+        ST_TRY(ew(M, row_sumsq(T, d, a.xmid, d / 64, M->rowsq, st)));
+      }
+    } else if (!enc) {
       Scope sc(M, CAT_ELEM, 0);
       ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, a.xmid, M->W(*n.n2g), n.n2b ? M->W(*n.n2b) : nullptr, a.nb, a.st2, st)));
       h2 = a.nb;
@@ -812,6 +857,7 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
     LinEpi gate;
     gate.act = a.act;
     gate.keep_pre = l + 1 >= keep_from;
+    gate.norm_stats = a.st2;
     ST_TRY(linear(M, h2, T, *n.w1, n.b1, nullptr, a.fpre, &gate));
     if (!gate.fused) {
       Scope sc(M, CAT_ELEM, 0);
@@ -823,7 +869,8 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
       Scope sc(M, CAT_ELEM, 0);
       ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, a.nb, M->W(*n.n2g), M->W(*n.n2b), M->xs[l + 1], a.st2, st)));
     } else {
-      ST_TRY(linear(M, a.act, T, *n.w2, n.b2, a.xmid, M->xs[l + 1]));
+      have_sq = l + 1 < c.n_layers && folds_norm(M, *layer_names(M, l + 1).wqkv, T);
+      ST_TRY(linear(M, a.act, T, *n.w2, n.b2, a.xmid, M->xs[l + 1], nullptr, &have_sq));
     }
   }
   void* xl = M->xs[c.n_layers];
@@ -911,6 +958,10 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
         else ST_TRY(ew(M, gelu_bwd(dt, T * f, M->dact, a.fpre, M->dffn, st)));
       }
       if (on) {
+        if (folds_norm(M, *n.w1, T)) {  // the forward pass never wrote the normalised rows
+          Scope sc(M, CAT_ELEM, 0);
+          ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, a.xmid, M->W(*n.n2g), nullptr, a.nb, a.st2, st)));
+        }
         ST_TRY(linear_dw(M, M->dffn, a.nb, T, *n.w1, glo));
         if (n.b1) ST_TRY(bias_grad(M, M->dffn, T, *n.b1, glo));
       }
@@ -935,6 +986,10 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
         ST_TRY(ew(M, rope(dt, M->dqkv, T, S, H, hd, M->cos_sin, -1, st)));
       }
       if (on) {
+        if (folds_norm(M, *n.wqkv, T)) {
+          Scope sc(M, CAT_ELEM, 0);
+          ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, x, M->W(*n.n1g), nullptr, a.na, a.st1, st)));
+        }
         ST_TRY(linear_dw(M, M->dqkv, a.na, T, *n.wqkv, glo));
         if (n.bqkv) ST_TRY(bias_grad(M, M->dqkv, T, *n.bqkv, glo));
       }
@@ -1765,10 +1820,47 @@ hift_status hift_kernel_gemm_packed_ws(int32_t out_f32, int64_t Mm, int64_t N, i
   return HIFT_OK;
 }
 
+hift_status hift_kernel_gemm_packed_rowsq(int64_t Mm, int64_t N, int64_t K, const void* A, int64_t lda, const void* Bp,
+                                          void* C, int64_t ldc, const void* R, float* rowsq, void* workspace,
+                                          void* stream) {
+  if (!A || !Bp || !C || !rowsq) return fail(HIFT_EINVAL, "null operand");
+  if (N % 256 != 0) return fail(HIFT_EINVAL, "N must be a multiple of 256");
+  if (reinterpret_cast<uintptr_t>(workspace) & 15) return fail(HIFT_EINVAL, "work space not 16-byte aligned");
+  Gemm g;
+  g.dtype = DT_BF16;
+  g.M = Mm; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.C = C; g.ldc = ldc; g.R = R; g.ldr = ldc;
+  g.rowsq_out = rowsq;
+  g.ws = workspace;
+  if (!packed_gemm_applies(g)) return fail(HIFT_EINVAL, "problem is not one the packed-operand kernel takes");
+  HIP_TRY(gemm_packed(g, Bp, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_row_sumsq(int64_t rows, int32_t d, const void* x, int32_t n, float* out, void* stream) {
+  if (rows < 0 || d < 1 || n < 1) return fail(HIFT_EINVAL, "bad argument");
+  if (rows == 0) return HIFT_OK;
+  if (!x || !out) return fail(HIFT_EINVAL, "null operand");
+  HIP_TRY(row_sumsq(rows, d, x, n, out, (hipStream_t)stream));
+  return HIFT_OK;
+}
+
 hift_status hift_kernel_linear_fused(int32_t epilogue, int64_t Mm, int64_t N, int64_t K, const void* A, int64_t lda,
                                      const void* W, void* packed_scratch, void* C, void* aux, const float* cos_sin,
                                      int32_t seq, int64_t rot_cols, void* stream) {
+  return hift_kernel_linear_norm_fused(epilogue, Mm, N, K, A, lda, W, nullptr, packed_scratch, C, aux, cos_sin, seq,
+                                       rot_cols, nullptr, 0.f, nullptr, nullptr, stream);
+}
+
+hift_status hift_kernel_linear_norm_fused(int32_t epilogue, int64_t Mm, int64_t N, int64_t K, const void* A, int64_t lda,
+                                          const void* W, const void* gain, void* packed_scratch, void* C, void* aux,
+                                          const float* cos_sin, int32_t seq, int64_t rot_cols, const float* rowsq,
+                                          float norm_eps, float* stats, void* workspace, void* stream) {
   if (!A || !W || !packed_scratch) return fail(HIFT_EINVAL, "null operand");
+  if (reinterpret_cast<uintptr_t>(workspace) & 15) return fail(HIFT_EINVAL, "work space not 16-byte aligned");
+  if ((gain == nullptr) != (rowsq == nullptr)) return fail(HIFT_EINVAL, "gain and rowsq go together");
+  if (gain && (epilogue == HIFT_EPILOGUE_SWIGLU_BWD || K % 512 != 0 || K > 6144 || (reinterpret_cast<uintptr_t>(rowsq) & 15) != 0))
+    return fail(HIFT_EINVAL, "folded normalisation: forward epilogues only, K a multiple of 512 up to 6144, rowsq 16-byte aligned");
   if (epilogue != HIFT_EPILOGUE_SWIGLU && epilogue != HIFT_EPILOGUE_ROPE && epilogue != HIFT_EPILOGUE_SWIGLU_BWD)
     return fail(HIFT_EINVAL, "epilogue unknown");
   const bool bwd = epilogue == HIFT_EPILOGUE_SWIGLU_BWD;
@@ -1794,7 +1886,11 @@ hift_status hift_kernel_linear_fused(int32_t epilogue, int64_t Mm, int64_t N, in
   }
   if (!packed_gemm_applies(g)) return fail(HIFT_EINVAL, "problem is not one the packed-operand kernel takes");
   hipStream_t st = (hipStream_t)stream;
-  HIP_TRY(pack_b(W, K, N, K, true, packed_scratch, st, order));
+  if (gain) {
+    g.rowsq = rowsq; g.norm_eps = norm_eps; g.norm_stats = stats;
+  }
+  g.ws = workspace;
+  HIP_TRY(pack_b(W, K, N, K, true, packed_scratch, st, order, gain));
   HIP_TRY(gemm_packed(g, packed_scratch, st));
   return HIFT_OK;
 }

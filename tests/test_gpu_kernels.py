@@ -423,6 +423,137 @@ def test_gemm_with_packed_weight_operand_and_shared_last_round(M, N, K):
         assert not bad.any(), (out_f32, int(bad.sum()), float(np.max(np.abs(got - ref))))
 
 
+@pytest.mark.parametrize("M,N,K,shared", [(2048, 3328, 256, 0), (1990, 3328, 96, 0), (2048, 5120, 1024, 1)])
+def test_packed_gemm_leaves_row_sums_of_squares(M, N, K, shared):
+    """The contraction that writes rows x = A . B^T + R (bf16) also leaves, per row and 64-column strip, the sum of
+    squares of the values it stored: against the float64 product.  A stored value is within one bf16 rounding
+    (2^-9 relative, plus the accumulation) of the exact one, its square within 2^-8."""
+    import torch
+    import paper_2401_15207_amd as H
+    rng = np.random.default_rng(M + N + K + 5)
+    A = _bf16_round(rng.standard_normal((M, K)))
+    B = _bf16_round(rng.standard_normal((N, K)) * 0.5)
+    R = _bf16_round(rng.standard_normal((M, N)) * 3.0)
+    ref = A.astype(np.float64) @ B.astype(np.float64).T + R
+    dBp = torch.empty(H.kernel_packed_bytes(N, K) // 2, dtype=torch.bfloat16, device="cuda")
+    H.kernel_pack_b(1, N, K, _dev(B, True), K, dBp)
+    ws = torch.zeros(H.kernel_packed_workspace_bytes() // 4, dtype=torch.float32, device="cuda") if shared else None
+    dC = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    sq = torch.full((M, N // 64), float("nan"), dtype=torch.float32, device="cuda")
+    H.kernel_gemm_packed_rowsq(M, N, K, _dev(A, True), K, dBp, dC, N, _dev(R, True), sq, ws)
+    torch.cuda.synchronize()
+    got = dC.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 2 ** -8 * np.abs(ref) + 1e-5 * np.sqrt(K))
+    q = sq.cpu().numpy().astype(np.float64)
+    q_ref = (ref ** 2).reshape(M, N // 64, 64).sum(-1)
+    assert np.all(np.abs(q - q_ref) <= 2 ** -7 * q_ref + 1e-4)
+    # and exactly (up to the order of the fp32 sum) the squares of what was stored
+    q_own = (got ** 2).reshape(M, N // 64, 64).sum(-1)
+    assert np.all(np.abs(q - q_own) <= 1e-5 * q_own + 1e-12)
+
+
+@pytest.mark.parametrize("rows,d,n", [(2048, 4096, 64), (77, 5120, 80), (3, 520, 9), (0, 64, 1)])
+def test_row_sums_of_squares(rows, d, n):
+    import torch
+    import paper_2401_15207_amd as H
+    rng = np.random.default_rng(rows + d)
+    x = _bf16_round(rng.standard_normal((rows, d)) * 2.0)
+    out = torch.full((rows, n), float("nan"), dtype=torch.float32, device="cuda")
+    H.kernel_row_sumsq(rows, d, _dev(x, True), n, out)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy().astype(np.float64)
+    ref = (x.astype(np.float64) ** 2).sum(-1)
+    assert np.all(np.abs(o[:, 0] - ref) <= 1e-5 * ref)
+    assert np.all(o[:, 1:] == 0.0)
+
+
+def _norm_fold_slack(x, rstd, g, w):
+    """Bound on what rounding gain * W to bf16 can move rstd x . (gain W)^T: 2^-9 of the sum of magnitudes."""
+    return 2 ** -9 * ((np.abs(x) * rstd) @ np.abs(g[None, :] * w).T)
+
+
+@pytest.mark.parametrize("M,f,K,shared", [(2048, 1664, 512, 0), (1992, 1792, 1024, 0), (2048, 2560, 1024, 1)])
+def test_linear_with_rms_normalisation_folded_and_gated_activation(M, f, K, shared):
+    """silu(gate) * up of rmsnorm(x, gain) . [Wg | Wu]^T, computed from x, gain * W and the row sums of squares,
+    against the oracle's rmsnorm and swiglu on the float64 product."""
+    import torch
+    import paper_2401_15207_amd as H_
+    from oracle import hift_oracle as O
+    rng = np.random.default_rng(M + f + K + 9)
+    x = _bf16_round(rng.standard_normal((M, K)) * rng.uniform(0.3, 6.0, (M, 1)))
+    g = _bf16_round(1.0 + 0.3 * rng.standard_normal(K))
+    w = _bf16_round(rng.standard_normal((2 * f, K)) * (1.5 / np.sqrt(K)))
+    eps = 1e-5
+    h, (_, rstd) = O.rmsnorm_fwd(x.astype(np.float64), g.astype(np.float64), eps)
+    pre_ref = h @ w.astype(np.float64).T
+    slack = _norm_fold_slack(x.astype(np.float64), rstd, g.astype(np.float64), w.astype(np.float64))
+    dx = _dev(x, True)
+    sq = torch.empty((M, K // 64), dtype=torch.float32, device="cuda")
+    H_.kernel_row_sumsq(M, K, dx, K // 64, sq)
+    scratch = torch.empty(H_.kernel_packed_bytes(2 * f, K) // 2, dtype=torch.bfloat16, device="cuda")
+    pre = torch.full((M, 2 * f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    act = torch.full((M, f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    stats = torch.full((M, 2), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.zeros(H_.kernel_packed_workspace_bytes() // 4, dtype=torch.float32, device="cuda") if shared else None
+    H_.kernel_linear_norm_fused(H_.EPILOGUE_SWIGLU, M, 2 * f, K, dx, K, _dev(w, True), _dev(g, True), scratch, pre, act,
+                                None, 0, 0, sq, eps, stats, ws)
+    torch.cuda.synchronize()
+    st = stats.cpu().numpy().astype(np.float64)
+    assert np.all(st[:, 0] == 0.0)
+    assert np.all(np.abs(st[:, 1] - rstd[:, 0]) <= 1e-5 * rstd[:, 0])
+    p = pre.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(p - pre_ref) <= 2 ** -8 * np.abs(pre_ref) + slack + 1e-5)
+    a = act.float().cpu().numpy().astype(np.float64)
+    a_ref = O.swiglu_fwd(p[:, :f], p[:, f:])          # the activation is formed from the stored pre-activations
+    assert np.all(np.abs(a - a_ref) <= 2 ** -8 * np.abs(a_ref) + 1e-6)
+
+
+@pytest.mark.parametrize("M,S,heads,K", [(2048, 512, 10, 512), (1000, 200, 18, 1024)])
+def test_linear_with_rms_normalisation_folded_and_rotary_embedding(M, S, heads, K):
+    """rope(rmsnorm(x, gain) . Wqkv^T) from x, gain * W and the row sums of squares, against the oracle's
+    rmsnorm and rope on the float64 product."""
+    import torch
+    import paper_2401_15207_amd as H_
+    from oracle import hift_oracle as O
+    hd, d = 128, heads * 128
+    N = 3 * d
+    rng = np.random.default_rng(M + S + heads + K + 3)
+    x = _bf16_round(rng.standard_normal((M, K)) * rng.uniform(0.3, 6.0, (M, 1)))
+    g = _bf16_round(1.0 + 0.3 * rng.standard_normal(K))
+    w = _bf16_round(rng.standard_normal((N, K)) / np.sqrt(K))
+    eps = 1e-6
+    h, (_, rstd) = O.rmsnorm_fwd(x.astype(np.float64), g.astype(np.float64), eps)
+    y_ref = h @ w.astype(np.float64).T
+    slack = _norm_fold_slack(x.astype(np.float64), rstd, g.astype(np.float64), w.astype(np.float64))
+    cos, sin = O.rope_angles(S, hd, 10000.0, np.float64)
+    pos = np.arange(M) % S
+    rot_cols = 2 * d
+
+    def heads_of(a):
+        return a[:, :rot_cols].reshape(M, 2 * heads, hd).transpose(1, 0, 2)
+
+    blk = heads_of(y_ref)
+    mag = np.abs(y_ref).copy()
+    mag[:, :rot_cols] = (np.abs(blk) + np.abs(np.roll(blk, hd // 2, axis=-1))).transpose(1, 0, 2).reshape(M, rot_cols)
+    sblk = heads_of(slack)
+    slack[:, :rot_cols] = (sblk + np.roll(sblk, hd // 2, axis=-1)).transpose(1, 0, 2).reshape(M, rot_cols)
+    y_ref[:, :rot_cols] = O.rope_fwd(blk, cos[pos], sin[pos]).transpose(1, 0, 2).reshape(M, rot_cols)
+    tab = torch.from_numpy(np.stack([cos, sin], -1).astype(np.float32)).cuda().contiguous()
+    dx = _dev(x, True)
+    sq = torch.empty((M, K // 64), dtype=torch.float32, device="cuda")
+    H_.kernel_row_sumsq(M, K, dx, K // 64, sq)
+    scratch = torch.empty(H_.kernel_packed_bytes(N, K) // 2, dtype=torch.bfloat16, device="cuda")
+    y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    stats = torch.full((M, 2), float("nan"), dtype=torch.float32, device="cuda")
+    H_.kernel_linear_norm_fused(H_.EPILOGUE_ROPE, M, N, K, dx, K, _dev(w, True), _dev(g, True), scratch, y, None, tab, S,
+                                rot_cols, sq, eps, stats)
+    torch.cuda.synchronize()
+    st = stats.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(st[:, 1] - rstd[:, 0]) <= 1e-5 * rstd[:, 0])
+    got = y.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - y_ref) <= 2 ** -8 * np.abs(y_ref) + slack + 1e-5 * mag + 1e-6)
+
+
 @pytest.mark.parametrize("B,H,S,hd,causal,rope", [(2, 3, 200, 64, 1, 1), (1, 2, 512, 128, 1, 1), (2, 2, 136, 128, 0, 0),
                                                    (1, 2, 72, 64, 1, 0), (1, 1, 8, 128, 1, 1), (2, 4, 384, 64, 0, 1),
                                                    (4, 32, 512, 128, 1, 1)])
