@@ -8,10 +8,11 @@
 // Forward: one workgroup = 32 NW query rows of one (batch, head), NW = 2 or 4 wavefronts; each wavefront owns
 // 32 rows from start to end, so the softmax of a row never leaves its wavefront.  Keys and values pass
 // through LDS in tiles of 64 keys; the next tile is on its way from HBM (direct-to-LDS loads) while the
-// current one is used.  Two passes over the keys: the first finds each row's maximum and
-// normaliser (online), the second recomputes the scores, writes the normalised probabilities and
-// accumulates P.V from the bf16-rounded probabilities, which is exactly what separate softmax and
-// contraction kernels compute.
+// current one is used.  When the probabilities are wanted: two passes over the keys, the first finds each
+// row's maximum and normaliser (online), the second recomputes the scores, writes the normalised
+// probabilities and accumulates P.V from the bf16-rounded probabilities, which is exactly what separate
+// softmax and contraction kernels compute.  When they are not (the model's case: the backward kernels form
+// them again from the rows' log-sums): one pass with running sums, normalised at the end.
 //
 // MFMA (v_mfma_f32_32x32x16_bf16) conventions, as in gemm.hip: an operand fragment gives lane l row
 // l%32 and the eight k-values 8*(l/32)..+7; acc = mfma(X, Y, acc) leaves in lane l, element e the
@@ -258,6 +259,90 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
   using std::true_type;
 
   if constexpr (!BWD) {
+    if (prob == nullptr) {
+      // ---- one pass (nobody reads the probabilities): exponentials against a reference maximum m_ref of the row
+      // (log2 domain), which is raised, and the sums so far rescaled, only when a score exceeds it by more than
+      // 2^8: the unnormalised probabilities then stay below 2^8, which costs bf16 (a relative format) nothing.
+      // O = (sum_j p_j V_j) / (sum_j p_j) at the end. ----
+      float m = -INFINITY, l = 0.f;
+      f32x16 oacc[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[nb][e] = 0.f;
+      request(0, true);
+      for (int kt = 0; kt < n_tiles; ++kt) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (kt + 1 < n_tiles) request(kt + 1, true);
+        if (CAUSAL && kt * KTILE > q0 + 31) continue;  // wholly above the diagonal for this wavefront
+        const unsigned char* Kb = lds + (kt & 1) * (2 * TILEB);
+        const unsigned char* Vb = Kb + TILEB;
+        float s[32];
+        if (tile_plain(kt)) scores(false_type{}, Kb, kt, s, qf);
+        else scores(true_type{}, Kb, kt, s, qf);
+        float mr = s[0];
+#pragma unroll
+        for (int e = 1; e < 32; ++e) mr = fmaxf(mr, s[e]);
+        mr = fmaxf(mr, __shfl_xor(mr, 32, 64));  // the two lanes of a row must agree on the reference
+        const float cand = mr * scale_log2e;     // finite: every row has an unmasked key in every tile it visits
+        if (__builtin_amdgcn_ballot_w64(cand > m + 8.0f) != 0) {
+          const float mn = fmaxf(m, cand);
+          const float alpha = __builtin_amdgcn_exp2f(m - mn);  // 0 on the first tile (m = -inf)
+          l *= alpha;
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[nb][e] *= alpha;
+          m = mn;
+        }
+        u32x4 pk[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          bf16x8 t;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[8 * i + e], scale_log2e, -m));  // exp2(-inf) = 0
+            l += pr;
+            t[e] = static_cast<__bf16>(pr);
+          }
+          pk[i] = __builtin_bit_cast(u32x4, t);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          bf16x8 vt[NB];
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            const unsigned char* a0 = Vb + t * 16 * ROWB + vaddr[nb][0];
+            const unsigned char* a1 = Vb + t * 16 * ROWB + vaddr[nb][1];
+            const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(a0));
+            const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(a1));
+            typedef short v8i16 __attribute__((ext_vector_type(8)));
+            const v8i16 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            vt[nb] = __builtin_bit_cast(bf16x8, both);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          const bf16x8 pf = __builtin_bit_cast(bf16x8, pk[t]);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[nb], pf, oacc[nb], 0, 0, 0);
+        }
+      }
+      l += __shfl_xor(l, 32, 64);  // the two lanes of a row summed different keys
+      const float inv = l > 0.f ? 1.0f / l : 0.f;
+      if (lse && row_ok && fh == 0) lse[(int64_t)bh * S + row] = m + __builtin_amdgcn_logf(l);
+      if (row_ok) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            bf16x4 o4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(oacc[nb][4 * g + e] * inv);
+            *reinterpret_cast<bf16x4*>(O + (int64_t)row * ldc + nb * 32 + 8 * g + 4 * fh) = o4;
+          }
+      }
+      return;
+    }
     // ---- pass 1: row maximum and normaliser (m in the log2 domain: raw score * scale_log2e) ----
     float m = -INFINITY, l = 0.f;
     request(0, false);
