@@ -739,6 +739,32 @@ __global__ void __launch_bounds__(BLK) copy_stream_k(u32x4_t* __restrict__ dst, 
 }
 
 // ---------------------------------------------------------------------------- optimizer
+// fp32 loads and stores of data that is touched once per step (master weights, gradients, moments): non-temporal,
+// so that 6 GB of them do not push everything else out of the caches
+template <int V>
+__device__ __forceinline__ void ldnt(const float* p, float (&f)[V]) {
+  typedef float vt __attribute__((ext_vector_type(V)));
+  if constexpr (V == 1) {
+    f[0] = __builtin_nontemporal_load(p);
+  } else {
+    const vt t = __builtin_nontemporal_load(reinterpret_cast<const vt*>(p));
+#pragma unroll
+    for (int e = 0; e < V; ++e) f[e] = t[e];
+  }
+}
+template <int V>
+__device__ __forceinline__ void stnt(float* p, const float (&f)[V]) {
+  typedef float vt __attribute__((ext_vector_type(V)));
+  if constexpr (V == 1) {
+    __builtin_nontemporal_store(f[0], p);
+  } else {
+    vt t;
+#pragma unroll
+    for (int e = 0; e < V; ++e) t[e] = f[e];
+    __builtin_nontemporal_store(t, reinterpret_cast<vt*>(p));
+  }
+}
+
 // Group-local update over contiguous fp32 master weights.  KIND 0 AdamW (decoupled decay),
 // 1 AdaGrad, 2 SGD with momentum, 3 plain SGD.  Four parameters per thread (16-byte accesses).
 template <int KIND, int V>
@@ -750,10 +776,10 @@ __global__ void __launch_bounds__(BLK) opt_k(int64_t n, float lr, float b1, floa
   const int64_t i = ((int64_t)blockIdx.x * BLK + threadIdx.x) * V;
   if (i >= n) return;
   float th[V], g[V], a[V], b[V];
-  ldv<float, V>(master + i, th);
-  ldv<float, V>(grad + i, g);
-  if (KIND != 3) ldv<float, V>(s1 + i, a);
-  if (KIND == 0) ldv<float, V>(s2 + i, b);
+  ldnt<V>(master + i, th);
+  ldnt<V>(grad + i, g);
+  if (KIND != 3) ldnt<V>(s1 + i, a);
+  if (KIND == 0) ldnt<V>(s2 + i, b);
 #pragma unroll
   for (int e = 0; e < V; ++e) {
     if (KIND == 0) {
@@ -774,9 +800,9 @@ __global__ void __launch_bounds__(BLK) opt_k(int64_t n, float lr, float b1, floa
       th[e] -= lr * gg;
     }
   }
-  stv<float, V>(master + i, th);
-  if (KIND != 3) stv<float, V>(s1 + i, a);
-  if (KIND == 0) stv<float, V>(s2 + i, b);
+  stnt<V>(master + i, th);
+  if (KIND != 3) stnt<V>(s1 + i, a);
+  if (KIND == 0) stnt<V>(s2 + i, b);
   if (cc) stv<bf16, V>(cc + i, th);
 }
 
