@@ -391,7 +391,9 @@ hift_status hift_kernel_optimizer(const hift_opt* opt, int64_t count, int32_t de
  * qkv: device [batch*seq, 3*heads*head_dim], row = q | k | v of all heads side by side (already rotated
  * where the architecture rotates).  The scale is 1/sqrt(head_dim); causal != 0 masks keys after the query.
  * Forward: ctx: device [batch*seq, heads*head_dim].  prob: device [batch, heads, seq, seq] bf16 or NULL;
- * if given it receives the probabilities, completely (zeros where masked).  lse: device fp32
+ * if given it receives the probabilities, completely (zeros where masked), and ctx is the product of
+ * those rounded probabilities with v; if NULL the rows are normalised once at the end instead (one pass
+ * over the keys; ctx then differs from the other case in the last bf16 digit).  lse: device fp32
  * [batch*heads*seq] or NULL; if given it receives log2 of each row's sum of exponentials of the scaled
  * scores, which is all the backward needs of the softmax.
  * Backward: ctx and lse as the forward left them; dctx: device [batch*seq, heads*head_dim], gradient of
