@@ -307,7 +307,8 @@ hift_status hift_kernel_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, 
 
 /* The forward and dX contractions of large layers read the weight operand from a copy packed in
  * the register order of the matrix instruction (1 KB blocks: block (nb, kk), lane l holds
- * B[nb*32 + l%32][kk*16 + (l/32)*8 .. +7]; rows padded to a multiple of 256).
+ * B[nb*32 + pi(l%32)][kk*16 + (l/32)*8 .. +7], pi = the row index with bits 2 and 3 exchanged, which
+ * makes eight consecutive output columns land in one lane; rows padded to a multiple of 256).
  * hift_kernel_packed_bytes: size of that copy for a [N, K] operand, 0 if it cannot be packed
  * (needs N >= 256 and K a multiple of 32).  hift_kernel_pack_b: builds it from bf16 B given
  * k-major (B(n,k) at B[n*ldb + k]) or transposed (at B[k*ldb + n]).  hift_kernel_gemm_packed:

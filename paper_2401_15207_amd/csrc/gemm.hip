@@ -437,7 +437,7 @@ __device__ __forceinline__ void load_to_lds_b128(u32x4 rsrc, uint32_t lds_addr, 
 // ------------------------------------------------------------------------------------------
 // Weights do not change inside a step, so the library keeps a second copy of every large weight
 // matrix in the order the MFMA wants it: block (nb, kk) of 1 KB holds, for lane l, the 8 values
-// B[nb*32 + l%32][kk*16 + (l/32)*8 ..+7].  A wavefront loads its B fragments straight from
+// B[nb*32 + pi(l%32)][kk*16 + (l/32)*8 ..+7] (pi_row below: why the rows of a block are permuted).  A wavefront loads its B fragments straight from
 // HBM/L2 into registers with fully coalesced 1 KB loads, eight k-steps ahead; only the activation
 // operand goes through LDS.  Rows of the packed copy are padded to a multiple of 256, so no load
 // leaves the buffer.
@@ -456,6 +456,13 @@ __device__ __forceinline__ int64_t pk_block_pos(int64_t s, int order, int64_t ha
   }
   return s;
 }
+
+// Row r of a 32-row block of B sits where row pi(r) would (bits 2 and 3 of the index exchanged).  acc = mfma(B
+// fragment, A fragment, acc) leaves in lane l, element e the entry (A row l % 32, B row 8 (e / 4) + 4 (l / 32) + e % 4);
+// with the rows fed in this order, element e belongs to column 16 (e / 8) + 8 (l / 32) + e % 8 of the block: elements
+// 0..7 and 8..15 are eight consecutive columns each, 16 bytes of a bf16 output row, and the epilogues of the
+// packed-operand kernel write rows straight from the registers.
+__device__ __forceinline__ int pi_row(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
 // Product of eight bf16 pairs, each rounded once.
 __device__ __forceinline__ u32x4 scale8(u32x4 a, u32x4 b) {
@@ -476,7 +483,7 @@ __global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int6
   if (w >= n_blocks * k_steps) return;
   const int lane = threadIdx.x & 63;
   const int64_t nb = w / k_steps, kk = w % k_steps;
-  const int64_t n = nb * 32 + (lane & 31), k0 = kk * 16 + (lane >> 5) * 8;
+  const int64_t n = nb * 32 + pi_row(lane & 31), k0 = kk * 16 + (lane >> 5) * 8;
   bf16x8 v;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -520,7 +527,7 @@ __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B,
       const int64_t kk = ti * 16 + kkl;
       if (kk < k_steps)
         Bp[(pk_block_pos(nb, order, half) * k_steps + kk) * 64 + lane] =
-            *reinterpret_cast<const u32x4*>(tile + (lane & 31) * PITCH + (kkl * 16 + (lane >> 5) * 8) * 2);
+            *reinterpret_cast<const u32x4*>(tile + pi_row(lane & 31) * PITCH + (kkl * 16 + (lane >> 5) * 8) * 2);
     }
   } else {
     const int64_t kk0 = to * 2, n00 = ti * 256;
@@ -553,7 +560,7 @@ __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B,
       bf16x8 t;
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        t[e] = *reinterpret_cast<const bf16*>(tile + (kkl * 16 + (lane >> 5) * 8 + e) * PITCH + (nbl * 32 + (lane & 31)) * 2);
+        t[e] = *reinterpret_cast<const bf16*>(tile + (kkl * 16 + (lane >> 5) * 8 + e) * PITCH + (nbl * 32 + pi_row(lane & 31)) * 2);
       Bp[(pk_block_pos(ti * 8 + nbl, order, half) * k_steps + kk0 + kkl) * 64 + lane] = __builtin_bit_cast(u32x4, t);
     }
   }
@@ -579,9 +586,8 @@ constexpr int PK_SQ_MAX = 12;  // folded normalisation: 16-byte pieces of row pa
 // Fused epilogues of the packed-operand kernel (bf16 output).  The packed copy holds B's 32-row blocks in
 // an order (PK_ORDER_*) that puts, side by side in a wavefront's two accumulator columns, the blocks
 // that are combined element by element: gate and up block of the same features (EPI_SWIGLU), or a
-// block and the one 64 columns further in the same head (EPI_ROPE).  A wavefront stages 64 rows of its
-// 64 accumulator columns in LDS as fp32 and walks whole rows: lane -> (row, one of eight 8-column
-// chunks); chunks 0..3 are of the first block, 4..7 the same columns of the second.
+// block and the one 64 columns further in the same head (EPI_ROPE): both values then sit in the same
+// lane and element of the two accumulators.
 // x / (1 + e^-x) with the hardware's base-2 exponential and reciprocal (about 1e-7 relative each; the
 // library's expf and the IEEE division cost more than the memory traffic of the elementwise kernels).
 // e^-x = inf for x < -88: 1 / inf = 0 and the result is -0.
@@ -589,142 +595,139 @@ __device__ __forceinline__ float silu_fast(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
 }
 
-template <int MT, int EPI>
-__device__ __forceinline__ void store_tile_fused(const GemmP& p, f32x16 (&acc)[MT][2], unsigned char* smem, int64_t m0, int tn,
-                                                 int wave, int lane, int slot, const float* row_rstd) {
-  // m0: first row of this wavefront's sub-tile; wave: its 64-column strip (0..3) of the 256-column tile;
-  // slot: which staging region of LDS it uses
-  constexpr int RP = 64, PITCH = 64 * 4 + 16;
-  static_assert((32 * MT) % RP == 0, "whole passes");
-  const int frow = lane & 31, fhalf = lane >> 5;
-  unsigned char* reg = smem + slot * (RP * PITCH);
-  const int cc = lane & 7, rr = lane >> 3, half = cc >> 2, c4 = cc & 3;
-  // column of this lane's own chunk in C
-  const int64_t col = EPI == EPI_SWIGLU ? (int64_t)half * (p.N / 2) + 128 * (int64_t)tn + 32 * wave + 8 * c4
-                                        : 256 * (int64_t)tn + 128 * (wave >> 1) + 32 * (wave & 1) + 64 * half + 8 * c4;
+// Epilogues of the packed-operand kernel, straight from the registers (see pi_row): lane (frow, fh) holds, of tile rows
+// 32 i + frow and each of its wavefront's two 32-column blocks j, the columns 16 h + 8 fh ..+7 (h = 0, 1) as elements
+// 8 h ..+7 of acc[i][j]: a 16-byte piece of a bf16 row.  The four pieces of a row's 64 columns are stored by
+// consecutive instructions and meet again in the L2 line.  No LDS, no barrier.
+//   EPI_NONE        C = acc (+ bias) (+ R), bf16 or fp32; with rowsq_out also the sum of squares of the row's 64 stored values
+//   EPI_SWIGLU      blocks j = 0 / 1 are gate / up of the same features (PK_ORDER_HALVES)
+//   EPI_ROPE        block j = 1 lies 64 columns after block j = 0 in the same head (PK_ORDER_PAIR64)
+//   EPI_SWIGLU_BWD  acc = d act; with the forward's pre-activations g | u (C2, [M, 2 N]) writes d g = d act u s (1 + g (1 - s))
+//                   and d u = d act g s, s = 1 / (1 + e^-g), to C [M, 2 N]
+// row_rstd (forward epilogues, or null): the folded row normalisation's factor per tile row.
+template <int MT, typename OutT, int EPI>
+__device__ __forceinline__ void store_tile_regs(const GemmP& p, f32x16 (&acc)[MT][2], int64_t m0, int64_t n0, int tn, int wave,
+                                                int lane, const float* row_rstd) {
+  const int frow = lane & 31, fh = lane >> 5;
   bf16* C = reinterpret_cast<bf16*>(p.C);
+  auto round8 = [](const float (&x)[8]) __attribute__((always_inline)) {
+    bf16x8 t;
 #pragma unroll
-  for (int pass = 0; pass < 32 * MT / RP; ++pass) {
-    __syncthreads();  // operand tiles (first pass) or the previous pass are no longer read
+    for (int e = 0; e < 8; ++e) t[e] = static_cast<__bf16>(x[e]);
+    return t;
+  };
 #pragma unroll
-    for (int ii = 0; ii < RP / 32; ++ii) {
-      const int i = pass * (RP / 32) + ii;
-      // folded row normalisation: every accumulator of a lane belongs to tile row 32 i + frow
-      const float r = row_rstd ? row_rstd[32 * i + frow] : 1.0f;
+  for (int i = 0; i < MT; ++i) {
+    const int64_t row = m0 + 32 * i + frow;
+    const bool ok = row < p.M;
+    const float rs = row_rstd ? row_rstd[32 * i + frow] : 1.0f;
+    if constexpr (EPI == EPI_NONE) {
+      float q = 0.f;
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-          if (row_rstd) v *= r;
-          *reinterpret_cast<f32x4*>(reg + (ii * 32 + frow) * PITCH + (j * 32 + 8 * g + 4 * fhalf) * 4) = v;
-        }
-    }
-    __syncthreads();
-    if (EPI == EPI_SWIGLU && C) {  // the pre-activations: each lane its own chunk, 8 rows per sweep
-#pragma unroll 2
-      for (int it = 0; it < RP / 8; ++it) {
-        const int lr = it * 8 + rr;
-        const int64_t row = m0 + pass * RP + lr;
-        if (row >= p.M) continue;
-        const f32x4 lo = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + cc * 32);
-        const f32x4 hi = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + cc * 32 + 16);
-        bf16x8 t;
+        for (int h = 0; h < 2; ++h) {
+          const int64_t col = n0 + wave * 64 + j * 32 + 16 * h + 8 * fh;
+          if (!ok || col >= p.N) continue;
+          float x[8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { t[e] = static_cast<__bf16>(lo[e]); t[4 + e] = static_cast<__bf16>(hi[e]); }
-        *reinterpret_cast<bf16x8*>(C + row * p.ldc + col) = t;
+          for (int e = 0; e < 8; ++e) x[e] = acc[i][j][8 * h + e];
+          if (p.bias) {
+            const bf16x8 bv = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16*>(p.bias) + col);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] += static_cast<float>(bv[e]);
+          }
+          if constexpr (sizeof(OutT) == 2) {
+            if (p.R) {
+              const bf16x8 rv = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16*>(p.R) + row * p.ldr + col);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) x[e] += static_cast<float>(rv[e]);
+            }
+            const bf16x8 t = round8(x);
+            *reinterpret_cast<bf16x8*>(C + row * p.ldc + col) = t;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) q += static_cast<float>(t[e]) * static_cast<float>(t[e]);
+          } else {
+            float* cp = reinterpret_cast<float*>(p.C) + row * p.ldc + col;
+            if (p.R) {
+              const float* rp = reinterpret_cast<const float*>(p.R) + row * p.ldr + col;
+              const f32x4 r0 = *reinterpret_cast<const f32x4*>(rp), r1 = *reinterpret_cast<const f32x4*>(rp + 4);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) { x[e] += r0[e]; x[4 + e] += r1[e]; }
+            }
+            *reinterpret_cast<f32x4*>(cp) = f32x4{x[0], x[1], x[2], x[3]};
+            *reinterpret_cast<f32x4*>(cp + 4) = f32x4{x[4], x[5], x[6], x[7]};
+          }
+        }
+      if constexpr (sizeof(OutT) == 2) {
+        if (p.rowsq_out) {  // N is a whole number of strips here; the row's other half is in lane + 32
+          q += __shfl_xor(q, 32, 64);
+          if (ok && fh == 0) p.rowsq_out[row * (p.N / 64) + (n0 >> 6) + wave] = q;
+        }
       }
-    }
-    // the combining step: lane -> (row, 8 columns of the first block and the same of the second), 16 rows per sweep
-    const int q4 = lane & 3, r16 = lane >> 2;
-#pragma unroll 2
-    for (int it = 0; it < RP / 16; ++it) {
-      const int lr = it * 16 + r16;
-      const int64_t row = m0 + pass * RP + lr;
-      if (row >= p.M) continue;
-      float x1[8], x2[8];
-      *reinterpret_cast<f32x4*>(x1) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + q4 * 32);
-      *reinterpret_cast<f32x4*>(x1 + 4) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + q4 * 32 + 16);
-      *reinterpret_cast<f32x4*>(x2) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + (q4 + 4) * 32);
-      *reinterpret_cast<f32x4*>(x2 + 4) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + (q4 + 4) * 32 + 16);
-      if (EPI == EPI_SWIGLU) {  // x1 = gate, x2 = up: the activation from the values as they are stored
-        bf16x8 a;
+    } else if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float g = static_cast<float>(static_cast<__bf16>(x1[e])), u = static_cast<float>(static_cast<__bf16>(x2[e]));
-          a[e] = static_cast<__bf16>(silu_fast(g) * u);
+      for (int h = 0; h < 2; ++h) {
+        const int64_t feat = 128 * (int64_t)tn + 32 * wave + 16 * h + 8 * fh;
+        if (!ok) continue;
+        float g[8], u[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { g[e] = acc[i][0][8 * h + e] * rs; u[e] = acc[i][1][8 * h + e] * rs; }
+        const bf16x8 gb = round8(g), ub = round8(u);
+        if (C) {
+          *reinterpret_cast<bf16x8*>(C + row * p.ldc + feat) = gb;
+          *reinterpret_cast<bf16x8*>(C + row * p.ldc + p.N / 2 + feat) = ub;
         }
-        *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(p.C2) + row * p.ldc2 + 128 * (int64_t)tn + 32 * wave + 8 * q4) = a;
-      } else {
-        const int64_t c1 = 256 * (int64_t)tn + 128 * (wave >> 1) + 32 * (wave & 1) + 8 * q4;  // x1's column; x2's is 64 further
-        bf16x8 t1, t2;
+        float a[8];  // the activation from the values as they are stored
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] = silu_fast(static_cast<float>(gb[e])) * static_cast<float>(ub[e]);
+        *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(p.C2) + row * p.ldc2 + feat) = round8(a);
+      }
+    } else if constexpr (EPI == EPI_ROPE) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int fq = 32 * (wave & 1) + 16 * h + 8 * fh;  // frequency index = column within the first half of the head
+        const int64_t c1 = 256 * (int64_t)tn + 128 * (wave >> 1) + fq;  // x1's column; x2's is 64 further
+        if (!ok) continue;
+        float x1[8], x2[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { x1[e] = acc[i][0][8 * h + e] * rs; x2[e] = acc[i][1][8 * h + e] * rs; }
         if (c1 < p.rot_cols) {
-          // pairs (x1, x2) at frequencies 32 (wave & 1) + 8 q4 ..+7:  x1' = x1 cos - x2 sin,  x2' = x2 cos + x1 sin
-          const float2* cs = p.cos_sin + (int64_t)((uint32_t)row % (uint32_t)p.S) * 64 + 32 * (wave & 1) + 8 * q4;
+          // pairs (x1, x2):  x1' = x1 cos - x2 sin,  x2' = x2 cos + x1 sin
+          const float2* cs = p.cos_sin + (int64_t)((uint32_t)row % (uint32_t)p.S) * 64 + fq;
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const float2 c = cs[e];
-            t1[e] = static_cast<__bf16>(x1[e] * c.x - x2[e] * c.y);
-            t2[e] = static_cast<__bf16>(x2[e] * c.x + x1[e] * c.y);
+            const float y1 = x1[e] * c.x - x2[e] * c.y, y2 = x2[e] * c.x + x1[e] * c.y;
+            x1[e] = y1;
+            x2[e] = y2;
           }
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) { t1[e] = static_cast<__bf16>(x1[e]); t2[e] = static_cast<__bf16>(x2[e]); }
         }
-        *reinterpret_cast<bf16x8*>(C + row * p.ldc + c1) = t1;
-        *reinterpret_cast<bf16x8*>(C + row * p.ldc + c1 + 64) = t2;
+        *reinterpret_cast<bf16x8*>(C + row * p.ldc + c1) = round8(x1);
+        *reinterpret_cast<bf16x8*>(C + row * p.ldc + c1 + 64) = round8(x2);
       }
-    }
-  }
-}
-
-// Epilogue of dX through the down projection of the gated feed-forward block: the accumulators are d act;
-// with the forward's pre-activations g | u (C2, [M, 2 N]) it writes d g = d act u s (1 + g (1 - s)) and
-// d u = d act g s, s = 1 / (1 + e^-g), to C [M, 2 N].  Plain block order; staging and row walk as in store_tile.
-template <int MT>
-__device__ __forceinline__ void store_tile_gate_bwd(const GemmP& p, f32x16 (&acc)[MT][2], unsigned char* smem, int64_t m0, int64_t n0,
-                                                    int wave, int lane) {
-  constexpr int RP = 64, PITCH = 64 * 4 + 16;
-  const int frow = lane & 31, fhalf = lane >> 5;
-  unsigned char* reg = smem + wave * (RP * PITCH);
-  const int cc = lane & 7, rr = lane >> 3;
-  const int64_t col = n0 + wave * 64 + cc * 8;
-  bf16* C = reinterpret_cast<bf16*>(p.C);
-  const bf16* GU = reinterpret_cast<const bf16*>(p.C2);
-#pragma unroll
-  for (int pass = 0; pass < 32 * MT / RP; ++pass) {
-    __syncthreads();
-#pragma unroll
-    for (int ii = 0; ii < RP / 32; ++ii)
+    } else {
+      const bf16* GU = reinterpret_cast<const bf16*>(p.C2);
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int i = pass * (RP / 32) + ii;
-          const f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-          *reinterpret_cast<f32x4*>(reg + (ii * 32 + frow) * PITCH + (j * 32 + 8 * g + 4 * fhalf) * 4) = v;
-        }
-    __syncthreads();
-#pragma unroll 2
-    for (int it = 0; it < RP / 8; ++it) {
-      const int lr = it * 8 + rr;
-      const int64_t row = m0 + pass * RP + lr;
-      if (row >= p.M || col >= p.N) continue;
-      float da[8];
-      *reinterpret_cast<f32x4*>(da) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + cc * 32);
-      *reinterpret_cast<f32x4*>(da + 4) = *reinterpret_cast<const f32x4*>(reg + lr * PITCH + cc * 32 + 16);
-      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(GU + row * p.ldc2 + col);
-      const bf16x8 uv = *reinterpret_cast<const bf16x8*>(GU + row * p.ldc2 + p.N + col);
-      bf16x8 dg, du;
+        for (int h = 0; h < 2; ++h) {
+          const int64_t col = n0 + wave * 64 + j * 32 + 16 * h + 8 * fh;
+          if (!ok || col >= p.N) continue;
+          const bf16x8 gv = *reinterpret_cast<const bf16x8*>(GU + row * p.ldc2 + col);
+          const bf16x8 uv = *reinterpret_cast<const bf16x8*>(GU + row * p.ldc2 + p.N + col);
+          float dg[8], du[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float g = static_cast<float>(gv[e]), u = static_cast<float>(uv[e]);
-        const float s = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
-        dg[e] = static_cast<__bf16>(da[e] * u * s * (1.0f + g * (1.0f - s)));
-        du[e] = static_cast<__bf16>(da[e] * g * s);
-      }
-      *reinterpret_cast<bf16x8*>(C + row * p.ldc + col) = dg;
-      *reinterpret_cast<bf16x8*>(C + row * p.ldc + p.N + col) = du;
+          for (int e = 0; e < 8; ++e) {
+            const float da = acc[i][j][8 * h + e];
+            const float g = static_cast<float>(gv[e]), u = static_cast<float>(uv[e]);
+            const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+            dg[e] = da * u * sg * (1.0f + g * (1.0f - sg));
+            du[e] = da * g * sg;
+          }
+          *reinterpret_cast<bf16x8*>(C + row * p.ldc + col) = round8(dg);
+          *reinterpret_cast<bf16x8*>(C + row * p.ldc + p.N + col) = round8(du);
+        }
     }
   }
 }
@@ -901,7 +904,7 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
       q += __shfl_xor(q, 1);
       const float rstd = 1.0f / sqrtf(q / (float)p.K + p.norm_eps);
       if ((tid & 1) == 0) {
-        row_rstd[r] = rstd;  // read after the epilogue's first barrier
+        row_rstd[r] = rstd;
         if (p.norm_stats && tn == 0 && part == 0 && row < p.M) {  // what the normalisation's backward reads
           p.norm_stats[2 * row] = 0.f;
           p.norm_stats[2 * row + 1] = rstd;
@@ -958,9 +961,10 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
         }
   }
 
-  if constexpr (EPI == EPI_NONE) store_tile<BM, WN, VEC_EPI, OutT>(p, acc, smem, m0, n0, 0, wave, wave, lane, 0, 0);
-  else if constexpr (EPI == EPI_SWIGLU_BWD) store_tile_gate_bwd<MT>(p, acc, smem, m0, n0, wave, lane);
-  else store_tile_fused<MT, EPI>(p, acc, smem, m0, tn, wave, lane, wave, p.rowsq ? row_rstd : nullptr);
+  if constexpr (NORM_EPI) {
+    if (p.rowsq) __syncthreads();  // row_rstd is complete
+  }
+  store_tile_regs<MT, OutT, EPI>(p, acc, m0, n0, tn, wave, lane, NORM_EPI && p.rowsq ? row_rstd : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1164,9 +1168,7 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   }
   const u32x4* bp = reinterpret_cast<const u32x4*>(Bp);
   p.tiles_n = (int)((p.N + 255) / 256);
-  constexpr int OPER = PK_STAGES * 32 * PK_MT * PK_ROW;  // ring of A stages
-  constexpr int STAGE = 4 * 64 * (64 * 4 + 16);          // fp32 epilogue staging, 4 waves
-  constexpr int LDS = STAGE > OPER ? STAGE : OPER;
+  constexpr int LDS = PK_STAGES * 32 * PK_MT * PK_ROW;  // ring of A stages
   static_assert(LDS <= 160 * 1024, "LDS of a gfx950 compute unit");
   p.tiles_m = (int)((p.M + 32 * PK_MT - 1) / (32 * PK_MT));
   // The last round: if at most half the compute units would have a tile, 2 to 4 workgroups share each

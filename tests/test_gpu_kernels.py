@@ -134,10 +134,13 @@ def test_pack_of_unaligned_source_matches_aligned(bk):
     torch.cuda.synchronize()
     a, b = p1.view(torch.int16).cpu().numpy(), p2.view(torch.int16).cpu().numpy()
     assert np.array_equal(a, b)
-    # block (nb, kk), lane l, element e  <-  B[nb*32 + l%32][kk*16 + (l/32)*8 + e]
+    # block (nb, kk), lane l, element e  <-  B[nb*32 + pi(l%32)][kk*16 + (l/32)*8 + e], pi = bits 2 and 3 exchanged
     blk = a.view(np.uint16).reshape(-1, K // 16, 64, 8)
     want = np.zeros((blk.shape[0] * 32, K), np.float32)
     want[:N] = B
+    r = np.arange(32)
+    pi = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1)
+    want = want.reshape(-1, 32, K)[:, pi, :]
     want = want.reshape(-1, 32, K // 16, 2, 8).transpose(0, 2, 3, 1, 4).reshape(blk.shape)
     assert np.array_equal((blk.astype(np.uint32) << 16).view(np.float32), want)
 
