@@ -226,19 +226,6 @@ __device__ __forceinline__ void store_tile(const GemmP& p, f32x16 (&acc)[WM / 32
 #pragma unroll
           for (int e = 0; e < 4; ++e) { t[e] = static_cast<__bf16>(lo[e]); t[4 + e] = static_cast<__bf16>(hi[e]); }
           *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(C) + row * p.ldc + col) = t;
-          if constexpr (WN == 64) {
-            if (p.rowsq_out) {
-              // sum of squares of this row's 64 stored values of the strip (the eight lanes of a row are
-              // all here: N is a whole number of strips), one partial per row and strip
-              float q = 0.f;
-#pragma unroll
-              for (int e = 0; e < 8; ++e) { const float f = static_cast<float>(t[e]); q += f * f; }
-              q += __shfl_xor(q, 1);
-              q += __shfl_xor(q, 2);
-              q += __shfl_xor(q, 4);
-              if (cc == 0) p.rowsq_out[row * (p.N / 64) + (n0 + wn * WN) / 64] = q;
-            }
-          }
         } else {
           float* cp = reinterpret_cast<float*>(C) + row * p.ldc + col;
           if (R) {
