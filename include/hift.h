@@ -380,6 +380,20 @@ hift_status hift_kernel_linear_norm_fused(int32_t epilogue, int64_t M, int64_t N
                                           int64_t rot_cols, const float* rowsq, float norm_eps,
                                           float* stats, void* workspace, void* stream);
 
+/* A linear layer followed by GELU (erf form), or the dX contraction through the layer after it followed by
+ * GELU's derivative, with the elementwise step in the contraction's epilogue (forward and backward of
+ * Algorithm 1 step h for the feed-forward block of the GELU architectures; bf16).  A: device [M, K] (row
+ * stride lda); W: device [N, K] bf16, contiguous; packed_scratch as for hift_kernel_linear_fused.
+ *   backward = 0: bias device bf16 [N] or NULL; C: device [M, N] or NULL, the rounded pre-activations
+ *     A . W^T + bias; aux: device [M, N], receives gelu of the rounded pre-activations.
+ *   backward = 1: A . W^T is the gradient of the activation and is not stored; aux: device [M, N], the
+ *     forward's pre-activations (read only); C: device [M, N], receives that gradient times gelu'(pre).
+ * erf is evaluated by a formula with absolute error below 1.5e-7.  N a multiple of 8; HIFT_EINVAL for
+ * problems the packed-operand kernel does not take. */
+hift_status hift_kernel_linear_gelu(int32_t backward, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                                    const void* W, const void* bias, void* packed_scratch, void* C, void* aux,
+                                    void* stream);
+
 /* Group-local optimizer update on `count` contiguous parameters (the update inside Algorithm 1's
  * backward step): master, grad, state1, state2 fp32; compute_copy (bf16, may be NULL) receives the
  * rounded new values.  t is the group's update number (1 on its first update). */

@@ -103,6 +103,7 @@ _SIGS = {
     "hift_kernel_row_sumsq": [_i64, _i32, _vp, _i32, _vp, _vp],
     "hift_kernel_linear_norm_fused": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _vp,
                                       C.c_float, _vp, _vp, _vp],
+    "hift_kernel_linear_gelu": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_attention_fwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_attention_bwd": [_i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_cross_entropy": [_i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp],
@@ -267,6 +268,13 @@ def kernel_linear_norm_fused(epilogue, M, N, K, A, lda, W, gain, packed_scratch,
     _check(lib.hift_kernel_linear_norm_fused(epilogue, M, N, K, _ptr(A), lda, _ptr(W), _ptr(gain), _ptr(packed_scratch),
                                              _ptr(Cm), _ptr(aux), _ptr(cos_sin), seq, rot_cols, _ptr(rowsq), norm_eps,
                                              _ptr(stats), _ptr(workspace), st))
+
+
+def kernel_linear_gelu(backward, M, N, K, A, lda, W, bias, packed_scratch, Cm, aux, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_linear_gelu(int(backward), M, N, K, _ptr(A), lda, _ptr(W), _ptr(bias), _ptr(packed_scratch),
+                                       _ptr(Cm), _ptr(aux), st))
 
 
 def kernel_attention_fwd(batch, heads, seq, head_dim, causal, qkv, prob, ctx, lse=None, stream=None):

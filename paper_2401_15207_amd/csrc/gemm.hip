@@ -582,6 +582,21 @@ __device__ __forceinline__ float silu_fast(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
 }
 
+// erf by formula 7.1.26 of Abramowitz and Stegun (absolute error below 1.5e-7, far inside bf16), with the hardware's
+// reciprocal and base-2 exponential: the library's erff would make an epilogue issue-bound.
+__device__ __forceinline__ float erf_fast(float z) {
+  const float a = fabsf(z);
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * a);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  return copysignf(1.0f - poly * __builtin_amdgcn_exp2f(-1.4426950408889634f * a * a), z);
+}
+// x Phi(x) and its derivative Phi(x) + x phi(x)
+__device__ __forceinline__ float gelu_fast(float x) { return 0.5f * x * (1.0f + erf_fast(0.70710678118654752f * x)); }
+__device__ __forceinline__ float gelu_grad_fast(float x) {
+  return 0.5f * (1.0f + erf_fast(0.70710678118654752f * x)) +
+         x * 0.3989422804014327f * __builtin_amdgcn_exp2f(-0.72134752044448170f * x * x);
+}
+
 // Epilogues of the packed-operand kernel, straight from the registers (see pi_row): lane (frow, fh) holds, of tile rows
 // 32 i + frow and each of its wavefront's two 32-column blocks j, the columns 16 h + 8 fh ..+7 (h = 0, 1) as elements
 // 8 h ..+7 of acc[i][j]: a 16-byte piece of a bf16 row.  The four pieces of a row's 64 columns are stored by
@@ -591,6 +606,8 @@ __device__ __forceinline__ float silu_fast(float x) {
 //   EPI_ROPE        block j = 1 lies 64 columns after block j = 0 in the same head (PK_ORDER_PAIR64)
 //   EPI_SWIGLU_BWD  acc = d act; with the forward's pre-activations g | u (C2, [M, 2 N]) writes d g = d act u s (1 + g (1 - s))
 //                   and d u = d act g s, s = 1 / (1 + e^-g), to C [M, 2 N]
+//   EPI_GELU        pre = acc + bias to C (if given), gelu of the rounded pre to C2
+//   EPI_GELU_BWD    acc = d act; with the forward's pre-activations (C2) writes d act gelu'(pre) to C
 // row_rstd (forward epilogues, or null): the folded row normalisation's factor per tile row.
 template <int MT, typename OutT, int EPI>
 __device__ __forceinline__ void store_tile_regs(const GemmP& p, f32x16 (&acc)[MT][2], int64_t m0, int64_t n0, int tn, int wave,
@@ -693,6 +710,35 @@ __device__ __forceinline__ void store_tile_regs(const GemmP& p, f32x16 (&acc)[MT
         *reinterpret_cast<bf16x8*>(C + row * p.ldc + c1) = round8(x1);
         *reinterpret_cast<bf16x8*>(C + row * p.ldc + c1 + 64) = round8(x2);
       }
+    } else if constexpr (EPI == EPI_GELU || EPI == EPI_GELU_BWD) {
+      bf16* C2 = reinterpret_cast<bf16*>(p.C2);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int64_t col = n0 + wave * 64 + j * 32 + 16 * h + 8 * fh;
+          if (!ok || col >= p.N) continue;
+          float x[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) x[e] = acc[i][j][8 * h + e];
+          if constexpr (EPI == EPI_GELU) {
+            if (p.bias) {
+              const bf16x8 bv = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16*>(p.bias) + col);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) x[e] += static_cast<float>(bv[e]);
+            }
+            const bf16x8 pb = round8(x);
+            if (C) *reinterpret_cast<bf16x8*>(C + row * p.ldc + col) = pb;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = gelu_fast(static_cast<float>(pb[e]));  // from the values as they are stored
+            *reinterpret_cast<bf16x8*>(C2 + row * p.ldc2 + col) = round8(x);
+          } else {
+            const bf16x8 pv = *reinterpret_cast<const bf16x8*>(C2 + row * p.ldc2 + col);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] *= gelu_grad_fast(static_cast<float>(pv[e]));
+            *reinterpret_cast<bf16x8*>(C + row * p.ldc + col) = round8(x);
+          }
+        }
     } else {
       const bf16* GU = reinterpret_cast<const bf16*>(p.C2);
 #pragma unroll
@@ -1127,8 +1173,8 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   p.bias = g.bias; p.R = g.R; p.ldr = g.ldr;
   p.nh = 1; p.sa1 = p.sa2 = p.sb1 = p.sb2 = p.sc1 = p.sc2 = 0;
   if (g.epi != EPI_NONE) {
-    // the fused epilogues write bf16 rows in 16-byte pieces and take neither bias nor residual
-    if (g.out_f32 || g.bias || g.R) return hipErrorInvalidValue;
+    // the fused epilogues write bf16 rows in 16-byte pieces and take neither bias (but for EPI_GELU) nor residual
+    if (g.out_f32 || (g.bias && g.epi != EPI_GELU) || g.R) return hipErrorInvalidValue;
     if (g.epi == EPI_SWIGLU) {
       if (g.N % 256 != 0 || !g.C2 || !al16(g.C2) || g.ldc2 % 8 != 0 || g.ldc2 < g.N / 2) return hipErrorInvalidValue;
     } else if (g.epi == EPI_ROPE) {
@@ -1137,6 +1183,9 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
         return hipErrorInvalidValue;
     } else if (g.epi == EPI_SWIGLU_BWD) {
       if (g.N % 8 != 0 || !g.C || !g.C2 || !al16(g.C2) || g.ldc2 % 8 != 0 || g.ldc2 < 2 * g.N || g.ldc < 2 * g.N)
+        return hipErrorInvalidValue;
+    } else if (g.epi == EPI_GELU || g.epi == EPI_GELU_BWD) {
+      if (g.N % 8 != 0 || !g.C2 || !al16(g.C2) || g.ldc2 % 8 != 0 || g.ldc2 < g.N || (g.epi == EPI_GELU_BWD && !g.C))
         return hipErrorInvalidValue;
     } else {
       return hipErrorInvalidValue;
@@ -1179,6 +1228,8 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   if (g.epi == EPI_SWIGLU) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_SWIGLU>>(grid, 256, LDS, st, p, bp);
   if (g.epi == EPI_ROPE) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_ROPE>>(grid, 256, LDS, st, p, bp);
   if (g.epi == EPI_SWIGLU_BWD) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_SWIGLU_BWD>>(grid, 256, LDS, st, p, bp);
+  if (g.epi == EPI_GELU) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_GELU>>(grid, 256, LDS, st, p, bp);
+  if (g.epi == EPI_GELU_BWD) return launch_pk<gemm_pk_k<PK_MT, true, bf16, EPI_GELU_BWD>>(grid, 256, LDS, st, p, bp);
   return launch_pk<gemm_pk_k<PK_MT, true, bf16>>(grid, 256, LDS, st, p, bp);
 }
 

@@ -39,6 +39,11 @@ struct Gemm {
   //               cos_sin: [>= S, 64] pairs (cos, sin), fp32.
   //   EPI_SWIGLU_BWD  (plain block order) the product is d act [M, N]; C2 holds the forward's pre-activations
   //               gate | up [M, 2 N] (ldc2, read only); C [M, 2 N] (ldc) receives d gate | d up.  d act is not stored.
+  //   EPI_GELU    (plain block order; bias allowed) C [M, N] (may be null: not kept) receives the pre-activations
+  //               A . B^T + bias; C2 [M, N] (ldc2) receives gelu of the rounded pre-activations (erf form; erf by a
+  //               formula with absolute error below 1.5e-7).
+  //   EPI_GELU_BWD  (plain block order) the product is d act [M, N]; C2 holds the forward's pre-activations [M, N]
+  //               (ldc2, read only); C [M, N] receives d act * gelu'(pre).  d act is not stored.
   int epi = 0;
   void* C2 = nullptr; int64_t ldc2 = 0;
   const void* cos_sin = nullptr; int S = 0; int64_t rot_cols = 0;
@@ -58,7 +63,7 @@ struct Gemm {
   const float* rowsq = nullptr; float norm_eps = 0.f; float* norm_stats = nullptr;
 };
 constexpr size_t PACKED_WS_BYTES = 1024 + size_t(256) * 128 * 256 * 4;
-enum { EPI_NONE = 0, EPI_SWIGLU = 1, EPI_ROPE = 2, EPI_SWIGLU_BWD = 3 };
+enum { EPI_NONE = 0, EPI_SWIGLU = 1, EPI_ROPE = 2, EPI_SWIGLU_BWD = 3, EPI_GELU = 4, EPI_GELU_BWD = 5 };
 enum { BAND_NONE = 0, BAND_SKIP_UPPER = 1, BAND_K_UPTO_ROW = 2, BAND_K_FROM_ROW = 3 };
 // variant (optional) receives which kernel ran: 0 plain FMA, 1 MFMA 128x128 tiles, 2 MFMA 256x256 tiles
 hipError_t gemm(const Gemm& g, hipStream_t st, int* variant = nullptr);

@@ -525,6 +525,7 @@ struct LinEpi {
   bool keep_pre = true;
   bool fused = false;
   float* norm_stats = nullptr;  // weights with a folded normalisation: where (0, 1 / rms) per row goes, or null
+  bool gelu = false;            // plain block order: bias and GELU in the epilogue (act [rows, out]; keep_pre as above)
 };
 
 // Whether a linear layer with this weight applies the normalisation in front of it itself: x is then the rows
@@ -567,6 +568,14 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
       if (w.pk_gain >= 0) {
         g.rowsq = M->rowsq; g.norm_eps = M->cfg.norm_eps; g.norm_stats = epi->norm_stats;
       }
+    } else if (epi && epi->gelu && epi->act && !R && w.rows % 8 == 0) {
+      static const bool epi_on = [] { const char* e = getenv("HIFT_EPI_FUSED"); return !(e && e[0] == '0'); }();
+      if (epi_on) {
+        g.epi = EPI_GELU;
+        g.C2 = epi->act; g.ldc2 = w.rows;
+        if (!epi->keep_pre) g.C = nullptr;
+        epi->fused = true;
+      }
     }
     if (rowsq) {
       *rowsq = *rowsq && g.epi == EPI_NONE && w.rows % 256 == 0;
@@ -585,8 +594,9 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
 // gate_pre / dgu: if given and the packed kernel takes the problem, dx (the gradient of the gated activation,
 // [rows, in]) is not stored; the epilogue turns it into the gradient of gate | up ([rows, 2 in]) with the forward's
 // pre-activations and *fused is set.  Otherwise dx is written and the caller runs the separate kernel.
+// gelu: the activation was GELU: gate_pre is [rows, in] and dgu [rows, in] receives d act * gelu'(pre).
 hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor& w, const void* R, void* dx,
-                      const void* gate_pre = nullptr, void* dgu = nullptr, bool* fused = nullptr) {
+                      const void* gate_pre = nullptr, void* dgu = nullptr, bool* fused = nullptr, bool gelu = false) {
   // dx[rows, in] = dy[rows, out] . w[out, in] (+ R)
   Gemm g;
   g.dtype = M->dt;
@@ -600,9 +610,10 @@ hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor&
     static const bool epi_on = [] { const char* e = getenv("HIFT_EPI_FUSED"); return !(e && e[0] == '0'); }();
     if (epi_on && gate_pre && dgu && fused && !R && w.cols % 8 == 0 && (reinterpret_cast<uintptr_t>(dgu) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(gate_pre) & 15) == 0) {
-      g.epi = EPI_SWIGLU_BWD;
-      g.C2 = const_cast<void*>(gate_pre); g.ldc2 = 2 * w.cols;
-      g.C = dgu; g.ldc = 2 * w.cols;
+      const int64_t width = gelu ? w.cols : 2 * w.cols;
+      g.epi = gelu ? EPI_GELU_BWD : EPI_SWIGLU_BWD;
+      g.C2 = const_cast<void*>(gate_pre); g.ldc2 = width;
+      g.C = dgu; g.ldc = width;
       *fused = true;
     }
     g.ws = M->gemm_ws;
@@ -858,6 +869,7 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
     gate.act = a.act;
     gate.keep_pre = l + 1 >= keep_from;
     gate.norm_stats = a.st2;
+    gate.gelu = !rms;
     ST_TRY(linear(M, h2, T, *n.w1, n.b1, nullptr, a.fpre, &gate));
     if (!gate.fused) {
       Scope sc(M, CAT_ELEM, 0);
@@ -951,7 +963,7 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
       }
       bool gate_done = false;
       if (rms) ST_TRY(linear_dx(M, Dc, T, *n.w2, nullptr, M->dact, a.fpre, M->dffn, &gate_done));
-      else ST_TRY(linear_dx(M, Dc, T, *n.w2, nullptr, M->dact));
+      else ST_TRY(linear_dx(M, Dc, T, *n.w2, nullptr, M->dact, a.fpre, M->dffn, &gate_done, true));
       if (!gate_done) {
         Scope sc(M, CAT_ELEM, 0);
         if (rms) ST_TRY(ew(M, swiglu_bwd(dt, T, f, M->dact, a.fpre, M->dffn, st)));
@@ -1012,8 +1024,9 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
         ST_TRY(linear_dw(M, D1, a.act, T, *n.w2, glo));
         ST_TRY(bias_grad(M, D1, T, *n.b2, glo));
       }
-      ST_TRY(linear_dx(M, D1, T, *n.w2, nullptr, M->dact));
-      {
+      bool gelu_done = false;
+      ST_TRY(linear_dx(M, D1, T, *n.w2, nullptr, M->dact, a.fpre, M->dffn, &gelu_done, true));
+      if (!gelu_done) {
         Scope sc(M, CAT_ELEM, 0);
         ST_TRY(ew(M, gelu_bwd(dt, T * f, M->dact, a.fpre, M->dffn, st)));
       }
@@ -1891,6 +1904,25 @@ hift_status hift_kernel_linear_norm_fused(int32_t epilogue, int64_t Mm, int64_t 
   }
   g.ws = workspace;
   HIP_TRY(pack_b(W, K, N, K, true, packed_scratch, st, order, gain));
+  HIP_TRY(gemm_packed(g, packed_scratch, st));
+  return HIFT_OK;
+}
+
+hift_status hift_kernel_linear_gelu(int32_t backward, int64_t Mm, int64_t N, int64_t K, const void* A, int64_t lda,
+                                    const void* W, const void* bias, void* packed_scratch, void* C, void* aux,
+                                    void* stream) {
+  if (!A || !W || !packed_scratch || !aux) return fail(HIFT_EINVAL, "null operand");
+  if (backward && (!C || bias)) return fail(HIFT_EINVAL, "the backward epilogue needs C and takes no bias");
+  if (packed_b_bytes(N, K) == 0 || N % 8 != 0) return fail(HIFT_EINVAL, "shape cannot be packed (N a multiple of 8, K of 32)");
+  Gemm g;
+  g.dtype = DT_BF16;
+  g.M = Mm; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.C = C; g.ldc = N; g.bias = bias;
+  g.epi = backward ? EPI_GELU_BWD : EPI_GELU;
+  g.C2 = aux; g.ldc2 = N;
+  if (!packed_gemm_applies(g)) return fail(HIFT_EINVAL, "problem is not one the packed-operand kernel takes");
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(pack_b(W, K, N, K, true, packed_scratch, st));
   HIP_TRY(gemm_packed(g, packed_scratch, st));
   return HIFT_OK;
 }

@@ -397,6 +397,59 @@ def test_linear_dx_with_gated_activation_backward_in_the_epilogue(M, f, K):
     assert np.all(np.abs(got - ref) <= 2 ** -8 * np.abs(ref) + 1e-5 * fac * np.sqrt(K) + 1e-7)
 
 
+@pytest.mark.parametrize("M,N,K,keep", [(2048, 3328, 256, 1), (1992, 3592, 96, 1), (2048, 20480, 64, 0)])
+def test_linear_with_bias_and_gelu_in_the_epilogue(M, N, K, keep):
+    """gelu(x . W^T + b) formed in the contraction's epilogue from the bf16-rounded pre-activations, against the
+    oracle's erf-form GELU of those.  The kernel's erf has an absolute error below 1.5e-7, which gelu scales by |x| / 2."""
+    import torch
+    import paper_2401_15207_amd as H_
+    from oracle import hift_oracle as O
+    rng = np.random.default_rng(M + N + K + 2)
+    x = _bf16_round(rng.standard_normal((M, K)))
+    w = _bf16_round(rng.standard_normal((N, K)) * (2.0 / np.sqrt(K)))
+    b = _bf16_round(rng.standard_normal(N))
+    pre_ref = x.astype(np.float64) @ w.astype(np.float64).T + b
+    scratch = torch.empty(H_.kernel_packed_bytes(N, K) // 2, dtype=torch.bfloat16, device="cuda")
+    pre = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    act = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    H_.kernel_linear_gelu(0, M, N, K, _dev(x, True), K, _dev(w, True), _dev(b, True), scratch, pre if keep else None, act)
+    torch.cuda.synchronize()
+    a = act.float().cpu().numpy().astype(np.float64)
+    if keep:
+        p = pre.float().cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(p - pre_ref) <= 2 ** -8 * np.abs(pre_ref) + 1e-5)
+        a_ref = O.gelu_fwd(p)
+        assert np.all(np.abs(a - a_ref) <= 2 ** -8 * np.abs(a_ref) + 1e-6 * (1.0 + np.abs(p)))
+    else:
+        assert torch.isnan(pre.float()).all()
+        p = _bf16_round(pre_ref).astype(np.float64)     # within one rounding of what the kernel held
+        a_ref = O.gelu_fwd(p)
+        slack = 2 ** -7 * (np.abs(a_ref) + np.abs(p) * 1.2)      # |gelu'| <= 1.13
+        assert np.all(np.abs(a - a_ref) <= slack + 1e-6)
+
+
+@pytest.mark.parametrize("M,N,K", [(2048, 3328, 64), (1992, 3592, 96)])
+def test_linear_dx_with_gelu_backward_in_the_epilogue(M, N, K):
+    """dY . W (the gradient of the activation, never stored) times gelu'(pre) in the contraction's epilogue, against
+    the oracle's gelu_bwd on the float64 product."""
+    import torch
+    import paper_2401_15207_amd as H_
+    from oracle import hift_oracle as O
+    rng = np.random.default_rng(M + N + K + 4)
+    dy = _bf16_round(rng.standard_normal((M, K)))
+    wt = _bf16_round(rng.standard_normal((N, K)) / np.sqrt(K))           # rows = columns of the second projection
+    pre = _bf16_round(rng.standard_normal((M, N)) * 2.0)
+    dact = dy.astype(np.float64) @ wt.astype(np.float64).T
+    ref = O.gelu_bwd(dact, pre.astype(np.float64))
+    scratch = torch.empty(H_.kernel_packed_bytes(N, K) // 2, dtype=torch.bfloat16, device="cuda")
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    H_.kernel_linear_gelu(1, M, N, K, _dev(dy, True), K, _dev(wt, True), None, scratch, out, _dev(pre, True))
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    # one bf16 rounding; the fp32 accumulation of d act and the 1e-6 of the derivative enter through |d act|
+    assert np.all(np.abs(got - ref) <= 2 ** -8 * np.abs(ref) + 1e-5 * np.sqrt(K) * 1.2 + 2e-6 * np.abs(dact) + 1e-7)
+
+
 @pytest.mark.parametrize("M,N,K", [(2048, 5120, 2048), (2048, 5632, 1024), (1990, 4392, 1024)])
 def test_gemm_with_packed_weight_operand_and_shared_last_round(M, N, K):
     """Tiles of the last, partial round shared by 2 to 4 workgroups along K and summed by the last one to
