@@ -10,6 +10,10 @@
 //     each computing (BM/2)x(BN/2) with v_mfma_f32_32x32x16_bf16, fp32 accumulation.
 //     LDS rows are 128 bytes (64 bf16) with the 16-byte chunk index XOR-swizzled by the row so
 //     that both the 16-byte stores and the MFMA fragment reads spread over all banks.
+//   * bf16 with the weight operand pre-packed in MFMA fragment order (forward and dX of the large layers, the
+//     dominant kernel of a step): 128x256 tiles, weight fragments straight from memory into registers, the
+//     activation operand through a ring of direct-to-LDS stages, epilogues (bias, residual, RoPE, SwiGLU and GELU
+//     forward and backward, folded RMS normalisation) straight from the accumulators.  See further down.
 //   * fp32 and odd shapes: a plain 64x64x16 LDS-tiled FMA kernel with arbitrary strides.
 #include <cstdlib>
 #include <type_traits>
