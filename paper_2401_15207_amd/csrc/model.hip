@@ -213,7 +213,7 @@ struct Bump {
 };
 
 struct LayerAct {
-  void *na, *qkv, *prob, *ctx, *xmid, *nb, *fpre, *act;  // na: h1 | s1, nb: h2 | s2
+  void *na, *qkv, *ctx, *xmid, *nb, *fpre, *act;  // na: h1 | s1, nb: h2 | s2
   float *st1, *st2;
   float* lse;  // fused attention: log2 of each row's sum of exponentials, [B, H, S]
 };
@@ -265,7 +265,7 @@ struct hift_model {
   std::vector<LayerAct> la;
   void *e0 = nullptr, *xf = nullptr, *xcls = nullptr, *logits = nullptr;
   float *st_e = nullptr, *st_f = nullptr, *row_loss = nullptr, *loss_dev = nullptr, *part = nullptr;
-  void *D[3] = {nullptr, nullptr, nullptr}, *dqkv = nullptr, *dprob = nullptr, *attn_dsum = nullptr, *dact = nullptr, *dffn = nullptr,
+  void *D[3] = {nullptr, nullptr, nullptr}, *dqkv = nullptr, *prob = nullptr, *dprob = nullptr, *attn_dsum = nullptr, *dact = nullptr, *dffn = nullptr,
        *dcls = nullptr;
   // streams and events
   hipStream_t cs, hs, ds;
@@ -344,7 +344,6 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes, s
   for (auto& a : M.la) {
     a.na = b.take(T * d * es);
     a.qkv = b.take(T * 3 * d * es);
-    a.prob = b.take(B * H * S * S * es);
     a.ctx = b.take(T * d * es);
     a.xmid = b.take(T * d * es);
     a.nb = b.take(T * d * es);
@@ -372,6 +371,10 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes, s
   M.part = (float*)b.take((size_t)2 * ((T + 63) / 64) * wmax * 4);
   for (auto& x : M.D) x = b.take(T * d * es);
   M.dqkv = b.take(T * 3 * d * es);
+  // one probability matrix and its gradient for the attention that runs as separate contractions and softmax
+  // kernels (fp32, head widths other than 64 and 128, odd sequence lengths): the backward pass forms a layer's
+  // probabilities again from its q and k instead of keeping them per layer
+  M.prob = b.take(B * H * S * S * es);
   M.dprob = b.take(B * H * S * S * es);
   M.attn_dsum = b.take(B * H * S * 4);
   M.dact = b.take(T * f * es);
@@ -654,6 +657,34 @@ bool attention_is_fused(const hift_model* M, const LayerAct& a, int S) {
          attention_bwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, a.ctx, M->D[2], M->dqkv);
 }
 
+// Probabilities of one layer into M->prob, for the unfused attention: scores q . k^T, then the softmax in place.
+hift_status attention_probs(hift_model* M, LayerAct& a, int B, int S) {
+  const hift_config& c = M->cfg;
+  const int64_t d = c.d_model, H = c.n_heads, hd = d / H;
+  const size_t es = M->es;
+  unsigned char* qkv = (unsigned char*)a.qkv;
+  const bool causal = c.arch != HIFT_ARCH_POSTLN_ENCODER;
+  {
+    Gemm g;  // scores = q . k^T
+    g.dtype = M->dt;
+    g.M = S; g.N = S; g.K = hd;
+    g.A = qkv; g.lda = 3 * d;
+    g.B = qkv + d * es; g.ldb = 3 * d;
+    g.C = M->prob; g.ldc = S;
+    g.nb = B; g.nh = (int)H;
+    g.sa1 = (int64_t)S * 3 * d; g.sa2 = hd; g.sb1 = g.sa1; g.sb2 = hd;
+    g.sc1 = H * (int64_t)S * S; g.sc2 = (int64_t)S * S;
+    if (causal) g.band = BAND_SKIP_UPPER;  // the softmax never reads scores above the diagonal
+    Scope sc(M, CAT_ATTN, 2.0 * B * H * S * S * hd);
+    K_TRY(gemm(g, M->cs));
+  }
+  {
+    Scope sc(M, CAT_ELEM, 0);
+    K_TRY(softmax_fwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, M->prob, M->cs));
+  }
+  return HIFT_OK;
+}
+
 // keep = false: no backward pass will come through this layer; the fused kernel then stores nothing but the context
 hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S, bool keep) {
   const hift_config& c = M->cfg;
@@ -667,29 +698,12 @@ hift_status attention_fwd(hift_model* M, LayerAct& a, int B, int S, bool keep) {
     K_TRY(attention_fwd_fused(B, (int)H, S, (int)hd, causal, a.qkv, 3 * d, nullptr, a.ctx, d, keep ? a.lse : nullptr, M->cs));
     return HIFT_OK;
   }
-  {
-    Gemm g;  // scores = q . k^T
-    g.dtype = M->dt;
-    g.M = S; g.N = S; g.K = hd;
-    g.A = qkv; g.lda = 3 * d;
-    g.B = qkv + d * es; g.ldb = 3 * d;
-    g.C = a.prob; g.ldc = S;
-    g.nb = B; g.nh = (int)H;
-    g.sa1 = (int64_t)S * 3 * d; g.sa2 = hd; g.sb1 = g.sa1; g.sb2 = hd;
-    g.sc1 = H * (int64_t)S * S; g.sc2 = (int64_t)S * S;
-    if (causal) g.band = BAND_SKIP_UPPER;  // the softmax never reads scores above the diagonal
-    Scope sc(M, CAT_ATTN, 2.0 * B * H * S * S * hd);
-    K_TRY(gemm(g, M->cs));
-  }
-  {
-    Scope sc(M, CAT_ELEM, 0);
-    K_TRY(softmax_fwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, a.prob, M->cs));
-  }
+  ST_TRY(attention_probs(M, a, B, S));
   {
     Gemm g;  // ctx = p . v
     g.dtype = M->dt;
     g.M = S; g.N = hd; g.K = S;
-    g.A = a.prob; g.lda = S;
+    g.A = M->prob; g.lda = S;
     g.B = qkv + 2 * d * es; g.ldb = 3 * d; g.b_kmajor = false;
     g.C = a.ctx; g.ldc = d;
     g.nb = B; g.nh = (int)H;
@@ -727,11 +741,12 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
                               M->cs));
     return HIFT_OK;
   }
+  ST_TRY(attention_probs(M, a, B, S));  // the forward pass kept q and k, not the probabilities
   {
     Gemm g;  // dv[j,e] = sum_i p[i,j] dctx[i,e]
     batch(g);
     g.M = S; g.N = hd; g.K = S;
-    g.A = a.prob; g.lda = S; g.a_kmajor = false; g.sa1 = sP1; g.sa2 = sP2;
+    g.A = M->prob; g.lda = S; g.a_kmajor = false; g.sa1 = sP1; g.sa2 = sP2;
     g.B = dctx; g.ldb = d; g.b_kmajor = false; g.sb1 = sX1; g.sb2 = hd;
     g.C = dqkv + 2 * d * es; g.ldc = 3 * d; g.sc1 = sQ1; g.sc2 = hd;
     if (causal) g.band = BAND_K_FROM_ROW;  // p[i,j] = 0 for i < j
@@ -751,7 +766,7 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
   }
   {
     Scope sc(M, CAT_ELEM, 0);
-    K_TRY(softmax_bwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, a.prob, M->dprob, M->cs));
+    K_TRY(softmax_bwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, M->prob, M->dprob, M->cs));
   }
   {
     Gemm g;  // dq[i,e] = sum_j ds[i,j] k[j,e]
