@@ -161,11 +161,6 @@ struct Stage {
   }
 };
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-  bf16x2 v = {static_cast<__bf16>(a), static_cast<__bf16>(b)};
-  return *reinterpret_cast<uint32_t*>(&v);
-}
 
 // Epilogue shared by the contraction kernels: accumulators (transposed sub-tiles, see above) ->
 // C (+bias)(+residual), through LDS when rows can be moved as 16-byte pieces.
@@ -772,7 +767,7 @@ __device__ __forceinline__ void store_tile_regs(const GemmP& p, f32x16 (&acc)[MT
 template <int MT, bool VEC_EPI, typename OutT, int EPI = EPI_NONE>
 __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restrict__ Bp, int64_t k_steps) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int BM = 32 * MT, BN = 256, WN = 64, NT = 2;
+  constexpr int BM = 32 * MT, BN = 256, NT = 2;
   constexpr int STG = BM * PK_ROW;  // one stage of A
   constexpr int NP = MT;            // 1 KB pieces (8 rows) of a stage each wavefront requests
 
