@@ -333,6 +333,17 @@ hift_status hift_kernel_gemm_packed_ws(int32_t out_f32, int64_t M, int64_t N, in
                                        const void* bias, const void* R, void* workspace,
                                        size_t workspace_bytes, void* stream);
 
+/* hift_kernel_gemm_packed_ws for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the work space is an array built into the library, 32 MiB + 1 KiB
+ * on every GPU the library is loaded on, held until the process ends.  Allocates nothing; the first call on a GPU
+ * looks the array's address up.  Same arguments, result and errors as hift_kernel_gemm_packed_ws without the work
+ * space; HIFT_EINVAL also if the problem's shared round would need more than the array holds.  Every call on a GPU
+ * uses that GPU's one array (its counters are cleared by a small kernel on `stream` first): calls that overlap on
+ * one GPU, on different streams or from different threads, race. */
+hift_status hift_kernel_gemm_packed_static(int32_t out_f32, int64_t M, int64_t N, int64_t K, const void* A,
+                                           int64_t lda, const void* Bp, void* C, int64_t ldc, const void* bias,
+                                           const void* R, void* stream);
+
 /* A linear layer of the RMSNorm / rotary / gated-FFN decoder with the elementwise step that follows it
  * done in the contraction's epilogue (forward and backward of Algorithm 1 step h; bf16).  A: device
  * [M, K] (row stride lda); W: device [N, K] bf16, contiguous; packed_scratch: device,

@@ -98,6 +98,7 @@ _SIGS = {
     "hift_kernel_norm_fwd": [_i32, _i32, _i64, _i32, C.c_float, _vp, _vp, _vp, _vp, _vp, _vp],
     "hift_kernel_packed_workspace_bytes": [_P(_sz)],
     "hift_kernel_gemm_packed_ws": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _sz, _vp],
+    "hift_kernel_gemm_packed_static": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp],
     "hift_kernel_linear_fused": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _i64, _vp],
     "hift_kernel_gemm_packed_rowsq": [_i64, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp],
     "hift_kernel_row_sumsq": [_i64, _i32, _vp, _i32, _vp, _vp],
@@ -236,6 +237,13 @@ def kernel_gemm_packed_ws(out_f32, M, N, K, A, lda, Bp, Cm, ldc, bias, R, worksp
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib.hift_kernel_gemm_packed_ws(out_f32, M, N, K, _ptr(A), lda, _ptr(Bp), _ptr(Cm), ldc, _ptr(bias), _ptr(R),
                                           _ptr(workspace), workspace.numel() * workspace.element_size(), st))
+
+
+def kernel_gemm_packed_static(out_f32, M, N, K, A, lda, Bp, Cm, ldc, bias=None, R=None, stream=None):
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib.hift_kernel_gemm_packed_static(int(out_f32), M, N, K, _ptr(A), lda, _ptr(Bp), _ptr(Cm), ldc, _ptr(bias),
+                                              _ptr(R), st))
 
 
 EPILOGUE_SWIGLU, EPILOGUE_ROPE, EPILOGUE_SWIGLU_BWD = 1, 2, 3

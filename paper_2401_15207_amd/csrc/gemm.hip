@@ -1164,6 +1164,25 @@ hipError_t launch_pk(dim3 grid, int threads, int lds, hipStream_t st, const Gemm
 
 }  // namespace
 
+// How many workgroups share each tile of the last round of a problem of `blocks` tiles (1: the round is not shared):
+// 2 to 4 when at most half the compute units would have a tile, every share at least 8 stages of K long.
+// HIFT_GEMM_SPLIT=0 in the environment: never.
+static int shared_round_split(int blocks, int64_t K) {
+  static const bool split_on = [] { const char* e = getenv("HIFT_GEMM_SPLIT"); return !(e && e[0] == '0'); }();
+  const int rem = blocks % 256;
+  if (!split_on || rem == 0 || rem > 128 || K % PK_DK != 0) return 1;
+  int split = 256 / rem;
+  if (split > 4) split = 4;
+  while (split > 1 && K / PK_DK < 8 * split) --split;
+  return split;
+}
+
+size_t packed_ws_needed(const Gemm& g) {
+  const int blocks = (int)((g.M + 32 * PK_MT - 1) / (32 * PK_MT)) * (int)((g.N + 255) / 256);
+  const int split = shared_round_split(blocks, g.K);
+  return split > 1 ? 1024 + (size_t)split * (blocks % 256) * (32 * PK_MT * 256 * 4) : 0;
+}
+
 hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   if (!packed_gemm_applies(g)) return hipErrorInvalidValue;
   GemmP p;
@@ -1209,12 +1228,9 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   // The last round: if at most half the compute units would have a tile, 2 to 4 workgroups share each
   // (HIFT_GEMM_SPLIT=0 in the environment: never).
   int blocks = p.tiles_m * p.tiles_n;
-  static const bool split_on = [] { const char* e = getenv("HIFT_GEMM_SPLIT"); return !(e && e[0] == '0'); }();
   const int rem = blocks % 256;
-  if (split_on && g.ws && (reinterpret_cast<uintptr_t>(g.ws) & 15) == 0 && rem > 0 && rem <= 128 && g.K % PK_DK == 0) {
-    int split = 256 / rem;
-    if (split > 4) split = 4;
-    while (split > 1 && g.K / PK_DK < 8 * split) --split;  // at least 8 stages per share
+  if (g.ws && (reinterpret_cast<uintptr_t>(g.ws) & 15) == 0) {
+    const int split = shared_round_split(blocks, g.K);
     if (split > 1) {
       p.split = split;
       p.split_from = blocks - rem;

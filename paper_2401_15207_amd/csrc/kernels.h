@@ -85,6 +85,8 @@ hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajo
                   int order = PK_ORDER_PLAIN, const void* gain = nullptr);
 bool packed_gemm_applies(const Gemm& g);
 hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st);
+// Bytes of work space gemm_packed would use for this problem if given one (0: its last round is not shared).
+size_t packed_ws_needed(const Gemm& g);
 
 // ---- row-wise and elementwise kernels ------------------------------------------------------
 hipError_t embed_fwd(int dt, const int32_t* tokens, int64_t T, int S, int d, int V,

@@ -1848,6 +1848,46 @@ hift_status hift_kernel_gemm_packed_ws(int32_t out_f32, int64_t Mm, int64_t N, i
   return HIFT_OK;
 }
 
+// Work space of hift_kernel_gemm_packed_static: one array per GPU, held from the moment the library is loaded.
+// In host code the name is only a handle for hipGetSymbolAddress; kernels are given the address it returns.
+static __device__ __align__(256) unsigned char scratch[PACKED_WS_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES];  // device address of `scratch` on each GPU, once asked for
+}  // namespace
+
+hift_status hift_kernel_gemm_packed_static(int32_t out_f32, int64_t Mm, int64_t N, int64_t K, const void* A, int64_t lda,
+                                           const void* Bp, void* C, int64_t ldc, const void* bias, const void* R,
+                                           void* stream) {
+  if (!A || !Bp || !C) return fail(HIFT_EINVAL, "null operand");
+  Gemm g;
+  g.dtype = DT_BF16;
+  g.out_f32 = out_f32 != 0;
+  g.M = Mm; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.C = C; g.ldc = ldc; g.bias = bias; g.R = R; g.ldr = ldc;
+  if (!packed_gemm_applies(g)) return fail(HIFT_EINVAL, "problem is not one the packed-operand kernel takes");
+  const size_t need = packed_ws_needed(g);
+  if (need > sizeof(scratch))
+    return fail(HIFT_EINVAL, "the shared last round of this problem needs %zu bytes of work space, the built-in one holds %zu",
+                need, sizeof(scratch));
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(HIFT_EDEVICE, "device index %d outside [0,%d)", dev, MAX_DEVICES);
+  void* ws = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!ws) {  // first call on this GPU (two threads racing here both store the same address)
+    HIP_TRY(hipGetSymbolAddress(&ws, HIP_SYMBOL(scratch)));
+    if (!ws) return fail(HIFT_EDEVICE, "hipGetSymbolAddress returned a null address");
+    __atomic_store_n(&g_scratch_ptr[dev], ws, __ATOMIC_RELEASE);
+  }
+  hipStream_t st = (hipStream_t)stream;
+  // the counters must be zero at the start; a launch leaves them so, but the array outlives a call that failed half-way
+  if (need) HIP_TRY(fill_zero(ws, 1024, st));
+  g.ws = ws;
+  HIP_TRY(gemm_packed(g, Bp, st));
+  return HIFT_OK;
+}
+
 hift_status hift_kernel_gemm_packed_rowsq(int64_t Mm, int64_t N, int64_t K, const void* A, int64_t lda, const void* Bp,
                                           void* C, int64_t ldc, const void* R, float* rowsq, void* workspace,
                                           void* stream) {
