@@ -99,6 +99,53 @@ def test_adagrad_and_sgd_momentum_by_hand():
     assert np.allclose(th, 0.95)
 
 
+def test_adagrad_and_sgd_weight_decay_by_hand():
+    # L2 decay enters the gradient before anything else: g' = g + wd * theta, on decayed elements only
+    th, acc = np.array([2.0, 2.0]), np.zeros(2)
+    O.adagrad_update(th, np.array([0.5, 0.5]), acc, 0.1, 1e-10, 0.25, np.array([1.0, 0.0]))
+    # element 0: g' = 0.5 + 0.25 * 2 = 1.0, acc = 1.0, step = 0.1 * 1 / (1 + 1e-10); element 1: as without decay
+    assert acc[0] == 1.0 and acc[1] == 0.25
+    assert np.allclose(th, [2.0 - 0.1 / (1.0 + 1e-10), 2.0 - 0.1 * 0.5 / (0.5 + 1e-10)], rtol=1e-15)
+    O.adagrad_update(th, np.array([-1.0, 0.0]), acc, 0.1, 1e-10, 0.25, np.array([1.0, 0.0]))
+    g2 = -1.0 + 0.25 * 1.9                       # theta after the first step is 1.9 to 1e-11
+    assert np.allclose(acc[0], 1.0 + g2 * g2, rtol=1e-9) and acc[1] == 0.25
+    assert np.allclose(th[0], 1.9 - 0.1 * g2 / np.sqrt(1.0 + g2 * g2), rtol=1e-9)
+    th, buf = np.array([2.0, 2.0]), np.zeros(2)
+    O.sgd_update(th, np.array([0.5, 0.5]), buf, 1, 0.1, 0.9, 0.25, np.array([1.0, 0.0]))
+    assert np.array_equal(buf, [1.0, 0.5]) and np.allclose(th, [1.9, 1.95], rtol=1e-15)
+    O.sgd_update(th, np.array([0.25, 0.25]), buf, 2, 0.1, 0.9, 0.25, np.array([1.0, 0.0]))
+    b0 = 0.9 * 1.0 + (0.25 + 0.25 * 1.9)        # = 1.625
+    assert np.allclose(buf, [b0, 0.9 * 0.5 + 0.25], rtol=1e-15)
+    assert np.allclose(th, [1.9 - 0.1 * b0, 1.95 - 0.07], rtol=1e-15)
+    th = np.array([2.0])                         # no momentum: theta <- theta - lr (g + wd theta)
+    O.sgd_update(th, np.array([0.5]), np.zeros(1), 1, 0.1, 0.0, 0.25, np.ones(1))
+    assert np.allclose(th, 2.0 - 0.1 * 1.0, rtol=1e-15)
+
+
+@pytest.mark.parametrize("kind", ["adagrad", "sgdm", "sgd"])
+def test_adagrad_and_sgd_with_weight_decay_against_torch_optim(kind):
+    """Three updates with a non-zero L2 decay against torch.optim's own implementations (float64)."""
+    import torch
+    rng = np.random.default_rng(3)
+    n, lr, wd = 50, 0.05, 0.3
+    th0 = rng.standard_normal(n)
+    grads = [rng.standard_normal(n) for _ in range(3)]
+    p = torch.nn.Parameter(torch.tensor(th0.copy()))
+    if kind == "adagrad":
+        topt = torch.optim.Adagrad([p], lr=lr, weight_decay=wd, eps=1e-10, initial_accumulator_value=0.0, lr_decay=0.0)
+    else:
+        topt = torch.optim.SGD([p], lr=lr, weight_decay=wd, momentum=0.9 if kind == "sgdm" else 0.0)
+    th, st = th0.copy(), np.zeros(n)
+    for t, g in enumerate(grads, 1):
+        p.grad = torch.tensor(g.copy())
+        topt.step()
+        if kind == "adagrad":
+            O.adagrad_update(th, g, st, lr, 1e-10, wd, np.ones(n))
+        else:
+            O.sgd_update(th, g, st, t, lr, 0.9 if kind == "sgdm" else 0.0, wd, np.ones(n))
+        assert np.allclose(th, p.detach().numpy(), rtol=1e-13, atol=1e-15), (kind, t)
+
+
 def test_per_group_step_counter_drives_bias_correction():
     # the second visit of a group is its update number 2, whatever the global step is
     o, _ = _fresh()
