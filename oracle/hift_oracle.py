@@ -612,6 +612,90 @@ def adafactor_update(theta, g, state, shape, t, lr, wd, decay, eps1=1e-30, clip=
     theta -= lr * U
 
 
+# ----------------------------------------------------------------------------------------
+# low-rank adapters on the attention projections (the LoRA baseline of section 4.3, whose step
+# time the paper sets beside HiFT's)
+# ----------------------------------------------------------------------------------------
+def lora_tensors(cfg: dict, rank: int):
+    """Adapter tensors [(name, shape)], in storage order: per hidden layer A_q [r, d], B_q [d, r], A_v [r, d],
+    B_v [d, r].  The query and value projections become W + (alpha / r) B A; everything else is frozen."""
+    d = cfg["d_model"]
+    out = []
+    for l in range(cfg["n_layers"]):
+        p = f"l{l}."
+        out += [(p + "lora_aq", (rank, d)), (p + "lora_bq", (d, rank)), (p + "lora_av", (rank, d)), (p + "lora_bv", (d, rank))]
+    return out
+
+
+def lora_n_params(cfg: dict, rank: int) -> int:
+    return sum(int(np.prod(shape)) for _n, shape in lora_tensors(cfg, rank))
+
+
+def _lora_views(cfg, rank, flat):
+    views, off = {}, 0
+    for name, shape in lora_tensors(cfg, rank):
+        n = int(np.prod(shape))
+        views[name] = flat[off:off + n].reshape(shape)
+        off += n
+    return views
+
+
+def lora_merge(cfg: dict, flat: np.ndarray, lora: np.ndarray, rank: int, alpha: float) -> np.ndarray:
+    """The base parameters with every adapted projection replaced by W + (alpha / rank) B A (a copy)."""
+    d, s = cfg["d_model"], alpha / rank
+    merged = np.array(flat, copy=True)
+    P, A = _Params(cfg, merged), _lora_views(cfg, rank, lora)
+    for l in range(cfg["n_layers"]):
+        p = f"l{l}."
+        P[p + "wqkv"][0:d] += s * (A[p + "lora_bq"] @ A[p + "lora_aq"])
+        P[p + "wqkv"][2 * d:3 * d] += s * (A[p + "lora_bv"] @ A[p + "lora_av"])
+    return merged
+
+
+def lora_loss_and_grad(cfg: dict, flat: np.ndarray, lora: np.ndarray, tokens, labels, rank: int, alpha: float):
+    """Loss of the model with merged adapters and its gradient with respect to the adapters alone.  An adapter is a
+    reparametrisation W' = W + s B A of a projection, so with G = d loss / d W' (from the full backward pass):
+    d loss / d B = s G A^T and d loss / d A = s B^T G."""
+    d, s = cfg["d_model"], alpha / rank
+    loss, g = loss_and_grad(cfg, lora_merge(cfg, flat, lora, rank, alpha), tokens, labels)
+    G, A = _Params(cfg, g), _lora_views(cfg, rank, lora)
+    out = np.zeros_like(lora)
+    D = _lora_views(cfg, rank, out)
+    for l in range(cfg["n_layers"]):
+        p = f"l{l}."
+        for part, rows in (("q", slice(0, d)), ("v", slice(2 * d, 3 * d))):
+            Gw = G[p + "wqkv"][rows]
+            D[p + "lora_b" + part][...] = s * (Gw @ A[p + "lora_a" + part].T)
+            D[p + "lora_a" + part][...] = s * (A[p + "lora_b" + part].T @ Gw)
+    return loss, out
+
+
+class LoraOracle:
+    """A run that trains the adapters only (AdamW, no weight decay on anything but matrices -- every adapter is
+    one); the base parameters never change.  With half_weights the loss is evaluated at the bf16 rounding of base and
+    adapters, as the mixed-precision GPU path does."""
+
+    def __init__(self, cfg, opt, params, lora, rank, alpha, half_weights=False):
+        self.cfg, self.opt, self.rank, self.alpha, self.half = dict(cfg), dict(opt), rank, alpha, half_weights
+        self.theta = np.array(params, dtype=np.float64).reshape(-1).copy()
+        self.lora = np.array(lora, dtype=np.float64).reshape(-1).copy()
+        assert self.theta.size == n_params(cfg) and self.lora.size == lora_n_params(cfg, rank)
+        self.m, self.v = np.zeros_like(self.lora), np.zeros_like(self.lora)
+        self.t = 0
+        self.last_grad = None
+
+    def step(self, tokens, labels) -> float:
+        base = bf16_round(self.theta) if self.half else self.theta
+        at = bf16_round(self.lora) if self.half else self.lora
+        loss, g = lora_loss_and_grad(self.cfg, base, at, tokens, labels, self.rank, self.alpha)
+        self.last_grad = g
+        self.t += 1
+        o = self.opt
+        adamw_update(self.lora, g, self.m, self.v, self.t, o["lr"], o["beta1"], o["beta2"], o["eps"],
+                     o["weight_decay"], np.ones_like(self.lora))
+        return loss
+
+
 def bf16_round(x: np.ndarray) -> np.ndarray:
     """Nearest bfloat16 value (1 sign, 8 exponent, 7 fraction bits; ties to even), returned in
     x's dtype.  Values are first rounded to float32 (nearest even), whose upper 16 bits are the
