@@ -33,6 +33,17 @@ __device__ __forceinline__ void stv(T* p, const float (&f)[V]) {
   *reinterpret_cast<Vec<T, V>*>(p) = t;
 }
 
+// Hides a 16-byte piece from the optimiser for a moment.  Kernels that keep a row in registers in its storage type
+// and walk it several times place this between the passes: otherwise the conversions to fp32 of all passes are merged
+// and the row is kept a second time as floats, which costs the registers the kernel's occupancy depends on.
+template <typename T, int V>
+__device__ __forceinline__ void opaque(Vec<T, V>& v) {
+  static_assert(sizeof(Vec<T, V>) == 16, "one 16-byte piece");
+  u32x4_t t = __builtin_bit_cast(u32x4_t, v);
+  asm volatile("" : "+v"(t));
+  v = __builtin_bit_cast(Vec<T, V>, t);
+}
+
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---------------------------------------------------------------------------- embedding
@@ -334,47 +345,54 @@ __global__ void __launch_bounds__(64) norm_bwd_dx_reg_k(int64_t rows, int d, con
   const int64_t row = blockIdx.x;
   const int lane = threadIdx.x;
   const float mean = stats[2 * row], rstd = stats[2 * row + 1];
-  float xh[NCH][V], dh[NCH][V];  // normalised input; dy * gain
+  // x, dy and the residual gradient stay in their storage type (16 bytes per piece), requested all at once; the
+  // gain is read again in the second pass (a few KB shared by all rows: it stays in the cache)
+  Vec<T, V> rx[NCH], rdy[NCH], rres[NCH];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int j = (c * 64 + lane) * V;
+    if (j < d) {
+      rx[c] = *reinterpret_cast<const Vec<T, V>*>(x + row * d + j);
+      rdy[c] = *reinterpret_cast<const Vec<T, V>*>(dy + row * d + j);
+      if (dres) rres[c] = *reinterpret_cast<const Vec<T, V>*>(dres + row * d + j);
+    }
+  }
+  float s1 = 0.f, s2 = 0.f;
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const int j = (c * 64 + lane) * V;
     if (j < d) {
       float gg[V];
-      ldv<T, V>(x + row * d + j, xh[c]);
-      ldv<T, V>(dy + row * d + j, dh[c]);
       ldv<T, V>(g + j, gg);
 #pragma unroll
       for (int e = 0; e < V; ++e) {
-        xh[c][e] = (xh[c][e] - mean) * rstd;
-        dh[c][e] *= gg[e];
+        const float dh = to_f32(rdy[c].v[e]) * gg[e];
+        s1 += dh;
+        s2 += dh * ((to_f32(rx[c].v[e]) - mean) * rstd);
       }
-    } else {
-#pragma unroll
-      for (int e = 0; e < V; ++e) xh[c][e] = dh[c][e] = 0.f;
     }
   }
-  float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-  for (int c = 0; c < NCH; ++c)
-#pragma unroll
-    for (int e = 0; e < V; ++e) {
-      s1 += dh[c][e];
-      s2 += dh[c][e] * xh[c][e];
-    }
   s1 = RMS ? 0.f : wave_sum(s1) / d;
   s2 = wave_sum(s2) / d;
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
+    opaque(rx[c]);
+    opaque(rdy[c]);
+  }
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
     const int j = (c * 64 + lane) * V;
     if (j < d) {
-      float o[V];
+      float gg[V], o[V];
+      ldv<T, V>(g + j, gg);
 #pragma unroll
-      for (int e = 0; e < V; ++e) o[e] = rstd * (dh[c][e] - s1 - xh[c][e] * s2);
+      for (int e = 0; e < V; ++e) {
+        const float dh = to_f32(rdy[c].v[e]) * gg[e], xh = (to_f32(rx[c].v[e]) - mean) * rstd;
+        o[e] = rstd * (dh - s1 - xh * s2);
+      }
       if (dres) {
-        float r[V];
-        ldv<T, V>(dres + row * d + j, r);
 #pragma unroll
-        for (int e = 0; e < V; ++e) o[e] += r[e];
+        for (int e = 0; e < V; ++e) o[e] += to_f32(rres[c].v[e]);
       }
       stv<T, V>(dx + row * d + j, o);
     }
@@ -689,13 +707,78 @@ __global__ void __launch_bounds__(BLK) ce_row_k(int64_t rows, int vocab, T* __re
   }
 }
 
+// Same, with the row held in registers (vocab <= BLK * V * NV): every logit is read once and its gradient written
+// once, all loads of a row in flight together; the maximum, the sum of exponentials and the gradient are three
+// passes over registers.  The values stay in their storage type (16 bytes per piece) until they are used.
+template <typename T, int V, int NV>
+__global__ void __launch_bounds__(BLK) ce_row_reg_k(int64_t rows, int vocab, T* __restrict__ logits,
+                                                     const int32_t* __restrict__ labels, float* __restrict__ row_loss) {
+  __shared__ float red[BLK / 64];
+  const int64_t row = blockIdx.x;
+  T* lr = logits + row * vocab;
+  int lab = labels[row];
+  const float inv_n = 1.0f / row_loss[rows];
+  if (lab < 0) {  // no target: zero gradient, zero loss
+    float z[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) z[e] = 0.f;
+    for (int j = threadIdx.x * V; j < vocab; j += BLK * V) stv<T, V>(lr + j, z);
+    if (threadIdx.x == 0) row_loss[row] = 0.f;
+    return;
+  }
+  if (lab >= vocab) lab = vocab - 1;
+  Vec<T, V> raw[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int j = (i * BLK + threadIdx.x) * V;
+    if (j < vocab) raw[i] = *reinterpret_cast<const Vec<T, V>*>(lr + j);
+  }
+  constexpr float LOG2E = 1.4426950408889634f;
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+    if ((i * BLK + threadIdx.x) * V < vocab) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) mx = fmaxf(mx, to_f32(raw[i].v[e]));
+    }
+  mx = block_max<BLK / 64>(mx, red);
+#pragma unroll
+  for (int i = 0; i < NV; ++i) opaque(raw[i]);
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+    if ((i * BLK + threadIdx.x) * V < vocab) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) sum += __builtin_amdgcn_exp2f((to_f32(raw[i].v[e]) - mx) * LOG2E);  // hardware exponential: 1e-7 relative
+    }
+  sum = block_sum<BLK / 64>(sum, red);
+#pragma unroll
+  for (int i = 0; i < NV; ++i) opaque(raw[i]);
+  const float lse = mx + logf(sum), inv = 1.0f / sum;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int j = (i * BLK + threadIdx.x) * V;
+    if (j < vocab) {
+      float a[V];
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        const float x = to_f32(raw[i].v[e]);
+        const bool hit = j + e == lab;
+        if (hit) row_loss[row] = lse - x;
+        a[e] = (__builtin_amdgcn_exp2f((x - mx) * LOG2E) * inv - (hit ? 1.f : 0.f)) * inv_n;
+      }
+      stv<T, V>(lr + j, a);
+    }
+  }
+}
+
 __global__ void __launch_bounds__(BLK) ce_final_k(int64_t rows, const float* __restrict__ row_loss,
                                                    float* __restrict__ loss_out) {
   __shared__ float red[BLK / 64];
   float c = 0.f;
   for (int64_t r = threadIdx.x; r < rows; r += BLK) c += row_loss[r];
   c = block_sum<BLK / 64>(c, red);
-  if (threadIdx.x == 0) *loss_out = c / row_loss[rows];
+  if (threadIdx.x == 0) *loss_out = row_loss[rows] > 0.f ? c / row_loss[rows] : 0.f;  // no row with a target: loss 0
 }
 
 // ---------------------------------------------------------------------------- casts, fill
@@ -708,6 +791,11 @@ template <typename T>
 __global__ void __launch_bounds__(BLK) cast_to_f32_k(int64_t n, const T* __restrict__ s, float* __restrict__ d) {
   const int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x;
   if (i < n) d[i] = to_f32(s[i]);
+}
+template <typename T>
+__global__ void __launch_bounds__(BLK) scale_k(int64_t n, float a, T* __restrict__ x) {
+  const int64_t i = (int64_t)blockIdx.x * BLK + threadIdx.x;
+  if (i < n) x[i] = from_f32<T>(a * to_f32(x[i]));
 }
 __global__ void __launch_bounds__(BLK) fill_zero_k(uint4* __restrict__ p, int64_t n16, unsigned char* tail_p,
                                                     int tail) {
@@ -1147,9 +1235,27 @@ hipError_t cross_entropy(int dt, int64_t rows, int V_, void* logits, const int32
   if (rows == 0) return fill_zero(loss_out, 4, st);
   ce_count_k<<<1, BLK, 0, st>>>(rows, labels, row_loss);
 #define OK(v) (V_ % (v) == 0 && aligned16(logits))
-  DISPATCH_TV(dt, OK, (ce_row_k<T, V><<<dim3((unsigned)rows), BLK, 0, st>>>(rows, V_, (T*)logits, labels, row_loss)));
+  // 16-byte pieces of a row a thread keeps: 16 (rows of up to 32768 bf16 or 16384 fp32 values) or 32
+  if (dt == DT_BF16 && OK(8) && V_ <= BLK * 8 * 16) {
+    ce_row_reg_k<bf16, 8, 16><<<dim3((unsigned)rows), BLK, 0, st>>>(rows, V_, (bf16*)logits, labels, row_loss);
+  } else if (dt == DT_BF16 && OK(8) && V_ <= BLK * 8 * 32) {
+    ce_row_reg_k<bf16, 8, 32><<<dim3((unsigned)rows), BLK, 0, st>>>(rows, V_, (bf16*)logits, labels, row_loss);
+  } else if (dt == DT_F32 && OK(4) && V_ <= BLK * 4 * 16) {
+    ce_row_reg_k<float, 4, 16><<<dim3((unsigned)rows), BLK, 0, st>>>(rows, V_, (float*)logits, labels, row_loss);
+  } else if (dt == DT_F32 && OK(4) && V_ <= BLK * 4 * 32) {
+    ce_row_reg_k<float, 4, 32><<<dim3((unsigned)rows), BLK, 0, st>>>(rows, V_, (float*)logits, labels, row_loss);
+  } else {
+    DISPATCH_TV(dt, OK, (ce_row_k<T, V><<<dim3((unsigned)rows), BLK, 0, st>>>(rows, V_, (T*)logits, labels, row_loss)));
+  }
 #undef OK
   ce_final_k<<<1, BLK, 0, st>>>(rows, row_loss, loss_out);
+  LAUNCH_CHECK();
+}
+
+hipError_t scale_inplace(int dt, int64_t n, float a, void* x, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  if (dt == DT_F32) scale_k<float><<<dim3((unsigned)cdiv(n, BLK)), BLK, 0, st>>>(n, a, (float*)x);
+  else scale_k<bf16><<<dim3((unsigned)cdiv(n, BLK)), BLK, 0, st>>>(n, a, (bf16*)x);
   LAUNCH_CHECK();
 }
 

@@ -143,6 +143,8 @@ hipError_t embed_bwd(int dt, const int32_t* tokens, int64_t T, int S, int d, int
 // rows of x at positions b*S (first token of every sequence) -> y [B, d], and the adjoint
 hipError_t gather_first(int dt, int B, int S, int d, const void* x, void* y, hipStream_t st);
 hipError_t scatter_first(int dt, int B, int S, int d, const void* dy, void* dx, hipStream_t st);
+// x[i] = a x[i] (one rounding in the storage type); for the small operands of the low-rank adapters
+hipError_t scale_inplace(int dt, int64_t n, float a, void* x, hipStream_t st);
 hipError_t cast_f32_to(int dt, int64_t n, const float* src, void* dst, hipStream_t st);
 hipError_t cast_to_f32(int dt, int64_t n, const void* src, float* dst, hipStream_t st);
 hipError_t fill_zero(void* p, size_t bytes, hipStream_t st);
