@@ -28,27 +28,6 @@ import numpy as np  # noqa: E402
 BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 
 
-def fill_weights(model, cfg, seed):
-    """N(0, 0.02^2) matrices, unit gains, zero biases, drawn on the device unit by unit."""
-    import torch
-    g = torch.Generator(device="cuda")
-    g.manual_seed(seed)
-    per_unit = {}
-    for name, shape, kind, unit, off in model.tensors:
-        per_unit.setdefault(unit, []).append((shape, kind))
-    for unit in sorted(per_unit):
-        parts = []
-        for shape, kind in per_unit[unit]:
-            n = int(np.prod(shape))
-            if kind == 0:
-                parts.append(torch.randn(n, generator=g, device="cuda", dtype=torch.float32) * 0.02)
-            else:
-                parts.append(torch.full((n,), 1.0 if kind == 1 else 0.0, device="cuda"))
-        flat = torch.cat(parts).cpu().numpy()
-        model.write_params(unit, unit + 1, flat)
-        del parts, flat
-
-
 def cpu_baseline(wl_name, seed):
     """Times one oracle step on the depth-2 twin of the workload (same widths, batch, sequence)."""
     from hift_inputs import WORKLOADS, init_params, make_batch, model_config
@@ -84,6 +63,25 @@ def cpu_baseline(wl_name, seed):
                    f"of {wl_name} (same widths, batch {twin['batch']} x {twin['seq']}): {dt:.1f} s = {T / dt:.1f} tokens/s; "
                    f"value is that rate scaled to {full['n_layers']} layers by the matrix-product flop ratio {scale:.2f}"),
     }
+
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E
+
+
+def hbm_rooflines(rowwise, n_opt, ms_opt, by_opt, n_pack, ms_pack, by_pack):
+    """Achieved GB/s against the 8 TB/s peak for every memory-bound kernel kind that ran in the event-bracketed
+    pass: algorithmic bytes (each element read once, each written once) / event time."""
+    out = {}
+    rows = dict(rowwise)
+    rows["optimizer update (one entry per step)"] = (n_opt, ms_opt, by_opt)
+    rows["weight re-pack (one entry per step)"] = (n_pack, ms_pack, by_pack)
+    for name, (n, ms, b) in rows.items():
+        if n == 0 or ms <= 0:
+            continue
+        gbps = b / (ms * 1e-3) / 1e9
+        out[name] = {"launches": n, "avg_us": round(1e3 * ms / n, 2), "mb_per_launch": round(b / n / 1e6, 2),
+                     "gbps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 3)}
+    return out
 
 
 def measured_traffic():
@@ -154,6 +152,50 @@ def kernel_bench(reps):
     print(json.dumps({"kernel_bench": out, "copy_reference_bytes_each_way": 1 << 30}))
 
 
+def lora_bench(a):
+    """The LoRA baseline of section 4.3 on the same kernels: adapters of rank --lora-rank on the query and value
+    projections, full forward, activation gradients down to the first layer, AdamW on the adapters.  One JSON line
+    (not the benchmark's metric: a comparison figure)."""
+    import torch
+    import paper_2401_15207_amd as H
+    from hift_inputs import WORKLOADS, fill_weights_on_device, make_batch, model_config
+    wl = WORKLOADS[a.workload]
+    cfg = model_config(wl)
+    B, S = wl["batch"], wl["seq"]
+    model = H.HiftModel(cfg, wl["opt"], 1, B, S, init_params=None, lora_rank=a.lora_rank, lora_alpha=2.0 * a.lora_rank)
+    fill_weights_on_device(model, a.seed)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(a.seed + 1)
+    model.lora_write((torch.randn(model.lora_param_count(), generator=g, device="cuda") * 0.02).cpu().numpy())
+    n_total = a.steps + a.warmup
+    batches = []
+    for t in range(1, n_total + 1):
+        tok, lab = make_batch(wl, a.seed, t)
+        batches.append((torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda()))
+    for t in range(a.warmup):
+        model.lora_step(*batches[t], want_loss=False)
+    model.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(a.warmup, n_total):
+        model.lora_step(*batches[t], want_loss=False)
+    model.synchronize()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    model.profile_enable(True)
+    for t in range(a.warmup, n_total):
+        model.lora_step(*batches[t], want_loss=False)
+    model.synchronize()
+    cls = {name: model.profile_read(i)[1] / max(a.steps, 1) for i, name in
+           enumerate(["linear_gemm_packed", "attention_gemm", "rowwise_elementwise", "optimizer", "linear_gemm_other", "weight_repack"])}
+    model.profile_enable(False)
+    loss = model.lora_step(*batches[0], want_loss=True)
+    print(json.dumps({"lora_step": {"workload": a.workload, "rank": a.lora_rank, "adapter_params": model.lora_param_count(),
+                                    "tokens_per_s": a.steps * B * S / elapsed, "ms_per_step": 1e3 * elapsed / max(a.steps, 1),
+                                    "steps": a.steps, "warmup": a.warmup, "kernel_classes_ms_per_step": cls, "last_loss": loss,
+                                    "memory_gb": round(model.memory()["total"] / 1e9, 2)}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -172,6 +214,8 @@ def main():
                     help="park the fp32 master of inactive groups in pinned memory too (small-memory mode)")
     ap.add_argument("--no-packed-copies", action="store_true",
                     help="do not keep the fragment-order weight copies (small-memory mode; slower contractions)")
+    ap.add_argument("--lora-rank", type=int, default=0,
+                    help="time the LoRA comparison step (adapters of this rank on the query and value projections) and exit")
     ap.add_argument("--kernel-bench", type=int, default=0, metavar="REPS",
                     help="time the contraction kernel alone at the 7B shapes, REPS launches each, and exit")
     a = ap.parse_args()
@@ -183,10 +227,13 @@ def main():
     if a.kernel_bench > 0:
         kernel_bench(a.kernel_bench)
         return
+    if a.lora_rank > 0:
+        lora_bench(a)
+        return
 
     import torch
     import paper_2401_15207_amd as H
-    from hift_inputs import WORKLOADS, make_batch, model_config
+    from hift_inputs import WORKLOADS, fill_weights_on_device, make_batch, model_config
 
     wl = WORKLOADS[a.workload]
     cfg = model_config(wl)
@@ -198,9 +245,9 @@ def main():
                         master_on_host=int(a.master_on_host), no_packed_copies=int(a.no_packed_copies))
     mem = model.memory()
     model.set_state_copy_engine(a.copy_engine, a.copy_blocks)
-    fill_weights(model, cfg, a.seed)
+    fill_weights_on_device(model, a.seed)
     k = model.set_group_schedule(wl["strategy"], wl["m"], a.seed)
-    n_total = a.steps + a.warmup
+    n_total = max(a.steps + a.warmup, k)
     batches = []
     for t in range(1, n_total + 1):
         tok, lab = make_batch(wl, a.seed, t)
@@ -210,37 +257,53 @@ def main():
 
     t = 0
     loss = None
-    for _ in range(a.warmup):
-        t += 1
-        model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=False)
-    model.synchronize()
-    torch.cuda.synchronize()
+
+    def run(n, groups=None):
+        """n scheduled steps without waiting in between; returns wall seconds."""
+        nonlocal t
+        model.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            t += 1
+            gid = model.schedule_group_at(t)
+            if groups is not None:
+                groups.append(gid)
+            model.step(*batches[(t - 1) % n_total], gid, want_loss=False)
+        model.synchronize()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    run(a.warmup)
 
     # timed region: K steps.  `value` is taken here, with nothing but the steps on the streams.
     h2d0, d2h0 = model.transfer_stats()
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        t += 1
-        model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=False)
-    model.synchronize()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    groups_timed = []
+    elapsed = run(a.steps, groups_timed)
     h2d1, d2h1 = model.transfer_stats()
 
-    # the next K steps repeat the region with every kernel launch bracketed by HIP events on the
-    # compute stream: per-class kernel time for the roofline figures (the brackets keep
-    # consecutive kernels from overlapping, so this pass is a few percent slower)
+    # A step's cost depends on the depth of its group, so K steps that are not whole sweeps over the k groups
+    # weigh some depths more than others: one full sweep is timed as well (the timed region itself when it
+    # already is whole sweeps).
+    whole_sweeps = a.steps % k == 0 and a.steps > 0
+    if whole_sweeps:
+        cycle_s, cycle_steps = elapsed, a.steps
+    else:
+        run((k - t % k) % k)          # to the start of a sweep
+        cycle_s, cycle_steps = run(k), k
+
+    # Then the timed region again, over the same groups in the same order (filler steps bring the schedule back to
+    # where the timed region began), with every kernel launch bracketed by HIP events on the compute stream:
+    # per-class kernel time for the roofline figures (the brackets keep consecutive kernels from overlapping,
+    # so this pass is a few percent slower).
+    run((a.warmup - t) % k)
     model.profile_enable(True)
-    tp0 = time.perf_counter()
-    for _ in range(a.steps):
-        t += 1
-        model.step(*batches[(t - 1) % n_total], model.schedule_group_at(t), want_loss=False)
-    model.synchronize()
-    torch.cuda.synchronize()
-    t_prof = time.perf_counter() - tp0
+    groups_profiled = []
+    t_prof = run(a.steps, groups_profiled)
     n_gemm, ms_gemm, fl_gemm = model.profile_read(0)
     n_att, ms_att, fl_att = model.profile_read(1)
-    n_el, ms_el, _ = model.profile_read(2)
+    n_el, ms_el, by_el = model.profile_read(2)
+    rowwise = model.profile_read_rowwise()
     n_opt, ms_opt, by_opt = model.profile_read(3)
     n_rest, ms_rest, fl_rest = model.profile_read(4)
     n_pack, ms_pack, by_pack = model.profile_read(5)
@@ -285,6 +348,10 @@ def main():
                       "weight operand in MFMA fragment order",
             "achieved": gemm_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": gemm_tflops / BF16_PEAK_TFLOPS, "traffic": measured_traffic(),
+            "traffic_source": "profiles/gemm_traffic.json: stored rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the stand-alone "
+                              "kernel, weighted by one sweep's launch counts; not measured in this run; null when the "
+                              "kernel source no longer matches the hash stored with them",
+            "groups": groups_profiled,
             "launches": n_gemm, "avg_launch_ms": ms_gemm / max(n_gemm, 1),
             "flops_per_launch": fl_gemm / max(n_gemm, 1),
         },
@@ -297,6 +364,13 @@ def main():
         "linear_gemm_all_tflops": (fl_gemm + fl_rest) / ((ms_gemm + ms_rest) * 1e-3) / 1e12 if ms_gemm + ms_rest > 0 else 0.0,
         "linear_gemm_other_tflops": fl_rest / (ms_rest * 1e-3) / 1e12 if ms_rest > 0 else 0.0,
         "attention_gemm_tflops": fl_att / (ms_att * 1e-3) / 1e12 if ms_att > 0 else 0.0,
+        "groups_timed": groups_timed,
+        "cycle_mean_ms": 1e3 * cycle_s / cycle_steps,
+        "cycle_tokens_per_s": cycle_steps * B * S / cycle_s,
+        "cycle_note": f"wall time of {cycle_steps} consecutive scheduled steps = {cycle_steps // k} whole sweep(s) over the {k} groups"
+                      + (" (the timed region itself)" if whole_sweeps else " (timed after the K steps of `value`)"),
+        "hbm_rooflines": hbm_rooflines(rowwise, n_opt, ms_opt, by_opt, n_pack, ms_pack, by_pack),
+        "rowwise_gbps": by_el / (ms_el * 1e-3) / 1e9 if ms_el > 0 else 0.0,
         "optimizer_gbps": by_opt / (ms_opt * 1e-3) / 1e9 if ms_opt > 0 else 0.0,
         "weight_repack_gbps": by_pack / (ms_pack * 1e-3) / 1e9 if ms_pack > 0 else 0.0,
         "state_copy_gb_per_step": {"h2d": (h2d1 - h2d0) / 1e9 / max(a.steps, 1), "d2h": (d2h1 - d2h0) / 1e9 / max(a.steps, 1)},

@@ -155,3 +155,27 @@ def make_batch(workload: dict, seed: int, step: int, batch: int | None = None,
     else:
         lab = next_token_labels(tok)
     return tok, lab
+
+
+def fill_weights_on_device(model, seed: int) -> None:
+    """Initial weights for models too large to draw on the host (the 7B and 13B shapes at full depth): N(0, 0.02^2)
+    matrices, unit gains, zero biases, drawn with torch's generator on the GPU unit by unit and handed to
+    `model.write_params`.  `model` needs `tensors` (name, shape, kind, unit, offset per tensor, in parameter order)
+    and `write_params(unit_lo, unit_hi, values)`."""
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    per_unit = {}
+    for _name, shape, kind, unit, _off in model.tensors:
+        per_unit.setdefault(unit, []).append((shape, kind))
+    for unit in sorted(per_unit):
+        parts = []
+        for shape, kind in per_unit[unit]:
+            n = int(np.prod(shape))
+            if kind == KIND_MATRIX:
+                parts.append(torch.randn(n, generator=g, device="cuda", dtype=torch.float32) * 0.02)
+            else:
+                parts.append(torch.full((n,), 1.0 if kind == KIND_GAIN else 0.0, device="cuda"))
+        flat = torch.cat(parts).cpu().numpy()
+        model.write_params(unit, unit + 1, flat)
+        del parts, flat

@@ -18,14 +18,14 @@ pytestmark = pytest.mark.gpu
 def test_c4_full_depth_step_properties():
     import torch
     import paper_2401_15207_amd as H
-    from bench import fill_weights
+    from hift_inputs import fill_weights_on_device
     wl = WORKLOADS["C4"]
     cfg = model_config(wl)
     opt = wl["opt"]
     B, S, L = wl["batch"], wl["seq"], cfg["n_layers"]
     model = H.HiftModel(cfg, opt, wl["m"], B, S, init_params=None, state_on_host=1)
     try:
-        fill_weights(model, cfg, 0)
+        fill_weights_on_device(model, 0)
         k = model.set_group_schedule(wl["strategy"], wl["m"], 0)
         assert k == L + 2
         dev = lambda t: [torch.from_numpy(x).cuda() for x in make_batch(wl, 0, t)]
@@ -96,7 +96,7 @@ def test_c4_full_depth_state_in_host_memory_changes_nothing():
     updated units are bit-identical (where the state lives must be invisible in the result)."""
     import torch
     import paper_2401_15207_amd as H
-    from bench import fill_weights
+    from hift_inputs import fill_weights_on_device
     wl = WORKLOADS["C4"]
     cfg = model_config(wl)
     B, S = wl["batch"], wl["seq"]
@@ -106,7 +106,7 @@ def test_c4_full_depth_state_in_host_memory_changes_nothing():
     for on_host in (1, 0):
         model = H.HiftModel(cfg, wl["opt"], wl["m"], B, S, init_params=None, state_on_host=on_host)
         try:
-            fill_weights(model, cfg, 0)
+            fill_weights_on_device(model, 0)
             model.set_group_schedule(wl["strategy"], wl["m"], 0)
             losses, units = [], []
             for t in range(1, steps + 1):
