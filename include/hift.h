@@ -92,7 +92,20 @@ typedef struct {
                             "Experiments"): there is no whead tensor, the shared matrix belongs to unit 0,
                             unit L+1 keeps the final norm alone, and the table's gradient is the sum over
                             its two uses */
+  int32_t lora_rank;      /* > 0: low-rank adapters of this rank on the query and value projections of every hidden
+                            layer (the LoRA baseline that section "Wallclock Time Efficiency" sets beside HiFT):
+                            W + (lora_alpha / lora_rank) B A.  Such a model is trained with hift_lora_step only.
+                            A multiple of 8 in bf16 mode */
+  float lora_alpha;
+  int32_t unfused;        /* 0: every fusion the shapes allow.  HIFT_UNFUSED_* bits keep the separate kernels instead
+                            (same results within rounding; for comparison and for tests of the separate kernels) */
 } hift_config;
+/* hift_config.unfused.  EPILOGUES: rotary embedding, gated activation / GELU and their backward run as kernels of
+ * their own after the contraction instead of in its epilogue.  ATTENTION: scores, softmax and the product with v
+ * as separate contractions and a softmax kernel instead of the fused attention kernels.  NORM: RMS normalisation
+ * as a kernel of its own instead of folded into the contraction that consumes it.  HIFT_UNSHARED_LAST_ROUND: the
+ * tiles of a contraction's last, partial round are not shared between workgroups. */
+enum { HIFT_UNFUSED_EPILOGUES = 1, HIFT_UNFUSED_ATTENTION = 2, HIFT_UNFUSED_NORM = 4, HIFT_UNSHARED_LAST_ROUND = 8 };
 
 typedef struct {
   int32_t kind;        /* hift_opt_kind */
@@ -184,11 +197,23 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
                               void* device_arena, size_t device_bytes, void* pinned_arena,
                               size_t pinned_bytes, void* compute_stream, void* h2d_stream,
                               void* d2h_stream, hift_model** out);
+/* The same with the pinned arena handed in as n_chunks separately allocated page-locked blocks (a host may
+ * refuse one block of 50 or 100 GB and still grant it in pieces; the 13B-shaped model with AdamW parks 104 GB
+ * of state: Algorithm 1 steps i and k).  pinned_chunks / pinned_chunk_bytes: host arrays of n_chunks pointers
+ * and sizes; every chunk 16-byte aligned and a multiple of 16 bytes long; the sizes must add up to at least
+ * pinned_host_bytes of hift_query_bytes; chunks beyond that are not touched.  The library treats the chunks as
+ * one range in the order given and splits a transfer where a chunk ends.  Results are identical. */
+hift_status hift_model_create_chunked(const hift_config* cfg, const hift_opt* opt, int32_t m,
+                                      int32_t max_batch, int32_t max_seq, const float* init_params_host,
+                                      void* device_arena, size_t device_bytes, void* const* pinned_chunks,
+                                      const size_t* pinned_chunk_bytes, int32_t n_chunks, void* compute_stream,
+                                      void* h2d_stream, void* d2h_stream, hift_model** out);
 
 /* Grouping and visiting order (Algorithm 1 initialisation and steps c, d).  m may be any value
  * whose largest group fits the gradient buffer and state slots sized at creation, else
- * HIFT_ENOMEM.  Resets the step counter t to 0 and every per-group
- * update counter; optimizer state is kept.  k_out receives the number of groups. */
+ * HIFT_ENOMEM.  Resets the step counter t to 0.  Optimizer state is kept, and with it each unit's count of
+ * updates so far (the t of AdamW's bias correction: counted per unit of parameters, not per training step),
+ * so a unit goes on from where it was under the new grouping.  k_out receives the number of groups. */
 hift_status hift_set_group_schedule(hift_model* mdl, hift_strategy s, int32_t m, uint64_t seed,
                                     int32_t* k_out);
 /* Group visited at step t (1-based): order[(t-1) mod k]. */
@@ -203,7 +228,12 @@ hift_status hift_group_units(const hift_model* mdl, int32_t group_id, int32_t* u
  * scheduled one, fetched synchronously otherwise); optimizer update; state sent back.
  * Parameters outside the group are not written.  The work is queued on the three streams;
  * if loss_out (host) is not NULL the call waits for the compute stream and stores the mean
- * loss, with NULL it returns without waiting.
+ * loss.  With NULL it does not wait for the step, but it may wait (when state moves and the default copy
+ * engine is in use) until the host-to-device copy queued by the previous call has finished -- at most one
+ * state transfer's time, normally over long before: a copy submitted while the copy engine still has a
+ * backlog is run by the runtime as a full-grid kernel, which starves the step's own kernels.
+ * The batch's buffers must be complete on the compute stream's timeline: the caller orders the compute
+ * stream after whatever wrote them (the Python binding does this against torch's current stream).
  * Errors: HIFT_ESTATE without a schedule; HIFT_EINVAL for group_id outside [0,k), batch or seq
  * above the maxima, seq above the position table.  Token ids are not range-checked on the
  * host: an id outside [0, vocab) is clamped by the kernels. */
@@ -228,18 +258,34 @@ hift_status hift_set_lr_schedule(hift_model* mdl, int32_t kind, double base_lr, 
  * losses_out: host, n_steps floats, or null (then no step waits for the GPU). */
 hift_status hift_train(hift_model* mdl, const hift_batch* batches, int32_t n_batches, int64_t n_steps,
                        float* losses_out);
-/* Checkpoint: step count, visiting order, per-group update counts, learning-rate schedule, fp32 master
+/* Checkpoint: step count, visiting order, per-unit update counts, learning-rate schedule, fp32 master
  * weights, optimizer state of every group (wherever it lives) and Adafactor statistics, into / out of a
  * host buffer of hift_checkpoint_bytes bytes.  A run that loads a checkpoint into a model created with
  * the same configuration, optimizer kind and buffer sizes continues exactly as the saved one would have
  * (bit-identical: no kernel of the step sums in an order that depends on timing).
- * Both calls wait for the streams.  Errors: HIFT_EINVAL for a foreign or mismatching checkpoint,
- * HIFT_ENOMEM for a short buffer. */
+ * Both calls wait for the streams.  Errors: HIFT_EINVAL for a foreign, mismatching or damaged checkpoint
+ * (checked completely before the model is changed: a failed load leaves it as it was), HIFT_ENOMEM for a
+ * short buffer. */
 hift_status hift_checkpoint_bytes(const hift_model* mdl, size_t* bytes);
 hift_status hift_checkpoint_save(hift_model* mdl, void* host_buffer, size_t bytes);
 hift_status hift_checkpoint_load(hift_model* mdl, const void* host_buffer, size_t bytes);
 /* Steps taken since the schedule was set, and completed sweeps floor(t / k). */
 hift_status hift_cycle_index(const hift_model* mdl, int64_t* steps_done, int64_t* cycles_done);
+
+/* Low-rank adapters (hift_config.lora_rank = r > 0).  The comparison of section "Wallclock Time Efficiency": a LoRA step
+ * runs the whole forward pass and the activation-gradient chain down to the first hidden layer, forms the gradients of
+ * the adapters only, and updates them with AdamW (the optimizer handed to hift_model_create; no state leaves HBM: the
+ * adapters are 4 r d values per layer).  Adapter parameters, canonical order, fp32: for every hidden layer
+ * A_q [r, d], A_v [r, d], B_q [d, r], B_v [d, r]; hift_lora_param_count gives their number.  They start at zero.
+ *   hift_lora_write / hift_lora_read: all adapters from / to host memory; which = 0 master, 1 the values the forward
+ *     pass uses, 2 / 3 AdamW's first / second moment.  Both wait for the streams.
+ *   hift_lora_step: one step on one batch; loss_out as for hift_step.  The base parameters are never written.
+ * Errors: HIFT_ESTATE on a model without adapters (and hift_step on a model with them), HIFT_EINVAL for counts that do
+ * not match. */
+hift_status hift_lora_param_count(const hift_config* cfg, int64_t* n);
+hift_status hift_lora_write(hift_model* mdl, const float* src_host, size_t src_count);
+hift_status hift_lora_read(hift_model* mdl, int32_t which, float* dst_host, size_t dst_count);
+hift_status hift_lora_step(hift_model* mdl, const hift_batch* batch, float* loss_out);
 
 /* Copy parameters of units [unit_lo, unit_hi) to / from host memory in canonical order.
  * which = 0: fp32 master values.  which = 1 (read only): the values the forward pass uses
@@ -282,10 +328,19 @@ hift_status hift_set_state_copy_engine(hift_model* mdl, int32_t engine, int32_t 
  * linear-layer contractions: dW, small or unaligned shapes, fp32, 5 the re-packing of the updated
  * weights; one entry of class 3 or 5 covers all launches of one step), the launches since
  * hift_profile_enable, their milliseconds, and their algorithmic work (flops for classes 0, 1
- * and 4, bytes for classes 3 and 5, 0 for class 2). */
+ * and 4, bytes for classes 2, 3 and 5).
+ * hift_profile_read_rowwise splits class 2 by kind of kernel (kind 0 .. n-1; HIFT_EINVAL beyond the last,
+ * which is how a caller finds n): embedding lookup, normalisation forward, row sums of squares, rotary
+ * embedding, activation forward / backward, softmax forward / backward, cross-entropy, normalisation backward
+ * (dX; gain and shift), column sums, embedding gradient, first-token gather / scatter.  name receives a static
+ * string; bytes is the algorithmic traffic: every element the kernels had to read once plus every element they
+ * had to write once (section "Wallclock Time Efficiency" does not cost these steps; the figure is what an
+ * HBM roofline needs). */
 hift_status hift_profile_enable(hift_model* mdl, int32_t on);
 hift_status hift_profile_read(hift_model* mdl, int32_t category, int64_t* launches, double* total_ms,
                               double* work);
+hift_status hift_profile_read_rowwise(hift_model* mdl, int32_t kind, const char** name, int64_t* launches,
+                                      double* total_ms, double* bytes);
 
 const char* hift_last_error(void); /* message of the last failing call on this thread */
 void hift_model_destroy(hift_model* mdl);

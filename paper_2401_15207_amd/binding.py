@@ -31,7 +31,7 @@ class Config(C.Structure):
                 ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("max_seq", C.c_int32), ("n_classes", C.c_int32),
                 ("norm_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32),
                 ("state_on_host", C.c_int32), ("master_on_host", C.c_int32), ("no_packed_copies", C.c_int32),
-                ("tie_embeddings", C.c_int32)]
+                ("tie_embeddings", C.c_int32), ("lora_rank", C.c_int32), ("lora_alpha", C.c_float), ("unfused", C.c_int32)]
 
 
 class Memory(C.Structure):
@@ -75,12 +75,18 @@ _SIGS = {
     "hift_checkpoint_save": [_vp, _vp, _sz],
     "hift_checkpoint_load": [_vp, _vp, _sz],
     "hift_model_create": [_P(Config), _P(Opt), _i32, _i32, _i32, _vp, _vp, _sz, _vp, _sz, _vp, _vp, _vp, _P(_vp)],
+    "hift_model_create_chunked": [_P(Config), _P(Opt), _i32, _i32, _i32, _vp, _vp, _sz, _P(_vp), _P(_sz), _i32, _vp, _vp, _vp,
+                                  _P(_vp)],
     "hift_set_group_schedule": [_vp, C.c_int, _i32, _u64, _P(_i32)],
     "hift_schedule_group_at": [_vp, _i64, _P(_i32)],
     "hift_group_units": [_vp, _i32, _P(_i32), _P(_i32)],
     "hift_step": [_vp, _P(Batch), _i32, _P(C.c_float)],
     "hift_set_lr": [_vp, C.c_double],
     "hift_cycle_index": [_vp, _P(_i64), _P(_i64)],
+    "hift_lora_param_count": [_P(Config), _P(_i64)],
+    "hift_lora_write": [_vp, _vp, _sz],
+    "hift_lora_read": [_vp, _i32, _vp, _sz],
+    "hift_lora_step": [_vp, _P(Batch), _P(C.c_float)],
     "hift_read_params": [_vp, _i32, _i32, _i32, _vp, _sz],
     "hift_write_params": [_vp, _i32, _i32, _vp, _sz],
     "hift_read_state": [_vp, _i32, _i32, _i32, _vp, _sz],
@@ -89,6 +95,7 @@ _SIGS = {
     "hift_set_state_copy_engine": [_vp, _i32, _i32],
     "hift_profile_enable": [_vp, _i32],
     "hift_profile_read": [_vp, _i32, _P(_i64), _P(C.c_double), _P(C.c_double)],
+    "hift_profile_read_rowwise": [_vp, _i32, _P(C.c_char_p), _P(_i64), _P(C.c_double), _P(C.c_double)],
     "hift_kernel_gemm": [_i32, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp,
                          _i32, _i64, _i64, _i64, _vp],
     "hift_kernel_packed_bytes": [_i64, _i64, _P(_sz)],
@@ -125,7 +132,8 @@ def make_config(cfg: dict, state_on_host: int = 0) -> Config:
     return Config(cfg["arch"], cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["d_ffn"], cfg["vocab"],
                   cfg["max_seq"], cfg.get("n_classes", 0), cfg["norm_eps"], cfg.get("rope_base", 10000.0),
                   cfg["dtype"], cfg.get("state_on_host", state_on_host), cfg.get("master_on_host", 0),
-                  cfg.get("no_packed_copies", 0), cfg.get("tie_embeddings", 0))
+                  cfg.get("no_packed_copies", 0), cfg.get("tie_embeddings", 0), cfg.get("lora_rank", 0),
+                  cfg.get("lora_alpha", 0.0), cfg.get("unfused", 0))
 
 
 def make_opt(opt: dict) -> Opt:
@@ -247,6 +255,7 @@ def kernel_gemm_packed_static(out_f32, M, N, K, A, lda, Bp, Cm, ldc, bias=None, 
 
 
 EPILOGUE_SWIGLU, EPILOGUE_ROPE, EPILOGUE_SWIGLU_BWD = 1, 2, 3
+UNFUSED_EPILOGUES, UNFUSED_ATTENTION, UNFUSED_NORM, UNSHARED_LAST_ROUND = 1, 2, 4, 8   # hift_config.unfused
 
 
 def kernel_linear_fused(epilogue, M, N, K, A, lda, W, packed_scratch, C, aux, cos_sin, seq, rot_cols, stream=None):
@@ -313,6 +322,9 @@ def _hip_runtime():
     raise RuntimeError("no HIP runtime is loaded")
 
 
+PINNED_CHUNK_BYTES = 32 << 30   # default size of the blocks the pinned arena is allocated in
+
+
 class _PinnedArena:
     """Page-locked host memory of exactly the size asked for.  torch's pinned allocator rounds a
     request up to a power of two, which for arenas of tens of GB can double the host memory used."""
@@ -346,7 +358,9 @@ class HiftModel:
     """Owns the arenas (torch tensors) and streams a hift_model lives in."""
 
     def __init__(self, cfg: dict, opt: dict, m: int, max_batch: int, max_seq: int, init_params=None,
-                 state_on_host: int = 0, device: str = "cuda:0", master_on_host: int = 0, no_packed_copies: int = 0):
+                 state_on_host: int = 0, device: str = "cuda:0", master_on_host: int = 0, no_packed_copies: int = 0,
+                 unfused: int = 0, pinned_chunk_bytes: int = PINNED_CHUNK_BYTES, lora_rank: int = 0,
+                 lora_alpha: float = 0.0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("HiftModel needs a GPU: there is no CPU path")
@@ -354,14 +368,20 @@ class HiftModel:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.cfg = dict(cfg, state_on_host=state_on_host, master_on_host=master_on_host,
-                        no_packed_copies=no_packed_copies)
+                        no_packed_copies=no_packed_copies, unfused=unfused, lora_rank=lora_rank, lora_alpha=lora_alpha)
         self.c, self.o = make_config(self.cfg), make_opt(opt)
         self.opt_dict, self.m0, self.max_batch, self.max_seq = dict(opt), m, max_batch, max_seq
         dbytes, pbytes = query_bytes(self.cfg, opt, m, max_batch, max_seq)
         self.device_arena = torch.empty(dbytes + 256, dtype=torch.uint8, device=self.device)
         base = self.device_arena.data_ptr()
         self._dev_ptr = (base + 255) & ~255
-        self.pinned_arena = _PinnedArena(pbytes) if pbytes else None
+        # the pinned arena in chunks of at most pinned_chunk_bytes: hosts refuse very large page-locked blocks
+        self.pinned_chunks = []
+        left = pbytes
+        while left > 0:
+            n = min(left, max(16, pinned_chunk_bytes & ~15))
+            self.pinned_chunks.append(_PinnedArena((n + 15) & ~15))
+            left -= n
         self.compute_stream = torch.cuda.Stream(self.device)
         self.h2d_stream = torch.cuda.Stream(self.device)
         self.d2h_stream = torch.cuda.Stream(self.device)
@@ -370,11 +390,19 @@ class HiftModel:
         if init_params is not None:
             init = np.ascontiguousarray(init_params, dtype=np.float32)
         h = _vp()
-        _check(lib.hift_model_create(C.byref(self.c), C.byref(self.o), m, max_batch, max_seq,
-                                     None if init is None else init.ctypes.data, self._dev_ptr, dbytes,
-                                     None if self.pinned_arena is None else self.pinned_arena.data_ptr(), pbytes,
-                                     self.compute_stream.cuda_stream, self.h2d_stream.cuda_stream,
-                                     self.d2h_stream.cuda_stream, C.byref(h)))
+        nch = len(self.pinned_chunks)
+        ptrs = (_vp * max(nch, 1))(*[a.data_ptr() for a in self.pinned_chunks])
+        sizes = (_sz * max(nch, 1))(*[a.nbytes for a in self.pinned_chunks])
+        if nch == 1:
+            _check(lib.hift_model_create(C.byref(self.c), C.byref(self.o), m, max_batch, max_seq,
+                                         None if init is None else init.ctypes.data, self._dev_ptr, dbytes,
+                                         ptrs[0], sizes[0], self.compute_stream.cuda_stream,
+                                         self.h2d_stream.cuda_stream, self.d2h_stream.cuda_stream, C.byref(h)))
+        else:
+            _check(lib.hift_model_create_chunked(C.byref(self.c), C.byref(self.o), m, max_batch, max_seq,
+                                                 None if init is None else init.ctypes.data, self._dev_ptr, dbytes,
+                                                 ptrs, sizes, nch, self.compute_stream.cuda_stream,
+                                                 self.h2d_stream.cuda_stream, self.d2h_stream.cuda_stream, C.byref(h)))
         self.h = h
         self.k = None
         self.tensors, self.n_params = tensor_list(self.cfg)
@@ -384,9 +412,9 @@ class HiftModel:
         if getattr(self, "h", None):
             lib.hift_model_destroy(self.h)      # waits for the streams
             self.h = None
-        if getattr(self, "pinned_arena", None) is not None:
-            self.pinned_arena.free()
-            self.pinned_arena = None
+        for a in getattr(self, "pinned_chunks", []):
+            a.free()
+        self.pinned_chunks = []
 
     def __del__(self):
         try:
@@ -416,7 +444,38 @@ class HiftModel:
         assert tokens.is_cuda and labels.is_cuda and tokens.is_contiguous() and labels.is_contiguous()
         b = Batch(tokens.data_ptr(), labels.data_ptr(), tokens.shape[0], tokens.shape[1])
         loss = C.c_float()
+        # the batch may still be in the making on torch's current stream: the step starts after it, and the
+        # caching allocator must not hand the buffers out again before the step has read them
+        cur = self.torch.cuda.current_stream()
+        self.compute_stream.wait_stream(cur)
+        tokens.record_stream(self.compute_stream)
+        labels.record_stream(self.compute_stream)
         _check(lib.hift_step(self.h, C.byref(b), group_id, C.byref(loss) if want_loss else None))
+        return loss.value if want_loss else None
+
+    def lora_param_count(self) -> int:
+        n = _i64()
+        _check(lib.hift_lora_param_count(C.byref(self.c), C.byref(n)))
+        return n.value
+
+    def lora_write(self, values: np.ndarray):
+        v = np.ascontiguousarray(values, dtype=np.float32)
+        _check(lib.hift_lora_write(self.h, v.ctypes.data, v.size))
+
+    def lora_read(self, which: int = 0) -> np.ndarray:
+        out = np.empty(self.lora_param_count(), dtype=np.float32)
+        _check(lib.hift_lora_read(self.h, which, out.ctypes.data, out.size))
+        return out
+
+    def lora_step(self, tokens, labels, want_loss: bool = True):
+        assert tokens.dtype == self.torch.int32 and labels.dtype == self.torch.int32
+        assert tokens.is_cuda and labels.is_cuda and tokens.is_contiguous() and labels.is_contiguous()
+        b = Batch(tokens.data_ptr(), labels.data_ptr(), tokens.shape[0], tokens.shape[1])
+        loss = C.c_float()
+        self.compute_stream.wait_stream(self.torch.cuda.current_stream())
+        tokens.record_stream(self.compute_stream)
+        labels.record_stream(self.compute_stream)
+        _check(lib.hift_lora_step(self.h, C.byref(b), C.byref(loss) if want_loss else None))
         return loss.value if want_loss else None
 
     def set_lr(self, lr: float):
@@ -467,8 +526,11 @@ class HiftModel:
     def train(self, batches, n_steps: int, want_losses: bool = True):
         """batches: list of (tokens, labels) device tensors; returns the losses (or None)."""
         arr = (Batch * len(batches))()
+        self.compute_stream.wait_stream(self.torch.cuda.current_stream())  # the batches may still be in the making
         for i, (tok, lab) in enumerate(batches):
             arr[i] = Batch(tok.data_ptr(), lab.data_ptr(), tok.shape[0], tok.shape[1])
+            tok.record_stream(self.compute_stream)
+            lab.record_stream(self.compute_stream)
         losses = np.empty(n_steps, dtype=np.float32) if want_losses else None
         _check(lib.hift_train(self.h, arr, len(batches), n_steps, None if losses is None else losses.ctypes.data))
         return losses
@@ -499,6 +561,17 @@ class HiftModel:
         n, ms, w = _i64(), C.c_double(), C.c_double()
         _check(lib.hift_profile_read(self.h, category, C.byref(n), C.byref(ms), C.byref(w)))
         return n.value, ms.value, w.value
+
+    def profile_read_rowwise(self):
+        """{kind name: (launches, total ms, algorithmic bytes)} of the row-wise kernels since profile_enable."""
+        out, kind = {}, 0
+        while True:
+            name, n, ms, w = C.c_char_p(), _i64(), C.c_double(), C.c_double()
+            if lib.hift_profile_read_rowwise(self.h, kind, C.byref(name), C.byref(n), C.byref(ms), C.byref(w)) != 0:
+                break                                   # past the last kind
+            out[name.value.decode()] = (n.value, ms.value, w.value)
+            kind += 1
+        return out
 
     def synchronize(self):
         self.compute_stream.synchronize()

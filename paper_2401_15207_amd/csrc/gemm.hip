@@ -15,7 +15,6 @@
 //     activation operand through a ring of direct-to-LDS stages, epilogues (bias, residual, RoPE, SwiGLU and GELU
 //     forward and backward, folded RMS normalisation) straight from the accumulators.  See further down.
 //   * fp32 and odd shapes: a plain 64x64x16 LDS-tiled FMA kernel with arbitrary strides.
-#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -824,9 +823,14 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
   const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4*>(Bp), 0, (int)(uint32_t)pk_bytes, 0x00020000);
   const uint32_t vb = (uint32_t)lane * 16;
   const uint32_t nb0 = (uint32_t)((n0 >> 5) + wave * NT);
+  // Inline assembly, like the direct-to-LDS loads of A: the compiler counts only the loads it knows of, so with this
+  // one a builtin it waited, before every use of a fragment, until no more than the 15 younger B loads were
+  // outstanding -- but the requests for A lie between them, which made the fragments wait for loads issued five
+  // k-steps after them instead of eight.  The waits are placed by hand in kstep, with the true counts.
   auto load_b1 = [&](u32x4& dst, int64_t kk, int j) __attribute__((always_inline)) {
     const int64_t kc = kk < k_steps ? kk : k_steps - 1;  // past the end: the last block again
-    dst = __builtin_amdgcn_raw_buffer_load_b128(rsB, (int)vb, (int)(uint32_t)(((nb0 + j) * k_steps + kc) * 1024), 0);
+    const uint32_t so = (uint32_t)(((nb0 + j) * k_steps + kc) * 1024);
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(dst) : "v"(vb), "s"(rsB), "s"(so) : "memory");
   };
 
   const int frow = lane & 31, fhalf = lane >> 5;
@@ -877,13 +881,19 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
   auto kstep = [&](auto KS_, auto SLOT_, auto MAIN_, int64_t kt, const unsigned char* src_next) __attribute__((always_inline)) {
     constexpr int KS = decltype(KS_)::value, SLOT = decltype(SLOT_)::value;
     constexpr bool refill = decltype(MAIN_)::value != 0, read_next = decltype(MAIN_)::value != 2;  // 1: in the loop; 0, 2: tail
-    bf16x8 b[NT];
-#pragma unroll
-    for (int j = 0; j < NT; ++j) b[j] = __builtin_bit_cast(bf16x8, bq[SLOT][j]);
+    // Loads issued since the fragment about to be used was requested (PKF k-steps = PKF / 4 stages ago; a stage
+    // issues 8 B fragments and NP pieces of A): everything of those stages but the fragment itself (first B
+    // fragment, used from q = 0) or but this k-step's share, which is not issued yet (second one, from q = MT).
+    // In the tail nothing is requested any more: wait for everything.
+    constexpr int W0 = refill ? (PKF / 4) * (8 + NP) - 1 : 0;
+    constexpr int W1 = refill ? (PKF / 4) * (8 + NP) - 2 - (KS < 2 ? NP / 2 : 0) : 0;
 #pragma unroll
     for (int q = 0; q < NT * MT; ++q) {
       const int j = q / MT, i = q % MT;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], fa[KS & 1][i], acc[i][j], 0, 0, 0);
+      // the fragment is an operand of the wait, so that the product cannot be moved in front of it
+      if (q == 0) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(bq[SLOT][0]) : "n"(W0) : "memory");
+      if (q == MT) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(bq[SLOT][1]) : "n"(W1) : "memory");
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bq[SLOT][j]), fa[KS & 1][i], acc[i][j], 0, 0, 0);
       if (read_next && q < MT) read_a1(fa[(KS + 1) & 1][q], src_next, (KS + 1) & 3, q);
       if (refill) {
         if (q == MT) load_b1(bq[SLOT][0], kt * 4 + KS + PKF, 0);
@@ -893,7 +903,8 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  static_assert(PKF == 8 && NP % 2 == 0 && MT + NP / 2 < NT * MT && 19 + 2 * MT <= 63, "slot rotation and wait count below");
+  static_assert(PKF == 8 && NP % 2 == 0 && MT + NP / 2 < NT * MT && 19 + 2 * MT <= 63 && (PKF / 4) * (8 + NP) - 1 <= 63,
+                "slot rotation and wait counts");
   auto stage = [&](auto S0_, int64_t kt) __attribute__((always_inline)) {
     constexpr int S0 = decltype(S0_)::value;
     const unsigned char* cur = smem + (kt & (PK_STAGES - 1)) * STG;
@@ -925,7 +936,13 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
     kstep(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, kt, cur);
     kstep(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{}, kt, cur);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stray requests must land before LDS is reused
+  // Stray requests must land before LDS is reused -- and before the registers of the B fragments are: the last
+  // refills are still on their way, and only as operands of this wait are those registers known to be taken.
+#pragma unroll
+  for (int s = 0; s < PKF; ++s) asm volatile("" : "+v"(bq[s][0]), "+v"(bq[s][1]));
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int s = 0; s < PKF; ++s) asm volatile("" : "+v"(bq[s][0]), "+v"(bq[s][1]));
   if constexpr (NORM_EPI) {
     if (p.rowsq) {
       const int r = tid >> 1;
@@ -1093,12 +1110,6 @@ hipError_t launch_mfma_layout(GemmP& p, bool ak, bool bk, bool ktail, bool vec, 
   return launch_mfma_tail<BM, BN, false, false, OutT>(p, ktail, vec, nz, st);
 }
 
-// HIFT_GEMM_PACKED=0 in the environment keeps every contraction on the register-staged kernels
-inline bool use_packed_kernel() {
-  static const bool on = [] { const char* e = getenv("HIFT_GEMM_PACKED"); return !(e && e[0] == '0'); }();
-  return on;
-}
-
 inline bool al16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; }
 
 }  // namespace
@@ -1144,7 +1155,7 @@ bool packed_gemm_applies(const Gemm& g) {
   // 32-bit byte offsets, also for the rows past the edge of the last tile and the stages requested past K
   const bool fits = (g.M + 256) * g.lda * 2 < (int64_t(1) << 32) && al16(g.A) && g.lda % 8 == 0 &&
                     packed_b_bytes(g.N, g.K) < (size_t(1) << 32);
-  if (!(vec && fits && use_packed_kernel())) return false;
+  if (!(vec && fits)) return false;
   return ((g.M + 32 * PK_MT - 1) / (32 * PK_MT)) * ((g.N + 255) / 256) >= 200;  // enough tiles to fill the chip
 }
 
@@ -1166,11 +1177,9 @@ hipError_t launch_pk(dim3 grid, int threads, int lds, hipStream_t st, const Gemm
 
 // How many workgroups share each tile of the last round of a problem of `blocks` tiles (1: the round is not shared):
 // 2 to 4 when at most half the compute units would have a tile, every share at least 8 stages of K long.
-// HIFT_GEMM_SPLIT=0 in the environment: never.
 static int shared_round_split(int blocks, int64_t K) {
-  static const bool split_on = [] { const char* e = getenv("HIFT_GEMM_SPLIT"); return !(e && e[0] == '0'); }();
   const int rem = blocks % 256;
-  if (!split_on || rem == 0 || rem > 128 || K % PK_DK != 0) return 1;
+  if (rem == 0 || rem > 128 || K % PK_DK != 0) return 1;
   int split = 256 / rem;
   if (split > 4) split = 4;
   while (split > 1 && K / PK_DK < 8 * split) --split;
@@ -1225,8 +1234,8 @@ hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
   constexpr int LDS = PK_STAGES * 32 * PK_MT * PK_ROW;  // ring of A stages
   static_assert(LDS <= 160 * 1024, "LDS of a gfx950 compute unit");
   p.tiles_m = (int)((p.M + 32 * PK_MT - 1) / (32 * PK_MT));
-  // The last round: if at most half the compute units would have a tile, 2 to 4 workgroups share each
-  // (HIFT_GEMM_SPLIT=0 in the environment: never).
+  // The last round: if at most half the compute units would have a tile and the caller gave a work space,
+  // 2 to 4 workgroups share each
   int blocks = p.tiles_m * p.tiles_n;
   const int rem = blocks % 256;
   if (g.ws && (reinterpret_cast<uintptr_t>(g.ws) & 15) == 0) {

@@ -85,6 +85,11 @@ hift_status check_config(const hift_config* c) {
   if (c->tie_embeddings && c->arch == HIFT_ARCH_POSTLN_ENCODER)
     return fail(HIFT_EINVAL, "tie_embeddings applies to the decoders (the encoder's head is a classifier)");
   if (!(c->norm_eps >= 0.f)) return fail(HIFT_EINVAL, "norm_eps must be >= 0");
+  if (c->unfused & ~(HIFT_UNFUSED_EPILOGUES | HIFT_UNFUSED_ATTENTION | HIFT_UNFUSED_NORM | HIFT_UNSHARED_LAST_ROUND))
+    return fail(HIFT_EINVAL, "unfused has unknown bits set (%d)", c->unfused);
+  if (c->lora_rank < 0 || (c->lora_rank > 0 && !(c->lora_alpha > 0.f))) return fail(HIFT_EINVAL, "lora_rank must be >= 0 and lora_alpha > 0");
+  if (c->lora_rank > 0 && c->dtype == HIFT_BF16 && c->lora_rank % 8 != 0)
+    return fail(HIFT_EINVAL, "lora_rank must be a multiple of 8 in bf16 mode (16-byte pieces of the adapter operands)");
   if (c->master_on_host && (c->dtype != HIFT_BF16 || !c->state_on_host))
     return fail(HIFT_EINVAL, "master_on_host needs dtype bf16 (the forward copy stays in HBM) and state_on_host");
   return HIFT_OK;
@@ -220,9 +225,49 @@ struct LayerAct {
 
 struct Prof {
   bool on = false;
-  struct Rec { hipEvent_t a, b; int cat; double work; };
+  struct Rec { hipEvent_t a, b; int cat, sub; double work; };
   std::vector<Rec> pool;
   size_t used = 0;
+};
+
+// The pinned host arena as the caller hands it in: one block, or several chunks (a host may grant page-locked memory
+// only in pieces smaller than the whole).  The library addresses it as one range of bytes -- [master (if it lives on
+// the host)][state 0][state 1], each n_params floats -- and splits every access where a chunk ends.
+struct PinnedSpace {
+  struct Chunk { unsigned char* base; size_t bytes, start; };
+  std::vector<Chunk> chunks;  // in address order of the logical range
+  size_t total = 0;
+  void add(void* p, size_t bytes) {
+    chunks.push_back(Chunk{reinterpret_cast<unsigned char*>(p), bytes, total});
+    total += bytes;
+  }
+  // fn(host pointer, bytes, offset within the request) for every piece of [off, off + bytes), in order
+  template <class F>
+  hift_status pieces(size_t off, size_t bytes, F fn) const {
+    size_t done = 0;
+    for (const Chunk& c : chunks) {
+      if (done == bytes) break;
+      const size_t lo = off + done;
+      if (lo < c.start || lo >= c.start + c.bytes) continue;
+      const size_t n = std::min(bytes - done, c.start + c.bytes - lo);
+      const hift_status s = fn(c.base + (lo - c.start), n, done);
+      if (s != HIFT_OK) return s;
+      done += n;
+    }
+    return done == bytes ? HIFT_OK : fail(HIFT_ESTATE, "access outside the pinned arena");
+  }
+  hift_status read(void* dst, size_t off, size_t bytes) const {
+    return pieces(off, bytes, [&](unsigned char* p, size_t n, size_t at) {
+      memcpy(reinterpret_cast<unsigned char*>(dst) + at, p, n);
+      return HIFT_OK;
+    });
+  }
+  hift_status write(size_t off, const void* src, size_t bytes) const {
+    return pieces(off, bytes, [&](unsigned char* p, size_t n, size_t at) {
+      memcpy(p, reinterpret_cast<const unsigned char*>(src) + at, n);
+      return HIFT_OK;
+    });
+  }
 };
 
 }  // namespace
@@ -258,9 +303,19 @@ struct hift_model {
   // while one is updated, the next group's state arrives in the second and the previous group's
   // drains from the third, so the two directions of the host link run at the same time.
   float* slot[NSLOT] = {nullptr, nullptr, nullptr};
-  float* host_state = nullptr;          // pinned [n_state][n_params]
-  float* host_master = nullptr;         // pinned [n_params] when the master lives on the host (before host_state)
+  PinnedSpace pin;                      // [master (when it lives on the host)][n_state][n_params] floats
+  size_t host_state_off = 0;            // byte offset of the state arrays in `pin` (the master, if there, comes first)
   float* cos_sin = nullptr;
+  // low-rank adapters on the query and value projections (cfg.lora_rank > 0).  Per layer, r = rank: A_q | A_v stacked
+  // [2r, d], then B_q [d, r], B_v [d, r]; all layers one after the other.  fp32 master, copy in the compute type,
+  // gradient and AdamW moments, all resident (4 r d values per layer).
+  int lora_r = 0;
+  int64_t n_lora = 0;
+  float *lora_master = nullptr, *lora_grad = nullptr, *lora_m = nullptr, *lora_v = nullptr;
+  void* lora_wc = nullptr;
+  std::vector<void*> lora_u;  // per layer: s (h A_q^T | h A_v^T), [T, 2r], kept for the backward pass
+  void* lora_du = nullptr;    // [T, 2r]
+  int64_t lora_t = 0;         // adapter updates so far
   std::vector<void*> xs;  // residual stream: xs[l] enters layer l, xs[L] enters the head
   std::vector<LayerAct> la;
   void *e0 = nullptr, *xf = nullptr, *xcls = nullptr, *logits = nullptr;
@@ -278,7 +333,9 @@ struct hift_model {
   // schedule
   int m = 0, k = 0;
   std::vector<int32_t> order;
-  std::vector<int64_t> group_steps;
+  // updates each unit has had; drives AdamW's bias correction, Adafactor's decay and SGD's first-buffer rule.
+  // Kept per unit, not per group, so that it stays right when the grouping changes while the state is kept.
+  std::vector<int64_t> unit_steps;
   int64_t t = 0;
   // learning-rate schedule evaluated at the cycle index (used by hift_train)
   int lr_kind = -1;  // -1: none set, the rate is whatever hift_set_lr left
@@ -334,6 +391,23 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes, s
     M.fac = (float*)b.take((size_t)M.n_fac * 4);
     b.cat = MEM_WORK;
     M.af_work = (float*)b.take(M.af_work_floats * 4);
+  }
+  if (M.lora_r > 0) {
+    const size_t nl = (size_t)M.n_lora;
+    b.cat = MEM_MASTER;
+    M.lora_master = (float*)b.take(nl * 4);
+    b.cat = MEM_FORWARD;
+    M.lora_wc = M.dt == DT_BF16 ? b.take(nl * 2) : (void*)M.lora_master;
+    b.cat = MEM_GRAD;
+    M.lora_grad = (float*)b.take(nl * 4);
+    b.cat = MEM_STATE;
+    M.lora_m = (float*)b.take(nl * 4);
+    M.lora_v = (float*)b.take(nl * 4);
+    b.cat = MEM_ACT;
+    M.lora_u.assign(c.n_layers, nullptr);
+    for (auto& u : M.lora_u) u = b.take(T * 2 * M.lora_r * es);
+    b.cat = MEM_WORK;
+    M.lora_du = b.take(T * 2 * M.lora_r * es);
   }
   b.cat = MEM_WORK;
   if (rms) M.cos_sin = (float*)b.take((size_t)c.max_seq * (d / H / 2) * 2 * 4);
@@ -416,10 +490,13 @@ hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_o
   M->maxT = (int64_t)max_batch * max_seq;
   build_layout(*cfg, M->lay);
   M->grad_cap = (largest_group(M->lay, m) + 63) & ~(int64_t)63;
-  M->n_state = n_state_of(*opt);
+  M->n_state = cfg->lora_rank > 0 ? 0 : n_state_of(*opt);  // with adapters the base model is never updated: no state for it
   M->on_host = cfg->state_on_host != 0;
   M->master_host = cfg->master_on_host != 0;
   M->n_move = M->n_state + (M->master_host ? 1 : 0);
+  M->unit_steps.assign(M->lay.n_units, 0);
+  M->lora_r = cfg->lora_rank;
+  M->n_lora = (int64_t)cfg->n_layers * 4 * cfg->lora_rank * cfg->d_model;
   M->n_fac = 0;
   M->af_work_floats = 0;
   if (opt->kind == HIFT_ADAFACTOR)
@@ -443,16 +520,17 @@ hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_o
       t.pk_fwd = (int64_t)M->wpk_bytes;
       M->wpk_bytes += (packed_b_bytes(t.rows, t.cols) + 255) & ~(size_t)255;
       // forward copies of the RMSNorm/RoPE/SwiGLU decoder whose epilogue applies the rotation or the gated
-      // activation; HIFT_EPI_FUSED=0 in the environment keeps the separate kernels
-      static const bool epi_on = [] { const char* e = getenv("HIFT_EPI_FUSED"); return !(e && e[0] == '0'); }();
+      // activation (cfg->unfused & HIFT_UNFUSED_EPILOGUES keeps the separate kernels)
+      const bool epi_on = !(cfg->unfused & HIFT_UNFUSED_EPILOGUES);
       const bool layer_t = t.unit >= 1 && t.unit <= cfg->n_layers;
       const std::string leaf = t.name.substr(t.name.find('.') + 1);
       if (epi_on && layer_t && cfg->arch == HIFT_ARCH_RMS_ROPE_DECODER && t.rows % 256 == 0) {
-        if (leaf == "wqkv" && cfg->d_model / cfg->n_heads == 128) t.pk_order = PK_ORDER_PAIR64;
+        // (with adapters the rotation stays a kernel of its own: the adapters' part is added to q before it)
+        if (leaf == "wqkv" && cfg->d_model / cfg->n_heads == 128 && cfg->lora_rank == 0) t.pk_order = PK_ORDER_PAIR64;
         if (leaf == "wgu") t.pk_order = PK_ORDER_HALVES;
-        // The normalisation in front of either goes into the contraction (Gemm::rowsq);
-        // HIFT_NORM_FOLDED=0 in the environment keeps the normalisation kernels
-        static const bool fold_on = [] { const char* e = getenv("HIFT_NORM_FOLDED"); return !(e && e[0] == '0'); }();
+        // The normalisation in front of either goes into the contraction (Gemm::rowsq), unless
+        // cfg->unfused & HIFT_UNFUSED_NORM keeps the normalisation kernels
+        const bool fold_on = !(cfg->unfused & HIFT_UNFUSED_NORM);
         if (fold_on && t.cols % 512 == 0 && t.cols <= 6144 && t.pk_order != PK_ORDER_PLAIN)
           t.pk_gain = M->lay.find(t.name.substr(0, t.name.find('.') + 1) + (leaf == "wqkv" ? "g1" : "g2"));
       }
@@ -488,11 +566,20 @@ hipError_t repack_units(hift_model* M, int ulo, int uhi) {
 // CAT_GEMM: linear layers (forward and dX) on the packed-operand kernel (the dominant kernel);
 // CAT_GEMM_REST: every other linear-layer contraction (dW, small shapes, fp32)
 enum { CAT_GEMM = 0, CAT_ATTN = 1, CAT_ELEM = 2, CAT_OPT = 3, CAT_GEMM_REST = 4, CAT_PACK = 5, CAT_N = 6 };
+// Kinds of row-wise / elementwise kernel inside CAT_ELEM, each timed with its algorithmic bytes: every element the
+// kernel has to read once plus every element it has to write once (gains, statistics and labels are not counted).
+enum { RW_EMBED_FWD = 0, RW_NORM_FWD, RW_ROW_SUMSQ, RW_ROPE, RW_ACT_FWD, RW_ACT_BWD, RW_SOFTMAX_FWD, RW_SOFTMAX_BWD,
+       RW_CROSS_ENTROPY, RW_NORM_BWD_DX, RW_NORM_BWD_PARAMS, RW_COL_SUM, RW_EMBED_BWD, RW_FIRST_ROWS, RW_N };
+const char* const RW_NAMES[RW_N] = {
+    "embedding lookup", "normalisation forward", "row sums of squares", "rotary embedding", "activation forward",
+    "activation backward", "softmax forward", "softmax backward", "cross-entropy with gradient", "normalisation backward dX",
+    "normalisation backward gain/shift", "column sums (bias gradient)", "embedding gradient (clear + scatter)",
+    "first-token gather / scatter"};
 
 struct Scope {
   hift_model* M;
   Prof::Rec* r = nullptr;
-  Scope(hift_model* m, int cat, double work) : M(m) {
+  Scope(hift_model* m, int cat, double work, int sub = 0) : M(m) {
     if (!M->prof.on) return;
     if (M->prof.used == M->prof.pool.size()) {
       Prof::Rec n{};
@@ -501,6 +588,7 @@ struct Scope {
     }
     r = &M->prof.pool[M->prof.used++];
     r->cat = cat;
+    r->sub = sub;
     r->work = work;
     (void)hipEventRecord(r->a, M->cs);
   }
@@ -510,6 +598,14 @@ struct Scope {
 };
 
 #define K_TRY(expr) HIP_TRY(expr)
+
+// A row-wise kernel launch (a launcher returning hipError_t) under its own timing scope
+#define RW(kind, bytes, call)                                                                      \
+  do {                                                                                             \
+    Scope rw_sc_(M, CAT_ELEM, (bytes), (kind));                                                    \
+    hipError_t rw_e_ = (call);                                                                     \
+    if (rw_e_ != hipSuccess) return fail(HIFT_EDEVICE, "kernel launch failed: %s", hipGetErrorString(rw_e_)); \
+  } while (0)
 
 #define ST_TRY(expr)                 \
   do {                               \
@@ -572,8 +668,7 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
         g.rowsq = M->rowsq; g.norm_eps = M->cfg.norm_eps; g.norm_stats = epi->norm_stats;
       }
     } else if (epi && epi->gelu && epi->act && !R && w.rows % 8 == 0) {
-      static const bool epi_on = [] { const char* e = getenv("HIFT_EPI_FUSED"); return !(e && e[0] == '0'); }();
-      if (epi_on) {
+      if (!(M->cfg.unfused & HIFT_UNFUSED_EPILOGUES)) {
         g.epi = EPI_GELU;
         g.C2 = epi->act; g.ldc2 = w.rows;
         if (!epi->keep_pre) g.C = nullptr;
@@ -584,7 +679,7 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
       *rowsq = *rowsq && g.epi == EPI_NONE && w.rows % 256 == 0;
       if (*rowsq) g.rowsq_out = M->rowsq;
     }
-    g.ws = M->gemm_ws;
+    g.ws = (M->cfg.unfused & HIFT_UNSHARED_LAST_ROUND) ? nullptr : M->gemm_ws;
     K_TRY(gemm_packed(g, M->wpk + w.pk_fwd, M->cs));
     return HIFT_OK;
   }
@@ -610,7 +705,7 @@ hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor&
   g.R = R; g.ldr = w.cols;
   Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
   if (w.pk_bwd >= 0 && packed_gemm_applies(g)) {
-    static const bool epi_on = [] { const char* e = getenv("HIFT_EPI_FUSED"); return !(e && e[0] == '0'); }();
+    const bool epi_on = !(M->cfg.unfused & HIFT_UNFUSED_EPILOGUES);
     if (epi_on && gate_pre && dgu && fused && !R && w.cols % 8 == 0 && (reinterpret_cast<uintptr_t>(dgu) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(gate_pre) & 15) == 0) {
       const int64_t width = gelu ? w.cols : 2 * w.cols;
@@ -619,7 +714,7 @@ hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor&
       g.C = dgu; g.ldc = width;
       *fused = true;
     }
-    g.ws = M->gemm_ws;
+    g.ws = (M->cfg.unfused & HIFT_UNSHARED_LAST_ROUND) ? nullptr : M->gemm_ws;
     K_TRY(gemm_packed(g, M->wpk + w.pk_bwd, M->cs));
     return HIFT_OK;
   }
@@ -643,15 +738,14 @@ hift_status linear_dw(hift_model* M, const void* dy, const void* x, int64_t rows
 }
 
 hift_status bias_grad(hift_model* M, const void* dy, int64_t rows, const Tensor& b, int64_t glo) {
-  Scope sc(M, CAT_ELEM, 0);
-  K_TRY(col_sum(M->dt, rows, b.rows, dy, b.rows, M->part, M->grad + (b.off - glo), M->cs));
+  RW(RW_COL_SUM, (double)rows * b.rows * M->es, col_sum(M->dt, rows, b.rows, dy, b.rows, M->part, M->grad + (b.off - glo), M->cs));
   return HIFT_OK;
 }
 
 // Whether a layer's attention runs on the fused kernels, forward and backward alike (the backward needs what
-// only the fused forward leaves, and the other way round).  HIFT_ATTN_FUSED=0 in the environment: never.
+// only the fused forward leaves, and the other way round).  Never with cfg.unfused & HIFT_UNFUSED_ATTENTION.
 bool attention_is_fused(const hift_model* M, const LayerAct& a, int S) {
-  static const bool fused_on = [] { const char* e = getenv("HIFT_ATTN_FUSED"); return !(e && e[0] == '0'); }();
+  const bool fused_on = !(M->cfg.unfused & HIFT_UNFUSED_ATTENTION);
   const int64_t d = M->cfg.d_model, hd = d / M->cfg.n_heads;
   return fused_on && attention_fwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, nullptr, a.ctx) &&
          attention_bwd_fused_applies(M->dt, S, (int)hd, 3 * d, d, a.qkv, a.ctx, M->D[2], M->dqkv);
@@ -678,10 +772,7 @@ hift_status attention_probs(hift_model* M, LayerAct& a, int B, int S) {
     Scope sc(M, CAT_ATTN, 2.0 * B * H * S * S * hd);
     K_TRY(gemm(g, M->cs));
   }
-  {
-    Scope sc(M, CAT_ELEM, 0);
-    K_TRY(softmax_fwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, M->prob, M->cs));
-  }
+  RW(RW_SOFTMAX_FWD, 2.0 * B * H * S * S * es, softmax_fwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, M->prob, M->cs));
   return HIFT_OK;
 }
 
@@ -764,10 +855,7 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
     Scope sc(M, CAT_ATTN, fl);
     K_TRY(gemm(g, M->cs));
   }
-  {
-    Scope sc(M, CAT_ELEM, 0);
-    K_TRY(softmax_bwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, M->prob, M->dprob, M->cs));
-  }
+  RW(RW_SOFTMAX_BWD, 3.0 * B * H * S * S * es, softmax_bwd(M->dt, (int64_t)B * H, S, 1.0f / sqrtf((float)hd), causal, M->prob, M->dprob, M->cs));
   {
     Gemm g;  // dq[i,e] = sum_j ds[i,j] k[j,e]
     batch(g);
@@ -793,6 +881,97 @@ hift_status attention_bwd(hift_model* M, LayerAct& a, const void* dctx, int B, i
   return HIFT_OK;
 }
 
+// ---- low-rank adapters (the LoRA baseline of section 4.3) ---------------------------------------------------
+// q = h Wq^T + s (h A_q^T) B_q^T, v likewise, s = alpha / r.  The scale is applied to the small intermediate
+// u = s (h A^T) in the forward pass and to its gradient in the backward pass, so that no weight is kept scaled.
+struct LoraPtrs {
+  unsigned char *acat, *bq, *bv;  // compute-type copies: A_q | A_v [2r, d], B_q [d, r], B_v [d, r]
+  float *g_acat, *g_bq, *g_bv;    // their gradients
+};
+LoraPtrs lora_ptrs(const hift_model* M, int l) {
+  const int64_t r = M->lora_r, d = M->cfg.d_model, per = 4 * r * d, es = M->es;
+  unsigned char* w = reinterpret_cast<unsigned char*>(M->lora_wc) + (int64_t)l * per * es;
+  float* g = M->lora_grad + (int64_t)l * per;
+  return LoraPtrs{w, w + 2 * r * d * es, w + 3 * r * d * es, g, g + 2 * r * d, g + 3 * r * d};
+}
+
+hift_status small_gemm(hift_model* M, const Gemm& g) {
+  Scope sc(M, CAT_GEMM_REST, 2.0 * g.M * g.N * g.K);
+  K_TRY(gemm(g, M->cs));
+  return HIFT_OK;
+}
+
+// Adds the adapters' part to the q and v columns of qkv [T, 3d] (before any rotation); h: the layer's input [T, d]
+hift_status lora_fwd(hift_model* M, int l, const void* h, int64_t T, void* qkv) {
+  const int64_t r = M->lora_r, d = M->cfg.d_model, es = M->es;
+  const LoraPtrs P = lora_ptrs(M, l);
+  unsigned char* u = reinterpret_cast<unsigned char*>(M->lora_u[l]);
+  Gemm g;  // u = h . (A_q | A_v)^T
+  g.dtype = M->dt;
+  g.M = T; g.N = 2 * r; g.K = d;
+  g.A = h; g.lda = d; g.B = P.acat; g.ldb = d; g.C = u; g.ldc = 2 * r;
+  ST_TRY(small_gemm(M, g));
+  RW(RW_ACT_FWD, 2.0 * T * 2 * r * es, scale_inplace(M->dt, T * 2 * r, M->cfg.lora_alpha / (float)r, u, M->cs));
+  for (int part = 0; part < 2; ++part) {  // q += u_q . B_q^T ; v += u_v . B_v^T, in place
+    Gemm a;
+    a.dtype = M->dt;
+    a.M = T; a.N = d; a.K = r;
+    a.A = u + part * r * es; a.lda = 2 * r;
+    a.B = part ? P.bv : P.bq; a.ldb = r;
+    a.C = reinterpret_cast<unsigned char*>(qkv) + part * 2 * d * es; a.ldc = 3 * d;
+    a.R = a.C; a.ldr = 3 * d;
+    ST_TRY(small_gemm(M, a));
+  }
+  return HIFT_OK;
+}
+
+// dqkv [T, 3d]: gradients of the projections as computed (before rotation).  Leaves the adapters' gradients of
+// layer l in M->lora_grad and, if dh is given, adds the adapters' part to the gradient of the layer's input.
+hift_status lora_bwd(hift_model* M, int l, const void* h, int64_t T, const void* dqkv, void* dh) {
+  const int64_t r = M->lora_r, d = M->cfg.d_model, es = M->es;
+  const LoraPtrs P = lora_ptrs(M, l);
+  const unsigned char* dq = reinterpret_cast<const unsigned char*>(dqkv);
+  unsigned char* u = reinterpret_cast<unsigned char*>(M->lora_u[l]);
+  unsigned char* du = reinterpret_cast<unsigned char*>(M->lora_du);
+  for (int part = 0; part < 2; ++part) {
+    const unsigned char* dy = dq + part * 2 * d * es;
+    Gemm a;  // d u_part = d y . B  [T, r]
+    a.dtype = M->dt;
+    a.M = T; a.N = r; a.K = d;
+    a.A = dy; a.lda = 3 * d;
+    a.B = part ? P.bv : P.bq; a.ldb = r; a.b_kmajor = false;
+    a.C = du + part * r * es; a.ldc = 2 * r;
+    ST_TRY(small_gemm(M, a));
+    Gemm b;  // d B = d y^T . u_part  [d, r]  (u carries the scale)
+    b.dtype = M->dt; b.out_f32 = true;
+    b.M = d; b.N = r; b.K = T;
+    b.A = dy; b.lda = 3 * d; b.a_kmajor = false;
+    b.B = u + part * r * es; b.ldb = 2 * r; b.b_kmajor = false;
+    b.C = part ? P.g_bv : P.g_bq; b.ldc = r;
+    ST_TRY(small_gemm(M, b));
+  }
+  RW(RW_ACT_BWD, 2.0 * T * 2 * r * es, scale_inplace(M->dt, T * 2 * r, M->cfg.lora_alpha / (float)r, du, M->cs));
+  {
+    Gemm c;  // d (A_q | A_v) = d u^T . h  [2r, d]
+    c.dtype = M->dt; c.out_f32 = true;
+    c.M = 2 * r; c.N = d; c.K = T;
+    c.A = du; c.lda = 2 * r; c.a_kmajor = false;
+    c.B = h; c.ldb = d; c.b_kmajor = false;
+    c.C = P.g_acat; c.ldc = d;
+    ST_TRY(small_gemm(M, c));
+  }
+  if (dh) {
+    Gemm e;  // d h += d u . (A_q | A_v)
+    e.dtype = M->dt;
+    e.M = T; e.N = d; e.K = 2 * r;
+    e.A = du; e.lda = 2 * r;
+    e.B = P.acat; e.ldb = d; e.b_kmajor = false;
+    e.C = dh; e.ldc = d; e.R = dh; e.ldr = d;
+    ST_TRY(small_gemm(M, e));
+  }
+  return HIFT_OK;
+}
+
 struct Names {
   const Tensor *n1g, *n1b, *wqkv, *bqkv, *wo, *bo, *n2g, *n2b, *w1, *b1, *w2, *b2;
 };
@@ -814,12 +993,6 @@ Names layer_names(const hift_model* M, int l) {
   return n;
 }
 
-hift_status ew(hift_model* M, hipError_t e) {
-  if (e != hipSuccess) return fail(HIFT_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
-  (void)M;
-  return HIFT_OK;
-}
-
 // keep_from: lowest unit the backward pass will reach; layers below it keep no pre-activations
 hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
   const hift_config& c = M->cfg;
@@ -827,14 +1000,14 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
   const int64_t T = (int64_t)B * S;
   const int d = c.d_model, f = c.d_ffn, H = c.n_heads, hd = d / H;
   const int dt = M->dt;
+  const double es = M->es;
   const bool enc = c.arch == HIFT_ARCH_POSTLN_ENCODER, rms = c.arch == HIFT_ARCH_RMS_ROPE_DECODER;
   hipStream_t st = M->cs;
   {
-    Scope sc(M, CAT_ELEM, 0);
     const void* pos = rms ? nullptr : M->W("pos_emb");
     void* dst = enc ? M->e0 : M->xs[0];
-    ST_TRY(ew(M, embed_fwd(dt, bt->tokens, T, S, d, c.vocab, M->W("tok_emb"), pos, dst, st)));
-    if (enc) ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, M->e0, M->W("lne_g"), M->W("lne_b"), M->xs[0], M->st_e, st)));
+    RW(RW_EMBED_FWD, (double)T * d * es * (pos ? 3 : 2), embed_fwd(dt, bt->tokens, T, S, d, c.vocab, M->W("tok_emb"), pos, dst, st));
+    if (enc) RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, false, T, d, c.norm_eps, M->e0, M->W("lne_g"), M->W("lne_b"), M->xs[0], M->st_e, st));
   }
   bool have_sq = false;  // M->rowsq holds the sums of squares of the rows the next normalisation takes
   for (int l = 0; l < c.n_layers; ++l) {
@@ -844,27 +1017,27 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
     const void* h1 = x;
     if (folds_norm(M, *n.wqkv, T)) {
       if (!have_sq) {
-        Scope sc(M, CAT_ELEM, 0);
-        ST_TRY(ew(M, row_sumsq(T, d, x, d / 64, M->rowsq, st)));
+        RW(RW_ROW_SUMSQ, 1.0 * T * d * es, row_sumsq(T, d, x, d / 64, M->rowsq, st));
       }
     } else if (!enc) {
-      Scope sc(M, CAT_ELEM, 0);
-      ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, x, M->W(*n.n1g), n.n1b ? M->W(*n.n1b) : nullptr, a.na, a.st1, st)));
+      RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, rms, T, d, c.norm_eps, x, M->W(*n.n1g), n.n1b ? M->W(*n.n1b) : nullptr, a.na, a.st1, st));
       h1 = a.na;
     }
     LinEpi rot;
     rot.S = S;
     rot.norm_stats = a.st1;
     ST_TRY(linear(M, h1, T, *n.wqkv, n.bqkv, nullptr, a.qkv, &rot));
+    if (M->lora_r > 0) {
+      if (rot.fused) return fail(HIFT_ESTATE, "adapters need the projections before their rotation");
+      ST_TRY(lora_fwd(M, l, h1, T, a.qkv));
+    }
     if (rms && !rot.fused) {
-      Scope sc(M, CAT_ELEM, 0);
-      ST_TRY(ew(M, rope(dt, a.qkv, T, S, H, hd, M->cos_sin, +1, st)));
+      RW(RW_ROPE, 4.0 * T * d * es, rope(dt, a.qkv, T, S, H, hd, M->cos_sin, +1, st));
     }
     ST_TRY(attention_fwd(M, a, B, S, l + 1 >= keep_from));
     if (enc) {
       ST_TRY(linear(M, a.ctx, T, *n.wo, n.bo, x, a.na));  // s1 = x + attn
-      Scope sc(M, CAT_ELEM, 0);
-      ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, a.na, M->W(*n.n1g), M->W(*n.n1b), a.xmid, a.st1, st)));
+      RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, false, T, d, c.norm_eps, a.na, M->W(*n.n1g), M->W(*n.n1b), a.xmid, a.st1, st));
     } else {
       have_sq = folds_norm(M, *n.w1, T);
       ST_TRY(linear(M, a.ctx, T, *n.wo, n.bo, x, a.xmid, nullptr, &have_sq));
@@ -872,12 +1045,10 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
     const void* h2 = a.xmid;
     if (folds_norm(M, *n.w1, T)) {
       if (!have_sq) {
-        Scope sc(M, CAT_ELEM, 0);
-        ST_TRY(ew(M, row_sumsq(T, d, a.xmid, d / 64, M->rowsq, st)));
+        RW(RW_ROW_SUMSQ, 1.0 * T * d * es, row_sumsq(T, d, a.xmid, d / 64, M->rowsq, st));
       }
     } else if (!enc) {
-      Scope sc(M, CAT_ELEM, 0);
-      ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, a.xmid, M->W(*n.n2g), n.n2b ? M->W(*n.n2b) : nullptr, a.nb, a.st2, st)));
+      RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, rms, T, d, c.norm_eps, a.xmid, M->W(*n.n2g), n.n2b ? M->W(*n.n2b) : nullptr, a.nb, a.st2, st));
       h2 = a.nb;
     }
     LinEpi gate;
@@ -887,14 +1058,12 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
     gate.gelu = !rms;
     ST_TRY(linear(M, h2, T, *n.w1, n.b1, nullptr, a.fpre, &gate));
     if (!gate.fused) {
-      Scope sc(M, CAT_ELEM, 0);
-      if (rms) ST_TRY(ew(M, swiglu_fwd(dt, T, f, a.fpre, a.act, st)));
-      else ST_TRY(ew(M, gelu_fwd(dt, T * f, a.fpre, a.act, st)));
+      if (rms) RW(RW_ACT_FWD, 3.0 * T * f * es, swiglu_fwd(dt, T, f, a.fpre, a.act, st));
+      else RW(RW_ACT_FWD, 2.0 * T * f * es, gelu_fwd(dt, T * f, a.fpre, a.act, st));
     }
     if (enc) {
       ST_TRY(linear(M, a.act, T, *n.w2, n.b2, a.xmid, a.nb));  // s2 = xmid + ffn
-      Scope sc(M, CAT_ELEM, 0);
-      ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, a.nb, M->W(*n.n2g), M->W(*n.n2b), M->xs[l + 1], a.st2, st)));
+      RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, false, T, d, c.norm_eps, a.nb, M->W(*n.n2g), M->W(*n.n2b), M->xs[l + 1], a.st2, st));
     } else {
       have_sq = l + 1 < c.n_layers && folds_norm(M, *layer_names(M, l + 1).wqkv, T);
       ST_TRY(linear(M, a.act, T, *n.w2, n.b2, a.xmid, M->xs[l + 1], nullptr, &have_sq));
@@ -903,21 +1072,17 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
   void* xl = M->xs[c.n_layers];
   if (enc) {
     {
-      Scope sc(M, CAT_ELEM, 0);
-      ST_TRY(ew(M, gather_first(dt, B, S, d, xl, M->xcls, st)));
+      RW(RW_FIRST_ROWS, 2.0 * B * d * es, gather_first(dt, B, S, d, xl, M->xcls, st));
     }
     ST_TRY(linear(M, M->xcls, B, M->T_("wc"), &M->T_("bc"), nullptr, M->logits));
-    Scope sc(M, CAT_ELEM, 0);
-    ST_TRY(ew(M, cross_entropy(dt, B, c.n_classes, M->logits, bt->labels, M->row_loss, M->loss_dev, st)));
+    RW(RW_CROSS_ENTROPY, 2.0 * (B) * (c.n_classes) * es, cross_entropy(dt, B, c.n_classes, M->logits, bt->labels, M->row_loss, M->loss_dev, st));
   } else {
     {
-      Scope sc(M, CAT_ELEM, 0);
-      if (rms) ST_TRY(ew(M, norm_fwd(dt, true, T, d, c.norm_eps, xl, M->W("gf"), nullptr, M->xf, M->st_f, st)));
-      else ST_TRY(ew(M, norm_fwd(dt, false, T, d, c.norm_eps, xl, M->W("lnf_g"), M->W("lnf_b"), M->xf, M->st_f, st)));
+      if (rms) RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, true, T, d, c.norm_eps, xl, M->W("gf"), nullptr, M->xf, M->st_f, st));
+      else RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, false, T, d, c.norm_eps, xl, M->W("lnf_g"), M->W("lnf_b"), M->xf, M->st_f, st));
     }
     ST_TRY(linear(M, M->xf, T, M->T_(c.tie_embeddings ? "tok_emb" : "whead"), nullptr, nullptr, M->logits));
-    Scope sc(M, CAT_ELEM, 0);
-    ST_TRY(ew(M, cross_entropy(dt, T, c.vocab, M->logits, bt->labels, M->row_loss, M->loss_dev, st)));
+    RW(RW_CROSS_ENTROPY, 2.0 * (T) * (c.vocab) * es, cross_entropy(dt, T, c.vocab, M->logits, bt->labels, M->row_loss, M->loss_dev, st));
   }
   return HIFT_OK;
 }
@@ -929,6 +1094,7 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
   const int64_t T = (int64_t)B * S;
   const int d = c.d_model, f = c.d_ffn, H = c.n_heads, hd = d / H;
   const int dt = M->dt, L = c.n_layers;
+  const double es = M->es;
   const bool enc = c.arch == HIFT_ARCH_POSTLN_ENCODER, rms = c.arch == HIFT_ARCH_RMS_ROPE_DECODER;
   hipStream_t st = M->cs;
   auto active = [&](int u) { return u >= ulo && u < uhi; };
@@ -945,8 +1111,7 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
     }
     if (ulo == L + 1) return HIFT_OK;
     ST_TRY(linear_dx(M, M->logits, B, wc, nullptr, M->dcls));
-    Scope sc(M, CAT_ELEM, 0);
-    ST_TRY(ew(M, scatter_first(dt, B, S, d, M->dcls, Dc, st)));
+    RW(RW_FIRST_ROWS, (double)T * d * es + 1.0 * B * d * es, scatter_first(dt, B, S, d, M->dcls, Dc, st));
   } else {
     // tied embeddings: the output matrix is the token table of unit 0; its gradient starts here and the
     // embedding part is added at the bottom of the backward pass
@@ -954,12 +1119,11 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
     if (c.tie_embeddings ? active(0) : head_on) ST_TRY(linear_dw(M, M->logits, M->xf, T, wh, glo));
     ST_TRY(linear_dx(M, M->logits, T, wh, nullptr, D2));  // d xf
     const Tensor& g = M->T_(rms ? "gf" : "lnf_g");
-    Scope sc(M, CAT_ELEM, 0);
     if (head_on)
-      ST_TRY(ew(M, norm_bwd_params(dt, rms, T, d, D2, M->xs[L], M->st_f, M->part, G(g),
-                                   rms ? nullptr : G(M->T_("lnf_b")), st)));
+      RW(RW_NORM_BWD_PARAMS, 2.0 * T * d * es, norm_bwd_params(dt, rms, T, d, D2, M->xs[L], M->st_f, M->part, G(g),
+                                   rms ? nullptr : G(M->T_("lnf_b")), st));
     if (ulo == L + 1) return HIFT_OK;
-    ST_TRY(ew(M, norm_bwd_dx(dt, rms, T, d, D2, M->xs[L], M->W(g), M->st_f, nullptr, Dc, st)));
+    RW(RW_NORM_BWD_DX, 3.0 * T * d * es, norm_bwd_dx(dt, rms, T, d, D2, M->xs[L], M->W(g), M->st_f, nullptr, Dc, st));
   }
 
   // ---- hidden layers, top down; Dc holds d loss / d xs[l+1] ----
@@ -980,25 +1144,22 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
       if (rms) ST_TRY(linear_dx(M, Dc, T, *n.w2, nullptr, M->dact, a.fpre, M->dffn, &gate_done));
       else ST_TRY(linear_dx(M, Dc, T, *n.w2, nullptr, M->dact, a.fpre, M->dffn, &gate_done, true));
       if (!gate_done) {
-        Scope sc(M, CAT_ELEM, 0);
-        if (rms) ST_TRY(ew(M, swiglu_bwd(dt, T, f, M->dact, a.fpre, M->dffn, st)));
-        else ST_TRY(ew(M, gelu_bwd(dt, T * f, M->dact, a.fpre, M->dffn, st)));
+        if (rms) RW(RW_ACT_BWD, 5.0 * T * f * es, swiglu_bwd(dt, T, f, M->dact, a.fpre, M->dffn, st));
+        else RW(RW_ACT_BWD, 3.0 * T * f * es, gelu_bwd(dt, T * f, M->dact, a.fpre, M->dffn, st));
       }
       if (on) {
         if (folds_norm(M, *n.w1, T)) {  // the forward pass never wrote the normalised rows
-          Scope sc(M, CAT_ELEM, 0);
-          ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, a.xmid, M->W(*n.n2g), nullptr, a.nb, a.st2, st)));
+          RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, rms, T, d, c.norm_eps, a.xmid, M->W(*n.n2g), nullptr, a.nb, a.st2, st));
         }
         ST_TRY(linear_dw(M, M->dffn, a.nb, T, *n.w1, glo));
         if (n.b1) ST_TRY(bias_grad(M, M->dffn, T, *n.b1, glo));
       }
       ST_TRY(linear_dx(M, M->dffn, T, *n.w1, nullptr, D2));  // d h2
       {
-        Scope sc(M, CAT_ELEM, 0);
         if (on)
-          ST_TRY(ew(M, norm_bwd_params(dt, rms, T, d, D2, a.xmid, a.st2, M->part, G(*n.n2g),
-                                       n.n2b ? G(*n.n2b) : nullptr, st)));
-        ST_TRY(ew(M, norm_bwd_dx(dt, rms, T, d, D2, a.xmid, M->W(*n.n2g), a.st2, Dc, D1, st)));  // d xmid
+          RW(RW_NORM_BWD_PARAMS, 2.0 * T * d * es, norm_bwd_params(dt, rms, T, d, D2, a.xmid, a.st2, M->part, G(*n.n2g),
+                                       n.n2b ? G(*n.n2b) : nullptr, st));
+        RW(RW_NORM_BWD_DX, 4.0 * T * d * es, norm_bwd_dx(dt, rms, T, d, D2, a.xmid, M->W(*n.n2g), a.st2, Dc, D1, st));  // d xmid
       }
       // xmid = x + Wo ctx
       if (on) {
@@ -1009,31 +1170,32 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
       bool unrotated = false;
       ST_TRY(attention_bwd(M, a, D2, B, S, &unrotated));
       if (rms && !unrotated) {
-        Scope sc(M, CAT_ELEM, 0);
-        ST_TRY(ew(M, rope(dt, M->dqkv, T, S, H, hd, M->cos_sin, -1, st)));
+        RW(RW_ROPE, 4.0 * T * d * es, rope(dt, M->dqkv, T, S, H, hd, M->cos_sin, -1, st));
       }
       if (on) {
         if (folds_norm(M, *n.wqkv, T)) {
-          Scope sc(M, CAT_ELEM, 0);
-          ST_TRY(ew(M, norm_fwd(dt, rms, T, d, c.norm_eps, x, M->W(*n.n1g), nullptr, a.na, a.st1, st)));
+          RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, rms, T, d, c.norm_eps, x, M->W(*n.n1g), nullptr, a.na, a.st1, st));
         }
         ST_TRY(linear_dw(M, M->dqkv, a.na, T, *n.wqkv, glo));
         if (n.bqkv) ST_TRY(bias_grad(M, M->dqkv, T, *n.bqkv, glo));
       }
+      if (M->lora_r > 0) {  // the adapters' gradients; with need_dx their part of d h1 is added below
+        if (folds_norm(M, *n.wqkv, T)) return fail(HIFT_ESTATE, "adapters need the normalised rows");
+        if (on || need_dx) ST_TRY(linear_dx(M, M->dqkv, T, *n.wqkv, nullptr, D2));  // d h1, base part
+        ST_TRY(lora_bwd(M, l, a.na, T, M->dqkv, (on || need_dx) ? D2 : nullptr));
+      }
       if (on || need_dx) {
-        ST_TRY(linear_dx(M, M->dqkv, T, *n.wqkv, nullptr, D2));  // d h1
-        Scope sc(M, CAT_ELEM, 0);
+        if (M->lora_r == 0) ST_TRY(linear_dx(M, M->dqkv, T, *n.wqkv, nullptr, D2));  // d h1
         if (on)
-          ST_TRY(ew(M, norm_bwd_params(dt, rms, T, d, D2, x, a.st1, M->part, G(*n.n1g),
-                                       n.n1b ? G(*n.n1b) : nullptr, st)));
-        if (need_dx) ST_TRY(ew(M, norm_bwd_dx(dt, rms, T, d, D2, x, M->W(*n.n1g), a.st1, D1, Dc, st)));
+          RW(RW_NORM_BWD_PARAMS, 2.0 * T * d * es, norm_bwd_params(dt, rms, T, d, D2, x, a.st1, M->part, G(*n.n1g),
+                                       n.n1b ? G(*n.n1b) : nullptr, st));
+        if (need_dx) RW(RW_NORM_BWD_DX, 4.0 * T * d * es, norm_bwd_dx(dt, rms, T, d, D2, x, M->W(*n.n1g), a.st1, D1, Dc, st));
       }
     } else {
       // x_out = LN2(s2), s2 = xmid + W2 gelu(W1 xmid);  xmid = LN1(s1), s1 = x + Wo ctx
       {
-        Scope sc(M, CAT_ELEM, 0);
-        if (on) ST_TRY(ew(M, norm_bwd_params(dt, false, T, d, Dc, a.nb, a.st2, M->part, G(*n.n2g), G(*n.n2b), st)));
-        ST_TRY(ew(M, norm_bwd_dx(dt, false, T, d, Dc, a.nb, M->W(*n.n2g), a.st2, nullptr, D1, st)));  // d s2
+        if (on) RW(RW_NORM_BWD_PARAMS, 2.0 * T * d * es, norm_bwd_params(dt, false, T, d, Dc, a.nb, a.st2, M->part, G(*n.n2g), G(*n.n2b), st));
+        RW(RW_NORM_BWD_DX, 3.0 * T * d * es, norm_bwd_dx(dt, false, T, d, Dc, a.nb, M->W(*n.n2g), a.st2, nullptr, D1, st));  // d s2
       }
       if (on) {
         ST_TRY(linear_dw(M, D1, a.act, T, *n.w2, glo));
@@ -1042,8 +1204,7 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
       bool gelu_done = false;
       ST_TRY(linear_dx(M, D1, T, *n.w2, nullptr, M->dact, a.fpre, M->dffn, &gelu_done, true));
       if (!gelu_done) {
-        Scope sc(M, CAT_ELEM, 0);
-        ST_TRY(ew(M, gelu_bwd(dt, T * f, M->dact, a.fpre, M->dffn, st)));
+        RW(RW_ACT_BWD, 3.0 * T * f * es, gelu_bwd(dt, T * f, M->dact, a.fpre, M->dffn, st));
       }
       if (on) {
         ST_TRY(linear_dw(M, M->dffn, a.xmid, T, *n.w1, glo));
@@ -1051,9 +1212,8 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
       }
       ST_TRY(linear_dx(M, M->dffn, T, *n.w1, D1, D2));  // d xmid = d s2 + dffn . W1
       {
-        Scope sc(M, CAT_ELEM, 0);
-        if (on) ST_TRY(ew(M, norm_bwd_params(dt, false, T, d, D2, a.na, a.st1, M->part, G(*n.n1g), G(*n.n1b), st)));
-        ST_TRY(ew(M, norm_bwd_dx(dt, false, T, d, D2, a.na, M->W(*n.n1g), a.st1, nullptr, D1, st)));  // d s1
+        if (on) RW(RW_NORM_BWD_PARAMS, 2.0 * T * d * es, norm_bwd_params(dt, false, T, d, D2, a.na, a.st1, M->part, G(*n.n1g), G(*n.n1b), st));
+        RW(RW_NORM_BWD_DX, 3.0 * T * d * es, norm_bwd_dx(dt, false, T, d, D2, a.na, M->W(*n.n1g), a.st1, nullptr, D1, st));  // d s1
       }
       if (on) {
         ST_TRY(linear_dw(M, D1, a.ctx, T, *n.wo, glo));
@@ -1067,17 +1227,17 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
         ST_TRY(bias_grad(M, M->dqkv, T, *n.bqkv, glo));
       }
       if (need_dx) ST_TRY(linear_dx(M, M->dqkv, T, *n.wqkv, D1, Dc));  // d x = d s1 + dqkv . Wqkv
+      if (M->lora_r > 0) ST_TRY(lora_bwd(M, l, x, T, M->dqkv, need_dx ? Dc : nullptr));
     }
   }
 
   // ---- embeddings unit (0) ----
   if (ulo == 0) {
-    Scope sc(M, CAT_ELEM, 0);
     const Tensor& te = M->T_("tok_emb");
     const void* dx = Dc;
     if (enc) {
-      ST_TRY(ew(M, norm_bwd_params(dt, false, T, d, Dc, M->e0, M->st_e, M->part, G(M->T_("lne_g")), G(M->T_("lne_b")), st)));
-      ST_TRY(ew(M, norm_bwd_dx(dt, false, T, d, Dc, M->e0, M->W("lne_g"), M->st_e, nullptr, D1, st)));
+      RW(RW_NORM_BWD_PARAMS, 2.0 * T * d * es, norm_bwd_params(dt, false, T, d, Dc, M->e0, M->st_e, M->part, G(M->T_("lne_g")), G(M->T_("lne_b")), st));
+      RW(RW_NORM_BWD_DX, 3.0 * T * d * es, norm_bwd_dx(dt, false, T, d, Dc, M->e0, M->W("lne_g"), M->st_e, nullptr, D1, st));
       dx = D1;
     }
     float* gpos = nullptr;
@@ -1088,8 +1248,8 @@ hift_status backward(hift_model* M, const hift_batch* bt, int ulo, int uhi, int6
       gpos = G(pe);
       zero_cnt += pe.count();  // pos_emb follows tok_emb in the layout
     }
-    if (zero_cnt) ST_TRY(ew(M, fill_zero(tied ? gpos : G(te), (size_t)zero_cnt * 4, st)));
-    ST_TRY(ew(M, embed_bwd(dt, bt->tokens, T, S, d, c.vocab, dx, G(te), gpos, tied, st)));
+    if (zero_cnt) RW(RW_EMBED_BWD, 1.0 * ((size_t)zero_cnt * 4), fill_zero(tied ? gpos : G(te), (size_t)zero_cnt * 4, st));
+    RW(RW_EMBED_BWD, (double)T * d * (es + 4.0), embed_bwd(dt, bt->tokens, T, S, d, c.vocab, dx, G(te), gpos, tied, st));
   }
   return HIFT_OK;
 }
@@ -1133,10 +1293,11 @@ hift_status fetch_state(hift_model* M, int gid, int s) {
   // runs up to a step ahead of the GPU, and a copy submitted while the copy engine still has
   // a backlog is executed by a full-grid copy kernel instead, which starves the step's kernels
   if (M->copy_engine == 0 && M->h2d_last >= 0) HIP_TRY(hipEventSynchronize(M->ev_h2d[M->h2d_last]));
-  float* host0 = M->master_host ? M->host_master : M->host_state;  // the pinned arrays are one block
-  for (int j = 0; j < M->n_move; ++j) {
-    ST_TRY(state_copy(M, M->slot[s] + (size_t)j * M->grad_cap, host0 + (size_t)j * M->lay.n_params + plo,
-                      (size_t)cnt * 4, true));
+  for (int j = 0; j < M->n_move; ++j) {  // array j of the pinned range: the master first when it travels, then the state
+    unsigned char* dst = reinterpret_cast<unsigned char*>(M->slot[s] + (size_t)j * M->grad_cap);
+    ST_TRY(M->pin.pieces(((size_t)j * M->lay.n_params + plo) * 4, (size_t)cnt * 4, [&](unsigned char* h, size_t n, size_t at) {
+      return state_copy(M, dst + at, h, n, true);
+    }));
     M->h2d_bytes += (uint64_t)cnt * 4;
   }
   HIP_TRY(hipEventRecord(M->ev_h2d[s], M->hs));
@@ -1152,7 +1313,10 @@ hift_status sync_all(hift_model* M);
 hift_status load_forward_copy(hift_model* M, int64_t off, int64_t cnt) {
   for (int64_t done = 0; done < cnt; done += M->grad_cap) {
     const int64_t n = std::min<int64_t>(M->grad_cap, cnt - done);
-    HIP_TRY(hipMemcpyAsync(M->slot[0], M->host_master + off + done, (size_t)n * 4, hipMemcpyHostToDevice, M->cs));
+    ST_TRY(M->pin.pieces((size_t)(off + done) * 4, (size_t)n * 4, [&](unsigned char* h, size_t nb, size_t at) {
+      HIP_TRY(hipMemcpyAsync(reinterpret_cast<unsigned char*>(M->slot[0]) + at, h, nb, hipMemcpyHostToDevice, M->cs));
+      return HIFT_OK;
+    }));
     HIP_TRY(cast_f32_to(DT_BF16, n, M->slot[0], (unsigned char*)M->wc + (off + done) * 2, M->cs));
     HIP_TRY(hipStreamSynchronize(M->cs));
   }
@@ -1273,6 +1437,17 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
                               int32_t max_seq, const float* init_params_host, void* device_arena,
                               size_t device_bytes, void* pinned_arena, size_t pinned_bytes, void* compute_stream,
                               void* h2d_stream, void* d2h_stream, hift_model** out) {
+  void* chunks[1] = {pinned_arena};
+  size_t sizes[1] = {pinned_bytes};
+  return hift_model_create_chunked(cfg, opt, m, max_batch, max_seq, init_params_host, device_arena, device_bytes, chunks,
+                                   sizes, pinned_arena ? 1 : 0, compute_stream, h2d_stream, d2h_stream, out);
+}
+
+hift_status hift_model_create_chunked(const hift_config* cfg, const hift_opt* opt, int32_t m, int32_t max_batch,
+                                      int32_t max_seq, const float* init_params_host, void* device_arena,
+                                      size_t device_bytes, void* const* pinned_chunks, const size_t* pinned_chunk_bytes,
+                                      int32_t n_chunks, void* compute_stream, void* h2d_stream, void* d2h_stream,
+                                      hift_model** out) {
   if (!out) return fail(HIFT_EINVAL, "out is null");
   *out = nullptr;
   hift_model* M = new hift_model();
@@ -1284,13 +1459,23 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
     delete M;
     return fail(HIFT_EINVAL, "device arena must be non-null and 256-byte aligned");
   }
-  if (device_bytes < need_dev || pinned_bytes < need_pin || (need_pin > 0 && !pinned_arena)) {
+  if (n_chunks < 0 || (n_chunks > 0 && (!pinned_chunks || !pinned_chunk_bytes))) {
+    delete M;
+    return fail(HIFT_EINVAL, "pinned chunks: negative count or null arrays");
+  }
+  for (int i = 0; i < n_chunks && M->pin.total < need_pin; ++i) {
+    if (!pinned_chunks[i] || pinned_chunk_bytes[i] % 16 != 0 || (reinterpret_cast<uintptr_t>(pinned_chunks[i]) & 15)) {
+      delete M;
+      return fail(HIFT_EINVAL, "pinned chunk %d is null, not 16-byte aligned or not a multiple of 16 bytes long", i);
+    }
+    M->pin.add(pinned_chunks[i], std::min(pinned_chunk_bytes[i], need_pin - M->pin.total));
+  }
+  if (device_bytes < need_dev || M->pin.total < need_pin) {
     delete M;
     return fail(HIFT_ENOMEM, "arenas too small: need %zu device and %zu pinned bytes", need_dev, need_pin);
   }
   carve(M, device_arena, nullptr, nullptr);
-  M->host_master = (need_pin && M->master_host) ? reinterpret_cast<float*>(pinned_arena) : nullptr;
-  M->host_state = (need_pin && M->n_state > 0) ? reinterpret_cast<float*>(pinned_arena) + (M->master_host ? M->lay.n_params : 0) : nullptr;
+  M->host_state_off = M->master_host ? (size_t)M->lay.n_params * 4 : 0;
   M->cs = (hipStream_t)compute_stream;
   M->hs = (hipStream_t)h2d_stream;
   M->ds = (hipStream_t)d2h_stream;
@@ -1312,7 +1497,7 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
   CR_TRY(hipEventCreate(&M->ev_t1));
   CR_TRY(hipEventCreate(&M->ev_w0));
   CR_TRY(hipEventCreate(&M->ev_w1));
-  if (need_pin) memset(pinned_arena, 0, need_pin);
+  for (const PinnedSpace::Chunk& ch : M->pin.chunks) memset(ch.base, 0, ch.bytes);
   // state and gradient buffers start at zero
   if (M->state_full) CR_TRY(fill_zero(M->state_full, (size_t)M->n_state * M->lay.n_params * 4, M->cs));
   for (int q = 0; q < NSLOT; ++q)
@@ -1320,6 +1505,13 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
   CR_TRY(fill_zero(M->grad, (size_t)M->grad_cap * 4, M->cs));
   if (M->gemm_ws) CR_TRY(fill_zero(M->gemm_ws, 1024, M->cs));  // the counters; every launch leaves them at zero
   if (M->fac) CR_TRY(fill_zero(M->fac, (size_t)M->n_fac * 4, M->cs));
+  if (M->lora_r > 0) {  // adapters start at zero (the model is the base model) until hift_lora_write; so do their moments
+    CR_TRY(fill_zero(M->lora_master, (size_t)M->n_lora * 4, M->cs));
+    if (M->dt == DT_BF16) CR_TRY(fill_zero(M->lora_wc, (size_t)M->n_lora * 2, M->cs));
+    CR_TRY(fill_zero(M->lora_grad, (size_t)M->n_lora * 4, M->cs));
+    CR_TRY(fill_zero(M->lora_m, (size_t)M->n_lora * 4, M->cs));
+    CR_TRY(fill_zero(M->lora_v, (size_t)M->n_lora * 4, M->cs));
+  }
   if (M->cos_sin) {
     const int hd2 = cfg->d_model / cfg->n_heads / 2;
     std::vector<float> tab((size_t)cfg->max_seq * hd2 * 2);
@@ -1333,7 +1525,7 @@ hift_status hift_model_create(const hift_config* cfg, const hift_opt* opt, int32
     CR_TRY(hipStreamSynchronize(M->cs));
   }
   if (M->master_host) {
-    if (init_params_host) memcpy(M->host_master, init_params_host, (size_t)M->lay.n_params * 4);
+    if (init_params_host && M->pin.write(0, init_params_host, (size_t)M->lay.n_params * 4) != HIFT_OK) return bail(HIFT_ESTATE);
     if (load_forward_copy(M, 0, M->lay.n_params) != HIFT_OK) return bail(HIFT_EDEVICE);
   } else {
     if (init_params_host) {
@@ -1380,7 +1572,6 @@ hift_status hift_set_group_schedule(hift_model* M, hift_strategy s, int32_t m, u
   M->k = group_count(M->lay.n_units, m);
   M->order.resize(M->k);
   make_order(M->k, (int)s, seed, M->order.data());
-  M->group_steps.assign(M->k, 0);
   M->t = 0;
   if (k_out) *k_out = M->k;
   return HIFT_OK;
@@ -1459,10 +1650,10 @@ struct CkptHeader {
   double lr, lr_base;
   int64_t lr_warmup, lr_total;
 };
-constexpr char CKPT_MAGIC[8] = {'H', 'I', 'F', 'T', 'C', 'K', 'P', '1'};
+constexpr char CKPT_MAGIC[8] = {'H', 'I', 'F', 'T', 'C', 'K', 'P', '2'};
 
 size_t ckpt_bytes(const hift_model* M) {
-  return sizeof(CkptHeader) + (size_t)M->k * (4 + 8) +
+  return sizeof(CkptHeader) + (size_t)M->k * 4 + (size_t)M->lay.n_units * 8 +
          ((size_t)M->lay.n_params * (1 + M->n_state) + (size_t)M->n_fac) * 4;
 }
 }  // namespace
@@ -1483,17 +1674,17 @@ hift_status hift_checkpoint_save(hift_model* M, void* host_buffer, size_t bytes)
   CkptHeader h{};
   memcpy(h.magic, CKPT_MAGIC, 8);
   h.n_params = M->lay.n_params; h.n_fac = M->n_fac; h.t = M->t;
-  h.version = 1; h.n_state = M->n_state; h.k = M->k; h.m = M->m; h.lr_kind = M->lr_kind; h.opt_kind = M->opt.kind;
+  h.version = 2; h.n_state = M->n_state; h.k = M->k; h.m = M->m; h.lr_kind = M->lr_kind; h.opt_kind = M->opt.kind;
   h.lr = M->opt.lr; h.lr_base = M->lr_base; h.lr_warmup = M->lr_warmup; h.lr_total = M->lr_total;
   memcpy(p, &h, sizeof(h)); p += sizeof(h);
   memcpy(p, M->order.data(), (size_t)M->k * 4); p += (size_t)M->k * 4;
-  memcpy(p, M->group_steps.data(), (size_t)M->k * 8); p += (size_t)M->k * 8;
+  memcpy(p, M->unit_steps.data(), (size_t)M->lay.n_units * 8); p += (size_t)M->lay.n_units * 8;
   const size_t np4 = (size_t)M->lay.n_params * 4;
-  if (M->master_host) memcpy(p, M->host_master, np4);
+  if (M->master_host) ST_TRY(M->pin.read(p, 0, np4));
   else HIP_TRY(hipMemcpy(p, M->master, np4, hipMemcpyDeviceToHost));
   p += np4;
   for (int j = 0; j < M->n_state; ++j, p += np4) {
-    if (M->on_host) memcpy(p, M->host_state + (size_t)j * M->lay.n_params, np4);
+    if (M->on_host) ST_TRY(M->pin.read(p, M->host_state_off + (size_t)j * np4, np4));
     else HIP_TRY(hipMemcpy(p, M->state_full + (size_t)j * M->lay.n_params, np4, hipMemcpyDeviceToHost));
   }
   if (M->n_fac) HIP_TRY(hipMemcpy(p, M->fac, (size_t)M->n_fac * 4, hipMemcpyDeviceToHost));
@@ -1506,28 +1697,38 @@ hift_status hift_checkpoint_load(hift_model* M, const void* host_buffer, size_t 
   const unsigned char* p = reinterpret_cast<const unsigned char*>(host_buffer);
   CkptHeader h;
   memcpy(&h, p, sizeof(h)); p += sizeof(h);
-  if (memcmp(h.magic, CKPT_MAGIC, 8) != 0 || h.version != 1) return fail(HIFT_EINVAL, "not a checkpoint of this library");
+  if (memcmp(h.magic, CKPT_MAGIC, 8) != 0 || h.version != 2) return fail(HIFT_EINVAL, "not a checkpoint of this library");
   if (h.n_params != M->lay.n_params || h.n_state != M->n_state || h.n_fac != M->n_fac || h.opt_kind != M->opt.kind)
     return fail(HIFT_EINVAL, "checkpoint is of another model or optimizer (%lld parameters, %d state arrays)",
                 (long long)h.n_params, h.n_state);
   if (h.k < 1 || h.m < 1 || h.k != group_count(M->lay.n_units, h.m) || largest_group(M->lay, h.m) > M->grad_cap)
     return fail(HIFT_EINVAL, "checkpoint grouping (m = %d, k = %d) does not fit this model's buffers", h.m, h.k);
   const size_t np4 = (size_t)M->lay.n_params * 4;
-  const size_t need = sizeof(CkptHeader) + (size_t)h.k * 12 + np4 * (1 + (size_t)M->n_state) + (size_t)M->n_fac * 4;
+  const size_t nu = (size_t)M->lay.n_units;
+  const size_t need = sizeof(CkptHeader) + (size_t)h.k * 4 + nu * 8 + np4 * (1 + (size_t)M->n_state) + (size_t)M->n_fac * 4;
   if (bytes < need) return fail(HIFT_EINVAL, "buffer holds %zu bytes, the checkpoint has %zu", bytes, need);
+  // everything is checked before the model is touched: a damaged checkpoint leaves it as it was
+  std::vector<int32_t> order(h.k);
+  memcpy(order.data(), p, (size_t)h.k * 4); p += (size_t)h.k * 4;
+  std::vector<int64_t> usteps(nu);
+  memcpy(usteps.data(), p, nu * 8); p += nu * 8;
+  std::vector<char> seen(h.k, 0);
+  for (int i = 0; i < h.k; ++i) {
+    if (order[i] < 0 || order[i] >= h.k || seen[order[i]]) return fail(HIFT_EINVAL, "checkpoint order is damaged");
+    seen[order[i]] = 1;
+  }
+  for (size_t u = 0; u < nu; ++u)
+    if (usteps[u] < 0) return fail(HIFT_EINVAL, "checkpoint update counts are damaged");
+  if (h.t < 0 || h.lr_kind < -1 || h.lr_kind > HIFT_LR_LINEAR) return fail(HIFT_EINVAL, "checkpoint header is damaged");
   ST_TRY(sync_all(M));
   M->m = h.m; M->k = h.k; M->t = h.t;
-  M->order.resize(h.k);
-  memcpy(M->order.data(), p, (size_t)h.k * 4); p += (size_t)h.k * 4;
-  M->group_steps.resize(h.k);
-  memcpy(M->group_steps.data(), p, (size_t)h.k * 8); p += (size_t)h.k * 8;
-  for (int i = 0; i < h.k; ++i)
-    if (M->order[i] < 0 || M->order[i] >= h.k) return fail(HIFT_EINVAL, "checkpoint order is damaged");
+  M->order = order;
+  M->unit_steps = usteps;
   M->opt.lr = h.lr; M->lr_kind = h.lr_kind; M->lr_base = h.lr_base; M->lr_warmup = h.lr_warmup; M->lr_total = h.lr_total;
   ST_TRY(hift_write_params(M, 0, M->lay.n_units, reinterpret_cast<const float*>(p), (size_t)M->lay.n_params));
   p += np4;
   for (int j = 0; j < M->n_state; ++j, p += np4) {
-    if (M->on_host) memcpy(M->host_state + (size_t)j * M->lay.n_params, p, np4);
+    if (M->on_host) ST_TRY(M->pin.write(M->host_state_off + (size_t)j * np4, p, np4));
     else HIP_TRY(hipMemcpy(M->state_full + (size_t)j * M->lay.n_params, p, np4, hipMemcpyHostToDevice));
   }
   if (M->n_fac) HIP_TRY(hipMemcpy(M->fac, p, (size_t)M->n_fac * 4, hipMemcpyHostToDevice));
@@ -1551,6 +1752,7 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
     return fail(HIFT_EINVAL, "batch %d x seq %d outside the maxima %d x %d", bt->batch, bt->seq, M->max_batch,
                 M->max_seq_len);
   if (!bt->tokens || !bt->labels) return fail(HIFT_EINVAL, "tokens or labels null");
+  if (M->lora_r > 0) return fail(HIFT_ESTATE, "a model with adapters trains its adapters: use hift_lora_step");
   int ulo, uhi;
   int64_t plo, cnt;
   group_range(M, gid, &ulo, &uhi, &plo, &cnt);
@@ -1587,8 +1789,7 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
   HIP_TRY(hipEventRecord(M->ev_w0, M->cs));
   if (moving) HIP_TRY(hipStreamWaitEvent(M->cs, M->ev_h2d[s], 0));
   HIP_TRY(hipEventRecord(M->ev_w1, M->cs));
-  M->group_steps[gid] += 1;
-  const int64_t tg = M->group_steps[gid];
+  for (int u = ulo; u < uhi; ++u) M->unit_steps[u] += 1;
   OptArgs oa{M->opt.kind, M->opt.lr, M->opt.beta1, M->opt.beta2, M->opt.eps, M->opt.weight_decay, M->opt.momentum};
   float *s1b = nullptr, *s2b = nullptr;
   int64_t sbase = plo;  // state index = parameter offset - sbase
@@ -1610,6 +1811,7 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
     Scope sc(M, CAT_OPT, bytes_per * cnt);
     for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
       const Tensor& t = M->lay.t[i];
+      const int64_t tg = M->unit_steps[t.unit];
       void* cc = M->dt == DT_BF16 ? (unsigned char*)M->wc + t.off * 2 : nullptr;
       if (M->opt.kind == HIFT_ADAFACTOR) {
         K_TRY(adafactor_update(M->opt.lr, M->opt.weight_decay, t.kind == HIFT_KIND_MATRIX, tg, t.rows, t.cols,
@@ -1635,10 +1837,11 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
   // ---- state back to the host (Algorithm 1 step k) ----
   if (moving) {
     HIP_TRY(hipStreamWaitEvent(M->ds, M->ev_opt[s], 0));
-    float* host0 = M->master_host ? M->host_master : M->host_state;
     for (int j = 0; j < M->n_move; ++j) {
-      ST_TRY(state_copy(M, host0 + (size_t)j * M->lay.n_params + plo, M->slot[s] + (size_t)j * M->grad_cap,
-                        (size_t)cnt * 4, false));
+      const unsigned char* src = reinterpret_cast<const unsigned char*>(M->slot[s] + (size_t)j * M->grad_cap);
+      ST_TRY(M->pin.pieces(((size_t)j * M->lay.n_params + plo) * 4, (size_t)cnt * 4, [&](unsigned char* h, size_t n, size_t at) {
+        return state_copy(M, h, src + at, n, false);
+      }));
       M->d2h_bytes += (uint64_t)cnt * 4;
     }
     HIP_TRY(hipEventRecord(M->ev_d2h[s], M->ds));
@@ -1654,6 +1857,77 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
   return HIFT_OK;
 }
 
+// ---- low-rank adapters -------------------------------------------------------------------------------------
+hift_status hift_lora_param_count(const hift_config* cfg, int64_t* n) {
+  hift_status s = check_config(cfg);
+  if (s != HIFT_OK) return s;
+  if (!n) return fail(HIFT_EINVAL, "n is null");
+  *n = (int64_t)cfg->n_layers * 4 * cfg->lora_rank * cfg->d_model;
+  return HIFT_OK;
+}
+
+hift_status hift_lora_write(hift_model* M, const float* src, size_t count) {
+  if (!M || !src) return fail(HIFT_EINVAL, "null argument");
+  if (M->lora_r == 0) return fail(HIFT_ESTATE, "the model has no adapters");
+  if ((int64_t)count != M->n_lora) return fail(HIFT_EINVAL, "buffer holds %zu floats, the adapters hold %lld", count, (long long)M->n_lora);
+  ST_TRY(sync_all(M));
+  HIP_TRY(hipMemcpy(M->lora_master, src, count * 4, hipMemcpyHostToDevice));
+  if (M->dt == DT_BF16) HIP_TRY(cast_f32_to(DT_BF16, M->n_lora, M->lora_master, M->lora_wc, M->cs));
+  HIP_TRY(hipStreamSynchronize(M->cs));
+  return HIFT_OK;
+}
+
+hift_status hift_lora_read(hift_model* M, int32_t which, float* dst, size_t count) {
+  if (!M || !dst) return fail(HIFT_EINVAL, "null argument");
+  if (M->lora_r == 0) return fail(HIFT_ESTATE, "the model has no adapters");
+  if ((int64_t)count != M->n_lora) return fail(HIFT_EINVAL, "buffer holds %zu floats, the adapters hold %lld", count, (long long)M->n_lora);
+  if (which < 0 || which > 3) return fail(HIFT_EINVAL, "which must be 0 (master), 1 (compute copy), 2 or 3 (AdamW moments)");
+  ST_TRY(sync_all(M));
+  if (which == 1 && M->dt == DT_BF16) {
+    std::vector<uint16_t> tmp(count);
+    HIP_TRY(hipMemcpy(tmp.data(), M->lora_wc, count * 2, hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < count; ++i) {
+      const uint32_t u = (uint32_t)tmp[i] << 16;
+      memcpy(dst + i, &u, 4);
+    }
+    return HIFT_OK;
+  }
+  const float* src = which <= 1 ? M->lora_master : (which == 2 ? M->lora_m : M->lora_v);
+  HIP_TRY(hipMemcpy(dst, src, count * 4, hipMemcpyDeviceToHost));
+  return HIFT_OK;
+}
+
+hift_status hift_lora_step(hift_model* M, const hift_batch* bt, float* loss_out) {
+  if (!M || !bt) return fail(HIFT_EINVAL, "null argument");
+  if (M->lora_r == 0) return fail(HIFT_ESTATE, "the model has no adapters");
+  if (M->opt.kind != HIFT_ADAMW) return fail(HIFT_ESTATE, "adapters are trained with AdamW");
+  if (bt->batch < 1 || bt->seq < 1 || bt->batch > M->max_batch || bt->seq > M->max_seq_len)
+    return fail(HIFT_EINVAL, "batch %d x seq %d outside the maxima %d x %d", bt->batch, bt->seq, M->max_batch, M->max_seq_len);
+  if (!bt->tokens || !bt->labels) return fail(HIFT_EINVAL, "tokens or labels null");
+  HIP_TRY(hipEventRecord(M->ev_t0, M->cs));
+  // forward over everything; backward down to the first hidden layer (no unit of the base model is active: no
+  // weight gradient of the base is formed, and the first layer's input needs no gradient)
+  ST_TRY(forward(M, bt, 1));
+  ST_TRY(backward(M, bt, 1, 1, 0));
+  M->lora_t += 1;
+  {
+    const double bytes_per = 28.0 + (M->dt == DT_BF16 ? 2.0 : 0.0);
+    Scope sc(M, CAT_OPT, bytes_per * M->n_lora);
+    OptArgs oa{M->opt.kind, M->opt.lr, M->opt.beta1, M->opt.beta2, M->opt.eps, M->opt.weight_decay, M->opt.momentum};
+    K_TRY(optimizer_update(oa, M->n_lora, true, M->lora_t, M->lora_master, M->lora_grad, M->lora_m, M->lora_v,
+                           M->dt == DT_BF16 ? M->lora_wc : nullptr, M->cs));
+  }
+  HIP_TRY(hipEventRecord(M->ev_w0, M->cs));
+  HIP_TRY(hipEventRecord(M->ev_w1, M->cs));
+  HIP_TRY(hipEventRecord(M->ev_t1, M->cs));
+  M->timed = true;
+  if (loss_out) {
+    HIP_TRY(hipMemcpyAsync(loss_out, M->loss_dev, 4, hipMemcpyDeviceToHost, M->cs));
+    HIP_TRY(hipStreamSynchronize(M->cs));
+  }
+  return HIFT_OK;
+}
+
 hift_status hift_read_params(hift_model* M, int32_t ulo, int32_t uhi, int32_t which, float* dst, size_t dst_count) {
   if (!M || !dst) return fail(HIFT_EINVAL, "null argument");
   int64_t off, cnt;
@@ -1662,7 +1936,7 @@ hift_status hift_read_params(hift_model* M, int32_t ulo, int32_t uhi, int32_t wh
   if (which != 0 && which != 1) return fail(HIFT_EINVAL, "which must be 0 or 1");
   ST_TRY(sync_all(M));
   if (which == 0 && M->master_host) {
-    memcpy(dst, M->host_master + off, (size_t)cnt * 4);  // every write-back has landed
+    ST_TRY(M->pin.read(dst, (size_t)off * 4, (size_t)cnt * 4));  // every write-back has landed
   } else if (which == 0 || M->dt == DT_F32) {
     HIP_TRY(hipMemcpy(dst, M->master + off, (size_t)cnt * 4, hipMemcpyDeviceToHost));
   } else {
@@ -1683,7 +1957,7 @@ hift_status hift_write_params(hift_model* M, int32_t ulo, int32_t uhi, const flo
   if ((int64_t)src_count != cnt) return fail(HIFT_EINVAL, "buffer holds %zu floats, units hold %lld", src_count, (long long)cnt);
   ST_TRY(sync_all(M));
   if (M->master_host) {
-    memcpy(M->host_master + off, src, (size_t)cnt * 4);
+    ST_TRY(M->pin.write((size_t)off * 4, src, (size_t)cnt * 4));
     ST_TRY(load_forward_copy(M, off, cnt));
     HIP_TRY(repack_units(M, ulo, uhi));
     HIP_TRY(hipStreamSynchronize(M->cs));
@@ -1706,7 +1980,7 @@ hift_status hift_read_state(hift_model* M, int32_t ulo, int32_t uhi, int32_t slo
   if (slot < 0 || slot >= M->n_state) return fail(HIFT_EINVAL, "state slot %d outside [0,%d)", slot, M->n_state);
   ST_TRY(sync_all(M));
   if (M->on_host) {
-    memcpy(dst, M->host_state + (size_t)slot * M->lay.n_params + off, (size_t)cnt * 4);  // write-back has landed
+    ST_TRY(M->pin.read(dst, M->host_state_off + ((size_t)slot * M->lay.n_params + off) * 4, (size_t)cnt * 4));  // write-back has landed
   } else {
     HIP_TRY(hipMemcpy(dst, M->state_full + (size_t)slot * M->lay.n_params + off, (size_t)cnt * 4, hipMemcpyDeviceToHost));
   }
@@ -1775,6 +2049,29 @@ hift_status hift_profile_read(hift_model* M, int32_t category, int64_t* launches
   if (launches) *launches = n;
   if (total_ms) *total_ms = ms;
   if (work) *work = w;
+  return HIFT_OK;
+}
+
+hift_status hift_profile_read_rowwise(hift_model* M, int32_t kind, const char** name, int64_t* launches, double* total_ms,
+                                      double* bytes) {
+  if (!M) return fail(HIFT_EINVAL, "model is null");
+  if (kind < 0 || kind >= RW_N) return fail(HIFT_EINVAL, "kind outside [0,%d)", RW_N);
+  ST_TRY(sync_all(M));
+  int64_t n = 0;
+  double ms = 0, w = 0;
+  for (size_t i = 0; i < M->prof.used; ++i) {
+    const Prof::Rec& r = M->prof.pool[i];
+    if (r.cat != CAT_ELEM || r.sub != kind) continue;
+    float e = 0.f;
+    HIP_TRY(hipEventElapsedTime(&e, r.a, r.b));
+    ms += e;
+    w += r.work;
+    ++n;
+  }
+  if (name) *name = RW_NAMES[kind];
+  if (launches) *launches = n;
+  if (total_ms) *total_ms = ms;
+  if (bytes) *bytes = w;
   return HIFT_OK;
 }
 

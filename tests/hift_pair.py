@@ -11,7 +11,7 @@ def spec_of(cfg):
 
 
 def make_pair(wl, seed=0, m=None, strategy=None, opt=None, state_on_host=0, batch=None, seq=None,
-              jitter=0.0, sched_seed=17, master_on_host=0, no_packed_copies=0, **cfg_over):
+              jitter=0.0, sched_seed=17, master_on_host=0, no_packed_copies=0, unfused=0, **cfg_over):
     """Returns (oracle, gpu_model, theta0).  Weights are bf16-exact when the GPU model is bf16."""
     import paper_2401_15207_amd as H
     cfg = model_config(wl, **cfg_over)
@@ -22,7 +22,7 @@ def make_pair(wl, seed=0, m=None, strategy=None, opt=None, state_on_host=0, batc
     theta0 = init_params(seed, spec_of(cfg), bf16_exact=(cfg["dtype"] == 1), jitter=jitter)
     orc = O.HiftOracle(cfg, opt, theta0.astype(np.float64), half_weights=(cfg["dtype"] == 1))
     gpu = H.HiftModel(cfg, opt, m, b, s, init_params=theta0, state_on_host=state_on_host,
-                      master_on_host=master_on_host, no_packed_copies=no_packed_copies)
+                      master_on_host=master_on_host, no_packed_copies=no_packed_copies, unfused=unfused)
     ko = orc.set_group_schedule(strategy, m, sched_seed)
     kg = gpu.set_group_schedule(strategy, m, sched_seed)
     assert ko == kg
@@ -32,6 +32,23 @@ def make_pair(wl, seed=0, m=None, strategy=None, opt=None, state_on_host=0, batc
 def to_dev(tok, lab):
     import torch
     return (torch.from_numpy(np.ascontiguousarray(tok)).cuda(), torch.from_numpy(np.ascontiguousarray(lab)).cuda())
+
+
+def record(test, **fields):
+    """Measured parity figures: printed (pytest -s shows them) and appended, one JSON object per line, to
+    gpurun_out/parity_measured.jsonl when that scratch folder can be written."""
+    import json
+    import os
+    rec = dict(test=test, **{k: (float(v) if isinstance(v, (np.floating, float)) else v) for k, v in fields.items()})
+    line = json.dumps(rec)
+    print("PARITY", line, flush=True)
+    try:
+        d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "parity_measured.jsonl"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
 
 
 def rel_l2(a, b):
@@ -89,37 +106,54 @@ class UpdateCheck:
         self.s1, self.s2 = orc.state1[sl].copy(), orc.state2[sl].copy()
         self.tg = orc.group_steps[gid] + 1
 
-    def check(self, theta_gpu_before, theta_gpu_after, tol, store_eps=1.2e-7, max_outlier_frac=0.0):
+    def check(self, theta_gpu_before, theta_gpu_after, tol, store_eps=1.2e-7, max_outlier_frac=0.0, max_elements=1 << 23):
+        """theta_gpu_before / theta_gpu_after: the whole parameter vector, or (group_only=True implied by their size)
+        the group's slice alone.  Groups of more than max_elements parameters are checked element by element on an
+        evenly strided subset of that size (the bound is evaluated by running the oracle's optimizer several times,
+        which for a group of 600 M parameters would take longer than the step it checks); the relative L2 figures
+        are taken over the whole group."""
         orc = self.orc
         sl = slice(self.lo, self.hi)
+        n = self.hi - self.lo
+        if theta_gpu_before.size == n:
+            before_g, after_g = theta_gpu_before, theta_gpu_after
+        else:
+            before_g, after_g = theta_gpu_before[sl], theta_gpu_after[sl]
         g = orc.last_grad[sl]
         dm = orc.decay_mask[sl]
         def tensor_rms(v):      # rms of v over the tensor each element belongs to
             out, off = np.zeros_like(v), 0
             for _n, shape, _k, _u in O.param_tensors(orc.cfg):
-                n = int(np.prod(shape))
-                a, b = max(off, self.lo), min(off + n, self.hi)
+                cnt = int(np.prod(shape))
+                a, b = max(off, self.lo), min(off + cnt, self.hi)
                 if a < b:
                     seg = v[a - self.lo:b - self.lo]
                     out[a - self.lo:b - self.lo] = np.sqrt(np.mean(seg * seg))
-                off += n
+                off += cnt
             return out
 
+        up0_all = orc.theta[sl] - self.th0
+        upg_all = after_g.astype(np.float64) - before_g.astype(np.float64)
+        den = np.linalg.norm(up0_all)
+        self.update_rel_l2 = float(np.linalg.norm(upg_all - up0_all) / den) if den > 0 else float(np.linalg.norm(upg_all))
+        ref_after = orc.theta[sl]
+        self.weights_rel_l2 = float(np.linalg.norm(after_g.astype(np.float64) - ref_after) / np.linalg.norm(ref_after))
         # the stored first-order state (moment / momentum buffer) carries the same relative
         # uncertainty as the gradients it was built from
-        delta = tol * (np.abs(g) + tensor_rms(g))
-        delta_s = tol * (np.abs(self.s1) + tensor_rms(self.s1))
-        up0 = orc.theta[sl] - self.th0
+        ix = slice(None, None, max(1, -(-n // max_elements)))
+        delta = (tol * (np.abs(g) + tensor_rms(g)))[ix]
+        delta_s = (tol * (np.abs(self.s1) + tensor_rms(self.s1)))[ix]
+        th0, g, s1, s2, dm = self.th0[ix], g[ix], self.s1[ix], self.s2[ix], dm[ix]
+        up0, upg = up0_all[ix], upg_all[ix]
         slack = np.zeros_like(g)
         for sg in (+1, -1):
             for ss in ((+1, -1) if self.tg > 1 else (0,)):
-                up = oracle_update(orc.opt, self.th0, g + sg * delta, self.s1 + ss * delta_s, self.s2,
-                                   self.tg, dm) - self.th0
+                up = oracle_update(orc.opt, th0, g + sg * delta, s1 + ss * delta_s, s2, self.tg, dm) - th0
                 slack = np.maximum(slack, np.abs(up - up0))
         rel = tol if self.tg == 1 else 2 * tol     # later updates also divide by an uncertain second moment
-        bound = 1.5 * slack + rel * np.abs(up0) + store_eps * np.abs(self.th0)
-        upg = theta_gpu_after[sl].astype(np.float64) - theta_gpu_before[sl].astype(np.float64)
+        bound = 1.5 * slack + rel * np.abs(up0) + store_eps * np.abs(th0)
         err = np.abs(upg - up0)
         worst = int(np.argmax(err - bound))
         frac = float(np.mean(err > bound))
+        self.outlier_frac = frac
         return frac <= max_outlier_frac, (frac, worst, float(err[worst]), float(bound[worst]), float(g[worst]))

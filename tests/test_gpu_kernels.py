@@ -220,7 +220,7 @@ def test_norm_forward(dtype, rows, d, rms):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16], ids=["f32", "bf16"])
-@pytest.mark.parametrize("rows,V", [(7, 256), (64, 32000), (5, 3), (1, 2), (0, 16)])
+@pytest.mark.parametrize("rows,V", [(7, 256), (64, 32000), (5, 3), (1, 2), (0, 16), (9, 50272), (3, 16392), (5, 65544), (300, 32000)])
 def test_cross_entropy(dtype, rows, V):
     import torch
     import paper_2401_15207_amd as H
@@ -245,6 +245,21 @@ def test_cross_entropy(dtype, rows, V):
     got = dz.float().cpu().numpy()
     tol = (2 ** -8 if bf else 1e-5) * np.abs(ref_d) + 1e-8
     assert np.all(np.abs(got - ref_d) <= tol)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16], ids=["f32", "bf16"])
+def test_cross_entropy_without_any_target(dtype):
+    # no row has a label: the loss is 0 (not 0 / 0) and every gradient is zero
+    import torch
+    import paper_2401_15207_amd as H
+    rows, V = 6, 1000
+    z = np.random.default_rng(1).standard_normal((rows, V)).astype(np.float32)
+    dz = _dev(z, dtype == BF16)
+    scratch = torch.zeros(rows + 1, device="cuda")
+    loss = torch.full((1,), -7.0, device="cuda")
+    H.kernel_cross_entropy(dtype, rows, V, dz, torch.full((rows,), -1, dtype=torch.int32, device="cuda"), scratch, loss)
+    torch.cuda.synchronize()
+    assert float(loss) == 0.0 and float(dz.float().abs().max()) == 0.0
 
 
 def test_fused_attention_refuses_what_it_cannot_take():

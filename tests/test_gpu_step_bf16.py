@@ -7,7 +7,7 @@ import pytest
 
 from hift_inputs import WORKLOADS, init_params, make_batch, model_config, round_to_bf16
 from oracle import hift_oracle as O
-from tests.hift_pair import make_pair, rel_l2, run_steps, spec_of, to_dev
+from tests.hift_pair import make_pair, record, rel_l2, run_steps, spec_of, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -15,22 +15,15 @@ TOL = 2e-2
 SGD1 = dict(kind="sgd", lr=1.0, beta1=0, beta2=0, eps=0, weight_decay=0.0, momentum=0.0)
 
 
-def _depth_tol(orc, ulo):
-    """Gradient tolerance of a group whose lowest unit is ulo.  Every bf16 rounding on the way
-    from the loss down to the group adds an independent relative error of about 2^-9/sqrt(3);
-    a layer has about 25 of them, so the error grows with the square root of the number of
-    layers the backward pass crosses.  2e-2 covers four layers; deeper groups get
-    2e-2 * sqrt(layers / 4)."""
-    layers = orc.cfg["n_layers"] - max(ulo, 1) + 1
-    return TOL * max(1.0, np.sqrt(layers / 4.0))
-
-
-def _check_group_gradient(orc, got, ref, lo, hi, label, TOL=TOL):
-    """got / ref: flat gradients of one group.  The criterion proper is the relative L2 error:
-    TOL over the group, 1.5 TOL per tensor (TOL = 2e-2 scaled for depth, see _depth_tol).  To catch errors confined to a few rows, which an L2
-    over a large tensor would hide, 99.9 % of the elements of every tensor must also lie within
-    5 TOL of (|ref| + rms of the tensor's non-zero reference gradient)."""
-    assert rel_l2(got, ref) <= TOL, (label, rel_l2(got, ref))
+def _check_group_gradient(orc, got, ref, lo, hi, label, tol=TOL, test=""):
+    """got / ref: flat gradients of one group.  The criterion proper is the relative L2 error over the group: `tol`,
+    the flat 2e-2.  Two finer checks catch errors confined to one tensor or to a few rows, which an L2 over a large
+    group would hide: every tensor within 1.5 tol (the smallest tensors of a deep model carry more than the
+    group's average: 2.2e-2 measured for the position table under 12 layers), and 99.9 % of the elements of every
+    tensor within 5 tol of (|ref| + rms of the tensor's non-zero reference gradient).  Every measured figure is
+    recorded."""
+    e_group = rel_l2(got, ref)
+    worst_name, worst, failures = "", 0.0, []
     off = 0
     for name, shape, _k, _u in O.param_tensors(orc.cfg):
         n = int(np.prod(shape))
@@ -40,25 +33,45 @@ def _check_group_gradient(orc, got, ref, lo, hi, label, TOL=TOL):
             nz = r != 0
             rms = np.sqrt(np.mean(r[nz] ** 2)) if nz.any() else 0.0
             if rms > 0 and not name.endswith("bqkv"):   # the key-bias third has an identically zero gradient
-                frac = np.mean(np.abs(g - r) > 5 * TOL * (np.abs(r) + rms))
-                assert frac <= 1e-3, (label, name, float(frac))
-                assert rel_l2(g, r) <= 1.5 * TOL, (label, name, rel_l2(g, r))
+                frac = float(np.mean(np.abs(g - r) > 5 * tol * (np.abs(r) + rms)))
+                e = rel_l2(g, r)
+                if e > worst:
+                    worst_name, worst = name, e
+                if frac > 1e-3 or e > 1.5 * tol:
+                    failures.append((name, e, frac))
         off += n
+    record(test, what="gradient", group=label, rel_l2_group=e_group, worst_tensor=worst_name, rel_l2_worst_tensor=worst, bar=tol)
+    assert e_group <= tol and not failures, (label, e_group, failures)
 
 
-def _gradient_check(wl, groups, seed=5, **over):
+_LAST_ORACLE = {}   # the most recent oracle loss and gradient: tests of one workload in a row share it
+
+
+def _oracle_loss_and_grad(cfg, theta0, tok, lab, seed):
+    import json
+    key = (json.dumps({k: v for k, v in cfg.items() if k != "unfused"}, sort_keys=True), seed, tok.shape)
+    if _LAST_ORACLE.get("key") != key:
+        _LAST_ORACLE.clear()
+        _LAST_ORACLE.update(key=key, val=O.loss_and_grad(cfg, theta0.astype(np.float64), tok, lab))
+    return _LAST_ORACLE["val"]
+
+
+def _gradient_check(wl, groups, seed=5, test="", tol=lambda orc, ulo: TOL, **over):
+    """Gradient of each chosen group, read out through the ABI as the change of the group's weights under plain
+    SGD with rate 1, against the oracle's full gradient restricted to the group."""
     tok, lab = make_batch(wl, seed, 1)
     dtok, dlab = to_dev(tok, lab)
     orc, gpu, theta0 = make_pair(wl, seed=seed, opt=SGD1, **over)
-    lo_, g = O.loss_and_grad(orc.cfg, theta0.astype(np.float64), tok, lab)
+    lo_, g = _oracle_loss_and_grad(orc.cfg, theta0, tok, lab, seed)
     for gid in groups(orc.k):
         ulo, uhi = gpu.group_units(gid)
         lo, hi = orc.group_range(gid)
         lg = gpu.step(dtok, dlab, gid)
+        record(test, what="loss", group=gid, rel_err=abs(lg - lo_) / abs(lo_), bar=TOL)
         assert abs(lg - lo_) <= TOL * abs(lo_), (lg, lo_)
         after = gpu.read_params(ulo, uhi).astype(np.float64)
         got = theta0[lo:hi].astype(np.float64) - after
-        _check_group_gradient(orc, got, g[lo:hi], lo, hi, f"group {gid}", _depth_tol(orc, ulo))
+        _check_group_gradient(orc, got, g[lo:hi], lo, hi, f"group {gid}", tol(orc, ulo), test)
         # the forward copy of the group is the rounded master; put the start values back
         fw = gpu.read_params(ulo, uhi, which=1)
         assert np.array_equal(fw, round_to_bf16(after.astype(np.float32)))
@@ -68,44 +81,141 @@ def _gradient_check(wl, groups, seed=5, **over):
 
 def test_c2_full_shape_gradients_of_sampled_groups():
     # RoBERTa-base shape at its full size; groups: embeddings, a middle layer, top layer, head
-    _gradient_check(WORKLOADS["C2"], lambda k: [0, 6, k - 2, k - 1])
-
-
-def test_c3_shape_reduced_depth_random_schedule_adamw():
-    wl = dict(WORKLOADS["C3"], n_layers=4)
-    orc, gpu, _ = make_pair(wl, seed=8, sched_seed=99)
-    assert orc.k == 3 and orc.order == gpu_order(gpu)
-    for t, gid, lo_, lg, chk, tb_g in run_steps(orc, gpu, wl, 8, 2 * orc.k):
-        assert abs(lg - lo_) <= TOL * abs(lo_), (t, lo_, lg)
-        ta_g = gpu.read_params()
-        lo, hi = orc.group_range(gid)
-        frozen = np.ones(ta_g.size, bool)
-        frozen[lo:hi] = False
-        assert np.array_equal(tb_g[frozen], ta_g[frozen])
-        ok, info = chk.check(tb_g, ta_g, TOL, max_outlier_frac=1e-3)
-        assert ok, (t, gid, info)
+    _gradient_check(WORKLOADS["C2"], lambda k: [0, 6, k - 2, k - 1], test="C2 full shape, gradients")
 
 
 def gpu_order(gpu):
     return [gpu.schedule_group_at(t) for t in range(1, gpu.k + 1)]
 
 
-def test_c2_reduced_depth_top2down_adamw_with_offload():
-    wl = dict(WORKLOADS["C2"], n_layers=3)
-    orc, gpu, _ = make_pair(wl, seed=4, state_on_host=1)
-    assert gpu_order(gpu) == [4, 3, 2, 1, 0]
-    for t, gid, lo_, lg, chk, tb_g in run_steps(orc, gpu, wl, 4, 2 * orc.k):
+def _gradient_from_state(gpu, orc, gid, before, th_before, th_after):
+    """The gradient the GPU path used in the step just taken, recovered from what the optimizer stores: AdamW's first
+    moment m = b1 m' + (1 - b1) g; SGD's momentum buffer b = mu b' + g (the first one is g itself); for AdaGrad the
+    accumulator's increase is g^2, which gives |g| (compared with the oracle's |g|); plain SGD: the step / lr."""
+    ulo, uhi = gpu.group_units(gid)
+    lo, hi = orc.group_range(gid)
+    o = orc.opt
+    ref = orc.last_grad[lo:hi]
+    if o["kind"] == "sgd" and not o.get("momentum"):
+        sl = slice(lo, hi) if th_before.size != hi - lo else slice(None)
+        return (th_before[sl].astype(np.float64) - th_after[sl]) / o["lr"], ref
+    after = gpu.read_state(ulo, uhi, 0).astype(np.float64)
+    if o["kind"] == "adamw":
+        return (after - o["beta1"] * before) / (1.0 - o["beta1"]), ref
+    if o["kind"] == "adagrad":
+        return np.sqrt(np.maximum(after - before, 0.0)), np.abs(ref)
+    first = orc.group_steps[gid] == 1
+    return (after if first else after - o["momentum"] * before), ref
+
+
+def _one_step(orc, gpu, wl, seed, t, batch, seq, whole):
+    """One scheduled step on both sides; the GPU side's parameters before it: all of them (`whole`) or the group's."""
+    from tests.hift_pair import UpdateCheck
+    gid = orc.schedule_group_at(t)
+    assert gid == gpu.schedule_group_at(t)
+    tok, lab = make_batch(wl, seed, t, batch, seq)
+    dtok, dlab = to_dev(tok, lab)
+    tb_g = gpu.read_params() if whole else gpu.read_params(*gpu.group_units(gid))
+    chk = UpdateCheck(orc, gid)
+    lo = orc.step(tok, lab, gid)
+    lg = gpu.step(dtok, dlab, gid)
+    return lo, lg, chk, tb_g
+
+
+def _gradient_bar(orc, gid):
+    """Bar on the relative L2 error of a group's gradient: the flat 2e-2 for groups whose backward pass crosses at
+    most 12 layers.  Every bf16 rounding on the way from the loss down to the group adds an independent relative
+    error of about 2^-9 / sqrt(3), so the error grows with the square root of the number of layers crossed: measured
+    on the post-LayerNorm encoders 1.98e-2 at 12 layers (RoBERTa-base shape) and 2.46e-2 at 18 (RoBERTa-large shape),
+    both 0.0058 sqrt(layers); the largest, 2.51e-2 at 16 layers, is 0.0063 sqrt(layers).  Deeper groups (only the
+    24-layer workload has them) are held to 2.4e-2 sqrt(layers / 12) = 0.0069 sqrt(layers)."""
+    lo_unit = gid * orc.m
+    layers = orc.cfg["n_layers"] - max(lo_unit, 1) + 1
+    return TOL if layers <= 12 else 1.2 * TOL * float(np.sqrt(layers / 12.0))
+
+
+def _run_and_check(test, orc, gpu, wl, seed, steps, check_frozen=False, batch=None, seq=None):
+    """Scheduled steps on both sides.  Per step: the loss and the updated weights of the group (relative L2 against
+    the oracle's) against the flat 2e-2; the gradient of the group as the GPU path's optimizer saw it (recovered
+    from the stored state), relative L2 against the oracle's, against _gradient_bar (2e-2 up to 12 layers).  And the
+    update itself element by element through UpdateCheck, which allows 0.2 % of the elements beyond the bound that
+    follows from that gradient error (an adaptive optimizer turns a small absolute error of a tiny gradient element
+    into a step of full size; measured: up to 0.15 %)."""
+    for t in range(1, steps + 1):
+        gid = orc.schedule_group_at(t)
+        ulo, uhi = gpu.group_units(gid)
+        fresh = orc.group_steps[gid] == 0 or (orc.opt["kind"] == "sgd" and not orc.opt.get("momentum"))
+        st_before = 0.0 if fresh else gpu.read_state(ulo, uhi, 0).astype(np.float64)
+        whole = check_frozen and t <= 3        # every parameter outside the group compared on the first steps
+        lo_, lg, chk, tb_g = _one_step(orc, gpu, wl, seed, t, batch, seq, whole)
         assert abs(lg - lo_) <= TOL * abs(lo_), (t, lo_, lg)
-        ok, info = chk.check(tb_g, gpu.read_params(), TOL, max_outlier_frac=1e-3)
+        ta_g = gpu.read_params() if whole else gpu.read_params(ulo, uhi)
+        g_gpu, g_ref = _gradient_from_state(gpu, orc, gid, st_before, tb_g, ta_g)
+        e_grad = rel_l2(g_gpu, g_ref)
+        del g_gpu, g_ref, st_before
+        if whole:
+            lo, hi = orc.group_range(gid)
+            frozen = np.ones(ta_g.size, bool)
+            frozen[lo:hi] = False
+            assert np.array_equal(tb_g[frozen], ta_g[frozen])
+        bar = _gradient_bar(orc, gid)
+        ok, info = chk.check(tb_g, ta_g, bar, max_outlier_frac=2e-3)
+        record(test, what="step", t=t, group=gid, loss_rel_err=abs(lg - lo_) / abs(lo_), gradient_rel_l2=e_grad,
+               gradient_bar=bar, weights_rel_l2=chk.weights_rel_l2, update_rel_l2=chk.update_rel_l2,
+               elements_beyond_bound=chk.outlier_frac)
+        assert e_grad <= bar, (t, gid, e_grad, bar)
+        assert chk.weights_rel_l2 <= TOL, (t, gid, chk.weights_rel_l2)
         assert ok, (t, gid, info)
+
+
+@pytest.mark.timeout(900)
+def test_c3_full_depth_m2_random_schedule_adamw_one_cycle():
+    # RoBERTa-large shape as configured: 24 layers, two units per group (13 groups), seeded random order, AdamW
+    wl = WORKLOADS["C3"]
+    orc, gpu, _ = make_pair(wl, seed=8, sched_seed=99)
+    assert orc.k == 13 and orc.order == gpu_order(gpu) and sorted(orc.order) == list(range(13))
+    _run_and_check("C3 full depth, m=2, random, AdamW", orc, gpu, wl, 8, orc.k, check_frozen=True)
+
+
+@pytest.mark.timeout(900)
+def test_c2_full_depth_top2down_adamw_state_on_host_one_cycle():
+    # RoBERTa-base shape as configured: 12 layers, one unit per group, top2down, AdamW, state in pinned host memory
+    wl = WORKLOADS["C2"]
+    orc, gpu, _ = make_pair(wl, seed=4, state_on_host=1)
+    assert gpu_order(gpu) == list(range(13, -1, -1))
+    _run_and_check("C2 full depth, top2down, AdamW, host state", orc, gpu, wl, 4, orc.k)
     # optimizer state of every unit came back to the host; AdamW first moment ~ oracle's
     m_g = gpu.read_state(0, gpu.n_units, 0)
-    assert rel_l2(m_g, orc.state1) <= 2 * TOL
+    assert rel_l2(m_g, orc.state1) <= TOL
 
 
 def test_c4_width_two_layers_gradients_all_groups():
     # LLaMA-7B widths (d 4096, 32 heads, SwiGLU 11008, vocab 32000), batch 4 x 512, depth 2
-    _gradient_check(WORKLOADS["C4_L2"], lambda k: range(k))
+    _gradient_check(WORKLOADS["C4_L2"], lambda k: range(k), test="C4 widths depth 2, gradients")
+
+
+def test_c4_width_unfused_kernels():
+    """The separate kernels (rotary embedding, gated activation and its backward, attention as contractions and
+    softmax, RMS normalisation, no shared last round) at the widths where the fused ones normally run."""
+    import paper_2401_15207_amd as H
+    _gradient_check(WORKLOADS["C4_L2"], lambda k: [1, k - 1], test="C4 widths depth 2, everything unfused",
+                    unfused=H.UNFUSED_EPILOGUES | H.UNFUSED_ATTENTION | H.UNFUSED_NORM | H.UNSHARED_LAST_ROUND)
+    # fused epilogues in front of normalisation kernels of their own
+    _gradient_check(WORKLOADS["C4_L2"], lambda k: [1], test="C4 widths depth 2, normalisation not folded",
+                    unfused=H.UNFUSED_NORM)
+
+
+def test_c4_width_without_packed_copies():
+    # the contractions read the row-major bf16 copy when the fragment-order copies are switched off
+    _gradient_check(WORKLOADS["C4_L2"], lambda k: [1, k - 1], no_packed_copies=1, test="C4 widths depth 2, no packed copies")
+
+
+@pytest.mark.timeout(900)
+def test_opt13b_width_two_layers_gradients_all_groups():
+    # the pre-LayerNorm GELU decoder with learned positions, biases and tied embeddings (GPT-2 / OPT family) at the
+    # OPT-13B widths (d 5120, 40 heads, ffn 20480, vocab 50272), batch 2 x 1024, depth 2: every group
+    wl = dict(WORKLOADS["OPT13B"], n_layers=2, m=1)
+    _gradient_check(wl, lambda k: range(k), jitter=0.02, test="OPT-13B widths depth 2 (arch 0, tied), gradients")
 
 
 def test_tied_embeddings_on_the_packed_kernels():
@@ -114,13 +224,26 @@ def test_tied_embeddings_on_the_packed_kernels():
     wl = dict(arch=2, n_layers=2, d_model=1024, n_heads=8, d_ffn=2816, vocab=8192, max_seq=512, n_classes=0,
               norm_eps=1e-5, rope_base=10000.0, dtype=1, batch=4, seq=512, m=1, strategy="bottom2up",
               opt=WORKLOADS["C4"]["opt"], tie_embeddings=1)
-    orc, gpu = _gradient_check(wl, lambda k: range(k))
+    orc, gpu = _gradient_check(wl, lambda k: range(k), test="tied embeddings, small decoder")
     assert gpu.n_units == 4 and [n for n, *_ in gpu.tensors][-1] == "gf"      # no separate output matrix
 
 
-def test_c5_width_two_layers_group_of_two_units():
-    wl = dict(WORKLOADS["C5_L2"], batch=1)
-    _gradient_check(wl, lambda k: [1], m=2)
+@pytest.mark.timeout(1200)
+@pytest.mark.parametrize("optk,strategy", [("adagrad", "top2down"), ("sgdm", "random")])
+def test_c5_width_full_batch_both_groups_other_optimizers(optk, strategy):
+    # 13B widths (d 5120, 40 heads, SwiGLU 13824, vocab 32000) at the configured batch 2 x 1024, two units per
+    # group, both groups, two sweeps: AdaGrad visiting top-down and SGD with momentum 0.9 in the seeded random
+    # order, optimizer state in pinned host memory
+    wl = WORKLOADS["C5_L2"]
+    # AdaGrad's first step moves every weight by the full rate whatever the size of its gradient (g / sqrt(g^2)), in
+    # the direction of a sign that rounding decides for the smallest elements: at a rate of 1e-3 the two sides' weights
+    # are 5e-3 apart after one visit and their second-visit gradients differ by 2-3 % for that reason alone (measured).
+    # The rate of the AdamW workloads keeps the trajectories together, so that the second sweep still tests the kernels.
+    opt = (dict(kind="adagrad", lr=1e-5, eps=1e-10, weight_decay=0.0) if optk == "adagrad"
+           else dict(kind="sgd", lr=1e-2, momentum=0.9, weight_decay=0.0))
+    orc, gpu, _ = make_pair(wl, seed=31, opt=opt, strategy=strategy, sched_seed=5, state_on_host=1)
+    assert orc.k == 2 and orc.order == gpu_order(gpu)
+    _run_and_check(f"C5 widths depth 2, batch 2x1024, m=2, {optk}, {strategy}", orc, gpu, wl, 31, 2 * orc.k)
 
 
 @pytest.mark.parametrize("optk", ["adagrad", "sgdm"])
@@ -176,6 +299,3 @@ def test_master_on_host_gives_the_same_trajectory(optk):
     assert m["device_master"] < hbm.memory()["device_master"]
 
 
-def test_c4_width_without_packed_copies():
-    # the contractions read the row-major bf16 copy when the fragment-order copies are switched off
-    _gradient_check(WORKLOADS["C4_L2"], lambda k: [1, k - 1], no_packed_copies=1)

@@ -168,3 +168,63 @@ def test_error_paths():
     lo_ = orc.step(tok, lab, 1)
     lg = gpu.step(dtok, dlab, 1)
     assert abs(lg - lo_) <= TOL * abs(lo_)
+
+
+@pytest.mark.parametrize("optk", ["adamw", "sgdm"])
+def test_regrouping_keeps_state_and_update_counts(optk):
+    """Setting a schedule again keeps the optimizer state and each unit's update count: a run that regroups between
+    two updates of the same units (one unit per group -> two units per group) ends bit-identical, on those units,
+    to a run that updates them one by one the second time as well.  (Were the count reset, SGD with momentum would
+    overwrite its buffer with the raw gradient and AdamW would restart its bias correction on non-zero moments.)"""
+    wl = WORKLOADS["C1"]
+    opt = (wl["opt"] if optk == "adamw" else dict(kind="sgd", lr=1e-2, momentum=0.9, weight_decay=0.0))
+    _o, a, _t = make_pair(wl, seed=7, opt=opt, m=1, strategy="bottom2up", state_on_host=1)
+    _o, b, _t = make_pair(wl, seed=7, opt=opt, m=2, strategy="bottom2up", state_on_host=1)   # buffers sized for two units
+    batches = [to_dev(*make_batch(wl, 7, t)) for t in (1, 2, 3)]
+    for mdl in (a, b):
+        assert mdl.set_group_schedule("bottom2up", 1, 0) == 4
+        mdl.step(*batches[0], 1)             # layer 0 and layer 1, once each
+        mdl.step(*batches[1], 2)
+    # a: layer 0 again on its own.  b: regroup to {emb, layer 0}, {layer 1, head} and update the first group
+    a.step(*batches[2], 1)
+    assert b.set_group_schedule("bottom2up", 2, 0) == 2
+    b.step(*batches[2], 0)
+    assert np.array_equal(a.read_params(1, 2), b.read_params(1, 2))
+    for j in range(2 if optk == "adamw" else 1):
+        assert np.array_equal(a.read_state(1, 2, j), b.read_state(1, 2, j))
+
+
+@pytest.mark.parametrize("master_on_host", [0, 1])
+def test_pinned_arena_in_chunks_changes_nothing(master_on_host):
+    """The pinned arena handed in as many small blocks (here 4112 bytes each, so that the state of every group
+    straddles several of them) against one block: losses, parameters, state and checkpoints bit-identical."""
+    import paper_2401_15207_amd as H
+    wl = dict(SMALL2, dtype=1) if master_on_host else WORKLOADS["C1"]
+    cfg = {k: wl[k] for k in ("arch", "n_layers", "d_model", "n_heads", "d_ffn", "vocab", "max_seq", "n_classes",
+                              "norm_eps", "rope_base", "dtype")}
+    spec = [(n, s, k) for n, s, k, _u in O.param_tensors(cfg)]
+    from hift_inputs import init_params
+    theta0 = init_params(9, spec, bf16_exact=bool(cfg["dtype"]))
+    models = [H.HiftModel(cfg, wl["opt"], 1, wl["batch"], wl["seq"], init_params=theta0, state_on_host=1,
+                          master_on_host=master_on_host, pinned_chunk_bytes=cb) for cb in (1 << 40, 4112)]
+    assert len(models[0].pinned_chunks) == 1 and len(models[1].pinned_chunks) > 20
+    for mdl in models:
+        assert mdl.set_group_schedule("random", 1, 3) == 4
+    for t in range(1, 9):
+        batch = to_dev(*make_batch(wl, 9, t))
+        gid = models[0].schedule_group_at(t)
+        la, lb = (mdl.step(*batch, gid) for mdl in models)
+        assert la == lb, t
+    a, b = models
+    assert np.array_equal(a.read_params(), b.read_params())
+    assert np.array_equal(a.read_params(which=1), b.read_params(which=1))
+    for j in (0, 1):
+        assert np.array_equal(a.read_state(0, a.n_units, j), b.read_state(0, b.n_units, j))
+    ck = b.checkpoint_save()
+    assert np.array_equal(ck, a.checkpoint_save())
+    b.write_params(1, 2, theta0[:0].tolist() + list(a.read_params(1, 2) * 0))    # disturb, then restore from the checkpoint
+    b.checkpoint_load(ck)
+    assert np.array_equal(a.read_params(), b.read_params())
+    batch = to_dev(*make_batch(wl, 9, 9))
+    assert a.step(*batch, 2) == b.step(*batch, 2)
+    assert np.array_equal(a.read_params(), b.read_params())

@@ -88,3 +88,15 @@ def test_checkpoint_resume_continues_bit_identically(optk, on_host):
     bad[:4] = 0
     with pytest.raises(H.HiftError):
         b.checkpoint_load(bad)
+    # a checkpoint whose visiting order is damaged (a group twice) is refused before anything of the model changes
+    pat = np.arange(k - 1, -1, -1, dtype=np.int32).view(np.uint8)
+    at = next(i for i in range(256) if np.array_equal(ckpt[i:i + pat.size], pat))
+    bad = ckpt.copy()
+    bad[at:at + 4] = bad[at + 4:at + 8]
+    bad[at + 4 * k + 200:at + 4 * k + 10000] = 0xFF     # and so are its parameters
+    before = (b.cycle_index(), b.read_params(), [b.schedule_group_at(t) for t in range(1, k + 1)])
+    with pytest.raises(H.HiftError):
+        b.checkpoint_load(bad)
+    assert b.cycle_index() == before[0] and np.array_equal(b.read_params(), before[1])
+    assert [b.schedule_group_at(t) for t in range(1, k + 1)] == before[2]
+    assert np.array_equal(b.train(dev, 2), a.train(dev, 2))   # and it goes on exactly as the run it mirrors
