@@ -210,6 +210,9 @@ def main():
                     help="units per group (default: the workload's); the number of units gives one group, "
                          "i.e. a full fine-tuning step on the same kernels")
     ap.add_argument("--state-resident", action="store_true", help="keep all optimizer state in HBM")
+    ap.add_argument("--opt", default="", choices=["", "adamw", "adagrad", "sgdm", "sgd"],
+                    help="optimizer (default: the workload's AdamW); the 13B-shaped workload sweeps them")
+    ap.add_argument("--strategy", default="", choices=["", "bottom2up", "top2down", "random"])
     ap.add_argument("--master-on-host", action="store_true",
                     help="park the fp32 master of inactive groups in pinned memory too (small-memory mode)")
     ap.add_argument("--no-packed-copies", action="store_true",
@@ -241,6 +244,14 @@ def main():
     t_setup = time.perf_counter()
     if a.m > 0:
         wl = dict(wl, m=a.m)
+    if a.opt:
+        lr = wl["opt"]["lr"]
+        wl = dict(wl, opt={"adamw": wl["opt"],
+                           "adagrad": dict(kind="adagrad", lr=lr, eps=1e-10, weight_decay=0.0, momentum=0.0),
+                           "sgdm": dict(kind="sgd", lr=lr, momentum=0.9, weight_decay=0.0),
+                           "sgd": dict(kind="sgd", lr=lr, momentum=0.0, weight_decay=0.0)}[a.opt])
+    if a.strategy:
+        wl = dict(wl, strategy=a.strategy)
     model = H.HiftModel(cfg, wl["opt"], wl["m"], B, S, init_params=None, state_on_host=0 if a.state_resident else 1,
                         master_on_host=int(a.master_on_host), no_packed_copies=int(a.no_packed_copies))
     mem = model.memory()
@@ -324,6 +335,8 @@ def main():
     _step_ms, exposed = model.last_step_ms()
 
     tokens = a.steps * B * S
+    opt_name = {"adamw": "AdamW", "adagrad": "AdaGrad"}.get(wl["opt"]["kind"], "SGD with momentum %g" % wl["opt"].get("momentum", 0.0)
+                                                                if wl["opt"].get("momentum") else "SGD")
     gemm_tflops = fl_gemm / (ms_gemm * 1e-3) / 1e12 if ms_gemm > 0 else 0.0
     out = {
         "metric": "trained tokens/sec per HiFT step at 7B shape (1 GPU); MFMA util % of bf16 peak",
@@ -334,12 +347,12 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload}: LLaMA-7B-shaped decoder, 32 layers d=4096 h=32 ffn=11008 vocab=32000, "
-                               f"batch {B} x seq {S}, m={wl['m']} ({k} groups), bottom2up, AdamW, optimizer state "
+                               f"batch {B} x seq {S}, m={wl['m']} ({k} groups), {wl['strategy']}, {opt_name}, optimizer state "
                                + ("resident in HBM" if a.state_resident else "of inactive groups in pinned host memory")
                                if a.workload == "C4" else
                                f"{a.workload}: arch {cfg['arch']}, {cfg['n_layers']} layers d={cfg['d_model']} h={cfg['n_heads']} "
                                f"ffn={cfg['d_ffn']} vocab={cfg['vocab']}" + (", tied embeddings" if cfg.get("tie_embeddings") else "")
-                               + f", batch {B} x seq {S}, m={wl['m']} ({k} groups), {wl['strategy']}, {wl['opt']['kind']}, state "
+                               + f", batch {B} x seq {S}, m={wl['m']} ({k} groups), {wl['strategy']}, {opt_name}, state "
                                + ("resident in HBM" if a.state_resident else "of inactive groups in pinned host memory"),
                    "groups": k, "tokens_per_step": B * S},
         "roofline": {

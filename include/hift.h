@@ -332,7 +332,8 @@ hift_status hift_set_state_copy_engine(hift_model* mdl, int32_t engine, int32_t 
  * hift_profile_read_rowwise splits class 2 by kind of kernel (kind 0 .. n-1; HIFT_EINVAL beyond the last,
  * which is how a caller finds n): embedding lookup, normalisation forward, row sums of squares, rotary
  * embedding, activation forward / backward, softmax forward / backward, cross-entropy, normalisation backward
- * (dX; gain and shift), column sums, embedding gradient, first-token gather / scatter.  name receives a static
+ * (dX; gain and shift), column sums, embedding gradient, first-token gather / scatter, loss bookkeeping (the two
+ * one-workgroup kernels around the cross-entropy: count of targets, mean of the row losses).  name receives a static
  * string; bytes is the algorithmic traffic: every element the kernels had to read once plus every element they
  * had to write once (section "Wallclock Time Efficiency" does not cost these steps; the figure is what an
  * HBM roofline needs). */

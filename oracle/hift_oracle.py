@@ -617,13 +617,13 @@ def adafactor_update(theta, g, state, shape, t, lr, wd, decay, eps1=1e-30, clip=
 # time the paper sets beside HiFT's)
 # ----------------------------------------------------------------------------------------
 def lora_tensors(cfg: dict, rank: int):
-    """Adapter tensors [(name, shape)], in storage order: per hidden layer A_q [r, d], B_q [d, r], A_v [r, d],
+    """Adapter tensors [(name, shape)], in storage order: per hidden layer A_q [r, d], A_v [r, d], B_q [d, r],
     B_v [d, r].  The query and value projections become W + (alpha / r) B A; everything else is frozen."""
     d = cfg["d_model"]
     out = []
     for l in range(cfg["n_layers"]):
         p = f"l{l}."
-        out += [(p + "lora_aq", (rank, d)), (p + "lora_bq", (d, rank)), (p + "lora_av", (rank, d)), (p + "lora_bv", (d, rank))]
+        out += [(p + "lora_aq", (rank, d)), (p + "lora_av", (rank, d)), (p + "lora_bq", (d, rank)), (p + "lora_bv", (d, rank))]
     return out
 
 
@@ -760,7 +760,13 @@ class HiftOracle:
     def step(self, tokens, labels, group_id: int) -> float:
         if self.k is None or not (0 <= group_id < self.k):
             raise ValueError("bad group")
-        at = bf16_round(self.theta) if self.half_weights else self.theta
+        if self.half_weights:
+            # the half-precision model: kept between steps, since only the group updated last has changed
+            if getattr(self, "_half", None) is None:
+                self._half = bf16_round(self.theta)
+            at = self._half
+        else:
+            at = self.theta
         loss, g = loss_and_grad(self.cfg, at, tokens, labels)
         self.last_grad = g
         lo, hi = self.group_range(group_id)
@@ -785,6 +791,8 @@ class HiftOracle:
                 off += c
         else:
             raise ValueError("unknown optimizer")
+        if self.half_weights:
+            self._half[lo:hi] = bf16_round(self.theta[lo:hi])
         self.t += 1
         return loss
 

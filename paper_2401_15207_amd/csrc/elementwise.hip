@@ -1230,10 +1230,15 @@ hipError_t softmax_bwd(int dt, int64_t nbh, int S, float scale, bool causal, con
   LAUNCH_CHECK();
 }
 
-hipError_t cross_entropy(int dt, int64_t rows, int V_, void* logits, const int32_t* labels, float* row_loss,
-                         float* loss_out, hipStream_t st) {
-  if (rows == 0) return fill_zero(loss_out, 4, st);
+hipError_t cross_entropy_count(int64_t rows, const int32_t* labels, float* row_loss, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
   ce_count_k<<<1, BLK, 0, st>>>(rows, labels, row_loss);
+  LAUNCH_CHECK();
+}
+
+hipError_t cross_entropy_rows(int dt, int64_t rows, int V_, void* logits, const int32_t* labels, float* row_loss,
+                              hipStream_t st) {
+  if (rows == 0) return hipSuccess;
 #define OK(v) (V_ % (v) == 0 && aligned16(logits))
   // 16-byte pieces of a row a thread keeps: 16 (rows of up to 32768 bf16 or 16384 fp32 values) or 32
   if (dt == DT_BF16 && OK(8) && V_ <= BLK * 8 * 16) {
@@ -1248,8 +1253,21 @@ hipError_t cross_entropy(int dt, int64_t rows, int V_, void* logits, const int32
     DISPATCH_TV(dt, OK, (ce_row_k<T, V><<<dim3((unsigned)rows), BLK, 0, st>>>(rows, V_, (T*)logits, labels, row_loss)));
   }
 #undef OK
+  LAUNCH_CHECK();
+}
+
+hipError_t cross_entropy_mean(int64_t rows, const float* row_loss, float* loss_out, hipStream_t st) {
+  if (rows == 0) return fill_zero(loss_out, 4, st);
   ce_final_k<<<1, BLK, 0, st>>>(rows, row_loss, loss_out);
   LAUNCH_CHECK();
+}
+
+hipError_t cross_entropy(int dt, int64_t rows, int V_, void* logits, const int32_t* labels, float* row_loss,
+                         float* loss_out, hipStream_t st) {
+  hipError_t e = cross_entropy_count(rows, labels, row_loss, st);
+  if (e == hipSuccess) e = cross_entropy_rows(dt, rows, V_, logits, labels, row_loss, st);
+  if (e == hipSuccess) e = cross_entropy_mean(rows, row_loss, loss_out, st);
+  return e;
 }
 
 hipError_t scale_inplace(int dt, int64_t n, float a, void* x, hipStream_t st) {

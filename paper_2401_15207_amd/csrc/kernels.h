@@ -136,6 +136,12 @@ hipError_t softmax_bwd(int dt, int64_t nbh, int S, float scale, bool causal, con
 // logits [rows, V] -> d loss / d logits in place; loss = mean over labels >= 0
 hipError_t cross_entropy(int dt, int64_t rows, int V, void* logits, const int32_t* labels,
                          float* row_loss, float* loss_out, hipStream_t st);
+// its three launches one by one (row_loss: rows + 1 floats): the number of rows with a target into row_loss[rows];
+// the rows (per-row loss into row_loss[r], gradient over the logits); the mean of the per-row losses
+hipError_t cross_entropy_count(int64_t rows, const int32_t* labels, float* row_loss, hipStream_t st);
+hipError_t cross_entropy_rows(int dt, int64_t rows, int V, void* logits, const int32_t* labels, float* row_loss,
+                              hipStream_t st);
+hipError_t cross_entropy_mean(int64_t rows, const float* row_loss, float* loss_out, hipStream_t st);
 // g_tok[v, :] = (add ? g_tok[v, :] : as zeroed by the caller) + sum over positions t holding token v of dx[t, :],
 // in position order (no atomics: the first position holding a token does its row);  g_pos[s, :] = sum_b dx[b*S+s, :]
 hipError_t embed_bwd(int dt, const int32_t* tokens, int64_t T, int S, int d, int V, const void* dx,

@@ -569,12 +569,12 @@ enum { CAT_GEMM = 0, CAT_ATTN = 1, CAT_ELEM = 2, CAT_OPT = 3, CAT_GEMM_REST = 4,
 // Kinds of row-wise / elementwise kernel inside CAT_ELEM, each timed with its algorithmic bytes: every element the
 // kernel has to read once plus every element it has to write once (gains, statistics and labels are not counted).
 enum { RW_EMBED_FWD = 0, RW_NORM_FWD, RW_ROW_SUMSQ, RW_ROPE, RW_ACT_FWD, RW_ACT_BWD, RW_SOFTMAX_FWD, RW_SOFTMAX_BWD,
-       RW_CROSS_ENTROPY, RW_NORM_BWD_DX, RW_NORM_BWD_PARAMS, RW_COL_SUM, RW_EMBED_BWD, RW_FIRST_ROWS, RW_N };
+       RW_CROSS_ENTROPY, RW_NORM_BWD_DX, RW_NORM_BWD_PARAMS, RW_COL_SUM, RW_EMBED_BWD, RW_FIRST_ROWS, RW_LOSS_MEAN, RW_N };
 const char* const RW_NAMES[RW_N] = {
     "embedding lookup", "normalisation forward", "row sums of squares", "rotary embedding", "activation forward",
     "activation backward", "softmax forward", "softmax backward", "cross-entropy with gradient", "normalisation backward dX",
     "normalisation backward gain/shift", "column sums (bias gradient)", "embedding gradient (clear + scatter)",
-    "first-token gather / scatter"};
+    "first-token gather / scatter", "loss bookkeeping (count of targets, mean of row losses; one workgroup each)"};
 
 struct Scope {
   hift_model* M;
@@ -1075,14 +1075,18 @@ hift_status forward(hift_model* M, const hift_batch* bt, int keep_from) {
       RW(RW_FIRST_ROWS, 2.0 * B * d * es, gather_first(dt, B, S, d, xl, M->xcls, st));
     }
     ST_TRY(linear(M, M->xcls, B, M->T_("wc"), &M->T_("bc"), nullptr, M->logits));
-    RW(RW_CROSS_ENTROPY, 2.0 * (B) * (c.n_classes) * es, cross_entropy(dt, B, c.n_classes, M->logits, bt->labels, M->row_loss, M->loss_dev, st));
+    RW(RW_LOSS_MEAN, 4.0 * (B), cross_entropy_count(B, bt->labels, M->row_loss, st));
+    RW(RW_CROSS_ENTROPY, 2.0 * (B) * (c.n_classes) * es, cross_entropy_rows(dt, B, c.n_classes, M->logits, bt->labels, M->row_loss, st));
+    RW(RW_LOSS_MEAN, 4.0 * (B), cross_entropy_mean(B, M->row_loss, M->loss_dev, st));
   } else {
     {
       if (rms) RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, true, T, d, c.norm_eps, xl, M->W("gf"), nullptr, M->xf, M->st_f, st));
       else RW(RW_NORM_FWD, 2.0 * T * d * es, norm_fwd(dt, false, T, d, c.norm_eps, xl, M->W("lnf_g"), M->W("lnf_b"), M->xf, M->st_f, st));
     }
     ST_TRY(linear(M, M->xf, T, M->T_(c.tie_embeddings ? "tok_emb" : "whead"), nullptr, nullptr, M->logits));
-    RW(RW_CROSS_ENTROPY, 2.0 * (T) * (c.vocab) * es, cross_entropy(dt, T, c.vocab, M->logits, bt->labels, M->row_loss, M->loss_dev, st));
+    RW(RW_LOSS_MEAN, 4.0 * (T), cross_entropy_count(T, bt->labels, M->row_loss, st));
+    RW(RW_CROSS_ENTROPY, 2.0 * (T) * (c.vocab) * es, cross_entropy_rows(dt, T, c.vocab, M->logits, bt->labels, M->row_loss, st));
+    RW(RW_LOSS_MEAN, 4.0 * (T), cross_entropy_mean(T, M->row_loss, M->loss_dev, st));
   }
   return HIFT_OK;
 }

@@ -76,7 +76,7 @@ def test_adapter_step_bf16_at_7b_widths():
     orc, gpu, theta0, lora0 = _pair(wl, 8, 16.0, seed=13, opt=opt, scale=0.02)
     b1 = opt["beta1"]
     cfg = model_config(wl)
-    for t in range(1, 3):
+    for t in range(1, 2):
         tok, lab = make_batch(wl, 13, t)
         m_before = gpu.lora_read(2).astype(np.float64)
         lo = orc.step(tok, lab)

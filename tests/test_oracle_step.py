@@ -199,6 +199,13 @@ def test_half_weights_step_evaluates_at_rounded_master_and_updates_master():
     exp = theta0[lo:hi] * (1 - p["lr"] * p["weight_decay"] * oh.decay_mask[lo:hi]) - p["lr"] * g / (np.abs(g) + p["eps"])
     assert np.allclose(oh.theta[lo:hi], exp, rtol=1e-12, atol=0)
     assert not np.array_equal(oh.theta[lo:hi], O.bf16_round(oh.theta[lo:hi]))   # master keeps full precision
+    # later steps, too, are evaluated at the rounding of the master as it then is (the oracle keeps the rounded model
+    # between steps and refreshes the group it updated: the same thing, written out here from scratch)
+    for t in range(2, 7):
+        gid = oh.schedule_group_at(t)
+        tok, lab = make_batch(WL, 1, t)
+        l_ref, g_ref = O.loss_and_grad(CFG, O.bf16_round(oh.theta), tok, lab)
+        assert oh.step(tok, lab, gid) == l_ref and np.array_equal(oh.last_grad, g_ref), t
 
 
 ADAFACTOR = dict(kind="adafactor", lr=1e-3, weight_decay=0.0)
