@@ -160,8 +160,8 @@ def make_batch(workload: dict, seed: int, step: int, batch: int | None = None,
 def fill_weights_on_device(model, seed: int) -> None:
     """Initial weights for models too large to draw on the host (the 7B and 13B shapes at full depth): N(0, 0.02^2)
     matrices, unit gains, zero biases, drawn with torch's generator on the GPU unit by unit and handed to
-    `model.write_params`.  `model` needs `tensors` (name, shape, kind, unit, offset per tensor, in parameter order)
-    and `write_params(unit_lo, unit_hi, values)`."""
+    `model.write_params_device` (or, through the host, to `model.write_params`).  `model` needs `tensors` (name,
+    shape, kind, unit, offset per tensor, in parameter order) and one of the two writers (unit_lo, unit_hi, values)."""
     import torch
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
@@ -176,6 +176,9 @@ def fill_weights_on_device(model, seed: int) -> None:
                 parts.append(torch.randn(n, generator=g, device="cuda", dtype=torch.float32) * 0.02)
             else:
                 parts.append(torch.full((n,), 1.0 if kind == KIND_GAIN else 0.0, device="cuda"))
-        flat = torch.cat(parts).cpu().numpy()
-        model.write_params(unit, unit + 1, flat)
+        flat = torch.cat(parts)
+        if hasattr(model, "write_params_device"):
+            model.write_params_device(unit, unit + 1, flat)
+        else:
+            model.write_params(unit, unit + 1, flat.cpu().numpy())
         del parts, flat

@@ -295,6 +295,10 @@ hift_status hift_read_params(hift_model* mdl, int32_t unit_lo, int32_t unit_hi, 
                              float* dst_host, size_t dst_count);
 hift_status hift_write_params(hift_model* mdl, int32_t unit_lo, int32_t unit_hi,
                               const float* src_host, size_t src_count);
+/* hift_write_params with the values already in device memory (src_device: device, fp32, caller-owned, complete
+ * before the call): models of tens of GB are initialised without a round trip through the host. */
+hift_status hift_write_params_device(hift_model* mdl, int32_t unit_lo, int32_t unit_hi,
+                                     const float* src_device, size_t src_count);
 /* Adafactor only: the statistics of tensor `tensor_index` (hift_tensor_at order): rows then cols floats
  * for a matrix, rows floats for a vector.  dst: host.  Waits for the streams. */
 hift_status hift_read_factored_state(hift_model* mdl, int32_t tensor_index, float* dst, size_t dst_count);

@@ -89,6 +89,7 @@ _SIGS = {
     "hift_lora_step": [_vp, _P(Batch), _P(C.c_float)],
     "hift_read_params": [_vp, _i32, _i32, _i32, _vp, _sz],
     "hift_write_params": [_vp, _i32, _i32, _vp, _sz],
+    "hift_write_params_device": [_vp, _i32, _i32, _vp, _sz],
     "hift_read_state": [_vp, _i32, _i32, _i32, _vp, _sz],
     "hift_transfer_stats": [_vp, _P(_u64), _P(_u64)],
     "hift_last_step_ms": [_vp, _P(C.c_float), _P(C.c_float)],
@@ -498,6 +499,12 @@ class HiftModel:
     def write_params(self, unit_lo: int, unit_hi: int, values: np.ndarray):
         v = np.ascontiguousarray(values, dtype=np.float32)
         _check(lib.hift_write_params(self.h, unit_lo, unit_hi, v.ctypes.data, v.size))
+
+    def write_params_device(self, unit_lo: int, unit_hi: int, values):
+        """values: contiguous float32 torch tensor on the device, complete on the current stream."""
+        assert values.is_cuda and values.dtype == self.torch.float32 and values.is_contiguous()
+        self.torch.cuda.current_stream().synchronize()
+        _check(lib.hift_write_params_device(self.h, unit_lo, unit_hi, values.data_ptr(), values.numel()))
 
     def read_state(self, unit_lo: int, unit_hi: int, slot: int) -> np.ndarray:
         out = np.empty(self._unit_count(unit_lo, unit_hi), dtype=np.float32)

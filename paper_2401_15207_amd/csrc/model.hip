@@ -1954,26 +1954,43 @@ hift_status hift_read_params(hift_model* M, int32_t ulo, int32_t uhi, int32_t wh
   return HIFT_OK;
 }
 
-hift_status hift_write_params(hift_model* M, int32_t ulo, int32_t uhi, const float* src, size_t src_count) {
+namespace {
+hift_status write_params_from(hift_model* M, int32_t ulo, int32_t uhi, const float* src, size_t src_count, bool src_on_device) {
   if (!M || !src) return fail(HIFT_EINVAL, "null argument");
   int64_t off, cnt;
   ST_TRY(unit_span(M, ulo, uhi, &off, &cnt));
   if ((int64_t)src_count != cnt) return fail(HIFT_EINVAL, "buffer holds %zu floats, units hold %lld", src_count, (long long)cnt);
   ST_TRY(sync_all(M));
   if (M->master_host) {
-    ST_TRY(M->pin.write((size_t)off * 4, src, (size_t)cnt * 4));
+    if (src_on_device) {
+      ST_TRY(M->pin.pieces((size_t)off * 4, (size_t)cnt * 4, [&](unsigned char* h, size_t n, size_t at) {
+        HIP_TRY(hipMemcpy(h, reinterpret_cast<const unsigned char*>(src) + at, n, hipMemcpyDeviceToHost));
+        return HIFT_OK;
+      }));
+    } else {
+      ST_TRY(M->pin.write((size_t)off * 4, src, (size_t)cnt * 4));
+    }
     ST_TRY(load_forward_copy(M, off, cnt));
     HIP_TRY(repack_units(M, ulo, uhi));
     HIP_TRY(hipStreamSynchronize(M->cs));
     return HIFT_OK;
   }
-  HIP_TRY(hipMemcpy(M->master + off, src, (size_t)cnt * 4, hipMemcpyHostToDevice));
+  HIP_TRY(hipMemcpy(M->master + off, src, (size_t)cnt * 4, src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice));
   if (M->dt == DT_BF16) {
     HIP_TRY(cast_f32_to(DT_BF16, cnt, M->master + off, (unsigned char*)M->wc + off * 2, M->cs));
     HIP_TRY(repack_units(M, ulo, uhi));
     HIP_TRY(hipStreamSynchronize(M->cs));
   }
   return HIFT_OK;
+}
+}  // namespace
+
+hift_status hift_write_params(hift_model* M, int32_t ulo, int32_t uhi, const float* src, size_t src_count) {
+  return write_params_from(M, ulo, uhi, src, src_count, false);
+}
+
+hift_status hift_write_params_device(hift_model* M, int32_t ulo, int32_t uhi, const float* src_device, size_t src_count) {
+  return write_params_from(M, ulo, uhi, src_device, src_count, true);
 }
 
 hift_status hift_read_state(hift_model* M, int32_t ulo, int32_t uhi, int32_t slot, float* dst, size_t dst_count) {

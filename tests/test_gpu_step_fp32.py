@@ -228,3 +228,22 @@ def test_pinned_arena_in_chunks_changes_nothing(master_on_host):
     batch = to_dev(*make_batch(wl, 9, 9))
     assert a.step(*batch, 2) == b.step(*batch, 2)
     assert np.array_equal(a.read_params(), b.read_params())
+
+
+@pytest.mark.parametrize("bf16,master_on_host", [(0, 0), (1, 0), (1, 1)])
+def test_parameters_written_from_device_memory(bf16, master_on_host):
+    # hift_write_params_device: the same parameters, forward copy and (through a step) packed copies as the host writer
+    import torch
+    wl = dict(SMALL2, dtype=bf16)
+    _o, a, theta0 = make_pair(wl, seed=14, state_on_host=1, master_on_host=master_on_host)
+    _o, b, _t = make_pair(wl, seed=15, state_on_host=1, master_on_host=master_on_host)     # other weights
+    off = 0
+    for u in range(b.n_units):
+        n = b._unit_count(u, u + 1)
+        b.write_params_device(u, u + 1, torch.from_numpy(theta0[off:off + n]).cuda())
+        off += n
+    assert np.array_equal(a.read_params(), b.read_params()) and np.array_equal(a.read_params(which=1), b.read_params(which=1))
+    batch = to_dev(*make_batch(wl, 14, 1))
+    gid = a.schedule_group_at(1)
+    assert a.step(*batch, gid) == b.step(*batch, gid)
+    assert np.array_equal(a.read_params(), b.read_params())
