@@ -123,8 +123,8 @@ def kernel_bench(reps):
         B = (torch.randn(N * K, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
         C = torch.empty(M * N, device="cuda", dtype=torch.float32 if of else torch.bfloat16)
         lda, ldb = (K if ak else M), (K if bk else N)
-        # forward and dX multiply by a weight matrix: the model keeps those in fragment order and
-        # runs the packed-operand kernel; dW has two activation operands and runs gemm_mfma_k
+        # forward and dX multiply by a weight matrix: the model keeps those in fragment order and runs the
+        # packed-operand kernel; dW has two activation operands stored contraction-index first and runs gemm_tt_k
         packed = ak == 1 and H.kernel_packed_bytes(N, K) > 0
         if packed:
             Bp = torch.empty(H.kernel_packed_bytes(N, K) // 2, device="cuda", dtype=torch.bfloat16)
@@ -143,7 +143,7 @@ def kernel_bench(reps):
         ms = e0.elapsed_time(e1) / reps
         alg_bytes = 2 * (M * K + N * K) + (4 if of else 2) * M * N
         out[name] = {"M": M, "N": N, "K": K, "us": 1e3 * ms, "tflops": 2.0 * M * N * K / ms / 1e9,
-                     "algorithmic_bytes": alg_bytes, "kernel": "gemm_pk_k" if packed else "gemm_mfma_k"}
+                     "algorithmic_bytes": alg_bytes, "kernel": "gemm_pk_k" if packed else ("gemm_tt_k" if not ak and not bk else "gemm_mfma_k")}
         del A, B, C, launch
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
     dst = torch.empty_like(src)

@@ -1017,6 +1017,150 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
 }
 
 // ------------------------------------------------------------------------------------------
+// bf16 MFMA kernel for two operands that are both stored contraction-index first: the weight gradient
+// ------------------------------------------------------------------------------------------
+// dW[out, in] = dY^T . X with dY [T, out] and X [T, in] as the backward pass leaves them: C[M, N] = sum_k A[k][m] B[k][n].
+// The operands go from memory into LDS as they are (rows of k, m contiguous), by direct-to-LDS loads, and the
+// MFMA fragments (lane l: row l % 32 of a 32-row block, the eight k-values 8 (l / 32) ..+7) are formed by
+// transposing LDS reads (ds_read_b64_tr_b16: within a group of 16 lanes, lane i receives as element e what lane
+// i/4 + 4e addressed as its element i%4), two per fragment.  No register staging and no in-register turn, which
+// is what holds gemm_mfma_k back on these operands.
+//   Tile 256 x 256, four wavefronts in a 2 x 2 grid, each 128 x 128 (256 accumulators); a stage is 32 k of both
+//   operands (2 x 16 KB), a ring of four stages, requested three ahead, one barrier per stage in the middle of
+//   the stage's second k-step.
+//   LDS row = 512 bytes = 32 pieces of 16 bytes; piece c of k-row r sits at position c ^ ((r & 3) << 2): one
+//   transposing read touches eight k-rows (r0 ..+3 and r0 + 8 ..+11), 64 bytes of each, which then fall into the
+//   four 64-byte bank groups two by two -- the 512 bytes of the instruction in the two cycles they need anyway.
+//   A load instruction fills two k-rows (lanes 0..31 and 32..63), so the swizzle is applied by choosing which
+//   piece a lane fetches.
+// Needs M and N multiples of 256 and K a multiple of 32 (every weight of the benchmark shapes); fp32 output.
+constexpr int TT_BK = 32, TT_STAGES = 4, TT_ROWB = 512, TT_OPB = TT_BK * TT_ROWB, TT_STG = 2 * TT_OPB;
+
+template <typename OutT>
+__global__ void __launch_bounds__(256) gemm_tt_k(GemmP p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int BM = 256, BN = 256, WM = 128, WN = 128, MT = 4, NT = 4;
+  typedef short v4i16 __attribute__((ext_vector_type(4)));
+  typedef short v8i16 __attribute__((ext_vector_type(8)));
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile = blockIdx.x;
+  const int ntile = p.tiles_m * p.tiles_n;
+  if ((ntile & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);  // a contiguous run of tiles per XCD
+  const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+  const int64_t nst = p.K / TT_BK;
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // ---- requests: wavefront w brings k-rows 8 w ..+7 of both operands of a stage, two rows per instruction
+  const uint64_t aa = reinterpret_cast<uint64_t>(p.A), ba = reinterpret_cast<uint64_t>(p.B);
+  const u32x4 rsA = {(uint32_t)aa, (uint32_t)(aa >> 32) & 0xFFFFu, (uint32_t)(((p.K - 1) * p.lda + p.M) * 2), 0x00020000u};
+  const u32x4 rsB = {(uint32_t)ba, (uint32_t)(ba >> 32) & 0xFFFFu, (uint32_t)(((p.K - 1) * p.ldb + p.N) * 2), 0x00020000u};
+  uint32_t voA[4], voB[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int kr = wave * 8 + q * 2 + (lane >> 5);             // k-row within the stage
+    const int c = (lane & 31) ^ ((kr & 3) << 2);               // the piece this lane fetches
+    voA[q] = (uint32_t)(((int64_t)kr * p.lda + m0 + c * 8) * 2);
+    voB[q] = (uint32_t)(((int64_t)kr * p.ldb + n0 + c * 8) * 2);
+  }
+  const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+  const uint32_t stepA = (uint32_t)(TT_BK * p.lda * 2), stepB = (uint32_t)(TT_BK * p.ldb * 2);
+  auto request = [&](int64_t st, int q) __attribute__((always_inline)) {  // q in 0..7: A pairs then B pairs
+    const int64_t sc = st < nst ? st : nst - 1;                            // past the end: the last stage again
+    const uint32_t dst = lds0 + (uint32_t)(st & (TT_STAGES - 1)) * TT_STG + (uint32_t)wave * 4096 + (q & 3) * 1024;
+    if (q < 4) load_to_lds_b128(rsA, dst, voA[q], (uint32_t)sc * stepA);
+    else load_to_lds_b128(rsB, dst + TT_OPB, voB[q & 3], (uint32_t)sc * stepB);
+  };
+
+  // ---- fragment addresses (k-step 0 of a stage; k-step 1 is 16 rows further)
+  const int sl = lane & 15, fh = lane >> 5;
+  int adA[MT][2], adB[NT][2];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int kr = 8 * fh + (sl >> 2) + 4 * hh;
+      const int colA = wm * WM + i * 32 + 16 * ((lane >> 4) & 1) + 4 * (sl & 3);
+      const int colB = wn * WN + i * 32 + 16 * ((lane >> 4) & 1) + 4 * (sl & 3);
+      adA[i][hh] = kr * TT_ROWB + (((colA >> 3) ^ ((kr & 3) << 2)) * 16) + (colA & 7) * 2;
+      adB[i][hh] = TT_OPB + kr * TT_ROWB + (((colB >> 3) ^ ((kr & 3) << 2)) * 16) + (colB & 7) * 2;
+    }
+  bf16x8 fa[2][MT], fb[2][NT];
+  auto read_frag = [&](bf16x8& f, const unsigned char* base, const int (&ad)[2]) __attribute__((always_inline)) {
+    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(base + ad[0]));
+    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4i16 __attribute__((address_space(3)))*)(base + ad[1]));
+    const v8i16 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    f = __builtin_bit_cast(bf16x8, both);
+  };
+
+  // ---- prologue: three stages on their way, the first one landed
+#pragma unroll
+  for (int st = 0; st < TT_STAGES - 1; ++st)
+#pragma unroll
+    for (int q = 0; q < 8; ++q) request(st, q);
+  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  __syncthreads();
+  {
+    const unsigned char* cur = smem;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) read_frag(fa[0][i], cur, adA[i]);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) read_frag(fb[0][j], cur, adB[j]);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) request(TT_STAGES - 1, q);
+  }
+
+  // ---- main loop.  At the top fa[0], fb[0] hold (or are about to receive) the fragments of the stage's first k-step.
+  for (int64_t st = 0; st < nst; ++st) {
+    const unsigned char* cur = smem + (st & (TT_STAGES - 1)) * TT_STG;
+    const unsigned char* nxt = smem + ((st + 1) & (TT_STAGES - 1)) * TT_STG;
+    // first k-step: one fragment of the second k-step is read after each of the first eight products
+#pragma unroll
+    for (int q = 0; q < MT * NT; ++q) {
+      const int i = q / NT, j = q % NT;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[0][j], fa[0][i], acc[i][j], 0, 0, 0);
+      if (q < MT) read_frag(fa[1][q], cur + 16 * TT_ROWB, adA[q]);
+      else if (q < MT + NT) read_frag(fb[1][q - MT], cur + 16 * TT_ROWB, adB[q - MT]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // second k-step, first half
+#pragma unroll
+    for (int q = 0; q < MT * NT / 2; ++q) {
+      const int i = q / NT, j = q % NT;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // The next stage is read from here on, and this stage's buffer is free once every wavefront is here: its own
+    // requests for the next stage have landed when at most the 16 younger ones (two stages) are outstanding.
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    // second half, with the first fragments of the next stage and the requests for the stage after the ring
+#pragma unroll
+    for (int q = MT * NT / 2; q < MT * NT; ++q) {
+      const int i = q / NT, j = q % NT, r = q - MT * NT / 2;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
+      if (r < MT) read_frag(fa[0][r], nxt, adA[r]);
+      else read_frag(fb[0][r - MT], nxt, adB[r - MT]);
+      request(st + TT_STAGES, r);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // stray requests must land before LDS is reused
+  // epilogue shared with gemm_mfma_k (accumulator layout is the same: the B-side fragment is the first MFMA operand)
+  store_tile<WM, WN, true, OutT>(p, acc, smem, m0, n0, wm, wn, wave, lane, 0, 0);
+}
+
+// ------------------------------------------------------------------------------------------
 // plain FMA kernel: any strides, any element type, fp32 accumulation
 // ------------------------------------------------------------------------------------------
 template <typename T, typename OutT>
@@ -1279,6 +1423,33 @@ hipError_t gemm(const Gemm& g, hipStream_t st, int* variant) {
     const int64_t ext_a = (g.a_kmajor ? g.M * g.lda : g.K * g.lda) * 2, ext_b = (g.b_kmajor ? g.N * g.ldb : g.K * g.ldb) * 2;
     const bool fits = ext_a < (int64_t(1) << 32) && ext_b < (int64_t(1) << 32) &&
                       (g.a_kmajor || g.M >= 8) && (g.b_kmajor || g.N >= 8) && g.K >= 8;
+    if (a_ok && b_ok && fits && !g.a_kmajor && !g.b_kmajor && nz == 1 && g.band == BAND_NONE && g.M % 256 == 0 &&
+        g.N % 256 == 0 && g.K % TT_BK == 0 && (g.M / 256) * (g.N / 256) >= 128 && g.N % 8 == 0 && g.ldc % 8 == 0 &&
+        al16(g.C) && (!g.R || (g.ldr % 8 == 0 && al16(g.R))) && (!g.bias || al16(g.bias))) {
+      // both operands contraction-index first (the weight gradient): direct-to-LDS loads and transposing LDS reads
+      constexpr int LDS_TT = TT_STAGES * TT_STG > 4 * 64 * (128 * 4 + 16) ? TT_STAGES * TT_STG : 4 * 64 * (128 * 4 + 16);
+      static_assert(LDS_TT <= 160 * 1024, "LDS of a gfx950 compute unit");
+      p.tiles_m = (int)(g.M / 256);
+      p.tiles_n = (int)(g.N / 256);
+      if (variant) *variant = 3;
+      static bool attr_f = false, attr_h = false;
+      if (g.out_f32) {
+        if (!attr_f) {
+          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tt_k<float>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TT);
+          if (e != hipSuccess) return e;
+          attr_f = true;
+        }
+        gemm_tt_k<float><<<dim3((unsigned)(p.tiles_m * p.tiles_n)), 256, LDS_TT, st>>>(p);
+      } else {
+        if (!attr_h) {
+          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tt_k<bf16>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TT);
+          if (e != hipSuccess) return e;
+          attr_h = true;
+        }
+        gemm_tt_k<bf16><<<dim3((unsigned)(p.tiles_m * p.tiles_n)), 256, LDS_TT, st>>>(p);
+      }
+      return hipGetLastError();
+    }
     if (a_ok && b_ok && fits) {
       const bool ktail = g.K % KT != 0;
       const int64_t t256 = ((g.M + 255) / 256) * ((g.N + 255) / 256) * (int64_t)nz;

