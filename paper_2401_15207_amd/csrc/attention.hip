@@ -70,6 +70,35 @@ __device__ __forceinline__ void unrotate(f32x16 (&acc)[NB], const float2* __rest
       }
 }
 
+// Rows that a wavefront holds as accumulators (lane l: row l % 32 of its 32 rows, as 4-column pieces: element e of
+// block nb is column 32 nb + 8 (e / 4) + 4 (l / 32) + e % 4) go to memory through LDS.  The output's rows lie a whole
+// row of the caller's matrix apart; written from the registers, every store instruction would touch 32 lines for 16
+// bytes each (measured: 3.8 of the key-major backward kernel's 48 microseconds).  Staged as [32 rows][32 NB columns]
+// in a region of the wavefront's own (32 (64 NB + 16) bytes; the pad spreads the rows over the banks), a store
+// instruction writes whole rows, 16 bytes per lane.  A wavefront reads back only what it wrote itself and its LDS
+// accesses complete in order: no barrier in here; the caller makes sure nobody else still uses the region.
+template <int NB>
+__device__ __forceinline__ void store_rows_staged(const f32x16 (&acc)[NB], float mul, unsigned char* stage, bf16* dst, int64_t ld,
+                                                  int rows_valid, int lane) {
+  constexpr int PITCH = NB * 64 + 16, LPR = NB * 4, RPI = 64 / LPR;  // bytes per staged row; lanes per row; rows per store
+  const int fr = lane & 31, fh = lane >> 5;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 o4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(acc[nb][4 * g + e] * mul);
+      *reinterpret_cast<bf16x4*>(stage + fr * PITCH + (nb * 32 + 8 * g + 4 * fh) * 2) = o4;
+    }
+  const int pr = lane / LPR, pc = lane % LPR;
+#pragma unroll
+  for (int r0 = 0; r0 < 32; r0 += RPI) {
+    const int rr = r0 + pr;
+    if (rr < rows_valid) *reinterpret_cast<u32x4*>(dst + (int64_t)rr * ld + pc * 8) = *reinterpret_cast<const u32x4*>(stage + rr * PITCH + pc * 16);
+  }
+}
+
 // LDS tiles are [64 keys][HD] bf16 without padding; the 16-byte piece c of row r sits at piece position
 // c ^ swz(r), which spreads both the fragment reads (sixteen rows, one piece) and the transposing
 // reads over the banks.  A tile is filled by loads that write 1 KB of consecutive LDS bytes each, so
@@ -330,17 +359,10 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
       l += __shfl_xor(l, 32, 64);  // the two lanes of a row summed different keys
       const float inv = l > 0.f ? 1.0f / l : 0.f;
       if (lse && row_ok && fh == 0) lse[(int64_t)bh * S + row] = m + __builtin_amdgcn_logf(l);
-      if (row_ok) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            bf16x4 o4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(oacc[nb][4 * g + e] * inv);
-            *reinterpret_cast<bf16x4*>(O + (int64_t)row * ldc + nb * 32 + 8 * g + 4 * fh) = o4;
-          }
-      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();  // every wavefront is done with the tiles: the context rows leave through their buffers
+      static_assert(NW * 32 * (ROWB + 16) <= 4 * TILEB, "staging fits the tile buffers");
+      store_rows_staged<NB>(oacc, inv, lds + wave * (32 * (ROWB + 16)), O + (int64_t)q0 * ldc, ldc, S - q0, lane);
       return;
     }
     // ---- pass 1: row maximum and normaliser (m in the log2 domain: raw score * scale_log2e) ----
@@ -523,19 +545,11 @@ __global__ void __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) attn_k(const bf16* _
         for (int nb = 0; nb < NB; ++nb) qacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_[nb], df, qacc[nb], 0, 0, 0);
       }
     }
-    if (row_ok) {
-      bf16* dq = dqkv + (int64_t)b * S * ld + (int64_t)h * HD + (int64_t)row * ld;
-      if (cos_sin) unrotate<NB>(qacc, cos_sin + (int64_t)row * (HD / 2), fh);  // q was rotated after its projection
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 o4;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(qacc[nb][4 * g + e]);
-          *reinterpret_cast<bf16x4*>(dq + nb * 32 + 8 * g + 4 * fh) = o4;
-        }
-    }
+    if (row_ok && cos_sin) unrotate<NB>(qacc, cos_sin + (int64_t)row * (HD / 2), fh);  // q was rotated after its projection
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();  // every wavefront is done with the tiles: dQ leaves through their buffers
+    store_rows_staged<NB>(qacc, 1.0f, lds + wave * (32 * (ROWB + 16)), dqkv + (int64_t)b * S * ld + (int64_t)h * HD + (int64_t)q0 * ld, ld,
+                          S - q0, lane);
   }
 }
 
@@ -665,83 +679,107 @@ __global__ void __launch_bounds__(256, 1) attn_bwd_kv_k(const bf16* __restrict__
     if (CAUSAL && it * QT + QT - 1 < j0) continue;  // every query of the tile precedes this wavefront's keys
     const unsigned char* Qb = lds + (it & 1) * BUF;
     const unsigned char* Ob = Qb + TQ;
+    // The tile's two blocks of 32 queries go through three phases each -- A: S^T and dP^T (2 KS products), B: the
+    // probabilities and dS^T from them (an exponential and a handful of VALU instructions per element), C: the
+    // sums into dV and dK (4 NB products) -- software-pipelined so that the VALU work of one block issues in the
+    // shadow of the other block's products: A(0); A(1) with B(0); C(0) with B(1); C(1).  A wavefront issues in
+    // order and a product holds the matrix pipe for 32 cycles, about what one element of phase B costs.
+    f32x4 lq[2][4], dq4[2][4];  // per-query scalars: element e of a lane is query qb0 + 16 (e / 8) + 8 fh + e % 8
 #pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-      const int qb0 = it * QT + blk * 32;  // first query of the block
-      // element e of a lane: query qb0 + 16 (e / 8) + 8 fh + e % 8
-      f32x4 lq[4], dq4[4];
+    for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int off = (blk * 32 + 16 * (c >> 1) + 8 * fh + 4 * (c & 1)) * 4;
-        lq[c] = *reinterpret_cast<const f32x4*>(Qb + 2 * TQ + off);
-        dq4[c] = *reinterpret_cast<const f32x4*>(Qb + 2 * TQ + 1024 + off);
+        lq[blk][c] = *reinterpret_cast<const f32x4*>(Qb + 2 * TQ + off);
+        dq4[blk][c] = *reinterpret_cast<const f32x4*>(Qb + 2 * TQ + 1024 + off);
       }
-      f32x16 st, dpt;
+    f32x16 st[2], dpt[2];
+    bf16x8 pf[2][2], sf[2][2];
+    bool plain[2];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) st[e] = dpt[e] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 xq = *reinterpret_cast<const bf16x8*>(Qb + faddr[blk][ks]);
-        const bf16x8 xo = *reinterpret_cast<const bf16x8*>(Ob + faddr[blk][ks]);
-        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xq, kf[ks], st, 0, 0, 0);
-        dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo, vf[ks], dpt, 0, 0, 0);
-      }
-      bf16x8 pf[2], sf[2];
+    for (int blk = 0; blk < 2; ++blk) {
+      const int qb0 = it * QT + blk * 32;
       // no query of the block is masked for any key of this wavefront: all inside the sequence and, under the
       // causal mask, at or after its last key
-      const bool plain = qb0 + 32 <= S && (!CAUSAL || qb0 >= j0 + 31);
-      if (plain) {
+      plain[blk] = qb0 + 32 <= S && (!CAUSAL || qb0 >= j0 + 31);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(st[e], scale_log2e, -lq[e / 4][e % 4]));
-          pf[e / 8][e % 8] = static_cast<__bf16>(pr);
-          sf[e / 8][e % 8] = static_cast<__bf16>(scale * pr * (dpt[e] - dq4[e / 4][e % 4]));
-        }
-      } else {
+      for (int e = 0; e < 16; ++e) st[blk][e] = dpt[blk][e] = 0.f;
+    }
+    auto element = [&](int blk, int e) __attribute__((always_inline)) {  // phase B for one element
+      const int qi = it * QT + blk * 32 + 16 * (e / 8) + 8 * fh + e % 8;
+      // (bitwise, not short-circuit: a branch per element would break the interleaving up)
+      const bool ok = plain[blk] | ((qi < S) & (!CAUSAL | (qi >= row)));
+      const float ex = __builtin_amdgcn_exp2f(__builtin_fmaf(st[blk][e], scale_log2e, -lq[blk][e / 4][e % 4]));
+      const float pr = ok ? ex : 0.f;
+      pf[blk][e / 8][e % 8] = static_cast<__bf16>(pr);
+      sf[blk][e / 8][e % 8] = static_cast<__bf16>(scale * pr * (dpt[blk][e] - dq4[blk][e / 4][e % 4]));
+    };
+    constexpr int EA = 16 / KS, EC = 16 / (2 * NB);  // elements of phase B per pair of products of phase A / C
+    auto phase_a = [&](int blk, int other) __attribute__((always_inline)) {  // other >= 0: phase B of that block rides along
+      bf16x8 xq[2], xo[2];
+      xq[0] = *reinterpret_cast<const bf16x8*>(Qb + faddr[blk][0]);
+      xo[0] = *reinterpret_cast<const bf16x8*>(Ob + faddr[blk][0]);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int qi = qb0 + 16 * (e / 8) + 8 * fh + e % 8;
-          const bool ok = qi < S && (!CAUSAL || qi >= row);
-          const float pr = ok ? __builtin_amdgcn_exp2f(__builtin_fmaf(st[e], scale_log2e, -lq[e / 4][e % 4])) : 0.f;
-          pf[e / 8][e % 8] = static_cast<__bf16>(pr);
-          sf[e / 8][e % 8] = static_cast<__bf16>(scale * pr * (dpt[e] - dq4[e / 4][e % 4]));
+      for (int ks = 0; ks < KS; ++ks) {
+        if (ks + 1 < KS) {
+          xq[(ks + 1) & 1] = *reinterpret_cast<const bf16x8*>(Qb + faddr[blk][ks + 1]);
+          xo[(ks + 1) & 1] = *reinterpret_cast<const bf16x8*>(Ob + faddr[blk][ks + 1]);
         }
+        st[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xq[ks & 1], kf[ks], st[blk], 0, 0, 0);
+        if (other >= 0)
+#pragma unroll
+          for (int e = 0; e < EA / 2; ++e) element(other, ks * EA + e);
+        __builtin_amdgcn_sched_barrier(0);
+        dpt[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo[ks & 1], vf[ks], dpt[blk], 0, 0, 0);
+        if (other >= 0)
+#pragma unroll
+          for (int e = EA / 2; e < EA; ++e) element(other, ks * EA + e);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    auto phase_c = [&](int blk, int other) __attribute__((always_inline)) {
+      bf16x8 xo[2][NB], xq[2][NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        xo[0][nb] = tr_frag(Ob + (2 * blk) * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
+        xq[0][nb] = tr_frag(Qb + (2 * blk) * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
       }
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2) {
-        const int t = 2 * blk + t2;
-        bf16x8 xo[NB], xq[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-          xo[nb] = tr_frag(Ob + t * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
-          xq[nb] = tr_frag(Qb + t * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
-        }
+          if (t2 == 0) {  // the second k-step's fragments are read under the first one's products
+            xo[1][nb] = tr_frag(Ob + (2 * blk + 1) * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
+            xq[1][nb] = tr_frag(Qb + (2 * blk + 1) * 16 * ROWB, xaddr[nb][0], xaddr[nb][1]);
+          }
+          vacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo[t2][nb], pf[blk][t2], vacc[nb], 0, 0, 0);
+          if (other >= 0)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          vacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo[nb], pf[t2], vacc[nb], 0, 0, 0);
-          kacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xq[nb], sf[t2], kacc[nb], 0, 0, 0);
+            for (int e = 0; e < EC / 2; ++e) element(other, (t2 * NB + nb) * EC + e);
+          __builtin_amdgcn_sched_barrier(0);
+          kacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xq[t2][nb], sf[blk][t2], kacc[nb], 0, 0, 0);
+          if (other >= 0)
+#pragma unroll
+            for (int e = EC / 2; e < EC; ++e) element(other, (t2 * NB + nb) * EC + e);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
-    }
+    };
+    static_assert(EA >= 2 && EC >= 2 && EA * KS == 16 && EC * 2 * NB == 16, "all 16 elements of a block ride along");
+    phase_a(0, -1);
+    phase_a(1, 0);
+    phase_c(0, 1);
+    phase_c(1, -1);
   }
-  if (row_ok) {
-    if (cos_sin) unrotate<NB>(kacc, cos_sin + (int64_t)row * (HD / 2), fh);
-    bf16* dk = dqkv + (int64_t)b * S * ld + d + (int64_t)h * HD + (int64_t)row * ld;
-    bf16* dv = dk + d;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 k4, v4;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          k4[e] = static_cast<__bf16>(kacc[nb][4 * g + e]);
-          v4[e] = static_cast<__bf16>(vacc[nb][4 * g + e]);
-        }
-        *reinterpret_cast<bf16x4*>(dk + nb * 32 + 8 * g + 4 * fh) = k4;
-        *reinterpret_cast<bf16x4*>(dv + nb * 32 + 8 * g + 4 * fh) = v4;
-      }
-  }
+  // dK and dV leave through LDS (store_rows_staged), in the tile buffers
+  if (row_ok && cos_sin) unrotate<NB>(kacc, cos_sin + (int64_t)row * (HD / 2), fh);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();  // every wavefront is done with the tiles
+  constexpr int OSTG = 32 * (ROWB + 16);
+  static_assert(4 * 2 * OSTG <= 2 * BUF, "staging fits the tile buffers");
+  bf16* dk0 = dqkv + (int64_t)b * S * ld + d + (int64_t)h * HD + (int64_t)j0 * ld;
+  store_rows_staged<NB>(kacc, 1.0f, lds + (2 * wave) * OSTG, dk0, ld, S - j0, lane);
+  store_rows_staged<NB>(vacc, 1.0f, lds + (2 * wave + 1) * OSTG, dk0 + d, ld, S - j0, lane);
 }
 
 inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -750,9 +788,8 @@ inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) =
 
 // prob may be null for the forward (the probabilities are then not stored)
 bool attention_fwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* prob, const void* ctx) {
-  return dt == DT_BF16 && (hd == 64 || hd == 128) && S >= 8 && S % 8 == 0 && ld % 8 == 0 && ldc % 4 == 0 && al16(qkv) && al16(prob) &&
-         (int64_t)S * ld * 2 < (int64_t(1) << 32) && (int64_t)S * S * 2 <= (int64_t(1) << 31) &&
-         (reinterpret_cast<uintptr_t>(ctx) & 7) == 0;
+  return dt == DT_BF16 && (hd == 64 || hd == 128) && S >= 8 && S % 8 == 0 && ld % 8 == 0 && ldc % 8 == 0 && al16(qkv) && al16(prob) &&
+         (int64_t)S * ld * 2 < (int64_t(1) << 32) && (int64_t)S * S * 2 <= (int64_t(1) << 31) && al16(ctx);
 }
 
 namespace {
@@ -798,7 +835,7 @@ hipError_t attention_fwd_fused(int B, int H, int S, int hd, bool causal, const v
 bool attention_bwd_fused_applies(int dt, int S, int hd, int64_t ld, int64_t ldc, const void* qkv, const void* ctx, const void* dctx,
                                  const void* dqkv) {
   return attention_fwd_fused_applies(dt, S, hd, ld, ldc, qkv, nullptr, ctx) && ldc % 8 == 0 && al16(ctx) && al16(dctx) &&
-         (reinterpret_cast<uintptr_t>(dqkv) & 7) == 0;
+         (reinterpret_cast<uintptr_t>(dqkv) & 15) == 0;
 }
 
 hipError_t attention_bwd_fused(int B, int H, int S, int hd, bool causal, const void* qkv, int64_t ld, const void* ctx,
