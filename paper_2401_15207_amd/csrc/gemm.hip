@@ -458,10 +458,24 @@ __device__ __forceinline__ u32x4 scale8(u32x4 a, u32x4 b) {
   return __builtin_bit_cast(u32x4, x);
 }
 
+// Eight consecutive values of the source as bf16: a 16-byte load, or, for an fp32 source (the master weights), two
+// loads and eight roundings to nearest even -- the bf16 model is by definition that rounding of the master.
+__device__ __forceinline__ u32x4 load8_bf16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ u32x4 load8_bf16(const float* p) {
+  const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+  bf16x8 t;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { t[e] = static_cast<__bf16>(a[e]); t[4 + e] = static_cast<__bf16>(b[e]); }
+  return __builtin_bit_cast(u32x4, t);
+}
+__device__ __forceinline__ bf16 load1_bf16(const bf16* p) { return *p; }
+__device__ __forceinline__ bf16 load1_bf16(const float* p) { return static_cast<__bf16>(*p); }
+
 // The packers take an optional gain [K]: the copy then holds B[n][k] gain[k] (a row normalisation's gain folded
 // into the weight that consumes the normalised rows).
 // Generic packer (any alignment): one wavefront per 1 KB block, element-wise reads.
-__global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int64_t ldb, int64_t N, int64_t K,
+template <typename SrcT>
+__global__ void __launch_bounds__(256) pack_b_k(const SrcT* __restrict__ B, int64_t ldb, int64_t N, int64_t K,
                                                  bool b_kmajor, u32x4* __restrict__ Bp, int64_t n_blocks, int64_t k_steps,
                                                  int order, int64_t half, const bf16* __restrict__ gain) {
   const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -474,7 +488,7 @@ __global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int6
   for (int e = 0; e < 8; ++e) {
     const int64_t k = k0 + e;
     float x = 0.f;
-    if (n < N && k < K) x = static_cast<float>(b_kmajor ? B[n * ldb + k] : B[k * ldb + n]);
+    if (n < N && k < K) x = static_cast<float>(load1_bf16(b_kmajor ? B + n * ldb + k : B + k * ldb + n));
     if (gain && k < K) x *= static_cast<float>(gain[k]);
     v[e] = static_cast<__bf16>(x);
   }
@@ -485,8 +499,8 @@ __global__ void __launch_bounds__(256) pack_b_k(const bf16* __restrict__ B, int6
 // reads of the source and the writes of the 1 KB blocks are whole contiguous runs.
 //   KMAJOR: tile = 32 rows (one n-block) x 256 k (16 k-steps); source rows are contiguous in k.
 //   else:   tile = 32 k (two k-steps) x 256 n (eight n-blocks); source rows are contiguous in n.
-template <bool KMAJOR>
-__global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B, int64_t ldb, int64_t N, int64_t K,
+template <bool KMAJOR, typename SrcT>
+__global__ void __launch_bounds__(256) pack_b_tile_k(const SrcT* __restrict__ B, int64_t ldb, int64_t N, int64_t K,
                                                       u32x4* __restrict__ Bp, int64_t k_steps, int tiles_inner, int order,
                                                       int64_t half, const bf16* __restrict__ gain) {
   constexpr int PITCH = 512 + 16;  // bytes per tile row in LDS; the pad spreads 16-byte reads of one column over the banks
@@ -501,7 +515,7 @@ __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B,
       const int r = ps * 8 + (tid >> 5), c = (tid & 31) * 8;
       const int64_t n = nb * 32 + r, k = k00 + c;
       u32x4 v = zero;
-      if (n < N && k < K) v = *reinterpret_cast<const u32x4*>(B + n * ldb + k);
+      if (n < N && k < K) v = load8_bf16(B + n * ldb + k);
       if (gain && n < N && k < K) v = scale8(v, *reinterpret_cast<const u32x4*>(gain + k));  // K % 8 == 0 here
       *reinterpret_cast<u32x4*>(tile + r * PITCH + c * 2) = v;
     }
@@ -522,11 +536,11 @@ __global__ void __launch_bounds__(256) pack_b_tile_k(const bf16* __restrict__ B,
       const int64_t k = kk0 * 16 + r, n = n00 + c;
       u32x4 v = zero;
       if (n + 8 <= N) {
-        v = *reinterpret_cast<const u32x4*>(B + k * ldb + n);
+        v = load8_bf16(B + k * ldb + n);
       } else if (n < N) {
         bf16x8 t;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = n + e < N ? B[k * ldb + n + e] : static_cast<__bf16>(0.f);
+        for (int e = 0; e < 8; ++e) t[e] = n + e < N ? load1_bf16(B + k * ldb + n + e) : static_cast<__bf16>(0.f);
         v = __builtin_bit_cast(u32x4, t);
       }
       if (gain && k < K) {
@@ -1265,34 +1279,44 @@ size_t packed_b_bytes(int64_t N, int64_t K) {
   return (size_t)((N + 255) / 256) * 8 * (size_t)(K / 16) * 1024;
 }
 
-hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st, int order,
-                  const void* gain) {
-  if (packed_b_bytes(N, K) == 0) return hipErrorInvalidValue;
-  if (order == PK_ORDER_HALVES ? N % 256 != 0 : order == PK_ORDER_PAIR64 ? N % 128 != 0 : order != PK_ORDER_PLAIN)
-    return hipErrorInvalidValue;
+namespace {
+template <typename SrcT>
+hipError_t pack_b_from(const SrcT* Bs, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st, int order,
+                       const void* gain) {
   const int64_t half = N / 64;  // 32-row blocks in half of B
   const int64_t n_blocks = ((N + 255) / 256) * 8, k_steps = K / 16;
-  const bf16* Bs = reinterpret_cast<const bf16*>(B);
   const bf16* gn = reinterpret_cast<const bf16*>(gain);
   u32x4* out = reinterpret_cast<u32x4*>(Bp);
-  if (al16(B) && ldb % 8 == 0 && (!gain || (al16(gain) && K % 8 == 0))) {
+  constexpr int PER16 = 16 / (int)sizeof(SrcT);  // source values per 16 bytes
+  const bool src_ok = (reinterpret_cast<uintptr_t>(Bs) & 15) == 0 && ldb % PER16 == 0 && ldb % 8 == 0;
+  if (src_ok && (!gain || (al16(gain) && K % 8 == 0))) {
     if (b_kmajor) {
       const int ti = (int)((K + 255) / 256);
-      pack_b_tile_k<true><<<dim3((unsigned)(n_blocks * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti, order, half, gn);
+      pack_b_tile_k<true, SrcT><<<dim3((unsigned)(n_blocks * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti, order, half, gn);
     } else {
       const int ti = (int)(n_blocks / 8);
-      pack_b_tile_k<false><<<dim3((unsigned)((K / 32) * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti, order, half, gn);
+      pack_b_tile_k<false, SrcT><<<dim3((unsigned)((K / 32) * ti)), 256, 0, st>>>(Bs, ldb, N, K, out, k_steps, ti, order, half, gn);
     }
   } else {
     const int64_t blocks = n_blocks * k_steps;
-    pack_b_k<<<dim3((unsigned)((blocks + 3) / 4)), 256, 0, st>>>(Bs, ldb, N, K, b_kmajor, out, n_blocks, k_steps, order, half, gn);
+    pack_b_k<SrcT><<<dim3((unsigned)((blocks + 3) / 4)), 256, 0, st>>>(Bs, ldb, N, K, b_kmajor, out, n_blocks, k_steps, order, half, gn);
   }
   return hipGetLastError();
+}
+}  // namespace
+
+hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st, int order,
+                  const void* gain, bool src_f32) {
+  if (packed_b_bytes(N, K) == 0) return hipErrorInvalidValue;
+  if (order == PK_ORDER_HALVES ? N % 256 != 0 : order == PK_ORDER_PAIR64 ? N % 128 != 0 : order != PK_ORDER_PLAIN)
+    return hipErrorInvalidValue;
+  if (src_f32) return pack_b_from(reinterpret_cast<const float*>(B), ldb, N, K, b_kmajor, Bp, st, order, gain);
+  return pack_b_from(reinterpret_cast<const bf16*>(B), ldb, N, K, b_kmajor, Bp, st, order, gain);
 }
 
 constexpr int PK_MT = 4;  // 128 x 256 tiles
 
-bool packed_gemm_applies(const Gemm& g) {
+bool packed_gemm_applies(const Gemm& g, bool any_tile_count) {
   if (g.dtype != DT_BF16 || !g.a_kmajor || g.nb * g.nh != 1 || packed_b_bytes(g.N, g.K) == 0) return false;
   const bool vec = g.N % 8 == 0 && g.ldc % 8 == 0 && al16(g.C) && (!g.R || (g.ldr % 8 == 0 && al16(g.R))) &&
                    (!g.bias || al16(g.bias));
@@ -1300,7 +1324,8 @@ bool packed_gemm_applies(const Gemm& g) {
   const bool fits = (g.M + 256) * g.lda * 2 < (int64_t(1) << 32) && al16(g.A) && g.lda % 8 == 0 &&
                     packed_b_bytes(g.N, g.K) < (size_t(1) << 32);
   if (!(vec && fits)) return false;
-  return ((g.M + 32 * PK_MT - 1) / (32 * PK_MT)) * ((g.N + 255) / 256) >= 200;  // enough tiles to fill the chip
+  // enough tiles to fill the chip -- unless the caller has no other kernel to go to (no row-major copy of the weight)
+  return any_tile_count || ((g.M + 32 * PK_MT - 1) / (32 * PK_MT)) * ((g.N + 255) / 256) >= 200;
 }
 
 namespace {
@@ -1337,7 +1362,7 @@ size_t packed_ws_needed(const Gemm& g) {
 }
 
 hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st) {
-  if (!packed_gemm_applies(g)) return hipErrorInvalidValue;
+  if (!packed_gemm_applies(g, true)) return hipErrorInvalidValue;
   GemmP p;
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.A = g.A; p.lda = g.lda; p.B = nullptr; p.ldb = 0; p.C = g.C; p.ldc = g.ldc;

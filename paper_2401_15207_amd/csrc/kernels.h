@@ -81,9 +81,12 @@ hipError_t gemm(const Gemm& g, hipStream_t st, int* variant = nullptr);
 enum { PK_ORDER_PLAIN = 0, PK_ORDER_HALVES = 1, PK_ORDER_PAIR64 = 2 };
 size_t packed_b_bytes(int64_t N, int64_t K);
 // gain (optional, bf16 [K]): the copy holds B[n][k] gain[k], each product rounded once.
+// src_f32: B holds fp32 values (the master weights); each is rounded to bf16 (nearest even) first, which is by
+// definition the value of the bf16 model, so the copy is the same as from a bf16 source.
 hipError_t pack_b(const void* B, int64_t ldb, int64_t N, int64_t K, bool b_kmajor, void* Bp, hipStream_t st,
-                  int order = PK_ORDER_PLAIN, const void* gain = nullptr);
-bool packed_gemm_applies(const Gemm& g);
+                  int order = PK_ORDER_PLAIN, const void* gain = nullptr, bool src_f32 = false);
+// any_tile_count: also problems with too few tiles to fill the chip (for weights that have no row-major copy to fall back on)
+bool packed_gemm_applies(const Gemm& g, bool any_tile_count = false);
 hipError_t gemm_packed(const Gemm& g, const void* Bp, hipStream_t st);
 // Bytes of work space gemm_packed would use for this problem if given one (0: its last round is not shared).
 size_t packed_ws_needed(const Gemm& g);

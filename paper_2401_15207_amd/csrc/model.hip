@@ -54,6 +54,9 @@ struct Tensor {
   // index of the normalisation gain folded into the forward copy, or -1: the layer then multiplies the rows
   // as they are before the normalisation, and the kernel scales by their 1 / rms (see Gemm::rowsq)
   int pk_gain = -1;
+  // position in the bf16 copy of the model (elements), or -1: a matrix that has both fragment-order copies keeps no
+  // row-major bf16 copy; what would read it reads the copies (contractions) or the fp32 master (re-packing)
+  int64_t wc_off = -1;
   int64_t fac_off = 0;  // Adafactor: first float of this tensor's statistics ([rows | cols], or [rows] for vectors)
   int64_t fac_count() const { return cols > 1 ? rows + cols : rows; }
   int64_t count() const { return rows * cols; }
@@ -347,8 +350,13 @@ struct hift_model {
   int copy_blocks = 16;
   Prof prof;
 
+  int64_t wc_count = 0;  // elements of the bf16 copy
   const Tensor& T_(const std::string& n) const { return lay.t[lay.find(n)]; }
-  void* W(const Tensor& t) const { return reinterpret_cast<unsigned char*>(wc) + t.off * es; }
+  // the tensor as the forward pass reads it (null for a matrix that lives only in its fragment-order copies)
+  void* W(const Tensor& t) const {
+    if (dt != DT_BF16) return reinterpret_cast<unsigned char*>(wc) + t.off * es;
+    return t.wc_off >= 0 ? reinterpret_cast<unsigned char*>(wc) + t.wc_off * 2 : nullptr;
+  }
   void* W(const std::string& n) const { return W(T_(n)); }
 };
 
@@ -368,7 +376,7 @@ void carve(hift_model* mm, void* dev, size_t* dev_bytes, size_t* pinned_bytes, s
   b.cat = MEM_MASTER;
   M.master = M.master_host ? nullptr : (float*)b.take(np * 4);
   b.cat = MEM_FORWARD;
-  M.wc = M.dt == DT_BF16 ? b.take(np * 2) : (void*)M.master;
+  M.wc = M.dt == DT_BF16 ? b.take((size_t)M.wc_count * 2) : (void*)M.master;
   b.cat = MEM_PACKED;
   M.wpk = M.wpk_bytes ? (unsigned char*)b.take(M.wpk_bytes) : nullptr;
   b.cat = MEM_GRAD;
@@ -541,7 +549,33 @@ hift_status init_model_shape(hift_model* M, const hift_config* cfg, const hift_o
       M->wpk_bytes += (packed_b_bytes(t.cols, t.rows) + 255) & ~(size_t)255;
     }
   }
+  // The bf16 copy of the model: every tensor, except matrices that have both fragment-order copies (7B shape: 13.5 GB
+  // less).  Kept for all when the master lives on the host (its pieces pass through a slot tensor by tensor boundaries
+  // unknown to them) and for a token table that is also the output matrix (the embedding lookup reads its rows).
+  M->wc_count = 0;
+  for (Tensor& t : M->lay.t) {
+    if (M->master_host) {  // the copy mirrors the parameter order exactly
+      t.wc_off = t.off;
+      M->wc_count = t.off + t.count();
+      continue;
+    }
+    const bool packed_only = t.pk_fwd >= 0 && t.pk_bwd >= 0 && t.unit != 0;
+    t.wc_off = packed_only ? -1 : M->wc_count;
+    if (!packed_only) M->wc_count += (t.count() + 7) & ~(int64_t)7;  // 16-byte aligned starts
+  }
   return HIFT_OK;
+}
+
+// bf16 copy of the tensors of units [ulo, uhi) from the fp32 master in HBM (tensors that keep one)
+hipError_t cast_units(hift_model* M, int ulo, int uhi) {
+  if (M->dt != DT_BF16) return hipSuccess;
+  for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
+    const Tensor& t = M->lay.t[i];
+    if (t.wc_off < 0) continue;
+    hipError_t e = cast_f32_to(DT_BF16, t.count(), M->master + t.off, M->W(t), M->cs);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 // Rebuilds the fragment-order copies of the matrices of units [ulo, uhi) from the bf16 weights.
@@ -549,13 +583,16 @@ hipError_t repack_units(hift_model* M, int ulo, int uhi) {
   if (!M->wpk) return hipSuccess;
   for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
     const Tensor& t = M->lay.t[i];
+    // source: the row-major bf16 copy, or, where none is kept, the fp32 master (rounded on the way: the same values)
+    const bool f32src = M->dt == DT_BF16 && t.wc_off < 0;
+    const void* src = f32src ? (const void*)(M->master + t.off) : (const void*)M->W(t);
     if (t.pk_fwd >= 0) {
-      hipError_t e = pack_b(M->W(t), t.cols, t.rows, t.cols, true, M->wpk + t.pk_fwd, M->cs, t.pk_order,
-                            t.pk_gain >= 0 ? M->W(M->lay.t[t.pk_gain]) : nullptr);
+      hipError_t e = pack_b(src, t.cols, t.rows, t.cols, true, M->wpk + t.pk_fwd, M->cs, t.pk_order,
+                            t.pk_gain >= 0 ? M->W(M->lay.t[t.pk_gain]) : nullptr, f32src);
       if (e != hipSuccess) return e;
     }
     if (t.pk_bwd >= 0) {
-      hipError_t e = pack_b(M->W(t), t.cols, t.cols, t.rows, false, M->wpk + t.pk_bwd, M->cs);
+      hipError_t e = pack_b(src, t.cols, t.cols, t.rows, false, M->wpk + t.pk_bwd, M->cs, PK_ORDER_PLAIN, nullptr, f32src);
       if (e != hipSuccess) return e;
     }
   }
@@ -651,7 +688,8 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
   g.bias = bias ? M->W(*bias) : nullptr;
   g.R = R; g.ldr = w.rows;
   Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
-  if (w.pk_fwd >= 0 && packed_gemm_applies(g)) {
+  const bool only_packed = M->dt == DT_BF16 && w.wc_off < 0;  // no row-major copy to fall back on: any batch goes here
+  if (w.pk_fwd >= 0 && packed_gemm_applies(g, only_packed)) {
     if (w.pk_order != PK_ORDER_PLAIN) {
       // the copy's block order is undone only by the epilogue it was made for
       if (!epi || bias || R) return fail(HIFT_ESTATE, "packed copy ordered for a fused epilogue used without one");
@@ -684,6 +722,7 @@ hift_status linear(hift_model* M, const void* x, int64_t rows, const Tensor& w, 
     return HIFT_OK;
   }
   if (rowsq) *rowsq = false;
+  if (only_packed) return fail(HIFT_ESTATE, "%s has no row-major copy and the packed-operand kernel refused the problem", w.name.c_str());
   if (sc.r) sc.r->cat = CAT_GEMM_REST;
   K_TRY(gemm(g, M->cs));
   return HIFT_OK;
@@ -704,7 +743,8 @@ hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor&
   g.C = dx; g.ldc = w.cols;
   g.R = R; g.ldr = w.cols;
   Scope sc(M, CAT_GEMM, 2.0 * rows * w.rows * w.cols);
-  if (w.pk_bwd >= 0 && packed_gemm_applies(g)) {
+  const bool only_packed = M->dt == DT_BF16 && w.wc_off < 0;
+  if (w.pk_bwd >= 0 && packed_gemm_applies(g, only_packed)) {
     const bool epi_on = !(M->cfg.unfused & HIFT_UNFUSED_EPILOGUES);
     if (epi_on && gate_pre && dgu && fused && !R && w.cols % 8 == 0 && (reinterpret_cast<uintptr_t>(dgu) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(gate_pre) & 15) == 0) {
@@ -718,6 +758,7 @@ hift_status linear_dx(hift_model* M, const void* dy, int64_t rows, const Tensor&
     K_TRY(gemm_packed(g, M->wpk + w.pk_bwd, M->cs));
     return HIFT_OK;
   }
+  if (only_packed) return fail(HIFT_ESTATE, "%s has no row-major copy and the packed-operand kernel refused the problem", w.name.c_str());
   if (sc.r) sc.r->cat = CAT_GEMM_REST;
   K_TRY(gemm(g, M->cs));
   return HIFT_OK;
@@ -1537,7 +1578,7 @@ hift_status hift_model_create_chunked(const hift_config* cfg, const hift_opt* op
     } else {
       CR_TRY(fill_zero(M->master, (size_t)M->lay.n_params * 4, M->cs));
     }
-    if (M->dt == DT_BF16) CR_TRY(cast_f32_to(DT_BF16, M->lay.n_params, M->master, M->wc, M->cs));
+    CR_TRY(cast_units(M, 0, M->lay.n_units));
   }
   CR_TRY(repack_units(M, 0, M->lay.n_units));
   CR_TRY(hipStreamSynchronize(M->cs));
@@ -1816,7 +1857,7 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
     for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
       const Tensor& t = M->lay.t[i];
       const int64_t tg = M->unit_steps[t.unit];
-      void* cc = M->dt == DT_BF16 ? (unsigned char*)M->wc + t.off * 2 : nullptr;
+      void* cc = M->dt == DT_BF16 ? M->W(t) : nullptr;  // null also for a matrix kept only in fragment order
       if (M->opt.kind == HIFT_ADAFACTOR) {
         K_TRY(adafactor_update(M->opt.lr, M->opt.weight_decay, t.kind == HIFT_KIND_MATRIX, tg, t.rows, t.cols,
                                mbase + t.off, M->grad + (t.off - plo), M->fac + t.fac_off, M->af_work, cc, M->cs));
@@ -1944,11 +1985,29 @@ hift_status hift_read_params(hift_model* M, int32_t ulo, int32_t uhi, int32_t wh
   } else if (which == 0 || M->dt == DT_F32) {
     HIP_TRY(hipMemcpy(dst, M->master + off, (size_t)cnt * 4, hipMemcpyDeviceToHost));
   } else {
-    std::vector<uint16_t> tmp((size_t)cnt);
-    HIP_TRY(hipMemcpy(tmp.data(), (unsigned char*)M->wc + off * 2, (size_t)cnt * 2, hipMemcpyDeviceToHost));
-    for (int64_t i = 0; i < cnt; ++i) {
-      const uint32_t u = (uint32_t)tmp[i] << 16;
-      memcpy(dst + i, &u, 4);
+    // tensor by tensor: from the bf16 copy, or, for a matrix kept only in fragment order, the master rounded to
+    // nearest even, which is what its copies hold
+    std::vector<uint16_t> tmp;
+    for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i) {
+      const Tensor& t = M->lay.t[i];
+      float* out = dst + (t.off - off);
+      if (t.wc_off >= 0) {
+        tmp.resize((size_t)t.count());
+        HIP_TRY(hipMemcpy(tmp.data(), M->W(t), (size_t)t.count() * 2, hipMemcpyDeviceToHost));
+        for (int64_t e = 0; e < t.count(); ++e) {
+          const uint32_t u = (uint32_t)tmp[e] << 16;
+          memcpy(out + e, &u, 4);
+        }
+      } else {
+        HIP_TRY(hipMemcpy(out, M->master + t.off, (size_t)t.count() * 4, hipMemcpyDeviceToHost));
+        for (int64_t e = 0; e < t.count(); ++e) {
+          uint32_t u;
+          memcpy(&u, out + e, 4);
+          if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + ((u >> 16) & 1u);  // nearest even; inf / nan stay
+          u &= 0xFFFF0000u;
+          memcpy(out + e, &u, 4);
+        }
+      }
     }
   }
   return HIFT_OK;
@@ -1980,7 +2039,7 @@ hift_status write_params_from(hift_model* M, int32_t ulo, int32_t uhi, const flo
   else HIP_TRY(hipMemcpy(M->master + off, src, (size_t)cnt * 4, hipMemcpyHostToDevice));
   if (M->dt != DT_BF16) HIP_TRY(hipStreamSynchronize(M->cs));
   if (M->dt == DT_BF16) {
-    HIP_TRY(cast_f32_to(DT_BF16, cnt, M->master + off, (unsigned char*)M->wc + off * 2, M->cs));
+    HIP_TRY(cast_units(M, ulo, uhi));
     HIP_TRY(repack_units(M, ulo, uhi));
     HIP_TRY(hipStreamSynchronize(M->cs));
   }
