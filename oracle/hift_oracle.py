@@ -259,12 +259,19 @@ def rmsnorm_bwd(dy, cache, g):
     return dx, dg
 
 
-def gelu_fwd(x):
-    return 0.5 * x * (1.0 + _erf(x / math.sqrt(2.0)))
+def gelu_cdf(x):
+    """Phi(x), the standard normal distribution function."""
+    return 0.5 * (1.0 + _erf(x / math.sqrt(2.0)))
 
 
-def gelu_bwd(dy, x):
-    cdf = 0.5 * (1.0 + _erf(x / math.sqrt(2.0)))
+def gelu_fwd(x, cdf=None):
+    """x Phi(x).  cdf: Phi(x) if the caller has it already (the error function is the slow part)."""
+    return x * (gelu_cdf(x) if cdf is None else cdf)
+
+
+def gelu_bwd(dy, x, cdf=None):
+    """dy (Phi(x) + x phi(x))."""
+    cdf = gelu_cdf(x) if cdf is None else cdf
     pdf = np.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi)
     return dy * (cdf + x * pdf)
 
@@ -447,7 +454,8 @@ def loss_and_grad(cfg: dict, flat: np.ndarray, tokens: np.ndarray, labels: np.nd
         else:
             pre = h2 @ P[p + "w1"].T + P[p + "b1"]
             c["pre"] = pre
-            act = gelu_fwd(pre)
+            c["cdf"] = gelu_cdf(pre)          # kept for the backward pass: the same values, evaluated once
+            act = gelu_fwd(pre, c["cdf"])
             fo = act @ P[p + "w2"].T + P[p + "b2"]
         c["act"] = act
         x = x + fo
@@ -503,7 +511,7 @@ def loss_and_grad(cfg: dict, flat: np.ndarray, tokens: np.ndarray, labels: np.nd
             G[p + "w2"][...] = dfo.T @ c["act"]
             G[p + "b2"][...] = dfo.sum(0)
             dact = dfo @ P[p + "w2"]
-            dpre = gelu_bwd(dact, c["pre"])
+            dpre = gelu_bwd(dact, c["pre"], c["cdf"])
             G[p + "w1"][...] = dpre.T @ c["h2"]
             G[p + "b1"][...] = dpre.sum(0)
             dh2 = dpre @ P[p + "w1"]
