@@ -1872,7 +1872,9 @@ hift_status hift_step(hift_model* M, const hift_batch* bt, int32_t gid, float* l
   if (M->wpk) {  // the updated matrices in fragment order, for the next forward and dX
     double bytes = 0;
     for (int i = M->lay.unit_first[ulo]; i < M->lay.unit_first[uhi]; ++i)
-      bytes += 4.0 * M->lay.t[i].count() * ((M->lay.t[i].pk_fwd >= 0) + (M->lay.t[i].pk_bwd >= 0));
+      // per copy: the source read once (fp32 master, or the bf16 copy where one is kept) and the copy written once
+      bytes += ((M->lay.t[i].wc_off < 0 ? 4.0 : 2.0) + 2.0) * M->lay.t[i].count() *
+               ((M->lay.t[i].pk_fwd >= 0) + (M->lay.t[i].pk_bwd >= 0));
     Scope sc(M, CAT_PACK, bytes);
     K_TRY(repack_units(M, ulo, uhi));
   }
