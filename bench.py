@@ -99,10 +99,16 @@ def measured_traffic():
         return None
 
 
-def kernel_bench(reps):
+def kernel_bench(reps, n_weights=1, vendor=False):
     """Times the linear-layer contraction at every shape of the 7B workload, stand-alone, with
     HIP events on the launch stream, then runs one plain 1 GiB device copy (the reference
-    kernel for scaling hardware byte counters).  One JSON line."""
+    kernel for scaling hardware byte counters).  One JSON line.
+
+    n_weights: how many copies of the weight operand the launches of a shape rotate through.  With one, the
+    operand stays in the last-level cache from launch to launch; inside a training step every weight is read once
+    per pass and comes from HBM, which 8 copies reproduce.  vendor: also time the same products through
+    torch.matmul (the vendor library's kernels), launches interleaved in the same process; its dW product writes
+    bf16 where this library's writes fp32."""
     import torch
     import paper_2401_15207_amd as H
     T, d, f, V = 2048, 4096, 11008, 32000
@@ -118,33 +124,53 @@ def kernel_bench(reps):
     g.manual_seed(0)
     out = {}
     st = torch.cuda.current_stream()
+    ws = torch.zeros(H.kernel_packed_workspace_bytes() // 4, device="cuda", dtype=torch.float32)
+
+    def timed(launch):
+        for i in range(max(2, n_weights)):
+            launch(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for i in range(reps):
+            launch(i)
+        e1.record(st)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
     for name, M, N, K, ak, bk, of in shapes:
         A = (torch.randn(M * K, generator=g, device="cuda") * 0.5).to(torch.bfloat16)
-        B = (torch.randn(N * K, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+        Bs = [(torch.randn(N * K, generator=g, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(n_weights)]
         C = torch.empty(M * N, device="cuda", dtype=torch.float32 if of else torch.bfloat16)
         lda, ldb = (K if ak else M), (K if bk else N)
         # forward and dX multiply by a weight matrix: the model keeps those in fragment order and runs the
-        # packed-operand kernel; dW has two activation operands stored contraction-index first and runs gemm_tt_k
+        # packed-operand kernel (with its work space for a shared last round); dW has two activation operands
+        # stored contraction-index first and runs gemm_tt_k
         packed = ak == 1 and H.kernel_packed_bytes(N, K) > 0
         if packed:
-            Bp = torch.empty(H.kernel_packed_bytes(N, K) // 2, device="cuda", dtype=torch.bfloat16)
-            H.kernel_pack_b(bk, N, K, B, ldb, Bp)
-            launch = lambda: H.kernel_gemm_packed(of, M, N, K, A, lda, Bp, C, N)
+            Bps = []
+            for B in Bs:
+                Bp = torch.empty(H.kernel_packed_bytes(N, K) // 2, device="cuda", dtype=torch.bfloat16)
+                H.kernel_pack_b(bk, N, K, B, ldb, Bp)
+                Bps.append(Bp)
+            launch = lambda i: H.kernel_gemm_packed_ws(of, M, N, K, A, lda, Bps[i % n_weights], C, N, None, None, ws)
         else:
-            launch = lambda: H.kernel_gemm(1, ak, bk, of, M, N, K, A, lda, B, ldb, C, N)
-        for _ in range(2):
-            launch()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(st)
-        for _ in range(reps):
-            launch()
-        e1.record(st)
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
+            launch = lambda i: H.kernel_gemm(1, ak, bk, of, M, N, K, A, lda, Bs[i % n_weights], ldb, C, N)
+        ms = timed(launch)
         alg_bytes = 2 * (M * K + N * K) + (4 if of else 2) * M * N
         out[name] = {"M": M, "N": N, "K": K, "us": 1e3 * ms, "tflops": 2.0 * M * N * K / ms / 1e9,
-                     "algorithmic_bytes": alg_bytes, "kernel": "gemm_pk_k" if packed else ("gemm_tt_k" if not ak and not bk else "gemm_mfma_k")}
-        del A, B, C, launch
+                     "algorithmic_bytes": alg_bytes, "weights_in_rotation": n_weights,
+                     "kernel": "gemm_pk_k" if packed else ("gemm_tt_k" if not ak and not bk else "gemm_mfma_k")}
+        if vendor:
+            Am = A.view(M, K) if ak else A.view(K, M).t()
+            Bms = [B.view(N, K).t() if bk else B.view(K, N) for B in Bs]
+            Cv = torch.empty(M, N, device="cuda", dtype=torch.bfloat16)
+            vms = timed(lambda i: torch.matmul(Am, Bms[i % n_weights], out=Cv))
+            out[name]["vendor_us"] = 1e3 * vms
+            out[name]["vendor_tflops"] = 2.0 * M * N * K / vms / 1e9
+            del Am, Bms, Cv
+        del A, Bs, C, launch
+        if packed:
+            del Bps
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
     dst = torch.empty_like(src)
     dst.copy_(src)                      # plain copy kernel: reads 1 GiB, writes 1 GiB
@@ -221,6 +247,11 @@ def main():
                     help="time the LoRA comparison step (adapters of this rank on the query and value projections) and exit")
     ap.add_argument("--kernel-bench", type=int, default=0, metavar="REPS",
                     help="time the contraction kernel alone at the 7B shapes, REPS launches each, and exit")
+    ap.add_argument("--kernel-bench-weights", type=int, default=1, metavar="N",
+                    help="with --kernel-bench: rotate each shape's launches through N copies of the weight operand "
+                         "(8: the weights come from HBM as inside a step; 1: they stay in the last-level cache)")
+    ap.add_argument("--vendor-library", action="store_true",
+                    help="with --kernel-bench: also time the same products through torch.matmul")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: the HiFT step library is single-GPU in this build "
@@ -228,7 +259,7 @@ def main():
         sys.exit(2)
 
     if a.kernel_bench > 0:
-        kernel_bench(a.kernel_bench)
+        kernel_bench(a.kernel_bench, a.kernel_bench_weights, a.vendor_library)
         return
     if a.lora_rank > 0:
         lora_bench(a)

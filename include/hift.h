@@ -357,7 +357,8 @@ void hift_model_destroy(hift_model* mdl);
 /* C[M,N] = op(A) op(B) (+ bias[n]) (+ R[m,n]);  a_kmajor: A(m,k) at A[m*lda + k], else at
  * A[k*lda + m]; b_kmajor: B(n,k) at B[n*ldb + k], else at B[k*ldb + n].  out_f32: C is fp32
  * whatever dtype is.  bias has A's element type, R has C's type and leading dimension.  Batched over `batch` problems with element
- * strides sa, sb, sc.  This is the one contraction used for every linear layer, its dX and dW
+ * strides sa, sb, sc.  HIFT_EINVAL when a leading dimension is shorter than a row of the layout named (lda < K or M, ldb < K or N,
+ * ldc < N).  This is the one contraction used for every linear layer, its dX and dW
  * (Algorithm 1 steps h and the backward step). */
 hift_status hift_kernel_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t out_f32,
                              int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
@@ -371,7 +372,8 @@ hift_status hift_kernel_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, 
  * makes eight consecutive output columns land in one lane; rows padded to a multiple of 256).
  * hift_kernel_packed_bytes: size of that copy for a [N, K] operand, 0 if it cannot be packed
  * (needs N >= 256 and K a multiple of 32).  hift_kernel_pack_b: builds it from bf16 B given
- * k-major (B(n,k) at B[n*ldb + k]) or transposed (at B[k*ldb + n]).  hift_kernel_gemm_packed:
+ * k-major (B(n,k) at B[n*ldb + k], ldb >= K) or transposed (at B[k*ldb + n], ldb >= N; HIFT_EINVAL for a shorter ldb: the
+ * library cannot see the size of the caller's array, so a wrong layout flag with a long enough ldb reads past it).  hift_kernel_gemm_packed:
  * C[M,N] = A . B^T (+bias)(+R) with bf16 k-major A; HIFT_EINVAL for problems the kernel does
  * not take (fewer than 200 tiles of 128x256, unaligned operands). */
 hift_status hift_kernel_packed_bytes(int64_t N, int64_t K, size_t* bytes);

@@ -2168,6 +2168,8 @@ hift_status hift_kernel_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, 
   if (dtype != HIFT_F32 && dtype != HIFT_BF16) return fail(HIFT_EINVAL, "dtype unknown");
   if (Mm < 0 || N < 0 || K < 0 || batch < 0) return fail(HIFT_EINVAL, "negative size");
   if ((Mm > 0 && N > 0) && (!A || !B || !C) && K > 0) return fail(HIFT_EINVAL, "null operand");
+  if (lda < (a_kmajor ? K : Mm) || ldb < (b_kmajor ? K : N) || ldc < N)
+    return fail(HIFT_EINVAL, "a leading dimension is shorter than the rows it strides over");
   Gemm g;
   g.dtype = dtype == HIFT_BF16 ? DT_BF16 : DT_F32;
   g.a_kmajor = a_kmajor != 0; g.b_kmajor = b_kmajor != 0; g.out_f32 = out_f32 != 0 || dtype == HIFT_F32;
@@ -2189,6 +2191,7 @@ hift_status hift_kernel_pack_b(int32_t b_kmajor, int64_t N, int64_t K, const voi
                                void* stream) {
   if (!B || !Bp) return fail(HIFT_EINVAL, "null operand");
   if (packed_b_bytes(N, K) == 0) return fail(HIFT_EINVAL, "shape cannot be packed (N >= 256, K a multiple of 32)");
+  if (ldb < (b_kmajor ? K : N)) return fail(HIFT_EINVAL, "ldb is shorter than a row of B in the layout named");
   HIP_TRY(pack_b(B, ldb, N, K, b_kmajor != 0, Bp, (hipStream_t)stream));
   return HIFT_OK;
 }

@@ -184,6 +184,22 @@ def test_gemm_empty():
     assert float(z[:4].abs().sum()) == 0.0
 
 
+def test_leading_dimension_shorter_than_a_row_is_refused():
+    """The kernels would read past the operand: the entry points turn the call down instead."""
+    import torch
+    import paper_2401_15207_amd as H
+    z = torch.zeros(16, device="cuda")
+    for lda, ldb, ldc in [(3, 4, 4), (4, 3, 4), (4, 4, 3)]:
+        with pytest.raises(H.HiftError):
+            H.kernel_gemm(F32, 1, 1, 1, 4, 4, 4, z, lda, z, ldb, z, ldc)
+    big = torch.zeros(512 * 64, device="cuda", dtype=torch.bfloat16)
+    packed = torch.zeros(H.kernel_packed_bytes(256, 64), device="cuda", dtype=torch.uint8)
+    with pytest.raises(H.HiftError):
+        H.kernel_pack_b(1, 256, 64, big, 32, packed)    # B(n,k) at B[n*ldb + k] needs ldb >= K
+    with pytest.raises(H.HiftError):
+        H.kernel_pack_b(0, 256, 64, big, 64, packed)    # B(n,k) at B[k*ldb + n] needs ldb >= N
+
+
 @pytest.mark.parametrize("kind", ["adamw", "adagrad", "sgdm", "sgd"])
 @pytest.mark.parametrize("n", [1, 7, 4096, 100003])
 def test_optimizer_kernel_against_oracle_formulas(kind, n):
