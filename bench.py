@@ -99,7 +99,7 @@ def measured_traffic():
         return None
 
 
-def kernel_bench(reps, n_weights=1, vendor=False):
+def kernel_bench(reps, n_weights=1, vendor=False, ksweep=False):
     """Times the linear-layer contraction at every shape of the 7B workload, stand-alone, with
     HIP events on the launch stream, then runs one plain 1 GiB device copy (the reference
     kernel for scaling hardware byte counters).  One JSON line.
@@ -120,6 +120,8 @@ def kernel_bench(reps, n_weights=1, vendor=False):
         ("dw_qkv", 3 * d, d, T, 0, 0, 1), ("dw_o", d, d, T, 0, 0, 1), ("dw_gate_up", 2 * f, d, T, 0, 0, 1),
         ("dw_down", d, f, T, 0, 0, 1), ("dw_head", V, d, T, 0, 0, 1),
     ]
+    if ksweep:  # one round of 128 x 256 tiles at growing K: the fixed cost of a round is the intercept
+        shapes = [("k%d" % K, T, d, K, 1, 1, 0) for K in (256, 512, 1024, 2048, 4096, 8192)]
     g = torch.Generator(device="cuda")
     g.manual_seed(0)
     out = {}
@@ -250,6 +252,8 @@ def main():
     ap.add_argument("--kernel-bench-weights", type=int, default=1, metavar="N",
                     help="with --kernel-bench: rotate each shape's launches through N copies of the weight operand "
                          "(8: the weights come from HBM as inside a step; 1: they stay in the last-level cache)")
+    ap.add_argument("--kernel-bench-ksweep", action="store_true",
+                    help="with --kernel-bench: instead of the 7B shapes, M = 2048, N = 4096 (one round of tiles) at K = 256 ... 8192")
     ap.add_argument("--vendor-library", action="store_true",
                     help="with --kernel-bench: also time the same products through torch.matmul")
     a = ap.parse_args()
@@ -259,7 +263,7 @@ def main():
         sys.exit(2)
 
     if a.kernel_bench > 0:
-        kernel_bench(a.kernel_bench, a.kernel_bench_weights, a.vendor_library)
+        kernel_bench(a.kernel_bench, a.kernel_bench_weights, a.vendor_library, a.kernel_bench_ksweep)
         return
     if a.lora_rank > 0:
         lora_bench(a)
