@@ -861,10 +861,49 @@ __global__ void __launch_bounds__(256) gemm_pk_k(GemmP p, const u32x4* __restric
   for (int s = 0; s < PK_RD; ++s)
 #pragma unroll
     for (int gi = 0; gi < NP; ++gi) request_piece(kt0 + s, gi);
+  // The first fragments and the wait for them in one statement: between a load and its wait the registers hold
+  // nothing yet, and the compiler, which takes them for defined, may move them elsewhere when registers are short
+  // (seen in a variant of this kernel: copies into accumulator registers right behind the loads).  Four k-steps
+  // lie 1 KB apart behind one scalar offset; a k range of fewer than PKF k-steps (loads past the end repeat the
+  // last fragment) takes them one by one.
+  static_assert(PKF == 8 && NT == 2, "operands of the statement below");
+  if (kt0 * 4 + PKF <= k_steps) {
+    const uint32_t o0 = (uint32_t)((nb0 * k_steps + kt0 * 4) * 1024), o1 = o0 + (uint32_t)(k_steps * 1024);
+    const uint32_t o2 = o0 + 4096u, o3 = o1 + 4096u;
+    asm volatile(
+        "buffer_load_dwordx4 %0, %16, %17, %18 offen\n\t"
+        "buffer_load_dwordx4 %1, %16, %17, %19 offen\n\t"
+        "buffer_load_dwordx4 %2, %16, %17, %18 offen offset:1024\n\t"
+        "buffer_load_dwordx4 %3, %16, %17, %19 offen offset:1024\n\t"
+        "buffer_load_dwordx4 %4, %16, %17, %18 offen offset:2048\n\t"
+        "buffer_load_dwordx4 %5, %16, %17, %19 offen offset:2048\n\t"
+        "buffer_load_dwordx4 %6, %16, %17, %18 offen offset:3072\n\t"
+        "buffer_load_dwordx4 %7, %16, %17, %19 offen offset:3072\n\t"
+        "buffer_load_dwordx4 %8, %16, %17, %20 offen\n\t"
+        "buffer_load_dwordx4 %9, %16, %17, %21 offen\n\t"
+        "buffer_load_dwordx4 %10, %16, %17, %20 offen offset:1024\n\t"
+        "buffer_load_dwordx4 %11, %16, %17, %21 offen offset:1024\n\t"
+        "buffer_load_dwordx4 %12, %16, %17, %20 offen offset:2048\n\t"
+        "buffer_load_dwordx4 %13, %16, %17, %21 offen offset:2048\n\t"
+        "buffer_load_dwordx4 %14, %16, %17, %20 offen offset:3072\n\t"
+        "buffer_load_dwordx4 %15, %16, %17, %21 offen offset:3072\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(bq[0][0]), "=&v"(bq[0][1]), "=&v"(bq[1][0]), "=&v"(bq[1][1]), "=&v"(bq[2][0]), "=&v"(bq[2][1]),
+          "=&v"(bq[3][0]), "=&v"(bq[3][1]), "=&v"(bq[4][0]), "=&v"(bq[4][1]), "=&v"(bq[5][0]), "=&v"(bq[5][1]),
+          "=&v"(bq[6][0]), "=&v"(bq[6][1]), "=&v"(bq[7][0]), "=&v"(bq[7][1])
+        : "v"(vb), "s"(rsB), "s"(o0), "s"(o1), "s"(o2), "s"(o3)
+        : "memory");
+  } else {
 #pragma unroll
-  for (int s = 0; s < PKF; ++s)
+    for (int s = 0; s < PKF; ++s)
 #pragma unroll
-    for (int j = 0; j < NT; ++j) load_b1(bq[s][j], kt0 * 4 + s, j);
+      for (int j = 0; j < NT; ++j) {
+        const int64_t kk = kt0 * 4 + s;
+        const uint32_t so = (uint32_t)(((nb0 + j) * k_steps + (kk < k_steps ? kk : k_steps - 1)) * 1024);
+        asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen\n\ts_waitcnt vmcnt(0)"
+                     : "=&v"(bq[s][j]) : "v"(vb), "s"(rsB), "s"(so) : "memory");
+      }
+  }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 #pragma unroll
