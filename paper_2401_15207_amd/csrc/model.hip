@@ -671,7 +671,10 @@ bool folds_norm(const hift_model* M, const Tensor& w, int64_t rows) {
   Gemm g;
   g.dtype = M->dt;
   g.M = rows; g.N = w.rows; g.K = w.cols; g.lda = w.cols; g.ldc = g.ldr = w.rows;
-  return packed_gemm_applies(g);  // alignment aside, which the arenas guarantee
+  // the same question linear() asks (alignment aside, which the arenas guarantee): a weight without a row-major copy
+  // goes through the packed-operand kernel at any batch, also one of too few tiles to fill the chip
+  const bool only_packed = M->dt == DT_BF16 && w.wc_off < 0;
+  return packed_gemm_applies(g, only_packed);
 }
 
 // rowsq (optional): in, whether the sums of squares of y's rows are wanted in M->rowsq (y feeds a weight that

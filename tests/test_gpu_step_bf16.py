@@ -56,10 +56,11 @@ def _oracle_loss_and_grad(cfg, theta0, tok, lab, seed):
     return _LAST_ORACLE["val"]
 
 
-def _gradient_check(wl, groups, seed=5, test="", tol=lambda orc, ulo: TOL, **over):
+def _gradient_check(wl, groups, seed=5, test="", tol=lambda orc, ulo: TOL, batch=None, seq=None, **over):
     """Gradient of each chosen group, read out through the ABI as the change of the group's weights under plain
-    SGD with rate 1, against the oracle's full gradient restricted to the group."""
-    tok, lab = make_batch(wl, seed, 1)
+    SGD with rate 1, against the oracle's full gradient restricted to the group.  batch, seq: a batch below the
+    maxima the model was created for."""
+    tok, lab = make_batch(wl, seed, 1, batch=batch, seq=seq)
     dtok, dlab = to_dev(tok, lab)
     orc, gpu, theta0 = make_pair(wl, seed=seed, opt=SGD1, **over)
     lo_, g = _oracle_loss_and_grad(orc.cfg, theta0, tok, lab, seed)
@@ -192,6 +193,13 @@ def test_c2_full_depth_top2down_adamw_state_on_host_one_cycle():
 def test_c4_width_two_layers_gradients_all_groups():
     # LLaMA-7B widths (d 4096, 32 heads, SwiGLU 11008, vocab 32000), batch 4 x 512, depth 2
     _gradient_check(WORKLOADS["C4_L2"], lambda k: range(k), test="C4 widths depth 2, gradients")
+
+
+def test_c4_width_short_ragged_batch():
+    """3 x 77 tokens in a model made for 4 x 512: 231 rows are no multiple of any tile (contractions with a ragged
+    edge in M, the weight-gradient contraction with a ragged contraction length, attention with a ragged last key
+    tile, row-wise kernels on a row count that is no multiple of their block)."""
+    _gradient_check(WORKLOADS["C4_L2"], lambda k: range(k), batch=3, seq=77, test="C4 widths depth 2, 3 x 77 tokens")
 
 
 def test_c4_width_unfused_kernels():
