@@ -340,12 +340,15 @@ def attention_bwd(dctx, q, k, v, p):
 
 def cross_entropy_fwd(logits, labels):
     """Mean over rows with label >= 0 of -log softmax(logits)[label].
-    Returns loss and d loss / d logits."""
+    Returns loss and d loss / d logits.  A batch without a single target (sequences of one token: the paper does
+    not treat it) has loss 0 and gradient 0: the mean over no rows is taken as the empty sum."""
     z = logits - logits.max(-1, keepdims=True)
     lse = np.log(np.exp(z).sum(-1, keepdims=True))
     logp = z - lse
     valid = labels >= 0
     nv = int(valid.sum())
+    if nv == 0:
+        return 0.0, np.zeros_like(logp)
     rows = np.nonzero(valid)[0]
     loss = -logp[rows, labels[rows]].sum() / nv
     dlogits = np.exp(logp)

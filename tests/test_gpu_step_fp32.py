@@ -116,6 +116,24 @@ def test_off_schedule_group_takes_the_synchronous_fetch_and_stays_correct():
     assert rel_l2(gpu.read_params(), orc.theta) <= TOL
 
 
+@pytest.mark.parametrize("bf16", [0, 1])
+def test_one_token_sequences_have_no_target(bf16):
+    """Sequences of one token give the decoder nothing to predict: loss 0, no gradient; AdamW then only decays the
+    matrices of the active group, as in the oracle."""
+    wl = dict(SMALL2, dtype=1) if bf16 else WORKLOADS["C1"]
+    orc, gpu, _ = make_pair(wl, seed=2)
+    tok, lab = make_batch(wl, 2, 1, batch=2, seq=1)
+    assert (lab < 0).all()
+    for t in range(1, orc.k + 1):
+        gid = orc.schedule_group_at(t)
+        lo_ = orc.step(tok, lab, gid)
+        lg = gpu.step(*to_dev(tok, lab), gid)
+        assert lo_ == 0.0 and lg == 0.0
+    got = gpu.read_params().astype(np.float64)
+    assert np.isfinite(got).all()
+    assert rel_l2(got, orc.theta) <= TOL
+
+
 def test_plain_sgd_moves_no_state():
     wl = WORKLOADS["C1"]
     orc, gpu, _ = make_pair(wl, seed=7, opt=dict(kind="sgd", lr=0.1, momentum=0.0, weight_decay=0.0), state_on_host=1)

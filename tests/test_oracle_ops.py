@@ -23,6 +23,20 @@ def test_cross_entropy_uniform_logits_is_log_vocab():
     assert np.isclose(dl[0, 3], (1 / 50 - 1) / 4)
 
 
+def test_cross_entropy_without_a_single_target_is_zero():
+    """The empty mean is read as the empty sum: loss 0, no gradient (sequences of one token have no next token)."""
+    loss, dl = O.cross_entropy_fwd(np.random.default_rng(0).standard_normal((4, 9)), np.full(4, -1))
+    assert loss == 0.0 and dl.shape == (4, 9) and not dl.any()
+    # and a decoder step on one-token sequences moves nothing
+    cfg = dict(arch=0, n_layers=1, d_model=8, n_heads=2, d_ffn=16, vocab=11, max_seq=4, n_classes=0, norm_eps=1e-5,
+               rope_base=10000.0, dtype=0)
+    n = sum(int(np.prod(sh)) for _n, sh, _k, _u in O.param_tensors(cfg))
+    theta = np.random.default_rng(1).standard_normal(n) * 0.1
+    tok = np.array([[3], [7]], np.int32)
+    loss, g = O.loss_and_grad(cfg, theta, tok, np.full((2, 1), -1, np.int32))
+    assert loss == 0.0 and not g.any()
+
+
 def test_rope_is_a_rotation():
     x = R.standard_normal((2, 3, 7, 8))
     cos, sin = O.rope_angles(7, 8, 10000.0, np.float64)
