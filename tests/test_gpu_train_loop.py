@@ -100,3 +100,41 @@ def test_checkpoint_resume_continues_bit_identically(optk, on_host):
     assert b.cycle_index() == before[0] and np.array_equal(b.read_params(), before[1])
     assert [b.schedule_group_at(t) for t in range(1, k + 1)] == before[2]
     assert np.array_equal(b.train(dev, 2), a.train(dev, 2))   # and it goes on exactly as the run it mirrors
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("master_on_host", [0, 1])
+def test_checkpoint_resume_at_the_7b_widths_in_bf16(master_on_host):
+    """The same at the LLaMA-7B widths (depth 2), where the matrices exist in HBM only in fragment order (or, with the
+    master on the host, as a bf16 copy besides): a model of other weights and another order takes the checkpoint
+    and continues bit for bit: losses, master, compute copy, optimizer state."""
+    import paper_2401_15207_amd as H
+    from hift_inputs import WORKLOADS, init_params, model_config
+    from tests.hift_pair import spec_of
+    wl = WORKLOADS["C4_L2"]
+    cfg = model_config(wl)
+    opt = dict(kind="adamw", lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+    _h, dev = _batches(wl, 33, 4)
+
+    def model(seed, strategy):
+        m = H.HiftModel(cfg, opt, 1, wl["batch"], wl["seq"], init_params=init_params(seed, spec_of(cfg), bf16_exact=True),
+                        state_on_host=1, master_on_host=master_on_host)
+        m.set_group_schedule(strategy, 1, 17)
+        return m
+
+    a = model(33, "top2down")
+    k = a.k
+    a.set_lr_schedule("linear", 1e-4, 1, 6)
+    a.train(dev, k + 1, want_losses=False)
+    ckpt = a.checkpoint_save()
+    la = a.train(dev, k + 1)
+    b = model(34, "bottom2up")
+    b.checkpoint_load(ckpt)
+    del ckpt
+    lb = b.train(dev, k + 1)
+    assert np.isfinite(la).all() and np.array_equal(la, lb)
+    assert np.array_equal(a.read_params(), b.read_params())
+    assert np.array_equal(a.read_params(which=1), b.read_params(which=1))
+    for j in (0, 1):
+        assert np.array_equal(a.read_state(0, a.n_units, j), b.read_state(0, b.n_units, j))
+
