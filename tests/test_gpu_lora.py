@@ -69,15 +69,17 @@ def test_zero_b_adapters_leave_the_base_model():
 
 
 @pytest.mark.timeout(600)
-def test_adapter_step_bf16_at_7b_widths():
-    # LLaMA-7B widths (d 4096, 32 heads, SwiGLU 11008, vocab 32000), depth 2, batch 4 x 512, rank 8, alpha 16
+@pytest.mark.parametrize("batch,seq", [(None, None), (3, 77)], ids=["4x512", "3x77"])
+def test_adapter_step_bf16_at_7b_widths(batch, seq):
+    # LLaMA-7B widths (d 4096, 32 heads, SwiGLU 11008, vocab 32000), depth 2, batch 4 x 512, rank 8, alpha 16;
+    # and a short ragged batch in the same model (231 rows: no multiple of any tile)
     wl = WORKLOADS["C4_L2"]
     opt = dict(ADAMW, lr=1e-4, weight_decay=0.0)
     orc, gpu, theta0, lora0 = _pair(wl, 8, 16.0, seed=13, opt=opt, scale=0.02)
     b1 = opt["beta1"]
     cfg = model_config(wl)
     for t in range(1, 2):
-        tok, lab = make_batch(wl, 13, t)
+        tok, lab = make_batch(wl, 13, t, batch=batch, seq=seq)
         m_before = gpu.lora_read(2).astype(np.float64)
         lo = orc.step(tok, lab)
         lg = gpu.lora_step(*to_dev(tok, lab))
@@ -85,7 +87,7 @@ def test_adapter_step_bf16_at_7b_widths():
         e_all = rel_l2(g, orc.last_grad)
         G, R = O._lora_views(cfg, 8, g), O._lora_views(cfg, 8, orc.last_grad)
         worst = max(G, key=lambda n: rel_l2(G[n], R[n]))
-        record("LoRA step, C4 widths depth 2, rank 8", what="step", t=t, loss_rel_err=abs(lg - lo) / abs(lo), gradient_rel_l2=e_all,
+        record("LoRA step, C4 widths depth 2, rank 8" + (f", {batch} x {seq} tokens" if batch else ""), what="step", t=t, loss_rel_err=abs(lg - lo) / abs(lo), gradient_rel_l2=e_all,
                worst_tensor=worst, rel_l2_worst_tensor=rel_l2(G[worst], R[worst]), weights_rel_l2=rel_l2(gpu.lora_read(0), orc.lora))
         assert abs(lg - lo) <= 2e-2 * abs(lo), (t, lo, lg)
         assert e_all <= 2e-2, (t, e_all)
