@@ -10,6 +10,23 @@ def spec_of(cfg):
     return [(n, s, k) for n, s, k, _u in O.param_tensors(cfg)]
 
 
+_LAST_WEIGHTS = {}
+
+
+def initial_weights(cfg, seed, jitter=0.0):
+    """init_params of a configuration, the most recent result kept: several tests build the same large model (the 7B
+    widths at depth 2 are 667 M values, seconds to draw) and only read the vector."""
+    import json
+    layout = {k: v for k, v in cfg.items() if k not in ("unfused", "norm_eps", "rope_base")}
+    key = (json.dumps(layout, sort_keys=True, default=str), seed, jitter)
+    if _LAST_WEIGHTS.get("key") != key:
+        _LAST_WEIGHTS.clear()
+        theta0 = init_params(seed, spec_of(cfg), bf16_exact=(cfg["dtype"] == 1), jitter=jitter)
+        theta0.setflags(write=False)
+        _LAST_WEIGHTS.update(key=key, val=theta0)
+    return _LAST_WEIGHTS["val"]
+
+
 def make_pair(wl, seed=0, m=None, strategy=None, opt=None, state_on_host=0, batch=None, seq=None,
               jitter=0.0, sched_seed=17, master_on_host=0, no_packed_copies=0, unfused=0, **cfg_over):
     """Returns (oracle, gpu_model, theta0).  Weights are bf16-exact when the GPU model is bf16."""
@@ -19,7 +36,7 @@ def make_pair(wl, seed=0, m=None, strategy=None, opt=None, state_on_host=0, batc
     m = m or wl["m"]
     strategy = strategy or wl["strategy"]
     b, s = batch or wl["batch"], seq or wl["seq"]
-    theta0 = init_params(seed, spec_of(cfg), bf16_exact=(cfg["dtype"] == 1), jitter=jitter)
+    theta0 = initial_weights(cfg, seed, jitter)
     orc = O.HiftOracle(cfg, opt, theta0.astype(np.float64), half_weights=(cfg["dtype"] == 1))
     gpu = H.HiftModel(cfg, opt, m, b, s, init_params=theta0, state_on_host=state_on_host,
                       master_on_host=master_on_host, no_packed_copies=no_packed_copies, unfused=unfused)

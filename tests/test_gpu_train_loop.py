@@ -116,19 +116,21 @@ def test_checkpoint_resume_at_the_7b_widths_in_bf16(master_on_host):
     opt = dict(kind="adamw", lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
     _h, dev = _batches(wl, 33, 4)
 
-    def model(seed, strategy):
-        m = H.HiftModel(cfg, opt, 1, wl["batch"], wl["seq"], init_params=init_params(seed, spec_of(cfg), bf16_exact=True),
-                        state_on_host=1, master_on_host=master_on_host)
+    theta = init_params(33, spec_of(cfg), bf16_exact=True)
+
+    def model(values, strategy):
+        m = H.HiftModel(cfg, opt, 1, wl["batch"], wl["seq"], init_params=values, state_on_host=1, master_on_host=master_on_host)
         m.set_group_schedule(strategy, 1, 17)
         return m
 
-    a = model(33, "top2down")
+    a = model(theta, "top2down")
     k = a.k
     a.set_lr_schedule("linear", 1e-4, 1, 6)
     a.train(dev, k + 1, want_losses=False)
     ckpt = a.checkpoint_save()
     la = a.train(dev, k + 1)
-    b = model(34, "bottom2up")
+    b = model(np.ascontiguousarray(theta[::-1]), "bottom2up")     # other weights (the same values in reverse), other order
+    del theta
     b.checkpoint_load(ckpt)
     del ckpt
     lb = b.train(dev, k + 1)
