@@ -258,7 +258,7 @@ def test_parameters_written_from_device_memory(bf16, master_on_host):
     off = 0
     for u in range(b.n_units):
         n = b._unit_count(u, u + 1)
-        b.write_params_device(u, u + 1, torch.from_numpy(theta0[off:off + n]).cuda())
+        b.write_params_device(u, u + 1, torch.from_numpy(theta0[off:off + n].copy()).cuda())
         off += n
     assert np.array_equal(a.read_params(), b.read_params()) and np.array_equal(a.read_params(which=1), b.read_params(which=1))
     batch = to_dev(*make_batch(wl, 14, 1))
